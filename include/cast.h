@@ -1,0 +1,176 @@
+/*
+ * libcast: the per-step optimizer hot path of CAST (arXiv 2509.25996) for AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer marked DEVICE is an address in the memory of the current HIP device;
+ * pointers marked HOST are ordinary process memory.  The caller owns every buffer: the
+ * library allocates nothing, keeps no state between calls and frees nothing.
+ *
+ * Execution: each call validates its arguments on the host, then enqueues its kernels on the
+ * HIP stream passed as `stream` (a hipStream_t cast to void*; NULL = the default stream) and
+ * returns without waiting.  Validation failures return a negative status and enqueue nothing.
+ *
+ * Tensors are dense, row-major [rows, cols] with leading dimension cols; rows = out_features,
+ * cols = in_features of a linear layer.  Groups of M consecutive entries run along a row
+ * (Sec. 3, Eq. 3).  Empty tensors (rows == 0 or cols == 0) are accepted and do nothing.
+ *
+ * Shapes accepted: M in {2, 4, 8}, 1 <= N < M, cols % M == 0.  With weight scaling in n
+ * segments: cols % n == 0 and (cols / n) % M == 0, so that no group lies in two segments.
+ * All fp32 buffers must be 16-byte aligned, bf16 buffers 8-byte aligned, word buffers 4-byte.
+ *
+ * Mask storage (one bit per parameter; Remark at the end of Sec. 4.1): uint32 words, each row
+ * padded to whole words; M[r, c] is bit (c % 32) of word [r * ceil(cols/32) + c / 32].
+ * Padding bits are written as zero.
+ *
+ * Tie rule for Eq. 6 (the paper's ">= xi" keeps more than N entries when magnitudes tie,
+ * against Eq. 4): exactly N entries are kept and among equal magnitudes the lower column
+ * index is kept.  Magnitude is the IEEE-754 bit pattern with the sign bit cleared, compared
+ * as an unsigned integer (-0 equals +0, denormals keep their order, NaN ranks above inf).
+ */
+#ifndef CAST_H
+#define CAST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t cast_status;
+enum {
+    CAST_OK = 0,
+    CAST_ERR_NULL = -1,   /* a required pointer is NULL                                   */
+    CAST_ERR_SHAPE = -2,  /* rows/cols/N/M/n violate the rules above                      */
+    CAST_ERR_ALIGN = -3,  /* a buffer is not aligned as required                          */
+    CAST_ERR_DTYPE = -4,  /* unknown dtype code                                           */
+    CAST_ERR_CONFIG = -5, /* a scalar of cast_adams_config is out of range (e.g. bias_corr <= 0) */
+    CAST_ERR_LAUNCH = -6  /* the HIP runtime refused the launch (hipGetLastError != success) */
+};
+
+enum { CAST_F32 = 0, CAST_BF16 = 1 };
+
+/* Test-only: second moment from g^2 instead of mu~^2 (Eq. 9's form; not the paper's method). */
+#define CAST_FLAG_V_FROM_GRAD 1u
+
+/* Inputs of one AdamS iteration (Algorithm 1).  All scalars are used as given, in fp32. */
+typedef struct {
+    int32_t  n_keep;         /* N                                                            */
+    int32_t  m_group;        /* M                                                            */
+    float    lr;             /* gamma_t                                        Algorithm 1   */
+    float    beta1, beta2;   /* beta_1, beta_2 (the paper prints no values)                  */
+    float    eps;            /* epsilon                                                      */
+    float    lambda;         /* regularization strength lambda                 Eq. 7         */
+    float    alpha;          /* alpha_t = t / T, in [0, 1]                     Eq. 7         */
+    float    bias_corr1;     /* 1 - beta_1^s, s >= 1, computed by the caller   Eq. 8         */
+    float    bias_corr2;     /* 1 - beta_2^s                                                 */
+    int32_t  refresh_mask;   /* 1 on iterations with t mod T_1 == 0: take the mask from the  */
+                             /* incoming weights (Eq. 6) and store it; 0: read mask_bits     */
+    int32_t  scale_segments; /* n of Eq. 12; 0 = no weight scaling                           */
+    int32_t  grad_dtype;     /* CAST_F32 or CAST_BF16                                        */
+    uint32_t flags;          /* 0, or CAST_FLAG_V_FROM_GRAD                                  */
+} cast_adams_config;
+
+const char *cast_status_str(cast_status s);
+
+/* Bytes of the mask, of the packed values and of the packed metadata for a shape (HOST
+ * outputs; any of the three may be NULL).  value_dtype sizes the values buffer. */
+cast_status cast_sizes(int64_t rows, int64_t cols, int n_keep, int m_group, int value_dtype,
+                       size_t *mask_bytes, size_t *values_bytes, size_t *meta_bytes);
+
+/*
+ * Magnitude mask, Eq. 6 (Sec. 4.1) under the N-per-group constraint of Eq. 4.
+ *   w          DEVICE in   fp32 [rows, cols]
+ *   mask_bits  DEVICE out  uint32 [rows, ceil(cols/32)]
+ */
+cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int n_keep, int m_group,
+                           uint32_t *mask_bits, void *stream);
+
+/*
+ * One AdamS iteration over one weight matrix: the body of Algorithm 1's loop (Eq. 8), with
+ * the proportional decay of Eq. 7 on the entries whose mask bit is 0.
+ *
+ *   w, m, v     DEVICE in/out  fp32 [rows, cols]: theta, first moment mu, second moment v.
+ *   grad        DEVICE in      [rows, cols] of cfg->grad_dtype.  With scale == NULL it is dL/dW;
+ *                              with scale != NULL it is dL/dW_scale and the chain rule of Eq. 12
+ *                              (dL/dW = A[r, s] * grad) is applied inside.
+ *   mask_bits   DEVICE         written when cfg->refresh_mask (from w as it comes in), else read.
+ *   scale       DEVICE in      A, fp32 [rows, n], or NULL iff cfg->scale_segments == 0.
+ *   scale_grad  DEVICE out     dL/dA, fp32 [rows, n] = sum over each row segment of grad * w (w as it
+ *                              comes in), or NULL to skip it.  Summed in fp32 in a fixed order, so it is
+ *                              reproducible but differs from a double sum by rounding.
+ *
+ * Per entry, in fp32, one rounding per operation, no fused multiply-add:
+ *   g = grad (* A);  mu = b1*mu + (1-b1)*g;  mu~ = keep ? mu : (1-alpha)*mu + (alpha*lambda)*Sign(w)
+ *   v = b2*v + (1-b2)*mu~^2;  w = w - lr * ((mu~/bias_corr1) / (sqrt(v/bias_corr2) + eps))
+ * mu (not mu~) and v are stored.  Sign(+-0) = Sign(NaN) = 0.
+ */
+cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
+                            const float *scale, float *scale_grad, int64_t rows, int64_t cols,
+                            const cast_adams_config *cfg /* HOST */, void *stream);
+
+/*
+ * Weight scaling forward / fold, Eq. 12 (Eq. 11 when n_segments == 1):
+ *   out[r, c] = scale[r, c / (cols / n_segments)] * w[r, c]      (one fp32 multiply)
+ *   w DEVICE in fp32 [rows, cols]; scale DEVICE in fp32 [rows, n_segments];
+ *   out DEVICE out [rows, cols] of out_dtype (bf16 = round to nearest even of the fp32 product);
+ *   out may be w itself when out_dtype is CAST_F32.
+ */
+cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
+                              int n_segments, void *out, int out_dtype, void *stream);
+
+/*
+ * Gradient of the scale alone, for callers that do not take it from cast_adams_step:
+ *   scale_grad[r, s] = sum over c in segment s of grad_scaled[r, c] * w[r, c]
+ * (the derivative of Eq. 12 with respect to A).  Same summation order as cast_adams_step.
+ */
+cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int grad_dtype,
+                                   int64_t rows, int64_t cols, int n_segments,
+                                   float *scale_grad, void *stream);
+
+/*
+ * Final hard prune (last loop of Algorithm 1 / Algorithm 2), fold of the scale (Sec. 4.2)
+ * and packing into values + index metadata.  The paper gives no packed layout; this one is
+ * the library's own:
+ *
+ *   mask_bits == NULL: the mask is Eq. 6 on w (projection onto the N:M set);
+ *   mask_bits != NULL: the stored mask is applied as is (Algorithm 1 literally); it must hold
+ *                      exactly N ones per group, which is NOT checked on the device.
+ *   values  DEVICE out [rows, cols*N/M] of value_dtype: for each group its kept entries in
+ *           ascending column order, each multiplied by scale[r, s] if scale != NULL (one fp32
+ *           multiply; bf16 = round to nearest even of that; any NaN becomes 0x7FC0).
+ *   meta    DEVICE out uint32 [rows, ceil((cols/M) * f / 32)]: each kept entry's position in its
+ *           group in b = ceil(log2 M) bits; the N positions of a group concatenated ascending,
+ *           first in the least significant bits; group field padded to f = next power of two
+ *           >= N*b bits (2:4 -> 4, 4:8 -> 16, 1:2 -> 1); group i of a row at bit
+ *           (i % (32/f)) * f of word i / (32/f); unused bits zero.
+ */
+cast_status cast_nm_project_compress(const float *w, const float *scale, int n_segments,
+                                     const uint32_t *mask_bits, int64_t rows, int64_t cols,
+                                     int n_keep, int m_group, void *values, int value_dtype,
+                                     uint32_t *meta, void *stream);
+
+/*
+ * Mask-learning statistics of one matrix (appendix "Mask Learning"): the numerators of the
+ * flip rate r_t / initial flip rate i_t and both terms of the sparse weight ratio S_t.
+ *   mask_bits, other_bits  DEVICE in  masks to compare (other_bits may be NULL: flips = 0)
+ *   flips     DEVICE in/out uint64[1]: += ||M - M_other||_0
+ *   l1        DEVICE in/out double[2]: [0] += ||W (.) M||_1, [1] += ||W||_1
+ * The outputs are accumulated into (clear them before the first matrix), so one pair of
+ * buffers can be summed over all matrices of a model as the appendix's definitions do.
+ * The double additions are atomic and their order is not fixed: l1 is reproducible only to rounding.
+ */
+cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
+                            int64_t rows, int64_t cols, unsigned long long *flips, double *l1,
+                            void *stream);
+
+/*
+ * Measurement aid, not part of the method: a plain device-to-device copy kernel of `bytes`
+ * bytes (a multiple of 16; both pointers 16-byte aligned), used to calibrate the HBM byte
+ * counters and to measure the achievable copy bandwidth beside the optimizer kernels.
+ */
+cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAST_H */

@@ -1,0 +1,196 @@
+"""Thin ctypes binding of libcast.so: the same entry points as ``include/cast.h``, taking
+torch tensors that already live on the GPU.  Argument marshalling only: every step of the
+method runs inside the library's HIP kernels.  A missing library is an error; there is no
+CPU path."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcast.so")
+
+CAST_F32, CAST_BF16 = 0, 1
+FLAG_V_FROM_GRAD = 1
+
+EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
+           "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe"]
+
+
+class CastError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({status_str(status)})")
+        self.status = status
+
+
+class _Config(C.Structure):
+    _fields_ = [("n_keep", C.c_int32), ("m_group", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float), ("lambda_", C.c_float), ("alpha", C.c_float),
+                ("bias_corr1", C.c_float), ("bias_corr2", C.c_float), ("refresh_mask", C.c_int32),
+                ("scale_segments", C.c_int32), ("grad_dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+@dataclass
+class AdamsConfig:
+    """Mirror of ``cast_adams_config`` (inputs of one iteration of Algorithm 1)."""
+    n_keep: int = 2
+    m_group: int = 4
+    lr: float = 1e-4
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    lambda_: float = 2e-6
+    alpha: float = 0.0
+    bias_corr1: float = 1.0
+    bias_corr2: float = 1.0
+    refresh_mask: int = 1
+    scale_segments: int = 0
+    grad_dtype: int = CAST_F32
+    flags: int = 0
+
+    def c_struct(self) -> _Config:
+        return _Config(self.n_keep, self.m_group, self.lr, self.beta1, self.beta2, self.eps, self.lambda_,
+                       self.alpha, self.bias_corr1, self.bias_corr2, self.refresh_mask, self.scale_segments,
+                       self.grad_dtype, self.flags)
+
+
+_lib = None
+
+
+def load():
+    """Load libcast.so (built in place by ``python -m paper_2509_25996_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_25996_amd.build` "
+                                "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    i64, vp, ci = C.c_int64, C.c_void_p, C.c_int
+    L.cast_status_str.argtypes = [C.c_int32]
+    L.cast_status_str.restype = C.c_char_p
+    L.cast_sizes.argtypes = [i64, i64, ci, ci, ci, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+    L.cast_nm_select.argtypes = [vp, i64, i64, ci, ci, vp, vp]
+    L.cast_adams_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, C.POINTER(_Config), vp]
+    L.cast_weight_scale.argtypes = [vp, vp, i64, i64, ci, vp, ci, vp]
+    L.cast_weight_scale_grad.argtypes = [vp, vp, ci, i64, i64, ci, vp, vp]
+    L.cast_nm_project_compress.argtypes = [vp, vp, ci, vp, i64, i64, ci, ci, vp, ci, vp, vp]
+    L.cast_mask_stats.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp]
+    L.cast_hbm_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
+    for name in EXPORTS:
+        if name != "cast_status_str":
+            getattr(L, name).restype = C.c_int32
+    _lib = L
+    return L
+
+
+def status_str(status: int) -> str:
+    return load().cast_status_str(status).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise CastError(status, what)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return CAST_F32
+    if t.dtype == torch.bfloat16:
+        return CAST_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(*tensors):
+    for t in tensors:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous and on the GPU")
+
+
+def cast_sizes(rows: int, cols: int, n_keep: int, m_group: int, value_dtype: int = CAST_F32):
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    _check(load().cast_sizes(rows, cols, n_keep, m_group, value_dtype, C.byref(a), C.byref(b), C.byref(c)), "cast_sizes")
+    return a.value, b.value, c.value
+
+
+def alloc_mask(rows: int, cols: int, device="cuda:0") -> torch.Tensor:
+    """int32 tensor [rows, ceil(cols/32)] holding the uint32 mask words."""
+    return torch.zeros((rows, (cols + 31) // 32), dtype=torch.int32, device=device)
+
+
+def cast_nm_select(w: torch.Tensor, n_keep: int, m_group: int, mask_bits: torch.Tensor, stream=None):
+    _dev(w, mask_bits)
+    rows, cols = w.shape
+    _check(load().cast_nm_select(_ptr(w), rows, cols, n_keep, m_group, _ptr(mask_bits), _stream(stream)), "cast_nm_select")
+
+
+def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scale_grad=None, stream=None):
+    _dev(w, grad, m, v, mask_bits, scale, scale_grad)
+    rows, cols = w.shape
+    cfg.grad_dtype = _dtype_code(grad)
+    cs = cfg.c_struct()
+    _check(load().cast_adams_step(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
+                                  rows, cols, C.byref(cs), _stream(stream)), "cast_adams_step")
+
+
+def cast_weight_scale(w, scale, out, stream=None):
+    _dev(w, scale, out)
+    rows, cols = w.shape
+    _check(load().cast_weight_scale(_ptr(w), _ptr(scale), rows, cols, scale.shape[1], _ptr(out), _dtype_code(out),
+                                    _stream(stream)), "cast_weight_scale")
+
+
+def cast_weight_scale_grad(w, grad_scaled, n_segments: int, scale_grad, stream=None):
+    _dev(w, grad_scaled, scale_grad)
+    rows, cols = w.shape
+    _check(load().cast_weight_scale_grad(_ptr(w), _ptr(grad_scaled), _dtype_code(grad_scaled), rows, cols, n_segments,
+                                         _ptr(scale_grad), _stream(stream)), "cast_weight_scale_grad")
+
+
+def cast_nm_project_compress(w, n_keep: int, m_group: int, values, meta, scale=None, mask_bits=None, stream=None):
+    _dev(w, values, meta, scale, mask_bits)
+    rows, cols = w.shape
+    n_seg = 0 if scale is None else scale.shape[1]
+    _check(load().cast_nm_project_compress(_ptr(w), _ptr(scale), n_seg, _ptr(mask_bits), rows, cols, n_keep, m_group,
+                                           _ptr(values), _dtype_code(values), _ptr(meta), _stream(stream)),
+           "cast_nm_project_compress")
+
+
+def cast_mask_stats(w, mask_bits, other_bits, flips, l1, stream=None):
+    """flips: int64 tensor [1]; l1: float64 tensor [2]; both accumulated into."""
+    _dev(w, mask_bits, other_bits, flips, l1)
+    rows, cols = w.shape
+    _check(load().cast_mask_stats(_ptr(w), _ptr(mask_bits), _ptr(other_bits), rows, cols, _ptr(flips), _ptr(l1),
+                                  _stream(stream)), "cast_mask_stats")
+
+
+def cast_hbm_copy_probe(dst, src, stream=None):
+    _dev(dst, src)
+    _check(load().cast_hbm_copy_probe(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)),
+           "cast_hbm_copy_probe")
+
+
+def iteration_config(t: int, total_steps: int, mask_period: int = 10, **kw) -> AdamsConfig:
+    """Scalars of iteration t of Algorithm 1's loop (t = 0 .. T-1): alpha_t = t/T, mask
+    refresh when t mod T_1 == 0, and bias corrections with exponent t + 1 (the printed
+    1 - beta^t is zero at t = 0)."""
+    cfg = AdamsConfig(**kw)
+    b1 = C.c_float(cfg.beta1).value
+    b2 = C.c_float(cfg.beta2).value
+    cfg.alpha = t / total_steps
+    cfg.bias_corr1 = 1.0 - b1 ** (t + 1)
+    cfg.bias_corr2 = 1.0 - b2 ** (t + 1)
+    cfg.refresh_mask = int(t % mask_period == 0)
+    return cfg

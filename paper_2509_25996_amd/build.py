@@ -1,0 +1,40 @@
+"""Builds libcast.so (the C-ABI library) in place with hipcc for gfx950.
+
+    python -m paper_2509_25996_amd.build
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libcast.so")
+SOURCES = ["cast_api.hip", "adams_step.hip", "select_pack.hip"]
+
+# -ffp-contract=off and the correctly rounded divide/sqrt keep every fp32 operation of the
+# update a single IEEE-754 rounding; packed fp32 instructions are switched off.
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
+         "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-gpu-flush-denormals-to-zero",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wextra", "-Wno-unused-parameter"]
+
+
+def build_library(verbose: bool = False, extra=()) -> str:
+    cmd = ["hipcc", *FLAGS, *extra, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    out = (proc.stdout + proc.stderr)
+    # the host pass does not know the device-only target feature and says so: harmless
+    out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if verbose and out.strip():
+        print(out)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True, extra=sys.argv[1:]))

@@ -1,0 +1,417 @@
+// The fused AdamS iteration (Algorithm 1 / Eq. 8 with the decay of Eq. 7 and the mask of
+// Eq. 6) and the reduction that yields dL/dA for the weight scaling of Eq. 12.
+//
+// The work is a single streaming read-modify-write over w, mu, v (fp32), the gradient (bf16
+// or fp32) and one mask bit per entry: 26.125 bytes per parameter with bf16 gradients and
+// nothing is read twice.  There is no contraction, so no MFMA; the kernel is bound by HBM.
+#include <stdlib.h>
+
+#include "cast_device.h"
+#include "cast_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace cast {
+
+struct SpanArgs {
+    float *w;
+    const void *grad;
+    float *m;
+    float *v;
+    uint32_t *mask;
+    const float *scale;
+    float *scale_grad;
+    int64_t total;
+    int64_t span_len;
+    int64_t num_spans;
+    int waves_per_span;
+    StepScalars s;
+};
+
+// Registers of one chunk: 4 consecutive entries of each array per lane.
+struct Chunk {
+    float w[4], m[4], v[4], g[4];
+    uint32_t nib;   // mask bits of the 4 entries
+    int64_t idx;    // flat index of the lane's first entry
+    bool act;       // the lane's 4 entries lie inside the span
+};
+
+template <bool BF16>
+__device__ __forceinline__ void load_grad4(const void *grad, int64_t idx, float (&g)[4])
+{
+    if constexpr (BF16) {
+        const uint2 p = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(grad) + idx);
+        g[0] = bf16_lo(p.x); g[1] = bf16_hi(p.x); g[2] = bf16_lo(p.y); g[3] = bf16_hi(p.y);
+    } else {
+        const float4 p = *reinterpret_cast<const float4 *>(static_cast<const float *>(grad) + idx);
+        g[0] = p.x; g[1] = p.y; g[2] = p.z; g[3] = p.w;
+    }
+}
+
+__device__ __forceinline__ void load4(const float *p, int64_t idx, float (&x)[4])
+{
+    const float4 t = *reinterpret_cast<const float4 *>(p + idx);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+
+__device__ __forceinline__ void store4(float *p, int64_t idx, const float (&x)[4])
+{
+    *reinterpret_cast<float4 *>(p + idx) = make_float4(x[0], x[1], x[2], x[3]);
+}
+
+template <bool BF16, bool REFRESH>
+__device__ __forceinline__ void chunk_load(Chunk &c, const SpanArgs &a, int64_t begin, int64_t off,
+                                           int64_t len)
+{
+    c.act = off < len;
+    c.idx = begin + off;
+    c.nib = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c.w[j] = c.m[j] = c.v[j] = c.g[j] = 0.0f;
+    if (c.act) {
+        load4(a.w, c.idx, c.w);
+        load_grad4<BF16>(a.grad, c.idx, c.g);
+        load4(a.m, c.idx, c.m);
+        load4(a.v, c.idx, c.v);
+        if constexpr (!REFRESH) c.nib = (a.mask[c.idx >> 5] >> (unsigned)(c.idx & 31)) & 0xFu;
+    }
+}
+
+// One wavefront (or waves_per_span cooperating ones) walks one span in chunks of 256 entries.
+// Control flow is uniform across the wavefront: lanes past the end of the span carry zeros
+// through the arithmetic and only their loads and stores are switched off, so the cross-lane
+// steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly) always see all 64 lanes.
+template <int M, bool BF16, bool REFRESH, bool SCALED>
+__global__ __launch_bounds__(kBlockThreads) void adams_step_vec(const SpanArgs a)
+{
+    __shared__ float partial[kBlockWaves];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int P = a.waves_per_span;
+    const int64_t span = (int64_t)blockIdx.x * (kBlockWaves / P) + wave / P;
+    const int sub = wave % P;
+    const bool live = span < a.num_spans;
+    const int64_t begin = span * a.span_len;
+    int64_t len = 0;
+    if (live) len = (a.total - begin < a.span_len) ? a.total - begin : a.span_len;
+    float A = 1.0f;
+    if constexpr (SCALED) { if (live) A = a.scale[span]; }
+    const bool want_gA = SCALED && a.scale_grad != nullptr;
+    float acc = 0.0f;
+
+    constexpr int U = 2;  // chunks in flight per wavefront
+    const int64_t stride = (int64_t)P * kChunk;
+    for (int64_t base = (int64_t)sub * kChunk; base < len; base += stride * U) {
+        Chunk c[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            chunk_load<BF16, REFRESH>(c[u], a, begin, base + u * stride + lane * kLaneElems, len);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if constexpr (REFRESH) {
+                c[u].nib = keep_nibble<M>(c[u].w, a.s.n_keep, lane);   // from the incoming weights
+                const uint32_t word = or_reduce_8lanes(c[u].nib << ((lane & 7) * 4));
+                if (c[u].act && (lane & 7) == 0) a.mask[c[u].idx >> 5] = word;
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float g = c[u].g[j];
+                if constexpr (SCALED) {
+                    if (want_gA) acc = acc + g * c[u].w[j];   // dL/dA term, incoming w
+                    g = A * g;                                // chain rule of Eq. 12
+                }
+                adams_entry(c[u].w[j], g, c[u].m[j], c[u].v[j], (c[u].nib >> j) & 1u, a.s);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (c[u].act) {
+                store4(a.w, c[u].idx, c[u].w);
+                store4(a.m, c[u].idx, c[u].m);
+                store4(a.v, c[u].idx, c[u].v);
+            }
+    }
+
+    if constexpr (SCALED) {
+        if (want_gA) {   // uniform over the workgroup
+            const float wave_total = wave_sum_fixed_order(acc);
+            if (P == 1) {
+                if (lane == 0 && live) a.scale_grad[span] = wave_total;
+            } else {
+                if (lane == 0) partial[wave] = wave_total;
+                __syncthreads();
+                if (lane == 0 && sub == 0 && live) {
+                    float t = partial[wave];
+                    for (int p = 1; p < P; ++p) t = t + partial[wave + p];
+                    a.scale_grad[span] = t;
+                }
+            }
+        }
+    }
+}
+
+// dL/dA alone, with exactly the traversal and summation order of adams_step_vec.
+template <bool BF16>
+__global__ __launch_bounds__(kBlockThreads) void scale_grad_vec(const float *w, const void *grad,
+                                                                float *scale_grad, int64_t total,
+                                                                int64_t span_len, int64_t num_spans,
+                                                                int waves_per_span)
+{
+    __shared__ float partial[kBlockWaves];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int P = waves_per_span;
+    const int64_t span = (int64_t)blockIdx.x * (kBlockWaves / P) + wave / P;
+    const int sub = wave % P;
+    const bool live = span < num_spans;
+    const int64_t begin = span * span_len;
+    int64_t len = 0;
+    if (live) len = (total - begin < span_len) ? total - begin : span_len;
+    float acc = 0.0f;
+    // the step kernel takes its chunks two at a time (base, base + stride) and adds them in
+    // that order, which is plain increasing order of chunks
+    for (int64_t base = (int64_t)sub * kChunk; base < len; base += (int64_t)P * kChunk) {
+        const int64_t off = base + lane * kLaneElems;
+        float wv[4] = {0, 0, 0, 0}, g[4] = {0, 0, 0, 0};
+        if (off < len) {
+            load4(w, begin + off, wv);
+            load_grad4<BF16>(grad, begin + off, g);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc = acc + g[j] * wv[j];
+    }
+    const float wave_total = wave_sum_fixed_order(acc);
+    if (P == 1) {
+        if (lane == 0 && live) scale_grad[span] = wave_total;
+    } else {
+        if (lane == 0) partial[wave] = wave_total;
+        __syncthreads();
+        if (lane == 0 && sub == 0 && live) {
+            float t = partial[wave];
+            for (int p = 1; p < P; ++p) t = t + partial[wave + p];
+            scale_grad[span] = t;
+        }
+    }
+}
+
+// ---- any shape with cols % M == 0: one thread per 64 consecutive columns of a row -----------
+struct UnitArgs {
+    float *w;
+    const void *grad;
+    float *m;
+    float *v;
+    uint32_t *mask;
+    const float *scale;
+    int64_t rows, cols;
+    int n_segments;
+    int refresh;
+    StepScalars s;
+};
+
+template <bool BF16>
+__device__ __forceinline__ float load_grad1(const void *grad, int64_t idx)
+{
+    if constexpr (BF16) return bf16_to_f32(static_cast<const uint16_t *>(grad)[idx]);
+    else return static_cast<const float *>(grad)[idx];
+}
+
+template <int M, bool BF16>
+__global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs a)
+{
+    const int64_t units_per_row = (a.cols + 63) / 64;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (tid >= a.rows * units_per_row) return;
+    const int64_t r = tid / units_per_row, c0 = (tid % units_per_row) * 64;
+    const int64_t words_per_row = (a.cols + 31) / 32;
+    const int64_t seg_len = a.n_segments > 0 ? a.cols / a.n_segments : a.cols;
+    for (int half = 0; half < 2; ++half) {
+        const int64_t cb = c0 + half * 32;
+        if (cb >= a.cols) break;
+        const int64_t ce = (cb + 32 < a.cols) ? cb + 32 : a.cols;
+        uint32_t *word_ptr = a.mask + r * words_per_row + cb / 32;
+        uint32_t word = a.refresh ? 0u : *word_ptr;
+        for (int64_t c = cb; c < ce; c += M) {
+            const int64_t idx = r * a.cols + c;
+            float wv[M];
+#pragma unroll
+            for (int j = 0; j < M; ++j) wv[j] = a.w[idx + j];
+            uint32_t bits;
+            if (a.refresh) {
+                bits = keep_bits_group<M>(wv, a.s.n_keep);
+                word |= bits << (unsigned)(c - cb);
+            } else {
+                bits = (word >> (unsigned)(c - cb)) & ((1u << M) - 1u);
+            }
+            float A = 1.0f;
+            if (a.scale) A = a.scale[r * a.n_segments + c / seg_len];
+#pragma unroll
+            for (int j = 0; j < M; ++j) {
+                float g = load_grad1<BF16>(a.grad, idx + j);
+                if (a.scale) g = A * g;
+                float mu = a.m[idx + j], vv = a.v[idx + j];
+                adams_entry(wv[j], g, mu, vv, (bits >> j) & 1u, a.s);
+                a.w[idx + j] = wv[j];
+                a.m[idx + j] = mu;
+                a.v[idx + j] = vv;
+            }
+        }
+        if (a.refresh) *word_ptr = word;
+    }
+}
+
+// dL/dA for any shape: one wavefront per row segment, lanes stride over its entries.
+template <bool BF16>
+__global__ __launch_bounds__(kBlockThreads) void scale_grad_rows(const float *w, const void *grad,
+                                                                 float *scale_grad, int64_t num_segments,
+                                                                 int64_t seg_len)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t seg = (int64_t)blockIdx.x * kBlockWaves + threadIdx.x / kWave;
+    float acc = 0.0f;
+    if (seg < num_segments)
+        for (int64_t i = lane; i < seg_len; i += kWave)
+            acc = acc + load_grad1<BF16>(grad, seg * seg_len + i) * w[seg * seg_len + i];
+    const float t = wave_sum_fixed_order(acc);
+    if (lane == 0 && seg < num_segments) scale_grad[seg] = t;
+}
+
+// ---- host side ------------------------------------------------------------------------------
+
+static int env_int(const char *name, int fallback)
+{
+    const char *e = getenv(name);
+    return e && *e ? atoi(e) : fallback;
+}
+
+SpanPlan plan_spans(int64_t rows, int64_t cols, int n_segments)
+{
+    // Tuning knobs (read once): CAST_SPAN_LEN forces the flat span length, CAST_WAVES_PER_SPAN
+    // the number of cooperating wavefronts.
+    static const int forced_len = env_int("CAST_SPAN_LEN", 0);
+    static const int forced_p = env_int("CAST_WAVES_PER_SPAN", 0);
+    constexpr int64_t kWantWaves = 16384;   // 2 rounds of 8 waves/SIMD over 256 CUs * 4 SIMDs
+    SpanPlan p{};
+    p.total = rows * cols;
+    p.waves_per_span = 1;
+    if (n_segments > 0) {
+        p.span_len = cols / n_segments;
+        p.num_spans = rows * n_segments;
+        p.vec = p.span_len % 32 == 0;
+        // long segments and few of them: let 2 or 4 wavefronts share one
+        while (p.waves_per_span < 4 && p.num_spans * p.waves_per_span < kWantWaves &&
+               p.span_len >= (int64_t)kChunk * 4 * p.waves_per_span)
+            p.waves_per_span *= 2;
+    } else {
+        p.vec = cols % 32 == 0;
+        int64_t len = (p.total / kWantWaves + kChunk - 1) / kChunk * kChunk;
+        if (len < kChunk) len = kChunk;
+        if (len > 8 * kChunk) len = 8 * kChunk;
+        if (forced_len >= kChunk && forced_len % kChunk == 0) len = forced_len;
+        p.span_len = len;
+        p.num_spans = (p.total + len - 1) / len;
+    }
+    if (forced_p == 1 || forced_p == 2 || forced_p == 4) p.waves_per_span = forced_p;
+    const int64_t spans_per_block = kBlockWaves / p.waves_per_span;
+    p.grid = (unsigned)((p.num_spans + spans_per_block - 1) / spans_per_block);
+    return p;
+}
+
+static StepScalars make_scalars(const cast_adams_config *cfg)
+{
+    StepScalars s;
+    s.lr = cfg->lr;
+    s.beta1 = cfg->beta1;
+    s.one_minus_beta1 = 1.0f - cfg->beta1;
+    s.beta2 = cfg->beta2;
+    s.one_minus_beta2 = 1.0f - cfg->beta2;
+    s.eps = cfg->eps;
+    s.one_minus_alpha = 1.0f - cfg->alpha;
+    s.alpha_lambda = cfg->alpha * cfg->lambda;
+    s.bias_corr1 = cfg->bias_corr1;
+    s.bias_corr2 = cfg->bias_corr2;
+    s.n_keep = cfg->n_keep;
+    s.v_from_grad = (cfg->flags & CAST_FLAG_V_FROM_GRAD) ? 1 : 0;
+    return s;
+}
+
+template <int M, bool BF16, bool REFRESH>
+static void launch_vec_scaled(bool scaled, const SpanPlan &p, const SpanArgs &a, hipStream_t st)
+{
+    if (scaled) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true>), dim3(p.grid), dim3(kBlockThreads), 0, st, a);
+    else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, false>), dim3(p.grid), dim3(kBlockThreads), 0, st, a);
+}
+
+template <int M, bool BF16>
+static void launch_vec_refresh(bool refresh, bool scaled, const SpanPlan &p, const SpanArgs &a, hipStream_t st)
+{
+    if (refresh) launch_vec_scaled<M, BF16, true>(scaled, p, a, st);
+    else launch_vec_scaled<M, BF16, false>(scaled, p, a, st);
+}
+
+template <int M>
+static void launch_vec_dtype(bool bf16, bool refresh, bool scaled, const SpanPlan &p, const SpanArgs &a, hipStream_t st)
+{
+    if (bf16) launch_vec_refresh<M, true>(refresh, scaled, p, a, st);
+    else launch_vec_refresh<M, false>(refresh, scaled, p, a, st);
+}
+
+template <int M>
+static void launch_unit_dtype(bool bf16, unsigned grid, const UnitArgs &a, hipStream_t st)
+{
+    if (bf16) hipLaunchKernelGGL((adams_step_unit<M, true>), dim3(grid), dim3(kBlockThreads), 0, st, a);
+    else hipLaunchKernelGGL((adams_step_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, a);
+}
+
+cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
+                              int64_t cols, int n_segments, float *scale_grad, hipStream_t st)
+{
+    if (rows == 0 || cols == 0) return CAST_OK;
+    const SpanPlan p = plan_spans(rows, cols, n_segments);
+    const bool bf16 = grad_dtype == CAST_BF16;
+    if (p.vec) {
+        if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, dim3(p.grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
+        else hipLaunchKernelGGL(scale_grad_vec<false>, dim3(p.grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
+    } else {
+        const unsigned grid = (unsigned)((p.num_spans + kBlockWaves - 1) / kBlockWaves);
+        if (bf16) hipLaunchKernelGGL(scale_grad_rows<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.num_spans, p.span_len);
+        else hipLaunchKernelGGL(scale_grad_rows<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.num_spans, p.span_len);
+    }
+    return launch_status();
+}
+
+cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
+                              const float *scale, float *scale_grad, int64_t rows, int64_t cols,
+                              const cast_adams_config *cfg, hipStream_t st)
+{
+    if (rows == 0 || cols == 0) return CAST_OK;
+    const SpanPlan p = plan_spans(rows, cols, cfg->scale_segments);
+    const bool bf16 = cfg->grad_dtype == CAST_BF16;
+    const bool refresh = cfg->refresh_mask != 0;
+    const bool scaled = scale != nullptr;
+    if (p.vec) {
+        SpanArgs a{w, grad, m, v, mask_bits, scale, scale_grad, p.total, p.span_len, p.num_spans,
+                   p.waves_per_span, make_scalars(cfg)};
+        switch (cfg->m_group) {
+        case 2: launch_vec_dtype<2>(bf16, refresh, scaled, p, a, st); break;
+        case 4: launch_vec_dtype<4>(bf16, refresh, scaled, p, a, st); break;
+        default: launch_vec_dtype<8>(bf16, refresh, scaled, p, a, st); break;
+        }
+        return launch_status();
+    }
+    // odd shapes: dL/dA first (it needs the incoming weights), then the element pass
+    if (scaled && scale_grad) {
+        cast_status rc = launch_scale_grad(w, grad, cfg->grad_dtype, rows, cols, cfg->scale_segments, scale_grad, st);
+        if (rc != CAST_OK) return rc;
+    }
+    UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg)};
+    const int64_t units = rows * ((cols + 63) / 64);
+    const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
+    switch (cfg->m_group) {
+    case 2: launch_unit_dtype<2>(bf16, grid, a, st); break;
+    case 4: launch_unit_dtype<4>(bf16, grid, a, st); break;
+    default: launch_unit_dtype<8>(bf16, grid, a, st); break;
+    }
+    return launch_status();
+}
+
+}  // namespace cast

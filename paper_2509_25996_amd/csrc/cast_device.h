@@ -1,0 +1,164 @@
+// Device-side building blocks shared by the gfx950 kernels of libcast.
+//
+// Wavefronts are 64 lanes.  In the vector kernels every lane owns 4 consecutive fp32
+// entries of a row (one 16-byte load per array), so a wavefront covers 256 consecutive
+// entries per step and every load/store instruction touches one contiguous 1 KiB block.
+// A group of M entries (Eq. 3) therefore lives in a quarter lane pair (M = 2: two groups per
+// lane), in one lane (M = 4) or in two adjacent lanes (M = 8), and the mask bits of 8
+// adjacent lanes form one 32-bit mask word.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#pragma clang fp contract(off)
+
+namespace cast {
+
+constexpr int kWave = 64;
+constexpr int kLaneElems = 4;                    // fp32 entries per lane per chunk
+constexpr int kChunk = kWave * kLaneElems;       // 256 entries per wavefront per chunk
+constexpr int kBlockThreads = 256;
+constexpr int kBlockWaves = kBlockThreads / kWave;
+
+// ---- cross-lane moves inside a row of 16 lanes (DPP: no LDS traffic) -------------------
+// quad_perm selectors: lane i of each quad reads lane perm[i] of the same quad.
+constexpr int kDppQuadXor1 = 0xB1;       // [1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;       // [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141; // lane i of each 8 reads lane 7-i
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+
+// OR of a value over each aligned run of 8 lanes; every lane of the run gets the result.
+__device__ __forceinline__ uint32_t or_reduce_8lanes(uint32_t x)
+{
+    x |= dpp_u32<kDppQuadXor1>(x);
+    x |= dpp_u32<kDppQuadXor2>(x);
+    x |= dpp_u32<kDppRowHalfMirror>(x);
+    return x;
+}
+
+// Butterfly sum over the 64 lanes in a fixed order (xor 1, 2, 4, ..., 32).
+__device__ __forceinline__ float wave_sum_fixed_order(float x)
+{
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) x = x + __shfl_xor(x, d, kWave);
+    return x;
+}
+
+// ---- Eq. 6: which of a lane's 4 entries are kept -----------------------------------------
+// Magnitude key: the bit pattern with the sign cleared, ordered as an unsigned integer.
+__device__ __forceinline__ uint32_t magnitude_key(float x) { return __float_as_uint(x) & 0x7fffffffu; }
+
+// Returns a 4-bit field, bit j set iff entry j of the lane is among the N largest
+// magnitudes of its group, ties going to the lower column.  The rank of an entry is the
+// number of entries of its group that precede it in that order; it is kept iff rank < N.
+// Must be called by all 64 lanes together (M = 8 exchanges keys with the neighbouring lane).
+template <int M>
+__device__ __forceinline__ uint32_t keep_nibble(const float (&w)[4], int n_keep, int lane)
+{
+    const uint32_t k0 = magnitude_key(w[0]), k1 = magnitude_key(w[1]);
+    const uint32_t k2 = magnitude_key(w[2]), k3 = magnitude_key(w[3]);
+    if constexpr (M == 2) {
+        // two groups per lane, N = 1: the first entry wins a tie
+        const uint32_t a = k0 >= k1, b = k2 >= k3;
+        return a | ((a ^ 1u) << 1) | (b << 2) | ((b ^ 1u) << 3);
+    } else {
+        // "x precedes y" for columns x < y  <=>  key_x >= key_y
+        const int c01 = k0 >= k1, c02 = k0 >= k2, c03 = k0 >= k3;
+        const int c12 = k1 >= k2, c13 = k1 >= k3, c23 = k2 >= k3;
+        int r0 = (1 - c01) + (1 - c02) + (1 - c03);
+        int r1 = c01 + (1 - c12) + (1 - c13);
+        int r2 = c02 + c12 + (1 - c23);
+        int r3 = c03 + c13 + c23;
+        if constexpr (M == 8) {
+            // the other half of the group sits in lane ^ 1.  For the even lane (lower columns)
+            // a neighbour entry precedes only if strictly larger; for the odd lane also if equal.
+            const uint32_t odd = (uint32_t)lane & 1u;
+            const uint32_t p0 = dpp_u32<kDppQuadXor1>(k0) + odd, p1 = dpp_u32<kDppQuadXor1>(k1) + odd;
+            const uint32_t p2 = dpp_u32<kDppQuadXor1>(k2) + odd, p3 = dpp_u32<kDppQuadXor1>(k3) + odd;
+            // keys are < 2^31, so key + 1 cannot wrap
+            r0 += (p0 > k0) + (p1 > k0) + (p2 > k0) + (p3 > k0);
+            r1 += (p0 > k1) + (p1 > k1) + (p2 > k1) + (p3 > k1);
+            r2 += (p0 > k2) + (p1 > k2) + (p2 > k2) + (p3 > k2);
+            r3 += (p0 > k3) + (p1 > k3) + (p2 > k3) + (p3 > k3);
+        }
+        return (uint32_t)(r0 < n_keep) | ((uint32_t)(r1 < n_keep) << 1) |
+               ((uint32_t)(r2 < n_keep) << 2) | ((uint32_t)(r3 < n_keep) << 3);
+    }
+}
+
+// Same rule for one whole group held by one thread (scalar kernels for odd shapes).
+template <int M>
+__device__ __forceinline__ uint32_t keep_bits_group(const float (&w)[M], int n_keep)
+{
+    uint32_t key[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) key[j] = magnitude_key(w[j]);
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < M; ++j) {
+        int rank = 0;
+#pragma unroll
+        for (int k = 0; k < M; ++k)
+            rank += (k < j) ? (key[k] >= key[j]) : ((k > j) ? (key[k] > key[j]) : 0);
+        bits |= (uint32_t)(rank < n_keep) << j;
+    }
+    return bits;
+}
+
+// ---- bf16 <-> fp32 ----------------------------------------------------------------------
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// round to nearest, ties to even; any NaN -> 0x7FC0
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x)
+{
+    uint32_t b = __float_as_uint(x);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+    b += 0x7fffu + ((b >> 16) & 1u);
+    return b >> 16;
+}
+
+// ---- Algorithm 1, one entry -------------------------------------------------------------
+// Scalars of one iteration, prepared on the host in fp32 (one rounding each).
+struct StepScalars {
+    float lr, beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
+    float one_minus_alpha, alpha_lambda, bias_corr1, bias_corr2;
+    int n_keep;
+    int v_from_grad;
+};
+
+// Every line is one correctly rounded fp32 operation: the library is compiled with
+// -ffp-contract=off (no fused multiply-add) and -fhip-fp32-correctly-rounded-divide-sqrt, and
+// fp32 denormals are not flushed on gfx9, so the result is the same on any IEEE-754 machine.
+__device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float &v, bool keep,
+                                            const StepScalars &s)
+{
+    const float t0 = s.beta1 * mu;
+    const float t1 = s.one_minus_beta1 * g;
+    const float mu_t = t0 + t1;                                   // Eq. 8, first line
+    const float sgn = (float)(w > 0.0f) - (float)(w < 0.0f);      // Sign(+-0) = Sign(NaN) = 0
+    const float d0 = s.one_minus_alpha * mu_t;
+    const float d1 = s.alpha_lambda * sgn;
+    const float decayed = d0 + d1;                                // Eq. 7 on the momentum
+    const float mu_tilde = keep ? mu_t : decayed;                 // Algorithm 1: only where m = 0
+    const float second = s.v_from_grad ? g * g : mu_tilde * mu_tilde;
+    const float s0 = s.beta2 * v;
+    const float s1 = s.one_minus_beta2 * second;
+    const float v_t = s0 + s1;                                    // v from the decayed momentum
+    const float mu_hat = mu_tilde / s.bias_corr1;                 // IEEE division (see the build flags)
+    const float v_hat = v_t / s.bias_corr2;
+    const float denom = __builtin_sqrtf(v_hat) + s.eps;            // IEEE square root
+    const float q = mu_hat / denom;
+    const float step = s.lr * q;
+    w = w - step;
+    mu = mu_t;                                                    // the undecayed moment is stored
+    v = v_t;
+}
+
+}  // namespace cast

@@ -1,0 +1,122 @@
+"""CPU-side checks of the C-ABI library: it loads without a GPU, exports every function the
+header declares, sizes buffers as documented and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2509_25996_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2509_25996_amd.build import build_library
+        build_library()
+    return B.load()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cast.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cast_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings(lib):
+    assert B.status_str(0) == "ok"
+    for s in range(-6, 0):
+        assert B.status_str(s) not in ("ok", "unknown status")
+    assert B.status_str(-99) == "unknown status"
+
+
+def test_sizes(lib):
+    # 2:4, 4096x4096: mask 1 bit/param, values half the entries, metadata 4 bits per group
+    m, v, t = B.cast_sizes(4096, 4096, 2, 4, B.CAST_F32)
+    assert m == 4096 * 4096 // 8 and v == 4096 * 2048 * 4 and t == 4096 * 1024 // 2
+    assert m * 32 == 4096 * 4096 * 4          # 1/32 of one fp32 state (Remark, Sec. 4.1)
+    m, v, t = B.cast_sizes(3, 40, 4, 8, B.CAST_BF16)
+    assert m == 3 * 2 * 4 and v == 3 * 20 * 2 and t == 3 * 3 * 4   # 5 groups, 2 per word -> 3 words
+    m, v, t = B.cast_sizes(5, 6, 1, 2, B.CAST_F32)
+    assert m == 5 * 4 and v == 5 * 3 * 4 and t == 5 * 4
+    assert B.cast_sizes(0, 128, 2, 4) == (0, 0, 0)
+    for bad in [(4, 6, 2, 4), (4, 8, 4, 4), (4, 8, 0, 4), (4, 9, 1, 3), (-1, 8, 2, 4)]:
+        with pytest.raises(B.CastError) as e:
+            B.cast_sizes(*bad)
+        assert e.value.status == -2
+
+
+def _cfg(**kw):
+    return B.AdamsConfig(**kw).c_struct()
+
+
+def test_validation_happens_before_any_launch(lib):
+    # fake, suitably aligned, non-null addresses: a call that passed validation would fault,
+    # so every case below must be rejected on the host
+    p = C.c_void_p(0x10000)
+    odd = C.c_void_p(0x10004)
+    nul = C.c_void_p(0)
+    st = C.c_void_p(0)
+    step = lib.cast_adams_step
+
+    def call(cfg, w=p, g=p, m=p, v=p, k=p, a=nul, ga=nul, rows=4, cols=64):
+        return step(w, g, m, v, k, a, ga, rows, cols, C.byref(cfg), st)
+
+    assert call(_cfg(n_keep=2, m_group=3)) == -2
+    assert call(_cfg(n_keep=4, m_group=4)) == -2
+    assert call(_cfg(), cols=66) == -2
+    assert call(_cfg(scale_segments=2)) == -1                    # segments announced, no scale buffer
+    assert call(_cfg(), a=p) == -2                               # scale buffer, no segments
+    assert call(_cfg(), ga=p) == -1                              # dL/dA asked without a scale
+    assert call(_cfg(scale_segments=3), a=p, cols=64) == -2      # 64 % 3
+    assert call(_cfg(scale_segments=32, m_group=4), a=p, cols=64) == -2   # segment of 2 entries < M
+    assert call(_cfg(grad_dtype=7)) == -4
+    assert call(_cfg(bias_corr1=0.0)) == -5
+    assert call(_cfg(bias_corr2=-1.0)) == -5
+    assert call(_cfg(bias_corr2=float("nan"))) == -5
+    assert call(_cfg(flags=8)) == -5
+    assert call(_cfg(), w=nul) == -1
+    assert call(_cfg(), k=nul) == -1
+    assert call(_cfg(), w=odd) == -3
+    assert call(_cfg(), m=odd) == -3
+    assert step(p, p, p, p, p, nul, nul, 4, 64, None, st) == -1
+    # empty tensors are accepted and do nothing, even with null buffers
+    assert call(_cfg(), w=nul, g=nul, m=nul, v=nul, k=nul, rows=0) == 0
+    assert call(_cfg(), w=nul, g=nul, m=nul, v=nul, k=nul, cols=0) == 0
+
+    assert lib.cast_nm_select(p, 4, 62, 2, 4, p, st) == -2
+    assert lib.cast_nm_select(nul, 4, 64, 2, 4, p, st) == -1
+    assert lib.cast_nm_select(odd, 4, 64, 2, 4, p, st) == -3
+    assert lib.cast_nm_select(nul, 0, 64, 2, 4, nul, st) == 0
+    assert lib.cast_weight_scale(p, p, 4, 64, 3, p, 0, st) == -2
+    assert lib.cast_weight_scale(p, p, 4, 64, 2, p, 5, st) == -4
+    assert lib.cast_weight_scale(p, nul, 4, 64, 2, p, 0, st) == -1
+    assert lib.cast_weight_scale_grad(p, p, 0, 4, 64, 0, p, st) == -2
+    assert lib.cast_weight_scale_grad(p, p, 0, 4, 64, 2, nul, st) == -1
+    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 2, 4, nul, 0, p, st) == -1
+    assert lib.cast_nm_project_compress(p, p, 3, nul, 4, 64, 2, 4, p, 0, p, st) == -2
+    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 2, 4, p, 9, p, st) == -4
+    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 60, 4, 8, p, 0, p, st) == -2
+    assert lib.cast_mask_stats(p, nul, nul, 4, 64, p, p, st) == -1
+    assert lib.cast_hbm_copy_probe(p, p, 24, st) == -2
+    assert lib.cast_hbm_copy_probe(p, odd, 32, st) == -3
+    assert lib.cast_hbm_copy_probe(nul, nul, 0, st) == 0
+
+
+def test_iteration_config_reading():
+    # Algorithm 1 loops t = 0..T-1 with alpha_t = t/T; masks refresh when t mod T_1 == 0
+    c0 = B.iteration_config(0, 100)
+    assert c0.alpha == 0.0 and c0.refresh_mask == 1
+    assert abs(c0.bias_corr1 - 0.1) < 1e-7 and abs(c0.bias_corr2 - 0.001) < 1e-7
+    c = B.iteration_config(25, 100, mask_period=10, lambda_=4e-7)
+    assert c.alpha == 0.25 and c.refresh_mask == 0 and c.lambda_ == 4e-7
+    assert B.iteration_config(30, 100).refresh_mask == 1

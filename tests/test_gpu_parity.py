@@ -1,0 +1,354 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded
+inputs.  Masks, packed values and metadata must match bit for bit.  fp32 state is compared
+twice: against the oracle run in the kernel's own precision (one fp32 rounding per operation),
+where the bound is max relative error 1e-6 and the observed difference is zero bits, and
+against the oracle in double, where the bound is 1e-6 of each entry's running maximum
+magnitude (see test_oracle_step.py for why that is the meaningful scale)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_25996_amd import binding as B
+from paper_2509_25996_amd import synth
+
+from gpu_util import (DEV, GpuState, OracleState, assert_same_bits, dev, host, max_rel_err, oracle_cfg, words)
+
+pytestmark = pytest.mark.gpu
+
+NM = [(1, 2), (2, 4), (1, 4), (3, 4), (4, 8), (2, 8), (7, 8)]
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _library():
+    B.load()
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    oracle.build()
+
+
+# --------------------------------------------------------------------------- selection (Eq. 6)
+def _select_gpu(w, n, m):
+    rows, cols = w.shape
+    mask = B.alloc_mask(rows, cols, DEV)
+    mask.fill_(-1)   # stale contents must be overwritten, padding bits included
+    B.cast_nm_select(dev(w), n, m, mask)
+    torch.cuda.synchronize()
+    return words(mask)
+
+
+@pytest.mark.parametrize("n,m", NM)
+@pytest.mark.parametrize("shape", [(768, 768), (3, 8 * 100), (5, 32 * 9), (7, 40), (1, 8), (64, 4096 + 32)])
+def test_select_matches_oracle(n, m, shape):
+    rows, cols = shape
+    w = synth.tie_outlier_weights(0, 1, rows, cols)
+    got = _select_gpu(w, n, m)
+    ref = oracle.pack_mask_bits(oracle.nm_select(w, n, m))
+    assert got.shape == ref.shape
+    assert (got == ref).all()
+
+
+def test_select_paper_example_and_special_values():
+    # Sec. 5.1's printed 1:2 example, through the GPU path
+    got = _select_gpu(np.array([[1.01, 1.00], [1.00, 1.01]], np.float32), 1, 2)
+    assert got.tolist() == [[0b01], [0b10]]
+    inf, nan, den = np.float32(np.inf), np.float32(np.nan), np.float32(1e-45)
+    w = np.array([[0.0, -0.0, den, 0.0, den, 2 * den, 0.0, -den, 1e30, -inf, 3.0, 2.0, inf, nan, -inf, 1.0,
+                   1.0, 2.0, nan, 3.0, 0, 0, 0, 0, -0.5, 0.5, 0.5, -0.5, 1, 1, 1, 1]], np.float32)
+    for n, m in [(2, 4), (1, 4), (4, 8), (1, 2), (3, 8)]:
+        for reps in (1, 8):   # 32 columns: scalar kernel; 256: vector kernel
+            ww = np.tile(w, (2, reps))
+            assert (_select_gpu(ww, n, m) == oracle.pack_mask_bits(oracle.nm_select(ww, n, m))).all()
+
+
+# --------------------------------------------------------------------------- AdamS step
+def _run_both(w0, grads, cfgs, arith, scales=None, bf16=False):
+    """grads: list of fp32 arrays (already bf16-representable when bf16).  Returns the two states
+    and per-step lists of dL/dA (gpu fp32, oracle double)."""
+    n_seg = cfgs[0].scale_segments
+    g = GpuState(w0, n_seg)
+    o = OracleState(w0, arith)
+    gAs = []
+    for t, (grad, cfg) in enumerate(zip(grads, cfgs)):
+        A = None if scales is None else scales[t]
+        gt = dev(grad, torch.bfloat16 if bf16 else None)
+        g.step(gt, cfg, scale=None if A is None else dev(A))
+        ref_gA = o.step(grad, oracle_cfg(cfg), A=A)
+        if A is not None:
+            gAs.append((host(g.scale_grad).copy(), ref_gA))
+    torch.cuda.synchronize()
+    return g, o, gAs
+
+
+def _check_state(g, o, exact, tol_w=1e-6):
+    assert (words(g.mask) == oracle.pack_mask_bits(o.keep)).all(), "mask bits"
+    for name, got, ref, sc in (("w", host(g.w), o.w, o.scale[0]), ("mu", host(g.m), o.m, o.scale[1]),
+                               ("v", host(g.v), o.v, o.scale[2])):
+        if exact:
+            assert max_rel_err(got, ref) <= 1e-6, name      # the stated bar ...
+            assert_same_bits(got, ref, name)                 # ... and what is actually observed
+        else:
+            tol = tol_w if name == "w" else 1e-6
+            err = np.abs(got.astype(np.float64) - ref)
+            assert (err <= tol * sc).all(), (name, float((err / np.maximum(sc, 1e-300)).max()))
+
+
+@pytest.mark.parametrize("lam,period", [(2e-6, 10), (2e-6, 1), (1e-3, 1)])
+def test_config1_768x768_ten_steps_then_pack(lam, period):
+    # one fp32 768x768 weight, fp32 grads, zero moments, 2:4, 10 steps, then hard projection + pack
+    rows = cols = 768
+    steps = 10
+    w0 = synth.weights(0, 0, rows, cols)
+    grads = [synth.grads_f32(0, 0, t, rows, cols) for t in range(steps)]
+    cfgs = [B.iteration_config(t, steps, mask_period=period, lr=1e-4, lambda_=lam) for t in range(steps)]
+    g, o, _ = _run_both(w0, grads, cfgs, "f32")
+    _check_state(g, o, exact=True)
+    g64, o64, _ = _run_both(w0, grads, cfgs, "f64")
+    _check_state(g64, o64, exact=False, tol_w=1e-6 if lam < 1e-4 else 8e-6)
+    # final hard N:M projection of the trained weights, packed
+    for vdtype, code in ((torch.float32, B.CAST_F32), (torch.bfloat16, B.CAST_BF16)):
+        _, vbytes, mbytes = B.cast_sizes(rows, cols, 2, 4, code)
+        values = torch.empty((rows, cols // 2), dtype=vdtype, device=DEV)
+        meta = torch.empty((rows, mbytes // 4 // rows), dtype=torch.int32, device=DEV)
+        assert values.numel() * values.element_size() == vbytes
+        B.cast_nm_project_compress(g.w, 2, 4, values, meta)
+        torch.cuda.synchronize()
+        ref_v, ref_m = oracle.project_compress(o.w, 2, 4)
+        assert (words(meta) == ref_m).all()
+        if vdtype == torch.float32:
+            assert_same_bits(host(values), ref_v, "values")
+        else:
+            assert (host(values.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref_v)).all()
+        # Algorithm 1 literally: the last refreshed mask instead of a fresh projection
+        B.cast_nm_project_compress(g.w, 2, 4, values, meta, mask_bits=g.mask)
+        torch.cuda.synchronize()
+        ref_v, ref_m = oracle.project_compress(o.w, 2, 4, keep=o.keep)
+        assert (words(meta) == ref_m).all()
+        if vdtype == torch.float32:
+            assert_same_bits(host(values), ref_v, "values (stored mask)")
+
+
+def _adam_on_scale(A, mA, vA, gA, k, lr=1e-3):
+    # the scale factors are ordinary parameters; this plain Adam only manufactures inputs (A_t) for both sides
+    mA[:] = 0.9 * mA + 0.1 * gA
+    vA[:] = 0.999 * vA + 0.001 * gA * gA
+    A -= (lr * (mA / (1 - 0.9 ** k)) / (np.sqrt(vA / (1 - 0.999 ** k)) + 1e-8)).astype(np.float32)
+
+
+@pytest.mark.parametrize("name,rows,cols", [("q", 768, 768), ("fc1", 3072, 768), ("fc2", 768, 3072)])
+def test_config2_bf16_grads_scaled_ramp_100_steps(name, rows, cols):
+    # the three distinct shapes of the 125M-class set; fp32 master weights, bf16 grads, 2:4, alpha ramped
+    # from 0 over 100 steps, masks refreshed every 10, n = 2 weight scaling starting from A = 1.
+    steps, n = 100, 2
+    lam = 1e-3   # of the gradients' order (Sec. 4.1.2) so that masks really flip inside 100 steps
+    tid = {"q": 0, "fc1": 4, "fc2": 5}[name]
+    w0 = synth.weights(0, tid, rows, cols)
+    g = GpuState(w0, n)
+    o = OracleState(w0, "f32")
+    A = np.ones((rows, n), np.float32)
+    mA, vA = np.zeros((rows, n)), np.zeros((rows, n))
+    first_keep = None
+    for t in range(steps):
+        gb = synth.grads_bf16(0, tid, t, rows, cols)
+        cfg = B.iteration_config(t, steps, mask_period=10, lr=1e-4, lambda_=lam, scale_segments=n)
+        g.step(gb.to(DEV), cfg, scale=dev(A))
+        ref_gA = o.step(synth.widen_bf16(gb), oracle_cfg(cfg), A=A)
+        if t == 0:
+            first_keep = o.keep.copy()
+        got_gA = host(g.scale_grad).astype(np.float64)
+        # fp32 tree sum vs double sum of ~cols/n products: bounded by the sum of magnitudes
+        bound = 1e-5 * np.abs(ref_gA).max() + 1e-6 * np.sqrt(cols) * 0.02 * 1e-3
+        assert np.abs(got_gA - ref_gA).max() <= bound
+        _adam_on_scale(A, mA, vA, ref_gA, t + 1)
+        if t % 10 == 9:
+            _check_state(g, o, exact=True)
+    assert (o.keep != first_keep).any(), "the test must exercise mask flips"
+    values = torch.empty((rows, cols // 2), dtype=torch.float32, device=DEV)
+    meta = torch.empty((rows, cols // 32), dtype=torch.int32, device=DEV)
+    B.cast_nm_project_compress(g.w, 2, 4, values, meta, scale=dev(A))
+    torch.cuda.synchronize()
+    ref_v, ref_m = oracle.project_compress(o.w, 2, 4, A=A)
+    assert (words(meta) == ref_m).all()
+    assert_same_bits(host(values), ref_v, "folded values")
+
+
+@pytest.mark.parametrize("n,m", NM)
+@pytest.mark.parametrize("rows,cols,nseg", [(6, 512, 0), (6, 512, 2), (5, 1280 + 64, 2), (7, 72, 3), (3, 40, 0),
+                                            (9, 24, 1), (2, 8, 0)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_step_every_pattern_and_odd_shapes(n, m, rows, cols, nseg, bf16):
+    if cols % m or (nseg and (cols // nseg) % m):
+        pytest.skip("shape not valid for this M")
+    steps = 3
+    rng = np.random.default_rng(rows * cols + n)
+    w0 = synth.tie_outlier_weights(1, 7, rows, cols) if cols % 8 == 0 else synth.weights(1, 7, rows, cols)
+    grads = []
+    for t in range(steps):
+        gr = synth.grads_f32(1, 7, t, rows, cols)
+        grads.append(synth.widen_bf16(torch.from_numpy(gr).to(torch.bfloat16)) if bf16 else gr)
+    cfgs = [B.iteration_config(t, steps, mask_period=2, lr=1e-3, lambda_=1e-3, n_keep=n, m_group=m,
+                               scale_segments=nseg) for t in range(steps)]
+    scales = None
+    if nseg:
+        scales = [(1 + 0.2 * rng.standard_normal((rows, nseg))).astype(np.float32) for _ in range(steps)]
+    g, o, gAs = _run_both(w0, grads, cfgs, "f32", scales=scales, bf16=bf16)
+    _check_state(g, o, exact=True)
+    for got, ref in gAs[-1:]:
+        assert np.abs(got - ref).max() <= 1e-5 * max(np.abs(ref).max(), 1e-12) + 1e-9
+
+
+def test_step_special_values_bit_exact():
+    # zeros of both signs, denormals, infinities and NaN in every array; all-zero groups; v denormal
+    rng = np.random.default_rng(3)
+    rows, cols = 4, 512
+    pool = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-39, 1e-38, np.inf, -np.inf, np.nan, 1.0, -2.5, 3e38, 1e-20, 0.02],
+                    np.float32)
+    def draw(p_special):
+        x = (rng.standard_normal((rows, cols)) * 0.02).astype(np.float32)
+        pick = rng.random((rows, cols)) < p_special
+        x[pick] = pool[rng.integers(0, len(pool), int(pick.sum()))]
+        return x
+    w0 = draw(0.3)
+    w0[:, :16] = 0.0
+    g, o = GpuState(w0), OracleState(w0, "f32")
+    g.m.copy_(dev(draw(0.2)))
+    g.v.copy_(dev(np.abs(draw(0.2))))
+    o.m[:] = host(g.m)
+    o.v[:] = host(g.v)
+    for t in range(3):
+        grad = draw(0.2)
+        cfg = B.iteration_config(t, 3, mask_period=1, lr=1e-2, lambda_=1e-3)
+        g.step(dev(grad), cfg)
+        o.step(grad, oracle_cfg(cfg))
+    torch.cuda.synchronize()
+    assert (words(g.mask) == oracle.pack_mask_bits(o.keep)).all()
+    for name, got, ref in (("w", host(g.w), o.w), ("mu", host(g.m), o.m), ("v", host(g.v), o.v)):
+        assert_same_bits(got, ref, name)
+
+
+def test_textbook_flag_and_alpha_zero():
+    # alpha = 0 with the second moment fed g^2 is plain Adam: compare with the library optimizer (fp32, a few ulp)
+    rows, cols, steps = 8, 256, 5
+    w0 = synth.weights(2, 0, rows, cols)
+    g = GpuState(w0)
+    p = torch.nn.Parameter(torch.from_numpy(w0.copy()).double())
+    opt = torch.optim.Adam([p], lr=1e-4, betas=(float(np.float32(0.9)), float(np.float32(0.999))), eps=1e-8)
+    for t in range(steps):
+        grad = synth.grads_f32(2, 0, t, rows, cols)
+        cfg = B.iteration_config(t, steps, mask_period=1, lr=1e-4, lambda_=1e-3, flags=B.FLAG_V_FROM_GRAD)
+        cfg.alpha = 0.0
+        g.step(dev(grad), cfg)
+        p.grad = torch.from_numpy(grad).double()
+        opt.step()
+    torch.cuda.synchronize()
+    ref_w = p.detach().numpy()
+    scale = np.maximum(np.abs(w0), np.abs(ref_w))     # entries that cross zero keep their earlier absolute error
+    assert (np.abs(host(g.w) - ref_w) <= 1e-6 * scale).all()
+    assert max_rel_err(host(g.v), opt.state[p]["exp_avg_sq"].numpy()) <= 1e-6
+
+
+def test_empty_tensors_do_nothing():
+    for rows, cols in [(0, 64), (4, 0), (0, 0)]:
+        w = torch.zeros((rows, cols), device=DEV)
+        mask = B.alloc_mask(rows, cols, DEV)
+        B.cast_nm_select(w, 2, 4, mask)
+        B.cast_adams_step(w, w.clone(), w.clone(), w.clone(), mask, B.AdamsConfig())
+        vals = torch.zeros((rows, cols // 2), device=DEV)
+        B.cast_nm_project_compress(w, 2, 4, vals, torch.zeros((rows, cols // 32), dtype=torch.int32, device=DEV))
+    torch.cuda.synchronize()
+
+
+def test_step_is_deterministic():
+    rows, cols, n = 256, 2048, 2
+    w0 = synth.weights(3, 0, rows, cols)
+    gb = synth.grads_bf16(3, 0, 0, rows, cols).to(DEV)
+    A = dev((1 + 0.1 * np.random.default_rng(0).standard_normal((rows, n))).astype(np.float32))
+    outs = []
+    for _ in range(2):
+        g = GpuState(w0, n)
+        g.step(gb, B.iteration_config(5, 10, mask_period=5, lambda_=1e-3, scale_segments=n), scale=A)
+        torch.cuda.synchronize()
+        outs.append([host(x).copy() for x in (g.w, g.m, g.v, g.mask, g.scale_grad)])
+    for a, b in zip(*outs):
+        assert a.tobytes() == b.tobytes()
+
+
+# --------------------------------------------------------------------------- Eq. 12 and dL/dA
+@pytest.mark.parametrize("rows,cols,n", [(64, 1024, 2), (5, 24, 3), (3, 36, 1), (16, 11008, 2), (4, 6, 2)])
+def test_weight_scale_and_grad(rows, cols, n):
+    rng = np.random.default_rng(cols)
+    w = synth.weights(4, 0, rows, cols)
+    A = (1 + 0.3 * rng.standard_normal((rows, n))).astype(np.float32)
+    out = torch.empty((rows, cols), device=DEV)
+    B.cast_weight_scale(dev(w), dev(A), out)
+    ref = oracle.weight_scale(w, A)
+    assert_same_bits(host(out), ref, "scaled weights")
+    if cols % 4 == 0:
+        outb = torch.empty((rows, cols), dtype=torch.bfloat16, device=DEV)
+        B.cast_weight_scale(dev(w), dev(A), outb)
+        assert (host(outb.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref)).all()
+    wd = dev(w)
+    B.cast_weight_scale(wd, dev(A), wd)      # in place (the fold)
+    assert_same_bits(host(wd), ref, "in-place fold")
+    for bf16 in (False, True):
+        gs = synth.grads_f32(4, 0, 0, rows, cols)
+        gt = torch.from_numpy(gs).to(torch.bfloat16) if bf16 else torch.from_numpy(gs)
+        gs = gt.float().numpy()
+        if bf16 and cols % 4:
+            continue
+        gA = torch.zeros((rows, n), device=DEV)
+        B.cast_weight_scale_grad(dev(w), gt.to(DEV), n, gA)
+        ref_gA = oracle.weight_scale_grad(w, gs, n)
+        terms = np.abs(gs.astype(np.float64) * w).reshape(rows, n, -1).sum(-1)
+        assert (np.abs(host(gA) - ref_gA) <= 1e-5 * terms + 1e-30).all()
+        if (cols // n) % 4 == 0:
+            # the fused step reports the same numbers, bit for bit
+            st = GpuState(w, n)
+            st.step(gt.to(DEV), B.iteration_config(0, 10, scale_segments=n), scale=dev(A))
+            assert host(st.scale_grad).tobytes() == host(gA).tobytes()
+
+
+# --------------------------------------------------------------------------- hard prune + pack
+@pytest.mark.parametrize("n,m", NM)
+@pytest.mark.parametrize("rows,cols", [(33, 1024), (4, 8 * 37), (3, 64), (2, 8)])
+@pytest.mark.parametrize("vdtype", [torch.float32, torch.bfloat16])
+def test_project_compress_matches_oracle(n, m, rows, cols, vdtype):
+    w = synth.tie_outlier_weights(5, 3, rows, cols)
+    rng = np.random.default_rng(0)
+    for use_scale in (False, True):
+        A = (1 + 0.3 * rng.standard_normal((rows, 2))).astype(np.float32) if use_scale else None
+        if use_scale and (cols // 2) % m:
+            continue
+        code = B.CAST_BF16 if vdtype == torch.bfloat16 else B.CAST_F32
+        _, vbytes, mbytes = B.cast_sizes(rows, cols, n, m, code)
+        values = torch.full((rows, cols // m * n), 7.0, dtype=vdtype, device=DEV)
+        meta = torch.full((rows, mbytes // 4 // rows), -1, dtype=torch.int32, device=DEV)
+        assert values.numel() * values.element_size() == vbytes
+        B.cast_nm_project_compress(dev(w), n, m, values, meta, scale=None if A is None else dev(A))
+        torch.cuda.synchronize()
+        ref_v, ref_m = oracle.project_compress(w, n, m, A=A)
+        assert (words(meta) == ref_m).all()
+        if vdtype == torch.float32:
+            assert_same_bits(host(values), ref_v, "values")
+        else:
+            assert (host(values.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref_v)).all()
+        # exactly N kept per group (Eq. 4): every group contributes N values, by construction of the shapes
+        assert values.shape[1] * m == cols * n
+
+
+# --------------------------------------------------------------------------- appendix statistics
+def test_mask_stats_match_oracle():
+    rows, cols = 96, 1024 + 40
+    w = synth.weights(6, 0, rows, cols)
+    w2 = (w + 0.01 * np.random.default_rng(1).standard_normal(w.shape)).astype(np.float32)
+    k0, k1 = oracle.nm_select(w, 2, 4), oracle.nm_select(w2, 2, 4)
+    m0, m1 = B.alloc_mask(rows, cols, DEV), B.alloc_mask(rows, cols, DEV)
+    B.cast_nm_select(dev(w), 2, 4, m0)
+    B.cast_nm_select(dev(w2), 2, 4, m1)
+    flips = torch.zeros(1, dtype=torch.int64, device=DEV)
+    l1 = torch.zeros(2, dtype=torch.float64, device=DEV)
+    B.cast_mask_stats(dev(w2), m1, m0, flips, l1)
+    B.cast_mask_stats(dev(w2), m1, m0, flips, l1)     # accumulates
+    torch.cuda.synchronize()
+    f, kept, total = oracle.mask_stats(w2, k1, k0)
+    assert int(flips.item()) == 2 * f and f > 0
+    assert np.allclose(host(l1), [2 * kept, 2 * total], rtol=1e-12)
