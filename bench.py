@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdamS N:M step on one MI355X.
+
+A "step" is one AdamS iteration (Algorithm 1 with the weight scaling of Eq. 12, n = 2) over
+every linear weight of a LLaMA2-7B-shaped model: 224 matrices, 6,476,005,376 parameters,
+fp32 weights and moments, bf16 gradients and one mask bit per parameter, all resident in HBM.
+Masks are refreshed every 10th step (T_1 = 10), so the timed region holds refresh and
+non-refresh steps in the paper's 1:9 ratio.  The final hard projection + packing runs once per
+training, not per step; it is timed separately and reported under "extra".
+
+Prints ONE JSON line (see README/DESIGN for the fields).  Inputs are synthetic Gaussians drawn
+in device memory; nothing is read from disk.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+BYTES_PER_PARAM = 26.125         # read w, mu, v (fp32) + g (bf16) + 1 mask bit; write w, mu, v
+# HBM bytes per parameter of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/; None until measured.
+MEASURED_TRAFFIC_BYTES_PER_PARAM = None
+
+LR, LAMBDA, TOTAL_STEPS, MASK_PERIOD, SEGMENTS = 2e-5, 4e-7, 7500, 10, 2   # Table 11 (LLaMA), Sec. 4.1, Sec. 5
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Model:
+    """Every linear weight of the workload with its optimizer state, in device memory."""
+
+    def __init__(self, workload: str, layers, torch, B, synth, dev):
+        self.shapes = synth.weight_set(workload, layers)
+        self.params = synth.set_params(self.shapes)
+        self.t = []
+        for i, (_, r, c) in enumerate(self.shapes):
+            w = synth.device_gaussian((r, c), 0.02, torch.float32, 1000 + i, dev)
+            g = synth.device_gaussian((r, c), 1e-3, torch.bfloat16, 500000 + i, dev)
+            self.t.append(dict(w=w, g=g, m=torch.zeros_like(w), v=torch.zeros_like(w),
+                               mask=B.alloc_mask(r, c, dev),
+                               A=torch.ones((r, SEGMENTS), device=dev),
+                               gA=torch.zeros((r, SEGMENTS), device=dev)))
+
+    def step(self, B, t: int, scaled: bool):
+        cfg = B.iteration_config(t, TOTAL_STEPS, mask_period=MASK_PERIOD, lr=LR, lambda_=LAMBDA,
+                                 scale_segments=SEGMENTS if scaled else 0)
+        for x in self.t:
+            B.cast_adams_step(x["w"], x["g"], x["m"], x["v"], x["mask"], cfg,
+                              scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None)
+        return cfg.refresh_mask
+
+
+def cpu_baseline(synth, seconds_hint=20.0):
+    """The oracle (plain C, fp32-per-operation variant, OpenMP over rows) on one LLaMA2-7B-shaped
+    decoder layer's 7 matrices, host cores only."""
+    import numpy as np
+
+    import oracle
+    oracle.build()
+    threads = min(16, os.cpu_count() or 1)
+    shapes = synth.weight_set("llama2_7b", 1)
+    rng = np.random.default_rng(0)
+    cfg = oracle.AdamsCfg(lr=LR, lambda_=LAMBDA, alpha=0.5, bias_corr1=0.9, bias_corr2=0.1,
+                          refresh_mask=0, scale_segments=SEGMENTS)
+    params, elapsed = 0, 0.0
+    for (_, r, c) in shapes:
+        w = (rng.standard_normal((r, c), np.float32) * np.float32(0.02))
+        g = (rng.standard_normal((r, c), np.float32) * np.float32(1e-3))
+        m = np.zeros_like(w)
+        v = np.zeros_like(w)
+        keep = oracle.nm_select(w[:1], 2, 4)  # warm the library
+        keep = np.zeros(w.shape, np.uint8)
+        A = np.ones((r, SEGMENTS), np.float32)
+        cfg.refresh_mask = 1
+        oracle.adams_step(w, g, m, v, keep, cfg, A=A, arithmetic="f32", nthreads=threads)   # untimed, builds the mask
+        cfg.refresh_mask = 0
+        t0 = time.perf_counter()
+        oracle.adams_step(w, g, m, v, keep, cfg, A=A, arithmetic="f32", nthreads=threads)
+        elapsed += time.perf_counter() - t0
+        params += r * c
+        if elapsed > seconds_hint:
+            break
+    return {"value": params / elapsed / 1e9, "unit": "Gparams/s", "cores": threads, "kind": "oracle",
+            "sample": f"one non-refresh AdamS 2:4 step (fp32-per-operation oracle, scaling n=2) over "
+                      f"{params} params of one LLaMA2-7B-shaped layer, {elapsed:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama2_7b", choices=["opt125m", "llama2_7b", "llama2_13b"])
+    ap.add_argument("--layers", type=int, default=None, help="use only the first LAYERS decoder blocks (debugging)")
+    ap.add_argument("--no-scale", action="store_true", help="time the step without weight scaling")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+
+    import torch
+
+    from paper_2509_25996_amd import binding as B
+    from paper_2509_25996_amd import synth
+    B.load()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    scaled = not args.no_scale
+
+    t0 = time.time()
+    model = Model(args.workload, args.layers, torch, B, synth, dev)
+    torch.cuda.synchronize()
+    log(f"[bench] {args.workload}: {len(model.shapes)} matrices, {model.params} params resident "
+        f"({torch.cuda.memory_allocated() / 2**30:.1f} GiB) after {time.time() - t0:.1f} s")
+
+    t = 0
+    for _ in range(args.warmup):
+        model.step(B, t, scaled)
+        t += 1
+    torch.cuda.synchronize()
+
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    kinds = []
+    torch.cuda.synchronize()
+    marks[0].record()
+    for k in range(args.steps):
+        kinds.append(model.step(B, t, scaled))
+        t += 1
+        marks[k + 1].record()
+    torch.cuda.synchronize()
+    total_ms = marks[0].elapsed_time(marks[-1])
+    step_ms = [marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)]
+    ms_per_step = total_ms / args.steps
+    value = model.params / (ms_per_step * 1e-3) / 1e9
+    plain = [m for m, k in zip(step_ms, kinds) if not k]
+    fresh = [m for m, k in zip(step_ms, kinds) if k]
+    log(f"[bench] {ms_per_step:.3f} ms/step, {value:.1f} Gparams/s; non-refresh {sum(plain) / max(len(plain), 1):.3f} ms, "
+        f"refresh {sum(fresh) / max(len(fresh), 1):.3f} ms")
+
+    # dominant kernel: the non-refresh fused step (9 of 10 steps); one launch per matrix
+    launches = len(model.shapes)
+    dom_ms = (sum(plain) / len(plain)) if plain else ms_per_step
+    bytes_per_launch = BYTES_PER_PARAM * model.params / launches
+    achieved = bytes_per_launch / (dom_ms * 1e-3 / launches) / 1e9
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": None if MEASURED_TRAFFIC_BYTES_PER_PARAM is None
+                else MEASURED_TRAFFIC_BYTES_PER_PARAM * model.params / launches,
+                "kernel": "adams_step_vec<M=4, bf16 grad, stored mask, scaled>" if scaled
+                else "adams_step_vec<M=4, bf16 grad, stored mask>",
+                "bytes_per_launch": bytes_per_launch, "avg_launch_us": round(dom_ms * 1e3 / launches, 2)}
+
+    extra = {"ms_step_non_refresh": round(dom_ms, 3),
+             "ms_step_refresh": round(sum(fresh) / len(fresh), 3) if fresh else None}
+    if not args.no_extra:
+        # achievable copy bandwidth on this machine (read + write of 2 GiB), for context beside the spec peak
+        n = 1 << 30
+        a = torch.empty(n // 4, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        B.cast_hbm_copy_probe(b, a)
+        e0.record()
+        for _ in range(10):
+            B.cast_hbm_copy_probe(b, a)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["copy_probe_GBs"] = round(2 * n * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del a, b
+        # the epilogue of training: hard 2:4 projection + fold + pack of every matrix (once per run)
+        outs = [(torch.empty((r, c // 2), device=dev), torch.empty((r, c // 32), dtype=torch.int32, device=dev))
+                for (_, r, c) in model.shapes[:7]]
+        for rep in range(2):
+            e0.record()
+            for i, x in enumerate(model.t):
+                vals, meta = outs[i % 7]
+                B.cast_nm_project_compress(x["w"], 2, 4, vals, meta, scale=x["A"] if scaled else None)
+            e1.record()
+            torch.cuda.synchronize()
+        pc_ms = e0.elapsed_time(e1)
+        extra["project_compress_ms"] = round(pc_ms, 3)
+        extra["project_compress_GBs"] = round(6.125 * model.params / (pc_ms * 1e-3) / 1e9, 1)
+
+    out = {"metric": "AdamS N:M step Gparams/s at LLaMA2-7B shape; % of MI355X peak HBM BW",
+           "value": round(value, 2), "unit": "Gparams/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{args.workload} linear weight set ({len(model.shapes)} matrices, {model.params} params), "
+                                  f"2:4, fp32 w/mu/v + bf16 grads + mask bits resident, "
+                                  f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step",
+                      "n_keep": 2, "m_group": 4, "scale_segments": SEGMENTS if scaled else 0,
+                      "pct_of_peak_hbm": round(100 * BYTES_PER_PARAM * value / HBM_PEAK_GBS, 2)},
+           "roofline": roofline, "extra": extra}
+    if not args.no_cpu_baseline:
+        del model
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(synth)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
