@@ -170,6 +170,15 @@ cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uin
  */
 cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * Diagnostic, runs on the HOST (both pointers HOST): out[i] = x[i] / y computed by the very
+ * routine the kernels use for the two bias-correction divisions of Eq. 8 (a short FMA sequence
+ * with a precomputed reciprocal inside a checked range, the IEEE division outside it).  It
+ * exists so that the claim "identical to the correctly rounded quotient" can be tested on any
+ * machine.
+ */
+cast_status cast_debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
+
 #ifdef __cplusplus
 }
 #endif

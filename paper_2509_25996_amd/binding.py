@@ -17,7 +17,8 @@ CAST_F32, CAST_BF16 = 0, 1
 FLAG_V_FROM_GRAD = 1
 
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
-           "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe"]
+           "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
+           "cast_debug_div_by_uniform"]
 
 
 class CastError(RuntimeError):
@@ -80,6 +81,7 @@ def load():
     L.cast_nm_project_compress.argtypes = [vp, vp, ci, vp, i64, i64, ci, ci, vp, ci, vp, vp]
     L.cast_mask_stats.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp]
     L.cast_hbm_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
+    L.cast_debug_div_by_uniform.argtypes = [vp, C.c_float, vp, i64]
     for name in EXPORTS:
         if name != "cast_status_str":
             getattr(L, name).restype = C.c_int32
@@ -180,6 +182,16 @@ def cast_hbm_copy_probe(dst, src, stream=None):
     _dev(dst, src)
     _check(load().cast_hbm_copy_probe(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)),
            "cast_hbm_copy_probe")
+
+
+def cast_debug_div_by_uniform(x, y: float):
+    """Host-side: numpy fp32 array x divided by y through the kernels' own division routine."""
+    import numpy as np
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty_like(x)
+    _check(load().cast_debug_div_by_uniform(x.ctypes.data_as(C.c_void_p), y, out.ctypes.data_as(C.c_void_p), x.size),
+           "cast_debug_div_by_uniform")
+    return out
 
 
 def iteration_config(t: int, total_steps: int, mask_period: int = 10, **kw) -> AdamsConfig:

@@ -39,24 +39,8 @@ struct Chunk {
 template <bool BF16>
 __device__ __forceinline__ void load_grad4(const void *grad, int64_t idx, float (&g)[4])
 {
-    if constexpr (BF16) {
-        const uint2 p = *reinterpret_cast<const uint2 *>(static_cast<const uint16_t *>(grad) + idx);
-        g[0] = bf16_lo(p.x); g[1] = bf16_hi(p.x); g[2] = bf16_lo(p.y); g[3] = bf16_hi(p.y);
-    } else {
-        const float4 p = *reinterpret_cast<const float4 *>(static_cast<const float *>(grad) + idx);
-        g[0] = p.x; g[1] = p.y; g[2] = p.z; g[3] = p.w;
-    }
-}
-
-__device__ __forceinline__ void load4(const float *p, int64_t idx, float (&x)[4])
-{
-    const float4 t = *reinterpret_cast<const float4 *>(p + idx);
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-}
-
-__device__ __forceinline__ void store4(float *p, int64_t idx, const float (&x)[4])
-{
-    *reinterpret_cast<float4 *>(p + idx) = make_float4(x[0], x[1], x[2], x[3]);
+    if constexpr (BF16) load4_bf16_stream(static_cast<const uint16_t *>(grad), idx, g);
+    else load4_stream(static_cast<const float *>(grad), idx, g);
 }
 
 template <bool BF16, bool REFRESH>
@@ -69,11 +53,11 @@ __device__ __forceinline__ void chunk_load(Chunk &c, const SpanArgs &a, int64_t 
 #pragma unroll
     for (int j = 0; j < 4; ++j) c.w[j] = c.m[j] = c.v[j] = c.g[j] = 0.0f;
     if (c.act) {
-        load4(a.w, c.idx, c.w);
+        load4_stream(a.w, c.idx, c.w);
         load_grad4<BF16>(a.grad, c.idx, c.g);
-        load4(a.m, c.idx, c.m);
-        load4(a.v, c.idx, c.v);
-        if constexpr (!REFRESH) c.nib = (a.mask[c.idx >> 5] >> (unsigned)(c.idx & 31)) & 0xFu;
+        load4_stream(a.m, c.idx, c.m);
+        load4_stream(a.v, c.idx, c.v);
+        if constexpr (!REFRESH) c.nib = (__builtin_nontemporal_load(a.mask + (c.idx >> 5)) >> (unsigned)(c.idx & 31)) & 0xFu;
     }
 }
 
@@ -81,7 +65,7 @@ __device__ __forceinline__ void chunk_load(Chunk &c, const SpanArgs &a, int64_t 
 // Control flow is uniform across the wavefront: lanes past the end of the span carry zeros
 // through the arithmetic and only their loads and stores are switched off, so the cross-lane
 // steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly) always see all 64 lanes.
-template <int M, bool BF16, bool REFRESH, bool SCALED>
+template <int M, bool BF16, bool REFRESH, bool SCALED, int U = 2>
 __global__ __launch_bounds__(kBlockThreads) void adams_step_vec(const SpanArgs a)
 {
     __shared__ float partial[kBlockWaves];
@@ -99,7 +83,7 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_vec(const SpanArgs a
     const bool want_gA = SCALED && a.scale_grad != nullptr;
     float acc = 0.0f;
 
-    constexpr int U = 2;  // chunks in flight per wavefront
+    // U = chunks in flight per wavefront
     const int64_t stride = (int64_t)P * kChunk;
     for (int64_t base = (int64_t)sub * kChunk; base < len; base += stride * U) {
         Chunk c[U];
@@ -111,13 +95,13 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_vec(const SpanArgs a
             if constexpr (REFRESH) {
                 c[u].nib = keep_nibble<M>(c[u].w, a.s.n_keep, lane);   // from the incoming weights
                 const uint32_t word = or_reduce_8lanes(c[u].nib << ((lane & 7) * 4));
-                if (c[u].act && (lane & 7) == 0) a.mask[c[u].idx >> 5] = word;
+                if (c[u].act && (lane & 7) == 0) __builtin_nontemporal_store(word, a.mask + (c[u].idx >> 5));
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 float g = c[u].g[j];
                 if constexpr (SCALED) {
-                    if (want_gA) acc = acc + g * c[u].w[j];   // dL/dA term, incoming w
+                    if (want_gA) acc = __builtin_fmaf(g, c[u].w[j], acc);   // dL/dA term, incoming w
                     g = A * g;                                // chain rule of Eq. 12
                 }
                 adams_entry(c[u].w[j], g, c[u].m[j], c[u].v[j], (c[u].nib >> j) & 1u, a.s);
@@ -126,9 +110,9 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_vec(const SpanArgs a
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (c[u].act) {
-                store4(a.w, c[u].idx, c[u].w);
-                store4(a.m, c[u].idx, c[u].m);
-                store4(a.v, c[u].idx, c[u].v);
+                store4_stream(a.w, c[u].idx, c[u].w);
+                store4_stream(a.m, c[u].idx, c[u].m);
+                store4_stream(a.v, c[u].idx, c[u].v);
             }
     }
 
@@ -174,11 +158,11 @@ __global__ __launch_bounds__(kBlockThreads) void scale_grad_vec(const float *w, 
         const int64_t off = base + lane * kLaneElems;
         float wv[4] = {0, 0, 0, 0}, g[4] = {0, 0, 0, 0};
         if (off < len) {
-            load4(w, begin + off, wv);
+            load4_stream(w, begin + off, wv);
             load_grad4<BF16>(grad, begin + off, g);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc = acc + g[j] * wv[j];
+        for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(g[j], wv[j], acc);
     }
     const float wave_total = wave_sum_fixed_order(acc);
     if (P == 1) {
@@ -270,7 +254,7 @@ __global__ __launch_bounds__(kBlockThreads) void scale_grad_rows(const float *w,
     float acc = 0.0f;
     if (seg < num_segments)
         for (int64_t i = lane; i < seg_len; i += kWave)
-            acc = acc + load_grad1<BF16>(grad, seg * seg_len + i) * w[seg * seg_len + i];
+            acc = __builtin_fmaf(load_grad1<BF16>(grad, seg * seg_len + i), w[seg * seg_len + i], acc);
     const float t = wave_sum_fixed_order(acc);
     if (lane == 0 && seg < num_segments) scale_grad[seg] = t;
 }
@@ -327,8 +311,8 @@ static StepScalars make_scalars(const cast_adams_config *cfg)
     s.eps = cfg->eps;
     s.one_minus_alpha = 1.0f - cfg->alpha;
     s.alpha_lambda = cfg->alpha * cfg->lambda;
-    s.bias_corr1 = cfg->bias_corr1;
-    s.bias_corr2 = cfg->bias_corr2;
+    s.bias_corr1 = make_divisor(cfg->bias_corr1);
+    s.bias_corr2 = make_divisor(cfg->bias_corr2);
     s.n_keep = cfg->n_keep;
     s.v_from_grad = (cfg->flags & CAST_FLAG_V_FROM_GRAD) ? 1 : 0;
     return s;
@@ -412,6 +396,13 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     default: launch_unit_dtype<8>(bf16, grid, a, st); break;
     }
     return launch_status();
+}
+
+cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n)
+{
+    const UniformDivisor d = make_divisor(y);
+    for (int64_t i = 0; i < n; ++i) out[i] = div_by_uniform(x[i], d);
+    return CAST_OK;
 }
 
 }  // namespace cast

@@ -188,4 +188,12 @@ cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *
     return launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+cast_status cast_debug_div_by_uniform(const float *x, float y, float *out, int64_t n)
+{
+    if (n < 0) return CAST_ERR_SHAPE;
+    if (n == 0) return CAST_OK;
+    if (!x || !out) return CAST_ERR_NULL;
+    return debug_div_by_uniform(x, y, out, n);
+}
+
 }  // extern "C"

@@ -124,11 +124,80 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x)
     return b >> 16;
 }
 
+// ---- streaming (non-temporal) 16- and 8-byte accesses -------------------------------------
+// Every byte of the optimizer state is touched once per step, so nothing is worth keeping in
+// the caches: the loads and stores carry the non-temporal hint.
+typedef float vf4_t __attribute__((ext_vector_type(4)));
+typedef float vf2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t vu2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void load4_stream(const float *p, int64_t idx, float (&x)[4])
+{
+    const vf4_t t = __builtin_nontemporal_load(reinterpret_cast<const vf4_t *>(p + idx));
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+
+__device__ __forceinline__ void store4_stream(float *p, int64_t idx, const float (&x)[4])
+{
+    const vf4_t t = {x[0], x[1], x[2], x[3]};
+    __builtin_nontemporal_store(t, reinterpret_cast<vf4_t *>(p + idx));
+}
+
+__device__ __forceinline__ void load4_bf16_stream(const uint16_t *p, int64_t idx, float (&g)[4])
+{
+    const vu2_t t = __builtin_nontemporal_load(reinterpret_cast<const vu2_t *>(p + idx));
+    g[0] = bf16_lo(t.x); g[1] = bf16_hi(t.x); g[2] = bf16_lo(t.y); g[3] = bf16_hi(t.y);
+}
+
+// ---- correctly rounded division by a divisor that is the same for every entry ---------------
+// The two bias corrections divide every entry by the same number.  With r = RN(1/y) from the
+// host, two Newton corrections carried by exact FMA residuals give RN(x/y) itself (Markstein's
+// theorem: a faithful quotient corrected once with the correctly rounded reciprocal is the
+// correctly rounded quotient) as long as nothing under- or overflows on the way.  That is
+// guaranteed by range checks: the host enables the short path only for 2^-12 <= y <= 2, and
+// an entry takes it only if 2^-63 <= |x| < 2^65; zeros, denormals, huge values, inf and NaN take
+// the full IEEE division.  The FMAs here are the division algorithm, not a contraction of
+// the update's own multiply-adds.
+struct UniformDivisor {
+    float y;      // the divisor
+    float r;      // RN(1 / y)
+    int fast;     // 1 if y is in the range where the short path is valid
+};
+
+inline UniformDivisor make_divisor(float y)
+{
+    UniformDivisor d;
+    d.y = y;
+    d.r = 1.0f / y;                                   // correctly rounded on the host
+    d.fast = (y >= 0x1p-12f && y <= 2.0f) ? 1 : 0;
+    return d;
+}
+
+__host__ __device__ __forceinline__ float div_by_uniform(float x, const UniformDivisor &d)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t bits = __float_as_uint(x);
+#else
+    uint32_t bits;
+    __builtin_memcpy(&bits, &x, 4);
+#endif
+    const uint32_t e = (bits >> 23) & 0xffu;
+    if (d.fast && (e - 64u) < 129u) {                      // biased exponent in [64, 192]
+        const float q0 = x * d.r;
+        const float e0 = __builtin_fmaf(-d.y, q0, x);
+        const float q1 = __builtin_fmaf(e0, d.r, q0);      // faithful
+        const float e1 = __builtin_fmaf(-d.y, q1, x);      // exact residual
+        return __builtin_fmaf(e1, d.r, q1);                // correctly rounded
+    }
+    return x / d.y;
+}
+
 // ---- Algorithm 1, one entry -------------------------------------------------------------
 // Scalars of one iteration, prepared on the host in fp32 (one rounding each).
 struct StepScalars {
     float lr, beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
-    float one_minus_alpha, alpha_lambda, bias_corr1, bias_corr2;
+    float one_minus_alpha, alpha_lambda;
+    UniformDivisor bias_corr1, bias_corr2;
     int n_keep;
     int v_from_grad;
 };
@@ -151,10 +220,10 @@ __device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float 
     const float s0 = s.beta2 * v;
     const float s1 = s.one_minus_beta2 * second;
     const float v_t = s0 + s1;                                    // v from the decayed momentum
-    const float mu_hat = mu_tilde / s.bias_corr1;                 // IEEE division (see the build flags)
-    const float v_hat = v_t / s.bias_corr2;
+    const float mu_hat = div_by_uniform(mu_tilde, s.bias_corr1);  // = RN(mu~ / bias_corr1)
+    const float v_hat = div_by_uniform(v_t, s.bias_corr2);
     const float denom = __builtin_sqrtf(v_hat) + s.eps;            // IEEE square root
-    const float q = mu_hat / denom;
+    const float q = mu_hat / denom;                                // IEEE division (see the build flags)
     const float step = s.lr * q;
     w = w - step;
     mu = mu_t;                                                    // the undecayed moment is stored

@@ -23,8 +23,6 @@ struct SpanPlan {
 
 SpanPlan plan_spans(int64_t rows, int64_t cols, int n_segments);
 
-struct StepScalarsHost;  // defined with the kernels
-
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
                               const cast_adams_config *cfg, hipStream_t stream);
@@ -42,6 +40,7 @@ cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const u
                               int64_t rows, int64_t cols, unsigned long long *flips, double *l1,
                               hipStream_t stream);
 cast_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
+cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
 
 inline cast_status launch_status()
 {

@@ -120,3 +120,23 @@ def test_iteration_config_reading():
     c = B.iteration_config(25, 100, mask_period=10, lambda_=4e-7)
     assert c.alpha == 0.25 and c.refresh_mask == 0 and c.lambda_ == 4e-7
     assert B.iteration_config(30, 100).refresh_mask == 1
+
+
+def test_division_by_a_common_divisor_is_the_ieee_quotient(lib):
+    # the kernels divide by the two bias corrections with a short FMA sequence; on the host the same
+    # routine must reproduce the correctly rounded quotient for every mantissa, inside and outside its fast range
+    import numpy as np
+    man = np.arange(2 ** 23, dtype=np.uint32)
+    rng = np.random.default_rng(0)
+    ys = [1 - 0.9, 1 - 0.999, 1 - 0.9 ** 7, 1 - 0.999 ** 500, 1.0, 0.99999994, 2.0 ** -12, 2.0, 3.0, 1e-5]
+    ys += list(rng.uniform(2.0 ** -12, 2.0, 3))
+    for k, y in enumerate(ys):
+        y = np.float32(y)
+        for e in ((64, 127, 192) if k < 4 else (100 + k,)) + ((0, 1, 63, 193, 254, 255) if k == 0 else ()):
+            sign = (k + e) & 1
+            x = ((sign << 31) | (e << 23) | man).astype(np.uint32).view(np.float32)
+            got = B.cast_debug_div_by_uniform(x, float(y))
+            with np.errstate(all="ignore"):
+                ref = (x / y).astype(np.float32)
+            same = (got.view(np.uint32) == ref.view(np.uint32)) | (np.isnan(got) & np.isnan(ref))
+            assert same.all(), (float(y), e)
