@@ -28,103 +28,130 @@ struct SpanArgs {
     StepScalars s;
 };
 
-// Registers of one chunk: 4 consecutive entries of each array per lane.
+// Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
+template <bool BF16>
 struct Chunk {
-    float w[4], m[4], v[4], g[4];
-    uint32_t nib;   // mask bits of the 4 entries
-    int64_t idx;    // flat index of the lane's first entry
-    bool act;       // the lane's 4 entries lie inside the span
+    vu4_t w, m, v;
+    vu4_t g;          // fp32 gradient: 4 dwords; bf16: the first 2 dwords hold 4 values
+    uint32_t word;    // the mask word that holds this lane's 4 bits (non-refresh steps)
 };
 
-template <bool BF16>
-__device__ __forceinline__ void load_grad4(const void *grad, int64_t idx, float (&g)[4])
-{
-    if constexpr (BF16) load4_bf16_stream(static_cast<const uint16_t *>(grad), idx, g);
-    else load4_stream(static_cast<const float *>(grad), idx, g);
-}
+// The five streams of one span, each behind a buffer resource whose length is the span's own,
+// so that any access past the end of the span is void (loads give 0, stores are dropped).
+struct SpanBuffers {
+    __amdgpu_buffer_rsrc_t w, m, v, g, mask;
+};
 
 template <bool BF16, bool REFRESH>
-__device__ __forceinline__ void chunk_load(Chunk &c, const SpanArgs &a, int64_t begin, int64_t off,
-                                           int64_t len)
+__device__ __forceinline__ void chunk_load(Chunk<BF16> &c, const SpanBuffers &b, int off)
 {
-    c.act = off < len;
-    c.idx = begin + off;
-    c.nib = 0;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) c.w[j] = c.m[j] = c.v[j] = c.g[j] = 0.0f;
-    if (c.act) {
-        load4_stream(a.w, c.idx, c.w);
-        load_grad4<BF16>(a.grad, c.idx, c.g);
-        load4_stream(a.m, c.idx, c.m);
-        load4_stream(a.v, c.idx, c.v);
-        if constexpr (!REFRESH) c.nib = (__builtin_nontemporal_load(a.mask + (c.idx >> 5)) >> (unsigned)(c.idx & 31)) & 0xFu;
+    c.w = __builtin_amdgcn_raw_buffer_load_b128(b.w, off * 4, 0, kAuxLoad);
+    if constexpr (BF16) {
+        const vu2_t t = __builtin_amdgcn_raw_buffer_load_b64(b.g, off * 2, 0, kAuxLoad);
+        c.g.x = t.x; c.g.y = t.y; c.g.z = 0; c.g.w = 0;
+    } else {
+        c.g = __builtin_amdgcn_raw_buffer_load_b128(b.g, off * 4, 0, kAuxLoad);
     }
+    c.m = __builtin_amdgcn_raw_buffer_load_b128(b.m, off * 4, 0, kAuxLoad);
+    c.v = __builtin_amdgcn_raw_buffer_load_b128(b.v, off * 4, 0, kAuxLoad);
+    if constexpr (!REFRESH) c.word = __builtin_amdgcn_raw_buffer_load_b32(b.mask, (off >> 5) * 4, 0, kAuxLoad);
+    else c.word = 0;
 }
 
-// One wavefront (or waves_per_span cooperating ones) walks one span in chunks of 256 entries.
-// Control flow is uniform across the wavefront: lanes past the end of the span carry zeros
-// through the arithmetic and only their loads and stores are switched off, so the cross-lane
-// steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly) always see all 64 lanes.
-template <int M, bool BF16, bool REFRESH, bool SCALED, int U = 2>
-__global__ __launch_bounds__(kBlockThreads) void adams_step_vec(const SpanArgs a)
+__device__ __forceinline__ void unpack4(const vu4_t &x, float (&f)[4])
 {
-    __shared__ float partial[kBlockWaves];
+    f[0] = __uint_as_float(x.x); f[1] = __uint_as_float(x.y); f[2] = __uint_as_float(x.z); f[3] = __uint_as_float(x.w);
+}
+
+__device__ __forceinline__ vu4_t pack4(const float (&f)[4])
+{
+    vu4_t x = {__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3])};
+    return x;
+}
+
+// One wavefront (or waves_per_span cooperating ones) walks one span in chunks of 256 entries,
+// loading the next chunk before it works on the current one so that memory requests stay in
+// flight during the arithmetic.  Control flow is uniform across the wavefront: lanes past the
+// end of the span carry zeros through the arithmetic and the buffer range check voids their
+// stores, so the cross-lane steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly)
+// always see all 64 lanes.
+template <int M, bool BF16, bool REFRESH, bool SCALED>
+__global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
+{
+    __shared__ float partial[kMaxBlockWaves];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
     const int P = a.waves_per_span;
-    const int64_t span = (int64_t)blockIdx.x * (kBlockWaves / P) + wave / P;
+    const int block_waves = blockDim.x / kWave;
+    const int64_t span = (int64_t)blockIdx.x * (block_waves / P) + wave / P;
     const int sub = wave % P;
-    const bool live = span < a.num_spans;
-    const int64_t begin = span * a.span_len;
-    int64_t len = 0;
-    if (live) len = (a.total - begin < a.span_len) ? a.total - begin : a.span_len;
+    const bool live_span = span < a.num_spans;
+    const int64_t begin = live_span ? span * a.span_len : 0;
+    int len = 0;
+    if (live_span) len = (int)((a.total - begin < a.span_len) ? a.total - begin : a.span_len);
+
+    SpanBuffers b;
+    b.w = span_resource(a.w + begin, len * 4);
+    b.m = span_resource(a.m + begin, len * 4);
+    b.v = span_resource(a.v + begin, len * 4);
+    if constexpr (BF16) b.g = span_resource(static_cast<const uint16_t *>(a.grad) + begin, len * 2);
+    else b.g = span_resource(static_cast<const float *>(a.grad) + begin, len * 4);
+    b.mask = span_resource(a.mask + (begin >> 5), len / 8);    // spans start and end on mask words
+
     float A = 1.0f;
-    if constexpr (SCALED) { if (live) A = a.scale[span]; }
+    if constexpr (SCALED) { if (live_span) A = a.scale[span]; }
     const bool want_gA = SCALED && a.scale_grad != nullptr;
     float acc = 0.0f;
 
-    // U = chunks in flight per wavefront
-    const int64_t stride = (int64_t)P * kChunk;
-    for (int64_t base = (int64_t)sub * kChunk; base < len; base += stride * U) {
-        Chunk c[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            chunk_load<BF16, REFRESH>(c[u], a, begin, base + u * stride + lane * kLaneElems, len);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if constexpr (REFRESH) {
-                c[u].nib = keep_nibble<M>(c[u].w, a.s.n_keep, lane);   // from the incoming weights
-                const uint32_t word = or_reduce_8lanes(c[u].nib << ((lane & 7) * 4));
-                if (c[u].act && (lane & 7) == 0) __builtin_nontemporal_store(word, a.mask + (c[u].idx >> 5));
-            }
+    const int stride = P * kChunk;
+    int off = sub * kChunk + lane * kLaneElems;      // this lane's first entry, relative to the span
+    Chunk<BF16> cur, nxt;
+    chunk_load<BF16, REFRESH>(cur, b, off);
+    for (int base = sub * kChunk; base < len; base += stride) {
+        chunk_load<BF16, REFRESH>(nxt, b, off + stride);        // past the end: all zeros, never used
+
+        float w[4], g[4], mu[4], v[4];
+        unpack4(cur.w, w);
+        unpack4(cur.m, mu);
+        unpack4(cur.v, v);
+        if constexpr (BF16) {
+            g[0] = bf16_lo(cur.g.x); g[1] = bf16_hi(cur.g.x); g[2] = bf16_lo(cur.g.y); g[3] = bf16_hi(cur.g.y);
+        } else {
+            unpack4(cur.g, g);
+        }
+        uint32_t nib;
+        if constexpr (REFRESH) {
+            nib = keep_nibble<M>(w, a.s.n_keep, lane);                   // from the incoming weights
+            const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
+            if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, b.mask, (off >> 5) * 4, 0, kAuxStore);
+        } else {
+            nib = (cur.word >> (off & 31)) & 0xFu;
+        }
+        if constexpr (SCALED) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float g = c[u].g[j];
-                if constexpr (SCALED) {
-                    if (want_gA) acc = __builtin_fmaf(g, c[u].w[j], acc);   // dL/dA term, incoming w
-                    g = A * g;                                // chain rule of Eq. 12
-                }
-                adams_entry(c[u].w[j], g, c[u].m[j], c[u].v[j], (c[u].nib >> j) & 1u, a.s);
+                if (want_gA) acc = __builtin_fmaf(g[j], w[j], acc);     // dL/dA term, incoming w
+                g[j] = A * g[j];                                         // chain rule of Eq. 12
             }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (c[u].act) {
-                store4_stream(a.w, c[u].idx, c[u].w);
-                store4_stream(a.m, c[u].idx, c[u].m);
-                store4_stream(a.v, c[u].idx, c[u].v);
-            }
+        adams_entries4(w, g, mu, v, nib, off < len, a.s);
+        __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
+        __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
+        __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
+
+        cur = nxt;
+        off += stride;
     }
 
     if constexpr (SCALED) {
         if (want_gA) {   // uniform over the workgroup
             const float wave_total = wave_sum_fixed_order(acc);
             if (P == 1) {
-                if (lane == 0 && live) a.scale_grad[span] = wave_total;
+                if (lane == 0 && live_span) a.scale_grad[span] = wave_total;
             } else {
                 if (lane == 0) partial[wave] = wave_total;
                 __syncthreads();
-                if (lane == 0 && sub == 0 && live) {
+                if (lane == 0 && sub == 0 && live_span) {
                     float t = partial[wave];
                     for (int p = 1; p < P; ++p) t = t + partial[wave + p];
                     a.scale_grad[span] = t;
@@ -134,26 +161,32 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_vec(const SpanArgs a
     }
 }
 
+template <bool BF16>
+__device__ __forceinline__ void load_grad4(const void *grad, int64_t idx, float (&g)[4])
+{
+    if constexpr (BF16) load4_bf16_stream(static_cast<const uint16_t *>(grad), idx, g);
+    else load4_stream(static_cast<const float *>(grad), idx, g);
+}
+
 // dL/dA alone, with exactly the traversal and summation order of adams_step_vec.
 template <bool BF16>
-__global__ __launch_bounds__(kBlockThreads) void scale_grad_vec(const float *w, const void *grad,
-                                                                float *scale_grad, int64_t total,
-                                                                int64_t span_len, int64_t num_spans,
-                                                                int waves_per_span)
+__global__ __launch_bounds__(kMaxBlockThreads) void scale_grad_vec(const float *w, const void *grad,
+                                                                   float *scale_grad, int64_t total,
+                                                                   int64_t span_len, int64_t num_spans,
+                                                                   int waves_per_span)
 {
-    __shared__ float partial[kBlockWaves];
+    __shared__ float partial[kMaxBlockWaves];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x / kWave;
     const int P = waves_per_span;
-    const int64_t span = (int64_t)blockIdx.x * (kBlockWaves / P) + wave / P;
+    const int block_waves = blockDim.x / kWave;
+    const int64_t span = (int64_t)blockIdx.x * (block_waves / P) + wave / P;
     const int sub = wave % P;
     const bool live = span < num_spans;
     const int64_t begin = span * span_len;
     int64_t len = 0;
     if (live) len = (total - begin < span_len) ? total - begin : span_len;
     float acc = 0.0f;
-    // the step kernel takes its chunks two at a time (base, base + stride) and adds them in
-    // that order, which is plain increasing order of chunks
     for (int64_t base = (int64_t)sub * kChunk; base < len; base += (int64_t)P * kChunk) {
         const int64_t off = base + lane * kLaneElems;
         float wv[4] = {0, 0, 0, 0}, g[4] = {0, 0, 0, 0};
@@ -269,33 +302,37 @@ static int env_int(const char *name, int fallback)
 
 SpanPlan plan_spans(int64_t rows, int64_t cols, int n_segments)
 {
+    // HBM rewards a narrow window of addresses in flight: wavefronts are kept short-lived (about
+    // two chunks of 256 entries each) and the spans of one workgroup are contiguous, so that the
+    // workgroups the dispatcher has resident at any time cover a compact range of every array.
     // Tuning knobs (read once): CAST_SPAN_LEN forces the flat span length, CAST_WAVES_PER_SPAN
-    // the number of cooperating wavefronts.
+    // the number of cooperating wavefronts, CAST_BLOCK_WAVES the workgroup size in wavefronts.
     static const int forced_len = env_int("CAST_SPAN_LEN", 0);
     static const int forced_p = env_int("CAST_WAVES_PER_SPAN", 0);
-    constexpr int64_t kWantWaves = 16384;   // 2 rounds of 8 waves/SIMD over 256 CUs * 4 SIMDs
+    static const int forced_bw = env_int("CAST_BLOCK_WAVES", 0);
     SpanPlan p{};
     p.total = rows * cols;
     p.waves_per_span = 1;
+    int block_waves = kBlockWaves;
     if (n_segments > 0) {
         p.span_len = cols / n_segments;
         p.num_spans = rows * n_segments;
-        p.vec = p.span_len % 32 == 0;
-        // long segments and few of them: let 2 or 4 wavefronts share one
-        while (p.waves_per_span < 4 && p.num_spans * p.waves_per_span < kWantWaves &&
-               p.span_len >= (int64_t)kChunk * 4 * p.waves_per_span)
-            p.waves_per_span *= 2;
+        p.vec = p.span_len % 32 == 0 && p.span_len < ((int64_t)1 << 28);   // 32-bit byte offsets inside a span
+        const int64_t chunks = (p.span_len + kChunk - 1) / kChunk;
+        while (p.waves_per_span < kMaxBlockWaves && chunks > p.waves_per_span) p.waves_per_span *= 2;
+        if (p.waves_per_span > block_waves) block_waves = p.waves_per_span;
     } else {
         p.vec = cols % 32 == 0;
-        int64_t len = (p.total / kWantWaves + kChunk - 1) / kChunk * kChunk;
-        if (len < kChunk) len = kChunk;
-        if (len > 8 * kChunk) len = 8 * kChunk;
+        int64_t len = 2 * kChunk;
         if (forced_len >= kChunk && forced_len % kChunk == 0) len = forced_len;
         p.span_len = len;
         p.num_spans = (p.total + len - 1) / len;
     }
-    if (forced_p == 1 || forced_p == 2 || forced_p == 4) p.waves_per_span = forced_p;
-    const int64_t spans_per_block = kBlockWaves / p.waves_per_span;
+    if (forced_p == 1 || forced_p == 2 || forced_p == 4 || forced_p == 8 || forced_p == 16) p.waves_per_span = forced_p;
+    if (forced_bw == 4 || forced_bw == 8 || forced_bw == 16) block_waves = forced_bw;
+    if (block_waves < p.waves_per_span) block_waves = p.waves_per_span;
+    p.block_threads = block_waves * kWave;
+    const int64_t spans_per_block = block_waves / p.waves_per_span;
     p.grid = (unsigned)((p.num_spans + spans_per_block - 1) / spans_per_block);
     return p;
 }
@@ -321,8 +358,8 @@ static StepScalars make_scalars(const cast_adams_config *cfg)
 template <int M, bool BF16, bool REFRESH>
 static void launch_vec_scaled(bool scaled, const SpanPlan &p, const SpanArgs &a, hipStream_t st)
 {
-    if (scaled) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true>), dim3(p.grid), dim3(kBlockThreads), 0, st, a);
-    else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, false>), dim3(p.grid), dim3(kBlockThreads), 0, st, a);
+    if (scaled) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true>), dim3(p.grid), dim3(p.block_threads), 0, st, a);
+    else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, false>), dim3(p.grid), dim3(p.block_threads), 0, st, a);
 }
 
 template <int M, bool BF16>
@@ -353,8 +390,8 @@ cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, 
     const SpanPlan p = plan_spans(rows, cols, n_segments);
     const bool bf16 = grad_dtype == CAST_BF16;
     if (p.vec) {
-        if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, dim3(p.grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
-        else hipLaunchKernelGGL(scale_grad_vec<false>, dim3(p.grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
+        if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
+        else hipLaunchKernelGGL(scale_grad_vec<false>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
     } else {
         const unsigned grid = (unsigned)((p.num_spans + kBlockWaves - 1) / kBlockWaves);
         if (bf16) hipLaunchKernelGGL(scale_grad_rows<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.num_spans, p.span_len);

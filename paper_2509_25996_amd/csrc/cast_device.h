@@ -19,6 +19,8 @@ constexpr int kLaneElems = 4;                    // fp32 entries per lane per ch
 constexpr int kChunk = kWave * kLaneElems;       // 256 entries per wavefront per chunk
 constexpr int kBlockThreads = 256;
 constexpr int kBlockWaves = kBlockThreads / kWave;
+constexpr int kMaxBlockWaves = 16;               // the step kernels run with 4, 8 or 16 wavefronts per workgroup
+constexpr int kMaxBlockThreads = kMaxBlockWaves * kWave;
 
 // ---- cross-lane moves inside a row of 16 lanes (DPP: no LDS traffic) -------------------
 // quad_perm selectors: lane i of each quad reads lane perm[i] of the same quad.
@@ -124,23 +126,37 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x)
     return b >> 16;
 }
 
-// ---- streaming (non-temporal) 16- and 8-byte accesses -------------------------------------
+// ---- streaming accesses through buffer resources ------------------------------------------
 // Every byte of the optimizer state is touched once per step, so nothing is worth keeping in
-// the caches: the loads and stores carry the non-temporal hint.
+// the caches: loads and stores carry the non-temporal hint.  The vector kernels address each
+// span through a buffer resource (base pointer + byte length in scalar registers, 32-bit
+// offsets in vector registers): the hardware range check returns zeros for loads past the end
+// of the span and drops stores there, so ragged tails need no branches and no 64-bit address
+// arithmetic per lane.
 typedef float vf4_t __attribute__((ext_vector_type(4)));
-typedef float vf2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t vu4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t vu2_t __attribute__((ext_vector_type(2)));
+
+// cache-policy bits of buffer instructions: 2 = nt (streaming), 16 = sc1
+#ifndef CAST_AUX_LOAD
+#define CAST_AUX_LOAD 2
+#endif
+#ifndef CAST_AUX_STORE
+#define CAST_AUX_STORE 2
+#endif
+constexpr int kAuxLoad = CAST_AUX_LOAD;
+constexpr int kAuxStore = CAST_AUX_STORE;
+constexpr int kRsrcWord3 = 0x00020000;        // raw buffer, 32-bit data format (gfx9 family)
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t span_resource(const void *base, int bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, kRsrcWord3);
+}
 
 __device__ __forceinline__ void load4_stream(const float *p, int64_t idx, float (&x)[4])
 {
     const vf4_t t = __builtin_nontemporal_load(reinterpret_cast<const vf4_t *>(p + idx));
     x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-}
-
-__device__ __forceinline__ void store4_stream(float *p, int64_t idx, const float (&x)[4])
-{
-    const vf4_t t = {x[0], x[1], x[2], x[3]};
-    __builtin_nontemporal_store(t, reinterpret_cast<vf4_t *>(p + idx));
 }
 
 __device__ __forceinline__ void load4_bf16_stream(const uint16_t *p, int64_t idx, float (&g)[4])
@@ -155,8 +171,8 @@ __device__ __forceinline__ void load4_bf16_stream(const uint16_t *p, int64_t idx
 // theorem: a faithful quotient corrected once with the correctly rounded reciprocal is the
 // correctly rounded quotient) as long as nothing under- or overflows on the way.  That is
 // guaranteed by range checks: the host enables the short path only for 2^-12 <= y <= 2, and
-// an entry takes it only if 2^-63 <= |x| < 2^65; zeros, denormals, huge values, inf and NaN take
-// the full IEEE division.  The FMAs here are the division algorithm, not a contraction of
+// an entry may take it only if 2^-63 <= |x| < 2^66; zeros, denormals, huge values, inf and NaN
+// take the full IEEE division.  The FMAs here are the division algorithm, not a contraction of
 // the update's own multiply-adds.
 struct UniformDivisor {
     float y;      // the divisor
@@ -173,26 +189,29 @@ inline UniformDivisor make_divisor(float y)
     return d;
 }
 
-__host__ __device__ __forceinline__ float div_by_uniform(float x, const UniformDivisor &d)
+__host__ __device__ __forceinline__ bool in_short_division_range(float x)
 {
-#if defined(__HIP_DEVICE_COMPILE__)
-    const uint32_t bits = __float_as_uint(x);
-#else
     uint32_t bits;
     __builtin_memcpy(&bits, &x, 4);
-#endif
-    const uint32_t e = (bits >> 23) & 0xffu;
-    if (d.fast && (e - 64u) < 129u) {                      // biased exponent in [64, 192]
-        const float q0 = x * d.r;
-        const float e0 = __builtin_fmaf(-d.y, q0, x);
-        const float q1 = __builtin_fmaf(e0, d.r, q0);      // faithful
-        const float e1 = __builtin_fmaf(-d.y, q1, x);      // exact residual
-        return __builtin_fmaf(e1, d.r, q1);                // correctly rounded
-    }
+    return (((bits >> 23) & 0xffu) - 64u) < 129u;      // biased exponent in [64, 192]
+}
+
+__host__ __device__ __forceinline__ float div_short(float x, const UniformDivisor &d)
+{
+    const float q0 = x * d.r;
+    const float e0 = __builtin_fmaf(-d.y, q0, x);
+    const float q1 = __builtin_fmaf(e0, d.r, q0);      // faithful
+    const float e1 = __builtin_fmaf(-d.y, q1, x);      // exact residual
+    return __builtin_fmaf(e1, d.r, q1);                // correctly rounded
+}
+
+__host__ __device__ __forceinline__ float div_by_uniform(float x, const UniformDivisor &d)
+{
+    if (d.fast && in_short_division_range(x)) return div_short(x, d);
     return x / d.y;
 }
 
-// ---- Algorithm 1, one entry -------------------------------------------------------------
+// ---- Algorithm 1 --------------------------------------------------------------------------
 // Scalars of one iteration, prepared on the host in fp32 (one rounding each).
 struct StepScalars {
     float lr, beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
@@ -202,11 +221,13 @@ struct StepScalars {
     int v_from_grad;
 };
 
-// Every line is one correctly rounded fp32 operation: the library is compiled with
+// Every line below is one correctly rounded fp32 operation: the library is compiled with
 // -ffp-contract=off (no fused multiply-add) and -fhip-fp32-correctly-rounded-divide-sqrt, and
 // fp32 denormals are not flushed on gfx9, so the result is the same on any IEEE-754 machine.
-__device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float &v, bool keep,
-                                            const StepScalars &s)
+
+// First half of the body of Algorithm 1's loop: the moments.
+__device__ __forceinline__ void adams_moments(float w, float g, float &mu, float v, bool keep,
+                                              const StepScalars &s, float &mu_tilde, float &v_t)
 {
     const float t0 = s.beta1 * mu;
     const float t1 = s.one_minus_beta1 * g;
@@ -215,19 +236,62 @@ __device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float 
     const float d0 = s.one_minus_alpha * mu_t;
     const float d1 = s.alpha_lambda * sgn;
     const float decayed = d0 + d1;                                // Eq. 7 on the momentum
-    const float mu_tilde = keep ? mu_t : decayed;                 // Algorithm 1: only where m = 0
+    mu_tilde = keep ? mu_t : decayed;                             // Algorithm 1: only where m = 0
     const float second = s.v_from_grad ? g * g : mu_tilde * mu_tilde;
     const float s0 = s.beta2 * v;
     const float s1 = s.one_minus_beta2 * second;
-    const float v_t = s0 + s1;                                    // v from the decayed momentum
-    const float mu_hat = div_by_uniform(mu_tilde, s.bias_corr1);  // = RN(mu~ / bias_corr1)
-    const float v_hat = div_by_uniform(v_t, s.bias_corr2);
-    const float denom = __builtin_sqrtf(v_hat) + s.eps;            // IEEE square root
-    const float q = mu_hat / denom;                                // IEEE division (see the build flags)
-    const float step = s.lr * q;
-    w = w - step;
+    v_t = s0 + s1;                                                // v from the decayed momentum
     mu = mu_t;                                                    // the undecayed moment is stored
+}
+
+// Second half: bias-corrected moments (already divided) to the new weight.
+__device__ __forceinline__ float adams_update(float w, float mu_hat, float v_hat, const StepScalars &s)
+{
+    const float denom = __builtin_sqrtf(v_hat) + s.eps;           // IEEE square root
+    const float q = mu_hat / denom;                               // IEEE division
+    const float step = s.lr * q;
+    return w - step;
+}
+
+// One entry, start to end (scalar kernels).
+__device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float &v, bool keep,
+                                            const StepScalars &s)
+{
+    float mu_tilde, v_t;
+    adams_moments(w, g, mu, v, keep, s, mu_tilde, v_t);
+    w = adams_update(w, div_by_uniform(mu_tilde, s.bias_corr1), div_by_uniform(v_t, s.bias_corr2), s);
     v = v_t;
+}
+
+// The 4 entries of a lane.  The choice between the short and the IEEE form of the two
+// bias-correction divisions is taken once per wavefront (a scalar branch): the short form if
+// every live lane's 8 dividends are in its range.  `live` is false for lanes past the end of
+// the span, whose zeros must not force the long form.
+__device__ __forceinline__ void adams_entries4(float (&w)[4], const float (&g)[4], float (&mu)[4],
+                                               float (&v)[4], uint32_t nib, bool live,
+                                               const StepScalars &s)
+{
+    float mt[4], vt[4];
+    bool out_of_range = false;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        adams_moments(w[j], g[j], mu[j], v[j], (nib >> j) & 1u, s, mt[j], vt[j]);
+        out_of_range = out_of_range || !in_short_division_range(mt[j]) || !in_short_division_range(vt[j]);
+    }
+    float mh[4], vh[4];
+    const bool short_ok = s.bias_corr1.fast && s.bias_corr2.fast;
+    if (short_ok && !__any(out_of_range && live)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { mh[j] = div_short(mt[j], s.bias_corr1); vh[j] = div_short(vt[j], s.bias_corr2); }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { mh[j] = mt[j] / s.bias_corr1.y; vh[j] = vt[j] / s.bias_corr2.y; }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        w[j] = adams_update(w[j], mh[j], vh[j], s);
+        v[j] = vt[j];
+    }
 }
 
 }  // namespace cast

@@ -17,8 +17,9 @@ struct SpanPlan {
     int64_t total;       // rows * cols
     int64_t span_len;    // entries per span (the last span of a flat plan may be shorter)
     int64_t num_spans;
-    int waves_per_span;  // 1, 2 or 4
-    unsigned grid;       // workgroups of 256 threads
+    int waves_per_span;  // 1, 2, 4, 8 or 16
+    int block_threads;   // 256, 512 or 1024
+    unsigned grid;       // workgroups
 };
 
 SpanPlan plan_spans(int64_t rows, int64_t cols, int n_segments);

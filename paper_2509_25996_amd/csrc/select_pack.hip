@@ -62,7 +62,9 @@ cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int n_k
                              uint32_t *mask_bits, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_spans(rows, cols, 0);
+    SpanPlan p = plan_spans(rows, cols, 0);
+    p.span_len = 2 * kChunk;
+    p.num_spans = (p.total + p.span_len - 1) / p.span_len;
     if (p.vec) {
         const unsigned grid = (unsigned)((p.num_spans + kBlockWaves - 1) / kBlockWaves);
         switch (m_group) {
@@ -254,7 +256,9 @@ cast_status launch_project_compress(const float *w, const float *scale, int n_se
     const bool bf16 = value_dtype == CAST_BF16;
     const int64_t seg_len = scale ? cols / n_segments : cols;
     if (n_keep == 2 && m_group == 4 && cols % 32 == 0 && seg_len % 4 == 0) {
-        const SpanPlan p = plan_spans(rows, cols, 0);
+        SpanPlan p = plan_spans(rows, cols, 0);
+        p.span_len = 2 * kChunk;
+        p.num_spans = (p.total + p.span_len - 1) / p.span_len;
         const unsigned grid = (unsigned)((p.num_spans + kBlockWaves - 1) / kBlockWaves);
         if (bf16) hipLaunchKernelGGL(project_compress_2of4_vec<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask_bits, values, meta, p.total, p.span_len, seg_len);
         else hipLaunchKernelGGL(project_compress_2of4_vec<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask_bits, values, meta, p.total, p.span_len, seg_len);
