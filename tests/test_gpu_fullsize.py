@@ -1,0 +1,76 @@
+"""Parity at the full sizes of the benchmark workloads, in the launch configuration the
+benchmark times (2:4, bf16 gradients, weight scaling with n = 2, one launch per matrix).
+
+The AdamS step is checked on sampled whole rows (a row is self-contained: groups and scale
+segments never cross rows), gathered before and after the GPU step and recomputed by the oracle.
+Selection and hard projection + pack of the tie/outlier stress input are compared in full."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_25996_amd import binding as B
+from paper_2509_25996_amd import synth
+
+from gpu_util import DEV, assert_same_bits, host, oracle_cfg, words
+
+pytestmark = pytest.mark.gpu
+
+SHAPES_7B = [(4096, 4096), (11008, 4096), (4096, 11008)]
+SHAPES_13B = [(5120, 5120), (13824, 5120), (5120, 13824)]
+
+
+@pytest.mark.parametrize("rows,cols", SHAPES_7B + SHAPES_13B)
+def test_step_on_sampled_rows_of_full_size_matrices(rows, cols):
+    n, steps, n_sample = 2, 3, 24
+    w = synth.device_gaussian((rows, cols), 0.02, torch.float32, 11, DEV)
+    g = synth.device_gaussian((rows, cols), 1e-3, torch.bfloat16, 12, DEV)
+    m, v = torch.zeros_like(w), torch.zeros_like(w)
+    mask = B.alloc_mask(rows, cols, DEV)
+    A = (1 + 0.05 * torch.randn((rows, n), device=DEV, generator=torch.Generator(DEV).manual_seed(3))).contiguous()
+    gA = torch.zeros((rows, n), device=DEV)
+    rng = np.random.default_rng(rows + cols)
+    pick = np.unique(np.concatenate([[0, rows - 1], rng.integers(0, rows, n_sample)]))
+    idx = torch.from_numpy(pick).to(DEV)
+    ow, og, oA = host(w[idx]).copy(), host(g[idx].float()).copy(), host(A[idx]).copy()
+    om, ov = np.zeros_like(ow), np.zeros_like(ow)
+    keep = np.zeros(ow.shape, np.uint8)
+    for t in range(steps):
+        cfg = B.iteration_config(t, 7500, mask_period=2, lr=2e-5, lambda_=4e-7, scale_segments=n)
+        cfg.alpha = 0.25 + 0.25 * t      # exercise the decay as late in training
+        B.cast_adams_step(w, g, m, v, mask, cfg, scale=A, scale_grad=gA)
+        ref_gA = oracle.adams_step(ow, og, om, ov, keep, oracle_cfg(cfg), A=oA, arithmetic="f32", nthreads=8)
+    torch.cuda.synchronize()
+    assert (words(mask[idx]) == oracle.pack_mask_bits(keep)).all()
+    assert_same_bits(host(w[idx]), ow, "w")
+    assert_same_bits(host(m[idx]), om, "mu")
+    assert_same_bits(host(v[idx]), ov, "v")
+    terms = np.abs(og.astype(np.float64) * host(w[idx])).reshape(len(pick), n, -1).sum(-1)
+    assert (np.abs(host(gA[idx]) - ref_gA) <= 2e-5 * terms + 1e-12).all()
+    # properties that hold for the whole matrix: exactly 2 bits per group in every mask word, state finite
+    bits = mask.view(torch.uint8)
+    lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.uint8, device=DEV)
+    nib_ok = torch.tensor([(bin(i & 15).count("1") == 2 and bin(i >> 4).count("1") == 2) for i in range(256)], device=DEV)
+    assert bool(nib_ok[bits.long()].all())
+    assert int(lut[bits.long()].sum(dtype=torch.int64)) == rows * cols // 2
+    assert bool(torch.isfinite(w).all()) and bool(torch.isfinite(v).all()) and bool((v >= 0).all())
+
+
+@pytest.mark.parametrize("rows,cols", SHAPES_7B)
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8)])
+def test_tie_outlier_select_project_pack_full_size(rows, cols, n, m):
+    w = synth.tie_outlier_weights(5, rows % 7, rows, cols)
+    wd = torch.from_numpy(w).to(DEV)
+    mask = B.alloc_mask(rows, cols, DEV)
+    B.cast_nm_select(wd, n, m, mask)
+    keep = oracle.nm_select(w, n, m)
+    assert (words(mask) == oracle.pack_mask_bits(keep)).all()
+    assert (keep.reshape(rows, -1, m).sum(-1) == n).all()
+    _, vbytes, mbytes = B.cast_sizes(rows, cols, n, m, B.CAST_F32)
+    values = torch.empty((rows, cols // m * n), device=DEV)
+    meta = torch.empty((rows, mbytes // 4 // rows), dtype=torch.int32, device=DEV)
+    B.cast_nm_project_compress(wd, n, m, values, meta)
+    torch.cuda.synchronize()
+    ref_v, ref_m = oracle.project_compress(w, n, m)
+    assert (words(meta) == ref_m).all()
+    assert_same_bits(host(values), ref_v, "values")
