@@ -39,14 +39,20 @@ def log(*a):
 class Model:
     """Every linear weight of the workload with its optimizer state, in device memory."""
 
-    def __init__(self, workload: str, layers, torch, B, synth, dev):
+    def __init__(self, workload: str, layers, torch, B, synth, dev, interleaved: bool):
         self.shapes = synth.weight_set(workload, layers)
         self.params = synth.set_params(self.shapes)
         self.t = []
         for i, (_, r, c) in enumerate(self.shapes):
             w = synth.device_gaussian((r, c), 0.02, torch.float32, 1000 + i, dev)
             g = synth.device_gaussian((r, c), 1e-3, torch.bfloat16, 500000 + i, dev)
-            self.t.append(dict(w=w, g=g, m=torch.zeros_like(w), v=torch.zeros_like(w),
+            if interleaved:
+                # w, mu, v of a matrix row-interleaved in one allocation ([rows][3][cols], row stride 3*cols):
+                # the three streams stay within tens of KiB of each other in HBM
+                w, m, v = B.interleaved_state(w)
+            else:
+                m, v = torch.zeros_like(w), torch.zeros_like(w)
+            self.t.append(dict(w=w, g=g, m=m, v=v,
                                mask=B.alloc_mask(r, c, dev),
                                A=torch.ones((r, SEGMENTS), device=dev),
                                gA=torch.zeros((r, SEGMENTS), device=dev)))
@@ -104,6 +110,8 @@ def main():
     ap.add_argument("--workload", default="llama2_7b", choices=["opt125m", "llama2_7b", "llama2_13b"])
     ap.add_argument("--layers", type=int, default=None, help="use only the first LAYERS decoder blocks (debugging)")
     ap.add_argument("--no-scale", action="store_true", help="time the step without weight scaling")
+    ap.add_argument("--layout", default="interleaved", choices=["interleaved", "separate"],
+                    help="w, mu, v of each matrix row-interleaved in one buffer (default) or three dense arrays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     args = ap.parse_args()
@@ -121,7 +129,7 @@ def main():
     scaled = not args.no_scale
 
     t0 = time.time()
-    model = Model(args.workload, args.layers, torch, B, synth, dev)
+    model = Model(args.workload, args.layers, torch, B, synth, dev, args.layout == "interleaved")
     torch.cuda.synchronize()
     log(f"[bench] {args.workload}: {len(model.shapes)} matrices, {model.params} params resident "
         f"({torch.cuda.memory_allocated() / 2**30:.1f} GiB) after {time.time() - t0:.1f} s")
@@ -198,7 +206,7 @@ def main():
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{args.workload} linear weight set ({len(model.shapes)} matrices, {model.params} params), "
-                                  f"2:4, fp32 w/mu/v + bf16 grads + mask bits resident, "
+                                  f"2:4, fp32 w/mu/v ({args.layout}) + bf16 grads + mask bits resident, "
                                   f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step",
                       "n_keep": 2, "m_group": 4, "scale_segments": SEGMENTS if scaled else 0,
                       "pct_of_peak_hbm": round(100 * BYTES_PER_PARAM * value / HBM_PEAK_GBS, 2)},

@@ -9,13 +9,19 @@
  * HIP stream passed as `stream` (a hipStream_t cast to void*; NULL = the default stream) and
  * returns without waiting.  Validation failures return a negative status and enqueue nothing.
  *
- * Tensors are dense, row-major [rows, cols] with leading dimension cols; rows = out_features,
- * cols = in_features of a linear layer.  Groups of M consecutive entries run along a row
- * (Sec. 3, Eq. 3).  Empty tensors (rows == 0 or cols == 0) are accepted and do nothing.
+ * Tensors are row-major [rows, cols]; rows = out_features, cols = in_features of a linear
+ * layer.  Groups of M consecutive entries run along a row (Sec. 3, Eq. 3).  The weights w and
+ * the two moments m, v share one row stride `ld` (in entries, ld >= cols; ld == cols for dense
+ * arrays): a caller may interleave the three arrays row by row in one allocation ([rows][3][cols],
+ * ld = 3*cols), which keeps their streams close together in HBM and is measurably faster.
+ * Every other buffer (gradient, mask bits, scale, packed outputs) is dense.  Empty tensors
+ * (rows == 0 or cols == 0) are accepted and do nothing.
  *
  * Shapes accepted: M in {2, 4, 8}, 1 <= N < M, cols % M == 0.  With weight scaling in n
  * segments: cols % n == 0 and (cols / n) % M == 0, so that no group lies in two segments.
  * All fp32 buffers must be 16-byte aligned, bf16 buffers 8-byte aligned, word buffers 4-byte.
+ * The fast kernels need rows (and scale segments) that are multiples of 32 entries and ld % 4 == 0;
+ * any other accepted shape runs on slower scalar kernels with identical results.
  *
  * Mask storage (one bit per parameter; Remark at the end of Sec. 4.1): uint32 words, each row
  * padded to whole words; M[r, c] is bit (c % 32) of word [r * ceil(cols/32) + c / 32].
@@ -79,17 +85,17 @@ cast_status cast_sizes(int64_t rows, int64_t cols, int n_keep, int m_group, int 
 
 /*
  * Magnitude mask, Eq. 6 (Sec. 4.1) under the N-per-group constraint of Eq. 4.
- *   w          DEVICE in   fp32 [rows, cols]
+ *   w          DEVICE in   fp32 [rows, cols], row stride ld
  *   mask_bits  DEVICE out  uint32 [rows, ceil(cols/32)]
  */
-cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int n_keep, int m_group,
-                           uint32_t *mask_bits, void *stream);
+cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
+                           int m_group, uint32_t *mask_bits, void *stream);
 
 /*
  * One AdamS iteration over one weight matrix: the body of Algorithm 1's loop (Eq. 8), with
  * the proportional decay of Eq. 7 on the entries whose mask bit is 0.
  *
- *   w, m, v     DEVICE in/out  fp32 [rows, cols]: theta, first moment mu, second moment v.
+ *   w, m, v     DEVICE in/out  fp32 [rows, cols], row stride ld: theta, first moment mu, second moment v.
  *   grad        DEVICE in      [rows, cols] of cfg->grad_dtype.  With scale == NULL it is dL/dW;
  *                              with scale != NULL it is dL/dW_scale and the chain rule of Eq. 12
  *                              (dL/dW = A[r, s] * grad) is applied inside.
@@ -106,17 +112,17 @@ cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int n_kee
  */
 cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                             const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                            const cast_adams_config *cfg /* HOST */, void *stream);
+                            int64_t ld, const cast_adams_config *cfg /* HOST */, void *stream);
 
 /*
  * Weight scaling forward / fold, Eq. 12 (Eq. 11 when n_segments == 1):
  *   out[r, c] = scale[r, c / (cols / n_segments)] * w[r, c]      (one fp32 multiply)
- *   w DEVICE in fp32 [rows, cols]; scale DEVICE in fp32 [rows, n_segments];
- *   out DEVICE out [rows, cols] of out_dtype (bf16 = round to nearest even of the fp32 product);
- *   out may be w itself when out_dtype is CAST_F32.
+ *   w DEVICE in fp32 [rows, cols], row stride ld; scale DEVICE in fp32 [rows, n_segments];
+ *   out DEVICE out dense [rows, cols] of out_dtype (bf16 = round to nearest even of the fp32 product);
+ *   out may be w itself when out_dtype is CAST_F32 and ld == cols.
  */
 cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
-                              int n_segments, void *out, int out_dtype, void *stream);
+                              int64_t ld, int n_segments, void *out, int out_dtype, void *stream);
 
 /*
  * Gradient of the scale alone, for callers that do not take it from cast_adams_step:
@@ -124,7 +130,7 @@ cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, 
  * (the derivative of Eq. 12 with respect to A).  Same summation order as cast_adams_step.
  */
 cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int grad_dtype,
-                                   int64_t rows, int64_t cols, int n_segments,
+                                   int64_t rows, int64_t cols, int64_t ld, int n_segments,
                                    float *scale_grad, void *stream);
 
 /*
@@ -146,8 +152,8 @@ cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int 
  */
 cast_status cast_nm_project_compress(const float *w, const float *scale, int n_segments,
                                      const uint32_t *mask_bits, int64_t rows, int64_t cols,
-                                     int n_keep, int m_group, void *values, int value_dtype,
-                                     uint32_t *meta, void *stream);
+                                     int64_t ld, int n_keep, int m_group, void *values,
+                                     int value_dtype, uint32_t *meta, void *stream);
 
 /*
  * Mask-learning statistics of one matrix (appendix "Mask Learning"): the numerators of the
@@ -160,8 +166,8 @@ cast_status cast_nm_project_compress(const float *w, const float *scale, int n_s
  * The double additions are atomic and their order is not fixed: l1 is reproducible only to rounding.
  */
 cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
-                            int64_t rows, int64_t cols, unsigned long long *flips, double *l1,
-                            void *stream);
+                            int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
+                            double *l1, void *stream);
 
 /*
  * Measurement aid, not part of the method: a plain device-to-device copy kernel of `bytes`

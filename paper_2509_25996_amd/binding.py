@@ -74,12 +74,12 @@ def load():
     L.cast_status_str.argtypes = [C.c_int32]
     L.cast_status_str.restype = C.c_char_p
     L.cast_sizes.argtypes = [i64, i64, ci, ci, ci, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
-    L.cast_nm_select.argtypes = [vp, i64, i64, ci, ci, vp, vp]
-    L.cast_adams_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, C.POINTER(_Config), vp]
-    L.cast_weight_scale.argtypes = [vp, vp, i64, i64, ci, vp, ci, vp]
-    L.cast_weight_scale_grad.argtypes = [vp, vp, ci, i64, i64, ci, vp, vp]
-    L.cast_nm_project_compress.argtypes = [vp, vp, ci, vp, i64, i64, ci, ci, vp, ci, vp, vp]
-    L.cast_mask_stats.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp]
+    L.cast_nm_select.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp]
+    L.cast_adams_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, C.POINTER(_Config), vp]
+    L.cast_weight_scale.argtypes = [vp, vp, i64, i64, i64, ci, vp, ci, vp]
+    L.cast_weight_scale_grad.argtypes = [vp, vp, ci, i64, i64, i64, ci, vp, vp]
+    L.cast_nm_project_compress.argtypes = [vp, vp, ci, vp, i64, i64, i64, ci, ci, vp, ci, vp, vp]
+    L.cast_mask_stats.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp]
     L.cast_hbm_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
     L.cast_debug_div_by_uniform.argtypes = [vp, C.c_float, vp, i64]
     for name in EXPORTS:
@@ -121,6 +121,27 @@ def _dev(*tensors):
             raise ValueError("tensors must be contiguous and on the GPU")
 
 
+def _ld(w, *same):
+    """Row stride of a [rows, cols] weight/moment tensor whose rows are contiguous; dense tensors
+    give ld == cols, row-interleaved state (see interleaved_state) gives ld == 3 * cols."""
+    if not w.is_cuda or w.dim() != 2 or (w.shape[1] > 1 and w.stride(1) != 1):
+        raise ValueError("w, m, v must be 2-D GPU tensors with contiguous rows")
+    ld = w.stride(0) if w.shape[0] > 1 else max(w.stride(0), w.shape[1])
+    for t in same:
+        if t.shape != w.shape or (t.shape[0] > 1 and t.stride(0) != w.stride(0)) or (t.shape[1] > 1 and t.stride(1) != 1):
+            raise ValueError("w, m and v must share one shape and one row stride")
+    return max(ld, w.shape[1])
+
+
+def interleaved_state(w0: torch.Tensor):
+    """Allocate w, m, v of one matrix interleaved row by row in one buffer [rows, 3, cols] (row
+    stride 3*cols for each of the three views).  w is initialised from w0, m and v are zero."""
+    rows, cols = w0.shape
+    state = torch.zeros((rows, 3, cols), dtype=torch.float32, device=w0.device)
+    state[:, 0, :].copy_(w0)
+    return state[:, 0, :], state[:, 1, :], state[:, 2, :]
+
+
 def cast_sizes(rows: int, cols: int, n_keep: int, m_group: int, value_dtype: int = CAST_F32):
     a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
     _check(load().cast_sizes(rows, cols, n_keep, m_group, value_dtype, C.byref(a), C.byref(b), C.byref(c)), "cast_sizes")
@@ -133,48 +154,49 @@ def alloc_mask(rows: int, cols: int, device="cuda:0") -> torch.Tensor:
 
 
 def cast_nm_select(w: torch.Tensor, n_keep: int, m_group: int, mask_bits: torch.Tensor, stream=None):
-    _dev(w, mask_bits)
+    _dev(mask_bits)
     rows, cols = w.shape
-    _check(load().cast_nm_select(_ptr(w), rows, cols, n_keep, m_group, _ptr(mask_bits), _stream(stream)), "cast_nm_select")
+    _check(load().cast_nm_select(_ptr(w), rows, cols, _ld(w), n_keep, m_group, _ptr(mask_bits), _stream(stream)),
+           "cast_nm_select")
 
 
 def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scale_grad=None, stream=None):
-    _dev(w, grad, m, v, mask_bits, scale, scale_grad)
+    _dev(grad, mask_bits, scale, scale_grad)
     rows, cols = w.shape
     cfg.grad_dtype = _dtype_code(grad)
     cs = cfg.c_struct()
     _check(load().cast_adams_step(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
-                                  rows, cols, C.byref(cs), _stream(stream)), "cast_adams_step")
+                                  rows, cols, _ld(w, m, v), C.byref(cs), _stream(stream)), "cast_adams_step")
 
 
 def cast_weight_scale(w, scale, out, stream=None):
-    _dev(w, scale, out)
+    _dev(scale, out)
     rows, cols = w.shape
-    _check(load().cast_weight_scale(_ptr(w), _ptr(scale), rows, cols, scale.shape[1], _ptr(out), _dtype_code(out),
-                                    _stream(stream)), "cast_weight_scale")
+    _check(load().cast_weight_scale(_ptr(w), _ptr(scale), rows, cols, _ld(w), scale.shape[1], _ptr(out),
+                                    _dtype_code(out), _stream(stream)), "cast_weight_scale")
 
 
 def cast_weight_scale_grad(w, grad_scaled, n_segments: int, scale_grad, stream=None):
-    _dev(w, grad_scaled, scale_grad)
+    _dev(grad_scaled, scale_grad)
     rows, cols = w.shape
-    _check(load().cast_weight_scale_grad(_ptr(w), _ptr(grad_scaled), _dtype_code(grad_scaled), rows, cols, n_segments,
-                                         _ptr(scale_grad), _stream(stream)), "cast_weight_scale_grad")
+    _check(load().cast_weight_scale_grad(_ptr(w), _ptr(grad_scaled), _dtype_code(grad_scaled), rows, cols, _ld(w),
+                                         n_segments, _ptr(scale_grad), _stream(stream)), "cast_weight_scale_grad")
 
 
 def cast_nm_project_compress(w, n_keep: int, m_group: int, values, meta, scale=None, mask_bits=None, stream=None):
-    _dev(w, values, meta, scale, mask_bits)
+    _dev(values, meta, scale, mask_bits)
     rows, cols = w.shape
     n_seg = 0 if scale is None else scale.shape[1]
-    _check(load().cast_nm_project_compress(_ptr(w), _ptr(scale), n_seg, _ptr(mask_bits), rows, cols, n_keep, m_group,
+    _check(load().cast_nm_project_compress(_ptr(w), _ptr(scale), n_seg, _ptr(mask_bits), rows, cols, _ld(w), n_keep, m_group,
                                            _ptr(values), _dtype_code(values), _ptr(meta), _stream(stream)),
            "cast_nm_project_compress")
 
 
 def cast_mask_stats(w, mask_bits, other_bits, flips, l1, stream=None):
     """flips: int64 tensor [1]; l1: float64 tensor [2]; both accumulated into."""
-    _dev(w, mask_bits, other_bits, flips, l1)
+    _dev(mask_bits, other_bits, flips, l1)
     rows, cols = w.shape
-    _check(load().cast_mask_stats(_ptr(w), _ptr(mask_bits), _ptr(other_bits), rows, cols, _ptr(flips), _ptr(l1),
+    _check(load().cast_mask_stats(_ptr(w), _ptr(mask_bits), _ptr(other_bits), rows, cols, _ld(w), _ptr(flips), _ptr(l1),
                                   _stream(stream)), "cast_mask_stats")
 
 

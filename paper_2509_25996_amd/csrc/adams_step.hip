@@ -21,10 +21,7 @@ struct SpanArgs {
     uint32_t *mask;
     const float *scale;
     float *scale_grad;
-    int64_t total;
-    int64_t span_len;
-    int64_t num_spans;
-    int waves_per_span;
+    SpanGeom geom;
     StepScalars s;
 };
 
@@ -81,22 +78,21 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     __shared__ float partial[kMaxBlockWaves];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
-    const int P = a.waves_per_span;
+    const int P = a.geom.waves_per_span;
     const int block_waves = blockDim.x / kWave;
     const int64_t span = (int64_t)blockIdx.x * (block_waves / P) + wave / P;
     const int sub = wave % P;
-    const bool live_span = span < a.num_spans;
-    const int64_t begin = live_span ? span * a.span_len : 0;
-    int len = 0;
-    if (live_span) len = (int)((a.total - begin < a.span_len) ? a.total - begin : a.span_len);
+    const SpanOrigin o = span_origin(a.geom, span);
+    const bool live_span = o.len > 0;
+    const int len = o.len;
 
     SpanBuffers b;
-    b.w = span_resource(a.w + begin, len * 4);
-    b.m = span_resource(a.m + begin, len * 4);
-    b.v = span_resource(a.v + begin, len * 4);
-    if constexpr (BF16) b.g = span_resource(static_cast<const uint16_t *>(a.grad) + begin, len * 2);
-    else b.g = span_resource(static_cast<const float *>(a.grad) + begin, len * 4);
-    b.mask = span_resource(a.mask + (begin >> 5), len / 8);    // spans start and end on mask words
+    b.w = span_resource(a.w + o.state_begin, len * 4);
+    b.m = span_resource(a.m + o.state_begin, len * 4);
+    b.v = span_resource(a.v + o.state_begin, len * 4);
+    if constexpr (BF16) b.g = span_resource(static_cast<const uint16_t *>(a.grad) + o.dense_begin, len * 2);
+    else b.g = span_resource(static_cast<const float *>(a.grad) + o.dense_begin, len * 4);
+    b.mask = span_resource(a.mask + (o.dense_begin >> 5), len / 8);    // spans start and end on mask words
 
     float A = 1.0f;
     if constexpr (SCALED) { if (live_span) A = a.scale[span]; }
@@ -161,49 +157,44 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     }
 }
 
-template <bool BF16>
-__device__ __forceinline__ void load_grad4(const void *grad, int64_t idx, float (&g)[4])
-{
-    if constexpr (BF16) load4_bf16_stream(static_cast<const uint16_t *>(grad), idx, g);
-    else load4_stream(static_cast<const float *>(grad), idx, g);
-}
-
 // dL/dA alone, with exactly the traversal and summation order of adams_step_vec.
 template <bool BF16>
 __global__ __launch_bounds__(kMaxBlockThreads) void scale_grad_vec(const float *w, const void *grad,
-                                                                   float *scale_grad, int64_t total,
-                                                                   int64_t span_len, int64_t num_spans,
-                                                                   int waves_per_span)
+                                                                   float *scale_grad, const SpanGeom geom)
 {
     __shared__ float partial[kMaxBlockWaves];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int P = waves_per_span;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int P = geom.waves_per_span;
     const int block_waves = blockDim.x / kWave;
     const int64_t span = (int64_t)blockIdx.x * (block_waves / P) + wave / P;
     const int sub = wave % P;
-    const bool live = span < num_spans;
-    const int64_t begin = span * span_len;
-    int64_t len = 0;
-    if (live) len = (total - begin < span_len) ? total - begin : span_len;
+    const SpanOrigin o = span_origin(geom, span);
+    const int len = o.len;
+    __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4), rg;
+    if constexpr (BF16) rg = span_resource(static_cast<const uint16_t *>(grad) + o.dense_begin, len * 2);
+    else rg = span_resource(static_cast<const float *>(grad) + o.dense_begin, len * 4);
     float acc = 0.0f;
-    for (int64_t base = (int64_t)sub * kChunk; base < len; base += (int64_t)P * kChunk) {
-        const int64_t off = base + lane * kLaneElems;
-        float wv[4] = {0, 0, 0, 0}, g[4] = {0, 0, 0, 0};
-        if (off < len) {
-            load4_stream(w, begin + off, wv);
-            load_grad4<BF16>(grad, begin + off, g);
+    for (int base = sub * kChunk; base < len; base += P * kChunk) {
+        const int off = base + lane * kLaneElems;
+        float wv[4], g[4];
+        unpack4(__builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad), wv);
+        if constexpr (BF16) {
+            const vu2_t t = __builtin_amdgcn_raw_buffer_load_b64(rg, off * 2, 0, kAuxLoad);
+            g[0] = bf16_lo(t.x); g[1] = bf16_hi(t.x); g[2] = bf16_lo(t.y); g[3] = bf16_hi(t.y);
+        } else {
+            unpack4(__builtin_amdgcn_raw_buffer_load_b128(rg, off * 4, 0, kAuxLoad), g);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) acc = __builtin_fmaf(g[j], wv[j], acc);
     }
     const float wave_total = wave_sum_fixed_order(acc);
     if (P == 1) {
-        if (lane == 0 && live) scale_grad[span] = wave_total;
+        if (lane == 0 && len > 0) scale_grad[span] = wave_total;
     } else {
         if (lane == 0) partial[wave] = wave_total;
         __syncthreads();
-        if (lane == 0 && sub == 0 && live) {
+        if (lane == 0 && sub == 0 && len > 0) {
             float t = partial[wave];
             for (int p = 1; p < P; ++p) t = t + partial[wave + p];
             scale_grad[span] = t;
@@ -219,7 +210,7 @@ struct UnitArgs {
     float *v;
     uint32_t *mask;
     const float *scale;
-    int64_t rows, cols;
+    int64_t rows, cols, ld;
     int n_segments;
     int refresh;
     StepScalars s;
@@ -248,7 +239,8 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs 
         uint32_t *word_ptr = a.mask + r * words_per_row + cb / 32;
         uint32_t word = a.refresh ? 0u : *word_ptr;
         for (int64_t c = cb; c < ce; c += M) {
-            const int64_t idx = r * a.cols + c;
+            const int64_t idx = r * a.ld + c;          // in w, mu, v
+            const int64_t gidx = r * a.cols + c;       // in the gradient
             float wv[M];
 #pragma unroll
             for (int j = 0; j < M; ++j) wv[j] = a.w[idx + j];
@@ -263,7 +255,7 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs 
             if (a.scale) A = a.scale[r * a.n_segments + c / seg_len];
 #pragma unroll
             for (int j = 0; j < M; ++j) {
-                float g = load_grad1<BF16>(a.grad, idx + j);
+                float g = load_grad1<BF16>(a.grad, gidx + j);
                 if (a.scale) g = A * g;
                 float mu = a.m[idx + j], vv = a.v[idx + j];
                 adams_entry(wv[j], g, mu, vv, (bits >> j) & 1u, a.s);
@@ -279,17 +271,21 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs 
 // dL/dA for any shape: one wavefront per row segment, lanes stride over its entries.
 template <bool BF16>
 __global__ __launch_bounds__(kBlockThreads) void scale_grad_rows(const float *w, const void *grad,
-                                                                 float *scale_grad, int64_t num_segments,
-                                                                 int64_t seg_len)
+                                                                 float *scale_grad, int64_t rows,
+                                                                 int64_t cols, int64_t ld, int n_segments)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t seg = (int64_t)blockIdx.x * kBlockWaves + threadIdx.x / kWave;
+    const int64_t seg_len = cols / n_segments;
+    const bool live = seg < rows * n_segments;
     float acc = 0.0f;
-    if (seg < num_segments)
+    if (live) {
+        const int64_t r = seg / n_segments, c0 = (seg % n_segments) * seg_len;
         for (int64_t i = lane; i < seg_len; i += kWave)
-            acc = __builtin_fmaf(load_grad1<BF16>(grad, seg * seg_len + i), w[seg * seg_len + i], acc);
+            acc = __builtin_fmaf(load_grad1<BF16>(grad, r * cols + c0 + i), w[r * ld + c0 + i], acc);
+    }
     const float t = wave_sum_fixed_order(acc);
-    if (lane == 0 && seg < num_segments) scale_grad[seg] = t;
+    if (lane == 0 && live) scale_grad[seg] = t;
 }
 
 // ---- host side ------------------------------------------------------------------------------
@@ -300,10 +296,10 @@ static int env_int(const char *name, int fallback)
     return e && *e ? atoi(e) : fallback;
 }
 
-SpanPlan plan_spans(int64_t rows, int64_t cols, int n_segments)
+SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments)
 {
     // HBM rewards a narrow window of addresses in flight: wavefronts are kept short-lived (about
-    // two chunks of 256 entries each) and the spans of one workgroup are contiguous, so that the
+    // one chunk of 256 entries each) and the spans of one workgroup are contiguous, so that the
     // workgroups the dispatcher has resident at any time cover a compact range of every array.
     // Tuning knobs (read once): CAST_SPAN_LEN forces the flat span length, CAST_WAVES_PER_SPAN
     // the number of cooperating wavefronts, CAST_BLOCK_WAVES the workgroup size in wavefronts.
@@ -311,29 +307,44 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int n_segments)
     static const int forced_p = env_int("CAST_WAVES_PER_SPAN", 0);
     static const int forced_bw = env_int("CAST_BLOCK_WAVES", 0);
     SpanPlan p{};
-    p.total = rows * cols;
-    p.waves_per_span = 1;
+    SpanGeom &g = p.geom;
+    g.total = rows * cols;
+    g.cols = cols;
+    g.row_gap = ld - cols;
+    g.waves_per_span = 1;
+    g.div_spans_per_row = make_fast_div(1);
     int block_waves = kBlockWaves;
-    if (n_segments > 0) {
-        p.span_len = cols / n_segments;
-        p.num_spans = rows * n_segments;
-        p.vec = p.span_len % 32 == 0 && p.span_len < ((int64_t)1 << 28);   // 32-bit byte offsets inside a span
-        const int64_t chunks = (p.span_len + kChunk - 1) / kChunk;
-        while (p.waves_per_span < kMaxBlockWaves && chunks > p.waves_per_span) p.waves_per_span *= 2;
-        if (p.waves_per_span > block_waves) block_waves = p.waves_per_span;
+    int per_row = n_segments;
+    if (per_row == 0 && ld != cols) {
+        // strided rows, no scaling: cut every row into equal pieces that start on mask words
+        for (int k = 1; k <= 64 && per_row == 0; ++k)
+            if (cols % k == 0 && (cols / k) % 32 == 0 && cols / k <= 4096) per_row = k;
+        if (per_row == 0 && cols % 32 == 0 && cols < ((int64_t)1 << 28)) per_row = 1;
+    }
+    if (per_row > 0) {
+        g.spans_per_row = per_row;
+        g.div_spans_per_row = make_fast_div((uint32_t)per_row);
+        g.span_len = cols / per_row;
+        g.num_spans = rows * per_row;
+        p.vec = cols % per_row == 0 && g.span_len % 32 == 0 && g.span_len < ((int64_t)1 << 28) && ld % 4 == 0 &&
+                g.num_spans < ((int64_t)1 << 31);
+        const int64_t chunks = (g.span_len + kChunk - 1) / kChunk;
+        while (g.waves_per_span < kMaxBlockWaves && chunks > g.waves_per_span) g.waves_per_span *= 2;
+        if (g.waves_per_span > block_waves) block_waves = g.waves_per_span;
     } else {
-        p.vec = cols % 32 == 0;
+        g.spans_per_row = 0;   // flat: the matrix is one contiguous array
+        p.vec = cols % 32 == 0 && ld == cols;
         int64_t len = 2 * kChunk;
         if (forced_len >= kChunk && forced_len % kChunk == 0) len = forced_len;
-        p.span_len = len;
-        p.num_spans = (p.total + len - 1) / len;
+        g.span_len = len;
+        g.num_spans = (g.total + len - 1) / len;
     }
-    if (forced_p == 1 || forced_p == 2 || forced_p == 4 || forced_p == 8 || forced_p == 16) p.waves_per_span = forced_p;
+    if (forced_p == 1 || forced_p == 2 || forced_p == 4 || forced_p == 8 || forced_p == 16) g.waves_per_span = forced_p;
     if (forced_bw == 4 || forced_bw == 8 || forced_bw == 16) block_waves = forced_bw;
-    if (block_waves < p.waves_per_span) block_waves = p.waves_per_span;
+    if (block_waves < g.waves_per_span) block_waves = g.waves_per_span;
     p.block_threads = block_waves * kWave;
-    const int64_t spans_per_block = block_waves / p.waves_per_span;
-    p.grid = (unsigned)((p.num_spans + spans_per_block - 1) / spans_per_block);
+    const int64_t spans_per_block = block_waves / g.waves_per_span;
+    p.grid = (unsigned)((g.num_spans + spans_per_block - 1) / spans_per_block);
     return p;
 }
 
@@ -384,34 +395,33 @@ static void launch_unit_dtype(bool bf16, unsigned grid, const UnitArgs &a, hipSt
 }
 
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
-                              int64_t cols, int n_segments, float *scale_grad, hipStream_t st)
+                              int64_t cols, int64_t ld, int n_segments, float *scale_grad, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_spans(rows, cols, n_segments);
+    const SpanPlan p = plan_spans(rows, cols, ld, n_segments);
     const bool bf16 = grad_dtype == CAST_BF16;
     if (p.vec) {
-        if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
-        else hipLaunchKernelGGL(scale_grad_vec<false>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.total, p.span_len, p.num_spans, p.waves_per_span);
+        if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.geom);
+        else hipLaunchKernelGGL(scale_grad_vec<false>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.geom);
     } else {
-        const unsigned grid = (unsigned)((p.num_spans + kBlockWaves - 1) / kBlockWaves);
-        if (bf16) hipLaunchKernelGGL(scale_grad_rows<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.num_spans, p.span_len);
-        else hipLaunchKernelGGL(scale_grad_rows<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, p.num_spans, p.span_len);
+        const unsigned grid = (unsigned)((rows * n_segments + kBlockWaves - 1) / kBlockWaves);
+        if (bf16) hipLaunchKernelGGL(scale_grad_rows<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, rows, cols, ld, n_segments);
+        else hipLaunchKernelGGL(scale_grad_rows<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, rows, cols, ld, n_segments);
     }
     return launch_status();
 }
 
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              const cast_adams_config *cfg, hipStream_t st)
+                              int64_t ld, const cast_adams_config *cfg, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_spans(rows, cols, cfg->scale_segments);
+    const SpanPlan p = plan_spans(rows, cols, ld, cfg->scale_segments);
     const bool bf16 = cfg->grad_dtype == CAST_BF16;
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = scale != nullptr;
     if (p.vec) {
-        SpanArgs a{w, grad, m, v, mask_bits, scale, scale_grad, p.total, p.span_len, p.num_spans,
-                   p.waves_per_span, make_scalars(cfg)};
+        SpanArgs a{w, grad, m, v, mask_bits, scale, scale_grad, p.geom, make_scalars(cfg)};
         switch (cfg->m_group) {
         case 2: launch_vec_dtype<2>(bf16, refresh, scaled, p, a, st); break;
         case 4: launch_vec_dtype<4>(bf16, refresh, scaled, p, a, st); break;
@@ -421,10 +431,10 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     }
     // odd shapes: dL/dA first (it needs the incoming weights), then the element pass
     if (scaled && scale_grad) {
-        cast_status rc = launch_scale_grad(w, grad, cfg->grad_dtype, rows, cols, cfg->scale_segments, scale_grad, st);
+        cast_status rc = launch_scale_grad(w, grad, cfg->grad_dtype, rows, cols, ld, cfg->scale_segments, scale_grad, st);
         if (rc != CAST_OK) return rc;
     }
-    UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg)};
+    UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, ld, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg)};
     const int64_t units = rows * ((cols + 63) / 64);
     const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
     switch (cfg->m_group) {

@@ -17,6 +17,8 @@ cast_status check_nm(int n_keep, int m_group)
     return CAST_OK;
 }
 
+cast_status check_ld(int64_t cols, int64_t ld) { return ld >= cols ? CAST_OK : CAST_ERR_SHAPE; }
+
 cast_status check_matrix(int64_t rows, int64_t cols, int m_group)
 {
     if (rows < 0 || cols < 0) return CAST_ERR_SHAPE;
@@ -36,7 +38,7 @@ cast_status check_segments(int64_t cols, int n_segments, int m_group)
 }
 
 // one wavefront per row segment, 4 per workgroup, at most 2^31-1 workgroups per launch
-bool too_many_segments(int64_t rows, int n_segments) { return rows > (((int64_t)1 << 32) / n_segments); }
+bool too_many_segments(int64_t rows, int n_segments) { return rows > (((int64_t)1 << 31) / n_segments); }
 
 bool dtype_ok(int d) { return d == CAST_F32 || d == CAST_BF16; }
 size_t dtype_align(int d) { return d == CAST_BF16 ? 8 : 16; }
@@ -75,28 +77,30 @@ cast_status cast_sizes(int64_t rows, int64_t cols, int n_keep, int m_group, int 
     return CAST_OK;
 }
 
-cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int n_keep, int m_group,
-                           uint32_t *mask_bits, void *stream)
+cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
+                           int m_group, uint32_t *mask_bits, void *stream)
 {
     cast_status rc = check_nm(n_keep, m_group);
     if (rc != CAST_OK) return rc;
     rc = check_matrix(rows, cols, m_group);
     if (rc != CAST_OK) return rc;
+    if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (rows == 0 || cols == 0) return CAST_OK;
     if (!w || !mask_bits) return CAST_ERR_NULL;
     if (!aligned(w, 16) || !aligned(mask_bits, 4)) return CAST_ERR_ALIGN;
-    return launch_nm_select(w, rows, cols, n_keep, m_group, mask_bits, static_cast<hipStream_t>(stream));
+    return launch_nm_select(w, rows, cols, ld, n_keep, m_group, mask_bits, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                             const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                            const cast_adams_config *cfg, void *stream)
+                            int64_t ld, const cast_adams_config *cfg, void *stream)
 {
     if (!cfg) return CAST_ERR_NULL;
     cast_status rc = check_nm(cfg->n_keep, cfg->m_group);
     if (rc != CAST_OK) return rc;
     rc = check_matrix(rows, cols, cfg->m_group);
     if (rc != CAST_OK) return rc;
+    if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (!dtype_ok(cfg->grad_dtype)) return CAST_ERR_DTYPE;
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
     if ((cfg->scale_segments > 0) != (scale != nullptr)) return scale ? CAST_ERR_SHAPE : CAST_ERR_NULL;
@@ -115,44 +119,45 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
     if (!aligned(w, 16) || !aligned(m, 16) || !aligned(v, 16) || !aligned(grad, dtype_align(cfg->grad_dtype)) ||
         !aligned(mask_bits, 4) || !aligned(scale, 4) || !aligned(scale_grad, 4))
         return CAST_ERR_ALIGN;
-    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, cfg, static_cast<hipStream_t>(stream));
+    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
-                              int n_segments, void *out, int out_dtype, void *stream)
+                              int64_t ld, int n_segments, void *out, int out_dtype, void *stream)
 {
-    if (rows < 0 || cols < 0 || n_segments < 1 || (cols % n_segments)) return CAST_ERR_SHAPE;
+    if (rows < 0 || cols < 0 || n_segments < 1 || (cols % n_segments) || ld < cols) return CAST_ERR_SHAPE;
     if (rows > 0 && cols > 0 && rows > (((int64_t)1 << 40) / cols)) return CAST_ERR_SHAPE;
     if (!dtype_ok(out_dtype)) return CAST_ERR_DTYPE;
     if (rows == 0 || cols == 0) return CAST_OK;
     if (!w || !scale || !out) return CAST_ERR_NULL;
     if (!aligned(w, 16) || !aligned(out, dtype_align(out_dtype)) || !aligned(scale, 4)) return CAST_ERR_ALIGN;
-    return launch_weight_scale(w, scale, rows, cols, n_segments, out, out_dtype, static_cast<hipStream_t>(stream));
+    return launch_weight_scale(w, scale, rows, cols, ld, n_segments, out, out_dtype, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int grad_dtype,
-                                   int64_t rows, int64_t cols, int n_segments, float *scale_grad,
-                                   void *stream)
+                                   int64_t rows, int64_t cols, int64_t ld, int n_segments,
+                                   float *scale_grad, void *stream)
 {
-    if (rows < 0 || cols < 0 || n_segments < 1 || (cols % n_segments)) return CAST_ERR_SHAPE;
+    if (rows < 0 || cols < 0 || n_segments < 1 || (cols % n_segments) || ld < cols) return CAST_ERR_SHAPE;
     if (rows > 0 && cols > 0 && rows > (((int64_t)1 << 40) / cols)) return CAST_ERR_SHAPE;
     if (!dtype_ok(grad_dtype)) return CAST_ERR_DTYPE;
     if (too_many_segments(rows, n_segments)) return CAST_ERR_SHAPE;
     if (rows == 0 || cols == 0) return CAST_OK;
     if (!w || !grad_scaled || !scale_grad) return CAST_ERR_NULL;
     if (!aligned(w, 16) || !aligned(grad_scaled, dtype_align(grad_dtype)) || !aligned(scale_grad, 4)) return CAST_ERR_ALIGN;
-    return launch_scale_grad(w, grad_scaled, grad_dtype, rows, cols, n_segments, scale_grad, static_cast<hipStream_t>(stream));
+    return launch_scale_grad(w, grad_scaled, grad_dtype, rows, cols, ld, n_segments, scale_grad, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_nm_project_compress(const float *w, const float *scale, int n_segments,
                                      const uint32_t *mask_bits, int64_t rows, int64_t cols,
-                                     int n_keep, int m_group, void *values, int value_dtype,
-                                     uint32_t *meta, void *stream)
+                                     int64_t ld, int n_keep, int m_group, void *values,
+                                     int value_dtype, uint32_t *meta, void *stream)
 {
     cast_status rc = check_nm(n_keep, m_group);
     if (rc != CAST_OK) return rc;
     rc = check_matrix(rows, cols, m_group);
     if (rc != CAST_OK) return rc;
+    if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (!dtype_ok(value_dtype)) return CAST_ERR_DTYPE;
     if (scale && cols > 0) {
         rc = check_segments(cols, n_segments, m_group);
@@ -162,21 +167,21 @@ cast_status cast_nm_project_compress(const float *w, const float *scale, int n_s
     if (!w || !values || !meta) return CAST_ERR_NULL;
     if (!aligned(w, 16) || !aligned(values, 8) || !aligned(meta, 4) || !aligned(mask_bits, 4) || !aligned(scale, 4))
         return CAST_ERR_ALIGN;
-    return launch_project_compress(w, scale, scale ? n_segments : 0, mask_bits, rows, cols, n_keep, m_group,
+    return launch_project_compress(w, scale, scale ? n_segments : 0, mask_bits, rows, cols, ld, n_keep, m_group,
                                    values, value_dtype, meta, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
-                            int64_t rows, int64_t cols, unsigned long long *flips, double *l1,
-                            void *stream)
+                            int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
+                            double *l1, void *stream)
 {
-    if (rows < 0 || cols < 0) return CAST_ERR_SHAPE;
+    if (rows < 0 || cols < 0 || ld < cols) return CAST_ERR_SHAPE;
     if (rows > 0 && cols > 0 && rows > (((int64_t)1 << 40) / cols)) return CAST_ERR_SHAPE;
     if (rows == 0 || cols == 0) return CAST_OK;
     if (!w || !mask_bits || !flips || !l1) return CAST_ERR_NULL;
     if (!aligned(w, 4) || !aligned(mask_bits, 4) || !aligned(other_bits, 4) || !aligned(flips, 8) || !aligned(l1, 8))
         return CAST_ERR_ALIGN;
-    return launch_mask_stats(w, mask_bits, other_bits, rows, cols, flips, l1, static_cast<hipStream_t>(stream));
+    return launch_mask_stats(w, mask_bits, other_bits, rows, cols, ld, flips, l1, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *stream)

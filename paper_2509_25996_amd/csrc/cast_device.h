@@ -22,6 +22,72 @@ constexpr int kBlockWaves = kBlockThreads / kWave;
 constexpr int kMaxBlockWaves = 16;               // the step kernels run with 4, 8 or 16 wavefronts per workgroup
 constexpr int kMaxBlockThreads = kMaxBlockWaves * kWave;
 
+// ---- how a matrix is cut into spans ---------------------------------------------------------
+// A span is the unit of work of one wavefront (or of 2..16 cooperating wavefronts of one
+// workgroup): a run of consecutive entries inside one row that starts and ends on a mask word.
+// w, mu and v may have a row stride ld > cols (e.g. the three arrays interleaved row by row in
+// one allocation, which keeps their streams close together in HBM); the gradient, the mask
+// bits and the packed outputs are always dense.
+struct FastDivU32 {           // n / d for 32-bit n by multiply-high and shifts (d >= 1)
+    uint32_t mul, shift, is_one;
+};
+
+inline FastDivU32 make_fast_div(uint32_t d)
+{
+    FastDivU32 f{0, 0, 1};
+    if (d <= 1) return f;
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;                                  // l = ceil(log2 d)
+    f.mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);        // floor(2^32 (2^l - d) / d) + 1
+    f.shift = l - 1;
+    f.is_one = 0;
+    return f;
+}
+
+__host__ __device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDivU32 &f)
+{
+    if (f.is_one) return n;
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t t = __umulhi(f.mul, n);
+#else
+    const uint32_t t = (uint32_t)(((uint64_t)f.mul * n) >> 32);
+#endif
+    return (t + ((n - t) >> 1)) >> f.shift;
+}
+
+struct SpanGeom {
+    int64_t total;          // rows * cols
+    int64_t cols;
+    int64_t row_gap;        // ld - cols: entries skipped between the rows of w, mu, v
+    int64_t span_len;       // entries per span (the last span of a flat plan may be shorter)
+    int64_t num_spans;
+    int spans_per_row;      // 0: flat plan (the matrix is one contiguous array, spans ignore rows)
+    int waves_per_span;     // 1, 2, 4, 8 or 16
+    FastDivU32 div_spans_per_row;
+};
+
+struct SpanOrigin {
+    int64_t state_begin;    // first entry of the span in w, mu, v
+    int64_t dense_begin;    // first entry of the span in dense [rows, cols] numbering
+    int len;                // entries (0 for spans past the end)
+};
+
+__device__ __forceinline__ SpanOrigin span_origin(const SpanGeom &g, int64_t span)
+{
+    SpanOrigin o{0, 0, 0};
+    if (span >= g.num_spans) return o;
+    o.dense_begin = span * g.span_len;
+    o.state_begin = o.dense_begin;
+    if (g.spans_per_row == 0) {
+        const int64_t rem = g.total - o.dense_begin;
+        o.len = (int)(rem < g.span_len ? rem : g.span_len);
+    } else {
+        o.len = (int)g.span_len;
+        if (g.row_gap != 0) o.state_begin += (int64_t)fast_div((uint32_t)span, g.div_spans_per_row) * g.row_gap;
+    }
+    return o;
+}
+
 // ---- cross-lane moves inside a row of 16 lanes (DPP: no LDS traffic) -------------------
 // quad_perm selectors: lane i of each quad reads lane perm[i] of the same quad.
 constexpr int kDppQuadXor1 = 0xB1;       // [1,0,3,2]

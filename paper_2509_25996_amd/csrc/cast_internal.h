@@ -4,42 +4,41 @@
 #include <stdint.h>
 
 #include "../../include/cast.h"
+#include "cast_device.h"
 
 namespace cast {
 
-// How a matrix is cut into spans, the unit of work of one wavefront (or of 2 or 4 cooperating
-// wavefronts of one workgroup).  With weight scaling a span is one row segment of Eq. 12, so
+// How one launch covers a matrix.  With weight scaling a span is one row segment of Eq. 12, so
 // its scale factor is a wave-uniform scalar and dL/dA of that segment is reduced inside the
-// workgroup, written once, without atomics.  Without scaling the matrix is treated as one
-// flat array cut into equal spans.
+// workgroup, written once, without atomics.  Without scaling a dense matrix is treated as one
+// flat array cut into short spans; a matrix with strided rows is cut into equal pieces of its rows.
 struct SpanPlan {
     bool vec;            // the vector kernels apply (spans start on mask-word boundaries)
-    int64_t total;       // rows * cols
-    int64_t span_len;    // entries per span (the last span of a flat plan may be shorter)
-    int64_t num_spans;
-    int waves_per_span;  // 1, 2, 4, 8 or 16
+    SpanGeom geom;
     int block_threads;   // 256, 512 or 1024
     unsigned grid;       // workgroups
 };
 
-SpanPlan plan_spans(int64_t rows, int64_t cols, int n_segments);
+SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments);
 
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              const cast_adams_config *cfg, hipStream_t stream);
+                              int64_t ld, const cast_adams_config *cfg, hipStream_t stream);
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
-                              int64_t cols, int n_segments, float *scale_grad, hipStream_t stream);
-cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int n_keep, int m_group,
-                             uint32_t *mask_bits, hipStream_t stream);
+                              int64_t cols, int64_t ld, int n_segments, float *scale_grad,
+                              hipStream_t stream);
+cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
+                             int m_group, uint32_t *mask_bits, hipStream_t stream);
 cast_status launch_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
-                                int n_segments, void *out, int out_dtype, hipStream_t stream);
+                                int64_t ld, int n_segments, void *out, int out_dtype,
+                                hipStream_t stream);
 cast_status launch_project_compress(const float *w, const float *scale, int n_segments,
                                     const uint32_t *mask_bits, int64_t rows, int64_t cols,
-                                    int n_keep, int m_group, void *values, int value_dtype,
-                                    uint32_t *meta, hipStream_t stream);
+                                    int64_t ld, int n_keep, int m_group, void *values,
+                                    int value_dtype, uint32_t *meta, hipStream_t stream);
 cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
-                              int64_t rows, int64_t cols, unsigned long long *flips, double *l1,
-                              hipStream_t stream);
+                              int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
+                              double *l1, hipStream_t stream);
 cast_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
 

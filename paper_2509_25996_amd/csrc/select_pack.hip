@@ -1,6 +1,8 @@
 // Mask selection alone (Eq. 6), weight scaling forward/fold (Eq. 12), the final hard prune
 // with packing into values + index metadata, the mask-learning statistics of the appendix
 // "Mask Learning", and a plain copy kernel used to calibrate bandwidth measurements.
+//
+// w may have a row stride ld >= cols; masks, packed values, metadata and scaled outputs are dense.
 #include "cast_device.h"
 #include "cast_internal.h"
 
@@ -8,40 +10,41 @@
 
 namespace cast {
 
-__device__ __forceinline__ void ld4(const float *p, int64_t idx, float (&x)[4])
+__device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
 {
-    const float4 t = *reinterpret_cast<const float4 *>(p + idx);
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    f[0] = __uint_as_float(x.x); f[1] = __uint_as_float(x.y); f[2] = __uint_as_float(x.z); f[3] = __uint_as_float(x.w);
 }
 
 // ---- Eq. 6 ----------------------------------------------------------------------------------
-// Flat walk, 256 entries per wavefront per chunk; requires cols % 32 == 0 so that flat mask
-// words coincide with the row-padded layout.
+// One wavefront per span, 256 entries per chunk; spans start on mask words.
 template <int M>
-__global__ __launch_bounds__(kBlockThreads) void nm_select_vec(const float *w, uint32_t *mask,
-                                                               int64_t total, int64_t span_len,
-                                                               int n_keep)
+__global__ __launch_bounds__(kMaxBlockThreads) void nm_select_vec(const float *w, uint32_t *mask,
+                                                                  const SpanGeom geom, int n_keep)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t span = (int64_t)blockIdx.x * kBlockWaves + threadIdx.x / kWave;
-    const int64_t begin = span * span_len;
-    int64_t len = total - begin;
-    if (len > span_len) len = span_len;
-    for (int64_t base = 0; base < len; base += kChunk) {   // len <= 0 for spans past the end
-        const int64_t off = base + lane * kLaneElems;
-        const bool act = off < len;
-        float x[4] = {0, 0, 0, 0};
-        if (act) ld4(w, begin + off, x);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int P = geom.waves_per_span;
+    const int64_t span = (int64_t)blockIdx.x * ((blockDim.x / kWave) / P) + wave / P;
+    const int sub = wave % P;
+    const SpanOrigin o = span_origin(geom, span);
+    const int len = o.len;
+    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
+    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask + (o.dense_begin >> 5), len / 8);
+    for (int base = sub * kChunk; base < len; base += P * kChunk) {
+        const int off = base + lane * kLaneElems;
+        float x[4];
+        unpack4u(__builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad), x);
         const uint32_t nib = keep_nibble<M>(x, n_keep, lane);
         const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
-        if (act && (lane & 7) == 0) mask[(begin + off) >> 5] = word;
+        if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmask, (off >> 5) * 4, 0, kAuxStore);
     }
 }
 
 // Any shape with cols % M == 0: one thread per mask word (32 consecutive columns of a row).
 template <int M>
 __global__ __launch_bounds__(kBlockThreads) void nm_select_unit(const float *w, uint32_t *mask,
-                                                                int64_t rows, int64_t cols, int n_keep)
+                                                                int64_t rows, int64_t cols, int64_t ld,
+                                                                int n_keep)
 {
     const int64_t words_per_row = (cols + 31) / 32;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -52,88 +55,84 @@ __global__ __launch_bounds__(kBlockThreads) void nm_select_unit(const float *w, 
     for (int64_t c = cb; c < ce; c += M) {
         float x[M];
 #pragma unroll
-        for (int j = 0; j < M; ++j) x[j] = w[r * cols + c + j];
+        for (int j = 0; j < M; ++j) x[j] = w[r * ld + c + j];
         word |= keep_bits_group<M>(x, n_keep) << (unsigned)(c - cb);
     }
     mask[tid] = word;
 }
 
-cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int n_keep, int m_group,
-                             uint32_t *mask_bits, hipStream_t st)
+cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
+                             int m_group, uint32_t *mask_bits, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    SpanPlan p = plan_spans(rows, cols, 0);
-    p.span_len = 2 * kChunk;
-    p.num_spans = (p.total + p.span_len - 1) / p.span_len;
+    const SpanPlan p = plan_spans(rows, cols, ld, 0);
     if (p.vec) {
-        const unsigned grid = (unsigned)((p.num_spans + kBlockWaves - 1) / kBlockWaves);
         switch (m_group) {
-        case 2: hipLaunchKernelGGL(nm_select_vec<2>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, p.total, p.span_len, n_keep); break;
-        case 4: hipLaunchKernelGGL(nm_select_vec<4>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, p.total, p.span_len, n_keep); break;
-        default: hipLaunchKernelGGL(nm_select_vec<8>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, p.total, p.span_len, n_keep); break;
+        case 2: hipLaunchKernelGGL(nm_select_vec<2>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
+        case 4: hipLaunchKernelGGL(nm_select_vec<4>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
+        default: hipLaunchKernelGGL(nm_select_vec<8>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
         }
     } else {
         const int64_t words = rows * ((cols + 31) / 32);
         const unsigned grid = (unsigned)((words + kBlockThreads - 1) / kBlockThreads);
         switch (m_group) {
-        case 2: hipLaunchKernelGGL(nm_select_unit<2>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, n_keep); break;
-        case 4: hipLaunchKernelGGL(nm_select_unit<4>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, n_keep); break;
-        default: hipLaunchKernelGGL(nm_select_unit<8>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, n_keep); break;
+        case 2: hipLaunchKernelGGL(nm_select_unit<2>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, ld, n_keep); break;
+        case 4: hipLaunchKernelGGL(nm_select_unit<4>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, ld, n_keep); break;
+        default: hipLaunchKernelGGL(nm_select_unit<8>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, ld, n_keep); break;
         }
     }
     return launch_status();
 }
 
 // ---- Eq. 12 forward / fold --------------------------------------------------------------------
-template <bool BF16OUT>
-__global__ __launch_bounds__(kBlockThreads) void weight_scale_vec(const float *w, const float *scale,
-                                                                  void *out, int64_t total,
-                                                                  int64_t seg_len)
+// One thread per W consecutive entries of a row (W = 4: 16-byte accesses; W = 1 for odd shapes).
+template <bool BF16OUT, int W>
+__global__ __launch_bounds__(kBlockThreads) void weight_scale_kernel(const float *w, const float *scale,
+                                                                     void *out, int64_t rows, int64_t cols,
+                                                                     int64_t ld, int64_t seg_len)
 {
-    // one thread per 4 consecutive entries; a segment boundary never falls inside them
-    const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (idx >= total) return;
-    float x[4];
-    ld4(w, idx, x);
-    const float A = scale[idx / seg_len];   // flat segment index = r * n + s
-#pragma unroll
-    for (int j = 0; j < 4; ++j) x[j] = A * x[j];
-    if constexpr (BF16OUT) {
-        uint2 o;
-        o.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
-        o.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
-        *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(out) + idx) = o;
+    const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * W;     // dense index
+    if (idx >= rows * cols) return;
+    const int64_t r = idx / cols, c = idx - r * cols;
+    const float A = scale[idx / seg_len];      // dense segment index = r * n + s
+    float x[W];
+    if constexpr (W == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(w + r * ld + c);
+        x[0] = A * t.x; x[1] = A * t.y; x[2] = A * t.z; x[3] = A * t.w;
     } else {
-        *reinterpret_cast<float4 *>(static_cast<float *>(out) + idx) = make_float4(x[0], x[1], x[2], x[3]);
+        x[0] = A * w[r * ld + c];
+    }
+    if constexpr (BF16OUT) {
+        uint16_t *o = static_cast<uint16_t *>(out) + idx;
+        if constexpr (W == 4) {
+            uint2 q;
+            q.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
+            q.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
+            *reinterpret_cast<uint2 *>(o) = q;
+        } else {
+            o[0] = (uint16_t)f32_to_bf16_rne(x[0]);
+        }
+    } else {
+        float *o = static_cast<float *>(out) + idx;
+        if constexpr (W == 4) *reinterpret_cast<float4 *>(o) = make_float4(x[0], x[1], x[2], x[3]);
+        else o[0] = x[0];
     }
 }
 
-template <bool BF16OUT>
-__global__ __launch_bounds__(kBlockThreads) void weight_scale_scalar(const float *w, const float *scale,
-                                                                     void *out, int64_t total,
-                                                                     int64_t seg_len)
-{
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const float y = scale[idx / seg_len] * w[idx];
-    if constexpr (BF16OUT) static_cast<uint16_t *>(out)[idx] = (uint16_t)f32_to_bf16_rne(y);
-    else static_cast<float *>(out)[idx] = y;
-}
-
 cast_status launch_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
-                                int n_segments, void *out, int out_dtype, hipStream_t st)
+                                int64_t ld, int n_segments, void *out, int out_dtype, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
     const int64_t total = rows * cols, seg_len = cols / n_segments;
     const bool bf16 = out_dtype == CAST_BF16;
-    if (seg_len % 4 == 0) {
+    if (seg_len % 4 == 0 && ld % 4 == 0) {
         const unsigned grid = (unsigned)((total / 4 + kBlockThreads - 1) / kBlockThreads);
-        if (bf16) hipLaunchKernelGGL(weight_scale_vec<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, total, seg_len);
-        else hipLaunchKernelGGL(weight_scale_vec<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, total, seg_len);
+        if (bf16) hipLaunchKernelGGL((weight_scale_kernel<true, 4>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
+        else hipLaunchKernelGGL((weight_scale_kernel<false, 4>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
     } else {
         const unsigned grid = (unsigned)((total + kBlockThreads - 1) / kBlockThreads);
-        if (bf16) hipLaunchKernelGGL(weight_scale_scalar<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, total, seg_len);
-        else hipLaunchKernelGGL(weight_scale_scalar<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, total, seg_len);
+        if (bf16) hipLaunchKernelGGL((weight_scale_kernel<true, 1>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
+        else hipLaunchKernelGGL((weight_scale_kernel<false, 1>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
     }
     return launch_status();
 }
@@ -143,28 +142,32 @@ cast_status launch_weight_scale(const float *w, const float *scale, int64_t rows
 // (fp32) or 4-byte (bf16) store and the 4-bit index fields of 8 adjacent lanes form one
 // metadata word, exactly like the mask words.
 template <bool BF16OUT>
-__global__ __launch_bounds__(kBlockThreads) void project_compress_2of4_vec(
+__global__ __launch_bounds__(kMaxBlockThreads) void project_compress_2of4_vec(
     const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
-    int64_t total, int64_t span_len, int64_t seg_len)
+    const SpanGeom geom, int64_t seg_len)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t span = (int64_t)blockIdx.x * kBlockWaves + threadIdx.x / kWave;
-    const int64_t begin = span * span_len;
-    int64_t len = total - begin;
-    if (len > span_len) len = span_len;
-    for (int64_t base = 0; base < len; base += kChunk) {
-        const int64_t off = base + lane * kLaneElems;
-        const bool act = off < len;
-        const int64_t idx = begin + off;
-        float x[4] = {0, 0, 0, 0};
-        uint32_t nib = 0x3u;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int P = geom.waves_per_span;
+    const int64_t span = (int64_t)blockIdx.x * ((blockDim.x / kWave) / P) + wave / P;
+    const int sub = wave % P;
+    const SpanOrigin o = span_origin(geom, span);
+    const int len = o.len;
+    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
+    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask ? mask + (o.dense_begin >> 5) : nullptr, mask ? len / 8 : 0);
+    const __amdgpu_buffer_rsrc_t rmeta = span_resource(meta + (o.dense_begin >> 5), len / 8);
+    // two values per group of four: the values of a span start at dense_begin / 2
+    const int vbytes = BF16OUT ? 2 : 4;
+    const __amdgpu_buffer_rsrc_t rval = span_resource(static_cast<char *>(values) + (o.dense_begin >> 1) * vbytes, (len >> 1) * vbytes);
+    for (int base = sub * kChunk; base < len; base += P * kChunk) {
+        const int off = base + lane * kLaneElems;
+        float x[4];
+        unpack4u(__builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad), x);
+        uint32_t nib;
+        if (mask) nib = (__builtin_amdgcn_raw_buffer_load_b32(rmask, (off >> 5) * 4, 0, kAuxLoad) >> (off & 31)) & 0xFu;
+        else nib = keep_nibble<4>(x, 2, lane);
         float A = 1.0f;
-        if (act) {
-            ld4(w, idx, x);
-            if (mask) nib = (mask[idx >> 5] >> (unsigned)(idx & 31)) & 0xFu;
-            if (scale) A = scale[idx / seg_len];
-        }
-        if (!mask) nib = keep_nibble<4>(x, 2, lane);
+        if (scale && off < len) A = scale[(o.dense_begin + off) / seg_len];
         // positions of the two kept entries, ascending
         const uint32_t first = (uint32_t)__builtin_ctz(nib | 0x10u);
         const uint32_t rest = nib & (nib - 1u);
@@ -174,14 +177,13 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_2of4_vec(
         if (scale) { a = A * a; b = A * b; }
         const uint32_t field = (first & 3u) | (second << 2);
         const uint32_t word = or_reduce_8lanes(field << ((lane & 7) * 4));
-        if (act) {
-            const int64_t o = (idx >> 2) * 2;   // two values per group
-            if constexpr (BF16OUT)
-                static_cast<uint32_t *>(values)[o >> 1] = f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16);
-            else
-                *reinterpret_cast<float2 *>(static_cast<float *>(values) + o) = make_float2(a, b);
-            if ((lane & 7) == 0) meta[idx >> 5] = word;
+        if constexpr (BF16OUT) {
+            __builtin_amdgcn_raw_buffer_store_b32(f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16), rval, (off >> 1) * 2, 0, kAuxStore);
+        } else {
+            const vu2_t pair = {__float_as_uint(a), __float_as_uint(b)};
+            __builtin_amdgcn_raw_buffer_store_b64(pair, rval, (off >> 1) * 4, 0, kAuxStore);
         }
+        if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off >> 5) * 4, 0, kAuxStore);
     }
 }
 
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_2of4_vec(
 template <int M, bool BF16OUT>
 __global__ __launch_bounds__(kBlockThreads) void project_compress_unit(
     const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
-    int64_t rows, int64_t cols, int n_keep, int n_segments)
+    int64_t rows, int64_t cols, int64_t ld, int n_keep, int n_segments)
 {
     constexpr int B = M == 2 ? 1 : (M == 4 ? 2 : 3);
     int f = 1;
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_unit(
         const int64_t gi = c / M;
         float x[M];
 #pragma unroll
-        for (int j = 0; j < M; ++j) x[j] = w[r * cols + c + j];
+        for (int j = 0; j < M; ++j) x[j] = w[r * ld + c + j];
         uint32_t bits;
         if (mask) bits = (mask[r * mask_wpr + c / 32] >> (unsigned)(c % 32)) & ((1u << M) - 1u);
         else bits = keep_bits_group<M>(x, n_keep);
@@ -241,35 +243,32 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_unit(
 template <int M>
 static void launch_pack_unit(bool bf16, unsigned grid, hipStream_t st, const float *w, const float *scale,
                              const uint32_t *mask, void *values, uint32_t *meta, int64_t rows,
-                             int64_t cols, int n_keep, int n_segments)
+                             int64_t cols, int64_t ld, int n_keep, int n_segments)
 {
-    if (bf16) hipLaunchKernelGGL((project_compress_unit<M, true>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, n_keep, n_segments);
-    else hipLaunchKernelGGL((project_compress_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, n_keep, n_segments);
+    if (bf16) hipLaunchKernelGGL((project_compress_unit<M, true>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments);
+    else hipLaunchKernelGGL((project_compress_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments);
 }
 
 cast_status launch_project_compress(const float *w, const float *scale, int n_segments,
                                     const uint32_t *mask_bits, int64_t rows, int64_t cols,
-                                    int n_keep, int m_group, void *values, int value_dtype,
-                                    uint32_t *meta, hipStream_t st)
+                                    int64_t ld, int n_keep, int m_group, void *values,
+                                    int value_dtype, uint32_t *meta, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
     const bool bf16 = value_dtype == CAST_BF16;
     const int64_t seg_len = scale ? cols / n_segments : cols;
-    if (n_keep == 2 && m_group == 4 && cols % 32 == 0 && seg_len % 4 == 0) {
-        SpanPlan p = plan_spans(rows, cols, 0);
-        p.span_len = 2 * kChunk;
-        p.num_spans = (p.total + p.span_len - 1) / p.span_len;
-        const unsigned grid = (unsigned)((p.num_spans + kBlockWaves - 1) / kBlockWaves);
-        if (bf16) hipLaunchKernelGGL(project_compress_2of4_vec<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask_bits, values, meta, p.total, p.span_len, seg_len);
-        else hipLaunchKernelGGL(project_compress_2of4_vec<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask_bits, values, meta, p.total, p.span_len, seg_len);
+    const SpanPlan p = plan_spans(rows, cols, ld, 0);
+    if (n_keep == 2 && m_group == 4 && p.vec && seg_len % 4 == 0) {
+        if (bf16) hipLaunchKernelGGL(project_compress_2of4_vec<true>, dim3(p.grid), dim3(p.block_threads), 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+        else hipLaunchKernelGGL(project_compress_2of4_vec<false>, dim3(p.grid), dim3(p.block_threads), 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
         return launch_status();
     }
     const int64_t units = rows * ((cols + 63) / 64);
     const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
     switch (m_group) {
-    case 2: launch_pack_unit<2>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, n_keep, n_segments); break;
-    case 4: launch_pack_unit<4>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, n_keep, n_segments); break;
-    default: launch_pack_unit<8>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, n_keep, n_segments); break;
+    case 2: launch_pack_unit<2>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, ld, n_keep, n_segments); break;
+    case 4: launch_pack_unit<4>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, ld, n_keep, n_segments); break;
+    default: launch_pack_unit<8>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, ld, n_keep, n_segments); break;
     }
     return launch_status();
 }
@@ -279,7 +278,7 @@ cast_status launch_project_compress(const float *w, const float *scale, int n_se
 // kind per workgroup.
 __global__ __launch_bounds__(kBlockThreads) void mask_stats_kernel(
     const float *w, const uint32_t *mask, const uint32_t *other, int64_t rows, int64_t cols,
-    unsigned long long *flips, double *l1)
+    int64_t ld, unsigned long long *flips, double *l1)
 {
     __shared__ double sh_kept[kBlockWaves], sh_total[kBlockWaves];
     __shared__ unsigned long long sh_flips[kBlockWaves];
@@ -294,7 +293,7 @@ __global__ __launch_bounds__(kBlockThreads) void mask_stats_kernel(
         const uint32_t word = mask[t];
         if (other) nf += (unsigned long long)__popc(word ^ other[t]);
         for (int64_t c = cb; c < ce; ++c) {
-            const double mag = fabs((double)w[r * cols + c]);
+            const double mag = fabs((double)w[r * ld + c]);
             total += mag;
             if ((word >> (unsigned)(c - cb)) & 1u) kept += mag;
         }
@@ -316,14 +315,14 @@ __global__ __launch_bounds__(kBlockThreads) void mask_stats_kernel(
 }
 
 cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
-                              int64_t rows, int64_t cols, unsigned long long *flips, double *l1,
-                              hipStream_t st)
+                              int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
+                              double *l1, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
     const int64_t n_words = rows * ((cols + 31) / 32);
     int64_t grid = (n_words + kBlockThreads - 1) / kBlockThreads;
     if (grid > 8192) grid = 8192;
-    hipLaunchKernelGGL(mask_stats_kernel, dim3((unsigned)grid), dim3(kBlockThreads), 0, st, w, mask_bits, other_bits, rows, cols, flips, l1);
+    hipLaunchKernelGGL(mask_stats_kernel, dim3((unsigned)grid), dim3(kBlockThreads), 0, st, w, mask_bits, other_bits, rows, cols, ld, flips, l1);
     return launch_status();
 }
 

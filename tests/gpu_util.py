@@ -62,11 +62,14 @@ def oracle_cfg(cfg: B.AdamsConfig) -> oracle.AdamsCfg:
 class GpuState:
     """w, mu, v, mask (and optionally A, dL/dA) of one matrix on the GPU."""
 
-    def __init__(self, w: np.ndarray, n_segments: int = 0):
+    def __init__(self, w: np.ndarray, n_segments: int = 0, interleaved: bool = False):
         rows, cols = w.shape
-        self.w = dev(w)
-        self.m = torch.zeros_like(self.w)
-        self.v = torch.zeros_like(self.w)
+        if interleaved:      # w, mu, v row-interleaved in one buffer: row stride 3 * cols
+            self.w, self.m, self.v = B.interleaved_state(dev(w))
+        else:
+            self.w = dev(w)
+            self.m = torch.zeros_like(self.w)
+            self.v = torch.zeros_like(self.w)
         self.mask = B.alloc_mask(rows, cols, DEV)
         self.scale_grad = torch.zeros((rows, n_segments), dtype=torch.float32, device=DEV) if n_segments else None
 

@@ -68,12 +68,13 @@ def test_validation_happens_before_any_launch(lib):
     st = C.c_void_p(0)
     step = lib.cast_adams_step
 
-    def call(cfg, w=p, g=p, m=p, v=p, k=p, a=nul, ga=nul, rows=4, cols=64):
-        return step(w, g, m, v, k, a, ga, rows, cols, C.byref(cfg), st)
+    def call(cfg, w=p, g=p, m=p, v=p, k=p, a=nul, ga=nul, rows=4, cols=64, ld=None):
+        return step(w, g, m, v, k, a, ga, rows, cols, cols if ld is None else ld, C.byref(cfg), st)
 
     assert call(_cfg(n_keep=2, m_group=3)) == -2
     assert call(_cfg(n_keep=4, m_group=4)) == -2
     assert call(_cfg(), cols=66) == -2
+    assert call(_cfg(), ld=60) == -2                             # row stride shorter than a row
     assert call(_cfg(scale_segments=2)) == -1                    # segments announced, no scale buffer
     assert call(_cfg(), a=p) == -2                               # scale buffer, no segments
     assert call(_cfg(), ga=p) == -1                              # dL/dA asked without a scale
@@ -88,25 +89,29 @@ def test_validation_happens_before_any_launch(lib):
     assert call(_cfg(), k=nul) == -1
     assert call(_cfg(), w=odd) == -3
     assert call(_cfg(), m=odd) == -3
-    assert step(p, p, p, p, p, nul, nul, 4, 64, None, st) == -1
+    assert step(p, p, p, p, p, nul, nul, 4, 64, 64, None, st) == -1
     # empty tensors are accepted and do nothing, even with null buffers
     assert call(_cfg(), w=nul, g=nul, m=nul, v=nul, k=nul, rows=0) == 0
     assert call(_cfg(), w=nul, g=nul, m=nul, v=nul, k=nul, cols=0) == 0
 
-    assert lib.cast_nm_select(p, 4, 62, 2, 4, p, st) == -2
-    assert lib.cast_nm_select(nul, 4, 64, 2, 4, p, st) == -1
-    assert lib.cast_nm_select(odd, 4, 64, 2, 4, p, st) == -3
-    assert lib.cast_nm_select(nul, 0, 64, 2, 4, nul, st) == 0
-    assert lib.cast_weight_scale(p, p, 4, 64, 3, p, 0, st) == -2
-    assert lib.cast_weight_scale(p, p, 4, 64, 2, p, 5, st) == -4
-    assert lib.cast_weight_scale(p, nul, 4, 64, 2, p, 0, st) == -1
-    assert lib.cast_weight_scale_grad(p, p, 0, 4, 64, 0, p, st) == -2
-    assert lib.cast_weight_scale_grad(p, p, 0, 4, 64, 2, nul, st) == -1
-    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 2, 4, nul, 0, p, st) == -1
-    assert lib.cast_nm_project_compress(p, p, 3, nul, 4, 64, 2, 4, p, 0, p, st) == -2
-    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 2, 4, p, 9, p, st) == -4
-    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 60, 4, 8, p, 0, p, st) == -2
-    assert lib.cast_mask_stats(p, nul, nul, 4, 64, p, p, st) == -1
+    assert lib.cast_nm_select(p, 4, 62, 62, 2, 4, p, st) == -2
+    assert lib.cast_nm_select(p, 4, 64, 63, 2, 4, p, st) == -2
+    assert lib.cast_nm_select(nul, 4, 64, 64, 2, 4, p, st) == -1
+    assert lib.cast_nm_select(odd, 4, 64, 64, 2, 4, p, st) == -3
+    assert lib.cast_nm_select(nul, 0, 64, 64, 2, 4, nul, st) == 0
+    assert lib.cast_weight_scale(p, p, 4, 64, 64, 3, p, 0, st) == -2
+    assert lib.cast_weight_scale(p, p, 4, 64, 32, 2, p, 0, st) == -2
+    assert lib.cast_weight_scale(p, p, 4, 64, 64, 2, p, 5, st) == -4
+    assert lib.cast_weight_scale(p, nul, 4, 64, 64, 2, p, 0, st) == -1
+    assert lib.cast_weight_scale_grad(p, p, 0, 4, 64, 64, 0, p, st) == -2
+    assert lib.cast_weight_scale_grad(p, p, 0, 4, 64, 64, 2, nul, st) == -1
+    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 64, 2, 4, nul, 0, p, st) == -1
+    assert lib.cast_nm_project_compress(p, p, 3, nul, 4, 64, 64, 2, 4, p, 0, p, st) == -2
+    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 64, 2, 4, p, 9, p, st) == -4
+    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 60, 60, 4, 8, p, 0, p, st) == -2
+    assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 8, 2, 4, p, 0, p, st) == -2
+    assert lib.cast_mask_stats(p, nul, nul, 4, 64, 64, p, p, st) == -1
+    assert lib.cast_mask_stats(p, p, nul, 4, 64, 63, p, p, st) == -2
     assert lib.cast_hbm_copy_probe(p, p, 24, st) == -2
     assert lib.cast_hbm_copy_probe(p, odd, 32, st) == -3
     assert lib.cast_hbm_copy_probe(nul, nul, 0, st) == 0

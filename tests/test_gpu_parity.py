@@ -61,11 +61,11 @@ def test_select_paper_example_and_special_values():
 
 
 # --------------------------------------------------------------------------- AdamS step
-def _run_both(w0, grads, cfgs, arith, scales=None, bf16=False):
+def _run_both(w0, grads, cfgs, arith, scales=None, bf16=False, interleaved=False):
     """grads: list of fp32 arrays (already bf16-representable when bf16).  Returns the two states
     and per-step lists of dL/dA (gpu fp32, oracle double)."""
     n_seg = cfgs[0].scale_segments
-    g = GpuState(w0, n_seg)
+    g = GpuState(w0, n_seg, interleaved)
     o = OracleState(w0, arith)
     gAs = []
     for t, (grad, cfg) in enumerate(zip(grads, cfgs)):
@@ -147,7 +147,7 @@ def test_config2_bf16_grads_scaled_ramp_100_steps(name, rows, cols):
     lam = 1e-3   # of the gradients' order (Sec. 4.1.2) so that masks really flip inside 100 steps
     tid = {"q": 0, "fc1": 4, "fc2": 5}[name]
     w0 = synth.weights(0, tid, rows, cols)
-    g = GpuState(w0, n)
+    g = GpuState(w0, n, interleaved=(name != "q"))     # the row-interleaved layout the benchmark uses
     o = OracleState(w0, "f32")
     A = np.ones((rows, n), np.float32)
     mA, vA = np.zeros((rows, n)), np.zeros((rows, n))
@@ -180,7 +180,8 @@ def test_config2_bf16_grads_scaled_ramp_100_steps(name, rows, cols):
 @pytest.mark.parametrize("rows,cols,nseg", [(6, 512, 0), (6, 512, 2), (5, 1280 + 64, 2), (7, 72, 3), (3, 40, 0),
                                             (9, 24, 1), (2, 8, 0)])
 @pytest.mark.parametrize("bf16", [False, True])
-def test_step_every_pattern_and_odd_shapes(n, m, rows, cols, nseg, bf16):
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_step_every_pattern_and_odd_shapes(n, m, rows, cols, nseg, bf16, interleaved):
     if cols % m or (nseg and (cols // nseg) % m):
         pytest.skip("shape not valid for this M")
     steps = 3
@@ -195,7 +196,7 @@ def test_step_every_pattern_and_odd_shapes(n, m, rows, cols, nseg, bf16):
     scales = None
     if nseg:
         scales = [(1 + 0.2 * rng.standard_normal((rows, nseg))).astype(np.float32) for _ in range(steps)]
-    g, o, gAs = _run_both(w0, grads, cfgs, "f32", scales=scales, bf16=bf16)
+    g, o, gAs = _run_both(w0, grads, cfgs, "f32", scales=scales, bf16=bf16, interleaved=interleaved)
     _check_state(g, o, exact=True)
     for got, ref in gAs[-1:]:
         assert np.abs(got - ref).max() <= 1e-5 * max(np.abs(ref).max(), 1e-12) + 1e-9
@@ -357,3 +358,44 @@ def test_mask_stats_match_oracle():
     f, kept, total = oracle.mask_stats(w2, k1, k0)
     assert int(flips.item()) == 2 * f and f > 0
     assert np.allclose(host(l1), [2 * kept, 2 * total], rtol=1e-12)
+
+
+# --------------------------------------------------------------------------- strided weights everywhere
+@pytest.mark.parametrize("rows,cols", [(16, 1024), (5, 8 * 37), (3, 40), (64, 4096 + 32)])
+def test_strided_weights_in_every_entry_point(rows, cols):
+    # w taken from a row-interleaved [rows, 3, cols] buffer (row stride 3*cols): same results as dense
+    w0 = synth.tie_outlier_weights(7, 1, rows, cols)
+    ws, ms, vs = B.interleaved_state(dev(w0))
+    ms.fill_(7.0)   # neighbours in memory must neither be read as weights nor written
+    vs.fill_(-3.0)
+    for n, m in [(2, 4), (4, 8), (1, 2)]:
+        mask = B.alloc_mask(rows, cols, DEV)
+        B.cast_nm_select(ws, n, m, mask)
+        keep = oracle.nm_select(w0, n, m)
+        assert (words(mask) == oracle.pack_mask_bits(keep)).all()
+        _, _, mbytes = B.cast_sizes(rows, cols, n, m)
+        values = torch.empty((rows, cols // m * n), device=DEV)
+        meta = torch.empty((rows, mbytes // 4 // rows), dtype=torch.int32, device=DEV)
+        A = (1 + 0.1 * np.random.default_rng(1).standard_normal((rows, 2))).astype(np.float32)
+        use_A = (cols // 2) % m == 0
+        B.cast_nm_project_compress(ws, n, m, values, meta, scale=dev(A) if use_A else None, mask_bits=mask)
+        ref_v, ref_m = oracle.project_compress(w0, n, m, A=A if use_A else None, keep=keep)
+        assert (words(meta) == ref_m).all()
+        assert_same_bits(host(values), ref_v, "values")
+    A = (1 + 0.1 * np.random.default_rng(2).standard_normal((rows, 2))).astype(np.float32)
+    out = torch.empty((rows, cols), dtype=torch.bfloat16, device=DEV)
+    B.cast_weight_scale(ws, dev(A), out)
+    assert (host(out.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(oracle.weight_scale(w0, A))).all()
+    gs = synth.grads_f32(7, 1, 0, rows, cols)
+    gA = torch.zeros((rows, 2), device=DEV)
+    B.cast_weight_scale_grad(ws, dev(gs), 2, gA)
+    ref = oracle.weight_scale_grad(w0, gs, 2)
+    terms = np.abs(gs.astype(np.float64) * w0).reshape(rows, 2, -1).sum(-1)
+    assert (np.abs(host(gA) - ref) <= 1e-5 * terms + 1e-30).all()
+    flips = torch.zeros(1, dtype=torch.int64, device=DEV)
+    l1 = torch.zeros(2, dtype=torch.float64, device=DEV)
+    B.cast_mask_stats(ws, mask, None, flips, l1)
+    torch.cuda.synchronize()
+    _, kept, total = oracle.mask_stats(w0, oracle.nm_select(w0, 1, 2))
+    assert np.allclose(host(l1), [kept, total], rtol=1e-12)
+    assert bool((ms == 7.0).all()) and bool((vs == -3.0).all()) and (host(ws) == w0).all()
