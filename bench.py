@@ -43,6 +43,9 @@ class Model:
         self.shapes = synth.weight_set(workload, layers)
         self.params = synth.set_params(self.shapes)
         self.t = []
+        self.list = None
+        self.row_splits = 1
+        self.launches = len(self.shapes)
         for i, (_, r, c) in enumerate(self.shapes):
             w = synth.device_gaussian((r, c), 0.02, torch.float32, 1000 + i, dev)
             g = synth.device_gaussian((r, c), 1e-3, torch.bfloat16, 500000 + i, dev)
@@ -57,12 +60,26 @@ class Model:
                                A=torch.ones((r, SEGMENTS), device=dev),
                                gA=torch.zeros((r, SEGMENTS), device=dev)))
 
+    def tensor_list(self, B, scaled: bool, dev):
+        """Descriptors for the one-call-per-step entry point, marshalled once."""
+        self.list = B.TensorList([dict(w=x["w"], grad=x["g"], m=x["m"], v=x["v"], mask=x["mask"],
+                                       scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None)
+                                  for x in self.t], dev)
+        self.launches = len({(x["w"].shape, x["w"].stride(0)) for x in self.t})   # one launch per distinct shape
+
     def step(self, B, t: int, scaled: bool):
         cfg = B.iteration_config(t, TOTAL_STEPS, mask_period=MASK_PERIOD, lr=LR, lambda_=LAMBDA,
                                  scale_segments=SEGMENTS if scaled else 0)
-        for x in self.t:
-            B.cast_adams_step(x["w"], x["g"], x["m"], x["v"], x["mask"], cfg,
-                              scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None)
+        if self.list is not None:
+            B.cast_adams_step_multi(self.list, cfg)
+        else:
+            k = self.row_splits
+            for x in self.t:
+                rows = x["w"].shape[0]
+                for i in range(k):      # k > 1: each matrix goes out as k launches over row blocks (experiment)
+                    a, b = rows * i // k, rows * (i + 1) // k
+                    B.cast_adams_step(x["w"][a:b], x["g"][a:b], x["m"][a:b], x["v"][a:b], x["mask"][a:b], cfg,
+                                      scale=x["A"][a:b] if scaled else None, scale_grad=x["gA"][a:b] if scaled else None)
         return cfg.refresh_mask
 
 
@@ -112,6 +129,9 @@ def main():
     ap.add_argument("--no-scale", action="store_true", help="time the step without weight scaling")
     ap.add_argument("--layout", default="interleaved", choices=["interleaved", "separate"],
                     help="w, mu, v of each matrix row-interleaved in one buffer (default) or three dense arrays")
+    ap.add_argument("--launch", default="list", choices=["list", "per-matrix"],
+                    help="one cast_adams_step_multi call per step (default) or one cast_adams_step call per matrix")
+    ap.add_argument("--row-splits", type=int, default=1, help="per-matrix launch only: launches per matrix (experiment)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     args = ap.parse_args()
@@ -130,6 +150,9 @@ def main():
 
     t0 = time.time()
     model = Model(args.workload, args.layers, torch, B, synth, dev, args.layout == "interleaved")
+    model.row_splits = args.row_splits
+    if args.launch == "list":
+        model.tensor_list(B, scaled, dev)
     torch.cuda.synchronize()
     log(f"[bench] {args.workload}: {len(model.shapes)} matrices, {model.params} params resident "
         f"({torch.cuda.memory_allocated() / 2**30:.1f} GiB) after {time.time() - t0:.1f} s")
@@ -158,8 +181,9 @@ def main():
     log(f"[bench] {ms_per_step:.3f} ms/step, {value:.1f} Gparams/s; non-refresh {sum(plain) / max(len(plain), 1):.3f} ms, "
         f"refresh {sum(fresh) / max(len(fresh), 1):.3f} ms")
 
-    # dominant kernel: the non-refresh fused step (9 of 10 steps); one launch per matrix
-    launches = len(model.shapes)
+    # dominant kernel: the non-refresh fused step (9 of 10 steps); one launch per matrix, or per distinct
+    # shape with the list call
+    launches = model.launches
     dom_ms = (sum(plain) / len(plain)) if plain else ms_per_step
     bytes_per_launch = BYTES_PER_PARAM * model.params / launches
     achieved = bytes_per_launch / (dom_ms * 1e-3 / launches) / 1e9
@@ -207,7 +231,8 @@ def main():
            "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{args.workload} linear weight set ({len(model.shapes)} matrices, {model.params} params), "
                                   f"2:4, fp32 w/mu/v ({args.layout}) + bf16 grads + mask bits resident, "
-                                  f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step",
+                                  f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step, "
+                                  f"{'one list call' if args.launch == 'list' else 'one call per matrix'} per step",
                       "n_keep": 2, "m_group": 4, "scale_segments": SEGMENTS if scaled else 0,
                       "pct_of_peak_hbm": round(100 * BYTES_PER_PARAM * value / HBM_PEAK_GBS, 2)},
            "roofline": roofline, "extra": extra}

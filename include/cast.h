@@ -115,6 +115,33 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
                             int64_t ld, const cast_adams_config *cfg /* HOST */, void *stream);
 
 /*
+ * The same iteration over a list of matrices that share one configuration (all linear weights
+ * of a model in one call).  Matrices of equal shape are stepped by one launch, which removes the
+ * launch-to-launch bubbles of hundreds of small launches; results are identical to calling
+ * cast_adams_step on each matrix.
+ *   tensors    HOST in   `count` descriptors; the device buffers they name follow the rules of
+ *                        cast_adams_step (scale / scale_grad NULL or not for all alike, per cfg)
+ *   workspace  DEVICE    at least cast_adams_multi_workspace_bytes(count) bytes, 16-byte aligned,
+ *                        owned by the caller; it is overwritten by every call and read by the
+ *                        kernels of that call, so it must not be shared between streams
+ */
+typedef struct {
+    float *w;
+    const void *grad;
+    float *m;
+    float *v;
+    uint32_t *mask_bits;
+    const float *scale;
+    float *scale_grad;
+    int64_t rows, cols, ld;
+} cast_tensor;
+
+size_t cast_adams_multi_workspace_bytes(int count);
+
+cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Weight scaling forward / fold, Eq. 12 (Eq. 11 when n_segments == 1):
  *   out[r, c] = scale[r, c / (cols / n_segments)] * w[r, c]      (one fp32 multiply)
  *   w DEVICE in fp32 [rows, cols], row stride ld; scale DEVICE in fp32 [rows, n_segments];

@@ -11,20 +11,26 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcast.so")
+LIB_PATH = os.environ.get("CAST_LIBRARY") or os.path.join(_HERE, "libcast.so")   # override: A/B experiments only
 
 CAST_F32, CAST_BF16 = 0, 1
 FLAG_V_FROM_GRAD = 1
 
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
-           "cast_debug_div_by_uniform"]
+           "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi"]
 
 
 class CastError(RuntimeError):
     def __init__(self, status: int, what: str):
         super().__init__(f"{what}: status {status} ({status_str(status)})")
         self.status = status
+
+
+class _Tensor(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
+                ("mask_bits", C.c_void_p), ("scale", C.c_void_p), ("scale_grad", C.c_void_p),
+                ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64)]
 
 
 class _Config(C.Structure):
@@ -82,8 +88,11 @@ def load():
     L.cast_mask_stats.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp]
     L.cast_hbm_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
     L.cast_debug_div_by_uniform.argtypes = [vp, C.c_float, vp, i64]
+    L.cast_adams_multi_workspace_bytes.argtypes = [ci]
+    L.cast_adams_multi_workspace_bytes.restype = C.c_size_t
+    L.cast_adams_step_multi.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp, C.c_size_t, vp]
     for name in EXPORTS:
-        if name != "cast_status_str":
+        if name not in ("cast_status_str", "cast_adams_multi_workspace_bytes"):
             getattr(L, name).restype = C.c_int32
     _lib = L
     return L
@@ -124,7 +133,11 @@ def _dev(*tensors):
 def _ld(w, *same):
     """Row stride of a [rows, cols] weight/moment tensor whose rows are contiguous; dense tensors
     give ld == cols, row-interleaved state (see interleaved_state) gives ld == 3 * cols."""
-    if not w.is_cuda or w.dim() != 2 or (w.shape[1] > 1 and w.stride(1) != 1):
+    if not w.is_cuda or w.dim() != 2:
+        raise ValueError("w, m, v must be 2-D GPU tensors with contiguous rows")
+    if w.numel() == 0:
+        return w.shape[1]
+    if w.shape[1] > 1 and w.stride(1) != 1:
         raise ValueError("w, m, v must be 2-D GPU tensors with contiguous rows")
     ld = w.stride(0) if w.shape[0] > 1 else max(w.stride(0), w.shape[1])
     for t in same:
@@ -167,6 +180,43 @@ def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scal
     cs = cfg.c_struct()
     _check(load().cast_adams_step(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
                                   rows, cols, _ld(w, m, v), C.byref(cs), _stream(stream)), "cast_adams_step")
+
+
+def cast_adams_multi_workspace_bytes(count: int) -> int:
+    return load().cast_adams_multi_workspace_bytes(count)
+
+
+class TensorList:
+    """The descriptors of a list of matrices for cast_adams_step_multi, marshalled once, plus the
+    device workspace the call needs.  Each item is a dict with w, grad, m, v, mask and optionally
+    scale, scale_grad (tensors)."""
+
+    def __init__(self, items, device="cuda:0"):
+        self.items = list(items)     # keeps the tensors alive
+        n = len(self.items)
+        self.array = (_Tensor * max(n, 1))()
+        self.grad_dtype = None
+        for k, x in enumerate(self.items):
+            w, m, v = x["w"], x["m"], x["v"]
+            _dev(x["grad"], x["mask"], x.get("scale"), x.get("scale_grad"))
+            dt = _dtype_code(x["grad"])
+            if self.grad_dtype not in (None, dt):
+                raise ValueError("all gradients of a list must have one dtype")
+            self.grad_dtype = dt
+            sc, sg = x.get("scale"), x.get("scale_grad")
+            self.array[k] = _Tensor(w.data_ptr(), x["grad"].data_ptr(), m.data_ptr(), v.data_ptr(), x["mask"].data_ptr(),
+                                    None if sc is None else sc.data_ptr(), None if sg is None else sg.data_ptr(),
+                                    w.shape[0], w.shape[1], _ld(w, m, v))
+        self.count = n
+        self.workspace = torch.empty(max(cast_adams_multi_workspace_bytes(n), 16), dtype=torch.uint8, device=device)
+
+
+def cast_adams_step_multi(tensors: TensorList, cfg: AdamsConfig, stream=None):
+    if tensors.count:
+        cfg.grad_dtype = tensors.grad_dtype
+    cs = cfg.c_struct()
+    _check(load().cast_adams_step_multi(tensors.array, tensors.count, C.byref(cs), _ptr(tensors.workspace),
+                                        tensors.workspace.numel(), _stream(stream)), "cast_adams_step_multi")
 
 
 def cast_weight_scale(w, scale, out, stream=None):

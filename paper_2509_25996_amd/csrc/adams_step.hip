@@ -6,6 +6,8 @@
 // nothing is read twice.  There is no contraction, so no MFMA; the kernel is bound by HBM.
 #include <stdlib.h>
 
+#include <vector>
+
 #include "cast_device.h"
 #include "cast_internal.h"
 
@@ -13,7 +15,9 @@
 
 namespace cast {
 
-struct SpanArgs {
+// The buffers of one matrix.  A launch either carries one set in its arguments or, for a list of
+// equally shaped matrices, reads the set of matrix blockIdx.y from a table in device memory.
+struct TensorPtrs {
     float *w;
     const void *grad;
     float *m;
@@ -21,6 +25,12 @@ struct SpanArgs {
     uint32_t *mask;
     const float *scale;
     float *scale_grad;
+    uint64_t pad;         // 64 bytes per entry
+};
+
+struct SpanArgs {
+    TensorPtrs one;
+    const TensorPtrs *table;   // NULL: use `one`
     SpanGeom geom;
     StepScalars s;
 };
@@ -72,31 +82,42 @@ __device__ __forceinline__ vu4_t pack4(const float (&f)[4])
 // end of the span carry zeros through the arithmetic and the buffer range check voids their
 // stores, so the cross-lane steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly)
 // always see all 64 lanes.
+// `matrix` selects the buffer set (entry of the table of a list call), `block` the workgroup's
+// share of that matrix: block_waves / waves_per_span consecutive spans.
 template <int M, bool BF16, bool REFRESH, bool SCALED>
-__global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
+__device__ __forceinline__ void step_block_task(const SpanArgs &a, uint32_t matrix, int64_t block, float *partial)
 {
-    __shared__ float partial[kMaxBlockWaves];
+    // The buffer set of this launch, or of one matrix of a list.  The table is read through the
+    // constant address space so that the (wave-uniform) loads are scalar loads and the pointers
+    // arrive in scalar registers, where buffer resources have to live.
+    TensorPtrs t = a.one;
+    if (a.table) {
+        typedef const TensorPtrs __attribute__((address_space(4))) ConstTensorPtrs;
+        const ConstTensorPtrs *e = (const ConstTensorPtrs *)(uintptr_t)a.table + matrix;
+        t.w = e->w; t.grad = e->grad; t.m = e->m; t.v = e->v;
+        t.mask = e->mask; t.scale = e->scale; t.scale_grad = e->scale_grad;
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
     const int P = a.geom.waves_per_span;
     const int block_waves = blockDim.x / kWave;
-    const int64_t span = (int64_t)blockIdx.x * (block_waves / P) + wave / P;
+    const int64_t span = block * (block_waves / P) + wave / P;
     const int sub = wave % P;
     const SpanOrigin o = span_origin(a.geom, span);
     const bool live_span = o.len > 0;
     const int len = o.len;
 
     SpanBuffers b;
-    b.w = span_resource(a.w + o.state_begin, len * 4);
-    b.m = span_resource(a.m + o.state_begin, len * 4);
-    b.v = span_resource(a.v + o.state_begin, len * 4);
-    if constexpr (BF16) b.g = span_resource(static_cast<const uint16_t *>(a.grad) + o.dense_begin, len * 2);
-    else b.g = span_resource(static_cast<const float *>(a.grad) + o.dense_begin, len * 4);
-    b.mask = span_resource(a.mask + (o.dense_begin >> 5), len / 8);    // spans start and end on mask words
+    b.w = span_resource(t.w + o.state_begin, len * 4);
+    b.m = span_resource(t.m + o.state_begin, len * 4);
+    b.v = span_resource(t.v + o.state_begin, len * 4);
+    if constexpr (BF16) b.g = span_resource(static_cast<const uint16_t *>(t.grad) + o.dense_begin, len * 2);
+    else b.g = span_resource(static_cast<const float *>(t.grad) + o.dense_begin, len * 4);
+    b.mask = span_resource(t.mask + (o.dense_begin >> 5), len / 8);    // spans start and end on mask words
 
     float A = 1.0f;
-    if constexpr (SCALED) { if (live_span) A = a.scale[span]; }
-    const bool want_gA = SCALED && a.scale_grad != nullptr;
+    if constexpr (SCALED) { if (live_span) A = t.scale[span]; }
+    const bool want_gA = SCALED && t.scale_grad != nullptr;
     float acc = 0.0f;
 
     const int stride = P * kChunk;
@@ -104,7 +125,12 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     Chunk<BF16> cur, nxt;
     chunk_load<BF16, REFRESH>(cur, b, off);
     for (int base = sub * kChunk; base < len; base += stride) {
-        chunk_load<BF16, REFRESH>(nxt, b, off + stride);        // past the end: all zeros, never used
+#ifdef CAST_EXPERIMENT_ALWAYS_PREFETCH
+        const bool more = true;
+#else
+        const bool more = base + stride < len;                  // wave-uniform
+#endif
+        if (more) chunk_load<BF16, REFRESH>(nxt, b, off + stride);
 
         float w[4], g[4], mu[4], v[4];
         unpack4(cur.w, w);
@@ -135,6 +161,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
         __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
 
+        if (!more || base + stride >= len) break;
         cur = nxt;
         off += stride;
     }
@@ -143,17 +170,49 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
         if (want_gA) {   // uniform over the workgroup
             const float wave_total = wave_sum_fixed_order(acc);
             if (P == 1) {
-                if (lane == 0 && live_span) a.scale_grad[span] = wave_total;
+                if (lane == 0 && live_span) t.scale_grad[span] = wave_total;
             } else {
                 if (lane == 0) partial[wave] = wave_total;
                 __syncthreads();
                 if (lane == 0 && sub == 0 && live_span) {
-                    float t = partial[wave];
-                    for (int p = 1; p < P; ++p) t = t + partial[wave + p];
-                    a.scale_grad[span] = t;
+                    float sum = partial[wave];
+                    for (int p = 1; p < P; ++p) sum = sum + partial[wave + p];
+                    t.scale_grad[span] = sum;
                 }
             }
         }
+    }
+}
+
+// One workgroup per share, dealt by the hardware dispatcher: grid = (shares per matrix, matrices).
+template <int M, bool BF16, bool REFRESH, bool SCALED>
+__global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
+{
+    __shared__ float partial[kMaxBlockWaves];
+    step_block_task<M, BF16, REFRESH, SCALED>(a, blockIdx.y, blockIdx.x, partial);
+}
+
+// Work queue: a fixed set of resident workgroups draws shares, in order, from a ticket counter in
+// device memory (zero at launch).  Whatever the relative speed of the compute units and of the 8
+// XCDs, the shares in flight are always the most recently drawn ones, so every array is walked
+// front to back through one narrow, steadily advancing window, which is what HBM serves fastest;
+// there are no wavefront launches after the first.  Every workgroup leaves when it draws a ticket
+// past the end: exactly tasks + gridDim.x tickets are drawn per launch and nobody waits for anybody.
+template <int M, bool BF16, bool REFRESH, bool SCALED>
+__global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const SpanArgs a, unsigned long long *ticket_counter,
+                                                                         unsigned long long tasks, FastDivU32 div_blocks_per_matrix,
+                                                                         uint32_t blocks_per_matrix)
+{
+    __shared__ float partial[kMaxBlockWaves];
+    __shared__ unsigned long long drawn[2];
+    for (int it = 0;; ++it) {
+        if (threadIdx.x == 0) drawn[it & 1] = atomicAdd(ticket_counter, 1ull);
+        __syncthreads();   // also separates this round's use of `partial` from the last one's
+        const unsigned long long ticket = drawn[it & 1];
+        if (ticket >= tasks) return;
+        const uint32_t task = __builtin_amdgcn_readfirstlane((uint32_t)ticket);
+        const uint32_t matrix = fast_div(task, div_blocks_per_matrix);
+        step_block_task<M, BF16, REFRESH, SCALED>(a, matrix, (int64_t)(task - matrix * blocks_per_matrix), partial);
     }
 }
 
@@ -361,30 +420,59 @@ static StepScalars make_scalars(const cast_adams_config *cfg)
     s.alpha_lambda = cfg->alpha * cfg->lambda;
     s.bias_corr1 = make_divisor(cfg->bias_corr1);
     s.bias_corr2 = make_divisor(cfg->bias_corr2);
+    s.decay_pos = s.alpha_lambda * 1.0f;
+    s.decay_neg = s.alpha_lambda * -1.0f;
+    s.decay_zero = s.alpha_lambda * 0.0f;       // keeps the sign a product with +0 has
     s.n_keep = cfg->n_keep;
     s.v_from_grad = (cfg->flags & CAST_FLAG_V_FROM_GRAD) ? 1 : 0;
+    // the short forms need both bias corrections in [2^-12, 2] and a small non-negative epsilon
+    s.short_forms = (s.bias_corr1.fast && s.bias_corr2.fast && cfg->eps >= 0.0f && cfg->eps <= 0x1p20f) ? 1 : 0;
     return s;
 }
 
-template <int M, bool BF16, bool REFRESH>
-static void launch_vec_scaled(bool scaled, const SpanPlan &p, const SpanArgs &a, hipStream_t st)
+// how a vector launch is issued: by the dispatcher (tickets == nullptr) or as a work queue
+struct VecLaunch {
+    unsigned grid_x, grid_y;
+    int block_threads;
+    unsigned long long *tickets;
+    unsigned long long tasks;
+    uint32_t blocks_per_matrix;
+};
+
+template <int M, bool BF16, bool REFRESH, bool SCALED>
+static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
-    if (scaled) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true>), dim3(p.grid), dim3(p.block_threads), 0, st, a);
-    else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, false>), dim3(p.grid), dim3(p.block_threads), 0, st, a);
+    if (l.tickets)
+        hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), dim3(l.block_threads), 0, st, a,
+                           l.tickets, l.tasks, make_fast_div(l.blocks_per_matrix), l.blocks_per_matrix);
+    else {
+        // experiment knob: cap the resident wavefronts per compute unit by reserving LDS per workgroup
+        static const int cap = env_int("CAST_STATIC_WAVES_PER_CU", 0);
+        unsigned lds = 0;
+        if (cap > 0) {
+            int blocks = cap / (l.block_threads / kWave);
+            if (blocks < 1) blocks = 1;
+            lds = (unsigned)(160 * 1024 / blocks) - 1024;
+        }
+        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), dim3(l.grid_x, l.grid_y), dim3(l.block_threads), lds, st, a);
+    }
 }
 
 template <int M, bool BF16>
-static void launch_vec_refresh(bool refresh, bool scaled, const SpanPlan &p, const SpanArgs &a, hipStream_t st)
+static void launch_vec_flags(bool refresh, bool scaled, const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
-    if (refresh) launch_vec_scaled<M, BF16, true>(scaled, p, a, st);
-    else launch_vec_scaled<M, BF16, false>(scaled, p, a, st);
+    if (refresh) { if (scaled) launch_vec_kernel<M, BF16, true, true>(l, a, st); else launch_vec_kernel<M, BF16, true, false>(l, a, st); }
+    else { if (scaled) launch_vec_kernel<M, BF16, false, true>(l, a, st); else launch_vec_kernel<M, BF16, false, false>(l, a, st); }
 }
 
-template <int M>
-static void launch_vec_dtype(bool bf16, bool refresh, bool scaled, const SpanPlan &p, const SpanArgs &a, hipStream_t st)
+static void launch_vec_any(int m_group, bool bf16, bool refresh, bool scaled, const VecLaunch &l, const SpanArgs &a,
+                           hipStream_t st)
 {
-    if (bf16) launch_vec_refresh<M, true>(refresh, scaled, p, a, st);
-    else launch_vec_refresh<M, false>(refresh, scaled, p, a, st);
+    switch (m_group) {
+    case 2: if (bf16) launch_vec_flags<2, true>(refresh, scaled, l, a, st); else launch_vec_flags<2, false>(refresh, scaled, l, a, st); break;
+    case 4: if (bf16) launch_vec_flags<4, true>(refresh, scaled, l, a, st); else launch_vec_flags<4, false>(refresh, scaled, l, a, st); break;
+    default: if (bf16) launch_vec_flags<8, true>(refresh, scaled, l, a, st); else launch_vec_flags<8, false>(refresh, scaled, l, a, st); break;
+    }
 }
 
 template <int M>
@@ -421,12 +509,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = scale != nullptr;
     if (p.vec) {
-        SpanArgs a{w, grad, m, v, mask_bits, scale, scale_grad, p.geom, make_scalars(cfg)};
-        switch (cfg->m_group) {
-        case 2: launch_vec_dtype<2>(bf16, refresh, scaled, p, a, st); break;
-        case 4: launch_vec_dtype<4>(bf16, refresh, scaled, p, a, st); break;
-        default: launch_vec_dtype<8>(bf16, refresh, scaled, p, a, st); break;
-        }
+        SpanArgs a{{w, grad, m, v, mask_bits, scale, scale_grad, 0}, nullptr, p.geom, make_scalars(cfg)};
+        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0}, a, st);
         return launch_status();
     }
     // odd shapes: dL/dA first (it needs the incoming weights), then the element pass
@@ -443,6 +527,93 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     default: launch_unit_dtype<8>(bf16, grid, a, st); break;
     }
     return launch_status();
+}
+
+// workspace of a list call: the table of buffer sets, then one ticket counter per launch
+size_t multi_workspace_bytes(int count)
+{
+    const size_t n = (size_t)(count > 0 ? count : 0);
+    return n * sizeof(TensorPtrs) + ((n * sizeof(unsigned long long) + 15) & ~(size_t)15);
+}
+
+static int device_compute_units()
+{
+    static int cus = 0;      // of the device current at the first call
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
+        else cus = 256;
+    }
+    return cus;
+}
+
+// A list of matrices that share one configuration.  Matrices of equal (rows, cols, ld) form one
+// launch: a work queue (see adams_step_vec_queue) over all their shares, with their buffer
+// addresses in a table that is copied, together with zeroed ticket counters, to the workspace
+// first.  Shapes the vector kernels do not take are stepped one by one.
+cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast_adams_config *cfg,
+                                    void *workspace, hipStream_t st)
+{
+    const bool bf16 = cfg->grad_dtype == CAST_BF16;
+    const bool refresh = cfg->refresh_mask != 0;
+    const bool scaled = cfg->scale_segments > 0;
+    // tuning knobs (read once): resident wavefronts per compute unit of the work queue; 0 = no queue
+    static const int waves_per_cu = env_int("CAST_QUEUE_WAVES_PER_CU", 16);
+    std::vector<int> order;           // indices of vector-path matrices, grouped by shape
+    std::vector<char> taken(count, 0);
+    struct Group { int first, n; SpanPlan plan; };
+    std::vector<Group> groups;
+    for (int i = 0; i < count; ++i) {
+        if (taken[i] || ts[i].rows == 0 || ts[i].cols == 0) continue;
+        const SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments);
+        if (!p.vec) continue;
+        Group g{(int)order.size(), 0, p};
+        // tickets are 32-bit task numbers inside the kernel
+        const int fit = (int)(((int64_t)1 << 31) / p.grid);
+        for (int j = i; j < count && g.n < fit && g.n < 65535; ++j)
+            if (!taken[j] && ts[j].rows == ts[i].rows && ts[j].cols == ts[i].cols && ts[j].ld == ts[i].ld) {
+                taken[j] = 1;
+                order.push_back(j);
+                ++g.n;
+            }
+        groups.push_back(g);
+    }
+    if (!order.empty()) {
+        const size_t table_bytes = (size_t)count * sizeof(TensorPtrs);
+        std::vector<unsigned char> image(table_bytes + groups.size() * sizeof(unsigned long long), 0);
+        TensorPtrs *table = reinterpret_cast<TensorPtrs *>(image.data());
+        for (size_t k = 0; k < order.size(); ++k) {
+            const cast_tensor &t = ts[order[k]];
+            table[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, 0};
+        }
+        // pageable source: the runtime stages it before returning, the copy itself is ordered on the stream
+        if (hipMemcpyAsync(workspace, image.data(), image.size(), hipMemcpyHostToDevice, st) != hipSuccess)
+            return CAST_ERR_LAUNCH;
+        unsigned long long *counters = reinterpret_cast<unsigned long long *>(static_cast<char *>(workspace) + table_bytes);
+        const StepScalars sc = make_scalars(cfg);
+        for (size_t gi = 0; gi < groups.size(); ++gi) {
+            const Group &g = groups[gi];
+            SpanArgs a{{}, static_cast<const TensorPtrs *>(workspace) + g.first, g.plan.geom, sc};
+            VecLaunch l{g.plan.grid, (unsigned)g.n, g.plan.block_threads, nullptr, 0, 0};
+            if (waves_per_cu > 0) {
+                const unsigned long long tasks = (unsigned long long)g.plan.grid * (unsigned)g.n;
+                int blocks_per_cu = waves_per_cu / (g.plan.block_threads / kWave);
+                if (blocks_per_cu < 1) blocks_per_cu = 1;
+                unsigned long long resident = (unsigned long long)device_compute_units() * blocks_per_cu;
+                if (resident > tasks) resident = tasks;
+                l = VecLaunch{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid};
+            }
+            launch_vec_any(cfg->m_group, bf16, refresh, scaled, l, a, st);
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+        }
+    }
+    for (int i = 0; i < count; ++i) {
+        if (taken[i]) continue;
+        const cast_tensor &t = ts[i];
+        cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg, st);
+        if (rc != CAST_OK) return rc;
+    }
+    return CAST_OK;
 }
 
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n)

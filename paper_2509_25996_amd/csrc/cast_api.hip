@@ -91,9 +91,10 @@ cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t l
     return launch_nm_select(w, rows, cols, ld, n_keep, m_group, mask_bits, static_cast<hipStream_t>(stream));
 }
 
-cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
-                            const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                            int64_t ld, const cast_adams_config *cfg, void *stream)
+// everything cast_adams_step checks before launching
+static cast_status validate_step(const float *w, const void *grad, const float *m, const float *v,
+                                 const uint32_t *mask_bits, const float *scale, const float *scale_grad,
+                                 int64_t rows, int64_t cols, int64_t ld, const cast_adams_config *cfg)
 {
     if (!cfg) return CAST_ERR_NULL;
     cast_status rc = check_nm(cfg->n_keep, cfg->m_group);
@@ -103,6 +104,11 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
     if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (!dtype_ok(cfg->grad_dtype)) return CAST_ERR_DTYPE;
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
+    if (cfg->flags & ~CAST_FLAG_V_FROM_GRAD) return CAST_ERR_CONFIG;
+    // the bias corrections divide: they must be positive finite numbers (1 - beta^s with s >= 1)
+    if (!(cfg->bias_corr1 > 0.0f) || !(cfg->bias_corr2 > 0.0f) || isinf(cfg->bias_corr1) || isinf(cfg->bias_corr2))
+        return CAST_ERR_CONFIG;
+    if (rows == 0 || cols == 0) return CAST_OK;      // nothing to do: buffers may be NULL
     if ((cfg->scale_segments > 0) != (scale != nullptr)) return scale ? CAST_ERR_SHAPE : CAST_ERR_NULL;
     if (scale_grad && !scale) return CAST_ERR_NULL;
     if (cfg->scale_segments > 0 && cols > 0) {
@@ -110,16 +116,39 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
         if (rc != CAST_OK) return rc;
         if (too_many_segments(rows, cfg->scale_segments)) return CAST_ERR_SHAPE;
     }
-    if (cfg->flags & ~CAST_FLAG_V_FROM_GRAD) return CAST_ERR_CONFIG;
-    // the bias corrections divide: they must be positive finite numbers (1 - beta^s with s >= 1)
-    if (!(cfg->bias_corr1 > 0.0f) || !(cfg->bias_corr2 > 0.0f) || isinf(cfg->bias_corr1) || isinf(cfg->bias_corr2))
-        return CAST_ERR_CONFIG;
-    if (rows == 0 || cols == 0) return CAST_OK;
     if (!w || !grad || !m || !v || !mask_bits) return CAST_ERR_NULL;
     if (!aligned(w, 16) || !aligned(m, 16) || !aligned(v, 16) || !aligned(grad, dtype_align(cfg->grad_dtype)) ||
         !aligned(mask_bits, 4) || !aligned(scale, 4) || !aligned(scale_grad, 4))
         return CAST_ERR_ALIGN;
+    return CAST_OK;
+}
+
+cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
+                            const float *scale, float *scale_grad, int64_t rows, int64_t cols,
+                            int64_t ld, const cast_adams_config *cfg, void *stream)
+{
+    const cast_status rc = validate_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg);
+    if (rc != CAST_OK) return rc;
     return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, static_cast<hipStream_t>(stream));
+}
+
+size_t cast_adams_multi_workspace_bytes(int count) { return multi_workspace_bytes(count); }
+
+cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
+                                  void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (!cfg) return CAST_ERR_NULL;
+    if (count == 0) return CAST_OK;
+    if (!tensors || !workspace) return CAST_ERR_NULL;
+    if (!aligned(workspace, 16)) return CAST_ERR_ALIGN;
+    if (workspace_bytes < multi_workspace_bytes(count)) return CAST_ERR_SHAPE;
+    for (int i = 0; i < count; ++i) {    // all or nothing: nothing is launched if any matrix is rejected
+        const cast_tensor &t = tensors[i];
+        const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg);
+        if (rc != CAST_OK) return rc;
+    }
+    return launch_adams_step_multi(tensors, count, cfg, workspace, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,

@@ -100,6 +100,16 @@ __device__ __forceinline__ uint32_t dpp_u32(uint32_t x)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
 }
 
+// A pointer that is the same in every lane, moved to scalar registers.
+template <typename T>
+__device__ __forceinline__ T *uniform_ptr(T *p)
+{
+    const uint64_t x = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
+    return reinterpret_cast<T *>(((uint64_t)hi << 32) | lo);
+}
+
 // OR of a value over each aligned run of 8 lanes; every lane of the run gets the result.
 __device__ __forceinline__ uint32_t or_reduce_8lanes(uint32_t x)
 {
@@ -282,9 +292,11 @@ __host__ __device__ __forceinline__ float div_by_uniform(float x, const UniformD
 struct StepScalars {
     float lr, beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
     float one_minus_alpha, alpha_lambda;
+    float decay_pos, decay_neg, decay_zero;   // alpha_lambda * Sign(w) for w > 0, w < 0, otherwise
     UniformDivisor bias_corr1, bias_corr2;
     int n_keep;
     int v_from_grad;
+    int short_forms;       // 1 if the uniform scalars allow the short division / square-root forms
 };
 
 // Every line below is one correctly rounded fp32 operation: the library is compiled with
@@ -298,12 +310,13 @@ __device__ __forceinline__ void adams_moments(float w, float g, float &mu, float
     const float t0 = s.beta1 * mu;
     const float t1 = s.one_minus_beta1 * g;
     const float mu_t = t0 + t1;                                   // Eq. 8, first line
-    const float sgn = (float)(w > 0.0f) - (float)(w < 0.0f);      // Sign(+-0) = Sign(NaN) = 0
+    // alpha*lambda*Sign(w) with Sign(+-0) = Sign(NaN) = 0: the three possible products come from the host
+    const float d1 = w > 0.0f ? s.decay_pos : (w < 0.0f ? s.decay_neg : s.decay_zero);
     const float d0 = s.one_minus_alpha * mu_t;
-    const float d1 = s.alpha_lambda * sgn;
     const float decayed = d0 + d1;                                // Eq. 7 on the momentum
     mu_tilde = keep ? mu_t : decayed;                             // Algorithm 1: only where m = 0
-    const float second = s.v_from_grad ? g * g : mu_tilde * mu_tilde;
+    const float squared = s.v_from_grad ? g : mu_tilde;
+    const float second = squared * squared;
     const float s0 = s.beta2 * v;
     const float s1 = s.one_minus_beta2 * second;
     v_t = s0 + s1;                                                // v from the decayed momentum
@@ -329,34 +342,83 @@ __device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float 
     v = v_t;
 }
 
-// The 4 entries of a lane.  The choice between the short and the IEEE form of the two
-// bias-correction divisions is taken once per wavefront (a scalar branch): the short form if
-// every live lane's 8 dividends are in its range.  `live` is false for lanes past the end of
-// the span, whose zeros must not force the long form.
+// Correctly rounded square root of a normal number well inside the exponent range: the hardware
+// approximation is within one unit in the last place, so the answer is that value or one of its
+// two neighbours; exact FMA residuals against the neighbours decide (the range and special-value
+// handling a general sqrtf needs is left out).
+__device__ __forceinline__ float sqrt_short(float x)
+{
+    const float s = __builtin_amdgcn_sqrtf(x);
+    const float s_dn = __uint_as_float(__float_as_uint(s) - 1u);
+    const float s_up = __uint_as_float(__float_as_uint(s) + 1u);
+    const float r_dn = __builtin_fmaf(-s_dn, s, x);               // x - s_dn * s
+    const float r_up = __builtin_fmaf(-s_up, s, x);               // x - s_up * s
+    float y = r_dn <= 0.0f ? s_dn : s;
+    y = r_up > 0.0f ? s_up : y;
+    return y;
+}
+
+// Correctly rounded x / d for operands well inside the exponent range: the refinement sequence
+// of the IEEE division without its range scaling and special-value fix-up.
+__device__ __forceinline__ float div_short_any(float x, float d)
+{
+    const float r0 = __builtin_amdgcn_rcpf(d);
+    const float e = __builtin_fmaf(-d, r0, 1.0f);
+    const float r = __builtin_fmaf(e, r0, r0);
+    const float q0 = x * r;
+    const float e0 = __builtin_fmaf(-d, q0, x);
+    const float q1 = __builtin_fmaf(e0, r, q0);
+    const float e1 = __builtin_fmaf(-d, q1, x);
+    return __builtin_fmaf(e1, r, q1);
+}
+
+// The 4 entries of a lane.  The division by the bias corrections, the square root and the
+// final division each have a short form that gives the same correctly rounded result when
+// every operand is a normal number far from the ends of the exponent range.  Whether that holds
+// is decided once per wavefront (a scalar branch) from the smallest and the largest magnitude
+// among the 8 dividends of the live lanes: 2^-63 <= |mu~|, v < 2^66 (so zeros, denormals, inf
+// take the long forms; a NaN goes through either form as a NaN).  `live` is false for lanes
+// past the end of the span, whose zeros must not force the long forms.
 __device__ __forceinline__ void adams_entries4(float (&w)[4], const float (&g)[4], float (&mu)[4],
                                                float (&v)[4], uint32_t nib, bool live,
                                                const StepScalars &s)
 {
     float mt[4], vt[4];
-    bool out_of_range = false;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        adams_moments(w[j], g[j], mu[j], v[j], (nib >> j) & 1u, s, mt[j], vt[j]);
-        out_of_range = out_of_range || !in_short_division_range(mt[j]) || !in_short_division_range(vt[j]);
-    }
-    float mh[4], vh[4];
-    const bool short_ok = s.bias_corr1.fast && s.bias_corr2.fast;
-    if (short_ok && !__any(out_of_range && live)) {
+    for (int j = 0; j < 4; ++j) adams_moments(w[j], g[j], mu[j], v[j], (nib >> j) & 1u, s, mt[j], vt[j]);
+    float lo = __builtin_fminf(__builtin_fabsf(mt[0]), __builtin_fabsf(mt[1]));
+    float hi = __builtin_fmaxf(__builtin_fabsf(mt[0]), __builtin_fabsf(mt[1]));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { mh[j] = div_short(mt[j], s.bias_corr1); vh[j] = div_short(vt[j], s.bias_corr2); }
+    for (int j = 2; j < 4; ++j) { lo = __builtin_fminf(lo, __builtin_fabsf(mt[j])); hi = __builtin_fmaxf(hi, __builtin_fabsf(mt[j])); }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { lo = __builtin_fminf(lo, vt[j]); hi = __builtin_fmaxf(hi, vt[j]); }
+    const bool out_of_range = !(lo >= 0x1p-63f) || !(hi < 0x1p66f);
+#ifdef CAST_EXPERIMENT_OLD_SHORT
+    if (s.short_forms && !__any(out_of_range && live)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            w[j] = adams_update(w[j], div_short(mt[j], s.bias_corr1), div_short(vt[j], s.bias_corr2), s);
+            v[j] = vt[j];
+        }
+    } else
+#endif
+    if (s.short_forms && !__any(out_of_range && live)) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float mu_hat = div_short(mt[j], s.bias_corr1);
+            const float v_hat = div_short(vt[j], s.bias_corr2);
+            const float denom = sqrt_short(v_hat) + s.eps;
+            const float q = div_short_any(mu_hat, denom);
+            const float step = s.lr * q;
+            w[j] = w[j] - step;
+            v[j] = vt[j];
+        }
     } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { mh[j] = mt[j] / s.bias_corr1.y; vh[j] = vt[j] / s.bias_corr2.y; }
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        w[j] = adams_update(w[j], mh[j], vh[j], s);
-        v[j] = vt[j];
+        for (int j = 0; j < 4; ++j) {
+            w[j] = adams_update(w[j], mt[j] / s.bias_corr1.y, vt[j] / s.bias_corr2.y, s);
+            v[j] = vt[j];
+        }
     }
 }
 

@@ -40,6 +40,9 @@ cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const u
                               int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
                               double *l1, hipStream_t stream);
 cast_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
+size_t multi_workspace_bytes(int count);
+cast_status launch_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
+                                    void *workspace, hipStream_t stream);
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
 
 inline cast_status launch_status()

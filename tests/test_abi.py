@@ -112,6 +112,19 @@ def test_validation_happens_before_any_launch(lib):
     assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 8, 2, 4, p, 0, p, st) == -2
     assert lib.cast_mask_stats(p, nul, nul, 4, 64, 64, p, p, st) == -1
     assert lib.cast_mask_stats(p, p, nul, 4, 64, 63, p, p, st) == -2
+    # list call: rejected as a whole if any matrix is bad, before anything is enqueued
+    T = B._Tensor
+    good = T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64)
+    bad = T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 66, 66)
+    arr = (T * 2)(good, bad)
+    cfg = _cfg()
+    assert lib.cast_adams_multi_workspace_bytes(2) == 144 and lib.cast_adams_multi_workspace_bytes(0) == 0
+    assert lib.cast_adams_step_multi(arr, 2, C.byref(cfg), p, 144, st) == -2
+    assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), p, 32, st) == -2       # workspace too small
+    assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), nul, 80, st) == -1
+    assert lib.cast_adams_step_multi(arr, 1, None, p, 80, st) == -1
+    assert lib.cast_adams_step_multi(arr, 0, C.byref(cfg), nul, 0, st) == 0
+    assert lib.cast_adams_step_multi(arr, -1, C.byref(cfg), p, 64, st) == -2
     assert lib.cast_hbm_copy_probe(p, p, 24, st) == -2
     assert lib.cast_hbm_copy_probe(p, odd, 32, st) == -3
     assert lib.cast_hbm_copy_probe(nul, nul, 0, st) == 0

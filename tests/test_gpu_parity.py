@@ -399,3 +399,37 @@ def test_strided_weights_in_every_entry_point(rows, cols):
     _, kept, total = oracle.mask_stats(w0, oracle.nm_select(w0, 1, 2))
     assert np.allclose(host(l1), [kept, total], rtol=1e-12)
     assert bool((ms == 7.0).all()) and bool((vs == -3.0).all()) and (host(ws) == w0).all()
+
+
+# --------------------------------------------------------------------------- list of matrices in one call
+@pytest.mark.parametrize("nseg", [0, 2])
+def test_multi_tensor_step_equals_single_steps(nseg):
+    shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (64, 512), (32, 1024), (3, 40), (0, 64), (16, 11008)]
+    rng = np.random.default_rng(9)
+
+    def make(interleaved):
+        items = []
+        for i, (r, c) in enumerate(shapes):
+            st = GpuState(synth.weights(8, i, r, c), nseg, interleaved=interleaved and r > 0)
+            st.m.copy_(dev(synth.grads_f32(8, i, 50, r, c) * 0.1))
+            st.v.copy_(dev(np.abs(synth.grads_f32(8, i, 51, r, c)) * 1e-3))
+            items.append(dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=synth.grads_bf16(8, i, 0, r, c).to(DEV),
+                              scale=dev((1 + 0.1 * rng.standard_normal((r, nseg))).astype(np.float32)) if nseg else None,
+                              scale_grad=st.scale_grad))
+        return items
+
+    for interleaved in (False, True):
+        rng = np.random.default_rng(9)
+        a = make(interleaved)
+        rng = np.random.default_rng(9)
+        b = make(interleaved)
+        tl = B.TensorList(b, DEV)
+        for t in range(3):
+            cfg = B.iteration_config(t, 4, mask_period=2, lr=1e-3, lambda_=1e-3, scale_segments=nseg)
+            for x in a:
+                B.cast_adams_step(x["w"], x["grad"], x["m"], x["v"], x["mask"], cfg, scale=x["scale"], scale_grad=x["scale_grad"])
+            B.cast_adams_step_multi(tl, cfg)
+        torch.cuda.synchronize()
+        for x, y in zip(a, b):
+            for k in ("w", "m", "v", "mask") + (("scale_grad",) if nseg else ()):
+                assert host(x[k]).tobytes() == host(y[k]).tobytes(), k
