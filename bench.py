@@ -45,6 +45,7 @@ class Model:
         self.t = []
         self.list = None
         self.row_splits = 1
+        self.flags = 0
         self.launches = len(self.shapes)
         for i, (_, r, c) in enumerate(self.shapes):
             w = synth.device_gaussian((r, c), 0.02, torch.float32, 1000 + i, dev)
@@ -60,16 +61,18 @@ class Model:
                                A=torch.ones((r, SEGMENTS), device=dev),
                                gA=torch.zeros((r, SEGMENTS), device=dev)))
 
-    def tensor_list(self, B, scaled: bool, dev):
+    def tensor_list(self, B, scaled: bool, dev, queue: bool):
         """Descriptors for the one-call-per-step entry point, marshalled once."""
         self.list = B.TensorList([dict(w=x["w"], grad=x["g"], m=x["m"], v=x["v"], mask=x["mask"],
                                        scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None)
                                   for x in self.t], dev)
-        self.launches = len({(x["w"].shape, x["w"].stride(0)) for x in self.t})   # one launch per distinct shape
+        self.flags = B.FLAG_WORK_QUEUE if queue else 0
+        if queue:
+            self.launches = len({(x["w"].shape, x["w"].stride(0)) for x in self.t})   # one launch per distinct shape
 
     def step(self, B, t: int, scaled: bool):
         cfg = B.iteration_config(t, TOTAL_STEPS, mask_period=MASK_PERIOD, lr=LR, lambda_=LAMBDA,
-                                 scale_segments=SEGMENTS if scaled else 0)
+                                 scale_segments=SEGMENTS if scaled else 0, flags=self.flags)
         if self.list is not None:
             B.cast_adams_step_multi(self.list, cfg)
         else:
@@ -129,8 +132,9 @@ def main():
     ap.add_argument("--no-scale", action="store_true", help="time the step without weight scaling")
     ap.add_argument("--layout", default="interleaved", choices=["interleaved", "separate"],
                     help="w, mu, v of each matrix row-interleaved in one buffer (default) or three dense arrays")
-    ap.add_argument("--launch", default="list", choices=["list", "per-matrix"],
-                    help="one cast_adams_step_multi call per step (default) or one cast_adams_step call per matrix")
+    ap.add_argument("--launch", default="list", choices=["list", "queue", "per-matrix"],
+                    help="one cast_adams_step_multi call per step (default; 'queue' adds CAST_FLAG_WORK_QUEUE) "
+                         "or one cast_adams_step call per matrix")
     ap.add_argument("--row-splits", type=int, default=1, help="per-matrix launch only: launches per matrix (experiment)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
@@ -151,8 +155,8 @@ def main():
     t0 = time.time()
     model = Model(args.workload, args.layers, torch, B, synth, dev, args.layout == "interleaved")
     model.row_splits = args.row_splits
-    if args.launch == "list":
-        model.tensor_list(B, scaled, dev)
+    if args.launch != "per-matrix":
+        model.tensor_list(B, scaled, dev, queue=args.launch == "queue")
     torch.cuda.synchronize()
     log(f"[bench] {args.workload}: {len(model.shapes)} matrices, {model.params} params resident "
         f"({torch.cuda.memory_allocated() / 2**30:.1f} GiB) after {time.time() - t0:.1f} s")
@@ -191,8 +195,8 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None if MEASURED_TRAFFIC_BYTES_PER_PARAM is None
                 else MEASURED_TRAFFIC_BYTES_PER_PARAM * model.params / launches,
-                "kernel": "adams_step_vec<M=4, bf16 grad, stored mask, scaled>" if scaled
-                else "adams_step_vec<M=4, bf16 grad, stored mask>",
+                "kernel": ("adams_step_vec_queue" if args.launch == "queue" else "adams_step_vec")
+                + ("<M=4, bf16 grad, stored mask, scaled>" if scaled else "<M=4, bf16 grad, stored mask>"),
                 "bytes_per_launch": bytes_per_launch, "avg_launch_us": round(dom_ms * 1e3 / launches, 2)}
 
     extra = {"ms_step_non_refresh": round(dom_ms, 3),
@@ -232,7 +236,7 @@ def main():
            "config": {"workload": f"{args.workload} linear weight set ({len(model.shapes)} matrices, {model.params} params), "
                                   f"2:4, fp32 w/mu/v ({args.layout}) + bf16 grads + mask bits resident, "
                                   f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step, "
-                                  f"{'one list call' if args.launch == 'list' else 'one call per matrix'} per step",
+                                  f"{ {'list': 'one list call', 'queue': 'one list call (work queue)', 'per-matrix': 'one call per matrix'}[args.launch]} per step",
                       "n_keep": 2, "m_group": 4, "scale_segments": SEGMENTS if scaled else 0,
                       "pct_of_peak_hbm": round(100 * BYTES_PER_PARAM * value / HBM_PEAK_GBS, 2)},
            "roofline": roofline, "extra": extra}

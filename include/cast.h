@@ -57,6 +57,10 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
 
 /* Test-only: second moment from g^2 instead of mu~^2 (Eq. 9's form; not the paper's method). */
 #define CAST_FLAG_V_FROM_GRAD 1u
+/* cast_adams_step_multi only (ignored elsewhere): step matrices of equal shape with one launch of
+ * resident workgroups that draw their work in order from a ticket counter, instead of one launch
+ * per matrix.  Same results bit for bit. */
+#define CAST_FLAG_WORK_QUEUE 2u
 
 /* Inputs of one AdamS iteration (Algorithm 1).  All scalars are used as given, in fp32. */
 typedef struct {
@@ -73,7 +77,7 @@ typedef struct {
                              /* incoming weights (Eq. 6) and store it; 0: read mask_bits     */
     int32_t  scale_segments; /* n of Eq. 12; 0 = no weight scaling                           */
     int32_t  grad_dtype;     /* CAST_F32 or CAST_BF16                                        */
-    uint32_t flags;          /* 0, or CAST_FLAG_V_FROM_GRAD                                  */
+    uint32_t flags;          /* 0, or an OR of CAST_FLAG_*                                   */
 } cast_adams_config;
 
 const char *cast_status_str(cast_status s);
@@ -116,9 +120,9 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
 
 /*
  * The same iteration over a list of matrices that share one configuration (all linear weights
- * of a model in one call).  Matrices of equal shape are stepped by one launch, which removes the
- * launch-to-launch bubbles of hundreds of small launches; results are identical to calling
- * cast_adams_step on each matrix.
+ * of a model in one call): validated as a whole before anything is launched, then stepped one
+ * launch per matrix, or, with CAST_FLAG_WORK_QUEUE, one work-queue launch per group of matrices
+ * of equal shape.  Results are identical to calling cast_adams_step on each matrix.
  *   tensors    HOST in   `count` descriptors; the device buffers they name follow the rules of
  *                        cast_adams_step (scale / scale_grad NULL or not for all alike, per cfg)
  *   workspace  DEVICE    at least cast_adams_multi_workspace_bytes(count) bytes, 16-byte aligned,

@@ -15,6 +15,7 @@ LIB_PATH = os.environ.get("CAST_LIBRARY") or os.path.join(_HERE, "libcast.so")  
 
 CAST_F32, CAST_BF16 = 0, 1
 FLAG_V_FROM_GRAD = 1
+FLAG_WORK_QUEUE = 2
 
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",

@@ -28,12 +28,22 @@ struct TensorPtrs {
     uint64_t pad;         // 64 bytes per entry
 };
 
+// The table is addressed through the constant address space: its entries do not change while a
+// kernel runs, and only then are they read with scalar loads, straight into the scalar registers
+// where buffer resources have to live.
+typedef const TensorPtrs __attribute__((address_space(4))) *ConstTable;
+
 struct SpanArgs {
-    TensorPtrs one;
-    const TensorPtrs *table;   // NULL: use `one`
+    TensorPtrs one;       // the buffer set of a single-matrix launch
+    ConstTable table;     // the buffer sets of a list launch (work queue)
     SpanGeom geom;
     StepScalars s;
 };
+
+static ConstTable as_const_table(const void *device_ptr)
+{
+    return (ConstTable)(uintptr_t)device_ptr;
+}
 
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
 template <bool BF16>
@@ -76,61 +86,92 @@ __device__ __forceinline__ vu4_t pack4(const float (&f)[4])
     return x;
 }
 
-// One wavefront (or waves_per_span cooperating ones) walks one span in chunks of 256 entries,
-// loading the next chunk before it works on the current one so that memory requests stay in
-// flight during the arithmetic.  Control flow is uniform across the wavefront: lanes past the
-// end of the span carry zeros through the arithmetic and the buffer range check voids their
-// stores, so the cross-lane steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly)
-// always see all 64 lanes.
+// What a wavefront needs to know about the span it works on; everything here is wave-uniform
+// and lives in scalar registers.
+struct SpanCtx {
+    SpanBuffers b;
+    float *scale_grad;   // where dL/dA of this matrix goes, or NULL
+    int64_t span;        // index of the span in the matrix (= index into scale / scale_grad)
+    float A;             // its scale factor
+    int len;             // entries; 0 for spans past the end of the matrix
+    int sub;             // which of the waves_per_span cooperating wavefronts this one is
+};
+
 // `matrix` selects the buffer set (entry of the table of a list call), `block` the workgroup's
 // share of that matrix: block_waves / waves_per_span consecutive spans.
-template <int M, bool BF16, bool REFRESH, bool SCALED>
-__device__ __forceinline__ void step_block_task(const SpanArgs &a, uint32_t matrix, int64_t block, float *partial)
+template <bool BF16, bool SCALED, bool FROM_TABLE>
+__device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, int64_t block, int wave, SpanCtx &c)
 {
     // The buffer set of this launch, or of one matrix of a list.  The table is read through the
     // constant address space so that the (wave-uniform) loads are scalar loads and the pointers
     // arrive in scalar registers, where buffer resources have to live.
-    TensorPtrs t = a.one;
-    if (a.table) {
-        typedef const TensorPtrs __attribute__((address_space(4))) ConstTensorPtrs;
-        const ConstTensorPtrs *e = (const ConstTensorPtrs *)(uintptr_t)a.table + matrix;
-        t.w = e->w; t.grad = e->grad; t.m = e->m; t.v = e->v;
-        t.mask = e->mask; t.scale = e->scale; t.scale_grad = e->scale_grad;
+    TensorPtrs t;
+    if constexpr (FROM_TABLE) {
+        // explicit scalar loads of the 64-byte entry (two 8-dword reads)
+        typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+        const uint64_t entry = uniform_u64((uint64_t)(uintptr_t)a.table + (uint64_t)matrix * sizeof(TensorPtrs));
+        u32x8 lo, hi;
+        asm volatile("s_load_dwordx8 %0, %2, 0x0\n\ts_load_dwordx8 %1, %2, 0x20\n\ts_waitcnt lgkmcnt(0)"
+                     : "=&s"(lo), "=&s"(hi) : "s"(entry) : "memory");
+        auto ptr = [](uint32_t l, uint32_t h) { return (uintptr_t)(((uint64_t)h << 32) | l); };
+        t.w = (float *)ptr(lo[0], lo[1]);
+        t.grad = (const void *)ptr(lo[2], lo[3]);
+        t.m = (float *)ptr(lo[4], lo[5]);
+        t.v = (float *)ptr(lo[6], lo[7]);
+        t.mask = (uint32_t *)ptr(hi[0], hi[1]);
+        t.scale = (const float *)ptr(hi[2], hi[3]);
+        t.scale_grad = (float *)ptr(hi[4], hi[5]);
+    } else {
+        t = a.one;
     }
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
+    const SpanSlot slot = span_slot(a.geom, block, wave, blockDim.x / kWave);
+    c.span = (int64_t)uniform_u64((unsigned long long)slot.span);
+    c.sub = slot.sub;
+    // 64-bit products are cheapest on the vector ALU, so the compiler may leave these wave-uniform
+    // numbers in vector registers; buffer resources need them in scalar registers
+    SpanOrigin o = span_origin(a.geom, c.span);
+    o.state_begin = (int64_t)uniform_u64((unsigned long long)o.state_begin);
+    o.dense_begin = (int64_t)uniform_u64((unsigned long long)o.dense_begin);
+    o.len = __builtin_amdgcn_readfirstlane(o.len);
+    c.len = o.len;
+    c.b.w = span_resource(t.w + o.state_begin, c.len * 4);
+    c.b.m = span_resource(t.m + o.state_begin, c.len * 4);
+    c.b.v = span_resource(t.v + o.state_begin, c.len * 4);
+    if constexpr (BF16) c.b.g = span_resource(static_cast<const uint16_t *>(t.grad) + o.dense_begin, c.len * 2);
+    else c.b.g = span_resource(static_cast<const float *>(t.grad) + o.dense_begin, c.len * 4);
+    c.b.mask = span_resource(t.mask + (o.dense_begin >> 5), c.len / 8);    // spans start and end on mask words
+    c.A = 1.0f;
+    c.scale_grad = nullptr;
+    if constexpr (SCALED) {
+        if (c.len > 0) c.A = t.scale[c.span];
+        c.scale_grad = t.scale_grad;
+    }
+}
+
+__device__ __forceinline__ int first_offset(const SpanCtx &c, int lane) { return c.sub * kChunk + lane * kLaneElems; }
+
+// One wavefront (or waves_per_span cooperating ones) walks one span in chunks of 256 entries;
+// `cur` holds the first chunk, already requested by the caller, and every further chunk is
+// requested before the current one is worked on, so that memory requests stay in flight during
+// the arithmetic.  Control flow is uniform across the wavefront: lanes past the end of the span
+// carry zeros through the arithmetic and the buffer range check voids their stores, so the
+// cross-lane steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly) always see
+// all 64 lanes.
+template <int M, bool BF16, bool REFRESH, bool SCALED>
+__device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Chunk<BF16> cur, int lane, int wave,
+                                         float *partial)
+{
     const int P = a.geom.waves_per_span;
-    const int block_waves = blockDim.x / kWave;
-    const int64_t span = block * (block_waves / P) + wave / P;
-    const int sub = wave % P;
-    const SpanOrigin o = span_origin(a.geom, span);
-    const bool live_span = o.len > 0;
-    const int len = o.len;
-
-    SpanBuffers b;
-    b.w = span_resource(t.w + o.state_begin, len * 4);
-    b.m = span_resource(t.m + o.state_begin, len * 4);
-    b.v = span_resource(t.v + o.state_begin, len * 4);
-    if constexpr (BF16) b.g = span_resource(static_cast<const uint16_t *>(t.grad) + o.dense_begin, len * 2);
-    else b.g = span_resource(static_cast<const float *>(t.grad) + o.dense_begin, len * 4);
-    b.mask = span_resource(t.mask + (o.dense_begin >> 5), len / 8);    // spans start and end on mask words
-
-    float A = 1.0f;
-    if constexpr (SCALED) { if (live_span) A = t.scale[span]; }
-    const bool want_gA = SCALED && t.scale_grad != nullptr;
+    const int len = c.len;
+    const SpanBuffers &b = c.b;
+    const float A = c.A;
+    const bool want_gA = SCALED && c.scale_grad != nullptr;
     float acc = 0.0f;
-
     const int stride = P * kChunk;
-    int off = sub * kChunk + lane * kLaneElems;      // this lane's first entry, relative to the span
-    Chunk<BF16> cur, nxt;
-    chunk_load<BF16, REFRESH>(cur, b, off);
-    for (int base = sub * kChunk; base < len; base += stride) {
-#ifdef CAST_EXPERIMENT_ALWAYS_PREFETCH
-        const bool more = true;
-#else
-        const bool more = base + stride < len;                  // wave-uniform
-#endif
-        if (more) chunk_load<BF16, REFRESH>(nxt, b, off + stride);
+    int off = first_offset(c, lane);      // this lane's first entry, relative to the span
+    for (int base = c.sub * kChunk; base < len; base += stride) {
+        Chunk<BF16> nxt;
+        chunk_load<BF16, REFRESH>(nxt, b, off + stride);        // past the end: all zeros, never used
 
         float w[4], g[4], mu[4], v[4];
         unpack4(cur.w, w);
@@ -161,7 +202,6 @@ __device__ __forceinline__ void step_block_task(const SpanArgs &a, uint32_t matr
         __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
 
-        if (!more || base + stride >= len) break;
         cur = nxt;
         off += stride;
     }
@@ -170,49 +210,103 @@ __device__ __forceinline__ void step_block_task(const SpanArgs &a, uint32_t matr
         if (want_gA) {   // uniform over the workgroup
             const float wave_total = wave_sum_fixed_order(acc);
             if (P == 1) {
-                if (lane == 0 && live_span) t.scale_grad[span] = wave_total;
+                if (lane == 0 && len > 0) c.scale_grad[c.span] = wave_total;
             } else {
                 if (lane == 0) partial[wave] = wave_total;
                 __syncthreads();
-                if (lane == 0 && sub == 0 && live_span) {
+                if (lane == 0 && c.sub == 0 && len > 0) {
                     float sum = partial[wave];
                     for (int p = 1; p < P; ++p) sum = sum + partial[wave + p];
-                    t.scale_grad[span] = sum;
+                    c.scale_grad[c.span] = sum;
                 }
             }
         }
     }
 }
 
-// One workgroup per share, dealt by the hardware dispatcher: grid = (shares per matrix, matrices).
+// One matrix, one workgroup per share, dealt by the hardware dispatcher.
 template <int M, bool BF16, bool REFRESH, bool SCALED>
 __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
 {
     __shared__ float partial[kMaxBlockWaves];
-    step_block_task<M, BF16, REFRESH, SCALED>(a, blockIdx.y, blockIdx.x, partial);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
+    SpanCtx c;
+    span_open<BF16, SCALED, false>(a, 0, blockIdx.x, wave, c);
+    Chunk<BF16> first;
+    chunk_load<BF16, REFRESH>(first, c.b, first_offset(c, lane));
+    span_run<M, BF16, REFRESH, SCALED>(a, c, first, lane, wave, partial);
 }
 
-// Work queue: a fixed set of resident workgroups draws shares, in order, from a ticket counter in
-// device memory (zero at launch).  Whatever the relative speed of the compute units and of the 8
-// XCDs, the shares in flight are always the most recently drawn ones, so every array is walked
-// front to back through one narrow, steadily advancing window, which is what HBM serves fastest;
-// there are no wavefront launches after the first.  Every workgroup leaves when it draws a ticket
-// past the end: exactly tasks + gridDim.x tickets are drawn per launch and nobody waits for anybody.
+// Work queue: a fixed set of resident workgroups draws runs of consecutive shares, in order, from
+// a ticket counter in device memory (zero at launch).  Whatever the relative speed of the compute
+// units and of the 8 XCDs, the shares in flight are always the most recently drawn ones, so every
+// array is walked front to back through one narrow, steadily advancing window, which is what HBM
+// serves fastest, and no wavefront is launched after the first.  One counter serves about 60
+// million tickets a second, so a ticket stands for 2^log2_run shares.  The loop is
+// software-pipelined: while a workgroup works on one share, the first chunk of its next share is
+// already on its way and the ticket after the current one has been asked for.  Every workgroup
+// leaves when its next share lies past the end; nobody waits for anybody.
+struct QueueArgs {
+    unsigned long long *ticket_counter;
+    uint32_t tasks;                  // shares in this launch (all matrices)
+    uint32_t blocks_per_matrix;
+    FastDivU32 div_blocks_per_matrix;
+    int log2_run;                    // shares per ticket = 1 << log2_run
+};
+
 template <int M, bool BF16, bool REFRESH, bool SCALED>
-__global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const SpanArgs a, unsigned long long *ticket_counter,
-                                                                         unsigned long long tasks, FastDivU32 div_blocks_per_matrix,
-                                                                         uint32_t blocks_per_matrix)
+__global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const SpanArgs a, const QueueArgs q)
 {
     __shared__ float partial[kMaxBlockWaves];
     __shared__ unsigned long long drawn[2];
-    for (int it = 0;; ++it) {
-        if (threadIdx.x == 0) drawn[it & 1] = atomicAdd(ticket_counter, 1ull);
-        __syncthreads();   // also separates this round's use of `partial` from the last one's
-        const unsigned long long ticket = drawn[it & 1];
-        if (ticket >= tasks) return;
-        const uint32_t task = __builtin_amdgcn_readfirstlane((uint32_t)ticket);
-        const uint32_t matrix = fast_div(task, div_blocks_per_matrix);
-        step_block_task<M, BF16, REFRESH, SCALED>(a, matrix, (int64_t)(task - matrix * blocks_per_matrix), partial);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t run_mask = (1u << q.log2_run) - 1u;
+    unsigned long long pending = 0;
+
+    if (threadIdx.x == 0) drawn[0] = atomicAdd(q.ticket_counter, 1ull);
+    __syncthreads();
+    const unsigned long long first_ticket = uniform_u64(drawn[0]);
+    if ((first_ticket << q.log2_run) >= q.tasks) return;
+    uint32_t share = (uint32_t)first_ticket << q.log2_run;      // wave-uniform
+    Chunk<BF16> cur;
+    {
+        const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
+        SpanCtx c;
+        span_open<BF16, SCALED, true>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
+        chunk_load<BF16, REFRESH>(cur, c.b, first_offset(c, lane));
+    }
+    if (threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
+
+    for (uint32_t seq = 0;; ++seq) {
+        const bool last_of_run = (seq & run_mask) == run_mask;          // wave-uniform
+        const int slot = ((seq >> q.log2_run) + 1) & 1;
+        if (last_of_run && threadIdx.x == 0) drawn[slot] = pending;
+        __syncthreads();   // publishes the ticket; also separates this round's use of `partial` from the last one's
+        unsigned long long next = (unsigned long long)share + 1;
+        if (last_of_run) next = uniform_u64(drawn[slot]) << q.log2_run;
+        const bool has_next = next < q.tasks;
+        const uint32_t next_share = __builtin_amdgcn_readfirstlane((uint32_t)next);
+        Chunk<BF16> nxt;
+        if (has_next) {
+            // Only one span context is ever alive (scalar registers are scarce): the next share's is
+            // built here just to address its first chunk, and again below when its turn comes.
+            const uint32_t matrix = fast_div(next_share, q.div_blocks_per_matrix);
+            SpanCtx ahead;
+            span_open<BF16, SCALED, true>(a, matrix, (int64_t)(next_share - matrix * q.blocks_per_matrix), wave, ahead);
+            chunk_load<BF16, REFRESH>(nxt, ahead.b, first_offset(ahead, lane));
+            if (last_of_run && threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
+        }
+        {
+            const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
+            SpanCtx c;
+            span_open<BF16, SCALED, true>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
+            span_run<M, BF16, REFRESH, SCALED>(a, c, cur, lane, wave, partial);
+        }
+        if (!has_next) return;
+        share = next_share;
+        cur = nxt;
     }
 }
 
@@ -225,9 +319,9 @@ __global__ __launch_bounds__(kMaxBlockThreads) void scale_grad_vec(const float *
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int P = geom.waves_per_span;
-    const int block_waves = blockDim.x / kWave;
-    const int64_t span = (int64_t)blockIdx.x * (block_waves / P) + wave / P;
-    const int sub = wave % P;
+    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
+    const int64_t span = slot.span;
+    const int sub = slot.sub;
     const SpanOrigin o = span_origin(geom, span);
     const int len = o.len;
     __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4), rg;
@@ -437,6 +531,7 @@ struct VecLaunch {
     unsigned long long *tickets;
     unsigned long long tasks;
     uint32_t blocks_per_matrix;
+    int log2_run;
 };
 
 template <int M, bool BF16, bool REFRESH, bool SCALED>
@@ -444,7 +539,7 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
 {
     if (l.tickets)
         hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), dim3(l.block_threads), 0, st, a,
-                           l.tickets, l.tasks, make_fast_div(l.blocks_per_matrix), l.blocks_per_matrix);
+                           QueueArgs{l.tickets, (uint32_t)l.tasks, l.blocks_per_matrix, make_fast_div(l.blocks_per_matrix), l.log2_run});
     else {
         // experiment knob: cap the resident wavefronts per compute unit by reserving LDS per workgroup
         static const int cap = env_int("CAST_STATIC_WAVES_PER_CU", 0);
@@ -454,7 +549,7 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
             if (blocks < 1) blocks = 1;
             lds = (unsigned)(160 * 1024 / blocks) - 1024;
         }
-        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), dim3(l.grid_x, l.grid_y), dim3(l.block_threads), lds, st, a);
+        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), dim3(l.block_threads), lds, st, a);
     }
 }
 
@@ -509,8 +604,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = scale != nullptr;
     if (p.vec) {
-        SpanArgs a{{w, grad, m, v, mask_bits, scale, scale_grad, 0}, nullptr, p.geom, make_scalars(cfg)};
-        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0}, a, st);
+        SpanArgs a{{w, grad, m, v, mask_bits, scale, scale_grad, 0}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
+        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0}, a, st);
         return launch_status();
     }
     // odd shapes: dL/dA first (it needs the incoming weights), then the element pass
@@ -557,8 +652,11 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     const bool bf16 = cfg->grad_dtype == CAST_BF16;
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = cfg->scale_segments > 0;
-    // tuning knobs (read once): resident wavefronts per compute unit of the work queue; 0 = no queue
+    // The work queue is opt-in: one launch per matrix has measured faster at every size tried.
+    const bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
+    // tuning knobs (read once): resident wavefronts per compute unit of the work queue
     static const int waves_per_cu = env_int("CAST_QUEUE_WAVES_PER_CU", 16);
+    static const int log2_run = env_int("CAST_QUEUE_LOG2_RUN", 1) & 7;      // shares per ticket = 1 << log2_run
     std::vector<int> order;           // indices of vector-path matrices, grouped by shape
     std::vector<char> taken(count, 0);
     struct Group { int first, n; SpanPlan plan; };
@@ -566,7 +664,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     for (int i = 0; i < count; ++i) {
         if (taken[i] || ts[i].rows == 0 || ts[i].cols == 0) continue;
         const SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments);
-        if (!p.vec) continue;
+        if (!p.vec || !use_queue || waves_per_cu <= 0) continue;
         Group g{(int)order.size(), 0, p};
         // tickets are 32-bit task numbers inside the kernel
         const int fit = (int)(((int64_t)1 << 31) / p.grid);
@@ -593,16 +691,13 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         const StepScalars sc = make_scalars(cfg);
         for (size_t gi = 0; gi < groups.size(); ++gi) {
             const Group &g = groups[gi];
-            SpanArgs a{{}, static_cast<const TensorPtrs *>(workspace) + g.first, g.plan.geom, sc};
-            VecLaunch l{g.plan.grid, (unsigned)g.n, g.plan.block_threads, nullptr, 0, 0};
-            if (waves_per_cu > 0) {
-                const unsigned long long tasks = (unsigned long long)g.plan.grid * (unsigned)g.n;
-                int blocks_per_cu = waves_per_cu / (g.plan.block_threads / kWave);
-                if (blocks_per_cu < 1) blocks_per_cu = 1;
-                unsigned long long resident = (unsigned long long)device_compute_units() * blocks_per_cu;
-                if (resident > tasks) resident = tasks;
-                l = VecLaunch{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid};
-            }
+            SpanArgs a{{}, as_const_table(static_cast<const TensorPtrs *>(workspace) + g.first), g.plan.geom, sc};
+            const unsigned long long tasks = (unsigned long long)g.plan.grid * (unsigned)g.n;
+            int blocks_per_cu = waves_per_cu / (g.plan.block_threads / kWave);
+            if (blocks_per_cu < 1) blocks_per_cu = 1;
+            unsigned long long resident = (unsigned long long)device_compute_units() * blocks_per_cu;
+            if (resident > tasks) resident = tasks;
+            const VecLaunch l{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid, log2_run};
             launch_vec_any(cfg->m_group, bf16, refresh, scaled, l, a, st);
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         }

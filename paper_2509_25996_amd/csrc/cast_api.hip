@@ -104,7 +104,7 @@ static cast_status validate_step(const float *w, const void *grad, const float *
     if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (!dtype_ok(cfg->grad_dtype)) return CAST_ERR_DTYPE;
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
-    if (cfg->flags & ~CAST_FLAG_V_FROM_GRAD) return CAST_ERR_CONFIG;
+    if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE)) return CAST_ERR_CONFIG;
     // the bias corrections divide: they must be positive finite numbers (1 - beta^s with s >= 1)
     if (!(cfg->bias_corr1 > 0.0f) || !(cfg->bias_corr2 > 0.0f) || isinf(cfg->bias_corr1) || isinf(cfg->bias_corr2))
         return CAST_ERR_CONFIG;

@@ -66,6 +66,23 @@ struct SpanGeom {
     FastDivU32 div_spans_per_row;
 };
 
+// Which span a wavefront works on and its place among the cooperating wavefronts.  The number
+// of cooperating wavefronts is a power of two, so this is shifts and masks on scalar registers
+// (a runtime division would be carried out, and leave its result, in vector registers).
+struct SpanSlot {
+    int64_t span;
+    int sub;
+};
+
+__device__ __forceinline__ SpanSlot span_slot(const SpanGeom &g, int64_t block, int wave, int block_waves)
+{
+    const int shift = __builtin_ctz((unsigned)g.waves_per_span);
+    SpanSlot s;
+    s.span = block * (block_waves >> shift) + (wave >> shift);
+    s.sub = wave & (g.waves_per_span - 1);
+    return s;
+}
+
 struct SpanOrigin {
     int64_t state_begin;    // first entry of the span in w, mu, v
     int64_t dense_begin;    // first entry of the span in dense [rows, cols] numbering
@@ -100,14 +117,12 @@ __device__ __forceinline__ uint32_t dpp_u32(uint32_t x)
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
 }
 
-// A pointer that is the same in every lane, moved to scalar registers.
-template <typename T>
-__device__ __forceinline__ T *uniform_ptr(T *p)
+// A 64-bit value that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ unsigned long long uniform_u64(unsigned long long x)
 {
-    const uint64_t x = reinterpret_cast<uint64_t>(p);
     const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
     const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return reinterpret_cast<T *>(((uint64_t)hi << 32) | lo);
+    return ((unsigned long long)hi << 32) | lo;
 }
 
 // OR of a value over each aligned run of 8 lanes; every lane of the run gets the result.
@@ -393,15 +408,6 @@ __device__ __forceinline__ void adams_entries4(float (&w)[4], const float (&g)[4
 #pragma unroll
     for (int j = 0; j < 4; ++j) { lo = __builtin_fminf(lo, vt[j]); hi = __builtin_fmaxf(hi, vt[j]); }
     const bool out_of_range = !(lo >= 0x1p-63f) || !(hi < 0x1p66f);
-#ifdef CAST_EXPERIMENT_OLD_SHORT
-    if (s.short_forms && !__any(out_of_range && live)) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            w[j] = adams_update(w[j], div_short(mt[j], s.bias_corr1), div_short(vt[j], s.bias_corr2), s);
-            v[j] = vt[j];
-        }
-    } else
-#endif
     if (s.short_forms && !__any(out_of_range && live)) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {

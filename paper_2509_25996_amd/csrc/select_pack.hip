@@ -24,8 +24,9 @@ __global__ __launch_bounds__(kMaxBlockThreads) void nm_select_vec(const float *w
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int P = geom.waves_per_span;
-    const int64_t span = (int64_t)blockIdx.x * ((blockDim.x / kWave) / P) + wave / P;
-    const int sub = wave % P;
+    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
+    const int64_t span = slot.span;
+    const int sub = slot.sub;
     const SpanOrigin o = span_origin(geom, span);
     const int len = o.len;
     const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
@@ -149,8 +150,9 @@ __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_2of4_vec(
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int P = geom.waves_per_span;
-    const int64_t span = (int64_t)blockIdx.x * ((blockDim.x / kWave) / P) + wave / P;
-    const int sub = wave % P;
+    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
+    const int64_t span = slot.span;
+    const int sub = slot.sub;
     const SpanOrigin o = span_origin(geom, span);
     const int len = o.len;
     const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);

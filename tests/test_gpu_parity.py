@@ -402,8 +402,9 @@ def test_strided_weights_in_every_entry_point(rows, cols):
 
 
 # --------------------------------------------------------------------------- list of matrices in one call
+@pytest.mark.parametrize("queue", [False, True])
 @pytest.mark.parametrize("nseg", [0, 2])
-def test_multi_tensor_step_equals_single_steps(nseg):
+def test_multi_tensor_step_equals_single_steps(nseg, queue):
     shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (64, 512), (32, 1024), (3, 40), (0, 64), (16, 11008)]
     rng = np.random.default_rng(9)
 
@@ -428,6 +429,7 @@ def test_multi_tensor_step_equals_single_steps(nseg):
             cfg = B.iteration_config(t, 4, mask_period=2, lr=1e-3, lambda_=1e-3, scale_segments=nseg)
             for x in a:
                 B.cast_adams_step(x["w"], x["grad"], x["m"], x["v"], x["mask"], cfg, scale=x["scale"], scale_grad=x["scale_grad"])
+            cfg.flags |= B.FLAG_WORK_QUEUE if queue else 0
             B.cast_adams_step_multi(tl, cfg)
         torch.cuda.synchronize()
         for x, y in zip(a, b):
