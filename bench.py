@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 BYTES_PER_PARAM = 26.125         # read w, mu, v (fp32) + g (bf16) + 1 mask bit; write w, mu, v
 # HBM bytes per parameter of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/; None until measured.
-MEASURED_TRAFFIC_BYTES_PER_PARAM = 26.19
+MEASURED_TRAFFIC_BYTES_PER_PARAM = 26.20
 
 LR, LAMBDA, TOTAL_STEPS, MASK_PERIOD, SEGMENTS = 2e-5, 4e-7, 7500, 10, 2   # Table 11 (LLaMA), Sec. 4.1, Sec. 5
 
@@ -39,8 +39,14 @@ def log(*a):
 class Model:
     """Every linear weight of the workload with its optimizer state, in device memory."""
 
-    def __init__(self, workload: str, layers, torch, B, synth, dev, interleaved: bool):
+    def __init__(self, workload: str, layers, torch, B, synth, dev, interleaved: bool, segment_rows: bool = False):
         self.shapes = synth.weight_set(workload, layers)
+        self.segments = SEGMENTS
+        if segment_rows:
+            # a [rows, cols] matrix with n scaling segments per row is, byte for byte, a [rows*n, cols/n]
+            # matrix with one: the interleave of w, mu, v then alternates every segment instead of every row
+            self.shapes = [(nm, r * SEGMENTS, c // SEGMENTS) for nm, r, c in self.shapes]
+            self.segments = 1
         self.params = synth.set_params(self.shapes)
         self.t = []
         self.list = None
@@ -58,8 +64,8 @@ class Model:
                 m, v = torch.zeros_like(w), torch.zeros_like(w)
             self.t.append(dict(w=w, g=g, m=m, v=v,
                                mask=B.alloc_mask(r, c, dev),
-                               A=torch.ones((r, SEGMENTS), device=dev),
-                               gA=torch.zeros((r, SEGMENTS), device=dev)))
+                               A=torch.ones((r, self.segments), device=dev),
+                               gA=torch.zeros((r, self.segments), device=dev)))
 
     def tensor_list(self, B, scaled: bool, dev, queue: bool):
         """Descriptors for the one-call-per-step entry point, marshalled once."""
@@ -72,7 +78,7 @@ class Model:
 
     def step(self, B, t: int, scaled: bool):
         cfg = B.iteration_config(t, TOTAL_STEPS, mask_period=MASK_PERIOD, lr=LR, lambda_=LAMBDA,
-                                 scale_segments=SEGMENTS if scaled else 0, flags=self.flags)
+                                 scale_segments=self.segments if scaled else 0, flags=self.flags)
         if self.list is not None:
             B.cast_adams_step_multi(self.list, cfg)
         else:
@@ -130,7 +136,7 @@ def main():
     ap.add_argument("--workload", default="llama2_7b", choices=["opt125m", "llama2_7b", "llama2_13b"])
     ap.add_argument("--layers", type=int, default=None, help="use only the first LAYERS decoder blocks (debugging)")
     ap.add_argument("--no-scale", action="store_true", help="time the step without weight scaling")
-    ap.add_argument("--layout", default="interleaved", choices=["interleaved", "separate"],
+    ap.add_argument("--layout", default="interleaved", choices=["interleaved", "interleaved-segments", "separate"],
                     help="w, mu, v of each matrix row-interleaved in one buffer (default) or three dense arrays")
     ap.add_argument("--launch", default="list", choices=["list", "queue", "per-matrix"],
                     help="one cast_adams_step_multi call per step (default; 'queue' adds CAST_FLAG_WORK_QUEUE) "
@@ -153,7 +159,8 @@ def main():
     scaled = not args.no_scale
 
     t0 = time.time()
-    model = Model(args.workload, args.layers, torch, B, synth, dev, args.layout == "interleaved")
+    model = Model(args.workload, args.layers, torch, B, synth, dev, args.layout != "separate",
+                  args.layout == "interleaved-segments")
     model.row_splits = args.row_splits
     if args.launch != "per-matrix":
         model.tensor_list(B, scaled, dev, queue=args.launch == "queue")

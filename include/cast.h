@@ -122,12 +122,17 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
  * The same iteration over a list of matrices that share one configuration (all linear weights
  * of a model in one call): validated as a whole before anything is launched, then stepped one
  * launch per matrix, or, with CAST_FLAG_WORK_QUEUE, one work-queue launch per group of matrices
- * of equal shape.  Results are identical to calling cast_adams_step on each matrix.
+ * of equal shape.  w, m, v and mask_bits come out as from cast_adams_step on each matrix, bit for
+ * bit; so does scale_grad, except for row segments of more than 4096 entries, which the list call
+ * (without the work queue) steps with one workgroup per 2048 entries: their sums are added in
+ * another, equally fixed order (per 2048 entries, then left to right).
  *   tensors    HOST in   `count` descriptors; the device buffers they name follow the rules of
  *                        cast_adams_step (scale / scale_grad NULL or not for all alike, per cfg)
- *   workspace  DEVICE    at least cast_adams_multi_workspace_bytes(count) bytes, 16-byte aligned,
- *                        owned by the caller; it is overwritten by every call and read by the
- *                        kernels of that call, so it must not be shared between streams
+ *   workspace  DEVICE    at least cast_adams_multi_workspace_bytes(tensors, count, cfg) bytes (it
+ *                        depends on shapes, row strides, scale_grad being NULL or not,
+ *                        cfg->scale_segments and cfg->flags only), 16-byte aligned, owned by the
+ *                        caller; it is overwritten by every call and used by the kernels of that
+ *                        call, so it must not be shared between streams (too small: CAST_ERR_SHAPE)
  */
 typedef struct {
     float *w;
@@ -140,7 +145,8 @@ typedef struct {
     int64_t rows, cols, ld;
 } cast_tensor;
 
-size_t cast_adams_multi_workspace_bytes(int count);
+size_t cast_adams_multi_workspace_bytes(const cast_tensor *tensors /* HOST */, int count,
+                                        const cast_adams_config *cfg /* HOST */);
 
 cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                   void *workspace, size_t workspace_bytes, void *stream);

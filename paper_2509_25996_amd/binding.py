@@ -89,7 +89,7 @@ def load():
     L.cast_mask_stats.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp]
     L.cast_hbm_copy_probe.argtypes = [vp, vp, C.c_size_t, vp]
     L.cast_debug_div_by_uniform.argtypes = [vp, C.c_float, vp, i64]
-    L.cast_adams_multi_workspace_bytes.argtypes = [ci]
+    L.cast_adams_multi_workspace_bytes.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config)]
     L.cast_adams_multi_workspace_bytes.restype = C.c_size_t
     L.cast_adams_step_multi.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp, C.c_size_t, vp]
     for name in EXPORTS:
@@ -183,8 +183,9 @@ def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scal
                                   rows, cols, _ld(w, m, v), C.byref(cs), _stream(stream)), "cast_adams_step")
 
 
-def cast_adams_multi_workspace_bytes(count: int) -> int:
-    return load().cast_adams_multi_workspace_bytes(count)
+def cast_adams_multi_workspace_bytes(array, count: int, cfg: "AdamsConfig") -> int:
+    cs = cfg.c_struct()
+    return load().cast_adams_multi_workspace_bytes(array, count, C.byref(cs))
 
 
 class TensorList:
@@ -209,7 +210,16 @@ class TensorList:
                                     None if sc is None else sc.data_ptr(), None if sg is None else sg.data_ptr(),
                                     w.shape[0], w.shape[1], _ld(w, m, v))
         self.count = n
-        self.workspace = torch.empty(max(cast_adams_multi_workspace_bytes(n), 16), dtype=torch.uint8, device=device)
+        # the workspace depends on the shapes, on the number of scaling segments and on the launch form
+        segments = {0 if x.get("scale") is None else x["scale"].shape[1] for x in self.items if x["w"].numel()}
+        if len(segments) > 1:
+            raise ValueError("all matrices of a list must have the same number of scaling segments")
+        probe = AdamsConfig(scale_segments=segments.pop() if segments else 0)
+        need = 16
+        for flags in (0, FLAG_WORK_QUEUE):
+            probe.flags = flags
+            need = max(need, cast_adams_multi_workspace_bytes(self.array, n, probe))
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=device)
 
 
 def cast_adams_step_multi(tensors: TensorList, cfg: AdamsConfig, stream=None):

@@ -25,8 +25,8 @@ struct TensorPtrs {
     uint32_t *mask;
     const float *scale;
     float *scale_grad;
-    uint64_t pad;         // 64 bytes per entry
-};
+    float *piece_sums;    // split plans: one partial dL/dA sum per piece, else unused
+};                        // 64 bytes per entry
 
 // The table is addressed through the constant address space: its entries do not change while a
 // kernel runs, and only then are they read with scalar loads, straight into the scalar registers
@@ -91,7 +91,8 @@ __device__ __forceinline__ vu4_t pack4(const float (&f)[4])
 struct SpanCtx {
     SpanBuffers b;
     float *scale_grad;   // where dL/dA of this matrix goes, or NULL
-    int64_t span;        // index of the span in the matrix (= index into scale / scale_grad)
+    int64_t span;        // index of the span in the matrix (= index into scale / scale_grad; split plans: piece number)
+    int64_t segment;     // split plans: the row segment the piece belongs to (index into scale)
     float A;             // its scale factor
     int len;             // entries; 0 for spans past the end of the matrix
     int sub;             // which of the waves_per_span cooperating wavefronts this one is
@@ -99,7 +100,7 @@ struct SpanCtx {
 
 // `matrix` selects the buffer set (entry of the table of a list call), `block` the workgroup's
 // share of that matrix: block_waves / waves_per_span consecutive spans.
-template <bool BF16, bool SCALED, bool FROM_TABLE>
+template <bool BF16, bool SCALED, bool FROM_TABLE, bool SPLIT = false>
 __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, int64_t block, int wave, SpanCtx &c)
 {
     // The buffer set of this launch, or of one matrix of a list.  The table is read through the
@@ -129,7 +130,14 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     c.sub = slot.sub;
     // 64-bit products are cheapest on the vector ALU, so the compiler may leave these wave-uniform
     // numbers in vector registers; buffer resources need them in scalar registers
-    SpanOrigin o = span_origin(a.geom, c.span);
+    SpanOrigin o;
+    c.segment = c.span;
+    if constexpr (SPLIT) {
+        o = piece_origin(a.geom, c.span, c.segment);
+        c.segment = (int64_t)uniform_u64((unsigned long long)c.segment);
+    } else {
+        o = span_origin(a.geom, c.span);
+    }
     o.state_begin = (int64_t)uniform_u64((unsigned long long)o.state_begin);
     o.dense_begin = (int64_t)uniform_u64((unsigned long long)o.dense_begin);
     o.len = __builtin_amdgcn_readfirstlane(o.len);
@@ -143,8 +151,8 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     c.A = 1.0f;
     c.scale_grad = nullptr;
     if constexpr (SCALED) {
-        if (c.len > 0) c.A = t.scale[c.span];
-        c.scale_grad = t.scale_grad;
+        if (c.len > 0) c.A = t.scale[c.segment];
+        c.scale_grad = SPLIT ? t.piece_sums : t.scale_grad;     // split plans: the pieces' sums are added up afterwards
     }
 }
 
@@ -224,15 +232,17 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
     }
 }
 
-// One matrix, one workgroup per share, dealt by the hardware dispatcher.
-template <int M, bool BF16, bool REFRESH, bool SCALED>
+// One matrix, one workgroup per share, dealt by the hardware dispatcher.  SPLIT: the spans are
+// pieces of row segments (Eq. 12) too long for one workgroup of short-lived wavefronts; each
+// workgroup leaves the dL/dA sum of its piece in a[.].piece_sums and sum_piece_sums adds them up.
+template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false>
 __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
 {
     __shared__ float partial[kMaxBlockWaves];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
     SpanCtx c;
-    span_open<BF16, SCALED, false>(a, 0, blockIdx.x, wave, c);
+    span_open<BF16, SCALED, false, SPLIT>(a, 0, blockIdx.x, wave, c);
     Chunk<BF16> first;
     chunk_load<BF16, REFRESH>(first, c.b, first_offset(c, lane));
     span_run<M, BF16, REFRESH, SCALED>(a, c, first, lane, wave, partial);
@@ -309,6 +319,56 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const S
         cur = nxt;
     }
 }
+
+// Second half of a split plan: dL/dA of a row segment = its pieces' sums, added in column order.
+// One launch serves up to kMaxPieceJobs matrices (blockIdx.y), their descriptors passed by value.
+struct PieceJob {
+    const float *piece_sums;
+    float *scale_grad;
+    int64_t segments;
+    int pieces_per_segment;
+};
+
+constexpr int kMaxPieceJobs = 32;
+
+struct PieceJobs {
+    PieceJob job[kMaxPieceJobs];
+};
+
+__global__ __launch_bounds__(kBlockThreads) void sum_piece_sums(const PieceJobs jobs)
+{
+    const PieceJob &j = jobs.job[blockIdx.y];
+    const int64_t seg = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (seg >= j.segments) return;
+    const float *p = j.piece_sums + seg * j.pieces_per_segment;
+    float total = p[0];
+    for (int k = 1; k < j.pieces_per_segment; ++k) total = total + p[k];
+    j.scale_grad[seg] = total;
+}
+
+// Collects the second halves of the split plans of a list call and launches them in batches.
+struct PieceJobQueue {
+    PieceJobs pending;
+    int count = 0;
+    int64_t most_segments = 0;
+
+    cast_status flush(hipStream_t st)
+    {
+        if (count == 0) return CAST_OK;
+        const unsigned grid = (unsigned)((most_segments + kBlockThreads - 1) / kBlockThreads);
+        hipLaunchKernelGGL(sum_piece_sums, dim3(grid, (unsigned)count), dim3(kBlockThreads), 0, st, pending);
+        count = 0;
+        most_segments = 0;
+        return launch_status();
+    }
+
+    cast_status add(const PieceJob &j, hipStream_t st)
+    {
+        pending.job[count++] = j;
+        if (j.segments > most_segments) most_segments = j.segments;
+        return count == kMaxPieceJobs ? flush(st) : CAST_OK;
+    }
+};
 
 // dL/dA alone, with exactly the traversal and summation order of adams_step_vec.
 template <bool BF16>
@@ -449,7 +509,7 @@ static int env_int(const char *name, int fallback)
     return e && *e ? atoi(e) : fallback;
 }
 
-SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments)
+SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool allow_split)
 {
     // HBM rewards a narrow window of addresses in flight: wavefronts are kept short-lived (about
     // one chunk of 256 entries each) and the spans of one workgroup are contiguous, so that the
@@ -459,6 +519,7 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments)
     static const int forced_len = env_int("CAST_SPAN_LEN", 0);
     static const int forced_p = env_int("CAST_WAVES_PER_SPAN", 0);
     static const int forced_bw = env_int("CAST_BLOCK_WAVES", 0);
+    static const int piece_len = env_int("CAST_PIECE_LEN", 1024);
     SpanPlan p{};
     SpanGeom &g = p.geom;
     g.total = rows * cols;
@@ -466,12 +527,15 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments)
     g.row_gap = ld - cols;
     g.waves_per_span = 1;
     g.div_spans_per_row = make_fast_div(1);
+    g.pieces_per_segment = 1;
+    g.div_pieces = make_fast_div(1);
+    static const int split_min_chunks = env_int("CAST_SPLIT_MIN_CHUNKS", 2 * kPieceChunks + 1);
     int block_waves = kBlockWaves;
     int per_row = n_segments;
     if (per_row == 0 && ld != cols) {
         // strided rows, no scaling: cut every row into equal pieces that start on mask words
         for (int k = 1; k <= 64 && per_row == 0; ++k)
-            if (cols % k == 0 && (cols / k) % 32 == 0 && cols / k <= 4096) per_row = k;
+            if (cols % k == 0 && (cols / k) % 32 == 0 && cols / k <= piece_len) per_row = k;
         if (per_row == 0 && cols % 32 == 0 && cols < ((int64_t)1 << 28)) per_row = 1;
     }
     if (per_row > 0) {
@@ -482,8 +546,31 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments)
         p.vec = cols % per_row == 0 && g.span_len % 32 == 0 && g.span_len < ((int64_t)1 << 28) && ld % 4 == 0 &&
                 g.num_spans < ((int64_t)1 << 31);
         const int64_t chunks = (g.span_len + kChunk - 1) / kChunk;
-        while (g.waves_per_span < kMaxBlockWaves && chunks > g.waves_per_span) g.waves_per_span *= 2;
-        if (g.waves_per_span > block_waves) block_waves = g.waves_per_span;
+        const int64_t pieces = (chunks + kPieceChunks - 1) / kPieceChunks;
+        g.segment_len = g.span_len;
+        if (allow_split && p.vec && n_segments > 0 && chunks >= split_min_chunks && pieces > 1 &&
+            g.num_spans * pieces < ((int64_t)1 << 31) && pieces * per_row < ((int64_t)1 << 24)) {
+            // More chunks than the wavefronts of a workgroup: with several chunks per wavefront the
+            // workgroups are few, large and long-lived, and the compute units run half empty.  Cut the
+            // segment into pieces of kPieceChunks chunks, one workgroup and one chunk per wavefront each.
+            g.pieces_per_segment = (int)pieces;
+            g.div_pieces = make_fast_div((uint32_t)pieces);
+            g.span_len = (int64_t)kPieceChunks * kChunk;
+            g.spans_per_row = per_row * (int)pieces;
+            g.div_spans_per_row = make_fast_div((uint32_t)g.spans_per_row);
+            p.segments = g.num_spans;
+            g.num_spans *= pieces;
+            g.waves_per_span = kPieceChunks;
+            block_waves = kPieceChunks;
+        } else {
+            if (chunks <= kBlockWaves) {
+                while (chunks > g.waves_per_span) g.waves_per_span *= 2;     // 1, 2 or 4: several spans per workgroup
+            } else {
+                // one span per workgroup: a wavefront per chunk, or all 16 with one or more chunks each
+                g.waves_per_span = chunks < kMaxBlockWaves ? (int)chunks : kMaxBlockWaves;
+                block_waves = g.waves_per_span;
+            }
+        }
     } else {
         g.spans_per_row = 0;   // flat: the matrix is one contiguous array
         p.vec = cols % 32 == 0 && ld == cols;
@@ -492,9 +579,12 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments)
         g.span_len = len;
         g.num_spans = (g.total + len - 1) / len;
     }
-    if (forced_p == 1 || forced_p == 2 || forced_p == 4 || forced_p == 8 || forced_p == 16) g.waves_per_span = forced_p;
-    if (forced_bw == 4 || forced_bw == 8 || forced_bw == 16) block_waves = forced_bw;
+    if (g.pieces_per_segment == 1) {
+        if (forced_p == 1 || forced_p == 2 || forced_p == 4 || forced_p == 8 || forced_p == 16) g.waves_per_span = forced_p;
+        if (forced_bw == 4 || forced_bw == 8 || forced_bw == 16) block_waves = forced_bw;
+    }
     if (block_waves < g.waves_per_span) block_waves = g.waves_per_span;
+    if (block_waves % g.waves_per_span) block_waves = g.waves_per_span;
     p.block_threads = block_waves * kWave;
     const int64_t spans_per_block = block_waves / g.waves_per_span;
     p.grid = (unsigned)((g.num_spans + spans_per_block - 1) / spans_per_block);
@@ -532,11 +622,18 @@ struct VecLaunch {
     unsigned long long tasks;
     uint32_t blocks_per_matrix;
     int log2_run;
+    bool split;
 };
 
 template <int M, bool BF16, bool REFRESH, bool SCALED>
 static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
+    if constexpr (SCALED) {
+        if (l.split) {
+            hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true>), dim3(l.grid_x), dim3(l.block_threads), 0, st, a);
+            return;
+        }
+    }
     if (l.tickets)
         hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), dim3(l.block_threads), 0, st, a,
                            QueueArgs{l.tickets, (uint32_t)l.tasks, l.blocks_per_matrix, make_fast_div(l.blocks_per_matrix), l.log2_run});
@@ -581,7 +678,7 @@ cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, 
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_spans(rows, cols, ld, n_segments);
+    const SpanPlan p = plan_spans(rows, cols, ld, n_segments, false);
     const bool bf16 = grad_dtype == CAST_BF16;
     if (p.vec) {
         if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.geom);
@@ -596,17 +693,29 @@ cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, 
 
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              int64_t ld, const cast_adams_config *cfg, hipStream_t st)
+                              int64_t ld, const cast_adams_config *cfg, PieceArea *area, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_spans(rows, cols, ld, cfg->scale_segments);
     const bool bf16 = cfg->grad_dtype == CAST_BF16;
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = scale != nullptr;
+    SpanPlan p = plan_spans(rows, cols, ld, cfg->scale_segments, area != nullptr && scale_grad != nullptr);
+    if (p.geom.pieces_per_segment > 1 && (uint64_t)p.geom.num_spans > area->floats)
+        p = plan_spans(rows, cols, ld, cfg->scale_segments, false);       // no room for the pieces' sums
+    const bool split = p.geom.pieces_per_segment > 1;
     if (p.vec) {
-        SpanArgs a{{w, grad, m, v, mask_bits, scale, scale_grad, 0}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
-        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0}, a, st);
-        return launch_status();
+        SpanArgs a{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr}, as_const_table(nullptr), p.geom,
+                   make_scalars(cfg)};
+        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0, split}, a, st);
+        if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+        if (split) {      // this matrix's part of the area is now in use until the pieces have been added up
+            const PieceJob job{area->base, scale_grad, p.segments, p.geom.pieces_per_segment};
+            const uint64_t used = ((uint64_t)p.geom.num_spans + 3) & ~(uint64_t)3;
+            area->base += used;
+            area->floats -= used < area->floats ? used : area->floats;
+            return static_cast<PieceJobQueue *>(area->jobs)->add(job, st);
+        }
+        return CAST_OK;
     }
     // odd shapes: dL/dA first (it needs the incoming weights), then the element pass
     if (scaled && scale_grad) {
@@ -624,11 +733,30 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     return launch_status();
 }
 
-// workspace of a list call: the table of buffer sets, then one ticket counter per launch
-size_t multi_workspace_bytes(int count)
+// Workspace of a list call: the table of buffer sets, one ticket counter per launch of the work
+// queue, then room for the piece sums of every matrix with a split plan.
+struct MultiLayout {
+    size_t table_bytes, counter_bytes;
+    uint64_t piece_floats;
+    size_t total() const { return table_bytes + counter_bytes + (size_t)piece_floats * sizeof(float); }
+};
+
+static MultiLayout multi_layout(const cast_tensor *ts, int count, const cast_adams_config *cfg)
 {
     const size_t n = (size_t)(count > 0 ? count : 0);
-    return n * sizeof(TensorPtrs) + ((n * sizeof(unsigned long long) + 15) & ~(size_t)15);
+    MultiLayout l{n * sizeof(TensorPtrs), (n * sizeof(unsigned long long) + 15) & ~(size_t)15, 0};
+    if (ts && cfg && cfg->scale_segments > 0 && !(cfg->flags & CAST_FLAG_WORK_QUEUE))
+        for (size_t i = 0; i < n; ++i) {
+            if (ts[i].rows <= 0 || ts[i].cols <= 0 || !ts[i].scale_grad) continue;
+            const SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments, true);
+            if (p.geom.pieces_per_segment > 1) l.piece_floats += ((uint64_t)p.geom.num_spans + 3) & ~(uint64_t)3;
+        }
+    return l;
+}
+
+size_t multi_workspace_bytes(const cast_tensor *ts, int count, const cast_adams_config *cfg)
+{
+    return multi_layout(ts, count, cfg).total();
 }
 
 static int device_compute_units()
@@ -664,7 +792,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     for (int i = 0; i < count; ++i) {
         if (taken[i] || ts[i].rows == 0 || ts[i].cols == 0) continue;
         const SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments);
-        if (!p.vec || !use_queue || waves_per_cu <= 0) continue;
+        if (!p.vec || !use_queue || waves_per_cu <= 0) continue;     // (the work queue never uses split plans)
         Group g{(int)order.size(), 0, p};
         // tickets are 32-bit task numbers inside the kernel
         const int fit = (int)(((int64_t)1 << 31) / p.grid);
@@ -676,13 +804,14 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
             }
         groups.push_back(g);
     }
+    const MultiLayout layout = multi_layout(ts, count, cfg);
     if (!order.empty()) {
-        const size_t table_bytes = (size_t)count * sizeof(TensorPtrs);
+        const size_t table_bytes = layout.table_bytes;
         std::vector<unsigned char> image(table_bytes + groups.size() * sizeof(unsigned long long), 0);
         TensorPtrs *table = reinterpret_cast<TensorPtrs *>(image.data());
         for (size_t k = 0; k < order.size(); ++k) {
             const cast_tensor &t = ts[order[k]];
-            table[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, 0};
+            table[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, nullptr};
         }
         // pageable source: the runtime stages it before returning, the copy itself is ordered on the stream
         if (hipMemcpyAsync(workspace, image.data(), image.size(), hipMemcpyHostToDevice, st) != hipSuccess)
@@ -697,18 +826,22 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
             if (blocks_per_cu < 1) blocks_per_cu = 1;
             unsigned long long resident = (unsigned long long)device_compute_units() * blocks_per_cu;
             if (resident > tasks) resident = tasks;
-            const VecLaunch l{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid, log2_run};
+            const VecLaunch l{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid, log2_run, false};
             launch_vec_any(cfg->m_group, bf16, refresh, scaled, l, a, st);
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         }
     }
+    PieceJobQueue jobs;
+    PieceArea area{reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes),
+                   layout.piece_floats, &jobs};
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
-        cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg, st);
+        cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
+                                           layout.piece_floats ? &area : nullptr, st);
         if (rc != CAST_OK) return rc;
     }
-    return CAST_OK;
+    return jobs.flush(st);
 }
 
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n)

@@ -129,10 +129,13 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
 {
     const cast_status rc = validate_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg);
     if (rc != CAST_OK) return rc;
-    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, static_cast<hipStream_t>(stream));
+    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, nullptr, static_cast<hipStream_t>(stream));
 }
 
-size_t cast_adams_multi_workspace_bytes(int count) { return multi_workspace_bytes(count); }
+size_t cast_adams_multi_workspace_bytes(const cast_tensor *tensors, int count, const cast_adams_config *cfg)
+{
+    return multi_workspace_bytes(tensors, count, cfg);
+}
 
 cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                   void *workspace, size_t workspace_bytes, void *stream)
@@ -142,12 +145,12 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
     if (count == 0) return CAST_OK;
     if (!tensors || !workspace) return CAST_ERR_NULL;
     if (!aligned(workspace, 16)) return CAST_ERR_ALIGN;
-    if (workspace_bytes < multi_workspace_bytes(count)) return CAST_ERR_SHAPE;
     for (int i = 0; i < count; ++i) {    // all or nothing: nothing is launched if any matrix is rejected
         const cast_tensor &t = tensors[i];
         const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg);
         if (rc != CAST_OK) return rc;
     }
+    if (workspace_bytes < multi_workspace_bytes(tensors, count, cfg)) return CAST_ERR_SHAPE;
     return launch_adams_step_multi(tensors, count, cfg, workspace, static_cast<hipStream_t>(stream));
 }
 

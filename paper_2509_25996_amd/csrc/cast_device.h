@@ -19,8 +19,9 @@ constexpr int kLaneElems = 4;                    // fp32 entries per lane per ch
 constexpr int kChunk = kWave * kLaneElems;       // 256 entries per wavefront per chunk
 constexpr int kBlockThreads = 256;
 constexpr int kBlockWaves = kBlockThreads / kWave;
-constexpr int kMaxBlockWaves = 16;               // the step kernels run with 4, 8 or 16 wavefronts per workgroup
+constexpr int kMaxBlockWaves = 16;               // the step kernels run with 4 to 16 wavefronts per workgroup
 constexpr int kMaxBlockThreads = kMaxBlockWaves * kWave;
+constexpr int kPieceChunks = 8;                  // split plans: chunks (= wavefronts) per piece of a row segment
 
 // ---- how a matrix is cut into spans ---------------------------------------------------------
 // A span is the unit of work of one wavefront (or of 2..16 cooperating wavefronts of one
@@ -62,13 +63,19 @@ struct SpanGeom {
     int64_t span_len;       // entries per span (the last span of a flat plan may be shorter)
     int64_t num_spans;
     int spans_per_row;      // 0: flat plan (the matrix is one contiguous array, spans ignore rows)
-    int waves_per_span;     // 1, 2, 4, 8 or 16
+    int waves_per_span;     // 1, 2 or 4 (several spans per workgroup), or 5..16 = the workgroup's wavefronts
     FastDivU32 div_spans_per_row;
+    // Split plan (pieces_per_segment > 1): a row segment of segment_len entries is cut into pieces of
+    // span_len entries (the last one shorter), one span each; spans_per_row then counts pieces.
+    int pieces_per_segment;
+    int64_t segment_len;
+    FastDivU32 div_pieces;
 };
 
-// Which span a wavefront works on and its place among the cooperating wavefronts.  The number
-// of cooperating wavefronts is a power of two, so this is shifts and masks on scalar registers
-// (a runtime division would be carried out, and leave its result, in vector registers).
+// Which span a wavefront works on and its place among the cooperating wavefronts.  Either the
+// whole workgroup shares one span, or the number of cooperating wavefronts is a power of two, so
+// this is shifts and masks on scalar registers (a runtime division would be carried out, and
+// leave its result, in vector registers).
 struct SpanSlot {
     int64_t span;
     int sub;
@@ -76,8 +83,13 @@ struct SpanSlot {
 
 __device__ __forceinline__ SpanSlot span_slot(const SpanGeom &g, int64_t block, int wave, int block_waves)
 {
-    const int shift = __builtin_ctz((unsigned)g.waves_per_span);
     SpanSlot s;
+    if (g.waves_per_span == block_waves) {     // one span per workgroup: any number of wavefronts
+        s.span = block;
+        s.sub = wave;
+        return s;
+    }
+    const int shift = __builtin_ctz((unsigned)g.waves_per_span);
     s.span = block * (block_waves >> shift) + (wave >> shift);
     s.sub = wave & (g.waves_per_span - 1);
     return s;
@@ -102,6 +114,23 @@ __device__ __forceinline__ SpanOrigin span_origin(const SpanGeom &g, int64_t spa
         o.len = (int)g.span_len;
         if (g.row_gap != 0) o.state_begin += (int64_t)fast_div((uint32_t)span, g.div_spans_per_row) * g.row_gap;
     }
+    return o;
+}
+
+// Split plan: span = piece number; `segment` tells which row segment (scale factor) it belongs to.
+__device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, int64_t span, int64_t &segment)
+{
+    SpanOrigin o{0, 0, 0};
+    segment = 0;
+    if (span >= g.num_spans) return o;
+    const uint32_t seg = fast_div((uint32_t)span, g.div_pieces);
+    const int64_t done = (int64_t)((uint32_t)span - seg * (uint32_t)g.pieces_per_segment) * g.span_len;
+    const int64_t rem = g.segment_len - done;
+    segment = seg;
+    o.len = (int)(rem < g.span_len ? rem : g.span_len);
+    o.dense_begin = (int64_t)seg * g.segment_len + done;
+    o.state_begin = o.dense_begin;
+    if (g.row_gap != 0) o.state_begin += (int64_t)fast_div((uint32_t)span, g.div_spans_per_row) * g.row_gap;
     return o;
 }
 

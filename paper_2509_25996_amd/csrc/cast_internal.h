@@ -15,15 +15,27 @@ namespace cast {
 struct SpanPlan {
     bool vec;            // the vector kernels apply (spans start on mask-word boundaries)
     SpanGeom geom;
-    int block_threads;   // 256, 512 or 1024
+    int block_threads;   // a multiple of 64, from 256 to 1024
     unsigned grid;       // workgroups
+    int64_t segments;    // split plans: row segments of the matrix (rows * n), else 0
 };
 
-SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments);
+// allow_split: row segments of more than 16 chunks of 256 entries may be cut into pieces with a
+// workgroup each; the caller then supplies a PieceArea for the pieces' dL/dA sums.
+SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool allow_split = false);
+
+// Device memory for the piece sums of split plans: what is left of it, and who collects the
+// second halves (adding the pieces up) of the matrices that took a part.
+struct PieceArea {
+    float *base;
+    uint64_t floats;
+    void *jobs;
+};
 
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              int64_t ld, const cast_adams_config *cfg, hipStream_t stream);
+                              int64_t ld, const cast_adams_config *cfg, PieceArea *area,
+                              hipStream_t stream);
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad,
                               hipStream_t stream);
@@ -40,7 +52,7 @@ cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const u
                               int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
                               double *l1, hipStream_t stream);
 cast_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
-size_t multi_workspace_bytes(int count);
+size_t multi_workspace_bytes(const cast_tensor *tensors, int count, const cast_adams_config *cfg);
 cast_status launch_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                     void *workspace, hipStream_t stream);
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
