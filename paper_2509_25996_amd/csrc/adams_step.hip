@@ -362,11 +362,12 @@ struct PieceJobQueue {
         return launch_status();
     }
 
-    cast_status add(const PieceJob &j, hipStream_t st)
+    bool full() const { return count == kMaxPieceJobs; }
+
+    void add(const PieceJob &j)      // not when full()
     {
         pending.job[count++] = j;
         if (j.segments > most_segments) most_segments = j.segments;
-        return count == kMaxPieceJobs ? flush(st) : CAST_OK;
     }
 };
 
@@ -713,7 +714,7 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
             const uint64_t used = ((uint64_t)p.geom.num_spans + 3) & ~(uint64_t)3;
             area->base += used;
             area->floats -= used < area->floats ? used : area->floats;
-            return static_cast<PieceJobQueue *>(area->jobs)->add(job, st);
+            static_cast<PieceJobQueue *>(area->jobs)->add(job);
         }
         return CAST_OK;
     }
@@ -837,6 +838,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
+        if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;     // make room
         cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
                                            layout.piece_floats ? &area : nullptr, st);
         if (rc != CAST_OK) return rc;
