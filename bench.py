@@ -52,6 +52,7 @@ class Model:
         self.list = None
         self.row_splits = 1
         self.flags = 0
+        self.rule = 0
         self.launches = len(self.shapes)
         for i, (_, r, c) in enumerate(self.shapes):
             w = synth.device_gaussian((r, c), 0.02, torch.float32, 1000 + i, dev)
@@ -67,18 +68,20 @@ class Model:
                                A=torch.ones((r, self.segments), device=dev),
                                gA=torch.zeros((r, self.segments), device=dev)))
 
-    def tensor_list(self, B, scaled: bool, dev, queue: bool):
+    def tensor_list(self, B, scaled: bool, dev, queue: bool, copies=None):
         """Descriptors for the one-call-per-step entry point, marshalled once."""
         self.list = B.TensorList([dict(w=x["w"], grad=x["g"], m=x["m"], v=x["v"], mask=x["mask"],
-                                       scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None)
-                                  for x in self.t], dev)
+                                       scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None,
+                                       compute_copy=None if copies is None else copies[i],
+                                       copy_scale=x["A"] if scaled and copies is not None else None)
+                                  for i, x in enumerate(self.t)], dev)
         self.flags = B.FLAG_WORK_QUEUE if queue else 0
         if queue:
             self.launches = len({(x["w"].shape, x["w"].stride(0)) for x in self.t})   # one launch per distinct shape
 
     def step(self, B, t: int, scaled: bool):
         cfg = B.iteration_config(t, TOTAL_STEPS, mask_period=MASK_PERIOD, lr=LR, lambda_=LAMBDA,
-                                 scale_segments=self.segments if scaled else 0, flags=self.flags)
+                                 scale_segments=self.segments if scaled else 0, flags=self.flags, rule=self.rule)
         if self.list is not None:
             B.cast_adams_step_multi(self.list, cfg)
         else:
@@ -235,6 +238,35 @@ def main():
         pc_ms = e0.elapsed_time(e1)
         extra["project_compress_ms"] = round(pc_ms, 3)
         extra["project_compress_GBs"] = round(6.125 * model.params / (pc_ms * 1e-3) / 1e9, 1)
+        del outs
+        if model.list is not None:
+            # the widened forms of the step, over the same set and through the same list call: a comparison
+            # rule (Eq. 10), and the step that also writes the bf16 weights of the next forward pass
+            # (28.125 B/param: 2 more bytes written)
+            def timed(flags_rule, reps=10):
+                t_ = 1
+                model.rule = flags_rule
+                for _ in range(2):
+                    model.step(B, t_, scaled)
+                e0.record()
+                for _ in range(reps):
+                    model.step(B, t_, scaled)      # t_ = 1: non-refresh steps
+                e1.record()
+                torch.cuda.synchronize()
+                model.rule = 0
+                return e0.elapsed_time(e1) / reps
+            copies = [torch.empty(x["w"].shape, dtype=torch.bfloat16, device=dev) for x in model.t]
+            model.tensor_list(B, scaled, dev, queue=False, copies=copies)
+            ms = timed(0)
+            extra["emit_compute_copy_ms_step"] = round(ms, 3)
+            extra["emit_compute_copy_GBs"] = round((BYTES_PER_PARAM + 2) * model.params / (ms * 1e-3) / 1e9, 1)
+            del copies
+            model.tensor_list(B, scaled, dev, queue=False)
+            for name, rule in (("adamw_l1", B.RULE_ADAMW_L1), ("adam_l1", B.RULE_ADAM_L1), ("additive", B.RULE_ADDITIVE),
+                               ("masked_frozen", B.RULE_MASKED_FROZEN)):
+                ms = timed(rule)
+                extra[f"rule_{name}_ms_step"] = round(ms, 3)
+                extra[f"rule_{name}_GBs"] = round(BYTES_PER_PARAM * model.params / (ms * 1e-3) / 1e9, 1)
 
     out = {"metric": "AdamS N:M step Gparams/s at LLaMA2-7B shape; % of MI355X peak HBM BW",
            "value": round(value, 2), "unit": "Gparams/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

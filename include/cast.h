@@ -62,6 +62,24 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  * per matrix.  Same results bit for bit. */
 #define CAST_FLAG_WORK_QUEUE 2u
 
+/* Update rules.  CAST_RULE_ADAMS is the paper's method (Algorithm 1, Eq. 8); the others are the
+ * rules it is set against, for ablations.  In all of them the decay acts only on entries whose
+ * mask bit is 0 and has strength alpha * lambda, like the second term of Eq. 7 (Eq. 9 and 10 are
+ * printed for one always-decayed parameter with strength lambda: alpha = 1 gives that form).
+ *   ADAMW_L1       Eq. 9:  mu, v from g and g^2;  w -= lr * (mu^/(sqrt(v^)+eps) + alpha*lambda*Sign(w))
+ *   ADAM_L1        Eq. 10: g~ = g + alpha*lambda*Sign(w);  mu, v from g~ and g~^2
+ *   ADDITIVE       Eq. 8 with mu~ = mu + alpha*lambda*Sign(w): the decay is added to the momentum
+ *                  instead of being traded against it (the additive decay of Sec. 4.1.2)
+ *   MASKED_FROZEN  sparsity-aware fine-tuning (Sec. 5.7): entries with mask bit 0 keep w, mu, v;
+ *                  the others follow Eq. 8 with mu~ = mu */
+enum {
+    CAST_RULE_ADAMS = 0,
+    CAST_RULE_ADAMW_L1 = 1,
+    CAST_RULE_ADAM_L1 = 2,
+    CAST_RULE_ADDITIVE = 3,
+    CAST_RULE_MASKED_FROZEN = 4
+};
+
 /* Inputs of one AdamS iteration (Algorithm 1).  All scalars are used as given, in fp32. */
 typedef struct {
     int32_t  n_keep;         /* N                                                            */
@@ -78,6 +96,7 @@ typedef struct {
     int32_t  scale_segments; /* n of Eq. 12; 0 = no weight scaling                           */
     int32_t  grad_dtype;     /* CAST_F32 or CAST_BF16                                        */
     uint32_t flags;          /* 0, or an OR of CAST_FLAG_*                                   */
+    int32_t  rule;           /* CAST_RULE_*; 0 = AdamS                                       */
 } cast_adams_config;
 
 const char *cast_status_str(cast_status s);
@@ -119,6 +138,25 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
                             int64_t ld, const cast_adams_config *cfg /* HOST */, void *stream);
 
 /*
+ * The same iteration, which in the same pass also writes the weights the next forward pass
+ * multiplies with (Algorithm 2 applies the weight scaling of Eq. 12 before every forward pass):
+ *   compute_copy  DEVICE out  bf16 dense [rows, cols], 16-byte aligned:
+ *                             round-to-nearest-even of copy_scale[r, s] * w_new (one fp32 multiply),
+ *                             or of w_new itself when copy_scale is NULL
+ *   copy_scale    DEVICE in   fp32 [rows, n] with n = cfg->scale_segments, or NULL (required NULL
+ *                             when n = 0).  It may be `scale` itself.  dL/dA of this iteration is
+ *                             only produced by this very launch, so the A folded here cannot have
+ *                             seen it yet: the copy is exact for a frozen A or for an A whose update
+ *                             lags one iteration; otherwise call cast_weight_scale after updating A.
+ * Costs 2 more bytes per parameter (28.125 with bf16 gradients) instead of a separate pass that
+ * reads w again (6 bytes per parameter).
+ */
+cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
+                                 const float *scale, float *scale_grad, const float *copy_scale,
+                                 void *compute_copy, int64_t rows, int64_t cols, int64_t ld,
+                                 const cast_adams_config *cfg /* HOST */, void *stream);
+
+/*
  * The same iteration over a list of matrices that share one configuration (all linear weights
  * of a model in one call): validated as a whole before anything is launched, then stepped one
  * launch per matrix, or, with CAST_FLAG_WORK_QUEUE, one work-queue launch per group of matrices
@@ -143,6 +181,8 @@ typedef struct {
     const float *scale;
     float *scale_grad;
     int64_t rows, cols, ld;
+    void *compute_copy;         /* as in cast_adams_step_emit, or NULL */
+    const float *copy_scale;    /* as in cast_adams_step_emit, or NULL */
 } cast_tensor;
 
 size_t cast_adams_multi_workspace_bytes(const cast_tensor *tensors /* HOST */, int count,

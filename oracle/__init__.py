@@ -37,7 +37,11 @@ class _Cfg(C.Structure):
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("lambda_", C.c_float), ("alpha", C.c_float), ("bias_corr1", C.c_float),
                 ("bias_corr2", C.c_float), ("refresh_mask", C.c_int32),
-                ("scale_segments", C.c_int32), ("v_from_grad", C.c_int32)]
+                ("scale_segments", C.c_int32), ("v_from_grad", C.c_int32), ("rule", C.c_int32)]
+
+
+# update rules (the enum of cast_oracle.c)
+RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = range(5)
 
 
 @dataclass
@@ -56,11 +60,12 @@ class AdamsCfg:
     refresh_mask: int = 1
     scale_segments: int = 0
     v_from_grad: int = 0
+    rule: int = 0
 
     def c_struct(self) -> _Cfg:
         return _Cfg(self.n_keep, self.m_group, self.lr, self.beta1, self.beta2, self.eps,
                     self.lambda_, self.alpha, self.bias_corr1, self.bias_corr2,
-                    self.refresh_mask, self.scale_segments, self.v_from_grad)
+                    self.refresh_mask, self.scale_segments, self.v_from_grad, self.rule)
 
 
 def iteration_scalars(t: int, total_steps: int, beta1: float, beta2: float):
@@ -89,7 +94,7 @@ def lib():
         L.oracle_unpack_mask_bits.restype = None
         for f in (L.oracle_adams_step_f64, L.oracle_adams_step_f32):
             f.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, C.POINTER(_Cfg), C.c_int]
-        L.oracle_adams_elements_state64.argtypes = [vp, vp, vp, vp, vp, i64] + [C.c_double] * 8 + [C.c_int]
+        L.oracle_adams_elements_state64.argtypes = [vp, vp, vp, vp, vp, i64] + [C.c_double] * 8 + [C.c_int, C.c_int]
         L.oracle_weight_scale.argtypes = [vp, vp, i64, i64, C.c_int, vp]
         L.oracle_weight_scale_grad.argtypes = [vp, vp, i64, i64, C.c_int, vp]
         L.oracle_meta_field_bits.argtypes = [C.c_int, C.c_int]
@@ -167,14 +172,14 @@ def adams_step(w, grad, mu, v, keep, cfg: AdamsCfg, A=None, want_gA=True, arithm
 
 
 def adams_elements_state64(theta, grad, mu, v, m_bits, *, lr, beta1, beta2, eps, lambda_, alpha,
-                           bias_corr1, bias_corr2, v_from_grad=0):
+                           bias_corr1, bias_corr2, v_from_grad=0, rule=0):
     """Algorithm 1's per-parameter body on flat float64 arrays, in place."""
     for a in (theta, grad, mu, v):
         assert a.dtype == np.float64 and a.flags.c_contiguous
     assert m_bits.dtype == np.uint8
     lib().oracle_adams_elements_state64(_p(theta), _p(grad), _p(mu), _p(v), _p(m_bits), theta.size,
                                         lr, beta1, beta2, eps, lambda_, alpha, bias_corr1,
-                                        bias_corr2, v_from_grad)
+                                        bias_corr2, v_from_grad, rule)
 
 
 def weight_scale(w, A):

@@ -49,7 +49,22 @@ typedef struct {
     int32_t refresh_mask;   /* 1: recompute the mask from the incoming weights (Eq. 6)  */
     int32_t scale_segments; /* n of Eq. 12; 0 = gradient is already w.r.t. W            */
     int32_t v_from_grad;    /* 1: second moment from g^2 (Eq. 9 form, test pin only)    */
+    int32_t rule;           /* which update rule; 0 = AdamS (Eq. 8), see RULE_* below   */
 } oracle_adams_cfg;
+
+/* The update rules the paper sets AdamS against (Sec. 4.1.2, 4.1.3, 5.7).  In all of them the
+ * decay acts only where the mask bit is 0 and has strength alpha*lambda, like Eq. 7's second
+ * term (Eq. 9 and 10 are printed for a single always-decayed parameter with strength lambda:
+ * alpha = 1 and mask bit 0 give exactly the printed forms). */
+enum {
+    RULE_ADAMS = 0,          /* Eq. 8                                                         */
+    RULE_ADAMW_L1 = 1,       /* Eq. 9: decay added to the update, outside the moments          */
+    RULE_ADAM_L1 = 2,        /* Eq. 10: decay added to the gradient, inside both moments       */
+    RULE_ADDITIVE = 3,       /* Eq. 8 with mu~ = mu + alpha*lambda*Sign: decay added to, not   */
+                             /* traded against, the momentum (the "additive decay" of Fig. 3) */
+    RULE_MASKED_FROZEN = 4   /* sparsity-aware fine-tuning (Sec. 5.7): entries with mask bit 0 */
+                             /* are not updated at all; the others follow Eq. 8 (mu~ = mu)     */
+};
 
 /* ------------------------------------------------------------------------------------ */
 /* Eq. 6 with the tie rule above.                                                        */
@@ -112,16 +127,51 @@ void oracle_unpack_mask_bits(const uint32_t *words, int64_t rows, int64_t cols, 
 typedef struct {
     double lr, beta1, beta2, eps, lambda, alpha, bias_corr1, bias_corr2;
     int v_from_grad;
+    int rule;
 } adams_params_f64;
 
 static double sign_f64(double x) { return (double)(x > 0.0) - (double)(x < 0.0); }
 
+/* Eq. 9 (decay after the adaptive step) and Eq. 10 (decay inside the gradient), real arithmetic. */
+static void adamw_l1_element_f64(double theta_prev, double g, double mu_prev, double v_prev, int m_bit,
+                                 const adams_params_f64 *p, double *theta, double *mu, double *v)
+{
+    double mu_t = p->beta1 * mu_prev + (1.0 - p->beta1) * g;
+    double v_t = p->beta2 * v_prev + (1.0 - p->beta2) * g * g;
+    double mu_hat = mu_t / p->bias_corr1;
+    double v_hat = v_t / p->bias_corr2;
+    double update = mu_hat / (sqrt(v_hat) + p->eps);
+    if (m_bit == 0) update += p->alpha * p->lambda * sign_f64(theta_prev);
+    *theta = theta_prev - p->lr * update;
+    *mu = mu_t;
+    *v = v_t;
+}
+
+static void adam_l1_element_f64(double theta_prev, double g, double mu_prev, double v_prev, int m_bit,
+                                const adams_params_f64 *p, double *theta, double *mu, double *v)
+{
+    double g_tilde = g;
+    if (m_bit == 0) g_tilde += p->alpha * p->lambda * sign_f64(theta_prev);
+    double mu_t = p->beta1 * mu_prev + (1.0 - p->beta1) * g_tilde;
+    double v_t = p->beta2 * v_prev + (1.0 - p->beta2) * g_tilde * g_tilde;
+    double mu_hat = mu_t / p->bias_corr1;
+    double v_hat = v_t / p->bias_corr2;
+    *theta = theta_prev - p->lr * (mu_hat / (sqrt(v_hat) + p->eps));
+    *mu = mu_t;
+    *v = v_t;
+}
+
 static void adams_element_f64(double theta_prev, double g, double mu_prev, double v_prev, int m_bit,
                               const adams_params_f64 *p, double *theta, double *mu, double *v)
 {
+    if (p->rule == RULE_ADAMW_L1) { adamw_l1_element_f64(theta_prev, g, mu_prev, v_prev, m_bit, p, theta, mu, v); return; }
+    if (p->rule == RULE_ADAM_L1) { adam_l1_element_f64(theta_prev, g, mu_prev, v_prev, m_bit, p, theta, mu, v); return; }
+    if (p->rule == RULE_MASKED_FROZEN && m_bit == 0) { *theta = theta_prev; *mu = mu_prev; *v = v_prev; return; }
     double mu_t = p->beta1 * mu_prev + (1.0 - p->beta1) * g;
     double mu_tilde;
-    if (m_bit == 0)
+    if (m_bit == 0 && p->rule == RULE_ADDITIVE)
+        mu_tilde = mu_t + p->alpha * p->lambda * sign_f64(theta_prev);
+    else if (m_bit == 0)
         mu_tilde = (1.0 - p->alpha) * mu_t + p->alpha * p->lambda * sign_f64(theta_prev);
     else
         mu_tilde = mu_t;
@@ -142,16 +192,75 @@ typedef struct {
     float lr, beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
     float one_minus_alpha, alpha_lambda, bias_corr1, bias_corr2;
     int v_from_grad;
+    int rule;
 } adams_params_f32;
 
-static void adams_element_f32(float theta_prev, float g, float mu_prev, float v_prev, int m_bit,
-                              const adams_params_f32 *p, float *theta, float *mu, float *v)
+static float sign_f32(float x) { return (float)(x > 0.0f) - (float)(x < 0.0f); }
+
+/* Eq. 9 and Eq. 10, one fp32 rounding per operation in the order written. */
+static void adamw_l1_element_f32(float theta_prev, float g, float mu_prev, float v_prev, int m_bit,
+                                 const adams_params_f32 *p, float *theta, float *mu, float *v)
 {
     float t0 = p->beta1 * mu_prev;
     float t1 = p->one_minus_beta1 * g;
     float mu_t = t0 + t1;
-    float mu_tilde;
+    float second = g * g;
+    float s0 = p->beta2 * v_prev;
+    float s1 = p->one_minus_beta2 * second;
+    float v_t = s0 + s1;
+    float mu_hat = mu_t / p->bias_corr1;
+    float v_hat = v_t / p->bias_corr2;
+    float denom = sqrtf(v_hat) + p->eps;
+    float update = mu_hat / denom;
     if (m_bit == 0) {
+        float decay = p->alpha_lambda * sign_f32(theta_prev);
+        update = update + decay;
+    }
+    float step = p->lr * update;
+    *theta = theta_prev - step;
+    *mu = mu_t;
+    *v = v_t;
+}
+
+static void adam_l1_element_f32(float theta_prev, float g, float mu_prev, float v_prev, int m_bit,
+                                const adams_params_f32 *p, float *theta, float *mu, float *v)
+{
+    float g_tilde = g;
+    if (m_bit == 0) {
+        float decay = p->alpha_lambda * sign_f32(theta_prev);
+        g_tilde = g + decay;
+    }
+    float t0 = p->beta1 * mu_prev;
+    float t1 = p->one_minus_beta1 * g_tilde;
+    float mu_t = t0 + t1;
+    float second = g_tilde * g_tilde;
+    float s0 = p->beta2 * v_prev;
+    float s1 = p->one_minus_beta2 * second;
+    float v_t = s0 + s1;
+    float mu_hat = mu_t / p->bias_corr1;
+    float v_hat = v_t / p->bias_corr2;
+    float denom = sqrtf(v_hat) + p->eps;
+    float q = mu_hat / denom;
+    float step = p->lr * q;
+    *theta = theta_prev - step;
+    *mu = mu_t;
+    *v = v_t;
+}
+
+static void adams_element_f32(float theta_prev, float g, float mu_prev, float v_prev, int m_bit,
+                              const adams_params_f32 *p, float *theta, float *mu, float *v)
+{
+    if (p->rule == RULE_ADAMW_L1) { adamw_l1_element_f32(theta_prev, g, mu_prev, v_prev, m_bit, p, theta, mu, v); return; }
+    if (p->rule == RULE_ADAM_L1) { adam_l1_element_f32(theta_prev, g, mu_prev, v_prev, m_bit, p, theta, mu, v); return; }
+    if (p->rule == RULE_MASKED_FROZEN && m_bit == 0) { *theta = theta_prev; *mu = mu_prev; *v = v_prev; return; }
+    float t0 = p->beta1 * mu_prev;
+    float t1 = p->one_minus_beta1 * g;
+    float mu_t = t0 + t1;
+    float mu_tilde;
+    if (m_bit == 0 && p->rule == RULE_ADDITIVE) {
+        float d1 = p->alpha_lambda * sign_f32(theta_prev);
+        mu_tilde = mu_t + d1;
+    } else if (m_bit == 0) {
         float sgn = (float)(theta_prev > 0.0f) - (float)(theta_prev < 0.0f);
         float d0 = p->one_minus_alpha * mu_t;
         float d1 = p->alpha_lambda * sgn;
@@ -176,6 +285,7 @@ static void adams_element_f32(float theta_prev, float g, float mu_prev, float v_
 static int check_step_shape(int64_t rows, int64_t cols, const oracle_adams_cfg *c)
 {
     if (rows < 0 || cols < 0) return -1;
+    if (c->rule < RULE_ADAMS || c->rule > RULE_MASKED_FROZEN) return -1;
     if (c->m_group < 2 || c->n_keep < 1 || c->n_keep >= c->m_group) return -1;
     if (cols % c->m_group) return -1;
     if (c->scale_segments < 0) return -1;
@@ -203,7 +313,7 @@ int oracle_adams_step_f64(float *w, const float *grad, float *mu, float *v, uint
     const int M = cfg->m_group, N = cfg->n_keep, n = cfg->scale_segments;
     if ((A != NULL) != (n > 0)) return -1;
     adams_params_f64 p = { cfg->lr, cfg->beta1, cfg->beta2, cfg->eps, cfg->lambda, cfg->alpha,
-                           cfg->bias_corr1, cfg->bias_corr2, cfg->v_from_grad };
+                           cfg->bias_corr1, cfg->bias_corr2, cfg->v_from_grad, cfg->rule };
     (void)nthreads;
 #pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
@@ -250,6 +360,7 @@ int oracle_adams_step_f32(float *w, const float *grad, float *mu, float *v, uint
     p.bias_corr1 = cfg->bias_corr1;
     p.bias_corr2 = cfg->bias_corr2;
     p.v_from_grad = cfg->v_from_grad;
+    p.rule = cfg->rule;
     (void)nthreads;
 #pragma omp parallel for num_threads(nthreads > 0 ? nthreads : 1) schedule(static)
     for (int64_t r = 0; r < rows; ++r) {
@@ -282,9 +393,9 @@ int oracle_adams_step_f32(float *w, const float *grad, float *mu, float *v, uint
 int oracle_adams_elements_state64(double *theta, const double *grad, double *mu, double *v,
                                   const uint8_t *m_bits, int64_t count, double lr, double beta1,
                                   double beta2, double eps, double lambda, double alpha,
-                                  double bias_corr1, double bias_corr2, int v_from_grad)
+                                  double bias_corr1, double bias_corr2, int v_from_grad, int rule)
 {
-    adams_params_f64 p = { lr, beta1, beta2, eps, lambda, alpha, bias_corr1, bias_corr2, v_from_grad };
+    adams_params_f64 p = { lr, beta1, beta2, eps, lambda, alpha, bias_corr1, bias_corr2, v_from_grad, rule };
     for (int64_t i = 0; i < count; ++i)
         adams_element_f64(theta[i], grad[i], mu[i], v[i], m_bits[i], &p, &theta[i], &mu[i], &v[i]);
     return 0;

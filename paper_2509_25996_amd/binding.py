@@ -16,10 +16,12 @@ LIB_PATH = os.environ.get("CAST_LIBRARY") or os.path.join(_HERE, "libcast.so")  
 CAST_F32, CAST_BF16 = 0, 1
 FLAG_V_FROM_GRAD = 1
 FLAG_WORK_QUEUE = 2
+RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = range(5)
 
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
-           "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi"]
+           "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi",
+           "cast_adams_step_emit"]
 
 
 class CastError(RuntimeError):
@@ -31,14 +33,15 @@ class CastError(RuntimeError):
 class _Tensor(C.Structure):
     _fields_ = [("w", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("mask_bits", C.c_void_p), ("scale", C.c_void_p), ("scale_grad", C.c_void_p),
-                ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64)]
+                ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("compute_copy", C.c_void_p), ("copy_scale", C.c_void_p)]
 
 
 class _Config(C.Structure):
     _fields_ = [("n_keep", C.c_int32), ("m_group", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float),
                 ("beta2", C.c_float), ("eps", C.c_float), ("lambda_", C.c_float), ("alpha", C.c_float),
                 ("bias_corr1", C.c_float), ("bias_corr2", C.c_float), ("refresh_mask", C.c_int32),
-                ("scale_segments", C.c_int32), ("grad_dtype", C.c_int32), ("flags", C.c_uint32)]
+                ("scale_segments", C.c_int32), ("grad_dtype", C.c_int32), ("flags", C.c_uint32), ("rule", C.c_int32)]
 
 
 @dataclass
@@ -58,11 +61,12 @@ class AdamsConfig:
     scale_segments: int = 0
     grad_dtype: int = CAST_F32
     flags: int = 0
+    rule: int = 0
 
     def c_struct(self) -> _Config:
         return _Config(self.n_keep, self.m_group, self.lr, self.beta1, self.beta2, self.eps, self.lambda_,
                        self.alpha, self.bias_corr1, self.bias_corr2, self.refresh_mask, self.scale_segments,
-                       self.grad_dtype, self.flags)
+                       self.grad_dtype, self.flags, self.rule)
 
 
 _lib = None
@@ -83,6 +87,7 @@ def load():
     L.cast_sizes.argtypes = [i64, i64, ci, ci, ci, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     L.cast_nm_select.argtypes = [vp, i64, i64, i64, ci, ci, vp, vp]
     L.cast_adams_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, C.POINTER(_Config), vp]
+    L.cast_adams_step_emit.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, C.POINTER(_Config), vp]
     L.cast_weight_scale.argtypes = [vp, vp, i64, i64, i64, ci, vp, ci, vp]
     L.cast_weight_scale_grad.argtypes = [vp, vp, ci, i64, i64, i64, ci, vp, vp]
     L.cast_nm_project_compress.argtypes = [vp, vp, ci, vp, i64, i64, i64, ci, ci, vp, ci, vp, vp]
@@ -183,6 +188,20 @@ def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scal
                                   rows, cols, _ld(w, m, v), C.byref(cs), _stream(stream)), "cast_adams_step")
 
 
+def cast_adams_step_emit(w, grad, m, v, mask_bits, cfg: AdamsConfig, compute_copy, copy_scale=None, scale=None,
+                         scale_grad=None, stream=None):
+    """cast_adams_step that also writes bf16(copy_scale * w_new) (or bf16(w_new)) into compute_copy."""
+    _dev(grad, mask_bits, scale, scale_grad, compute_copy, copy_scale)
+    if compute_copy.dtype != torch.bfloat16:
+        raise TypeError("compute_copy must be bfloat16")
+    rows, cols = w.shape
+    cfg.grad_dtype = _dtype_code(grad)
+    cs = cfg.c_struct()
+    _check(load().cast_adams_step_emit(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
+                                       _ptr(copy_scale), _ptr(compute_copy), rows, cols, _ld(w, m, v), C.byref(cs),
+                                       _stream(stream)), "cast_adams_step_emit")
+
+
 def cast_adams_multi_workspace_bytes(array, count: int, cfg: "AdamsConfig") -> int:
     cs = cfg.c_struct()
     return load().cast_adams_multi_workspace_bytes(array, count, C.byref(cs))
@@ -206,9 +225,14 @@ class TensorList:
                 raise ValueError("all gradients of a list must have one dtype")
             self.grad_dtype = dt
             sc, sg = x.get("scale"), x.get("scale_grad")
+            cp, cps = x.get("compute_copy"), x.get("copy_scale")
+            _dev(cp, cps)
+            if cp is not None and cp.dtype != torch.bfloat16:
+                raise TypeError("compute_copy must be bfloat16")
             self.array[k] = _Tensor(w.data_ptr(), x["grad"].data_ptr(), m.data_ptr(), v.data_ptr(), x["mask"].data_ptr(),
                                     None if sc is None else sc.data_ptr(), None if sg is None else sg.data_ptr(),
-                                    w.shape[0], w.shape[1], _ld(w, m, v))
+                                    w.shape[0], w.shape[1], _ld(w, m, v),
+                                    None if cp is None else cp.data_ptr(), None if cps is None else cps.data_ptr())
         self.count = n
         # the workspace depends on the shapes, on the number of scaling segments and on the launch form
         segments = {0 if x.get("scale") is None else x["scale"].shape[1] for x in self.items if x["w"].numel()}

@@ -38,6 +38,10 @@ struct SpanArgs {
     ConstTable table;     // the buffer sets of a list launch (work queue)
     SpanGeom geom;
     StepScalars s;
+    // EXTRA instantiations only: the bf16 copy of the updated weights for the next forward pass
+    // (Eq. 12 applied: copy_scale[r, s] * w_new, or w_new itself when copy_scale is NULL), or NULL
+    uint16_t *compute_copy;
+    const float *copy_scale;
 };
 
 static ConstTable as_const_table(const void *device_ptr)
@@ -96,11 +100,14 @@ struct SpanCtx {
     float A;             // its scale factor
     int len;             // entries; 0 for spans past the end of the matrix
     int sub;             // which of the waves_per_span cooperating wavefronts this one is
+    __amdgpu_buffer_rsrc_t copy;   // EXTRA: the span's part of the bf16 compute copy
+    float copy_A;                  // EXTRA: the factor folded into it
+    bool emit;                     // EXTRA: whether there is a compute copy to write
 };
 
 // `matrix` selects the buffer set (entry of the table of a list call), `block` the workgroup's
 // share of that matrix: block_waves / waves_per_span consecutive spans.
-template <bool BF16, bool SCALED, bool FROM_TABLE, bool SPLIT = false>
+template <bool BF16, bool SCALED, bool FROM_TABLE, bool SPLIT = false, int EXTRA = 0>
 __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, int64_t block, int wave, SpanCtx &c)
 {
     // The buffer set of this launch, or of one matrix of a list.  The table is read through the
@@ -154,6 +161,14 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
         if (c.len > 0) c.A = t.scale[c.segment];
         c.scale_grad = SPLIT ? t.piece_sums : t.scale_grad;     // split plans: the pieces' sums are added up afterwards
     }
+    c.emit = false;
+    c.copy_A = 1.0f;
+    if constexpr (EXTRA != 0) {
+        c.emit = a.compute_copy != nullptr;
+        // without a copy the resource is empty: every store through it would be void anyway
+        c.copy = span_resource(a.compute_copy + (c.emit ? o.dense_begin : 0), c.emit ? c.len * 2 : 0);
+        if (c.emit && a.copy_scale && c.len > 0) c.copy_A = a.copy_scale[c.segment];
+    }
 }
 
 __device__ __forceinline__ int first_offset(const SpanCtx &c, int lane) { return c.sub * kChunk + lane * kLaneElems; }
@@ -165,7 +180,7 @@ __device__ __forceinline__ int first_offset(const SpanCtx &c, int lane) { return
 // carry zeros through the arithmetic and the buffer range check voids their stores, so the
 // cross-lane steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly) always see
 // all 64 lanes.
-template <int M, bool BF16, bool REFRESH, bool SCALED>
+template <int M, bool BF16, bool REFRESH, bool SCALED, int EXTRA = 0>
 __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Chunk<BF16> cur, int lane, int wave,
                                          float *partial)
 {
@@ -205,10 +220,18 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
                 g[j] = A * g[j];                                         // chain rule of Eq. 12
             }
         }
-        adams_entries4(w, g, mu, v, nib, off < len, a.s);
+        adams_entries4<(EXTRA == 2), (EXTRA == 1)>(w, g, mu, v, nib, off < len, a.s);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
+        if constexpr (EXTRA != 0) {
+            if (c.emit) {      // the weights the next forward pass multiplies with: bf16(A * w_new), Eq. 12
+                vu2_t h;
+                h.x = f32_to_bf16_rne(c.copy_A * w[0]) | (f32_to_bf16_rne(c.copy_A * w[1]) << 16);
+                h.y = f32_to_bf16_rne(c.copy_A * w[2]) | (f32_to_bf16_rne(c.copy_A * w[3]) << 16);
+                __builtin_amdgcn_raw_buffer_store_b64(h, c.copy, off * 2, 0, kAuxStore);
+            }
+        }
 
         cur = nxt;
         off += stride;
@@ -235,17 +258,20 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
 // One matrix, one workgroup per share, dealt by the hardware dispatcher.  SPLIT: the spans are
 // pieces of row segments (Eq. 12) too long for one workgroup of short-lived wavefronts; each
 // workgroup leaves the dL/dA sum of its piece in a[.].piece_sums and sum_piece_sums adds them up.
-template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false>
+// EXTRA = 1: instantiations that can also write the bf16 compute copy; EXTRA = 2: those that, on
+// top, know the comparison update rules (a.s.rule), at the price of 12 more registers and one
+// wavefront per SIMD less.  The plain ones (0) carry none of that code.
+template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false, int EXTRA = 0>
 __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
 {
     __shared__ float partial[kMaxBlockWaves];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
     SpanCtx c;
-    span_open<BF16, SCALED, false, SPLIT>(a, 0, blockIdx.x, wave, c);
+    span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, 0, blockIdx.x, wave, c);
     Chunk<BF16> first;
     chunk_load<BF16, REFRESH>(first, c.b, first_offset(c, lane));
-    span_run<M, BF16, REFRESH, SCALED>(a, c, first, lane, wave, partial);
+    span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial);
 }
 
 // Work queue: a fixed set of resident workgroups draws runs of consecutive shares, in order, from
@@ -428,6 +454,8 @@ struct UnitArgs {
     int n_segments;
     int refresh;
     StepScalars s;
+    uint16_t *compute_copy;     // bf16 [rows, cols] or NULL
+    const float *copy_scale;    // [rows, n_segments] or NULL
 };
 
 template <bool BF16>
@@ -465,8 +493,9 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs 
             } else {
                 bits = (word >> (unsigned)(c - cb)) & ((1u << M) - 1u);
             }
-            float A = 1.0f;
+            float A = 1.0f, copy_A = 1.0f;
             if (a.scale) A = a.scale[r * a.n_segments + c / seg_len];
+            if (a.copy_scale) copy_A = a.copy_scale[r * a.n_segments + c / seg_len];
 #pragma unroll
             for (int j = 0; j < M; ++j) {
                 float g = load_grad1<BF16>(a.grad, gidx + j);
@@ -476,6 +505,7 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs 
                 a.w[idx + j] = wv[j];
                 a.m[idx + j] = mu;
                 a.v[idx + j] = vv;
+                if (a.compute_copy) a.compute_copy[gidx + j] = (uint16_t)f32_to_bf16_rne(copy_A * wv[j]);
             }
         }
         if (a.refresh) *word_ptr = word;
@@ -610,6 +640,9 @@ static StepScalars make_scalars(const cast_adams_config *cfg)
     s.decay_zero = s.alpha_lambda * 0.0f;       // keeps the sign a product with +0 has
     s.n_keep = cfg->n_keep;
     s.v_from_grad = (cfg->flags & CAST_FLAG_V_FROM_GRAD) ? 1 : 0;
+    s.rule = cfg->rule;
+    if (cfg->rule == CAST_RULE_ADDITIVE) s.one_minus_alpha = 1.0f;                              // mu~ = mu + alpha*lambda*Sign
+    if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1) s.v_from_grad = 1;   // Eq. 9, Eq. 10
     // the short forms need both bias corrections in [2^-12, 2] and a small non-negative epsilon
     s.short_forms = (s.bias_corr1.fast && s.bias_corr2.fast && cfg->eps >= 0.0f && cfg->eps <= 0x1p20f) ? 1 : 0;
     return s;
@@ -624,16 +657,28 @@ struct VecLaunch {
     uint32_t blocks_per_matrix;
     int log2_run;
     bool split;
+    int extra;       // 0, 1 (compute copy) or 2 (comparison rule, with or without compute copy): the EXTRA instantiations
 };
 
 template <int M, bool BF16, bool REFRESH, bool SCALED>
 static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
+    const dim3 grid(l.grid_x), block(l.block_threads);
     if constexpr (SCALED) {
         if (l.split) {
-            hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true>), dim3(l.grid_x), dim3(l.block_threads), 0, st, a);
+            if (l.extra == 2) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 2>), grid, block, 0, st, a);
+            else if (l.extra == 1) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 1>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true>), grid, block, 0, st, a);
             return;
         }
+    }
+    if (l.extra == 2) {
+        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, 2>), grid, block, 0, st, a);
+        return;
+    }
+    if (l.extra == 1) {
+        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, 1>), grid, block, 0, st, a);
+        return;
     }
     if (l.tickets)
         hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), dim3(l.block_threads), 0, st, a,
@@ -694,9 +739,13 @@ cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, 
 
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              int64_t ld, const cast_adams_config *cfg, PieceArea *area, hipStream_t st)
+                              int64_t ld, const cast_adams_config *cfg, void *compute_copy, const float *copy_scale,
+                              PieceArea *area, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
+    // a compute copy to write, or a comparison rule with code of its own: the EXTRA instantiations
+    const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
+    const int extra = own_rule ? 2 : (compute_copy != nullptr ? 1 : 0);
     const bool bf16 = cfg->grad_dtype == CAST_BF16;
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = scale != nullptr;
@@ -706,8 +755,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     const bool split = p.geom.pieces_per_segment > 1;
     if (p.vec) {
         SpanArgs a{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr}, as_const_table(nullptr), p.geom,
-                   make_scalars(cfg)};
-        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0, split}, a, st);
+                   make_scalars(cfg), static_cast<uint16_t *>(compute_copy), copy_scale};
+        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0, split, extra}, a, st);
         if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         if (split) {      // this matrix's part of the area is now in use until the pieces have been added up
             const PieceJob job{area->base, scale_grad, p.segments, p.geom.pieces_per_segment};
@@ -723,7 +772,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
         cast_status rc = launch_scale_grad(w, grad, cfg->grad_dtype, rows, cols, ld, cfg->scale_segments, scale_grad, st);
         if (rc != CAST_OK) return rc;
     }
-    UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, ld, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg)};
+    UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, ld, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg),
+               static_cast<uint16_t *>(compute_copy), copy_scale};
     const int64_t units = rows * ((cols + 63) / 64);
     const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
     switch (cfg->m_group) {
@@ -782,7 +832,11 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = cfg->scale_segments > 0;
     // The work queue is opt-in: one launch per matrix has measured faster at every size tried.
-    const bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
+    bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
+    // the work queue knows neither the comparison rules with code of their own nor the compute copy
+    if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN) use_queue = false;
+    for (int i = 0; i < count; ++i)
+        if (ts[i].compute_copy) use_queue = false;
     // tuning knobs (read once): resident wavefronts per compute unit of the work queue
     static const int waves_per_cu = env_int("CAST_QUEUE_WAVES_PER_CU", 16);
     static const int log2_run = env_int("CAST_QUEUE_LOG2_RUN", 1) & 7;      // shares per ticket = 1 << log2_run
@@ -821,13 +875,13 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         const StepScalars sc = make_scalars(cfg);
         for (size_t gi = 0; gi < groups.size(); ++gi) {
             const Group &g = groups[gi];
-            SpanArgs a{{}, as_const_table(static_cast<const TensorPtrs *>(workspace) + g.first), g.plan.geom, sc};
+            SpanArgs a{{}, as_const_table(static_cast<const TensorPtrs *>(workspace) + g.first), g.plan.geom, sc, nullptr, nullptr};
             const unsigned long long tasks = (unsigned long long)g.plan.grid * (unsigned)g.n;
             int blocks_per_cu = waves_per_cu / (g.plan.block_threads / kWave);
             if (blocks_per_cu < 1) blocks_per_cu = 1;
             unsigned long long resident = (unsigned long long)device_compute_units() * blocks_per_cu;
             if (resident > tasks) resident = tasks;
-            const VecLaunch l{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid, log2_run, false};
+            const VecLaunch l{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid, log2_run, false, 0};
             launch_vec_any(cfg->m_group, bf16, refresh, scaled, l, a, st);
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         }
@@ -840,7 +894,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         const cast_tensor &t = ts[i];
         if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;     // make room
         cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
-                                           layout.piece_floats ? &area : nullptr, st);
+                                           t.compute_copy, t.copy_scale, layout.piece_floats ? &area : nullptr, st);
         if (rc != CAST_OK) return rc;
     }
     return jobs.flush(st);

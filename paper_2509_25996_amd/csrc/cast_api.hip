@@ -94,7 +94,8 @@ cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t l
 // everything cast_adams_step checks before launching
 static cast_status validate_step(const float *w, const void *grad, const float *m, const float *v,
                                  const uint32_t *mask_bits, const float *scale, const float *scale_grad,
-                                 int64_t rows, int64_t cols, int64_t ld, const cast_adams_config *cfg)
+                                 int64_t rows, int64_t cols, int64_t ld, const cast_adams_config *cfg,
+                                 const void *compute_copy = nullptr, const float *copy_scale = nullptr)
 {
     if (!cfg) return CAST_ERR_NULL;
     cast_status rc = check_nm(cfg->n_keep, cfg->m_group);
@@ -105,12 +106,14 @@ static cast_status validate_step(const float *w, const void *grad, const float *
     if (!dtype_ok(cfg->grad_dtype)) return CAST_ERR_DTYPE;
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
     if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE)) return CAST_ERR_CONFIG;
+    if (cfg->rule < CAST_RULE_ADAMS || cfg->rule > CAST_RULE_MASKED_FROZEN) return CAST_ERR_CONFIG;
     // the bias corrections divide: they must be positive finite numbers (1 - beta^s with s >= 1)
     if (!(cfg->bias_corr1 > 0.0f) || !(cfg->bias_corr2 > 0.0f) || isinf(cfg->bias_corr1) || isinf(cfg->bias_corr2))
         return CAST_ERR_CONFIG;
     if (rows == 0 || cols == 0) return CAST_OK;      // nothing to do: buffers may be NULL
     if ((cfg->scale_segments > 0) != (scale != nullptr)) return scale ? CAST_ERR_SHAPE : CAST_ERR_NULL;
     if (scale_grad && !scale) return CAST_ERR_NULL;
+    if (copy_scale && (!compute_copy || cfg->scale_segments == 0)) return compute_copy ? CAST_ERR_SHAPE : CAST_ERR_NULL;
     if (cfg->scale_segments > 0 && cols > 0) {
         rc = check_segments(cols, cfg->scale_segments, cfg->m_group);
         if (rc != CAST_OK) return rc;
@@ -118,9 +121,22 @@ static cast_status validate_step(const float *w, const void *grad, const float *
     }
     if (!w || !grad || !m || !v || !mask_bits) return CAST_ERR_NULL;
     if (!aligned(w, 16) || !aligned(m, 16) || !aligned(v, 16) || !aligned(grad, dtype_align(cfg->grad_dtype)) ||
-        !aligned(mask_bits, 4) || !aligned(scale, 4) || !aligned(scale_grad, 4))
+        !aligned(mask_bits, 4) || !aligned(scale, 4) || !aligned(scale_grad, 4) || !aligned(compute_copy, 16) ||
+        !aligned(copy_scale, 4))
         return CAST_ERR_ALIGN;
     return CAST_OK;
+}
+
+cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
+                                 const float *scale, float *scale_grad, const float *copy_scale,
+                                 void *compute_copy, int64_t rows, int64_t cols, int64_t ld,
+                                 const cast_adams_config *cfg, void *stream)
+{
+    const cast_status rc = validate_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, compute_copy, copy_scale);
+    if (rc != CAST_OK) return rc;
+    if (rows > 0 && cols > 0 && !compute_copy) return CAST_ERR_NULL;
+    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, compute_copy, copy_scale, nullptr,
+                             static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
@@ -129,7 +145,8 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
 {
     const cast_status rc = validate_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg);
     if (rc != CAST_OK) return rc;
-    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, nullptr, static_cast<hipStream_t>(stream));
+    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, nullptr, nullptr, nullptr,
+                             static_cast<hipStream_t>(stream));
 }
 
 size_t cast_adams_multi_workspace_bytes(const cast_tensor *tensors, int count, const cast_adams_config *cfg)
@@ -147,7 +164,8 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
     if (!aligned(workspace, 16)) return CAST_ERR_ALIGN;
     for (int i = 0; i < count; ++i) {    // all or nothing: nothing is launched if any matrix is rejected
         const cast_tensor &t = tensors[i];
-        const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg);
+        const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
+                                             t.compute_copy, t.copy_scale);
         if (rc != CAST_OK) return rc;
     }
     if (workspace_bytes < multi_workspace_bytes(tensors, count, cfg)) return CAST_ERR_SHAPE;

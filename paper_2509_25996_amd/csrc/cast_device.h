@@ -341,7 +341,19 @@ struct StepScalars {
     int n_keep;
     int v_from_grad;
     int short_forms;       // 1 if the uniform scalars allow the short division / square-root forms
+    int rule;              // CAST_RULE_*; the kernels look at it only in their EXTRA instantiations
 };
+
+// The comparison rules (Eq. 9, Eq. 10, Sec. 5.7) as the kernels see them.  Additive decay needs no
+// code of its own: the host passes one_minus_alpha = 1 (1 * mu is mu, exactly).  For Eq. 9 and 10
+// the host also sets v_from_grad, and the kernels treat every entry as kept inside the moments.
+constexpr int kRuleAdamwL1 = 1, kRuleAdamL1 = 2, kRuleMaskedFrozen = 4;
+
+// alpha*lambda*Sign(w) with Sign(+-0) = Sign(NaN) = 0: the three possible products come from the host
+__device__ __forceinline__ float decay_term(float w, const StepScalars &s)
+{
+    return w > 0.0f ? s.decay_pos : (w < 0.0f ? s.decay_neg : s.decay_zero);
+}
 
 // Every line below is one correctly rounded fp32 operation: the library is compiled with
 // -ffp-contract=off (no fused multiply-add) and -fhip-fp32-correctly-rounded-divide-sqrt, and
@@ -354,8 +366,7 @@ __device__ __forceinline__ void adams_moments(float w, float g, float &mu, float
     const float t0 = s.beta1 * mu;
     const float t1 = s.one_minus_beta1 * g;
     const float mu_t = t0 + t1;                                   // Eq. 8, first line
-    // alpha*lambda*Sign(w) with Sign(+-0) = Sign(NaN) = 0: the three possible products come from the host
-    const float d1 = w > 0.0f ? s.decay_pos : (w < 0.0f ? s.decay_neg : s.decay_zero);
+    const float d1 = decay_term(w, s);
     const float d0 = s.one_minus_alpha * mu_t;
     const float decayed = d0 + d1;                                // Eq. 7 on the momentum
     mu_tilde = keep ? mu_t : decayed;                             // Algorithm 1: only where m = 0
@@ -367,22 +378,34 @@ __device__ __forceinline__ void adams_moments(float w, float g, float &mu, float
     mu = mu_t;                                                    // the undecayed moment is stored
 }
 
-// Second half: bias-corrected moments (already divided) to the new weight.
-__device__ __forceinline__ float adams_update(float w, float mu_hat, float v_hat, const StepScalars &s)
+// Second half: bias-corrected moments (already divided) to the adaptive step mu^ / (sqrt(v^) + eps)
+// and to the new weight.
+__device__ __forceinline__ float adams_quotient(float mu_hat, float v_hat, const StepScalars &s)
 {
     const float denom = __builtin_sqrtf(v_hat) + s.eps;           // IEEE square root
-    const float q = mu_hat / denom;                               // IEEE division
-    const float step = s.lr * q;
+    return mu_hat / denom;                                        // IEEE division
+}
+
+__device__ __forceinline__ float adams_update(float w, float mu_hat, float v_hat, const StepScalars &s)
+{
+    const float step = s.lr * adams_quotient(mu_hat, v_hat, s);
     return w - step;
 }
 
-// One entry, start to end (scalar kernels).
+// One entry, start to end, any rule (scalar kernels).
 __device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float &v, bool keep,
                                             const StepScalars &s)
 {
+    if (s.rule == kRuleMaskedFrozen && !keep) return;             // Sec. 5.7: not updated at all
+    const bool no_momentum_decay = s.rule == kRuleAdamwL1 || s.rule == kRuleAdamL1;
+    const float d = decay_term(w, s);
+    if (s.rule == kRuleAdamL1 && !keep) g = g + d;                // Eq. 10: decay inside the gradient
     float mu_tilde, v_t;
-    adams_moments(w, g, mu, v, keep, s, mu_tilde, v_t);
-    w = adams_update(w, div_by_uniform(mu_tilde, s.bias_corr1), div_by_uniform(v_t, s.bias_corr2), s);
+    adams_moments(w, g, mu, v, keep || no_momentum_decay, s, mu_tilde, v_t);
+    float q = adams_quotient(div_by_uniform(mu_tilde, s.bias_corr1), div_by_uniform(v_t, s.bias_corr2), s);
+    if (s.rule == kRuleAdamwL1 && !keep) q = q + d;               // Eq. 9: decay beside the adaptive step
+    const float step = s.lr * q;
+    w = w - step;
     v = v_t;
 }
 
@@ -423,13 +446,40 @@ __device__ __forceinline__ float div_short_any(float x, float d)
 // among the 8 dividends of the live lanes: 2^-63 <= |mu~|, v < 2^66 (so zeros, denormals, inf
 // take the long forms; a NaN goes through either form as a NaN).  `live` is false for lanes
 // past the end of the span, whose zeros must not force the long forms.
-__device__ __forceinline__ void adams_entries4(float (&w)[4], const float (&g)[4], float (&mu)[4],
+// EXTRA: the comparison rules of s.rule are honoured (Eq. 9, Eq. 10, frozen masked entries);
+// without it the code is Algorithm 1 alone.  Nothing of the incoming state is set aside for the
+// rules (registers decide how many wavefronts a compute unit holds): what a rule needs of the
+// old values is used before they are overwritten.
+// ONE_LOOP only chooses between two spellings of the same arithmetic (the short/long decision
+// inside or outside the loop over the four entries); which one the compiler schedules better was
+// measured per kernel flavour: outside for the plain step, inside when the compute copy is written
+// (6 % on that step).
+template <bool EXTRA = false, bool ONE_LOOP = false>
+__device__ __forceinline__ void adams_entries4(float (&w)[4], float (&g)[4], float (&mu)[4],
                                                float (&v)[4], uint32_t nib, bool live,
                                                const StepScalars &s)
 {
     float mt[4], vt[4];
+    uint32_t nib_moments = nib;      // which entries count as kept inside the moments
+    uint32_t held = 0;               // which entries are not updated at all
+    uint32_t decayed_step = 0;       // which entries get the decay beside the adaptive step
+    if constexpr (EXTRA) {
+        if (s.rule == kRuleAdamL1) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) adams_moments(w[j], g[j], mu[j], v[j], (nib >> j) & 1u, s, mt[j], vt[j]);
+            for (int j = 0; j < 4; ++j)
+                if (!((nib >> j) & 1u)) g[j] = g[j] + decay_term(w[j], s);            // Eq. 10
+        }
+        if (s.rule == kRuleAdamwL1 || s.rule == kRuleAdamL1) nib_moments = 0xFu;     // no decay on the momentum
+        if (s.rule == kRuleAdamwL1) decayed_step = ~nib & 0xFu;                      // Eq. 9
+        if (s.rule == kRuleMaskedFrozen) held = ~nib & 0xFu;                         // Sec. 5.7
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float mu_new = mu[j];
+        adams_moments(w[j], g[j], mu_new, v[j], (nib_moments >> j) & 1u, s, mt[j], vt[j]);
+        if constexpr (EXTRA) mu[j] = ((held >> j) & 1u) ? mu[j] : mu_new;
+        else mu[j] = mu_new;
+    }
     float lo = __builtin_fminf(__builtin_fabsf(mt[0]), __builtin_fabsf(mt[1]));
     float hi = __builtin_fmaxf(__builtin_fabsf(mt[0]), __builtin_fabsf(mt[1]));
 #pragma unroll
@@ -437,23 +487,44 @@ __device__ __forceinline__ void adams_entries4(float (&w)[4], const float (&g)[4
 #pragma unroll
     for (int j = 0; j < 4; ++j) { lo = __builtin_fminf(lo, vt[j]); hi = __builtin_fmaxf(hi, vt[j]); }
     const bool out_of_range = !(lo >= 0x1p-63f) || !(hi < 0x1p66f);
-    if (s.short_forms && !__any(out_of_range && live)) {
+    // what the rules change after the adaptive step q = mu^ / (sqrt(v^) + eps) is known
+    auto finish = [&](int j, float q) {
+        if constexpr (EXTRA) {
+            if ((decayed_step >> j) & 1u) q = q + decay_term(w[j], s);
+        }
+        const float step = s.lr * q;
+        if constexpr (EXTRA) {
+            w[j] = ((held >> j) & 1u) ? w[j] : w[j] - step;
+            v[j] = ((held >> j) & 1u) ? v[j] : vt[j];
+        } else {
+            w[j] = w[j] - step;
+            v[j] = vt[j];
+        }
+    };
+    const bool short_forms = s.short_forms && !__any(out_of_range && live);      // wave-uniform
+    if constexpr (ONE_LOOP) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (short_forms) {
+                const float mu_hat = div_short(mt[j], s.bias_corr1);
+                const float v_hat = div_short(vt[j], s.bias_corr2);
+                const float denom = sqrt_short(v_hat) + s.eps;
+                finish(j, div_short_any(mu_hat, denom));
+            } else {
+                finish(j, adams_quotient(mt[j] / s.bias_corr1.y, vt[j] / s.bias_corr2.y, s));
+            }
+        }
+    } else if (short_forms) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float mu_hat = div_short(mt[j], s.bias_corr1);
             const float v_hat = div_short(vt[j], s.bias_corr2);
             const float denom = sqrt_short(v_hat) + s.eps;
-            const float q = div_short_any(mu_hat, denom);
-            const float step = s.lr * q;
-            w[j] = w[j] - step;
-            v[j] = vt[j];
+            finish(j, div_short_any(mu_hat, denom));
         }
     } else {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            w[j] = adams_update(w[j], mt[j] / s.bias_corr1.y, vt[j] / s.bias_corr2.y, s);
-            v[j] = vt[j];
-        }
+        for (int j = 0; j < 4; ++j) finish(j, adams_quotient(mt[j] / s.bias_corr1.y, vt[j] / s.bias_corr2.y, s));
     }
 }
 

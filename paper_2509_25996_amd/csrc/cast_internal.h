@@ -34,8 +34,8 @@ struct PieceArea {
 
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              int64_t ld, const cast_adams_config *cfg, PieceArea *area,
-                              hipStream_t stream);
+                              int64_t ld, const cast_adams_config *cfg, void *compute_copy,
+                              const float *copy_scale, PieceArea *area, hipStream_t stream);
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad,
                               hipStream_t stream);

@@ -56,7 +56,8 @@ def oracle_cfg(cfg: B.AdamsConfig) -> oracle.AdamsCfg:
     return oracle.AdamsCfg(n_keep=cfg.n_keep, m_group=cfg.m_group, lr=cfg.lr, beta1=cfg.beta1, beta2=cfg.beta2,
                            eps=cfg.eps, lambda_=cfg.lambda_, alpha=cfg.alpha, bias_corr1=cfg.bias_corr1,
                            bias_corr2=cfg.bias_corr2, refresh_mask=cfg.refresh_mask,
-                           scale_segments=cfg.scale_segments, v_from_grad=int(bool(cfg.flags & B.FLAG_V_FROM_GRAD)))
+                           scale_segments=cfg.scale_segments, v_from_grad=int(bool(cfg.flags & B.FLAG_V_FROM_GRAD)),
+                           rule=cfg.rule)
 
 
 class GpuState:

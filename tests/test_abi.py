@@ -85,6 +85,7 @@ def test_validation_happens_before_any_launch(lib):
     assert call(_cfg(bias_corr2=-1.0)) == -5
     assert call(_cfg(bias_corr2=float("nan"))) == -5
     assert call(_cfg(flags=8)) == -5
+    assert call(_cfg(rule=5)) == -5 and call(_cfg(rule=-1)) == -5
     assert call(_cfg(), w=nul) == -1
     assert call(_cfg(), k=nul) == -1
     assert call(_cfg(), w=odd) == -3
@@ -112,6 +113,12 @@ def test_validation_happens_before_any_launch(lib):
     assert lib.cast_nm_project_compress(p, nul, 0, nul, 4, 64, 8, 2, 4, p, 0, p, st) == -2
     assert lib.cast_mask_stats(p, nul, nul, 4, 64, 64, p, p, st) == -1
     assert lib.cast_mask_stats(p, p, nul, 4, 64, 63, p, p, st) == -2
+    emit = lib.cast_adams_step_emit
+    c2 = _cfg(scale_segments=2)
+    assert emit(p, p, p, p, p, nul, nul, nul, nul, 4, 64, 64, C.byref(_cfg()), st) == -1        # no compute copy
+    assert emit(p, p, p, p, p, nul, nul, p, p, 4, 64, 64, C.byref(_cfg()), st) == -2            # copy_scale without segments
+    assert emit(p, p, p, p, p, p, nul, nul, C.c_void_p(0x10008), 4, 64, 64, C.byref(c2), st) == -3
+    assert emit(nul, nul, nul, nul, nul, nul, nul, nul, nul, 0, 64, 64, C.byref(_cfg()), st) == 0
     # list call: rejected as a whole if any matrix is bad, before anything is enqueued
     T = B._Tensor
     good = T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64)

@@ -470,3 +470,100 @@ def test_list_call_long_segments_scale_grad_against_oracle():
         runs.append(host(st.scale_grad).copy())
     assert (np.abs(runs[0] - gA_ref) <= 1e-5 * terms).all()
     assert runs[0].tobytes() == runs[1].tobytes()
+
+
+# --------------------------------------------------------------------------- comparison update rules (Eq. 9, 10, ...)
+@pytest.mark.parametrize("rule", [B.RULE_ADAMW_L1, B.RULE_ADAM_L1, B.RULE_ADDITIVE, B.RULE_MASKED_FROZEN])
+@pytest.mark.parametrize("n,m,rows,cols,nseg,bf16", [(2, 4, 16, 1024, 0, False), (2, 4, 16, 1024, 2, True),
+                                                     (4, 8, 6, 1280 + 64, 2, True), (1, 2, 7, 72, 3, False),
+                                                     (2, 4, 5, 11008, 2, True)])
+def test_comparison_rules_bit_exact(rule, n, m, rows, cols, nseg, bf16):
+    steps = 5
+    rng = np.random.default_rng(100 * rule + rows)
+    w0 = synth.tie_outlier_weights(4, rule, rows, cols) if cols % 8 == 0 else synth.weights(4, rule, rows, cols)
+    w0[0, :m] = 0.0                       # Sign(0) = 0: no decay on exact zeros
+    grads = []
+    for t in range(steps):
+        gr = synth.grads_f32(4, rule, t, rows, cols)
+        grads.append(synth.widen_bf16(torch.from_numpy(gr).to(torch.bfloat16)) if bf16 else gr)
+    cfgs = [B.iteration_config(t, steps, mask_period=2, lr=1e-3, lambda_=1e-3, n_keep=n, m_group=m, scale_segments=nseg,
+                               rule=rule) for t in range(steps)]
+    scales = None
+    if nseg:
+        scales = [(1 + 0.2 * rng.standard_normal((rows, nseg))).astype(np.float32) for _ in range(steps)]
+    for interleaved in (False, True):
+        g, o, _ = _run_both(w0, grads, cfgs, "f32", scales=scales, bf16=bf16, interleaved=interleaved)
+        _check_state(g, o, exact=True)
+    # the rules really differ from Algorithm 1 on this input
+    base = [B.iteration_config(t, steps, mask_period=2, lr=1e-3, lambda_=1e-3, n_keep=n, m_group=m, scale_segments=nseg)
+            for t in range(steps)]
+    g0, _, _ = _run_both(w0, grads, base, "f32", scales=scales, bf16=bf16)
+    assert host(g0.w).tobytes() != host(g.w).tobytes()
+
+
+def test_comparison_rules_special_values_and_list_call():
+    rng = np.random.default_rng(5)
+    rows, cols = 4, 512
+    pool = np.array([0.0, -0.0, 1e-45, -1e-45, 1e-39, np.inf, -np.inf, np.nan, 1.0, -2.5, 3e38, 1e-20, 0.02], np.float32)
+
+    def draw(p_special):
+        x = (rng.standard_normal((rows, cols)) * 0.02).astype(np.float32)
+        pick = rng.random((rows, cols)) < p_special
+        x[pick] = pool[rng.integers(0, len(pool), int(pick.sum()))]
+        return x
+    for rule in (B.RULE_ADAMW_L1, B.RULE_ADAM_L1, B.RULE_ADDITIVE, B.RULE_MASKED_FROZEN):
+        w0 = draw(0.3)
+        g, o = GpuState(w0), OracleState(w0, "f32")
+        g.m.copy_(dev(draw(0.2)))
+        g.v.copy_(dev(np.abs(draw(0.2))))
+        o.m[:] = host(g.m)
+        o.v[:] = host(g.v)
+        grad_dev = torch.zeros((rows, cols), device=DEV)
+        tl = B.TensorList([dict(w=g.w, m=g.m, v=g.v, mask=g.mask, grad=grad_dev)], DEV)
+        for t in range(3):
+            grad = draw(0.2)
+            grad_dev.copy_(dev(grad))
+            cfg = B.iteration_config(t, 3, mask_period=1, lr=1e-2, lambda_=1e-3, rule=rule)
+            if t == 1:
+                cfg.flags |= B.FLAG_WORK_QUEUE      # the queue does not know the rules: the call must not use it
+            B.cast_adams_step_multi(tl, cfg)
+            o.step(grad, oracle_cfg(cfg))
+        torch.cuda.synchronize()
+        assert (words(g.mask) == oracle.pack_mask_bits(o.keep)).all()
+        for name, got, ref in (("w", host(g.w), o.w), ("mu", host(g.m), o.m), ("v", host(g.v), o.v)):
+            assert_same_bits(got, ref, f"rule {rule} {name}")
+
+
+# --------------------------------------------------------------------------- compute copy for the next forward pass
+@pytest.mark.parametrize("rows,cols,nseg,with_copy_scale", [(16, 1024, 2, True), (16, 1024, 2, False), (16, 1024, 0, False),
+                                                            (7, 72, 3, True), (5, 11008, 2, True), (33, 4096 + 32, 1, True)])
+@pytest.mark.parametrize("refresh", [0, 1])
+def test_step_emits_bf16_compute_copy(rows, cols, nseg, with_copy_scale, refresh):
+    rng = np.random.default_rng(rows + cols)
+    w0 = synth.weights(6, 1, rows, cols)
+    w0[0, :8] = [np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-40, 3e38, -3e38]
+    gb = synth.grads_bf16(6, 1, 0, rows, cols)
+    A = (1 + 0.2 * rng.standard_normal((rows, nseg))).astype(np.float32) if nseg else None
+    A_copy = (1 + 0.2 * rng.standard_normal((rows, nseg))).astype(np.float32) if with_copy_scale else None
+    cfg = B.iteration_config(3, 10, mask_period=1, lr=1e-3, lambda_=1e-3, scale_segments=nseg)
+    cfg.refresh_mask = refresh
+    o = OracleState(w0, "f32")
+    o.keep[:] = oracle.nm_select(w0, 2, 4)
+    o.step(synth.widen_bf16(gb), oracle_cfg(cfg), A=A)
+    want = oracle.bf16_rne(o.w if A_copy is None else oracle.weight_scale(o.w, A_copy))
+    for interleaved, as_list in ((False, False), (True, False), (True, True)):
+        st = GpuState(w0, nseg, interleaved=interleaved)
+        B.cast_nm_select(st.w, 2, 4, st.mask)
+        copy = torch.full((rows, cols), 7.0, dtype=torch.bfloat16, device=DEV)
+        kw = dict(scale=None if A is None else dev(A), scale_grad=st.scale_grad if nseg else None)
+        if as_list:
+            tl = B.TensorList([dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=gb.to(DEV), compute_copy=copy,
+                                    copy_scale=None if A_copy is None else dev(A_copy), **kw)], DEV)
+            B.cast_adams_step_multi(tl, cfg)
+        else:
+            B.cast_adams_step_emit(st.w, gb.to(DEV), st.m, st.v, st.mask, cfg, copy,
+                                   copy_scale=None if A_copy is None else dev(A_copy), **kw)
+        torch.cuda.synchronize()
+        assert_same_bits(host(st.w), o.w, "w")
+        got = host(copy.view(torch.int16)).view(np.uint16)
+        assert (got == want).all(), (interleaved, as_list, int((got != want).sum()))
