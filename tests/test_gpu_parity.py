@@ -567,3 +567,48 @@ def test_step_emits_bf16_compute_copy(rows, cols, nseg, with_copy_scale, refresh
         assert_same_bits(host(st.w), o.w, "w")
         got = host(copy.view(torch.int16)).view(np.uint16)
         assert (got == want).all(), (interleaved, as_list, int((got != want).sum()))
+
+
+# --------------------------------------------------------------------------- short square root and division forms
+def _mantissa_sweep(exponent_bits: int) -> np.ndarray:
+    """All 2^23 fp32 values of one binade, as a [2048, 4096] matrix."""
+    bits = (np.uint32(exponent_bits) << np.uint32(23)) | np.arange(1 << 23, dtype=np.uint32)
+    return bits.view(np.float32).reshape(2048, 4096)
+
+
+@pytest.mark.parametrize("case", ["v binade 2^-20", "v binade 2^-19", "v binade 2^-63", "v binade 2^65", "g binade 2^-10",
+                                  "g binade 2^-63 (edge of the short range)", "g binade 2^65",
+                                  "v binade 2^-64 (just outside: long forms)", "g binade 2^66 (just outside: long forms)",
+                                  "g binade 2^65 over the smallest v", "g binade 2^-63 over the largest v"])
+def test_short_sqrt_and_division_every_mantissa(case):
+    """With beta1 = 0, beta2 = 1, both bias corrections 1, eps = 0, lr = 1 and w = 0 the step returns
+    w = -(g / sqrt(v)): the square root and the last division of Algorithm 1 on inputs of our choice.  Every
+    mantissa of one operand, against the IEEE operations of the oracle, bit for bit; binades at the edges of
+    the range in which the kernels use their short forms included (inside: short; outside: the long forms)."""
+    rng = np.random.default_rng(len(case))
+    shape = (2048, 4096)
+    other = np.exp2(rng.uniform(-0.5, 0.5, shape)).astype(np.float32)
+    if case.startswith("v"):
+        e = {"2^-20": 107, "2^-19": 108, "2^-63": 64, "2^65": 192, "2^-64": 63}[case.split()[2]]
+        v0 = _mantissa_sweep(e)
+        g = (other * np.float32(2.0 ** -12)).astype(np.float32)
+    else:
+        e = {"2^-10": 117, "2^-63": 64, "2^65": 192, "2^66": 193}[case.split()[2]]
+        g = _mantissa_sweep(e) * np.where(rng.random(shape) < 0.5, np.float32(-1), np.float32(1))
+        v_scale = 2.0 ** -62.4 if "smallest v" in case else (2.0 ** 65.4 if "largest v" in case else 2.0 ** -21)
+        v0 = (other * np.float32(v_scale)).astype(np.float32)
+    cfg = B.AdamsConfig(lr=1.0, beta1=0.0, beta2=1.0, eps=0.0, lambda_=0.0, alpha=0.0, bias_corr1=1.0, bias_corr2=1.0,
+                        refresh_mask=0)
+    w0 = np.zeros(shape, np.float32)
+    st = GpuState(w0)
+    st.v.copy_(dev(v0))
+    st.mask.fill_(-1)
+    st.step(dev(g), cfg)
+    torch.cuda.synchronize()
+    o = OracleState(w0, "f32")
+    o.v[:] = v0
+    o.keep[:] = 1
+    o.step(g, oracle_cfg(cfg), nthreads=16)
+    assert_same_bits(host(st.w), o.w, "w = -(g / sqrt(v))")
+    assert_same_bits(host(st.v), o.v, "v")
+    assert (host(st.m) == g).all()
