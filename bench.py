@@ -239,6 +239,19 @@ def main():
         extra["project_compress_ms"] = round(pc_ms, 3)
         extra["project_compress_GBs"] = round(6.125 * model.params / (pc_ms * 1e-3) / 1e9, 1)
         del outs
+        # mask-learning statistics of a refresh (flip count against the previous mask, ||W.M||_1, ||W||_1): a pass
+        # of its own over w and two masks, 4.25 B/param
+        flips = torch.zeros(1, dtype=torch.int64, device=dev)
+        l1 = torch.zeros(2, dtype=torch.float64, device=dev)
+        for rep in range(2):
+            e0.record()
+            for x in model.t:
+                B.cast_mask_stats(x["w"], x["mask"], x["mask"], flips, l1)
+            e1.record()
+            torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        extra["mask_stats_ms"] = round(ms, 3)
+        extra["mask_stats_GBs"] = round(4.25 * model.params / (ms * 1e-3) / 1e9, 1)
         if model.list is not None:
             # the widened forms of the step, over the same set and through the same list call: a comparison
             # rule (Eq. 10), and the step that also writes the bf16 weights of the next forward pass
