@@ -1,5 +1,7 @@
 """Parity at the full sizes of the benchmark workloads, in the launch configuration the
-benchmark times (2:4, bf16 gradients, weight scaling with n = 2, one launch per matrix).
+benchmark times (2:4, bf16 gradients, weight scaling with n = 2, w/mu/v row-interleaved in one
+buffer, the list call, which steps long row segments in pieces) and in the plain one (three dense
+arrays, one cast_adams_step call).
 
 The AdamS step is checked on sampled whole rows (a row is self-contained: groups and scale
 segments never cross rows), gathered before and after the GPU step and recomputed by the oracle.
@@ -20,12 +22,16 @@ SHAPES_7B = [(4096, 4096), (11008, 4096), (4096, 11008)]
 SHAPES_13B = [(5120, 5120), (13824, 5120), (5120, 13824)]
 
 
+@pytest.mark.parametrize("as_benchmarked", [True, False])
 @pytest.mark.parametrize("rows,cols", SHAPES_7B + SHAPES_13B)
-def test_step_on_sampled_rows_of_full_size_matrices(rows, cols):
+def test_step_on_sampled_rows_of_full_size_matrices(rows, cols, as_benchmarked):
     n, steps, n_sample = 2, 3, 24
     w = synth.device_gaussian((rows, cols), 0.02, torch.float32, 11, DEV)
     g = synth.device_gaussian((rows, cols), 1e-3, torch.bfloat16, 12, DEV)
-    m, v = torch.zeros_like(w), torch.zeros_like(w)
+    if as_benchmarked:
+        w, m, v = B.interleaved_state(w)
+    else:
+        m, v = torch.zeros_like(w), torch.zeros_like(w)
     mask = B.alloc_mask(rows, cols, DEV)
     A = (1 + 0.05 * torch.randn((rows, n), device=DEV, generator=torch.Generator(DEV).manual_seed(3))).contiguous()
     gA = torch.zeros((rows, n), device=DEV)
@@ -35,10 +41,14 @@ def test_step_on_sampled_rows_of_full_size_matrices(rows, cols):
     ow, og, oA = host(w[idx]).copy(), host(g[idx].float()).copy(), host(A[idx]).copy()
     om, ov = np.zeros_like(ow), np.zeros_like(ow)
     keep = np.zeros(ow.shape, np.uint8)
+    tl = B.TensorList([dict(w=w, grad=g, m=m, v=v, mask=mask, scale=A, scale_grad=gA)], DEV) if as_benchmarked else None
     for t in range(steps):
         cfg = B.iteration_config(t, 7500, mask_period=2, lr=2e-5, lambda_=4e-7, scale_segments=n)
         cfg.alpha = 0.25 + 0.25 * t      # exercise the decay as late in training
-        B.cast_adams_step(w, g, m, v, mask, cfg, scale=A, scale_grad=gA)
+        if as_benchmarked:
+            B.cast_adams_step_multi(tl, cfg)
+        else:
+            B.cast_adams_step(w, g, m, v, mask, cfg, scale=A, scale_grad=gA)
         ref_gA = oracle.adams_step(ow, og, om, ov, keep, oracle_cfg(cfg), A=oA, arithmetic="f32", nthreads=8)
     torch.cuda.synchronize()
     assert (words(mask[idx]) == oracle.pack_mask_bits(keep)).all()
