@@ -33,8 +33,10 @@ struct TensorPtrs {
 // where buffer resources have to live.
 typedef const TensorPtrs __attribute__((address_space(4))) *ConstTable;
 
+constexpr int kMaxFused = 4;      // matrices of equal shape that one dispatcher-dealt launch can step (gridDim.y)
+
 struct SpanArgs {
-    TensorPtrs one;       // the buffer set of a single-matrix launch
+    TensorPtrs set[kMaxFused];   // the buffer sets of a dispatcher-dealt launch: matrix blockIdx.y
     ConstTable table;     // the buffer sets of a list launch (work queue)
     SpanGeom geom;
     StepScalars s;
@@ -130,7 +132,7 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
         t.scale = (const float *)ptr(hi[2], hi[3]);
         t.scale_grad = (float *)ptr(hi[4], hi[5]);
     } else {
-        t = a.one;
+        t = a.set[matrix];     // a scalar load from the kernel arguments at a wave-uniform offset
     }
     const SpanSlot slot = span_slot(a.geom, block, wave, blockDim.x / kWave);
     c.span = (int64_t)uniform_u64((unsigned long long)slot.span);
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
     SpanCtx c;
-    span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, 0, blockIdx.x, wave, c);
+    span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
     Chunk<BF16> first;
     chunk_load<BF16, REFRESH>(first, c.b, first_offset(c, lane));
     span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial);
@@ -663,7 +665,7 @@ struct VecLaunch {
 template <int M, bool BF16, bool REFRESH, bool SCALED>
 static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
-    const dim3 grid(l.grid_x), block(l.block_threads);
+    const dim3 grid(l.grid_x, l.grid_y), block(l.block_threads);
     if constexpr (SCALED) {
         if (l.split) {
             if (l.extra == 2) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 2>), grid, block, 0, st, a);
@@ -692,7 +694,7 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
             if (blocks < 1) blocks = 1;
             lds = (unsigned)(160 * 1024 / blocks) - 1024;
         }
-        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), dim3(l.block_threads), lds, st, a);
+        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), grid, block, lds, st, a);
     }
 }
 
@@ -754,7 +756,7 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
         p = plan_spans(rows, cols, ld, cfg->scale_segments, false);       // no room for the pieces' sums
     const bool split = p.geom.pieces_per_segment > 1;
     if (p.vec) {
-        SpanArgs a{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr}, as_const_table(nullptr), p.geom,
+        SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr}}, as_const_table(nullptr), p.geom,
                    make_scalars(cfg), static_cast<uint16_t *>(compute_copy), copy_scale};
         launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0, split, extra}, a, st);
         if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
@@ -781,6 +783,19 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     case 4: launch_unit_dtype<4>(bf16, grid, a, st); break;
     default: launch_unit_dtype<8>(bf16, grid, a, st); break;
     }
+    return launch_status();
+}
+
+// Up to kMaxFused matrices of one shape in one launch (plain flavour, no split plan): the ramp-up
+// and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a 4096 x 4096 matrix takes.
+static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
+                                           hipStream_t st)
+{
+    SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg), nullptr, nullptr};
+    for (int k = 0; k < n; ++k)
+        a.set[k] = TensorPtrs{ts[k]->w, ts[k]->grad, ts[k]->m, ts[k]->v, ts[k]->mask_bits, ts[k]->scale, ts[k]->scale_grad, nullptr};
+    launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, cfg->refresh_mask != 0, cfg->scale_segments > 0,
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, 0}, a, st);
     return launch_status();
 }
 
@@ -889,9 +904,31 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     PieceJobQueue jobs;
     PieceArea area{reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes),
                    layout.piece_floats, &jobs};
+    static const int fuse_limit = env_int("CAST_FUSE", kMaxFused);            // matrices per launch (1 = never fuse)
+    static const int64_t fuse_max_params = (int64_t)env_int("CAST_FUSE_MAX_MPARAMS", 24) << 20;
+    const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
+        // small matrices of one shape that follow each other (q, k, v, o of a layer) share a launch
+        if (!own_rule && fuse_limit > 1 && t.rows > 0 && t.cols > 0 && !t.compute_copy && t.rows * t.cols <= fuse_max_params) {
+            const cast_tensor *same[kMaxFused] = {&t};
+            int n = 1;
+            while (n < fuse_limit && n < kMaxFused && i + n < count && !taken[i + n] && !ts[i + n].compute_copy &&
+                   ts[i + n].rows == t.rows && ts[i + n].cols == t.cols && ts[i + n].ld == t.ld &&
+                   (ts[i + n].scale_grad == nullptr) == (t.scale_grad == nullptr)) {
+                same[n] = &ts[i + n];
+                ++n;
+            }
+            if (n > 1) {
+                const SpanPlan p = plan_spans(t.rows, t.cols, t.ld, cfg->scale_segments, true);
+                if (p.vec && p.geom.pieces_per_segment == 1) {
+                    if (launch_adams_step_fused(same, n, p, cfg, st) != CAST_OK) return CAST_ERR_LAUNCH;
+                    i += n - 1;
+                    continue;
+                }
+            }
+        }
         if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;     // make room
         cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
                                            t.compute_copy, t.copy_scale, layout.piece_floats ? &area : nullptr, st);
