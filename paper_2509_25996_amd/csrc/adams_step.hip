@@ -33,7 +33,7 @@ struct TensorPtrs {
 // where buffer resources have to live.
 typedef const TensorPtrs __attribute__((address_space(4))) *ConstTable;
 
-constexpr int kMaxFused = 4;      // matrices of equal shape that one dispatcher-dealt launch can step (gridDim.y)
+constexpr int kMaxFused = 16;     // matrices of equal shape that one dispatcher-dealt launch can step (gridDim.y)
 
 struct SpanArgs {
     TensorPtrs set[kMaxFused];   // the buffer sets of a dispatcher-dealt launch: matrix blockIdx.y
@@ -904,27 +904,36 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     PieceJobQueue jobs;
     PieceArea area{reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes),
                    layout.piece_floats, &jobs};
+    // Small matrices of one shape share a launch (they need not follow each other in the list: the
+    // matrices are independent).  A launch is kept below about 72 M entries: q, k, v, o of a
+    // LLaMA2-7B layer go together, 16 of the 768 x 768 matrices of a 125M model; longer launches
+    // lose to the drift between compute units what they gain on ramps.
     static const int fuse_limit = env_int("CAST_FUSE", kMaxFused);            // matrices per launch (1 = never fuse)
     static const int64_t fuse_max_params = (int64_t)env_int("CAST_FUSE_MAX_MPARAMS", 24) << 20;
+    static const int64_t fuse_launch_params = (int64_t)env_int("CAST_FUSE_LAUNCH_MPARAMS", 72) << 20;
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
-        // small matrices of one shape that follow each other (q, k, v, o of a layer) share a launch
         if (!own_rule && fuse_limit > 1 && t.rows > 0 && t.cols > 0 && !t.compute_copy && t.rows * t.cols <= fuse_max_params) {
+            int most = (int)(fuse_launch_params / (t.rows * t.cols));
+            if (most > fuse_limit) most = fuse_limit;
+            if (most > kMaxFused) most = kMaxFused;
             const cast_tensor *same[kMaxFused] = {&t};
+            int where[kMaxFused] = {i};
             int n = 1;
-            while (n < fuse_limit && n < kMaxFused && i + n < count && !taken[i + n] && !ts[i + n].compute_copy &&
-                   ts[i + n].rows == t.rows && ts[i + n].cols == t.cols && ts[i + n].ld == t.ld &&
-                   (ts[i + n].scale_grad == nullptr) == (t.scale_grad == nullptr)) {
-                same[n] = &ts[i + n];
-                ++n;
-            }
+            for (int j = i + 1; j < count && n < most; ++j)
+                if (!taken[j] && !ts[j].compute_copy && ts[j].rows == t.rows && ts[j].cols == t.cols && ts[j].ld == t.ld &&
+                    (ts[j].scale_grad == nullptr) == (t.scale_grad == nullptr)) {
+                    same[n] = &ts[j];
+                    where[n] = j;
+                    ++n;
+                }
             if (n > 1) {
                 const SpanPlan p = plan_spans(t.rows, t.cols, t.ld, cfg->scale_segments, true);
                 if (p.vec && p.geom.pieces_per_segment == 1) {
                     if (launch_adams_step_fused(same, n, p, cfg, st) != CAST_OK) return CAST_ERR_LAUNCH;
-                    i += n - 1;
+                    for (int k = 0; k < n; ++k) taken[where[k]] = 1;
                     continue;
                 }
             }
