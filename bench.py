@@ -76,8 +76,9 @@ class Model:
                                        copy_scale=x["A"] if scaled and copies is not None else None)
                                   for i, x in enumerate(self.t)], dev)
         self.flags = B.FLAG_WORK_QUEUE if queue else 0
-        if queue:
-            self.launches = len({(x["w"].shape, x["w"].stride(0)) for x in self.t})   # one launch per distinct shape
+        # launches of the step kernel per call (the list call steps several small matrices with one launch)
+        probe = B.AdamsConfig(scale_segments=self.segments if scaled else 0, flags=self.flags)
+        self.launches, _ = B.cast_adams_multi_launches(self.list, probe)
 
     def step(self, B, t: int, scaled: bool):
         cfg = B.iteration_config(t, TOTAL_STEPS, mask_period=MASK_PERIOD, lr=LR, lambda_=LAMBDA,
@@ -195,8 +196,7 @@ def main():
     log(f"[bench] {ms_per_step:.3f} ms/step, {value:.1f} Gparams/s; non-refresh {sum(plain) / max(len(plain), 1):.3f} ms, "
         f"refresh {sum(fresh) / max(len(fresh), 1):.3f} ms")
 
-    # dominant kernel: the non-refresh fused step (9 of 10 steps); one launch per matrix, or per distinct
-    # shape with the list call
+    # dominant kernel: the non-refresh step kernel (9 of 10 steps), all its launches of a step taken together
     launches = model.launches
     dom_ms = (sum(plain) / len(plain)) if plain else ms_per_step
     bytes_per_launch = BYTES_PER_PARAM * model.params / launches

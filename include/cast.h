@@ -165,7 +165,9 @@ cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v,
  * (without the work queue) steps with one workgroup per 2048 entries: their sums are added in
  * another, equally fixed order (per 2048 entries, then left to right).
  *   tensors    HOST in   `count` descriptors; the device buffers they name follow the rules of
- *                        cast_adams_step (scale / scale_grad NULL or not for all alike, per cfg)
+ *                        cast_adams_step (scale / scale_grad NULL or not for all alike, per cfg).
+ *                        No two descriptors may name overlapping buffers: the matrices are stepped
+ *                        in an order of the library's choosing, several of them by one launch.
  *   workspace  DEVICE    at least cast_adams_multi_workspace_bytes(tensors, count, cfg) bytes (it
  *                        depends on shapes, row strides, scale_grad being NULL or not,
  *                        cfg->scale_segments and cfg->flags only), 16-byte aligned, owned by the
@@ -190,6 +192,16 @@ size_t cast_adams_multi_workspace_bytes(const cast_tensor *tensors /* HOST */, i
 
 cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* How many kernel launches cast_adams_step_multi makes for this list (HOST only, nothing is
+ * enqueued; assumes a workspace of the size cast_adams_multi_workspace_bytes returns):
+ * step_launches = launches of the step kernel (one launch may step several matrices),
+ * other_launches = the rest (dL/dA reductions of odd shapes, sums of split row segments).
+ * For accounting (time per launch = time per call / launches); either pointer may be NULL. */
+cast_status cast_adams_multi_launches(const cast_tensor *tensors /* HOST */, int count,
+                                      const cast_adams_config *cfg /* HOST */,
+                                      int32_t *step_launches /* HOST out */,
+                                      int32_t *other_launches /* HOST out */);
 
 /*
  * Weight scaling forward / fold, Eq. 12 (Eq. 11 when n_segments == 1):

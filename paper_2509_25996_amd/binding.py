@@ -21,7 +21,7 @@ RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = ran
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
            "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi",
-           "cast_adams_step_emit"]
+           "cast_adams_step_emit", "cast_adams_multi_launches"]
 
 
 class CastError(RuntimeError):
@@ -97,6 +97,7 @@ def load():
     L.cast_adams_multi_workspace_bytes.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config)]
     L.cast_adams_multi_workspace_bytes.restype = C.c_size_t
     L.cast_adams_step_multi.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp, C.c_size_t, vp]
+    L.cast_adams_multi_launches.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     for name in EXPORTS:
         if name not in ("cast_status_str", "cast_adams_multi_workspace_bytes"):
             getattr(L, name).restype = C.c_int32
@@ -252,6 +253,17 @@ def cast_adams_step_multi(tensors: TensorList, cfg: AdamsConfig, stream=None):
     cs = cfg.c_struct()
     _check(load().cast_adams_step_multi(tensors.array, tensors.count, C.byref(cs), _ptr(tensors.workspace),
                                         tensors.workspace.numel(), _stream(stream)), "cast_adams_step_multi")
+
+
+def cast_adams_multi_launches(tensors: TensorList, cfg: AdamsConfig):
+    """(launches of the step kernel, other launches) one cast_adams_step_multi call makes for this list."""
+    if tensors.count:
+        cfg.grad_dtype = tensors.grad_dtype
+    cs = cfg.c_struct()
+    a, b = C.c_int32(0), C.c_int32(0)
+    _check(load().cast_adams_multi_launches(tensors.array, tensors.count, C.byref(cs), C.byref(a), C.byref(b)),
+           "cast_adams_multi_launches")
+    return a.value, b.value
 
 
 def cast_weight_scale(w, scale, out, stream=None):

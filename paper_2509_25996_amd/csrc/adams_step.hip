@@ -840,9 +840,12 @@ static int device_compute_units()
 // launch: a work queue (see adams_step_vec_queue) over all their shares, with their buffer
 // addresses in a table that is copied, together with zeroed ticket counters, to the workspace
 // first.  Shapes the vector kernels do not take are stepped one by one.
+// With `tally` the call only counts the launches it would make (nothing is enqueued).
 cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast_adams_config *cfg,
-                                    void *workspace, hipStream_t st)
+                                    void *workspace, hipStream_t st, MultiTally *tally)
 {
+    const bool dry = tally != nullptr;
+    if (dry) *tally = MultiTally{0, 0};
     const bool bf16 = cfg->grad_dtype == CAST_BF16;
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = cfg->scale_segments > 0;
@@ -875,7 +878,8 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         groups.push_back(g);
     }
     const MultiLayout layout = multi_layout(ts, count, cfg);
-    if (!order.empty()) {
+    if (dry) tally->step_launches += (int)groups.size();
+    if (!order.empty() && !dry) {
         const size_t table_bytes = layout.table_bytes;
         std::vector<unsigned char> image(table_bytes + groups.size() * sizeof(unsigned long long), 0);
         TensorPtrs *table = reinterpret_cast<TensorPtrs *>(image.data());
@@ -932,18 +936,27 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
             if (n > 1) {
                 const SpanPlan p = plan_spans(t.rows, t.cols, t.ld, cfg->scale_segments, true);
                 if (p.vec && p.geom.pieces_per_segment == 1) {
-                    if (launch_adams_step_fused(same, n, p, cfg, st) != CAST_OK) return CAST_ERR_LAUNCH;
+                    if (dry) ++tally->step_launches;
+                    else if (launch_adams_step_fused(same, n, p, cfg, st) != CAST_OK) return CAST_ERR_LAUNCH;
                     for (int k = 0; k < n; ++k) taken[where[k]] = 1;
                     continue;
                 }
             }
+        }
+        if (dry) {       // one step launch; odd shapes with dL/dA take a reduction launch first; split plans a sum at the end
+            if (t.rows == 0 || t.cols == 0) continue;
+            const SpanPlan p = plan_spans(t.rows, t.cols, t.ld, cfg->scale_segments, layout.piece_floats > 0 && t.scale_grad);
+            ++tally->step_launches;
+            if (!p.vec && t.scale && t.scale_grad) ++tally->other_launches;
+            if (p.geom.pieces_per_segment > 1 && ++tally->split_matrices % kMaxPieceJobs == 1) ++tally->other_launches;
+            continue;
         }
         if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;     // make room
         cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
                                            t.compute_copy, t.copy_scale, layout.piece_floats ? &area : nullptr, st);
         if (rc != CAST_OK) return rc;
     }
-    return jobs.flush(st);
+    return dry ? CAST_OK : jobs.flush(st);
 }
 
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n)

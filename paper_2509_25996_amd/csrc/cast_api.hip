@@ -172,6 +172,24 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
     return launch_adams_step_multi(tensors, count, cfg, workspace, static_cast<hipStream_t>(stream));
 }
 
+cast_status cast_adams_multi_launches(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
+                                      int32_t *step_launches, int32_t *other_launches)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (!cfg || (count > 0 && !tensors)) return CAST_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const cast_tensor &t = tensors[i];
+        const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
+                                             t.compute_copy, t.copy_scale);
+        if (rc != CAST_OK) return rc;
+    }
+    MultiTally tally{0, 0};
+    const cast_status rc = launch_adams_step_multi(tensors, count, cfg, nullptr, nullptr, &tally);
+    if (step_launches) *step_launches = tally.step_launches;
+    if (other_launches) *other_launches = tally.other_launches;
+    return rc;
+}
+
 cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
                               int64_t ld, int n_segments, void *out, int out_dtype, void *stream)
 {

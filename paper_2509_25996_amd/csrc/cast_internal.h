@@ -53,8 +53,13 @@ cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const u
                               double *l1, hipStream_t stream);
 cast_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStream_t stream);
 size_t multi_workspace_bytes(const cast_tensor *tensors, int count, const cast_adams_config *cfg);
+struct MultiTally {
+    int step_launches;     // launches of the step kernels (a launch may step several matrices)
+    int other_launches;    // dL/dA reductions of odd shapes, sums of split plans
+    int split_matrices = 0;
+};
 cast_status launch_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
-                                    void *workspace, hipStream_t stream);
+                                    void *workspace, hipStream_t stream, MultiTally *tally = nullptr);
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
 
 inline cast_status launch_status()

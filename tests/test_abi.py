@@ -146,6 +146,27 @@ def test_validation_happens_before_any_launch(lib):
     assert lib.cast_hbm_copy_probe(nul, nul, 0, st) == 0
 
 
+def test_list_call_launch_tally(lib):
+    # host-only: which launches the list call would make for one LLaMA2-7B-shaped layer with n = 2 scaling
+    # (q, k, v, o share a launch; gate, up one each; down in pieces plus the sum of its pieces)
+    T = B._Tensor
+    a = 0x100000
+    layer = [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)]
+    arr = (T * 7)(*[T(a, a, a, a, a, a, a, r, c, 3 * c) for r, c in layer])
+    cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16).c_struct()
+    step, other = C.c_int32(-1), C.c_int32(-1)
+    assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
+    assert (step.value, other.value) == (4, 1)
+    cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, flags=B.FLAG_WORK_QUEUE).c_struct()
+    assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
+    assert (step.value, other.value) == (3, 0)          # one queue launch per shape
+    cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, rule=B.RULE_ADAM_L1).c_struct()
+    assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), None) == 0
+    assert step.value == 7                              # comparison rules: one launch per matrix
+    bad = (T * 1)(T(a, a, a, a, a, a, a, 4, 66, 66))
+    assert lib.cast_adams_multi_launches(bad, 1, C.byref(cfg), C.byref(step), C.byref(other)) == -2
+
+
 def test_iteration_config_reading():
     # Algorithm 1 loops t = 0..T-1 with alpha_t = t/T; masks refresh when t mod T_1 == 0
     c0 = B.iteration_config(0, 100)
