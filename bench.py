@@ -68,12 +68,14 @@ class Model:
                                A=torch.ones((r, self.segments), device=dev),
                                gA=torch.zeros((r, self.segments), device=dev)))
 
-    def tensor_list(self, B, scaled: bool, dev, queue: bool, copies=None):
+    def tensor_list(self, B, scaled: bool, dev, queue: bool, copies=None, stats=None):
         """Descriptors for the one-call-per-step entry point, marshalled once."""
         self.list = B.TensorList([dict(w=x["w"], grad=x["g"], m=x["m"], v=x["v"], mask=x["mask"],
                                        scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None,
                                        compute_copy=None if copies is None else copies[i],
-                                       copy_scale=x["A"] if scaled and copies is not None else None)
+                                       copy_scale=x["A"] if scaled and copies is not None else None,
+                                       initial_mask=None if stats is None else x["mask"],
+                                       refresh_stats=None if stats is None else stats[i])
                                   for i, x in enumerate(self.t)], dev)
         self.flags = B.FLAG_WORK_QUEUE if queue else 0
         # launches of the step kernel per call (the list call steps several small matrices with one launch)
@@ -252,18 +254,37 @@ def main():
         ms = e0.elapsed_time(e1)
         extra["mask_stats_ms"] = round(ms, 3)
         extra["mask_stats_GBs"] = round(4.25 * model.params / (ms * 1e-3) / 1e9, 1)
+        # the other entry points over the same set: mask selection alone (4.125 B/param), Eq. 12 applied into a bf16
+        # copy (6 B/param), dL/dA alone (6 B/param)
+        big = max(model.t, key=lambda x: x["w"].numel())
+        out16 = torch.empty(big["w"].shape, dtype=torch.bfloat16, device=dev)
+        for name, bpp, call in (
+                ("nm_select", 4.125, lambda x: B.cast_nm_select(x["w"], 2, 4, x["mask"])),
+                ("weight_scale_bf16", 6.0, lambda x: B.cast_weight_scale(x["w"], x["A"], out16.view(-1)[:x["w"].numel()].view(x["w"].shape))),
+                ("weight_scale_grad", 6.0, lambda x: B.cast_weight_scale_grad(x["w"], x["g"], SEGMENTS, x["gA"]))):
+            if not scaled and name != "nm_select":
+                continue
+            for rep in range(2):
+                e0.record()
+                for x in model.t:
+                    call(x)
+                e1.record()
+                torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            extra[f"{name}_ms"] = round(ms, 3)
+            extra[f"{name}_GBs"] = round(bpp * model.params / (ms * 1e-3) / 1e9, 1)
+        del out16
         if model.list is not None:
             # the widened forms of the step, over the same set and through the same list call: a comparison
             # rule (Eq. 10), and the step that also writes the bf16 weights of the next forward pass
             # (28.125 B/param: 2 more bytes written)
-            def timed(flags_rule, reps=10):
-                t_ = 1
+            def timed(flags_rule, reps=10, t_=1):
                 model.rule = flags_rule
                 for _ in range(2):
                     model.step(B, t_, scaled)
                 e0.record()
                 for _ in range(reps):
-                    model.step(B, t_, scaled)      # t_ = 1: non-refresh steps
+                    model.step(B, t_, scaled)      # t_ = 1: non-refresh steps; t_ = 10: refresh steps
                 e1.record()
                 torch.cuda.synchronize()
                 model.rule = 0
@@ -274,7 +295,13 @@ def main():
             extra["emit_compute_copy_ms_step"] = round(ms, 3)
             extra["emit_compute_copy_GBs"] = round((BYTES_PER_PARAM + 2) * model.params / (ms * 1e-3) / 1e9, 1)
             del copies
+            # refresh steps that also gather the mask-learning statistics (one more mask word read per 32 entries,
+            # per-workgroup sums through the workspace), against plain refresh steps
+            stats = [B.alloc_refresh_stats(dev) for _ in model.t]
+            model.tensor_list(B, scaled, dev, queue=False, stats=stats)
+            extra["refresh_with_stats_ms_step"] = round(timed(0, t_=10), 3)
             model.tensor_list(B, scaled, dev, queue=False)
+            extra["refresh_ms_step"] = round(timed(0, t_=10), 3)
             for name, rule in (("adamw_l1", B.RULE_ADAMW_L1), ("adam_l1", B.RULE_ADAM_L1), ("additive", B.RULE_ADDITIVE),
                                ("masked_frozen", B.RULE_MASKED_FROZEN)):
                 ms = timed(rule)

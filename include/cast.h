@@ -174,6 +174,21 @@ cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v,
  *                        caller; it is overwritten by every call and used by the kernels of that
  *                        call, so it must not be shared between streams (too small: CAST_ERR_SHAPE)
  */
+/* Mask-learning statistics of one matrix gathered by a refresh step itself (appendix "Mask
+ * Learning"; the numerators of the flip rate r_t and the initial flip rate i_t, and both terms of
+ * the sparse weight ratio S_t), from the weights as they come in:
+ *   flips_prev = ||M_new - M_stored||_0   against the mask mask_bits held when the call began
+ *   flips_init = ||M_new - M_initial||_0  against initial_mask_bits (0 when that is NULL)
+ *   l1_kept    = ||W (.) M_new||_1,  l1_all = ||W||_1
+ * Counts are exact; the norms are summed in a fixed order (fp32 within a workgroup, double across
+ * workgroups), so they are reproducible and within 1e-6 relative of a double sum. */
+typedef struct {
+    uint64_t flips_prev;
+    uint64_t flips_init;
+    double   l1_kept;
+    double   l1_all;
+} cast_refresh_stats;
+
 typedef struct {
     float *w;
     const void *grad;
@@ -185,6 +200,9 @@ typedef struct {
     int64_t rows, cols, ld;
     void *compute_copy;         /* as in cast_adams_step_emit, or NULL */
     const float *copy_scale;    /* as in cast_adams_step_emit, or NULL */
+    const uint32_t *initial_mask_bits;   /* DEVICE in, or NULL: see cast_refresh_stats */
+    cast_refresh_stats *refresh_stats;   /* DEVICE out, or NULL: overwritten by calls with          */
+                                         /* cfg->refresh_mask = 1, left alone by the others         */
 } cast_tensor;
 
 size_t cast_adams_multi_workspace_bytes(const cast_tensor *tensors /* HOST */, int count,

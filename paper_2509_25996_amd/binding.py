@@ -34,7 +34,8 @@ class _Tensor(C.Structure):
     _fields_ = [("w", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p),
                 ("mask_bits", C.c_void_p), ("scale", C.c_void_p), ("scale_grad", C.c_void_p),
                 ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
-                ("compute_copy", C.c_void_p), ("copy_scale", C.c_void_p)]
+                ("compute_copy", C.c_void_p), ("copy_scale", C.c_void_p),
+                ("initial_mask_bits", C.c_void_p), ("refresh_stats", C.c_void_p)]
 
 
 class _Config(C.Structure):
@@ -208,10 +209,22 @@ def cast_adams_multi_workspace_bytes(array, count: int, cfg: "AdamsConfig") -> i
     return load().cast_adams_multi_workspace_bytes(array, count, C.byref(cs))
 
 
+def alloc_refresh_stats(device="cuda:0") -> "torch.Tensor":
+    """Device storage of one cast_refresh_stats (two uint64 counts, two doubles)."""
+    return torch.zeros(4, dtype=torch.int64, device=device)
+
+
+def read_refresh_stats(t: "torch.Tensor") -> dict:
+    """A cast_refresh_stats written by a refresh step, as Python numbers (synchronises)."""
+    h = t.cpu()
+    norms = h[2:].view(torch.float64)
+    return {"flips_prev": int(h[0]), "flips_init": int(h[1]), "l1_kept": float(norms[0]), "l1_all": float(norms[1])}
+
+
 class TensorList:
     """The descriptors of a list of matrices for cast_adams_step_multi, marshalled once, plus the
     device workspace the call needs.  Each item is a dict with w, grad, m, v, mask and optionally
-    scale, scale_grad (tensors)."""
+    scale, scale_grad, compute_copy, copy_scale, initial_mask, refresh_stats (tensors)."""
 
     def __init__(self, items, device="cuda:0"):
         self.items = list(items)     # keeps the tensors alive
@@ -227,13 +240,17 @@ class TensorList:
             self.grad_dtype = dt
             sc, sg = x.get("scale"), x.get("scale_grad")
             cp, cps = x.get("compute_copy"), x.get("copy_scale")
-            _dev(cp, cps)
+            im, rs = x.get("initial_mask"), x.get("refresh_stats")
+            _dev(cp, cps, im, rs)
+            if rs is not None and (rs.dtype != torch.int64 or rs.numel() != 4):
+                raise TypeError("refresh_stats must come from alloc_refresh_stats()")
             if cp is not None and cp.dtype != torch.bfloat16:
                 raise TypeError("compute_copy must be bfloat16")
             self.array[k] = _Tensor(w.data_ptr(), x["grad"].data_ptr(), m.data_ptr(), v.data_ptr(), x["mask"].data_ptr(),
                                     None if sc is None else sc.data_ptr(), None if sg is None else sg.data_ptr(),
                                     w.shape[0], w.shape[1], _ld(w, m, v),
-                                    None if cp is None else cp.data_ptr(), None if cps is None else cps.data_ptr())
+                                    None if cp is None else cp.data_ptr(), None if cps is None else cps.data_ptr(),
+                                    None if im is None else im.data_ptr(), None if rs is None else rs.data_ptr())
         self.count = n
         # the workspace depends on the shapes, on the number of scaling segments and on the launch form
         segments = {0 if x.get("scale") is None else x["scale"].shape[1] for x in self.items if x["w"].numel()}

@@ -26,7 +26,18 @@ struct TensorPtrs {
     const float *scale;
     float *scale_grad;
     float *piece_sums;    // split plans: one partial dL/dA sum per piece, else unused
-};                        // 64 bytes per entry
+    // Flavours that gather refresh statistics only (never read by the work queue):
+    struct StatsPartial *stats_partials;   // one slot per workgroup of the launch, or NULL
+    const uint32_t *initial_mask;          // the mask flips_init counts against, or NULL
+};                        // 80 bytes per entry; the work queue reads the first 64
+
+// What one workgroup contributes to the mask-learning statistics of a refresh step
+// (appendix "Mask Learning"): changed mask bits against the stored and the initial mask, and
+// the L1 norms of the kept and of all incoming weights.
+struct StatsPartial {
+    uint32_t flips_prev, flips_init;
+    float l1_kept, l1_all;
+};
 
 // The table is addressed through the constant address space: its entries do not change while a
 // kernel runs, and only then are they read with scalar loads, straight into the scalar registers
@@ -57,15 +68,19 @@ struct Chunk {
     vu4_t w, m, v;
     vu4_t g;          // fp32 gradient: 4 dwords; bf16: the first 2 dwords hold 4 values
     uint32_t word;    // the mask word that holds this lane's 4 bits (non-refresh steps)
+    uint32_t initial; // the same word of the initial mask (refresh steps that gather statistics)
 };
 
 // The five streams of one span, each behind a buffer resource whose length is the span's own,
 // so that any access past the end of the span is void (loads give 0, stores are dropped).
 struct SpanBuffers {
     __amdgpu_buffer_rsrc_t w, m, v, g, mask;
+    __amdgpu_buffer_rsrc_t initial_mask;      // flavours with refresh statistics only
 };
 
-template <bool BF16, bool REFRESH>
+// WORD: whether the stored mask word is wanted (non-refresh steps; refresh steps that count flips);
+// INITIAL: whether the initial mask's word is (the latter only)
+template <bool BF16, bool WORD, bool INITIAL = false>
 __device__ __forceinline__ void chunk_load(Chunk<BF16> &c, const SpanBuffers &b, int off)
 {
     c.w = __builtin_amdgcn_raw_buffer_load_b128(b.w, off * 4, 0, kAuxLoad);
@@ -77,8 +92,10 @@ __device__ __forceinline__ void chunk_load(Chunk<BF16> &c, const SpanBuffers &b,
     }
     c.m = __builtin_amdgcn_raw_buffer_load_b128(b.m, off * 4, 0, kAuxLoad);
     c.v = __builtin_amdgcn_raw_buffer_load_b128(b.v, off * 4, 0, kAuxLoad);
-    if constexpr (!REFRESH) c.word = __builtin_amdgcn_raw_buffer_load_b32(b.mask, (off >> 5) * 4, 0, kAuxLoad);
+    if constexpr (WORD) c.word = __builtin_amdgcn_raw_buffer_load_b32(b.mask, (off >> 5) * 4, 0, kAuxLoad);
     else c.word = 0;
+    if constexpr (INITIAL) c.initial = __builtin_amdgcn_raw_buffer_load_b32(b.initial_mask, (off >> 5) * 4, 0, kAuxLoad);
+    else c.initial = 0;
 }
 
 __device__ __forceinline__ void unpack4(const vu4_t &x, float (&f)[4])
@@ -105,6 +122,7 @@ struct SpanCtx {
     __amdgpu_buffer_rsrc_t copy;   // EXTRA: the span's part of the bf16 compute copy
     float copy_A;                  // EXTRA: the factor folded into it
     bool emit;                     // EXTRA: whether there is a compute copy to write
+    StatsPartial *stats_slot;      // EXTRA: where this workgroup leaves its refresh statistics, or NULL
 };
 
 // `matrix` selects the buffer set (entry of the table of a list call), `block` the workgroup's
@@ -170,6 +188,11 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
         // without a copy the resource is empty: every store through it would be void anyway
         c.copy = span_resource(a.compute_copy + (c.emit ? o.dense_begin : 0), c.emit ? c.len * 2 : 0);
         if (c.emit && a.copy_scale && c.len > 0) c.copy_A = a.copy_scale[c.segment];
+        c.stats_slot = t.stats_partials ? t.stats_partials + block : nullptr;
+        const bool initial = t.stats_partials && t.initial_mask;
+        c.b.initial_mask = span_resource(t.initial_mask + (initial ? (o.dense_begin >> 5) : 0), initial ? c.len / 8 : 0);
+    } else {
+        c.stats_slot = nullptr;
     }
 }
 
@@ -182,10 +205,19 @@ __device__ __forceinline__ int first_offset(const SpanCtx &c, int lane) { return
 // carry zeros through the arithmetic and the buffer range check voids their stores, so the
 // cross-lane steps (M = 8 key exchange, mask word assembly, the dL/dA butterfly) always see
 // all 64 lanes.
+// LDS through which the wavefronts of a workgroup combine their refresh statistics.
+struct StatsShared {
+    uint32_t flips[kMaxBlockWaves];       // flips against the stored mask | flips against the initial mask << 16
+    float l1_kept[kMaxBlockWaves], l1_all[kMaxBlockWaves];
+};
+
 template <int M, bool BF16, bool REFRESH, bool SCALED, int EXTRA = 0>
 __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Chunk<BF16> cur, int lane, int wave,
-                                         float *partial)
+                                         float *partial, StatsShared *stats_shared = nullptr)
 {
+    constexpr bool kStats = REFRESH && EXTRA != 0;      // refresh statistics are gathered if c.stats_slot says so
+    uint32_t flips_prev = 0, flips_init = 0;
+    float l1_kept = 0.0f, l1_all = 0.0f;
     const int P = a.geom.waves_per_span;
     const int len = c.len;
     const SpanBuffers &b = c.b;
@@ -196,7 +228,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
     int off = first_offset(c, lane);      // this lane's first entry, relative to the span
     for (int base = c.sub * kChunk; base < len; base += stride) {
         Chunk<BF16> nxt;
-        chunk_load<BF16, REFRESH>(nxt, b, off + stride);        // past the end: all zeros, never used
+        chunk_load<BF16, (!REFRESH || EXTRA != 0), (REFRESH && EXTRA != 0)>(nxt, b, off + stride);     // past the end: all zeros, never used
 
         float w[4], g[4], mu[4], v[4];
         unpack4(cur.w, w);
@@ -210,6 +242,21 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         uint32_t nib;
         if constexpr (REFRESH) {
             nib = keep_nibble<M>(w, a.s.n_keep, lane);                   // from the incoming weights
+            if constexpr (kStats) {
+                if (c.stats_slot) {      // appendix "Mask Learning": flips against the stored and the initial mask, L1 norms
+                    const uint32_t shift = off & 31;
+                    if (off < len) {     // (lanes past the end hold zeros, of which the first N of a group count as kept)
+                        flips_prev += __popc((nib ^ (cur.word >> shift)) & 0xFu);
+                        flips_init += __popc((nib ^ (cur.initial >> shift)) & 0xFu);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float mag = __builtin_fabsf(w[j]);
+                        l1_all = l1_all + mag;
+                        l1_kept = l1_kept + (((nib >> j) & 1u) ? mag : 0.0f);
+                    }
+                }
+            }
             const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
             if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, b.mask, (off >> 5) * 4, 0, kAuxStore);
         } else {
@@ -239,6 +286,19 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         off += stride;
     }
 
+    bool synced = false;      // whether a workgroup barrier has been passed since the statistics went to LDS
+    if constexpr (kStats) {
+        if (c.stats_slot) {      // uniform over the workgroup: every wavefront leaves its sums in LDS
+            const uint32_t flips = wave_sum_u32(flips_prev | (flips_init << 16));     // at most 64 * 4 * 64 each
+            l1_kept = wave_sum_fixed_order(l1_kept);
+            l1_all = wave_sum_fixed_order(l1_all);
+            if (lane == 0) {
+                stats_shared->flips[wave] = flips;
+                stats_shared->l1_kept[wave] = l1_kept;
+                stats_shared->l1_all[wave] = l1_all;
+            }
+        }
+    }
     if constexpr (SCALED) {
         if (want_gA) {   // uniform over the workgroup
             const float wave_total = wave_sum_fixed_order(acc);
@@ -247,11 +307,29 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
             } else {
                 if (lane == 0) partial[wave] = wave_total;
                 __syncthreads();
+                synced = true;
                 if (lane == 0 && c.sub == 0 && len > 0) {
                     float sum = partial[wave];
                     for (int p = 1; p < P; ++p) sum = sum + partial[wave + p];
                     c.scale_grad[c.span] = sum;
                 }
+            }
+        }
+    }
+    if constexpr (kStats) {
+        if (c.stats_slot) {      // one slot per workgroup, the wavefronts' sums added in wavefront order
+            if (!synced) __syncthreads();
+            if (threadIdx.x == 0) {
+                uint32_t flips = 0;
+                StatsPartial out{0, 0, 0.0f, 0.0f};
+                for (int k = 0; k < (int)(blockDim.x / kWave); ++k) {
+                    flips = stats_shared->flips[k];
+                    out.flips_prev += flips & 0xFFFFu;
+                    out.flips_init += flips >> 16;
+                    out.l1_kept = k == 0 ? stats_shared->l1_kept[0] : out.l1_kept + stats_shared->l1_kept[k];
+                    out.l1_all = k == 0 ? stats_shared->l1_all[0] : out.l1_all + stats_shared->l1_all[k];
+                }
+                *c.stats_slot = out;
             }
         }
     }
@@ -272,8 +350,13 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     SpanCtx c;
     span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
     Chunk<BF16> first;
-    chunk_load<BF16, REFRESH>(first, c.b, first_offset(c, lane));
-    span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial);
+    chunk_load<BF16, (!REFRESH || EXTRA != 0), (REFRESH && EXTRA != 0)>(first, c.b, first_offset(c, lane));
+    if constexpr (REFRESH && EXTRA != 0) {
+        __shared__ StatsShared stats_shared;
+        span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial, &stats_shared);
+    } else {
+        span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial);
+    }
 }
 
 // Work queue: a fixed set of resident workgroups draws runs of consecutive shares, in order, from
@@ -313,7 +396,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const S
         const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
         SpanCtx c;
         span_open<BF16, SCALED, true>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
-        chunk_load<BF16, REFRESH>(cur, c.b, first_offset(c, lane));
+        chunk_load<BF16, !REFRESH>(cur, c.b, first_offset(c, lane));
     }
     if (threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
 
@@ -333,7 +416,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const S
             const uint32_t matrix = fast_div(next_share, q.div_blocks_per_matrix);
             SpanCtx ahead;
             span_open<BF16, SCALED, true>(a, matrix, (int64_t)(next_share - matrix * q.blocks_per_matrix), wave, ahead);
-            chunk_load<BF16, REFRESH>(nxt, ahead.b, first_offset(ahead, lane));
+            chunk_load<BF16, !REFRESH>(nxt, ahead.b, first_offset(ahead, lane));
             if (last_of_run && threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
         }
         {
@@ -533,6 +616,129 @@ __global__ __launch_bounds__(kBlockThreads) void scale_grad_rows(const float *w,
     const float t = wave_sum_fixed_order(acc);
     if (lane == 0 && live) scale_grad[seg] = t;
 }
+
+// Refresh statistics for shapes the vector kernels do not take: one thread per 64 columns of a row,
+// run before the step (it needs the stored mask and the incoming weights); the new mask is
+// worked out here a second time.  One slot per workgroup, like the vector kernels.
+template <int M>
+__global__ __launch_bounds__(kBlockThreads) void refresh_stats_unit(const float *w, const uint32_t *mask,
+                                                                    const uint32_t *initial_mask, int64_t rows, int64_t cols,
+                                                                    int64_t ld, int n_keep, StatsPartial *partials)
+{
+    __shared__ StatsShared sh;
+    const int64_t units_per_row = (cols + 63) / 64;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t flips_prev = 0, flips_init = 0;
+    float l1_kept = 0.0f, l1_all = 0.0f;
+    if (tid < rows * units_per_row) {
+        const int64_t r = tid / units_per_row, c0 = (tid % units_per_row) * 64;
+        const int64_t words_per_row = (cols + 31) / 32;
+        for (int half = 0; half < 2; ++half) {
+            const int64_t cb = c0 + half * 32;
+            if (cb >= cols) break;
+            const int64_t ce = (cb + 32 < cols) ? cb + 32 : cols;
+            const int64_t word_index = r * words_per_row + cb / 32;
+            uint32_t fresh = 0;
+            for (int64_t c = cb; c < ce; c += M) {
+                float wv[M];
+#pragma unroll
+                for (int j = 0; j < M; ++j) wv[j] = w[r * ld + c + j];
+                const uint32_t bits = keep_bits_group<M>(wv, n_keep);
+                fresh |= bits << (unsigned)(c - cb);
+#pragma unroll
+                for (int j = 0; j < M; ++j) {
+                    const float mag = __builtin_fabsf(wv[j]);
+                    l1_all = l1_all + mag;
+                    l1_kept = l1_kept + (((bits >> j) & 1u) ? mag : 0.0f);
+                }
+            }
+            flips_prev += __popc(fresh ^ mask[word_index]);
+            if (initial_mask) flips_init += __popc(fresh ^ initial_mask[word_index]);
+        }
+    }
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    flips_prev = wave_sum_u32(flips_prev);
+    flips_init = wave_sum_u32(flips_init);
+    l1_kept = wave_sum_fixed_order(l1_kept);
+    l1_all = wave_sum_fixed_order(l1_all);
+    __shared__ uint32_t sh_init[kBlockWaves];
+    if (lane == 0) { sh.flips[wave] = flips_prev; sh_init[wave] = flips_init; sh.l1_kept[wave] = l1_kept; sh.l1_all[wave] = l1_all; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        StatsPartial out{flips_prev, flips_init, l1_kept, l1_all};
+        for (int k = 1; k < kBlockWaves; ++k) {
+            out.flips_prev += sh.flips[k];
+            out.flips_init += sh_init[k];
+            out.l1_kept = out.l1_kept + sh.l1_kept[k];
+            out.l1_all = out.l1_all + sh.l1_all[k];
+        }
+        partials[blockIdx.x] = out;
+    }
+}
+
+// Second half of the refresh statistics: the slots of a matrix added up, counts exactly, norms in
+// double, always in the same order (each thread a strided share, then a tree), so the result is
+// reproducible.  One workgroup per matrix, up to kMaxStatsJobs matrices per launch.
+struct StatsJob {
+    const StatsPartial *partials;
+    int64_t slots;
+    cast_refresh_stats *out;
+    int has_initial;
+};
+
+constexpr int kMaxStatsJobs = 32;
+
+struct StatsJobs {
+    StatsJob job[kMaxStatsJobs];
+};
+
+__global__ __launch_bounds__(kMaxBlockThreads) void sum_refresh_stats(const StatsJobs jobs)
+{
+    __shared__ unsigned long long sh_prev[kMaxBlockThreads], sh_init[kMaxBlockThreads];
+    __shared__ double sh_kept[kMaxBlockThreads], sh_all[kMaxBlockThreads];
+    const StatsJob &j = jobs.job[blockIdx.x];
+    unsigned long long prev = 0, init = 0;
+    double kept = 0.0, all = 0.0;
+    for (int64_t i = threadIdx.x; i < j.slots; i += kMaxBlockThreads) {
+        const StatsPartial p = j.partials[i];
+        prev += p.flips_prev;
+        init += p.flips_init;
+        kept += (double)p.l1_kept;
+        all += (double)p.l1_all;
+    }
+    sh_prev[threadIdx.x] = prev; sh_init[threadIdx.x] = init; sh_kept[threadIdx.x] = kept; sh_all[threadIdx.x] = all;
+    __syncthreads();
+    for (int half = kMaxBlockThreads / 2; half > 0; half >>= 1) {
+        if ((int)threadIdx.x < half) {
+            sh_prev[threadIdx.x] += sh_prev[threadIdx.x + half];
+            sh_init[threadIdx.x] += sh_init[threadIdx.x + half];
+            sh_kept[threadIdx.x] += sh_kept[threadIdx.x + half];
+            sh_all[threadIdx.x] += sh_all[threadIdx.x + half];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        j.out->flips_prev = sh_prev[0];
+        j.out->flips_init = j.has_initial ? sh_init[0] : 0ull;
+        j.out->l1_kept = sh_kept[0];
+        j.out->l1_all = sh_all[0];
+    }
+}
+
+struct StatsJobQueue {
+    StatsJobs pending;
+    int count = 0;
+
+    cast_status flush(hipStream_t st)
+    {
+        if (count == 0) return CAST_OK;
+        hipLaunchKernelGGL(sum_refresh_stats, dim3((unsigned)count), dim3(kMaxBlockThreads), 0, st, pending);
+        count = 0;
+        return launch_status();
+    }
+    bool full() const { return count == kMaxStatsJobs; }
+    void add(const StatsJob &j) { pending.job[count++] = j; }      // not when full()
+};
 
 // ---- host side ------------------------------------------------------------------------------
 
@@ -741,23 +947,37 @@ cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, 
 
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              int64_t ld, const cast_adams_config *cfg, void *compute_copy, const float *copy_scale,
-                              PieceArea *area, hipStream_t st)
+                              int64_t ld, const cast_adams_config *cfg, const StepExtras &x, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    // a compute copy to write, or a comparison rule with code of its own: the EXTRA instantiations
-    const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
-    const int extra = own_rule ? 2 : (compute_copy != nullptr ? 1 : 0);
     const bool bf16 = cfg->grad_dtype == CAST_BF16;
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = scale != nullptr;
+    PieceArea *area = x.area;
     SpanPlan p = plan_spans(rows, cols, ld, cfg->scale_segments, area != nullptr && scale_grad != nullptr);
     if (p.geom.pieces_per_segment > 1 && (uint64_t)p.geom.num_spans > area->floats)
         p = plan_spans(rows, cols, ld, cfg->scale_segments, false);       // no room for the pieces' sums
     const bool split = p.geom.pieces_per_segment > 1;
+    // refresh statistics: one slot per workgroup in the caller's workspace, added up afterwards
+    const int64_t unit_grid = (rows * ((cols + 63) / 64) + kBlockThreads - 1) / kBlockThreads;
+    const uint64_t stats_slots = p.vec ? p.grid : (uint64_t)unit_grid;
+    const bool stats = refresh && x.refresh_stats != nullptr && x.stats_area != nullptr && stats_slots <= x.stats_area->slots;
+    if (refresh && x.refresh_stats != nullptr && !stats) return CAST_ERR_SHAPE;      // workspace too small (not reachable through the API)
+    StatsPartial *stats_partials = stats ? x.stats_area->base : nullptr;
+    const uint32_t *stats_initial = stats ? x.initial_mask : nullptr;
+    if (stats) {
+        x.stats_area->base += stats_slots;
+        x.stats_area->slots -= stats_slots;
+        static_cast<StatsJobQueue *>(x.stats_area->jobs)->add(StatsJob{stats_partials, (int64_t)stats_slots, x.refresh_stats,
+                                                                        x.initial_mask != nullptr});
+    }
+    // a compute copy to write or refresh statistics to gather (1), or a comparison rule with code of
+    // its own (2): the EXTRA instantiations
+    const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
+    const int extra = own_rule ? 2 : ((x.compute_copy != nullptr || stats) ? 1 : 0);
     if (p.vec) {
-        SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr}}, as_const_table(nullptr), p.geom,
-                   make_scalars(cfg), static_cast<uint16_t *>(compute_copy), copy_scale};
+        SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial}},
+                   as_const_table(nullptr), p.geom, make_scalars(cfg), static_cast<uint16_t *>(x.compute_copy), x.copy_scale};
         launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0, split, extra}, a, st);
         if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         if (split) {      // this matrix's part of the area is now in use until the pieces have been added up
@@ -769,15 +989,23 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
         }
         return CAST_OK;
     }
-    // odd shapes: dL/dA first (it needs the incoming weights), then the element pass
+    // odd shapes: refresh statistics and dL/dA first (they need the stored mask and the incoming weights), then the element pass
+    if (stats) {
+        const dim3 grid((unsigned)unit_grid), block(kBlockThreads);
+        switch (cfg->m_group) {
+        case 2: hipLaunchKernelGGL(refresh_stats_unit<2>, grid, block, 0, st, w, mask_bits, stats_initial, rows, cols, ld, cfg->n_keep, stats_partials); break;
+        case 4: hipLaunchKernelGGL(refresh_stats_unit<4>, grid, block, 0, st, w, mask_bits, stats_initial, rows, cols, ld, cfg->n_keep, stats_partials); break;
+        default: hipLaunchKernelGGL(refresh_stats_unit<8>, grid, block, 0, st, w, mask_bits, stats_initial, rows, cols, ld, cfg->n_keep, stats_partials); break;
+        }
+        if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+    }
     if (scaled && scale_grad) {
         cast_status rc = launch_scale_grad(w, grad, cfg->grad_dtype, rows, cols, ld, cfg->scale_segments, scale_grad, st);
         if (rc != CAST_OK) return rc;
     }
     UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, ld, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg),
-               static_cast<uint16_t *>(compute_copy), copy_scale};
-    const int64_t units = rows * ((cols + 63) / 64);
-    const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
+               static_cast<uint16_t *>(x.compute_copy), x.copy_scale};
+    const unsigned grid = (unsigned)unit_grid;
     switch (cfg->m_group) {
     case 2: launch_unit_dtype<2>(bf16, grid, a, st); break;
     case 4: launch_unit_dtype<4>(bf16, grid, a, st); break;
@@ -793,7 +1021,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
 {
     SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg), nullptr, nullptr};
     for (int k = 0; k < n; ++k)
-        a.set[k] = TensorPtrs{ts[k]->w, ts[k]->grad, ts[k]->m, ts[k]->v, ts[k]->mask_bits, ts[k]->scale, ts[k]->scale_grad, nullptr};
+        a.set[k] = TensorPtrs{ts[k]->w, ts[k]->grad, ts[k]->m, ts[k]->v, ts[k]->mask_bits, ts[k]->scale, ts[k]->scale_grad, nullptr, nullptr, nullptr};
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, cfg->refresh_mask != 0, cfg->scale_segments > 0,
                    VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, 0}, a, st);
     return launch_status();
@@ -804,14 +1032,25 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
 struct MultiLayout {
     size_t table_bytes, counter_bytes;
     uint64_t piece_floats;
-    size_t total() const { return table_bytes + counter_bytes + (size_t)piece_floats * sizeof(float); }
+    uint64_t stats_slots;
+    size_t total() const
+    {
+        return table_bytes + counter_bytes + (size_t)piece_floats * sizeof(float) + (size_t)stats_slots * sizeof(StatsPartial);
+    }
 };
 
 static MultiLayout multi_layout(const cast_tensor *ts, int count, const cast_adams_config *cfg)
 {
     const size_t n = (size_t)(count > 0 ? count : 0);
-    MultiLayout l{n * sizeof(TensorPtrs), (n * sizeof(unsigned long long) + 15) & ~(size_t)15, 0};
-    if (ts && cfg && cfg->scale_segments > 0 && !(cfg->flags & CAST_FLAG_WORK_QUEUE))
+    MultiLayout l{n * sizeof(TensorPtrs), (n * sizeof(unsigned long long) + 15) & ~(size_t)15, 0, 0};
+    for (size_t i = 0; ts && cfg && i < n; ++i) {      // a slot per workgroup for every matrix that wants refresh statistics
+        if (ts[i].rows <= 0 || ts[i].cols <= 0 || !ts[i].refresh_stats) continue;
+        const bool may_split = cfg->scale_segments > 0 && ts[i].scale_grad;
+        const SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments, may_split);
+        const int64_t unit_grid = (ts[i].rows * ((ts[i].cols + 63) / 64) + kBlockThreads - 1) / kBlockThreads;
+        l.stats_slots += p.vec ? p.grid : (uint64_t)unit_grid;
+    }
+    if (ts && cfg && cfg->scale_segments > 0)
         for (size_t i = 0; i < n; ++i) {
             if (ts[i].rows <= 0 || ts[i].cols <= 0 || !ts[i].scale_grad) continue;
             const SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments, true);
@@ -853,8 +1092,9 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
     // the work queue knows neither the comparison rules with code of their own nor the compute copy
     if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN) use_queue = false;
+    const bool want_stats = cfg->refresh_mask != 0;
     for (int i = 0; i < count; ++i)
-        if (ts[i].compute_copy) use_queue = false;
+        if (ts[i].compute_copy || (want_stats && ts[i].refresh_stats)) use_queue = false;      // nor refresh statistics
     // tuning knobs (read once): resident wavefronts per compute unit of the work queue
     static const int waves_per_cu = env_int("CAST_QUEUE_WAVES_PER_CU", 16);
     static const int log2_run = env_int("CAST_QUEUE_LOG2_RUN", 1) & 7;      // shares per ticket = 1 << log2_run
@@ -885,7 +1125,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         TensorPtrs *table = reinterpret_cast<TensorPtrs *>(image.data());
         for (size_t k = 0; k < order.size(); ++k) {
             const cast_tensor &t = ts[order[k]];
-            table[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, nullptr};
+            table[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, nullptr, nullptr, nullptr};
         }
         // pageable source: the runtime stages it before returning, the copy itself is ordered on the stream
         if (hipMemcpyAsync(workspace, image.data(), image.size(), hipMemcpyHostToDevice, st) != hipSuccess)
@@ -908,6 +1148,8 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     PieceJobQueue jobs;
     PieceArea area{reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes),
                    layout.piece_floats, &jobs};
+    StatsJobQueue stats_jobs;
+    StatsArea stats_area{reinterpret_cast<StatsPartial *>(area.base + layout.piece_floats), layout.stats_slots, &stats_jobs};
     // Small matrices of one shape share a launch (they need not follow each other in the list: the
     // matrices are independent).  A launch is kept below about 72 M entries: q, k, v, o of a
     // LLaMA2-7B layer go together, 16 of the 768 x 768 matrices of a 125M model; longer launches
@@ -919,7 +1161,9 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
-        if (!own_rule && fuse_limit > 1 && t.rows > 0 && t.cols > 0 && !t.compute_copy && t.rows * t.cols <= fuse_max_params) {
+        const bool with_stats = want_stats && t.refresh_stats != nullptr;
+        if (!own_rule && fuse_limit > 1 && t.rows > 0 && t.cols > 0 && !t.compute_copy && !with_stats &&
+            t.rows * t.cols <= fuse_max_params) {
             int most = (int)(fuse_launch_params / (t.rows * t.cols));
             if (most > fuse_limit) most = fuse_limit;
             if (most > kMaxFused) most = kMaxFused;
@@ -927,7 +1171,8 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
             int where[kMaxFused] = {i};
             int n = 1;
             for (int j = i + 1; j < count && n < most; ++j)
-                if (!taken[j] && !ts[j].compute_copy && ts[j].rows == t.rows && ts[j].cols == t.cols && ts[j].ld == t.ld &&
+                if (!taken[j] && !ts[j].compute_copy && !(want_stats && ts[j].refresh_stats) && ts[j].rows == t.rows &&
+                    ts[j].cols == t.cols && ts[j].ld == t.ld &&
                     (ts[j].scale_grad == nullptr) == (t.scale_grad == nullptr)) {
                     same[n] = &ts[j];
                     where[n] = j;
@@ -949,14 +1194,27 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
             ++tally->step_launches;
             if (!p.vec && t.scale && t.scale_grad) ++tally->other_launches;
             if (p.geom.pieces_per_segment > 1 && ++tally->split_matrices % kMaxPieceJobs == 1) ++tally->other_launches;
+            if (with_stats) {
+                if (!p.vec) ++tally->other_launches;
+                if (++tally->stats_matrices % kMaxStatsJobs == 1) ++tally->other_launches;
+            }
             continue;
         }
         if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;     // make room
-        cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
-                                           t.compute_copy, t.copy_scale, layout.piece_floats ? &area : nullptr, st);
+        if (stats_jobs.full() && stats_jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
+        StepExtras x;
+        x.compute_copy = t.compute_copy;
+        x.copy_scale = t.copy_scale;
+        x.initial_mask = t.initial_mask_bits;
+        x.refresh_stats = t.refresh_stats;
+        x.area = layout.piece_floats ? &area : nullptr;
+        x.stats_area = layout.stats_slots ? &stats_area : nullptr;
+        cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg, x, st);
         if (rc != CAST_OK) return rc;
     }
-    return dry ? CAST_OK : jobs.flush(st);
+    if (dry) return CAST_OK;
+    if (jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
+    return stats_jobs.flush(st);
 }
 
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n)

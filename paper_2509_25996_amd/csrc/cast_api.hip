@@ -135,8 +135,10 @@ cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v,
     const cast_status rc = validate_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, compute_copy, copy_scale);
     if (rc != CAST_OK) return rc;
     if (rows > 0 && cols > 0 && !compute_copy) return CAST_ERR_NULL;
-    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, compute_copy, copy_scale, nullptr,
-                             static_cast<hipStream_t>(stream));
+    StepExtras x;
+    x.compute_copy = compute_copy;
+    x.copy_scale = copy_scale;
+    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, x, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
@@ -145,7 +147,7 @@ cast_status cast_adams_step(float *w, const void *grad, float *m, float *v, uint
 {
     const cast_status rc = validate_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg);
     if (rc != CAST_OK) return rc;
-    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, nullptr, nullptr, nullptr,
+    return launch_adams_step(w, grad, m, v, mask_bits, scale, scale_grad, rows, cols, ld, cfg, StepExtras{},
                              static_cast<hipStream_t>(stream));
 }
 
@@ -168,6 +170,8 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
                                              t.compute_copy, t.copy_scale);
         if (rc != CAST_OK) return rc;
     }
+    for (int i = 0; i < count; ++i)
+        if (!aligned(tensors[i].initial_mask_bits, 4) || !aligned(tensors[i].refresh_stats, 8)) return CAST_ERR_ALIGN;
     if (workspace_bytes < multi_workspace_bytes(tensors, count, cfg)) return CAST_ERR_SHAPE;
     return launch_adams_step_multi(tensors, count, cfg, workspace, static_cast<hipStream_t>(stream));
 }

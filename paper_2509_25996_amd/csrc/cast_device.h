@@ -139,6 +139,7 @@ __device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, int64_t sp
 constexpr int kDppQuadXor1 = 0xB1;       // [1,0,3,2]
 constexpr int kDppQuadXor2 = 0x4E;       // [2,3,0,1]
 constexpr int kDppRowHalfMirror = 0x141; // lane i of each 8 reads lane 7-i
+constexpr int kDppRowMirror = 0x140;     // lane i of each 16 reads lane 15-i
 
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t x)
@@ -163,12 +164,30 @@ __device__ __forceinline__ uint32_t or_reduce_8lanes(uint32_t x)
     return x;
 }
 
-// Butterfly sum over the 64 lanes in a fixed order (xor 1, 2, 4, ..., 32).
+// Sum over the 64 lanes in a fixed order, the same in every lane of the result: a butterfly inside
+// each row of 16 lanes with four DPP moves (partner lane ^1, lane ^2, mirror within 8, mirror
+// within 16: no LDS traffic), then the four row sums added in row order from scalar registers.
 __device__ __forceinline__ float wave_sum_fixed_order(float x)
 {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) x = x + __shfl_xor(x, d, kWave);
-    return x;
+    x = x + __uint_as_float(dpp_u32<kDppQuadXor1>(__float_as_uint(x)));
+    x = x + __uint_as_float(dpp_u32<kDppQuadXor2>(__float_as_uint(x)));
+    x = x + __uint_as_float(dpp_u32<kDppRowHalfMirror>(__float_as_uint(x)));
+    x = x + __uint_as_float(dpp_u32<kDppRowMirror>(__float_as_uint(x)));
+    const float r0 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), 0));
+    const float r1 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), 16));
+    const float r2 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), 32));
+    const float r3 = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(x), 48));
+    return ((r0 + r1) + r2) + r3;
+}
+
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x)
+{
+    x += dpp_u32<kDppQuadXor1>(x);
+    x += dpp_u32<kDppQuadXor2>(x);
+    x += dpp_u32<kDppRowHalfMirror>(x);
+    x += dpp_u32<kDppRowMirror>(x);
+    return __builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16) + __builtin_amdgcn_readlane(x, 32) +
+           __builtin_amdgcn_readlane(x, 48);
 }
 
 // ---- Eq. 6: which of a lane's 4 entries are kept -----------------------------------------

@@ -32,10 +32,30 @@ struct PieceArea {
     void *jobs;
 };
 
+struct StatsPartial;
+
+// Device memory for the per-workgroup refresh statistics: what is left of it, and who collects
+// the jobs that add the slots of a matrix up.
+struct StatsArea {
+    StatsPartial *base;
+    uint64_t slots;
+    void *jobs;
+};
+
+// What a step may do beyond Algorithm 1's loop body.
+struct StepExtras {
+    void *compute_copy = nullptr;              // bf16 copy of the new weights for the next forward pass
+    const float *copy_scale = nullptr;         // the A folded into it
+    const uint32_t *initial_mask = nullptr;    // refresh statistics: the mask flips_init counts against
+    cast_refresh_stats *refresh_stats = nullptr;
+    PieceArea *area = nullptr;                 // list calls: room for split plans
+    StatsArea *stats_area = nullptr;           // list calls: room for refresh statistics
+};
+
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
-                              int64_t ld, const cast_adams_config *cfg, void *compute_copy,
-                              const float *copy_scale, PieceArea *area, hipStream_t stream);
+                              int64_t ld, const cast_adams_config *cfg, const StepExtras &extras,
+                              hipStream_t stream);
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad,
                               hipStream_t stream);
@@ -57,6 +77,7 @@ struct MultiTally {
     int step_launches;     // launches of the step kernels (a launch may step several matrices)
     int other_launches;    // dL/dA reductions of odd shapes, sums of split plans
     int split_matrices = 0;
+    int stats_matrices = 0;
 };
 cast_status launch_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                     void *workspace, hipStream_t stream, MultiTally *tally = nullptr);

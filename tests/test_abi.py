@@ -126,15 +126,18 @@ def test_validation_happens_before_any_launch(lib):
     arr = (T * 2)(good, bad)
     cfg = _cfg()
     ws_bytes = lambda a, n, c: lib.cast_adams_multi_workspace_bytes(a, n, C.byref(c))
-    assert ws_bytes(arr, 2, cfg) == 144 and ws_bytes(arr, 0, cfg) == 0 and ws_bytes(None, 2, cfg) == 144
+    assert ws_bytes(arr, 2, cfg) == 176 and ws_bytes(arr, 0, cfg) == 0 and ws_bytes(None, 2, cfg) == 176    # 2 x 80 + 16
     # row segments of more than 16 chunks of 256 entries are stepped in pieces of 8 chunks whose dL/dA sums
     # pass through the workspace (one float per piece); not when the work queue steps them
     wide = (T * 2)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 3, 11008, 11008), good)
     seg = _cfg(scale_segments=2)
-    assert ws_bytes(wide, 2, seg) == 144 + 4 * 20          # 3 rows x 2 segments x 3 pieces, rounded up to 4 floats
-    assert ws_bytes(wide, 2, _cfg(scale_segments=2, flags=2)) == 144
-    assert ws_bytes(wide, 2, _cfg(scale_segments=8)) == 144
+    assert ws_bytes(wide, 2, seg) == 176 + 4 * 20          # 3 rows x 2 segments x 3 pieces, rounded up to 4 floats
+    assert ws_bytes(wide, 2, _cfg(scale_segments=2, flags=2)) == 176 + 4 * 20     # kept for matrices the queue does not take
+    assert ws_bytes(wide, 2, _cfg(scale_segments=8)) == 176
     assert lib.cast_adams_step_multi(wide, 1, C.byref(seg), p, 144, st) == -2      # no room for the sums
+    # refresh statistics: one 16-byte slot per workgroup of the matrix's launch (4 x 64 entries: one workgroup)
+    with_stats = (T * 1)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64, None, None, None, 0x10000))
+    assert ws_bytes(with_stats, 1, cfg) == 80 + 16 + 16
     assert lib.cast_adams_step_multi(arr, 2, C.byref(cfg), p, 144, st) == -2
     assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), p, 32, st) == -2       # workspace too small
     assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), nul, 80, st) == -1

@@ -614,3 +614,59 @@ def test_short_sqrt_and_division_every_mantissa(case):
     assert_same_bits(host(st.w), o.w, "w = -(g / sqrt(v))")
     assert_same_bits(host(st.v), o.v, "v")
     assert (host(st.m) == g).all()
+
+
+# --------------------------------------------------------------------------- refresh statistics gathered by the step itself
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
+def test_refresh_steps_gather_mask_learning_statistics(n, m):
+    """Flip counts against the stored and the initial mask and both L1 norms (appendix "Mask Learning") come
+    out of the refresh step itself; vector shapes, a split plan, odd shapes; exact counts, reproducible norms."""
+    shapes = [(64, 512), (16, 11008), (7, 72), (9, 24), (33, 4096 + 32), (64, 512)]
+    shapes = [(r, c) for r, c in shapes if c % m == 0 and (c // 2) % m == 0]
+    nseg, steps = 2, 5
+    rng = np.random.default_rng(17)
+
+    def run():
+        items, states = [], []
+        for i, (r, c) in enumerate(shapes):
+            w0 = synth.weights(12, i, r, c)
+            st = GpuState(w0, nseg, interleaved=(i % 2 == 0))
+            initial = B.alloc_mask(r, c, DEV)
+            B.cast_nm_select(st.w, n, m, initial)
+            stats = B.alloc_refresh_stats(DEV)
+            items.append(dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=torch.zeros((r, c), dtype=torch.bfloat16, device=DEV),
+                              scale=torch.ones((r, nseg), device=DEV), scale_grad=st.scale_grad, initial_mask=initial,
+                              refresh_stats=stats))
+            states.append((w0, st, stats))
+        tl = B.TensorList(items, DEV)
+        history = []
+        for t in range(steps):
+            for i, (r, c) in enumerate(shapes):
+                items[i]["grad"].copy_(synth.grads_bf16(12, i, t, r, c).to(DEV))
+            cfg = B.iteration_config(t, steps, mask_period=2, lr=3e-3, lambda_=2e-2, n_keep=n, m_group=m, scale_segments=nseg)
+            before = [(host(st.w).copy(), oracle.unpack_mask_bits(words(st.mask), shapes[i][1])) for i, (_, st, _) in enumerate(states)]
+            B.cast_adams_step_multi(tl, cfg)
+            torch.cuda.synchronize()
+            history.append((cfg.refresh_mask, before, [B.read_refresh_stats(s) for (_, _, s) in states],
+                            [host(s).tobytes() for (_, _, s) in states]))
+        return states, history
+
+    states, history = run()
+    flipped = 0
+    for t, (refresh, before, got, _) in enumerate(history):
+        if not refresh:
+            if t > 0:      # left alone by steps that do not refresh
+                assert got == history[t - 1][2]
+            continue
+        for i, ((w_in, keep_prev), g) in enumerate(zip(before, got)):
+            keep_new = oracle.nm_select(w_in, n, m)
+            keep_init = oracle.nm_select(states[i][0], n, m)
+            f_prev, kept, total = oracle.mask_stats(w_in, keep_new, keep_prev)
+            f_init, _, _ = oracle.mask_stats(w_in, keep_new, keep_init)
+            assert g["flips_prev"] == f_prev and g["flips_init"] == f_init, (t, shapes[i], g, f_prev, f_init)
+            assert abs(g["l1_kept"] - kept) <= 1e-6 * kept and abs(g["l1_all"] - total) <= 1e-6 * total
+            if t > 0:
+                flipped += f_prev
+    assert flipped > 0                      # the decay really moved masks between refreshes
+    _, again = run()
+    assert [h[3] for h in again] == [h[3] for h in history]      # bit for bit reproducible
