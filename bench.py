@@ -53,6 +53,7 @@ class Model:
         self.row_splits = 1
         self.flags = 0
         self.rule = 0
+        self.nm = (2, 4)
         self.launches = len(self.shapes)
         for i, (_, r, c) in enumerate(self.shapes):
             w = synth.device_gaussian((r, c), 0.02, torch.float32, 1000 + i, dev)
@@ -84,7 +85,8 @@ class Model:
 
     def step(self, B, t: int, scaled: bool):
         cfg = B.iteration_config(t, TOTAL_STEPS, mask_period=MASK_PERIOD, lr=LR, lambda_=LAMBDA,
-                                 scale_segments=self.segments if scaled else 0, flags=self.flags, rule=self.rule)
+                                 scale_segments=self.segments if scaled else 0, flags=self.flags, rule=self.rule,
+                                 n_keep=self.nm[0], m_group=self.nm[1])
         if self.list is not None:
             B.cast_adams_step_multi(self.list, cfg)
         else:
@@ -166,6 +168,8 @@ def main():
                     help="one cast_adams_step_multi call per step (default; 'queue' adds CAST_FLAG_WORK_QUEUE) "
                          "or one cast_adams_step call per matrix")
     ap.add_argument("--row-splits", type=int, default=1, help="per-matrix launch only: launches per matrix (experiment)")
+    ap.add_argument("--nm", default="2:4", choices=["1:2", "2:4", "4:8"],
+                    help="sparsity pattern of the timed steps (the metric is quoted on 2:4; the extras stay 2:4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     args = ap.parse_args()
@@ -186,6 +190,9 @@ def main():
     model = Model(args.workload, args.layers, torch, B, synth, dev, args.layout != "separate",
                   args.layout == "interleaved-segments")
     model.row_splits = args.row_splits
+    model.nm = tuple(int(x) for x in args.nm.split(":"))
+    if model.nm != (2, 4) and not args.no_extra:
+        sys.exit("--nm other than 2:4 needs --no-extra")
     if args.launch != "per-matrix":
         model.tensor_list(B, scaled, dev, queue=args.launch == "queue")
     torch.cuda.synchronize()
@@ -331,10 +338,10 @@ def main():
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
            "config": {"workload": f"{args.workload} linear weight set ({len(model.shapes)} matrices, {model.params} params), "
-                                  f"2:4, fp32 w/mu/v ({args.layout}) + bf16 grads + mask bits resident, "
+                                  f"{args.nm}, fp32 w/mu/v ({args.layout}) + bf16 grads + mask bits resident, "
                                   f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step, "
                                   f"{ {'list': 'one list call', 'queue': 'one list call (work queue)', 'per-matrix': 'one call per matrix'}[args.launch]} per step",
-                      "n_keep": 2, "m_group": 4, "scale_segments": SEGMENTS if scaled else 0,
+                      "n_keep": model.nm[0], "m_group": model.nm[1], "scale_segments": SEGMENTS if scaled else 0,
                       "pct_of_peak_hbm": round(100 * BYTES_PER_PARAM * value / HBM_PEAK_GBS, 2)},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:
