@@ -292,6 +292,23 @@ cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *
  */
 cast_status cast_debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
 
+/*
+ * Diagnostic, runs on the HOST: how the step kernels would cover a [rows, cols] matrix with row
+ * stride ld and n_segments scaling segments (allow_split as in a list call with a workspace), and
+ * where wavefront `wave` of workgroup `block` would work, computed by the very functions the
+ * kernels use.  It exists so that "every entry is covered exactly once and nothing outside the
+ * matrix is touched" can be tested for any shape without a GPU.
+ *   plan[0] = 1 if the vector kernels apply (else the scalar kernels run and the rest is unused)
+ *   plan[1] = workgroups, plan[2] = wavefronts per workgroup, plan[3] = cooperating wavefronts per span,
+ *   plan[4] = pieces per row segment (1 = not split)
+ *   span[0] = first entry in w/m/v (with row stride), span[1] = first entry in dense numbering,
+ *   span[2] = entries (0: this wavefront has nothing to do), span[3] = index into scale / scale_grad
+ *             (split plans: piece number), span[4] = its place among the cooperating wavefronts
+ */
+cast_status cast_debug_plan(int64_t rows, int64_t cols, int64_t ld, int n_segments, int allow_split,
+                            int64_t block, int wave, int64_t plan[5] /* HOST out */,
+                            int64_t span[5] /* HOST out */);
+
 #ifdef __cplusplus
 }
 #endif

@@ -265,6 +265,32 @@ cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *
     return launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+cast_status cast_debug_plan(int64_t rows, int64_t cols, int64_t ld, int n_segments, int allow_split,
+                            int64_t block, int wave, int64_t plan[5], int64_t span[5])
+{
+    if (!plan || !span) return CAST_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || ld < cols || n_segments < 0 || block < 0 || wave < 0) return CAST_ERR_SHAPE;
+    if (n_segments > 0 && cols % n_segments) return CAST_ERR_SHAPE;
+    const SpanPlan p = plan_spans(rows, cols, ld, n_segments, allow_split != 0);
+    const int block_waves = p.block_threads / kWave;
+    plan[0] = p.vec ? 1 : 0;
+    plan[1] = p.grid;
+    plan[2] = block_waves;
+    plan[3] = p.geom.waves_per_span;
+    plan[4] = p.geom.pieces_per_segment;
+    for (int k = 0; k < 5; ++k) span[k] = 0;
+    if (!p.vec || block >= (int64_t)p.grid || wave >= block_waves) return CAST_OK;
+    const SpanSlot slot = span_slot(p.geom, block, wave, block_waves);
+    int64_t segment = slot.span;
+    const SpanOrigin o = p.geom.pieces_per_segment > 1 ? piece_origin(p.geom, slot.span, segment) : span_origin(p.geom, slot.span);
+    span[0] = o.state_begin;
+    span[1] = o.dense_begin;
+    span[2] = o.len;
+    span[3] = slot.span;
+    span[4] = slot.sub;
+    return CAST_OK;
+}
+
 cast_status cast_debug_div_by_uniform(const float *x, float y, float *out, int64_t n)
 {
     if (n < 0) return CAST_ERR_SHAPE;

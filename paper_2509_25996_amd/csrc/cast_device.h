@@ -81,7 +81,7 @@ struct SpanSlot {
     int sub;
 };
 
-__device__ __forceinline__ SpanSlot span_slot(const SpanGeom &g, int64_t block, int wave, int block_waves)
+__host__ __device__ __forceinline__ SpanSlot span_slot(const SpanGeom &g, int64_t block, int wave, int block_waves)
 {
     SpanSlot s;
     if (g.waves_per_span == block_waves) {     // one span per workgroup: any number of wavefronts
@@ -101,7 +101,7 @@ struct SpanOrigin {
     int len;                // entries (0 for spans past the end)
 };
 
-__device__ __forceinline__ SpanOrigin span_origin(const SpanGeom &g, int64_t span)
+__host__ __device__ __forceinline__ SpanOrigin span_origin(const SpanGeom &g, int64_t span)
 {
     SpanOrigin o{0, 0, 0};
     if (span >= g.num_spans) return o;
@@ -118,7 +118,7 @@ __device__ __forceinline__ SpanOrigin span_origin(const SpanGeom &g, int64_t spa
 }
 
 // Split plan: span = piece number; `segment` tells which row segment (scale factor) it belongs to.
-__device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, int64_t span, int64_t &segment)
+__host__ __device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, int64_t span, int64_t &segment)
 {
     SpanOrigin o{0, 0, 0};
     segment = 0;
