@@ -15,8 +15,9 @@
 
 namespace cast {
 
-// The buffers of one matrix.  A launch either carries one set in its arguments or, for a list of
-// equally shaped matrices, reads the set of matrix blockIdx.y from a table in device memory.
+// The buffers of one matrix.  A dispatcher-dealt launch carries up to kMaxFused sets in its
+// arguments (workgroups with blockIdx.y = k step matrix k); the work queue reads the set of a
+// matrix from a table in device memory.
 struct TensorPtrs {
     float *w;
     const void *grad;
