@@ -159,7 +159,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama2_7b", choices=["opt125m", "llama2_7b", "llama2_13b"])
+    ap.add_argument("--workload", default="llama2_7b", choices=["opt125m", "llama2_7b", "llama2_13b", "llama3_8b"])
     ap.add_argument("--layers", type=int, default=None, help="use only the first LAYERS decoder blocks (debugging)")
     ap.add_argument("--no-scale", action="store_true", help="time the step without weight scaling")
     ap.add_argument("--layout", default="interleaved", choices=["interleaved", "interleaved-segments", "separate"],

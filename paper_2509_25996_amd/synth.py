@@ -31,10 +31,17 @@ def llama2_13b_block():
             ("gate", 13824, 5120), ("up", 13824, 5120), ("down", 5120, 13824)]
 
 
+def llama3_8b_block():
+    # grouped-query attention: 8 key/value heads of 128, so k and v are 1024 x 4096
+    return [("q", 4096, 4096), ("k", 1024, 4096), ("v", 1024, 4096), ("o", 4096, 4096),
+            ("gate", 14336, 4096), ("up", 14336, 4096), ("down", 4096, 14336)]
+
+
 WEIGHT_SETS = {
     "opt125m": (12, opt125m_block),
     "llama2_7b": (32, llama2_7b_block),
     "llama2_13b": (40, llama2_13b_block),
+    "llama3_8b": (32, llama3_8b_block),
 }
 
 

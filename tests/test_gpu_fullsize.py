@@ -20,10 +20,11 @@ pytestmark = pytest.mark.gpu
 
 SHAPES_7B = [(4096, 4096), (11008, 4096), (4096, 11008)]
 SHAPES_13B = [(5120, 5120), (13824, 5120), (5120, 13824)]
+SHAPES_LLAMA3_8B = [(1024, 4096), (4096, 14336)]      # the shapes LLaMA3-8B adds (k/v of grouped-query attention, down)
 
 
 @pytest.mark.parametrize("as_benchmarked", [True, False])
-@pytest.mark.parametrize("rows,cols", SHAPES_7B + SHAPES_13B)
+@pytest.mark.parametrize("rows,cols", SHAPES_7B + SHAPES_13B + SHAPES_LLAMA3_8B)
 def test_step_on_sampled_rows_of_full_size_matrices(rows, cols, as_benchmarked):
     n, steps, n_sample = 2, 3, 24
     w = synth.device_gaussian((rows, cols), 0.02, torch.float32, 11, DEV)
