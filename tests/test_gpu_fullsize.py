@@ -85,3 +85,40 @@ def test_tie_outlier_select_project_pack_full_size(rows, cols, n, m):
     ref_v, ref_m = oracle.project_compress(w, n, m)
     assert (words(meta) == ref_m).all()
     assert_same_bits(host(values), ref_v, "values")
+
+
+def test_whole_125m_set_through_the_list_call():
+    """Every linear weight of the 125M-shaped set (84 matrices, 84.9 M parameters) stepped by the list call
+    (which steps up to 16 small matrices of one shape per launch) over a ramp with mask refreshes, against the
+    oracle tensor by tensor, bit for bit."""
+    shapes = synth.weight_set("opt125m")
+    n, steps = 2, 6
+    items, refs = [], []
+    for i, (_, r, c) in enumerate(shapes):
+        w0 = synth.weights(21, i, r, c)
+        w, m, v = B.interleaved_state(torch.from_numpy(w0).to(DEV))
+        A = (1 + 0.05 * np.random.default_rng(i).standard_normal((r, n))).astype(np.float32)
+        items.append(dict(w=w, m=m, v=v, mask=B.alloc_mask(r, c, DEV), grad=torch.zeros((r, c), dtype=torch.bfloat16, device=DEV),
+                          scale=torch.from_numpy(A).to(DEV), scale_grad=torch.zeros((r, n), device=DEV)))
+        refs.append(dict(w=w0.copy(), m=np.zeros_like(w0), v=np.zeros_like(w0), keep=np.zeros(w0.shape, np.uint8), A=A))
+    tl = B.TensorList(items, DEV)
+    step_launches, _ = B.cast_adams_multi_launches(tl, B.AdamsConfig(scale_segments=n))
+    assert step_launches < len(shapes) // 2          # small matrices share launches
+    for t in range(steps):
+        cfg = B.iteration_config(t, steps, mask_period=2, lr=1e-3, lambda_=1e-3, scale_segments=n)
+        for i, (_, r, c) in enumerate(shapes):
+            g = synth.grads_bf16(21, i, t, r, c)
+            items[i]["grad"].copy_(g.to(DEV))
+            ref = refs[i]
+            ref["gA"] = oracle.adams_step(ref["w"], synth.widen_bf16(g), ref["m"], ref["v"], ref["keep"], oracle_cfg(cfg),
+                                          A=ref["A"], arithmetic="f32", nthreads=16)
+        B.cast_adams_step_multi(tl, cfg)
+    torch.cuda.synchronize()
+    for i, (name, r, c) in enumerate(shapes):
+        x, ref = items[i], refs[i]
+        assert (words(x["mask"]) == oracle.pack_mask_bits(ref["keep"])).all(), name
+        assert_same_bits(host(x["w"]), ref["w"], name + " w")
+        assert_same_bits(host(x["m"]), ref["m"], name + " mu")
+        assert_same_bits(host(x["v"]), ref["v"], name + " v")
+        g = synth.widen_bf16(synth.grads_bf16(21, i, steps - 1, r, c))
+        assert np.abs(host(x["scale_grad"]) - ref["gA"]).max() <= 1e-5 * np.abs(ref["gA"]).max() + 1e-7
