@@ -164,6 +164,14 @@ __device__ __forceinline__ uint32_t or_reduce_8lanes(uint32_t x)
     return x;
 }
 
+// OR over each aligned run of 16 lanes (a DPP row).
+__device__ __forceinline__ uint32_t or_reduce_16lanes(uint32_t x)
+{
+    x = or_reduce_8lanes(x);
+    x |= dpp_u32<kDppRowMirror>(x);
+    return x;
+}
+
 // Sum over the 64 lanes in a fixed order, the same in every lane of the result: a butterfly inside
 // each row of 16 lanes with four DPP moves (partner lane ^1, lane ^2, mirror within 8, mirror
 // within 16: no LDS traffic), then the four row sums added in row order from scalar registers.

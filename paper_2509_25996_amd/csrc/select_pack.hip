@@ -139,14 +139,25 @@ cast_status launch_weight_scale(const float *w, const float *scale, int64_t rows
 }
 
 // ---- hard prune + fold + pack ---------------------------------------------------------------
-// 2:4, the paper's pattern: a lane holds one group; its two kept values leave as one 8-byte
-// (fp32) or 4-byte (bf16) store and the 4-bit index fields of 8 adjacent lanes form one
-// metadata word, exactly like the mask words.
-template <bool BF16OUT>
-__global__ __launch_bounds__(kMaxBlockThreads) void project_compress_2of4_vec(
+// The half-density patterns 2:4 (the paper's), 4:8 and 1:2.  A lane holds 4 consecutive entries and
+// always ends up with exactly two kept values, which leave as one 8-byte (fp32) or 4-byte (bf16)
+// store at values[off / 2]:
+//   2:4  the lane is one group; the 4-bit index fields of 8 adjacent lanes form one metadata word;
+//   1:2  the lane is two groups with one kept entry each; 16 lanes' bit pairs form one word;
+//   4:8  two adjacent lanes are one group: they exchange their kept values (DPP), the even lane
+//        stores the group's first two and the odd lane its last two; the group's four 3-bit indices
+//        fill a 16-bit field and 4 lanes form one word.
+__device__ __forceinline__ float pick4(const float (&x)[4], uint32_t i)
+{
+    return i == 0 ? x[0] : (i == 1 ? x[1] : (i == 2 ? x[2] : x[3]));
+}
+
+template <int M, bool BF16OUT>
+__global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
     const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
     const SpanGeom geom, int64_t seg_len)
 {
+    constexpr int kEntriesPerWord = M == 4 ? 32 : (M == 8 ? 16 : 64);      // columns one metadata word describes
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int P = geom.waves_per_span;
@@ -157,8 +168,8 @@ __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_2of4_vec(
     const int len = o.len;
     const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
     const __amdgpu_buffer_rsrc_t rmask = span_resource(mask ? mask + (o.dense_begin >> 5) : nullptr, mask ? len / 8 : 0);
-    const __amdgpu_buffer_rsrc_t rmeta = span_resource(meta + (o.dense_begin >> 5), len / 8);
-    // two values per group of four: the values of a span start at dense_begin / 2
+    const __amdgpu_buffer_rsrc_t rmeta = span_resource(meta + o.dense_begin / kEntriesPerWord, len / kEntriesPerWord * 4);
+    // half of the entries are kept: the values of a span start at dense_begin / 2
     const int vbytes = BF16OUT ? 2 : 4;
     const __amdgpu_buffer_rsrc_t rval = span_resource(static_cast<char *>(values) + (o.dense_begin >> 1) * vbytes, (len >> 1) * vbytes);
     for (int base = sub * kChunk; base < len; base += P * kChunk) {
@@ -167,25 +178,64 @@ __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_2of4_vec(
         unpack4u(__builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad), x);
         uint32_t nib;
         if (mask) nib = (__builtin_amdgcn_raw_buffer_load_b32(rmask, (off >> 5) * 4, 0, kAuxLoad) >> (off & 31)) & 0xFu;
-        else nib = keep_nibble<4>(x, 2, lane);
+        else nib = keep_nibble<M>(x, M / 2, lane);
         float A = 1.0f;
         if (scale && off < len) A = scale[(o.dense_begin + off) / seg_len];
-        // positions of the two kept entries, ascending
-        const uint32_t first = (uint32_t)__builtin_ctz(nib | 0x10u);
-        const uint32_t rest = nib & (nib - 1u);
-        const uint32_t second = (uint32_t)__builtin_ctz(rest | 0x10u) & 3u;
-        float a = first == 0 ? x[0] : (first == 1 ? x[1] : x[2]);
-        float b = second == 1 ? x[1] : (second == 2 ? x[2] : x[3]);
+        float a, b;          // the two values this lane stores
+        uint32_t word;       // the metadata word its run of lanes forms
+        if constexpr (M == 4) {
+            const uint32_t first = (uint32_t)__builtin_ctz(nib | 0x10u);      // positions of the two kept entries, ascending
+            const uint32_t rest = nib & (nib - 1u);
+            const uint32_t second = (uint32_t)__builtin_ctz(rest | 0x10u) & 3u;
+            a = first == 0 ? x[0] : (first == 1 ? x[1] : x[2]);
+            b = second == 1 ? x[1] : (second == 2 ? x[2] : x[3]);
+            const uint32_t field = (first & 3u) | (second << 2);
+            word = or_reduce_8lanes(field << ((lane & 7) * 4));
+        } else if constexpr (M == 2) {
+            const uint32_t ia = (nib & 1u) ? 0u : 1u, ib = (nib & 4u) ? 0u : 1u;   // which entry of each pair is kept
+            a = ia ? x[1] : x[0];
+            b = ib ? x[3] : x[2];
+            word = or_reduce_16lanes((ia | (ib << 1)) << ((lane & 15) * 2));
+        } else {
+            // own kept entries in ascending order (p = 4: no such entry) and how many there are
+            const uint32_t r1 = nib & (nib - 1u), r2 = r1 & (r1 - 1u), r3 = r2 & (r2 - 1u);
+            const uint32_t p0 = (uint32_t)__builtin_ctz(nib | 0x10u), p1 = (uint32_t)__builtin_ctz(r1 | 0x10u);
+            const uint32_t p2 = (uint32_t)__builtin_ctz(r2 | 0x10u), p3 = (uint32_t)__builtin_ctz(r3 | 0x10u);
+            const uint32_t cnt = (uint32_t)__popc(nib);
+            float own[4] = {pick4(x, p0 & 3u), pick4(x, p1 & 3u), pick4(x, p2 & 3u), pick4(x, p3 & 3u)};
+            float other[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) other[k] = __uint_as_float(dpp_u32<kDppQuadXor1>(__float_as_uint(own[k])));
+            const uint32_t other_cnt = dpp_u32<kDppQuadXor1>(cnt);
+            const bool odd = (lane & 1) != 0;
+            const uint32_t c0 = odd ? other_cnt : cnt;       // kept entries in the even lane: they come first
+            // the group's kept values in order are L[i] = i < c0 ? E[i] : O[i - c0]; this lane stores L[2*odd], L[2*odd + 1]
+            const uint32_t i0 = odd ? 2u : 0u, i1 = i0 + 1u;
+            const float e0 = pick4(odd ? other : own, i0), o0 = pick4(odd ? own : other, (i0 - c0) & 3u);
+            const float e1 = pick4(odd ? other : own, i1), o1 = pick4(odd ? own : other, (i1 - c0) & 3u);
+            a = i0 < c0 ? e0 : o0;
+            b = i1 < c0 ? e1 : o1;
+            // indices: own s-th kept entry has in-group index 4*odd + p_s and position (odd ? c0 : 0) + s in the field
+            const uint32_t at = odd ? c0 : 0u, hi = odd ? 4u : 0u;
+            uint32_t field = 0;
+            field |= cnt > 0 ? (hi + p0) << (3u * at) : 0u;
+            field |= cnt > 1 ? (hi + p1) << (3u * (at + 1u)) : 0u;
+            field |= cnt > 2 ? (hi + p2) << (3u * (at + 2u)) : 0u;
+            field |= cnt > 3 ? (hi + p3) << (3u * (at + 3u)) : 0u;
+            field |= dpp_u32<kDppQuadXor1>(field);          // both lanes of the group now hold its 12 bits
+            field <<= (lane & 2) * 8;                       // second group of the word: upper 16 bits
+            word = field | dpp_u32<kDppQuadXor2>(field);
+        }
         if (scale) { a = A * a; b = A * b; }
-        const uint32_t field = (first & 3u) | (second << 2);
-        const uint32_t word = or_reduce_8lanes(field << ((lane & 7) * 4));
         if constexpr (BF16OUT) {
             __builtin_amdgcn_raw_buffer_store_b32(f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16), rval, (off >> 1) * 2, 0, kAuxStore);
         } else {
             const vu2_t pair = {__float_as_uint(a), __float_as_uint(b)};
             __builtin_amdgcn_raw_buffer_store_b64(pair, rval, (off >> 1) * 4, 0, kAuxStore);
         }
-        if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off >> 5) * 4, 0, kAuxStore);
+        constexpr int kLanesPerWord = kEntriesPerWord / kLaneElems;
+        if ((lane & (kLanesPerWord - 1)) == 0)
+            __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off / kEntriesPerWord) * 4, 0, kAuxStore);
     }
 }
 
@@ -260,9 +310,25 @@ cast_status launch_project_compress(const float *w, const float *scale, int n_se
     const bool bf16 = value_dtype == CAST_BF16;
     const int64_t seg_len = scale ? cols / n_segments : cols;
     const SpanPlan p = plan_spans(rows, cols, ld, 0);
-    if (n_keep == 2 && m_group == 4 && p.vec && seg_len % 4 == 0) {
-        if (bf16) hipLaunchKernelGGL(project_compress_2of4_vec<true>, dim3(p.grid), dim3(p.block_threads), 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
-        else hipLaunchKernelGGL(project_compress_2of4_vec<false>, dim3(p.grid), dim3(p.block_threads), 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+    // the vector kernel: half-density patterns, spans and rows that are whole metadata words
+    // (32 columns for 2:4, 16 for 4:8, 64 for 1:2), scale segments that are whole groups
+    const int word_cols = m_group == 4 ? 32 : (m_group == 8 ? 16 : 64);
+    if (2 * n_keep == m_group && p.vec && seg_len % m_group == 0 && cols % word_cols == 0 && p.geom.span_len % word_cols == 0) {
+        const dim3 grid(p.grid), block(p.block_threads);
+        switch (m_group) {
+        case 4:
+            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<4, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            else hipLaunchKernelGGL((project_compress_half_vec<4, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            break;
+        case 8:
+            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<8, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            else hipLaunchKernelGGL((project_compress_half_vec<8, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            break;
+        default:
+            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<2, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            else hipLaunchKernelGGL((project_compress_half_vec<2, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            break;
+        }
         return launch_status();
     }
     const int64_t units = rows * ((cols + 63) / 64);

@@ -670,3 +670,33 @@ def test_refresh_steps_gather_mask_learning_statistics(n, m):
     assert flipped > 0                      # the decay really moved masks between refreshes
     _, again = run()
     assert [h[3] for h in again] == [h[3] for h in history]      # bit for bit reproducible
+
+
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
+@pytest.mark.parametrize("rows,cols", [(33, 1024), (16, 4096 + 64), (5, 11008)])
+def test_project_compress_vector_kernels_layouts_and_stored_masks(n, m, rows, cols):
+    """The half-density patterns on shapes the vector kernel takes: dense and row-interleaved weights, the
+    mask recomputed (projection) or given (Algorithm 1's last refreshed mask, here taken from other weights so
+    that using it is visible), fp32 and bf16 values, with and without the fold of the scale."""
+    w = synth.tie_outlier_weights(7, 3, rows, cols)
+    other = synth.weights(7, 4, rows, cols)
+    keep_other = oracle.nm_select(other, n, m)
+    A = (1 + 0.3 * np.random.default_rng(1).standard_normal((rows, 2))).astype(np.float32)
+    for interleaved in (False, True):
+        wd = B.interleaved_state(dev(w))[0] if interleaved else dev(w)
+        stored = B.alloc_mask(rows, cols, DEV)
+        B.cast_nm_select(dev(other), n, m, stored)
+        for mask, keep in ((None, None), (stored, keep_other)):
+            for scale in (None, A):
+                for vdtype, code in ((torch.float32, B.CAST_F32), (torch.bfloat16, B.CAST_BF16)):
+                    _, vbytes, mbytes = B.cast_sizes(rows, cols, n, m, code)
+                    values = torch.full((rows, cols // m * n), 7.0, dtype=vdtype, device=DEV)
+                    meta = torch.full((rows, mbytes // 4 // rows), -1, dtype=torch.int32, device=DEV)
+                    B.cast_nm_project_compress(wd, n, m, values, meta, scale=None if scale is None else dev(scale), mask_bits=mask)
+                    torch.cuda.synchronize()
+                    ref_v, ref_m = oracle.project_compress(w, n, m, A=scale, keep=keep)
+                    assert (words(meta) == ref_m).all(), (interleaved, mask is not None, scale is not None)
+                    if vdtype == torch.float32:
+                        assert_same_bits(host(values), ref_v, "values")
+                    else:
+                        assert (host(values.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref_v)).all()
