@@ -68,7 +68,7 @@ def test_step_on_sampled_rows_of_full_size_matrices(rows, cols, as_benchmarked):
 
 
 @pytest.mark.parametrize("rows,cols", SHAPES_7B)
-@pytest.mark.parametrize("n,m", [(2, 4), (4, 8)])
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
 def test_tie_outlier_select_project_pack_full_size(rows, cols, n, m):
     w = synth.tie_outlier_weights(5, rows % 7, rows, cols)
     wd = torch.from_numpy(w).to(DEV)
