@@ -1,0 +1,79 @@
+"""A complete pass through the library on synthetic data: Algorithm 1's loop over a few weight matrices with
+the list call (alpha_t = t/T, mask refresh every T_1 steps, weight scaling with n = 2 segments, refresh
+statistics gathered by the refresh steps themselves), then the hard N:M projection with the last refreshed
+mask, the fold of the scale factors and packing (Algorithm 1's last lines, Eq. 12).
+
+    python -m paper_2509_25996_amd.example
+
+Gradients are random draws, not a loss: the point is the calling sequence, and that under the ramp the
+masked weights are driven to zero (Sec. 4.1, appendix "Mask Learning"), which the numbers it prints show.
+The scale factors stay at one here; a trainer would update them from scale_grad with its own optimizer.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+from . import synth
+
+
+def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10, lr=1e-3, lam=1e-3, n_keep=2, m_group=4,
+        segments=2, device="cuda:0", verbose=True):
+    """Returns a dict of what a training script would monitor; see the module docstring."""
+    B.load()
+    items, stats = [], []
+    for i, (r, c) in enumerate(shapes):
+        w, m, v = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, 100 + i, device))
+        mask, initial = B.alloc_mask(r, c, device), B.alloc_mask(r, c, device)
+        B.cast_nm_select(w, n_keep, m_group, initial)                 # the mask of the dense model, for the initial flip rate
+        mask.copy_(initial)
+        stats.append(B.alloc_refresh_stats(device))
+        items.append(dict(w=w, m=m, v=v, mask=mask, grad=torch.empty((r, c), dtype=torch.bfloat16, device=device),
+                          scale=torch.ones((r, segments), device=device), scale_grad=torch.zeros((r, segments), device=device),
+                          initial_mask=initial, refresh_stats=stats[-1]))
+    tensors = B.TensorList(items, device)
+    total = sum(r * c for r, c in shapes)
+    history = []
+    gen = torch.Generator(device=device).manual_seed(0)
+    for t in range(steps):
+        for x in items:                                               # stand-in for the backward pass
+            x["grad"].copy_(torch.randn(x["grad"].shape, device=device, generator=gen) * 1e-3)
+        cfg = B.iteration_config(t, steps, mask_period=mask_period, lr=lr, lambda_=lam, n_keep=n_keep, m_group=m_group,
+                                 scale_segments=segments)
+        B.cast_adams_step_multi(tensors, cfg)
+        if cfg.refresh_mask:
+            s = [B.read_refresh_stats(x) for x in stats]
+            flip_rate = sum(x["flips_prev"] for x in s) / total       # r_t
+            initial_flip_rate = sum(x["flips_init"] for x in s) / total       # i_t
+            kept_ratio = sum(x["l1_kept"] for x in s) / sum(x["l1_all"] for x in s)       # S_t
+            history.append((t, flip_rate, initial_flip_rate, kept_ratio))
+            if verbose and (t // mask_period) % max(1, steps // mask_period // 8) == 0:
+                print(f"step {t:5d}  alpha {cfg.alpha:5.3f}  flip rate {flip_rate:.5f}  against the initial mask "
+                      f"{initial_flip_rate:.5f}  ||W.M||_1 / ||W||_1 = {kept_ratio:.5f}")
+    # Algorithm 1's end: prune with the last refreshed mask, fold the scale, pack values + index metadata
+    packed = []
+    for x, (r, c) in zip(items, shapes):
+        _, _, meta_bytes = B.cast_sizes(r, c, n_keep, m_group, B.CAST_BF16)
+        values = torch.empty((r, c // m_group * n_keep), dtype=torch.bfloat16, device=device)
+        meta = torch.empty((r, meta_bytes // 4 // r), dtype=torch.int32, device=device)
+        B.cast_nm_project_compress(x["w"], n_keep, m_group, values, meta, scale=x["scale"], mask_bits=x["mask"])
+        packed.append((values, meta))
+    torch.cuda.synchronize()
+    # what the pruning removes: the largest masked weight and the share of the L1 norm it carried
+    worst, masked_l1, all_l1 = 0.0, 0.0, 0.0
+    for x, (r, c) in zip(items, shapes):
+        words = x["mask"].cpu().numpy().view("uint32")
+        bits = ((words[:, :, None] >> torch.arange(32).numpy()[None, None, :]) & 1).reshape(r, -1)[:, :c].astype(bool)
+        w = x["w"].cpu().numpy()
+        worst = max(worst, float(abs(w[~bits]).max()))
+        masked_l1 += float(abs(w[~bits]).sum())
+        all_l1 += float(abs(w).sum())
+    if verbose:
+        print(f"after {steps} steps: largest masked |w| = {worst:.3e} (lr = {lr:g}); pruning removes "
+              f"{100 * masked_l1 / all_l1:.4f} % of ||W||_1; packed {len(packed)} matrices")
+    return {"history": history, "largest_masked_weight": worst, "pruned_l1_share": masked_l1 / all_l1, "packed": packed,
+            "items": items}
+
+
+if __name__ == "__main__":
+    run()

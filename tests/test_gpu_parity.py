@@ -700,3 +700,18 @@ def test_project_compress_vector_kernels_layouts_and_stored_masks(n, m, rows, co
                         assert_same_bits(host(values), ref_v, "values")
                     else:
                         assert (host(values.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref_v)).all()
+
+
+def test_example_loop_drives_masked_weights_to_zero():
+    """The calling sequence of the package's example (list call with refresh statistics over a ramp, then the
+    projection with the last refreshed mask): the end state the paper describes (Sec. 4.1, appendix "Mask
+    Learning") must come out: masked weights within a few lr of zero, S_t -> 1, masks settling."""
+    from paper_2509_25996_amd import example
+    out = example.run(shapes=((64, 1024), (96, 512)), steps=300, mask_period=10, lr=1e-3, lam=1e-3, verbose=False)
+    assert out["largest_masked_weight"] <= 20e-3 * 1.0 and out["pruned_l1_share"] <= 2e-2
+    ts, flips, flips_init, kept = zip(*out["history"])
+    assert kept[-1] >= 0.98 and kept[-1] > kept[1]
+    assert flips[-1] <= flips[2]                 # late masks change less than early ones
+    assert flips_init[-1] > 0                     # and differ from the dense model's mask
+    for values, meta in out["packed"]:
+        assert bool(torch.isfinite(values.float()).all())
