@@ -183,6 +183,17 @@ template <int M, bool BF16, bool REFRESH, bool SCALED>
 static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
     const dim3 grid(l.grid_x, l.grid_y), block(l.block_threads);
+    if (l.tickets) {
+        const QueueArgs q{l.tickets, (uint32_t)l.tasks, l.blocks_per_matrix, make_fast_div(l.blocks_per_matrix), l.log2_run};
+        if constexpr (SCALED) {
+            if (l.split) {
+                hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, true, true>), dim3(l.grid_x), block, 0, st, a, q);
+                return;
+            }
+        }
+        hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), block, 0, st, a, q);
+        return;
+    }
     if constexpr (SCALED) {
         if (l.split) {
             if (l.extra == 2) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 2>), grid, block, 0, st, a);
@@ -199,10 +210,7 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
         hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, 1>), grid, block, 0, st, a);
         return;
     }
-    if (l.tickets)
-        hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), dim3(l.block_threads), 0, st, a,
-                           QueueArgs{l.tickets, (uint32_t)l.tasks, l.blocks_per_matrix, make_fast_div(l.blocks_per_matrix), l.log2_run});
-    else {
+    {
         // experiment knob: cap the resident wavefronts per compute unit by reserving LDS per workgroup
         static const int cap = env_int("CAST_STATIC_WAVES_PER_CU", 0);
         unsigned lds = 0;
@@ -409,56 +417,98 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     // tuning knobs (read once): resident wavefronts per compute unit of the work queue
     static const int waves_per_cu = env_int("CAST_QUEUE_WAVES_PER_CU", 16);
     static const int log2_run = env_int("CAST_QUEUE_LOG2_RUN", 1) & 7;      // shares per ticket = 1 << log2_run
+    static const int queue_block_waves = env_int("CAST_QUEUE_BLOCK_WAVES", 8);
+    const MultiLayout layout = multi_layout(ts, count, cfg);
+    PieceJobQueue jobs;
+    PieceArea area{reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes),
+                   layout.piece_floats, &jobs};
     std::vector<int> order;           // indices of vector-path matrices, grouped by shape
     std::vector<char> taken(count, 0);
-    struct Group { int first, n; SpanPlan plan; };
+    struct Group { int first, n; SpanPlan plan; int block_waves; unsigned blocks_per_matrix; };
     std::vector<Group> groups;
     for (int i = 0; i < count; ++i) {
         if (taken[i] || ts[i].rows == 0 || ts[i].cols == 0) continue;
-        const SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments);
-        if (!p.vec || !use_queue || waves_per_cu <= 0) continue;     // (the work queue never uses split plans)
-        Group g{(int)order.size(), 0, p};
+        const bool wants_gA = scaled && ts[i].scale_grad != nullptr;
+        SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments, wants_gA && layout.piece_floats > 0);
+        if (!p.vec || !use_queue || waves_per_cu <= 0) continue;
+        if (p.geom.spans_per_row == 0) {      // flat: one chunk per span
+            p.geom.span_len = kChunk;
+            p.geom.num_spans = (p.geom.total + kChunk - 1) / kChunk;
+        }
+        // the work queue gives every wavefront one chunk of a share; other plans go the ordinary way
+        if (p.geom.span_len > (int64_t)p.geom.waves_per_span * kChunk) continue;
+        // workgroups of the work queue: as many spans side by side as fit the wanted size
+        const int P = p.geom.waves_per_span;
+        int block_waves = p.block_threads / kWave;
+        if ((P & (P - 1)) == 0 && P < queue_block_waves && queue_block_waves <= kMaxBlockWaves && queue_block_waves % P == 0)
+            block_waves = queue_block_waves;
+        const int64_t spans_per_block = block_waves / P;
+        Group g{(int)order.size(), 0, p, block_waves, (unsigned)((p.geom.num_spans + spans_per_block - 1) / spans_per_block)};
         // tickets are 32-bit task numbers inside the kernel
-        const int fit = (int)(((int64_t)1 << 31) / p.grid);
+        const int fit = (int)(((int64_t)1 << 31) / g.blocks_per_matrix);
         for (int j = i; j < count && g.n < fit && g.n < 65535; ++j)
-            if (!taken[j] && ts[j].rows == ts[i].rows && ts[j].cols == ts[i].cols && ts[j].ld == ts[i].ld) {
+            if (!taken[j] && ts[j].rows == ts[i].rows && ts[j].cols == ts[i].cols && ts[j].ld == ts[i].ld &&
+                (ts[j].scale_grad == nullptr) == (ts[i].scale_grad == nullptr)) {
                 taken[j] = 1;
                 order.push_back(j);
                 ++g.n;
             }
         groups.push_back(g);
     }
-    const MultiLayout layout = multi_layout(ts, count, cfg);
-    if (dry) tally->step_launches += (int)groups.size();
+    if (dry) {
+        tally->step_launches += (int)groups.size();
+        for (const Group &g : groups)
+            if (g.plan.geom.pieces_per_segment > 1)
+                for (int k = 0; k < g.n; ++k)
+                    if (++tally->split_matrices % kMaxPieceJobs == 1) ++tally->other_launches;
+    }
     if (!order.empty() && !dry) {
         const size_t table_bytes = layout.table_bytes;
         std::vector<unsigned char> image(table_bytes + groups.size() * sizeof(unsigned long long), 0);
         TensorPtrs *table = reinterpret_cast<TensorPtrs *>(image.data());
-        for (size_t k = 0; k < order.size(); ++k) {
-            const cast_tensor &t = ts[order[k]];
-            table[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, nullptr, nullptr, nullptr};
+        std::vector<PieceJob> piece_jobs;      // of the matrices with split plans, launched after their group
+        std::vector<size_t> piece_job_group;
+        for (size_t gi = 0; gi < groups.size(); ++gi) {
+            const Group &g = groups[gi];
+            const bool split = g.plan.geom.pieces_per_segment > 1;
+            for (int k = 0; k < g.n; ++k) {
+                const cast_tensor &t = ts[order[g.first + k]];
+                float *piece_sums = nullptr;
+                if (split) {      // (the layout has counted every such matrix, so the area has the room)
+                    piece_sums = area.base;
+                    const uint64_t used = ((uint64_t)g.plan.geom.num_spans + 3) & ~(uint64_t)3;
+                    area.base += used;
+                    area.floats -= used < area.floats ? used : area.floats;
+                    piece_jobs.push_back(PieceJob{piece_sums, t.scale_grad, g.plan.segments, g.plan.geom.pieces_per_segment});
+                    piece_job_group.push_back(gi);
+                }
+                table[g.first + k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, piece_sums, nullptr, nullptr};
+            }
         }
         // pageable source: the runtime stages it before returning, the copy itself is ordered on the stream
         if (hipMemcpyAsync(workspace, image.data(), image.size(), hipMemcpyHostToDevice, st) != hipSuccess)
             return CAST_ERR_LAUNCH;
         unsigned long long *counters = reinterpret_cast<unsigned long long *>(static_cast<char *>(workspace) + table_bytes);
         const StepScalars sc = make_scalars(cfg);
+        size_t next_job = 0;
         for (size_t gi = 0; gi < groups.size(); ++gi) {
             const Group &g = groups[gi];
             SpanArgs a{{}, as_const_table(static_cast<const TensorPtrs *>(workspace) + g.first), g.plan.geom, sc, nullptr, nullptr};
-            const unsigned long long tasks = (unsigned long long)g.plan.grid * (unsigned)g.n;
-            int blocks_per_cu = waves_per_cu / (g.plan.block_threads / kWave);
+            const unsigned long long tasks = (unsigned long long)g.blocks_per_matrix * (unsigned)g.n;
+            int blocks_per_cu = waves_per_cu / g.block_waves;
             if (blocks_per_cu < 1) blocks_per_cu = 1;
             unsigned long long resident = (unsigned long long)device_compute_units() * blocks_per_cu;
             if (resident > tasks) resident = tasks;
-            const VecLaunch l{(unsigned)resident, 1, g.plan.block_threads, counters + gi, tasks, g.plan.grid, log2_run, false, 0};
+            const VecLaunch l{(unsigned)resident, 1, g.block_waves * kWave, counters + gi, tasks, g.blocks_per_matrix, log2_run,
+                              g.plan.geom.pieces_per_segment > 1, 0};
             launch_vec_any(cfg->m_group, bf16, refresh, scaled, l, a, st);
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+            for (; next_job < piece_jobs.size() && piece_job_group[next_job] == gi; ++next_job) {
+                if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
+                jobs.add(piece_jobs[next_job]);
+            }
         }
     }
-    PieceJobQueue jobs;
-    PieceArea area{reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes),
-                   layout.piece_floats, &jobs};
     StatsJobQueue stats_jobs;
     StatsArea stats_area{reinterpret_cast<StatsPartial *>(area.base + layout.piece_floats), layout.stats_slots, &stats_jobs};
     // Small matrices of one shape share a launch (they need not follow each other in the list: the

@@ -148,6 +148,9 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
         t.mask = (uint32_t *)ptr(hi[0], hi[1]);
         t.scale = (const float *)ptr(hi[2], hi[3]);
         t.scale_grad = (float *)ptr(hi[4], hi[5]);
+        t.piece_sums = (float *)ptr(hi[6], hi[7]);
+        t.stats_partials = nullptr;
+        t.initial_mask = nullptr;
     } else {
         t = a.set[matrix];     // a scalar load from the kernel arguments at a wave-uniform offset
     }
@@ -375,14 +378,56 @@ struct QueueArgs {
     int log2_run;                    // shares per ticket = 1 << log2_run
 };
 
+// One chunk of 256 entries of the plain flavour (no compute copy, no statistics, AdamS rule family):
+// what span_run does per iteration, for the work queue, which runs its own pipeline.
 template <int M, bool BF16, bool REFRESH, bool SCALED>
+__device__ __forceinline__ void chunk_step(const SpanArgs &a, const SpanCtx &c, const Chunk<BF16> &cur, int lane, int off,
+                                           bool want_gA, float &acc)
+{
+    const SpanBuffers &b = c.b;
+    float w[4], g[4], mu[4], v[4];
+    unpack4(cur.w, w);
+    unpack4(cur.m, mu);
+    unpack4(cur.v, v);
+    if constexpr (BF16) {
+        g[0] = bf16_lo(cur.g.x); g[1] = bf16_hi(cur.g.x); g[2] = bf16_lo(cur.g.y); g[3] = bf16_hi(cur.g.y);
+    } else {
+        unpack4(cur.g, g);
+    }
+    uint32_t nib;
+    if constexpr (REFRESH) {
+        nib = keep_nibble<M>(w, a.s.n_keep, lane);
+        const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
+        if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, b.mask, (off >> 5) * 4, 0, kAuxStore);
+    } else {
+        nib = (cur.word >> (off & 31)) & 0xFu;
+    }
+    if constexpr (SCALED) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (want_gA) acc = __builtin_fmaf(g[j], w[j], acc);
+            g[j] = c.A * g[j];
+        }
+    }
+    adams_entries4<false, false>(w, g, mu, v, nib, off < c.len, a.s);
+    __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
+    __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
+    __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
+}
+
+// Every wavefront has one chunk of a share (the host sends only such plans here): while it works on
+// it, its chunk of the next share is on its way.  One barrier per share publishes the ticket and
+// hands the wavefronts' dL/dA sums of the share before to the wavefront that adds them up (two sets
+// of LDS slots, used in turn).  SPLIT: as in adams_step_vec.
+template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false>
 __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const SpanArgs a, const QueueArgs q)
 {
-    __shared__ float partial[kMaxBlockWaves];
+    __shared__ float partial[2][kMaxBlockWaves];
     __shared__ unsigned long long drawn[2];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint32_t run_mask = (1u << q.log2_run) - 1u;
+    const int P = a.geom.waves_per_span;
     unsigned long long pending = 0;
 
     if (threadIdx.x == 0) drawn[0] = atomicAdd(q.ticket_counter, 1ull);
@@ -394,39 +439,70 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const S
     {
         const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
         SpanCtx c;
-        span_open<BF16, SCALED, true>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
+        span_open<BF16, SCALED, true, SPLIT>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
         chunk_load<BF16, !REFRESH>(cur, c.b, first_offset(c, lane));
     }
     if (threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
+    float *sum_to = nullptr;      // where this wavefront puts the dL/dA of the share before, if it is the one to add it up
 
-    for (uint32_t seq = 0;; ++seq) {
+    uint32_t seq = 0;             // shares this workgroup has finished
+    for (;; ++seq) {
         const bool last_of_run = (seq & run_mask) == run_mask;          // wave-uniform
         const int slot = ((seq >> q.log2_run) + 1) & 1;
         if (last_of_run && threadIdx.x == 0) drawn[slot] = pending;
-        __syncthreads();   // publishes the ticket; also separates this round's use of `partial` from the last one's
+        __syncthreads();
+        if constexpr (SCALED) {
+            if (sum_to != nullptr && lane == 0) {
+                const float *from = partial[(seq + 1) & 1] + wave;
+                float sum = from[0];
+                for (int p = 1; p < P; ++p) sum = sum + from[p];
+                *sum_to = sum;
+            }
+        }
         unsigned long long next = (unsigned long long)share + 1;
         if (last_of_run) next = uniform_u64(drawn[slot]) << q.log2_run;
         const bool has_next = next < q.tasks;
         const uint32_t next_share = __builtin_amdgcn_readfirstlane((uint32_t)next);
+        if (has_next && last_of_run && threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
+        // Scalar registers hold one span context at a time: the next share's is built only to request
+        // its first chunk, and the current share's after that.
         Chunk<BF16> nxt;
         if (has_next) {
-            // Only one span context is ever alive (scalar registers are scarce): the next share's is
-            // built here just to address its first chunk, and again below when its turn comes.
             const uint32_t matrix = fast_div(next_share, q.div_blocks_per_matrix);
             SpanCtx ahead;
-            span_open<BF16, SCALED, true>(a, matrix, (int64_t)(next_share - matrix * q.blocks_per_matrix), wave, ahead);
+            span_open<BF16, SCALED, true, SPLIT>(a, matrix, (int64_t)(next_share - matrix * q.blocks_per_matrix), wave, ahead);
             chunk_load<BF16, !REFRESH>(nxt, ahead.b, first_offset(ahead, lane));
-            if (last_of_run && threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
         }
-        {
-            const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
-            SpanCtx c;
-            span_open<BF16, SCALED, true>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
-            span_run<M, BF16, REFRESH, SCALED>(a, c, cur, lane, wave, partial);
+        const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
+        SpanCtx c;
+        span_open<BF16, SCALED, true, SPLIT>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
+        const bool want_gA = SCALED && c.scale_grad != nullptr;
+        float acc = 0.0f;
+        chunk_step<M, BF16, REFRESH, SCALED>(a, c, cur, lane, first_offset(c, lane), want_gA, acc);
+        if constexpr (SCALED) {
+            sum_to = nullptr;
+            if (want_gA) {
+                const float wave_total = wave_sum_fixed_order(acc);
+                if (P == 1) {
+                    if (lane == 0 && c.len > 0) c.scale_grad[c.span] = wave_total;
+                } else {
+                    if (lane == 0) partial[seq & 1][wave] = wave_total;
+                    if (c.sub == 0 && c.len > 0) sum_to = c.scale_grad + c.span;
+                }
+            }
         }
-        if (!has_next) return;
+        if (!has_next) break;
         share = next_share;
         cur = nxt;
+    }
+    if constexpr (SCALED) {
+        __syncthreads();
+        if (sum_to != nullptr && lane == 0) {      // the last share's sums
+            const float *from = partial[seq & 1] + wave;
+            float sum = from[0];
+            for (int p = 1; p < P; ++p) sum = sum + from[p];
+            *sum_to = sum;
+        }
     }
 }
 

@@ -128,11 +128,11 @@ def test_validation_happens_before_any_launch(lib):
     ws_bytes = lambda a, n, c: lib.cast_adams_multi_workspace_bytes(a, n, C.byref(c))
     assert ws_bytes(arr, 2, cfg) == 176 and ws_bytes(arr, 0, cfg) == 0 and ws_bytes(None, 2, cfg) == 176    # 2 x 80 + 16
     # row segments of more than 16 chunks of 256 entries are stepped in pieces of 8 chunks whose dL/dA sums
-    # pass through the workspace (one float per piece); not when the work queue steps them
+    # pass through the workspace (one float per piece)
     wide = (T * 2)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 3, 11008, 11008), good)
     seg = _cfg(scale_segments=2)
     assert ws_bytes(wide, 2, seg) == 176 + 4 * 20          # 3 rows x 2 segments x 3 pieces, rounded up to 4 floats
-    assert ws_bytes(wide, 2, _cfg(scale_segments=2, flags=2)) == 176 + 4 * 20     # kept for matrices the queue does not take
+    assert ws_bytes(wide, 2, _cfg(scale_segments=2, flags=2)) == 176 + 4 * 20     # the work queue steps them in pieces too
     assert ws_bytes(wide, 2, _cfg(scale_segments=8)) == 176
     assert lib.cast_adams_step_multi(wide, 1, C.byref(seg), p, 144, st) == -2      # no room for the sums
     # refresh statistics: one 16-byte slot per workgroup of the matrix's launch (4 x 64 entries: one workgroup)
@@ -162,7 +162,7 @@ def test_list_call_launch_tally(lib):
     assert (step.value, other.value) == (4, 1)
     cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, flags=B.FLAG_WORK_QUEUE).c_struct()
     assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
-    assert (step.value, other.value) == (3, 0)          # one queue launch per shape
+    assert (step.value, other.value) == (3, 1)          # one queue launch per shape, and the sum of down's pieces
     cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, rule=B.RULE_ADAM_L1).c_struct()
     assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), None) == 0
     assert step.value == 7                              # comparison rules: one launch per matrix

@@ -406,7 +406,7 @@ def test_strided_weights_in_every_entry_point(rows, cols):
 @pytest.mark.parametrize("nseg", [0, 2])
 def test_multi_tensor_step_equals_single_steps(nseg, queue):
     # (16, 11008) and (7, 8768) have row segments of more than 16 chunks of 256 entries: the list call steps
-    # them in pieces of 2048 entries (unless the work queue is on) and adds the pieces' dL/dA sums afterwards
+    # them in pieces of 2048 entries (with or without the work queue) and adds the pieces' dL/dA sums afterwards
     # runs of equal shapes: the list call steps up to 4 small matrices of one shape with one launch
     shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (5, 72), (64, 512), (32, 1024), (32, 1024), (3, 40), (0, 64),
               (16, 11008), (16, 11008), (7, 8768), (64, 512), (64, 512), (64, 512), (64, 512), (64, 512), (0, 64), (64, 512)]
@@ -440,7 +440,7 @@ def test_multi_tensor_step_equals_single_steps(nseg, queue):
             for k in ("w", "m", "v", "mask"):
                 assert host(x[k]).tobytes() == host(y[k]).tobytes(), k
             if nseg and x["w"].numel():
-                in_pieces = not queue and x["w"].shape[1] // nseg > 4096
+                in_pieces = x["w"].shape[1] // nseg > 4096
                 ga, gb = host(x["scale_grad"]), host(y["scale_grad"])
                 if in_pieces:      # another summation order: equal up to fp32 rounding of sums of ~5000 terms of ~2e-5
                     assert np.abs(ga.astype(np.float64) - gb).max() <= 1e-6
