@@ -15,15 +15,46 @@ __device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
     f[0] = __uint_as_float(x.x); f[1] = __uint_as_float(x.y); f[2] = __uint_as_float(x.z); f[3] = __uint_as_float(x.w);
 }
 
+// These kernels do little arithmetic per byte, so what counts is memory requests in flight: a
+// wavefront takes up to kBatch chunks of its span and asks for all of them before it works on the
+// first.  The plan: dense matrices are cut into spans of kBatch chunks, one wavefront each; rows
+// with a stride are cut into the fewest equal pieces of at most 16 * kBatch chunks that start on
+// `align` columns, and as many wavefronts share a piece as it has kBatch chunks (a power of two).
+constexpr int kBatch = 4;
+
+static SpanPlan plan_batched(int64_t rows, int64_t cols, int64_t ld, int align)
+{
+    int per_row = 0;
+    if (ld != cols)
+        for (int k = 1; k <= 64 && per_row == 0; ++k)
+            if (cols % k == 0 && (cols / k) % align == 0 && cols / k <= (int64_t)kMaxBlockWaves * kBatch * kChunk) per_row = k;
+    SpanPlan p = plan_spans(rows, cols, ld, per_row);
+    if (!p.vec) return p;
+    SpanGeom &g = p.geom;
+    if (g.spans_per_row == 0) {
+        g.span_len = (int64_t)kBatch * kChunk;
+        g.num_spans = (g.total + g.span_len - 1) / g.span_len;
+    }
+    const int64_t chunks = (g.span_len + kChunk - 1) / kChunk;
+    int P = 1;
+    while ((int64_t)P * kBatch < chunks && P < kMaxBlockWaves) P *= 2;
+    g.waves_per_span = P;
+    const int block_waves = P > kBlockWaves ? P : kBlockWaves;
+    p.block_threads = block_waves * kWave;
+    const int64_t spans_per_block = block_waves / P;
+    p.grid = (unsigned)((g.num_spans + spans_per_block - 1) / spans_per_block);
+    return p;
+}
+
 // ---- Eq. 6 ----------------------------------------------------------------------------------
-// One wavefront per span, 256 entries per chunk; spans start on mask words.
+// Spans start on mask words; a wavefront's chunks of a span are sub, sub + P, sub + 2P, ...
 template <int M>
 __global__ __launch_bounds__(kMaxBlockThreads) void nm_select_vec(const float *w, uint32_t *mask,
                                                                   const SpanGeom geom, int n_keep)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int P = geom.waves_per_span;
+    const int stride = geom.waves_per_span * kChunk;
     const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
     const int64_t span = slot.span;
     const int sub = slot.sub;
@@ -31,13 +62,21 @@ __global__ __launch_bounds__(kMaxBlockThreads) void nm_select_vec(const float *w
     const int len = o.len;
     const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
     const __amdgpu_buffer_rsrc_t rmask = span_resource(mask + (o.dense_begin >> 5), len / 8);
-    for (int base = sub * kChunk; base < len; base += P * kChunk) {
-        const int off = base + lane * kLaneElems;
-        float x[4];
-        unpack4u(__builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad), x);
-        const uint32_t nib = keep_nibble<M>(x, n_keep, lane);
-        const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
-        if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmask, (off >> 5) * 4, 0, kAuxStore);
+    for (int base = sub * kChunk; base < len; base += kBatch * stride) {
+        vu4_t raw[kBatch];
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k)      // past the end of the span: zeros
+            raw[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, (base + k * stride + lane * kLaneElems) * 4, 0, kAuxLoad);
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            if (base + k * stride >= len) break;      // wave-uniform
+            const int off = base + k * stride + lane * kLaneElems;
+            float x[4];
+            unpack4u(raw[k], x);
+            const uint32_t nib = keep_nibble<M>(x, n_keep, lane);
+            const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
+            if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmask, (off >> 5) * 4, 0, kAuxStore);
+        }
     }
 }
 
@@ -66,7 +105,7 @@ cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int64_t
                              int m_group, uint32_t *mask_bits, hipStream_t st)
 {
     if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_spans(rows, cols, ld, 0);
+    const SpanPlan p = plan_batched(rows, cols, ld, 32);
     if (p.vec) {
         switch (m_group) {
         case 2: hipLaunchKernelGGL(nm_select_vec<2>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
@@ -155,12 +194,12 @@ __device__ __forceinline__ float pick4(const float (&x)[4], uint32_t i)
 template <int M, bool BF16OUT>
 __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
     const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
-    const SpanGeom geom, int64_t seg_len)
+    const SpanGeom geom, uint32_t seg_len, FastDivU32 div_seg_len)
 {
     constexpr int kEntriesPerWord = M == 4 ? 32 : (M == 8 ? 16 : 64);      // columns one metadata word describes
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int P = geom.waves_per_span;
+    const int stride = geom.waves_per_span * kChunk;
     const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
     const int64_t span = slot.span;
     const int sub = slot.sub;
@@ -172,70 +211,90 @@ __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
     // half of the entries are kept: the values of a span start at dense_begin / 2
     const int vbytes = BF16OUT ? 2 : 4;
     const __amdgpu_buffer_rsrc_t rval = span_resource(static_cast<char *>(values) + (o.dense_begin >> 1) * vbytes, (len >> 1) * vbytes);
-    for (int base = sub * kChunk; base < len; base += P * kChunk) {
-        const int off = base + lane * kLaneElems;
-        float x[4];
-        unpack4u(__builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad), x);
-        uint32_t nib;
-        if (mask) nib = (__builtin_amdgcn_raw_buffer_load_b32(rmask, (off >> 5) * 4, 0, kAuxLoad) >> (off & 31)) & 0xFu;
-        else nib = keep_nibble<M>(x, M / 2, lane);
-        float A = 1.0f;
-        if (scale && off < len) A = scale[(o.dense_begin + off) / seg_len];
-        float a, b;          // the two values this lane stores
-        uint32_t word;       // the metadata word its run of lanes forms
-        if constexpr (M == 4) {
-            const uint32_t first = (uint32_t)__builtin_ctz(nib | 0x10u);      // positions of the two kept entries, ascending
-            const uint32_t rest = nib & (nib - 1u);
-            const uint32_t second = (uint32_t)__builtin_ctz(rest | 0x10u) & 3u;
-            a = first == 0 ? x[0] : (first == 1 ? x[1] : x[2]);
-            b = second == 1 ? x[1] : (second == 2 ? x[2] : x[3]);
-            const uint32_t field = (first & 3u) | (second << 2);
-            word = or_reduce_8lanes(field << ((lane & 7) * 4));
-        } else if constexpr (M == 2) {
-            const uint32_t ia = (nib & 1u) ? 0u : 1u, ib = (nib & 4u) ? 0u : 1u;   // which entry of each pair is kept
-            a = ia ? x[1] : x[0];
-            b = ib ? x[3] : x[2];
-            word = or_reduce_16lanes((ia | (ib << 1)) << ((lane & 15) * 2));
-        } else {
-            // own kept entries in ascending order (p = 4: no such entry) and how many there are
-            const uint32_t r1 = nib & (nib - 1u), r2 = r1 & (r1 - 1u), r3 = r2 & (r2 - 1u);
-            const uint32_t p0 = (uint32_t)__builtin_ctz(nib | 0x10u), p1 = (uint32_t)__builtin_ctz(r1 | 0x10u);
-            const uint32_t p2 = (uint32_t)__builtin_ctz(r2 | 0x10u), p3 = (uint32_t)__builtin_ctz(r3 | 0x10u);
-            const uint32_t cnt = (uint32_t)__popc(nib);
-            float own[4] = {pick4(x, p0 & 3u), pick4(x, p1 & 3u), pick4(x, p2 & 3u), pick4(x, p3 & 3u)};
-            float other[4];
+    // Eq. 12: the scale factor of an entry is that of its segment, dense index / seg_len.  One
+    // 64-bit division per span, then 32-bit ones relative to the span's first segment.
+    int64_t first_seg = 0;
+    uint32_t first_seg_off = 0;
+    if (scale) {
+        first_seg = o.dense_begin / (int64_t)seg_len;
+        first_seg_off = (uint32_t)(o.dense_begin - first_seg * (int64_t)seg_len);
+    }
+    for (int base = sub * kChunk; base < len; base += kBatch * stride) {
+        vu4_t raw[kBatch];
+        uint32_t bits[kBatch];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) other[k] = __uint_as_float(dpp_u32<kDppQuadXor1>(__float_as_uint(own[k])));
-            const uint32_t other_cnt = dpp_u32<kDppQuadXor1>(cnt);
-            const bool odd = (lane & 1) != 0;
-            const uint32_t c0 = odd ? other_cnt : cnt;       // kept entries in the even lane: they come first
-            // the group's kept values in order are L[i] = i < c0 ? E[i] : O[i - c0]; this lane stores L[2*odd], L[2*odd + 1]
-            const uint32_t i0 = odd ? 2u : 0u, i1 = i0 + 1u;
-            const float e0 = pick4(odd ? other : own, i0), o0 = pick4(odd ? own : other, (i0 - c0) & 3u);
-            const float e1 = pick4(odd ? other : own, i1), o1 = pick4(odd ? own : other, (i1 - c0) & 3u);
-            a = i0 < c0 ? e0 : o0;
-            b = i1 < c0 ? e1 : o1;
-            // indices: own s-th kept entry has in-group index 4*odd + p_s and position (odd ? c0 : 0) + s in the field
-            const uint32_t at = odd ? c0 : 0u, hi = odd ? 4u : 0u;
-            uint32_t field = 0;
-            field |= cnt > 0 ? (hi + p0) << (3u * at) : 0u;
-            field |= cnt > 1 ? (hi + p1) << (3u * (at + 1u)) : 0u;
-            field |= cnt > 2 ? (hi + p2) << (3u * (at + 2u)) : 0u;
-            field |= cnt > 3 ? (hi + p3) << (3u * (at + 3u)) : 0u;
-            field |= dpp_u32<kDppQuadXor1>(field);          // both lanes of the group now hold its 12 bits
-            field <<= (lane & 2) * 8;                       // second group of the word: upper 16 bits
-            word = field | dpp_u32<kDppQuadXor2>(field);
+        for (int k = 0; k < kBatch; ++k) {      // past the end of the span: zeros
+            const int off = base + k * stride + lane * kLaneElems;
+            raw[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad);
+            bits[k] = mask ? __builtin_amdgcn_raw_buffer_load_b32(rmask, (off >> 5) * 4, 0, kAuxLoad) : 0u;
         }
-        if (scale) { a = A * a; b = A * b; }
-        if constexpr (BF16OUT) {
-            __builtin_amdgcn_raw_buffer_store_b32(f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16), rval, (off >> 1) * 2, 0, kAuxStore);
-        } else {
-            const vu2_t pair = {__float_as_uint(a), __float_as_uint(b)};
-            __builtin_amdgcn_raw_buffer_store_b64(pair, rval, (off >> 1) * 4, 0, kAuxStore);
+#pragma unroll
+        for (int k = 0; k < kBatch; ++k) {
+            if (base + k * stride >= len) break;      // wave-uniform
+            const int off = base + k * stride + lane * kLaneElems;
+            float x[4];
+            unpack4u(raw[k], x);
+            uint32_t nib;
+            if (mask) nib = (bits[k] >> (off & 31)) & 0xFu;
+            else nib = keep_nibble<M>(x, M / 2, lane);
+            float A = 1.0f;
+            if (scale && off < len) A = scale[first_seg + fast_div(first_seg_off + (uint32_t)off, div_seg_len)];
+            float a, b;          // the two values this lane stores
+            uint32_t word;       // the metadata word its run of lanes forms
+            if constexpr (M == 4) {
+                const uint32_t first = (uint32_t)__builtin_ctz(nib | 0x10u);      // positions of the two kept entries, ascending
+                const uint32_t rest = nib & (nib - 1u);
+                const uint32_t second = (uint32_t)__builtin_ctz(rest | 0x10u) & 3u;
+                a = first == 0 ? x[0] : (first == 1 ? x[1] : x[2]);
+                b = second == 1 ? x[1] : (second == 2 ? x[2] : x[3]);
+                const uint32_t field = (first & 3u) | (second << 2);
+                word = or_reduce_8lanes(field << ((lane & 7) * 4));
+            } else if constexpr (M == 2) {
+                const uint32_t ia = (nib & 1u) ? 0u : 1u, ib = (nib & 4u) ? 0u : 1u;   // which entry of each pair is kept
+                a = ia ? x[1] : x[0];
+                b = ib ? x[3] : x[2];
+                word = or_reduce_16lanes((ia | (ib << 1)) << ((lane & 15) * 2));
+            } else {
+                // own kept entries in ascending order (p = 4: no such entry) and how many there are
+                const uint32_t r1 = nib & (nib - 1u), r2 = r1 & (r1 - 1u), r3 = r2 & (r2 - 1u);
+                const uint32_t p0 = (uint32_t)__builtin_ctz(nib | 0x10u), p1 = (uint32_t)__builtin_ctz(r1 | 0x10u);
+                const uint32_t p2 = (uint32_t)__builtin_ctz(r2 | 0x10u), p3 = (uint32_t)__builtin_ctz(r3 | 0x10u);
+                const uint32_t cnt = (uint32_t)__popc(nib);
+                float own[4] = {pick4(x, p0 & 3u), pick4(x, p1 & 3u), pick4(x, p2 & 3u), pick4(x, p3 & 3u)};
+                float other[4];
+    #pragma unroll
+                for (int k = 0; k < 4; ++k) other[k] = __uint_as_float(dpp_u32<kDppQuadXor1>(__float_as_uint(own[k])));
+                const uint32_t other_cnt = dpp_u32<kDppQuadXor1>(cnt);
+                const bool odd = (lane & 1) != 0;
+                const uint32_t c0 = odd ? other_cnt : cnt;       // kept entries in the even lane: they come first
+                // the group's kept values in order are L[i] = i < c0 ? E[i] : O[i - c0]; this lane stores L[2*odd], L[2*odd + 1]
+                const uint32_t i0 = odd ? 2u : 0u, i1 = i0 + 1u;
+                const float e0 = pick4(odd ? other : own, i0), o0 = pick4(odd ? own : other, (i0 - c0) & 3u);
+                const float e1 = pick4(odd ? other : own, i1), o1 = pick4(odd ? own : other, (i1 - c0) & 3u);
+                a = i0 < c0 ? e0 : o0;
+                b = i1 < c0 ? e1 : o1;
+                // indices: own s-th kept entry has in-group index 4*odd + p_s and position (odd ? c0 : 0) + s in the field
+                const uint32_t at = odd ? c0 : 0u, hi = odd ? 4u : 0u;
+                uint32_t field = 0;
+                field |= cnt > 0 ? (hi + p0) << (3u * at) : 0u;
+                field |= cnt > 1 ? (hi + p1) << (3u * (at + 1u)) : 0u;
+                field |= cnt > 2 ? (hi + p2) << (3u * (at + 2u)) : 0u;
+                field |= cnt > 3 ? (hi + p3) << (3u * (at + 3u)) : 0u;
+                field |= dpp_u32<kDppQuadXor1>(field);          // both lanes of the group now hold its 12 bits
+                field <<= (lane & 2) * 8;                       // second group of the word: upper 16 bits
+                word = field | dpp_u32<kDppQuadXor2>(field);
+            }
+            if (scale) { a = A * a; b = A * b; }
+            if constexpr (BF16OUT) {
+                __builtin_amdgcn_raw_buffer_store_b32(f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16), rval, (off >> 1) * 2, 0, kAuxStore);
+            } else {
+                const vu2_t pair = {__float_as_uint(a), __float_as_uint(b)};
+                __builtin_amdgcn_raw_buffer_store_b64(pair, rval, (off >> 1) * 4, 0, kAuxStore);
+            }
+            constexpr int kLanesPerWord = kEntriesPerWord / kLaneElems;
+            if ((lane & (kLanesPerWord - 1)) == 0)
+                __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off / kEntriesPerWord) * 4, 0, kAuxStore);
         }
-        constexpr int kLanesPerWord = kEntriesPerWord / kLaneElems;
-        if ((lane & (kLanesPerWord - 1)) == 0)
-            __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off / kEntriesPerWord) * 4, 0, kAuxStore);
     }
 }
 
@@ -308,25 +367,28 @@ cast_status launch_project_compress(const float *w, const float *scale, int n_se
 {
     if (rows == 0 || cols == 0) return CAST_OK;
     const bool bf16 = value_dtype == CAST_BF16;
-    const int64_t seg_len = scale ? cols / n_segments : cols;
-    const SpanPlan p = plan_spans(rows, cols, ld, 0);
+    const int64_t seg_len64 = scale ? cols / n_segments : cols;
     // the vector kernel: half-density patterns, spans and rows that are whole metadata words
     // (32 columns for 2:4, 16 for 4:8, 64 for 1:2), scale segments that are whole groups
     const int word_cols = m_group == 4 ? 32 : (m_group == 8 ? 16 : 64);
-    if (2 * n_keep == m_group && p.vec && seg_len % m_group == 0 && cols % word_cols == 0 && p.geom.span_len % word_cols == 0) {
+    const SpanPlan p = plan_batched(rows, cols, ld, word_cols < 32 ? 32 : word_cols);
+    if (2 * n_keep == m_group && p.vec && seg_len64 % m_group == 0 && cols % word_cols == 0 && p.geom.span_len % word_cols == 0 &&
+        seg_len64 < ((int64_t)1 << 31)) {
+        const uint32_t seg_len = (uint32_t)seg_len64;
+        const FastDivU32 div_seg_len = make_fast_div(seg_len);
         const dim3 grid(p.grid), block(p.block_threads);
         switch (m_group) {
         case 4:
-            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<4, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
-            else hipLaunchKernelGGL((project_compress_half_vec<4, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<4, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
+            else hipLaunchKernelGGL((project_compress_half_vec<4, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
             break;
         case 8:
-            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<8, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
-            else hipLaunchKernelGGL((project_compress_half_vec<8, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<8, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
+            else hipLaunchKernelGGL((project_compress_half_vec<8, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
             break;
         default:
-            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<2, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
-            else hipLaunchKernelGGL((project_compress_half_vec<2, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len);
+            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<2, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
+            else hipLaunchKernelGGL((project_compress_half_vec<2, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
             break;
         }
         return launch_status();
