@@ -264,6 +264,17 @@ cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, 
     return launch_status();
 }
 
+// Takes `slots` partial-sum slots out of the statistics area of a list call and queues the job
+// that adds them up into `out` (the caller has checked that the area has the room).
+static StatsPartial *take_stats_slots(StatsArea *area, uint64_t slots, cast_refresh_stats *out, const uint32_t *initial_mask)
+{
+    StatsPartial *base = area->base;
+    area->base += slots;
+    area->slots -= slots;
+    static_cast<StatsJobQueue *>(area->jobs)->add(StatsJob{base, (int64_t)slots, out, initial_mask != nullptr});
+    return base;
+}
+
 cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, uint32_t *mask_bits,
                               const float *scale, float *scale_grad, int64_t rows, int64_t cols,
                               int64_t ld, const cast_adams_config *cfg, const StepExtras &x, hipStream_t st)
@@ -282,21 +293,16 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     const uint64_t stats_slots = p.vec ? p.grid : (uint64_t)unit_grid;
     const bool stats = refresh && x.refresh_stats != nullptr && x.stats_area != nullptr && stats_slots <= x.stats_area->slots;
     if (refresh && x.refresh_stats != nullptr && !stats) return CAST_ERR_SHAPE;      // workspace too small (not reachable through the API)
-    StatsPartial *stats_partials = stats ? x.stats_area->base : nullptr;
+    StatsPartial *stats_partials = stats ? take_stats_slots(x.stats_area, stats_slots, x.refresh_stats, x.initial_mask) : nullptr;
     const uint32_t *stats_initial = stats ? x.initial_mask : nullptr;
-    if (stats) {
-        x.stats_area->base += stats_slots;
-        x.stats_area->slots -= stats_slots;
-        static_cast<StatsJobQueue *>(x.stats_area->jobs)->add(StatsJob{stats_partials, (int64_t)stats_slots, x.refresh_stats,
-                                                                        x.initial_mask != nullptr});
-    }
     // a compute copy to write or refresh statistics to gather (1), or a comparison rule with code of
     // its own (2): the EXTRA instantiations
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     const int extra = own_rule ? 2 : ((x.compute_copy != nullptr || stats) ? 1 : 0);
     if (p.vec) {
-        SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial}},
-                   as_const_table(nullptr), p.geom, make_scalars(cfg), static_cast<uint16_t *>(x.compute_copy), x.copy_scale};
+        SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
+                     static_cast<uint16_t *>(x.compute_copy), x.copy_scale}},
+                   as_const_table(nullptr), p.geom, make_scalars(cfg)};
         launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0, split, extra}, a, st);
         if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         if (split) {      // this matrix's part of the area is now in use until the pieces have been added up
@@ -333,16 +339,28 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     return launch_status();
 }
 
-// Up to kMaxFused matrices of one shape in one launch (plain flavour, no split plan): the ramp-up
-// and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a 4096 x 4096 matrix takes.
+// Up to kMaxFused matrices of one shape in one launch (no split plan, no comparison rule with code of
+// its own): the ramp-up and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a
+// 4096 x 4096 matrix takes.  `extra`: the matrices have compute copies to write or refresh
+// statistics to gather (the flavour that can do both), each its own or none.
 static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
-                                           hipStream_t st)
+                                           bool extra, StatsArea *stats_area, hipStream_t st)
 {
-    SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg), nullptr, nullptr};
-    for (int k = 0; k < n; ++k)
-        a.set[k] = TensorPtrs{ts[k]->w, ts[k]->grad, ts[k]->m, ts[k]->v, ts[k]->mask_bits, ts[k]->scale, ts[k]->scale_grad, nullptr, nullptr, nullptr};
-    launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, cfg->refresh_mask != 0, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, 0}, a, st);
+    SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
+    const bool refresh = cfg->refresh_mask != 0;
+    for (int k = 0; k < n; ++k) {
+        const cast_tensor &t = *ts[k];
+        StatsPartial *partials = nullptr;
+        if (extra && refresh && t.refresh_stats) {
+            if (stats_area == nullptr || p.grid > stats_area->slots) return CAST_ERR_SHAPE;      // (not reachable through the API)
+            partials = take_stats_slots(stats_area, p.grid, t.refresh_stats, t.initial_mask_bits);
+        }
+        a.set[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, nullptr, partials,
+                              partials ? t.initial_mask_bits : nullptr,
+                              extra ? static_cast<uint16_t *>(t.compute_copy) : nullptr, extra ? t.copy_scale : nullptr};
+    }
+    launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, extra ? 1 : 0}, a, st);
     return launch_status();
 }
 
@@ -482,7 +500,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
                     piece_jobs.push_back(PieceJob{piece_sums, t.scale_grad, g.plan.segments, g.plan.geom.pieces_per_segment});
                     piece_job_group.push_back(gi);
                 }
-                table[g.first + k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, piece_sums, nullptr, nullptr};
+                table[g.first + k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, piece_sums, nullptr, nullptr, nullptr, nullptr};
             }
         }
         // pageable source: the runtime stages it before returning, the copy itself is ordered on the stream
@@ -493,7 +511,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         size_t next_job = 0;
         for (size_t gi = 0; gi < groups.size(); ++gi) {
             const Group &g = groups[gi];
-            SpanArgs a{{}, as_const_table(static_cast<const TensorPtrs *>(workspace) + g.first), g.plan.geom, sc, nullptr, nullptr};
+            SpanArgs a{{}, as_const_table(static_cast<const TensorPtrs *>(workspace) + g.first), g.plan.geom, sc};
             const unsigned long long tasks = (unsigned long long)g.blocks_per_matrix * (unsigned)g.n;
             int blocks_per_cu = waves_per_cu / g.block_waves;
             if (blocks_per_cu < 1) blocks_per_cu = 1;
@@ -511,58 +529,76 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     }
     StatsJobQueue stats_jobs;
     StatsArea stats_area{reinterpret_cast<StatsPartial *>(area.base + layout.piece_floats), layout.stats_slots, &stats_jobs};
-    // Small matrices of one shape share a launch (they need not follow each other in the list: the
-    // matrices are independent).  A launch is kept below about 72 M entries: q, k, v, o of a
+    // Small matrices of one shape and one kernel flavour share a launch (they need not follow each
+    // other in the list: the matrices are independent).  A launch is kept below about 72 M entries: q, k, v, o of a
     // LLaMA2-7B layer go together, 16 of the 768 x 768 matrices of a 125M model; longer launches
     // lose to the drift between compute units what they gain on ramps.
     static const int fuse_limit = env_int("CAST_FUSE", kMaxFused);            // matrices per launch (1 = never fuse)
     static const int64_t fuse_max_params = (int64_t)env_int("CAST_FUSE_MAX_MPARAMS", 24) << 20;
     static const int64_t fuse_launch_params = (int64_t)env_int("CAST_FUSE_LAUNCH_MPARAMS", 72) << 20;
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
+    int dry_stats = 0;      // dry run: statistics jobs waiting for their launch
+    auto stats_room = [&](int n) -> cast_status {      // room for n more statistics jobs before their launch is enqueued
+        if (dry) {
+            if (dry_stats + n > kMaxStatsJobs) {
+                if (dry_stats > 0) ++tally->other_launches;
+                dry_stats = 0;
+            }
+            return CAST_OK;
+        }
+        return stats_jobs.count + n > kMaxStatsJobs ? stats_jobs.flush(st) : CAST_OK;
+    };
+    auto needs_extra = [&](const cast_tensor &t) { return t.compute_copy != nullptr || (want_stats && t.refresh_stats != nullptr); };
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
         const bool with_stats = want_stats && t.refresh_stats != nullptr;
-        if (!own_rule && fuse_limit > 1 && t.rows > 0 && t.cols > 0 && !t.compute_copy && !with_stats &&
-            t.rows * t.cols <= fuse_max_params) {
+        if (!own_rule && fuse_limit > 1 && t.rows > 0 && t.cols > 0 && t.rows * t.cols <= fuse_max_params) {
             int most = (int)(fuse_launch_params / (t.rows * t.cols));
             if (most > fuse_limit) most = fuse_limit;
             if (most > kMaxFused) most = kMaxFused;
+            const bool extra = needs_extra(t);
             const cast_tensor *same[kMaxFused] = {&t};
             int where[kMaxFused] = {i};
-            int n = 1;
+            int n = 1, n_stats = with_stats ? 1 : 0;
             for (int j = i + 1; j < count && n < most; ++j)
-                if (!taken[j] && !ts[j].compute_copy && !(want_stats && ts[j].refresh_stats) && ts[j].rows == t.rows &&
-                    ts[j].cols == t.cols && ts[j].ld == t.ld &&
+                if (!taken[j] && needs_extra(ts[j]) == extra && ts[j].rows == t.rows && ts[j].cols == t.cols && ts[j].ld == t.ld &&
                     (ts[j].scale_grad == nullptr) == (t.scale_grad == nullptr)) {
                     same[n] = &ts[j];
                     where[n] = j;
                     ++n;
+                    if (want_stats && ts[j].refresh_stats) ++n_stats;
                 }
             if (n > 1) {
                 const SpanPlan p = plan_spans(t.rows, t.cols, t.ld, cfg->scale_segments, true);
                 if (p.vec && p.geom.pieces_per_segment == 1) {
-                    if (dry) ++tally->step_launches;
-                    else if (launch_adams_step_fused(same, n, p, cfg, st) != CAST_OK) return CAST_ERR_LAUNCH;
+                    if (stats_room(n_stats) != CAST_OK) return CAST_ERR_LAUNCH;
+                    if (dry) {
+                        ++tally->step_launches;
+                        dry_stats += n_stats;
+                    } else {
+                        const cast_status rc = launch_adams_step_fused(same, n, p, cfg, extra, layout.stats_slots ? &stats_area : nullptr, st);
+                        if (rc != CAST_OK) return rc;
+                    }
                     for (int k = 0; k < n; ++k) taken[where[k]] = 1;
                     continue;
                 }
             }
         }
+        if (t.rows == 0 || t.cols == 0) continue;
+        if (with_stats && stats_room(1) != CAST_OK) return CAST_ERR_LAUNCH;
         if (dry) {       // one step launch; odd shapes with dL/dA take a reduction launch first; split plans a sum at the end
-            if (t.rows == 0 || t.cols == 0) continue;
             const SpanPlan p = plan_spans(t.rows, t.cols, t.ld, cfg->scale_segments, layout.piece_floats > 0 && t.scale_grad);
             ++tally->step_launches;
             if (!p.vec && t.scale && t.scale_grad) ++tally->other_launches;
             if (p.geom.pieces_per_segment > 1 && ++tally->split_matrices % kMaxPieceJobs == 1) ++tally->other_launches;
             if (with_stats) {
                 if (!p.vec) ++tally->other_launches;
-                if (++tally->stats_matrices % kMaxStatsJobs == 1) ++tally->other_launches;
+                ++dry_stats;
             }
             continue;
         }
         if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;     // make room
-        if (stats_jobs.full() && stats_jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
         StepExtras x;
         x.compute_copy = t.compute_copy;
         x.copy_scale = t.copy_scale;
@@ -573,7 +609,10 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         cast_status rc = launch_adams_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg, x, st);
         if (rc != CAST_OK) return rc;
     }
-    if (dry) return CAST_OK;
+    if (dry) {
+        if (dry_stats > 0) ++tally->other_launches;
+        return CAST_OK;
+    }
     if (jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
     return stats_jobs.flush(st);
 }

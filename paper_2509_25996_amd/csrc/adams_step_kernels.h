@@ -28,7 +28,11 @@ struct TensorPtrs {
     // Flavours that gather refresh statistics only (never read by the work queue):
     struct StatsPartial *stats_partials;   // one slot per workgroup of the launch, or NULL
     const uint32_t *initial_mask;          // the mask flips_init counts against, or NULL
-};                        // 80 bytes per entry; the work queue reads the first 64
+    // Flavours that can write the bf16 copy of the updated weights for the next forward pass
+    // (Eq. 12 applied: copy_scale[r, s] * w_new, or w_new itself when copy_scale is NULL), or NULL:
+    uint16_t *compute_copy;
+    const float *copy_scale;
+};                        // 96 bytes per entry; the work queue reads the first 64
 
 // What one workgroup contributes to the mask-learning statistics of a refresh step
 // (appendix "Mask Learning"): changed mask bits against the stored and the initial mask, and
@@ -50,10 +54,6 @@ struct SpanArgs {
     ConstTable table;     // the buffer sets of a list launch (work queue)
     SpanGeom geom;
     StepScalars s;
-    // EXTRA instantiations only: the bf16 copy of the updated weights for the next forward pass
-    // (Eq. 12 applied: copy_scale[r, s] * w_new, or w_new itself when copy_scale is NULL), or NULL
-    uint16_t *compute_copy;
-    const float *copy_scale;
 };
 
 static ConstTable as_const_table(const void *device_ptr)
@@ -151,6 +151,8 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
         t.piece_sums = (float *)ptr(hi[6], hi[7]);
         t.stats_partials = nullptr;
         t.initial_mask = nullptr;
+        t.compute_copy = nullptr;
+        t.copy_scale = nullptr;
     } else {
         t = a.set[matrix];     // a scalar load from the kernel arguments at a wave-uniform offset
     }
@@ -186,10 +188,10 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     c.emit = false;
     c.copy_A = 1.0f;
     if constexpr (EXTRA != 0) {
-        c.emit = a.compute_copy != nullptr;
+        c.emit = t.compute_copy != nullptr;
         // without a copy the resource is empty: every store through it would be void anyway
-        c.copy = span_resource(a.compute_copy + (c.emit ? o.dense_begin : 0), c.emit ? c.len * 2 : 0);
-        if (c.emit && a.copy_scale && c.len > 0) c.copy_A = a.copy_scale[c.segment];
+        c.copy = span_resource(t.compute_copy + (c.emit ? o.dense_begin : 0), c.emit ? c.len * 2 : 0);
+        if (c.emit && t.copy_scale && c.len > 0) c.copy_A = t.copy_scale[c.segment];
         c.stats_slot = t.stats_partials ? t.stats_partials + block : nullptr;
         const bool initial = t.stats_partials && t.initial_mask;
         c.b.initial_mask = span_resource(t.initial_mask + (initial ? (o.dense_begin >> 5) : 0), initial ? c.len / 8 : 0);

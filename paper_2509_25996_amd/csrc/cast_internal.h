@@ -75,9 +75,8 @@ cast_status launch_copy_probe(void *dst, const void *src, size_t bytes, hipStrea
 size_t multi_workspace_bytes(const cast_tensor *tensors, int count, const cast_adams_config *cfg);
 struct MultiTally {
     int step_launches;     // launches of the step kernels (a launch may step several matrices)
-    int other_launches;    // dL/dA reductions of odd shapes, sums of split plans
+    int other_launches;    // dL/dA reductions of odd shapes, sums of split plans and of refresh statistics
     int split_matrices = 0;
-    int stats_matrices = 0;
 };
 cast_status launch_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                     void *workspace, hipStream_t stream, MultiTally *tally = nullptr);

@@ -126,22 +126,22 @@ def test_validation_happens_before_any_launch(lib):
     arr = (T * 2)(good, bad)
     cfg = _cfg()
     ws_bytes = lambda a, n, c: lib.cast_adams_multi_workspace_bytes(a, n, C.byref(c))
-    assert ws_bytes(arr, 2, cfg) == 176 and ws_bytes(arr, 0, cfg) == 0 and ws_bytes(None, 2, cfg) == 176    # 2 x 80 + 16
+    assert ws_bytes(arr, 2, cfg) == 208 and ws_bytes(arr, 0, cfg) == 0 and ws_bytes(None, 2, cfg) == 208    # 2 x 96 + 16
     # row segments of more than 16 chunks of 256 entries are stepped in pieces of 8 chunks whose dL/dA sums
     # pass through the workspace (one float per piece)
     wide = (T * 2)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 3, 11008, 11008), good)
     seg = _cfg(scale_segments=2)
-    assert ws_bytes(wide, 2, seg) == 176 + 4 * 20          # 3 rows x 2 segments x 3 pieces, rounded up to 4 floats
-    assert ws_bytes(wide, 2, _cfg(scale_segments=2, flags=2)) == 176 + 4 * 20     # the work queue steps them in pieces too
-    assert ws_bytes(wide, 2, _cfg(scale_segments=8)) == 176
-    assert lib.cast_adams_step_multi(wide, 1, C.byref(seg), p, 144, st) == -2      # no room for the sums
+    assert ws_bytes(wide, 2, seg) == 208 + 4 * 20          # 3 rows x 2 segments x 3 pieces, rounded up to 4 floats
+    assert ws_bytes(wide, 2, _cfg(scale_segments=2, flags=2)) == 208 + 4 * 20     # the work queue steps them in pieces too
+    assert ws_bytes(wide, 2, _cfg(scale_segments=8)) == 208
+    assert lib.cast_adams_step_multi(wide, 1, C.byref(seg), p, 176, st) == -2      # no room for the sums
     # refresh statistics: one 16-byte slot per workgroup of the matrix's launch (4 x 64 entries: one workgroup)
     with_stats = (T * 1)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64, None, None, None, 0x10000))
-    assert ws_bytes(with_stats, 1, cfg) == 80 + 16 + 16
-    assert lib.cast_adams_step_multi(arr, 2, C.byref(cfg), p, 144, st) == -2
+    assert ws_bytes(with_stats, 1, cfg) == 96 + 16 + 16
+    assert lib.cast_adams_step_multi(arr, 2, C.byref(cfg), p, 176, st) == -2
     assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), p, 32, st) == -2       # workspace too small
-    assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), nul, 80, st) == -1
-    assert lib.cast_adams_step_multi(arr, 1, None, p, 80, st) == -1
+    assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), nul, 112, st) == -1
+    assert lib.cast_adams_step_multi(arr, 1, None, p, 112, st) == -1
     assert lib.cast_adams_step_multi(arr, 0, C.byref(cfg), nul, 0, st) == 0
     assert lib.cast_adams_step_multi(arr, -1, C.byref(cfg), p, 64, st) == -2
     assert lib.cast_hbm_copy_probe(p, p, 24, st) == -2
@@ -163,6 +163,15 @@ def test_list_call_launch_tally(lib):
     cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, flags=B.FLAG_WORK_QUEUE).c_struct()
     assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
     assert (step.value, other.value) == (3, 1)          # one queue launch per shape, and the sum of down's pieces
+    # compute copies, and refresh statistics on a refresh step: q, k, v, o still share a launch
+    emit = (T * 7)(*[T(a, a, a, a, a, a, a, r, c, 3 * c, a, a) for r, c in layer])
+    cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16).c_struct()
+    assert lib.cast_adams_multi_launches(emit, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
+    assert (step.value, other.value) == (4, 1)
+    stats = (T * 7)(*[T(a, a, a, a, a, a, a, r, c, 3 * c, None, None, a, a) for r, c in layer])
+    cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, refresh_mask=1).c_struct()
+    assert lib.cast_adams_multi_launches(stats, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
+    assert (step.value, other.value) == (4, 2)          # the sum of down's pieces, the sums of the statistics
     cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, rule=B.RULE_ADAM_L1).c_struct()
     assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), None) == 0
     assert step.value == 7                              # comparison rules: one launch per matrix

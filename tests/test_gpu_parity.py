@@ -463,7 +463,7 @@ def test_list_call_long_segments_scale_grad_against_oracle():
     for _ in range(2):
         st = GpuState(w0, nseg, interleaved=True)
         tl = B.TensorList([dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=g.to(DEV), scale=dev(A), scale_grad=st.scale_grad)], DEV)
-        assert tl.workspace.numel() >= 64 + 16 + 4 * r * nseg * 3
+        assert tl.workspace.numel() >= 96 + 16 + 4 * r * nseg * 3
         B.cast_adams_step_multi(tl, cfg)
         torch.cuda.synchronize()
         assert_same_bits(host(st.w), ref.w, "w")
@@ -670,6 +670,60 @@ def test_refresh_steps_gather_mask_learning_statistics(n, m):
     assert flipped > 0                      # the decay really moved masks between refreshes
     _, again = run()
     assert [h[3] for h in again] == [h[3] for h in history]      # bit for bit reproducible
+
+
+def test_list_call_shares_launches_among_matrices_with_copies_and_statistics():
+    """Matrices of one shape that all write compute copies or gather refresh statistics share launches like plain
+    ones do: same bits as a list call per matrix (which cannot share anything), copies and statistics included."""
+    shapes = [(48, 1024)] * 6 + [(16, 512)] * 3 + [(48, 1024)] * 2
+    nseg, steps = 2, 4
+    rng = np.random.default_rng(23)
+    scales = [(1 + 0.2 * rng.standard_normal((r, nseg))).astype(np.float32) for r, _ in shapes]
+
+    def make():
+        items = []
+        for i, (r, c) in enumerate(shapes):
+            st = GpuState(synth.weights(14, i, r, c), nseg, interleaved=True)
+            initial = B.alloc_mask(r, c, DEV)
+            B.cast_nm_select(st.w, 2, 4, initial)
+            item = dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=None, scale=dev(scales[i]), scale_grad=st.scale_grad)
+            if i < 9:       # the last two are plain: they must not end up in a launch of the other flavour's matrices
+                item["compute_copy"] = torch.full((r, c), 7.0, dtype=torch.bfloat16, device=DEV)
+                if i % 2 == 0:
+                    item["copy_scale"] = item["scale"]
+                if i % 3 != 1:
+                    item["initial_mask"] = initial if i % 3 == 0 else None
+                    item["refresh_stats"] = B.alloc_refresh_stats(DEV)
+            items.append(item)
+        return items
+
+    together, apart = make(), make()
+    for t in range(steps):
+        cfg = B.iteration_config(t, steps, mask_period=2, lr=3e-3, lambda_=2e-2, scale_segments=nseg)
+        for i, (r, c) in enumerate(shapes):
+            g = synth.grads_bf16(14, i, t, r, c).to(DEV)
+            together[i]["grad"], apart[i]["grad"] = g, g
+        B.cast_adams_step_multi(B.TensorList(together, DEV), cfg)
+        for item in apart:
+            B.cast_adams_step_multi(B.TensorList([item], DEV), cfg)
+        torch.cuda.synchronize()
+        for i, (x, y) in enumerate(zip(together, apart)):
+            for k in ("w", "m", "v", "mask", "scale_grad"):
+                assert host(x[k]).tobytes() == host(y[k]).tobytes(), (t, i, k)
+            if "compute_copy" in x:
+                assert host(x["compute_copy"].view(torch.int16)).tobytes() == host(y["compute_copy"].view(torch.int16)).tobytes(), (t, i)
+            if "refresh_stats" in x:
+                assert host(x["refresh_stats"]).tobytes() == host(y["refresh_stats"]).tobytes(), (t, i)
+                if cfg.refresh_mask and t > 0:
+                    assert B.read_refresh_stats(x["refresh_stats"])["l1_all"] > 0
+    # and the whole thing against the oracle, for the first matrix
+    ref = OracleState(synth.weights(14, 0, *shapes[0]), "f32")
+    for t in range(steps):
+        cfg = B.iteration_config(t, steps, mask_period=2, lr=3e-3, lambda_=2e-2, scale_segments=nseg)
+        ref.step(synth.widen_bf16(synth.grads_bf16(14, 0, t, *shapes[0])), oracle_cfg(cfg), A=scales[0])
+    assert_same_bits(host(together[0]["w"]), ref.w, "w")
+    want = oracle.bf16_rne(oracle.weight_scale(ref.w, scales[0]))
+    assert (host(together[0]["compute_copy"].view(torch.int16)).view(np.uint16) == want).all()
 
 
 @pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
