@@ -37,7 +37,8 @@ class _Cfg(C.Structure):
                 ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("lambda_", C.c_float), ("alpha", C.c_float), ("bias_corr1", C.c_float),
                 ("bias_corr2", C.c_float), ("refresh_mask", C.c_int32),
-                ("scale_segments", C.c_int32), ("v_from_grad", C.c_int32), ("rule", C.c_int32)]
+                ("scale_segments", C.c_int32), ("v_from_grad", C.c_int32), ("rule", C.c_int32),
+                ("mu_bf16", C.c_int32)]
 
 
 # update rules (the enum of cast_oracle.c)
@@ -61,11 +62,12 @@ class AdamsCfg:
     scale_segments: int = 0
     v_from_grad: int = 0
     rule: int = 0
+    mu_bf16: int = 0        # first moment kept in bf16 between iterations (storage variant, not in the paper)
 
     def c_struct(self) -> _Cfg:
         return _Cfg(self.n_keep, self.m_group, self.lr, self.beta1, self.beta2, self.eps,
                     self.lambda_, self.alpha, self.bias_corr1, self.bias_corr2,
-                    self.refresh_mask, self.scale_segments, self.v_from_grad, self.rule)
+                    self.refresh_mask, self.scale_segments, self.v_from_grad, self.rule, self.mu_bf16)
 
 
 def iteration_scalars(t: int, total_steps: int, beta1: float, beta2: float):

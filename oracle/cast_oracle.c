@@ -50,7 +50,22 @@ typedef struct {
     int32_t scale_segments; /* n of Eq. 12; 0 = gradient is already w.r.t. W            */
     int32_t v_from_grad;    /* 1: second moment from g^2 (Eq. 9 form, test pin only)    */
     int32_t rule;           /* which update rule; 0 = AdamS (Eq. 8), see RULE_* below   */
+    int32_t mu_bf16;        /* 1: the first moment is KEPT in bf16 between iterations (a
+                             * storage variant outside the paper): what is stored is the new
+                             * mu rounded to nearest-even bf16; everything computed in the
+                             * same iteration (mu~, v, the update) uses the unrounded value  */
 } oracle_adams_cfg;
+
+uint16_t oracle_bf16_rne(float x);
+
+/* the value a bf16 store of x reads back as */
+static float through_bf16(float x)
+{
+    uint32_t bits = (uint32_t)oracle_bf16_rne(x) << 16;
+    float y;
+    memcpy(&y, &bits, sizeof y);
+    return y;
+}
 
 /* The update rules the paper sets AdamS against (Sec. 4.1.2, 4.1.3, 5.7).  In all of them the
  * decay acts only where the mask bit is 0 and has strength alpha*lambda, like Eq. 7's second
@@ -332,7 +347,7 @@ int oracle_adams_step_f64(float *w, const float *grad, float *mu, float *v, uint
                 double th, m1, v1;
                 adams_element_f64(w[idx], g, mu[idx], v[idx], keep[idx], &p, &th, &m1, &v1);
                 w[idx] = (float)th;
-                mu[idx] = (float)m1;
+                mu[idx] = cfg->mu_bf16 ? through_bf16((float)m1) : (float)m1;
                 v[idx] = (float)v1;
             }
         }
@@ -379,7 +394,7 @@ int oracle_adams_step_f32(float *w, const float *grad, float *mu, float *v, uint
                 float th, m1, v1;
                 adams_element_f32(w[idx], g, mu[idx], v[idx], keep[idx], &p, &th, &m1, &v1);
                 w[idx] = th;
-                mu[idx] = m1;
+                mu[idx] = cfg->mu_bf16 ? through_bf16(m1) : m1;
                 v[idx] = v1;
             }
         }
