@@ -61,6 +61,15 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  * resident workgroups that draw their work in order from a ticket counter, instead of one launch
  * per matrix.  Same results bit for bit. */
 #define CAST_FLAG_WORK_QUEUE 2u
+/* Storage variant outside the paper (Algorithm 1 does not say how the moments are kept): the first
+ * moment is kept in bf16.  `m` then points to bf16 values (uint16_t), 16-byte aligned, whose row
+ * stride in bf16 entries is cols when ld == cols and 2 * ld otherwise (the byte pitch of w and v,
+ * as when the rows of the three arrays are interleaved in one allocation).  The new mu is rounded
+ * to nearest even when stored; mu~, v and the update of the same iteration use the unrounded
+ * value.  22.125 instead of 26.125 bytes per parameter.  Only with CAST_RULE_ADAMS and
+ * CAST_RULE_ADDITIVE, and without compute copy and refresh statistics (else CAST_ERR_CONFIG);
+ * the work queue flag is ignored with it. */
+#define CAST_FLAG_MU_BF16 4u
 
 /* Update rules.  CAST_RULE_ADAMS is the paper's method (Algorithm 1, Eq. 8); the others are the
  * rules it is set against, for ablations.  In all of them the decay acts only on entries whose

@@ -16,6 +16,7 @@ LIB_PATH = os.environ.get("CAST_LIBRARY") or os.path.join(_HERE, "libcast.so")  
 CAST_F32, CAST_BF16 = 0, 1
 FLAG_V_FROM_GRAD = 1
 FLAG_WORK_QUEUE = 2
+FLAG_MU_BF16 = 4
 RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = range(5)
 
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
@@ -149,16 +150,36 @@ def _ld(w, *same):
     if w.shape[1] > 1 and w.stride(1) != 1:
         raise ValueError("w, m, v must be 2-D GPU tensors with contiguous rows")
     ld = w.stride(0) if w.shape[0] > 1 else max(w.stride(0), w.shape[1])
+    ld = max(ld, w.shape[1])
     for t in same:
-        if t.shape != w.shape or (t.shape[0] > 1 and t.stride(0) != w.stride(0)) or (t.shape[1] > 1 and t.stride(1) != 1):
+        # a first moment kept in bf16: dense if w is, else the byte pitch of w (twice its row stride in entries)
+        want = w.stride(0) if t.dtype == torch.float32 else (w.shape[1] if ld == w.shape[1] else 2 * ld)
+        if t.shape != w.shape or (t.shape[0] > 1 and t.stride(0) != want) or (t.shape[1] > 1 and t.stride(1) != 1):
             raise ValueError("w, m and v must share one shape and one row stride")
-    return max(ld, w.shape[1])
+    return ld
 
 
-def interleaved_state(w0: torch.Tensor):
+def _mu_flag(cfg, m) -> None:
+    """Sets or clears CAST_FLAG_MU_BF16 according to the dtype of the first moment."""
+    if m.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("m must be float32 or bfloat16")
+    cfg.flags = (cfg.flags & ~FLAG_MU_BF16) | (FLAG_MU_BF16 if m.dtype == torch.bfloat16 else 0)
+
+
+def interleaved_state(w0: torch.Tensor, mu_bf16: bool = False):
     """Allocate w, m, v of one matrix interleaved row by row in one buffer [rows, 3, cols] (row
-    stride 3*cols for each of the three views).  w is initialised from w0, m and v are zero."""
+    stride 3*cols for each of the three views).  w is initialised from w0, m and v are zero.
+    mu_bf16: m is bfloat16 and a row of the buffer is cols fp32, cols bf16, cols fp32 (10 * cols bytes)."""
     rows, cols = w0.shape
+    if mu_bf16:
+        if cols % 8:
+            raise ValueError("cols must be a multiple of 8")
+        raw = torch.zeros((rows, 10 * cols), dtype=torch.uint8, device=w0.device)
+        w = raw[:, :4 * cols].view(torch.float32)
+        m = raw[:, 4 * cols:6 * cols].view(torch.bfloat16)
+        v = raw[:, 6 * cols:].view(torch.float32)
+        w.copy_(w0)
+        return w, m, v
     state = torch.zeros((rows, 3, cols), dtype=torch.float32, device=w0.device)
     state[:, 0, :].copy_(w0)
     return state[:, 0, :], state[:, 1, :], state[:, 2, :]
@@ -186,6 +207,7 @@ def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scal
     _dev(grad, mask_bits, scale, scale_grad)
     rows, cols = w.shape
     cfg.grad_dtype = _dtype_code(grad)
+    _mu_flag(cfg, m)
     cs = cfg.c_struct()
     _check(load().cast_adams_step(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
                                   rows, cols, _ld(w, m, v), C.byref(cs), _stream(stream)), "cast_adams_step")
@@ -199,6 +221,7 @@ def cast_adams_step_emit(w, grad, m, v, mask_bits, cfg: AdamsConfig, compute_cop
         raise TypeError("compute_copy must be bfloat16")
     rows, cols = w.shape
     cfg.grad_dtype = _dtype_code(grad)
+    _mu_flag(cfg, m)
     cs = cfg.c_struct()
     _check(load().cast_adams_step_emit(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
                                        _ptr(copy_scale), _ptr(compute_copy), rows, cols, _ld(w, m, v), C.byref(cs),
@@ -232,8 +255,12 @@ class TensorList:
         n = len(self.items)
         self.array = (_Tensor * max(n, 1))()
         self.grad_dtype = None
+        self.mu_dtype = None
         for k, x in enumerate(self.items):
             w, m, v = x["w"], x["m"], x["v"]
+            if self.mu_dtype not in (None, m.dtype):
+                raise ValueError("all first moments of a list must have one dtype")
+            self.mu_dtype = m.dtype
             _dev(x["grad"], x["mask"], x.get("scale"), x.get("scale_grad"))
             dt = _dtype_code(x["grad"])
             if self.grad_dtype not in (None, dt):
@@ -268,6 +295,7 @@ class TensorList:
 def cast_adams_step_multi(tensors: TensorList, cfg: AdamsConfig, stream=None):
     if tensors.count:
         cfg.grad_dtype = tensors.grad_dtype
+        _mu_flag(cfg, tensors.items[0]["m"])
     cs = cfg.c_struct()
     _check(load().cast_adams_step_multi(tensors.array, tensors.count, C.byref(cs), _ptr(tensors.workspace),
                                         tensors.workspace.numel(), _stream(stream)), "cast_adams_step_multi")
@@ -277,6 +305,7 @@ def cast_adams_multi_launches(tensors: TensorList, cfg: AdamsConfig):
     """(launches of the step kernel, other launches) one cast_adams_step_multi call makes for this list."""
     if tensors.count:
         cfg.grad_dtype = tensors.grad_dtype
+        _mu_flag(cfg, tensors.items[0]["m"])
     cs = cfg.c_struct()
     a, b = C.c_int32(0), C.c_int32(0)
     _check(load().cast_adams_multi_launches(tensors.array, tensors.count, C.byref(cs), C.byref(a), C.byref(b)),

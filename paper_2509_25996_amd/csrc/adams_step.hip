@@ -75,6 +75,7 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool
     g.total = rows * cols;
     g.cols = cols;
     g.row_gap = ld - cols;
+    g.m_row_gap = g.row_gap;
     g.waves_per_span = 1;
     g.div_spans_per_row = make_fast_div(1);
     g.pieces_per_segment = 1;
@@ -196,11 +197,16 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
     }
     if constexpr (SCALED) {
         if (l.split) {
-            if (l.extra == 2) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 2>), grid, block, 0, st, a);
+            if (l.extra == kMuBf16) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, kMuBf16>), grid, block, 0, st, a);
+            else if (l.extra == 2) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 2>), grid, block, 0, st, a);
             else if (l.extra == 1) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 1>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true>), grid, block, 0, st, a);
             return;
         }
+    }
+    if (l.extra == kMuBf16) {
+        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, kMuBf16>), grid, block, 0, st, a);
+        return;
     }
     if (l.extra == 2) {
         hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, 2>), grid, block, 0, st, a);
@@ -264,6 +270,10 @@ cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, 
     return launch_status();
 }
 
+// Row stride, in its own entries, of a first moment kept in bf16: dense when w and v are, else the
+// same byte pitch as theirs (the three arrays interleaved row by row in one allocation).
+static int64_t mu_bf16_ld(int64_t cols, int64_t ld) { return ld == cols ? cols : 2 * ld; }
+
 // Takes `slots` partial-sum slots out of the statistics area of a list call and queues the job
 // that adds them up into `out` (the caller has checked that the area has the room).
 static StatsPartial *take_stats_slots(StatsArea *area, uint64_t slots, cast_refresh_stats *out, const uint32_t *initial_mask)
@@ -298,7 +308,10 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     // a compute copy to write or refresh statistics to gather (1), or a comparison rule with code of
     // its own (2): the EXTRA instantiations
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
-    const int extra = own_rule ? 2 : ((x.compute_copy != nullptr || stats) ? 1 : 0);
+    // (a first moment kept in bf16 comes with none of the above: the API has seen to that)
+    const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
+    const int extra = mu16 ? kMuBf16 : (own_rule ? 2 : ((x.compute_copy != nullptr || stats) ? 1 : 0));
+    p.geom.m_row_gap = mu_bf16_ld(cols, ld) - cols;
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
                      static_cast<uint16_t *>(x.compute_copy), x.copy_scale}},
@@ -329,7 +342,7 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
         if (rc != CAST_OK) return rc;
     }
     UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, ld, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg),
-               static_cast<uint16_t *>(x.compute_copy), x.copy_scale};
+               static_cast<uint16_t *>(x.compute_copy), x.copy_scale, mu16 ? mu_bf16_ld(cols, ld) : 0};
     const unsigned grid = (unsigned)unit_grid;
     switch (cfg->m_group) {
     case 2: launch_unit_dtype<2>(bf16, grid, a, st); break;
@@ -348,6 +361,8 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
 {
     SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
     const bool refresh = cfg->refresh_mask != 0;
+    const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
+    a.geom.m_row_gap = mu_bf16_ld(ts[0]->cols, ts[0]->ld) - ts[0]->cols;
     for (int k = 0; k < n; ++k) {
         const cast_tensor &t = *ts[k];
         StatsPartial *partials = nullptr;
@@ -360,7 +375,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
                               extra ? static_cast<uint16_t *>(t.compute_copy) : nullptr, extra ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, extra ? 1 : 0}, a, st);
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? kMuBf16 : (extra ? 1 : 0)}, a, st);
     return launch_status();
 }
 
@@ -429,6 +444,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
     // the work queue knows neither the comparison rules with code of their own nor the compute copy
     if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN) use_queue = false;
+    if (cfg->flags & CAST_FLAG_MU_BF16) use_queue = false;      // nor a first moment kept in bf16
     const bool want_stats = cfg->refresh_mask != 0;
     for (int i = 0; i < count; ++i)
         if (ts[i].compute_copy || (want_stats && ts[i].refresh_stats)) use_queue = false;      // nor refresh statistics

@@ -61,10 +61,16 @@ static ConstTable as_const_table(const void *device_ptr)
     return (ConstTable)(uintptr_t)device_ptr;
 }
 
+// Kernel flavours (template argument EXTRA): 0 plain; 1 can also write the bf16 compute copy and
+// gather refresh statistics; 2 knows, on top, the comparison update rules with code of their own;
+// 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16).
+constexpr bool has_extras(int extra) { return extra == 1 || extra == 2; }
+constexpr int kMuBf16 = 3;
+
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
 template <bool BF16>
 struct Chunk {
-    vu4_t w, m, v;
+    vu4_t w, m, v;    // a bf16 first moment: the first 2 dwords of m hold 4 values
     vu4_t g;          // fp32 gradient: 4 dwords; bf16: the first 2 dwords hold 4 values
     uint32_t word;    // the mask word that holds this lane's 4 bits (non-refresh steps)
     uint32_t initial; // the same word of the initial mask (refresh steps that gather statistics)
@@ -79,7 +85,7 @@ struct SpanBuffers {
 
 // WORD: whether the stored mask word is wanted (non-refresh steps; refresh steps that count flips);
 // INITIAL: whether the initial mask's word is (the latter only)
-template <bool BF16, bool WORD, bool INITIAL = false>
+template <bool BF16, bool WORD, bool INITIAL = false, bool MU16 = false>
 __device__ __forceinline__ void chunk_load(Chunk<BF16> &c, const SpanBuffers &b, int off)
 {
     c.w = __builtin_amdgcn_raw_buffer_load_b128(b.w, off * 4, 0, kAuxLoad);
@@ -89,7 +95,12 @@ __device__ __forceinline__ void chunk_load(Chunk<BF16> &c, const SpanBuffers &b,
     } else {
         c.g = __builtin_amdgcn_raw_buffer_load_b128(b.g, off * 4, 0, kAuxLoad);
     }
-    c.m = __builtin_amdgcn_raw_buffer_load_b128(b.m, off * 4, 0, kAuxLoad);
+    if constexpr (MU16) {
+        const vu2_t t = __builtin_amdgcn_raw_buffer_load_b64(b.m, off * 2, 0, kAuxLoad);
+        c.m.x = t.x; c.m.y = t.y; c.m.z = 0; c.m.w = 0;
+    } else {
+        c.m = __builtin_amdgcn_raw_buffer_load_b128(b.m, off * 4, 0, kAuxLoad);
+    }
     c.v = __builtin_amdgcn_raw_buffer_load_b128(b.v, off * 4, 0, kAuxLoad);
     if constexpr (WORD) c.word = __builtin_amdgcn_raw_buffer_load_b32(b.mask, (off >> 5) * 4, 0, kAuxLoad);
     else c.word = 0;
@@ -174,7 +185,8 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     o.len = __builtin_amdgcn_readfirstlane(o.len);
     c.len = o.len;
     c.b.w = span_resource(t.w + o.state_begin, c.len * 4);
-    c.b.m = span_resource(t.m + o.state_begin, c.len * 4);
+    if constexpr (EXTRA == kMuBf16) c.b.m = span_resource(reinterpret_cast<uint16_t *>(t.m) + (int64_t)uniform_u64((unsigned long long)o.m_begin), c.len * 2);
+    else c.b.m = span_resource(t.m + o.state_begin, c.len * 4);
     c.b.v = span_resource(t.v + o.state_begin, c.len * 4);
     if constexpr (BF16) c.b.g = span_resource(static_cast<const uint16_t *>(t.grad) + o.dense_begin, c.len * 2);
     else c.b.g = span_resource(static_cast<const float *>(t.grad) + o.dense_begin, c.len * 4);
@@ -187,7 +199,7 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     }
     c.emit = false;
     c.copy_A = 1.0f;
-    if constexpr (EXTRA != 0) {
+    if constexpr (has_extras(EXTRA)) {
         c.emit = t.compute_copy != nullptr;
         // without a copy the resource is empty: every store through it would be void anyway
         c.copy = span_resource(t.compute_copy + (c.emit ? o.dense_begin : 0), c.emit ? c.len * 2 : 0);
@@ -219,7 +231,8 @@ template <int M, bool BF16, bool REFRESH, bool SCALED, int EXTRA = 0>
 __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Chunk<BF16> cur, int lane, int wave,
                                          float *partial, StatsShared *stats_shared = nullptr)
 {
-    constexpr bool kStats = REFRESH && EXTRA != 0;      // refresh statistics are gathered if c.stats_slot says so
+    constexpr bool kStats = REFRESH && has_extras(EXTRA);      // refresh statistics are gathered if c.stats_slot says so
+    constexpr bool kMu16 = EXTRA == kMuBf16;
     uint32_t flips_prev = 0, flips_init = 0;
     float l1_kept = 0.0f, l1_all = 0.0f;
     const int P = a.geom.waves_per_span;
@@ -232,11 +245,15 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
     int off = first_offset(c, lane);      // this lane's first entry, relative to the span
     for (int base = c.sub * kChunk; base < len; base += stride) {
         Chunk<BF16> nxt;
-        chunk_load<BF16, (!REFRESH || EXTRA != 0), (REFRESH && EXTRA != 0)>(nxt, b, off + stride);     // past the end: all zeros, never used
+        chunk_load<BF16, (!REFRESH || has_extras(EXTRA)), kStats, kMu16>(nxt, b, off + stride);     // past the end: all zeros, never used
 
         float w[4], g[4], mu[4], v[4];
         unpack4(cur.w, w);
-        unpack4(cur.m, mu);
+        if constexpr (kMu16) {
+            mu[0] = bf16_lo(cur.m.x); mu[1] = bf16_hi(cur.m.x); mu[2] = bf16_lo(cur.m.y); mu[3] = bf16_hi(cur.m.y);
+        } else {
+            unpack4(cur.m, mu);
+        }
         unpack4(cur.v, v);
         if constexpr (BF16) {
             g[0] = bf16_lo(cur.g.x); g[1] = bf16_hi(cur.g.x); g[2] = bf16_lo(cur.g.y); g[3] = bf16_hi(cur.g.y);
@@ -275,9 +292,14 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         }
         adams_entries4<(EXTRA == 2), (EXTRA == 1)>(w, g, mu, v, nib, off < len, a.s);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
-        __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
+        if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
+            const vu2_t h = {f32_to_bf16_rne(mu[0]) | (f32_to_bf16_rne(mu[1]) << 16), f32_to_bf16_rne(mu[2]) | (f32_to_bf16_rne(mu[3]) << 16)};
+            __builtin_amdgcn_raw_buffer_store_b64(h, b.m, off * 2, 0, kAuxStore);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
+        }
         __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
-        if constexpr (EXTRA != 0) {
+        if constexpr (has_extras(EXTRA)) {
             if (c.emit) {      // the weights the next forward pass multiplies with: bf16(A * w_new), Eq. 12
                 vu2_t h;
                 h.x = f32_to_bf16_rne(c.copy_A * w[0]) | (f32_to_bf16_rne(c.copy_A * w[1]) << 16);
@@ -342,6 +364,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
 // One matrix, one workgroup per share, dealt by the hardware dispatcher.  SPLIT: the spans are
 // pieces of row segments (Eq. 12) too long for one workgroup of short-lived wavefronts; each
 // workgroup leaves the dL/dA sum of its piece in a[.].piece_sums and sum_piece_sums adds them up.
+// EXTRA = 3: the first moment is kept in bf16.
 // EXTRA = 1: instantiations that can also write the bf16 compute copy; EXTRA = 2: those that, on
 // top, know the comparison update rules (a.s.rule), at the price of 12 more registers and one
 // wavefront per SIMD less.  The plain ones (0) carry none of that code.
@@ -354,8 +377,8 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     SpanCtx c;
     span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
     Chunk<BF16> first;
-    chunk_load<BF16, (!REFRESH || EXTRA != 0), (REFRESH && EXTRA != 0)>(first, c.b, first_offset(c, lane));
-    if constexpr (REFRESH && EXTRA != 0) {
+    chunk_load<BF16, (!REFRESH || has_extras(EXTRA)), (REFRESH && has_extras(EXTRA)), EXTRA == kMuBf16>(first, c.b, first_offset(c, lane));
+    if constexpr (REFRESH && has_extras(EXTRA)) {
         __shared__ StatsShared stats_shared;
         span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial, &stats_shared);
     } else {
@@ -593,6 +616,7 @@ struct UnitArgs {
     StepScalars s;
     uint16_t *compute_copy;     // bf16 [rows, cols] or NULL
     const float *copy_scale;    // [rows, n_segments] or NULL
+    int64_t m_ld;               // > 0: m is bf16 with this row stride (in its own entries); 0: fp32 like w and v
 };
 
 template <bool BF16>
@@ -637,10 +661,12 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs 
             for (int j = 0; j < M; ++j) {
                 float g = load_grad1<BF16>(a.grad, gidx + j);
                 if (a.scale) g = A * g;
-                float mu = a.m[idx + j], vv = a.v[idx + j];
+                uint16_t *m16 = reinterpret_cast<uint16_t *>(a.m) + r * a.m_ld + c + j;
+                float mu = a.m_ld > 0 ? bf16_to_f32(*m16) : a.m[idx + j], vv = a.v[idx + j];
                 adams_entry(wv[j], g, mu, vv, (bits >> j) & 1u, a.s);
                 a.w[idx + j] = wv[j];
-                a.m[idx + j] = mu;
+                if (a.m_ld > 0) *m16 = (uint16_t)f32_to_bf16_rne(mu);
+                else a.m[idx + j] = mu;
                 a.v[idx + j] = vv;
                 if (a.compute_copy) a.compute_copy[gidx + j] = (uint16_t)f32_to_bf16_rne(copy_A * wv[j]);
             }

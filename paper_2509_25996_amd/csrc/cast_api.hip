@@ -105,8 +105,10 @@ static cast_status validate_step(const float *w, const void *grad, const float *
     if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (!dtype_ok(cfg->grad_dtype)) return CAST_ERR_DTYPE;
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
-    if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE)) return CAST_ERR_CONFIG;
+    if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE | CAST_FLAG_MU_BF16)) return CAST_ERR_CONFIG;
     if (cfg->rule < CAST_RULE_ADAMS || cfg->rule > CAST_RULE_MASKED_FROZEN) return CAST_ERR_CONFIG;
+    if ((cfg->flags & CAST_FLAG_MU_BF16) && ((cfg->rule != CAST_RULE_ADAMS && cfg->rule != CAST_RULE_ADDITIVE) || compute_copy))
+        return CAST_ERR_CONFIG;
     // the bias corrections divide: they must be positive finite numbers (1 - beta^s with s >= 1)
     if (!(cfg->bias_corr1 > 0.0f) || !(cfg->bias_corr2 > 0.0f) || isinf(cfg->bias_corr1) || isinf(cfg->bias_corr2))
         return CAST_ERR_CONFIG;
@@ -169,6 +171,7 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
         const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
                                              t.compute_copy, t.copy_scale);
         if (rc != CAST_OK) return rc;
+        if ((cfg->flags & CAST_FLAG_MU_BF16) && t.refresh_stats) return CAST_ERR_CONFIG;
     }
     for (int i = 0; i < count; ++i)
         if (!aligned(tensors[i].initial_mask_bits, 4) || !aligned(tensors[i].refresh_stats, 8)) return CAST_ERR_ALIGN;
@@ -186,6 +189,7 @@ cast_status cast_adams_multi_launches(const cast_tensor *tensors, int count, con
         const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
                                              t.compute_copy, t.copy_scale);
         if (rc != CAST_OK) return rc;
+        if ((cfg->flags & CAST_FLAG_MU_BF16) && t.refresh_stats) return CAST_ERR_CONFIG;
     }
     MultiTally tally{0, 0};
     const cast_status rc = launch_adams_step_multi(tensors, count, cfg, nullptr, nullptr, &tally);

@@ -60,6 +60,7 @@ struct SpanGeom {
     int64_t total;          // rows * cols
     int64_t cols;
     int64_t row_gap;        // ld - cols: entries skipped between the rows of w, mu, v
+    int64_t m_row_gap;      // the same for a first moment kept in bf16, in its own entries (else = row_gap)
     int64_t span_len;       // entries per span (the last span of a flat plan may be shorter)
     int64_t num_spans;
     int spans_per_row;      // 0: flat plan (the matrix is one contiguous array, spans ignore rows)
@@ -98,21 +99,27 @@ __host__ __device__ __forceinline__ SpanSlot span_slot(const SpanGeom &g, int64_
 struct SpanOrigin {
     int64_t state_begin;    // first entry of the span in w, mu, v
     int64_t dense_begin;    // first entry of the span in dense [rows, cols] numbering
+    int64_t m_begin;        // first entry of the span in a first moment kept in bf16
     int len;                // entries (0 for spans past the end)
 };
 
 __host__ __device__ __forceinline__ SpanOrigin span_origin(const SpanGeom &g, int64_t span)
 {
-    SpanOrigin o{0, 0, 0};
+    SpanOrigin o{0, 0, 0, 0};
     if (span >= g.num_spans) return o;
     o.dense_begin = span * g.span_len;
     o.state_begin = o.dense_begin;
+    o.m_begin = o.dense_begin;
     if (g.spans_per_row == 0) {
         const int64_t rem = g.total - o.dense_begin;
         o.len = (int)(rem < g.span_len ? rem : g.span_len);
     } else {
         o.len = (int)g.span_len;
-        if (g.row_gap != 0) o.state_begin += (int64_t)fast_div((uint32_t)span, g.div_spans_per_row) * g.row_gap;
+        if (g.row_gap != 0) {
+            const int64_t row = (int64_t)fast_div((uint32_t)span, g.div_spans_per_row);
+            o.state_begin += row * g.row_gap;
+            o.m_begin += row * g.m_row_gap;
+        }
     }
     return o;
 }
@@ -120,7 +127,7 @@ __host__ __device__ __forceinline__ SpanOrigin span_origin(const SpanGeom &g, in
 // Split plan: span = piece number; `segment` tells which row segment (scale factor) it belongs to.
 __host__ __device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, int64_t span, int64_t &segment)
 {
-    SpanOrigin o{0, 0, 0};
+    SpanOrigin o{0, 0, 0, 0};
     segment = 0;
     if (span >= g.num_spans) return o;
     const uint32_t seg = fast_div((uint32_t)span, g.div_pieces);
@@ -130,7 +137,12 @@ __host__ __device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, i
     o.len = (int)(rem < g.span_len ? rem : g.span_len);
     o.dense_begin = (int64_t)seg * g.segment_len + done;
     o.state_begin = o.dense_begin;
-    if (g.row_gap != 0) o.state_begin += (int64_t)fast_div((uint32_t)span, g.div_spans_per_row) * g.row_gap;
+    o.m_begin = o.dense_begin;
+    if (g.row_gap != 0) {
+        const int64_t row = (int64_t)fast_div((uint32_t)span, g.div_spans_per_row);
+        o.state_begin += row * g.row_gap;
+        o.m_begin += row * g.m_row_gap;
+    }
     return o;
 }
 
