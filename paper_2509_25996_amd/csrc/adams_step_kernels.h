@@ -145,7 +145,7 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     // arrive in scalar registers, where buffer resources have to live.
     TensorPtrs t;
     if constexpr (FROM_TABLE) {
-        // explicit scalar loads of the 64-byte entry (two 8-dword reads)
+        // explicit scalar loads of the first 64 bytes of the entry (two 8-dword reads)
         typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
         const uint64_t entry = uniform_u64((uint64_t)(uintptr_t)a.table + (uint64_t)matrix * sizeof(TensorPtrs));
         u32x8 lo, hi;

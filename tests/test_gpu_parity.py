@@ -407,7 +407,7 @@ def test_strided_weights_in_every_entry_point(rows, cols):
 def test_multi_tensor_step_equals_single_steps(nseg, queue):
     # (16, 11008) and (7, 8768) have row segments of more than 16 chunks of 256 entries: the list call steps
     # them in pieces of 2048 entries (with or without the work queue) and adds the pieces' dL/dA sums afterwards
-    # runs of equal shapes: the list call steps up to 4 small matrices of one shape with one launch
+    # runs of equal shapes: the list call steps up to 16 small matrices of one shape with one launch
     shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (5, 72), (64, 512), (32, 1024), (32, 1024), (3, 40), (0, 64),
               (16, 11008), (16, 11008), (7, 8768), (64, 512), (64, 512), (64, 512), (64, 512), (64, 512), (0, 64), (64, 512)]
     rng = np.random.default_rng(9)
