@@ -182,6 +182,9 @@ cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v,
  *                        cfg->scale_segments and cfg->flags only), 16-byte aligned, owned by the
  *                        caller; it is overwritten by every call and used by the kernels of that
  *                        call, so it must not be shared between streams (too small: CAST_ERR_SHAPE)
+ * Without CAST_FLAG_WORK_QUEUE the call enqueues kernel launches only (no copies, no memsets), so it
+ * can be recorded while the stream is being captured into a HIP graph; with the flag it first copies
+ * a table from pageable host memory to the workspace, which capture does not allow.
  */
 /* Mask-learning statistics of one matrix gathered by a refresh step itself (appendix "Mask
  * Learning"; the numerators of the flip rate r_t and the initial flip rate i_t, and both terms of

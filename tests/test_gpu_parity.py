@@ -769,3 +769,50 @@ def test_example_loop_drives_masked_weights_to_zero():
     assert flips_init[-1] > 0                     # and differ from the dense model's mask
     for values, meta in out["packed"]:
         assert bool(torch.isfinite(values.float()).all())
+
+
+def test_list_call_captured_in_a_graph_replays_like_eager_calls():
+    """The default list call enqueues kernels only (no copies, no memsets, nothing allocated), so a caller can
+    capture it in a HIP graph; every replay, with eager work in between, equals the same call made eagerly."""
+    shapes = [(64, 512)] * 5 + [(16, 11008)] * 2 + [(7, 72), (32, 1024), (32, 1024)]
+    nseg = 2
+    rng = np.random.default_rng(31)
+    scales = [(1 + 0.1 * rng.standard_normal((r, nseg))).astype(np.float32) for r, _ in shapes]
+
+    def make():
+        items = []
+        for i, (r, c) in enumerate(shapes):
+            st = GpuState(synth.weights(15, i, r, c), nseg, interleaved=c % 8 == 0)
+            items.append(dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=synth.grads_bf16(15, i, 0, r, c).to(DEV),
+                              scale=dev(scales[i]), scale_grad=st.scale_grad,
+                              compute_copy=torch.zeros((r, c), dtype=torch.bfloat16, device=DEV) if i % 3 == 0 else None))
+        return items
+
+    eager, graphed = make(), make()
+    tl_eager, tl_graph = B.TensorList(eager, DEV), B.TensorList(graphed, DEV)
+    cfg = B.iteration_config(4, 10, mask_period=1, lr=1e-3, lambda_=1e-3, scale_segments=nseg)     # a refresh step
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.cast_adams_step_multi(tl_graph, cfg)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for x, y in zip(eager, graphed):      # capturing runs nothing
+        assert host(x["w"]).tobytes() == host(y["w"]).tobytes()
+    for replay in range(3):
+        B.cast_adams_step_multi(tl_eager, cfg)
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (x, y) in enumerate(zip(eager, graphed)):
+            for k in ("w", "m", "v", "mask", "scale_grad"):
+                assert host(x[k]).tobytes() == host(y[k]).tobytes(), (replay, i, k)
+            if x["compute_copy"] is not None:
+                assert host(x["compute_copy"].view(torch.int16)).tobytes() == host(y["compute_copy"].view(torch.int16)).tobytes()
+        # eager work of the program's own between the replays
+        for x, y in zip(eager, graphed):
+            g = synth.grads_bf16(15, 0, replay + 1, *x["w"].shape).to(DEV) if x["w"].shape == shapes[0] else x["grad"]
+            x["grad"].copy_(g)
+            y["grad"].copy_(g)
+    assert float(eager[0]["w"].abs().sum()) > 0
