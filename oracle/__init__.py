@@ -18,17 +18,27 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cast_oracle.c")
-_LIB = os.path.join(_HERE, "liboracle.so")
+# CAST_ORACLE_LIB: load this library instead of building cast_oracle.c (the pins' own test uses it to
+# run them against deliberately broken builds of the oracle)
+_OVERRIDE = os.environ.get("CAST_ORACLE_LIB")
+_LIB = _OVERRIDE or os.path.join(_HERE, "liboracle.so")
 _lib = None
 
 
+def compile_source(src: str, out: str) -> None:
+    """gcc with the flags the oracle is defined under: no fast-math, no FMA contraction, so that every C
+    operation is one IEEE-754 operation of its declared type."""
+    cmd = ["gcc", "-std=c99", "-O2", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+           "-fno-fast-math", "-Wall", "-Wextra", "-o", out, src, "-lm"]
+    subprocess.run(cmd, check=True)
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle.  No fast-math, no FMA contraction: every C operation is one
-    IEEE-754 operation of its declared type."""
+    """Compile the oracle (unless CAST_ORACLE_LIB names a library to use instead)."""
+    if _OVERRIDE:
+        return _LIB
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-std=c99", "-O2", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
-        subprocess.run(cmd, check=True)
+        compile_source(_SRC, _LIB)
     return _LIB
 
 

@@ -89,6 +89,12 @@ def test_step_chain_rule_power_of_two_scale(oracle, arith):
         res.append((a, b, c, k))
     for x, y in zip(*res):
         assert (x.view(np.uint8) == y.view(np.uint8)).all()
+    # dL/dA of the scaled step is the sum over the incoming gradient times the raw weight (the function pinned
+    # by finite differences above), whatever A is: not times the scaled weight, not times the chained gradient
+    a, b, c, k = w.copy(), np.zeros_like(w), np.zeros_like(w), np.zeros(w.shape, np.uint8)
+    cfg = AdamsCfg(lambda_=1e-3, alpha=0.5, bias_corr1=0.1, bias_corr2=0.001, refresh_mask=1, scale_segments=n)
+    gA = oracle.adams_step(a, g, b, c, k, cfg, A=A, arithmetic=arith)
+    assert np.allclose(gA, oracle.weight_scale_grad(w, g, n), rtol=1e-14, atol=0)
 
 
 def test_mask_is_taken_from_unscaled_weights(oracle):

@@ -158,6 +158,20 @@ def test_kept_entries_receive_no_decay(oracle, arith):
 
 
 @pytest.mark.parametrize("arith", ["f64", "f32"])
+def test_exact_zero_masked_weight_stays_zero(oracle, arith):
+    # Sign(0) = 0 for both zeros: with no gradient and no momentum a masked zero receives no decay and stays
+    # put under full decay strength, while its nonzero neighbours move toward zero
+    w = np.array([[0.0, -0.0, 0.5, -0.5, 0.0, -0.0, 0.25, -0.25]], np.float32)
+    keep = np.array([[0, 0, 1, 1, 0, 0, 0, 0]], np.uint8)
+    a, mu, v = w.copy(), np.zeros_like(w), np.zeros_like(w)
+    cfg = AdamsCfg(lr=1e-2, lambda_=1e-3, alpha=1.0, bias_corr1=0.1, bias_corr2=0.001, refresh_mask=0)
+    oracle.adams_step(a, np.zeros_like(w), mu, v, keep, cfg, arithmetic=arith)
+    assert (a[0, [0, 1, 4, 5]] == 0.0).all() and (v[0, [0, 1, 4, 5]] == 0.0).all()
+    assert (a[0, 2:4] == w[0, 2:4]).all()                            # kept, no gradient: untouched
+    assert 0 < a[0, 6] < 0.25 and -0.25 < a[0, 7] < 0               # masked and nonzero: toward zero
+
+
+@pytest.mark.parametrize("arith", ["f64", "f32"])
 def test_alpha_zero_ignores_the_mask(oracle, arith):
     rng = np.random.default_rng(5)
     w, g, mu, v = _random_state(rng, 4, 32)
