@@ -293,7 +293,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         adams_entries4<(EXTRA == 2), (EXTRA == 1)>(w, g, mu, v, nib, off < len, a.s);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
         if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
-            const vu2_t h = {f32_to_bf16_rne(mu[0]) | (f32_to_bf16_rne(mu[1]) << 16), f32_to_bf16_rne(mu[2]) | (f32_to_bf16_rne(mu[3]) << 16)};
+            const vu2_t h = {f32x2_to_bf16_rne(mu[0], mu[1]), f32x2_to_bf16_rne(mu[2], mu[3])};
             __builtin_amdgcn_raw_buffer_store_b64(h, b.m, off * 2, 0, kAuxStore);
         } else {
             __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
@@ -302,8 +302,8 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         if constexpr (has_extras(EXTRA)) {
             if (c.emit) {      // the weights the next forward pass multiplies with: bf16(A * w_new), Eq. 12
                 vu2_t h;
-                h.x = f32_to_bf16_rne(c.copy_A * w[0]) | (f32_to_bf16_rne(c.copy_A * w[1]) << 16);
-                h.y = f32_to_bf16_rne(c.copy_A * w[2]) | (f32_to_bf16_rne(c.copy_A * w[3]) << 16);
+                h.x = f32x2_to_bf16_rne(c.copy_A * w[0], c.copy_A * w[1]);
+                h.y = f32x2_to_bf16_rne(c.copy_A * w[2], c.copy_A * w[3]);
                 __builtin_amdgcn_raw_buffer_store_b64(h, c.copy, off * 2, 0, kAuxStore);
             }
         }

@@ -285,6 +285,18 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x)
     return b >> 16;
 }
 
+// Two values at once with the hardware's packed conversion (round to nearest even; gfx950 has it):
+// lo -> bits 0..15, hi -> bits 16..31.  NaNs are made the canonical quiet NaN first, so that the
+// result is 0x7FC0 like the scalar form's whatever the conversion does with signs and payloads.
+__device__ __forceinline__ uint32_t f32x2_to_bf16_rne(float lo, float hi)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const float qnan = __uint_as_float(0x7fc00000u);
+    const f32x2 v = {lo != lo ? qnan : lo, hi != hi ? qnan : hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
 // ---- streaming accesses through buffer resources ------------------------------------------
 // Every byte of the optimizer state is touched once per step, so nothing is worth keeping in
 // the caches: loads and stores carry the non-temporal hint.  The vector kernels address each

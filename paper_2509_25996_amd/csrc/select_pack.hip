@@ -146,8 +146,8 @@ __global__ __launch_bounds__(kBlockThreads) void weight_scale_kernel(const float
         uint16_t *o = static_cast<uint16_t *>(out) + idx;
         if constexpr (W == 4) {
             uint2 q;
-            q.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
-            q.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
+            q.x = f32x2_to_bf16_rne(x[0], x[1]);
+            q.y = f32x2_to_bf16_rne(x[2], x[3]);
             *reinterpret_cast<uint2 *>(o) = q;
         } else {
             o[0] = (uint16_t)f32_to_bf16_rne(x[0]);
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
             }
             if (scale) { a = A * a; b = A * b; }
             if constexpr (BF16OUT) {
-                __builtin_amdgcn_raw_buffer_store_b32(f32_to_bf16_rne(a) | (f32_to_bf16_rne(b) << 16), rval, (off >> 1) * 2, 0, kAuxStore);
+                __builtin_amdgcn_raw_buffer_store_b32(f32x2_to_bf16_rne(a, b), rval, (off >> 1) * 2, 0, kAuxStore);
             } else {
                 const vu2_t pair = {__float_as_uint(a), __float_as_uint(b)};
                 __builtin_amdgcn_raw_buffer_store_b64(pair, rval, (off >> 1) * 4, 0, kAuxStore);
