@@ -427,10 +427,12 @@ static int device_compute_units()
     return cus;
 }
 
-// A list of matrices that share one configuration.  Matrices of equal (rows, cols, ld) form one
-// launch: a work queue (see adams_step_vec_queue) over all their shares, with their buffer
-// addresses in a table that is copied, together with zeroed ticket counters, to the workspace
-// first.  Shapes the vector kernels do not take are stepped one by one.
+// A list of matrices that share one configuration.  Default: one launch per matrix, small matrices
+// of one shape and one kernel flavour several to a launch, long row segments as split plans whose
+// pieces' sums (and the refresh statistics' partial sums) go through the workspace and are added up
+// by follow-up launches.  With CAST_FLAG_WORK_QUEUE, matrices of equal (rows, cols, ld) that the
+// queue can take form one launch of resident workgroups (see adams_step_vec_queue), their buffer
+// addresses in a table that is copied, together with zeroed ticket counters, to the workspace first.
 // With `tally` the call only counts the launches it would make (nothing is enqueued).
 cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast_adams_config *cfg,
                                     void *workspace, hipStream_t st, MultiTally *tally)
@@ -460,11 +462,12 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     std::vector<char> taken(count, 0);
     struct Group { int first, n; SpanPlan plan; int block_waves; unsigned blocks_per_matrix; };
     std::vector<Group> groups;
-    for (int i = 0; i < count; ++i) {
+    if (waves_per_cu <= 0) use_queue = false;
+    for (int i = 0; use_queue && i < count; ++i) {
         if (taken[i] || ts[i].rows == 0 || ts[i].cols == 0) continue;
         const bool wants_gA = scaled && ts[i].scale_grad != nullptr;
         SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments, wants_gA && layout.piece_floats > 0);
-        if (!p.vec || !use_queue || waves_per_cu <= 0) continue;
+        if (!p.vec) continue;
         if (p.geom.spans_per_row == 0) {      // flat: one chunk per span
             p.geom.span_len = kChunk;
             p.geom.num_spans = (p.geom.total + kChunk - 1) / kChunk;
