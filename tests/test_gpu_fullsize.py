@@ -122,3 +122,68 @@ def test_whole_125m_set_through_the_list_call():
         assert_same_bits(host(x["v"]), ref["v"], name + " v")
         g = synth.widen_bf16(synth.grads_bf16(21, i, steps - 1, r, c))
         assert np.abs(host(x["scale_grad"]) - ref["gA"]).max() <= 1e-5 * np.abs(ref["gA"]).max() + 1e-7
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_arrays_beyond_4_gib_sampled_rows(interleaved):
+    """One matrix whose fp32 arrays are 4.3 GB each (65544 x 16384; with row-interleaved state the offsets inside
+    the one allocation pass 2^32 entries): selection, the scaled step through both entry points and the pack,
+    checked on whole rows around every place where a byte or entry offset crosses 2^31 or 2^32, on the first
+    and last rows and on random ones."""
+    rows, cols, n = 65536 + 8, 16384, 2
+    w0 = synth.device_gaussian((rows, cols), 0.02, torch.float32, 41, DEV)
+    g = synth.device_gaussian((rows, cols), 1e-3, torch.bfloat16, 42, DEV)
+    if interleaved:
+        w, m, v = B.interleaved_state(w0)
+        del w0
+    else:
+        w, m, v = w0, torch.zeros_like(w0), torch.zeros_like(w0)
+    ld = w.stride(0)
+    crossing = []
+    for limit in (1 << 31, 1 << 32):
+        for unit in (4 * ld, 2 * cols, ld, cols):      # bytes of a state row, bytes of a gradient row, entries of either
+            r = limit // unit
+            crossing += [r - 1, r, r + 1]
+    rng = np.random.default_rng(7)
+    pick = np.unique(np.clip(np.concatenate([[0, 1, rows - 2, rows - 1], crossing, rng.integers(0, rows, 12)]), 0, rows - 1))
+    idx = torch.from_numpy(pick).to(DEV)
+    mask = B.alloc_mask(rows, cols, DEV)
+    A = (1 + 0.05 * torch.randn((rows, n), device=DEV, generator=torch.Generator(DEV).manual_seed(5))).contiguous()
+    gA = torch.zeros((rows, n), device=DEV)
+    ow, og, oA = host(w[idx]).copy(), host(g[idx].float()).copy(), host(A[idx]).copy()
+    om, ov = np.zeros_like(ow), np.zeros_like(ow)
+    keep = np.zeros(ow.shape, np.uint8)
+    # selection alone
+    B.cast_nm_select(w, 2, 4, mask)
+    torch.cuda.synchronize()
+    assert (words(mask[idx]) == oracle.pack_mask_bits(oracle.nm_select(ow, 2, 4))).all()
+    mask.zero_()
+    # three steps: list call (split plan), single call, list call
+    tl = B.TensorList([dict(w=w, grad=g, m=m, v=v, mask=mask, scale=A, scale_grad=gA)], DEV)
+    for t in range(3):
+        cfg = B.iteration_config(t, 7500, mask_period=2, lr=2e-5, lambda_=4e-7, scale_segments=n)
+        cfg.alpha = 0.25 + 0.25 * t
+        if t == 1:
+            B.cast_adams_step(w, g, m, v, mask, cfg, scale=A, scale_grad=gA)
+        else:
+            B.cast_adams_step_multi(tl, cfg)
+        ref_gA = oracle.adams_step(ow, og, om, ov, keep, oracle_cfg(cfg), A=oA, arithmetic="f32", nthreads=8)
+    torch.cuda.synchronize()
+    assert (words(mask[idx]) == oracle.pack_mask_bits(keep)).all()
+    assert_same_bits(host(w[idx]), ow, "w")
+    assert_same_bits(host(m[idx]), om, "mu")
+    assert_same_bits(host(v[idx]), ov, "v")
+    terms = np.abs(og.astype(np.float64) * host(w[idx])).reshape(len(pick), n, -1).sum(-1)
+    assert (np.abs(host(gA[idx]) - ref_gA) <= 2e-5 * terms + 1e-12).all()
+    # every mask word of the matrix has 16 of its 32 bits set (2:4)
+    lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.uint8, device=DEV)
+    assert int(lut[mask.view(torch.uint8).long()].sum(dtype=torch.int64)) == rows * cols // 2
+    # hard projection + fold + pack with the stored mask
+    _, vbytes, mbytes = B.cast_sizes(rows, cols, 2, 4, B.CAST_F32)
+    values = torch.empty((rows, cols // 2), device=DEV)
+    meta = torch.empty((rows, mbytes // 4 // rows), dtype=torch.int32, device=DEV)
+    B.cast_nm_project_compress(w, 2, 4, values, meta, scale=A, mask_bits=mask)
+    torch.cuda.synchronize()
+    ref_v, ref_m = oracle.project_compress(ow, 2, 4, A=oA, keep=keep)
+    assert (words(meta[idx]) == ref_m).all()
+    assert_same_bits(host(values[idx]), ref_v, "values")
