@@ -55,7 +55,9 @@ enum {
 
 enum { CAST_F32 = 0, CAST_BF16 = 1 };
 
-/* Test-only: second moment from g^2 instead of mu~^2 (Eq. 9's form; not the paper's method). */
+/* Second moment from g^2 instead of mu~^2 (Eq. 9's form; not the paper's method).  With alpha = 0
+ * this makes the step textbook Adam: what the tests pin against a library optimizer, and a way to
+ * step dense parameters such as the scale factors A of Eq. 12 with this library. */
 #define CAST_FLAG_V_FROM_GRAD 1u
 /* cast_adams_step_multi only (ignored elsewhere): step matrices of equal shape with one launch of
  * resident workgroups that draw their work in order from a ticket counter, instead of one launch

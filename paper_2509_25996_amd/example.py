@@ -7,7 +7,8 @@ mask, the fold of the scale factors and packing (Algorithm 1's last lines, Eq. 1
 
 Gradients are random draws, not a loss: the point is the calling sequence, and that under the ramp the
 masked weights are driven to zero (Sec. 4.1, appendix "Mask Learning"), which the numbers it prints show.
-The scale factors stay at one here; a trainer would update them from scale_grad with its own optimizer.
+The scale factors are stepped from scale_grad by a plain Adam, itself a call into the library (DenseAdam below):
+the paper leaves their optimizer open.
 """
 from __future__ import annotations
 
@@ -15,6 +16,25 @@ import torch
 
 from . import binding as B
 from . import synth
+
+
+class DenseAdam:
+    """Textbook Adam on a dense fp32 [rows, cols] tensor (cols even) as a special case of the library's step:
+    alpha = 0 switches the decay off (the mask is then ignored), CAST_FLAG_V_FROM_GRAD feeds the second moment
+    with g^2, and the N:M pattern is a formality (1:2).  Meant for the scale factors A of Eq. 12."""
+
+    def __init__(self, p: torch.Tensor, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8):
+        self.p, self.lr, self.beta1, self.beta2, self.eps = p, lr, beta1, beta2, eps
+        self.m, self.v = torch.zeros_like(p), torch.zeros_like(p)
+        self.mask = B.alloc_mask(p.shape[0], p.shape[1], p.device)      # read, never used: alpha = 0
+        self.t = 0
+
+    def step(self, grad: torch.Tensor, lr=None):
+        self.t += 1
+        cfg = B.AdamsConfig(n_keep=1, m_group=2, lr=self.lr if lr is None else lr, beta1=self.beta1, beta2=self.beta2,
+                            eps=self.eps, lambda_=0.0, alpha=0.0, bias_corr1=1.0 - self.beta1 ** self.t,
+                            bias_corr2=1.0 - self.beta2 ** self.t, refresh_mask=0, flags=B.FLAG_V_FROM_GRAD)
+        B.cast_adams_step(self.p, grad, self.m, self.v, self.mask, cfg)
 
 
 def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10, lr=1e-3, lam=1e-3, n_keep=2, m_group=4,
@@ -32,6 +52,7 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
                           scale=torch.ones((r, segments), device=device), scale_grad=torch.zeros((r, segments), device=device),
                           initial_mask=initial, refresh_stats=stats[-1]))
     tensors = B.TensorList(items, device)
+    scale_optimizers = [DenseAdam(x["scale"], lr=1e-4) for x in items]
     total = sum(r * c for r, c in shapes)
     history = []
     gen = torch.Generator(device=device).manual_seed(0)
@@ -41,6 +62,8 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
         cfg = B.iteration_config(t, steps, mask_period=mask_period, lr=lr, lambda_=lam, n_keep=n_keep, m_group=m_group,
                                  scale_segments=segments)
         B.cast_adams_step_multi(tensors, cfg)
+        for opt, x in zip(scale_optimizers, items):                   # A <- Adam(A, dL/dA); the step above used the old A
+            opt.step(x["scale_grad"])
         if cfg.refresh_mask:
             s = [B.read_refresh_stats(x) for x in stats]
             flip_rate = sum(x["flips_prev"] for x in s) / total       # r_t

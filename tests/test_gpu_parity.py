@@ -816,3 +816,29 @@ def test_list_call_captured_in_a_graph_replays_like_eager_calls():
             x["grad"].copy_(g)
             y["grad"].copy_(g)
     assert float(eager[0]["w"].abs().sum()) > 0
+
+
+def test_dense_adam_of_the_example_is_library_adam():
+    """The scale factors' optimizer of the example (the library's step with alpha = 0 and the second moment from
+    g^2) against torch.optim.Adam in double, and bit for bit against the oracle's textbook form."""
+    from paper_2509_25996_amd.example import DenseAdam
+    rows, n, steps, lr = 300, 2, 25, 1e-3
+    rng = np.random.default_rng(12)
+    a0 = (1 + 0.1 * rng.standard_normal((rows, n))).astype(np.float32)
+    grads = [(rng.standard_normal((rows, n)) * 1e-2).astype(np.float32) for _ in range(steps)]
+    p = dev(a0)
+    opt = DenseAdam(p, lr=lr)
+    ref = torch.nn.Parameter(torch.from_numpy(a0.astype(np.float64)))
+    lib = torch.optim.Adam([ref], lr=lr, betas=(0.9, 0.999), eps=1e-8)
+    o = OracleState(a0, "f32")
+    o.keep[:] = 1
+    for t, g in enumerate(grads, 1):
+        opt.step(dev(g))
+        ref.grad = torch.from_numpy(g.astype(np.float64))
+        lib.step()
+        cfg = oracle.AdamsCfg(n_keep=1, m_group=2, lr=lr, lambda_=0.0, alpha=0.0, bias_corr1=1 - 0.9 ** t, bias_corr2=1 - 0.999 ** t,
+                              refresh_mask=0, v_from_grad=1)
+        o.step(g, cfg)
+    torch.cuda.synchronize()
+    assert_same_bits(host(p), o.w, "A")
+    assert np.abs(host(p) - ref.detach().numpy()).max() <= 1e-6
