@@ -187,3 +187,53 @@ def test_arrays_beyond_4_gib_sampled_rows(interleaved):
     ref_v, ref_m = oracle.project_compress(ow, 2, 4, A=oA, keep=keep)
     assert (words(meta[idx]) == ref_m).all()
     assert_same_bits(host(values[idx]), ref_v, "values")
+
+
+def test_whole_125m_set_100_steps_of_the_ramp_then_pack():
+    """The 125M-class workload as a whole: all 84 linear weights, fp32 master weights, bf16 gradients, 100 AdamS
+    2:4 steps through the list call with the decay ramped linearly from 0, masks refreshed every 10 steps, weight
+    scaling n = 2, then hard projection + fold + pack; every tensor against the oracle, bit for bit.  Gradients are
+    drawn on the GPU from a seeded generator, one flat buffer per step, and handed to both sides."""
+    shapes = synth.weight_set("opt125m")
+    n, steps, lam = 2, 100, 1e-3      # lambda of the gradients' order, so that masks flip within 100 steps
+    total = synth.set_params(shapes)
+    gflat = torch.zeros(total, dtype=torch.bfloat16, device=DEV)
+    items, refs, at = [], [], 0
+    for i, (_, r, c) in enumerate(shapes):
+        w0 = synth.weights(22, i, r, c)
+        w, m, v = B.interleaved_state(torch.from_numpy(w0).to(DEV))
+        A = (1 + 0.05 * np.random.default_rng(100 + i).standard_normal((r, n))).astype(np.float32)
+        items.append(dict(w=w, m=m, v=v, mask=B.alloc_mask(r, c, DEV), grad=gflat[at:at + r * c].view(r, c),
+                          scale=torch.from_numpy(A).to(DEV), scale_grad=torch.zeros((r, n), device=DEV)))
+        refs.append(dict(w=w0.copy(), m=np.zeros_like(w0), v=np.zeros_like(w0), keep=np.zeros(w0.shape, np.uint8), A=A, at=at))
+        at += r * c
+    tl = B.TensorList(items, DEV)
+    gen = torch.Generator(device=DEV).manual_seed(2024)
+    first_keep = None
+    for t in range(steps):
+        gflat.copy_(torch.randn(total, device=DEV, generator=gen) * 1e-3)
+        ghost = gflat.float().cpu().numpy()
+        cfg = B.iteration_config(t, steps, mask_period=10, lr=1e-4, lambda_=lam, scale_segments=n)
+        B.cast_adams_step_multi(tl, cfg)
+        for (_, r, c), ref in zip(shapes, refs):
+            oracle.adams_step(ref["w"], ghost[ref["at"]:ref["at"] + r * c].reshape(r, c), ref["m"], ref["v"], ref["keep"],
+                              oracle_cfg(cfg), A=ref["A"], want_gA=False, arithmetic="f32", nthreads=16)
+        if t == 0:
+            first_keep = [ref["keep"].copy() for ref in refs]
+    torch.cuda.synchronize()
+    flipped = 0
+    for i, (name, r, c) in enumerate(shapes):
+        x, ref = items[i], refs[i]
+        assert (words(x["mask"]) == oracle.pack_mask_bits(ref["keep"])).all(), name
+        assert_same_bits(host(x["w"]), ref["w"], name + " w")
+        assert_same_bits(host(x["m"]), ref["m"], name + " mu")
+        assert_same_bits(host(x["v"]), ref["v"], name + " v")
+        flipped += int((ref["keep"] != first_keep[i]).sum())
+        _, _, mbytes = B.cast_sizes(r, c, 2, 4, B.CAST_F32)
+        values = torch.empty((r, c // 2), device=DEV)
+        meta = torch.empty((r, mbytes // 4 // r), dtype=torch.int32, device=DEV)
+        B.cast_nm_project_compress(x["w"], 2, 4, values, meta, scale=x["scale"], mask_bits=x["mask"])
+        ref_v, ref_m = oracle.project_compress(ref["w"], 2, 4, A=ref["A"], keep=ref["keep"])
+        assert (words(meta) == ref_m).all(), name
+        assert_same_bits(host(values), ref_v, name + " values")
+    assert flipped > 0
