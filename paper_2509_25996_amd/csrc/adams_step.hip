@@ -456,8 +456,11 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     static const int queue_block_waves = env_int("CAST_QUEUE_BLOCK_WAVES", 8);
     const MultiLayout layout = multi_layout(ts, count, cfg);
     PieceJobQueue jobs;
-    PieceArea area{reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes),
-                   layout.piece_floats, &jobs};
+    // the workspace: table of buffer sets, ticket counters, piece sums, statistics slots (a dry run has none)
+    float *const piece_base = workspace ? reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes)
+                                        : nullptr;
+    StatsPartial *const stats_base = workspace ? reinterpret_cast<StatsPartial *>(piece_base + layout.piece_floats) : nullptr;
+    PieceArea area{piece_base, layout.piece_floats, &jobs};
     std::vector<int> order;           // indices of vector-path matrices, grouped by shape
     std::vector<char> taken(count, 0);
     struct Group { int first, n; SpanPlan plan; int block_waves; unsigned blocks_per_matrix; };
@@ -547,7 +550,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         }
     }
     StatsJobQueue stats_jobs;
-    StatsArea stats_area{reinterpret_cast<StatsPartial *>(area.base + layout.piece_floats), layout.stats_slots, &stats_jobs};
+    StatsArea stats_area{stats_base, layout.stats_slots, &stats_jobs};
     // Small matrices of one shape and one kernel flavour share a launch (they need not follow each
     // other in the list: the matrices are independent).  A launch is kept below about 72 M entries: q, k, v, o of a
     // LLaMA2-7B layer go together, 16 of the 768 x 768 matrices of a 125M model; longer launches
