@@ -308,7 +308,9 @@ cast_status cast_debug_div_by_uniform(const float *x, float y, float *out, int64
 
 /*
  * Diagnostic, runs on the HOST: how the step kernels would cover a [rows, cols] matrix with row
- * stride ld and n_segments scaling segments (allow_split as in a list call with a workspace), and
+ * stride ld and n_segments scaling segments (allow_split = 1: as in a list call with a workspace;
+ * allow_split = 2 or 3 with n_segments = 0: the plan of the selection and pack kernels instead, with
+ * spans starting on multiples of 32 or 64 columns; other values: CAST_ERR_SHAPE), and
  * where wavefront `wave` of workgroup `block` would work, computed by the very functions the
  * kernels use.  It exists so that "every entry is covered exactly once and nothing outside the
  * matrix is touched" can be tested for any shape without a GPU.

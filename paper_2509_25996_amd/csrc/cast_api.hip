@@ -275,7 +275,11 @@ cast_status cast_debug_plan(int64_t rows, int64_t cols, int64_t ld, int n_segmen
     if (!plan || !span) return CAST_ERR_NULL;
     if (rows <= 0 || cols <= 0 || ld < cols || n_segments < 0 || block < 0 || wave < 0) return CAST_ERR_SHAPE;
     if (n_segments > 0 && cols % n_segments) return CAST_ERR_SHAPE;
-    const SpanPlan p = plan_spans(rows, cols, ld, n_segments, allow_split != 0);
+    // allow_split: 0, 1 = the step kernels' plan without / with split plans; 2, 3 = the plan of the selection and
+    // pack kernels with spans starting on 32 / 64 columns
+    if (allow_split < 0 || allow_split > 3 || (allow_split >= 2 && n_segments != 0)) return CAST_ERR_SHAPE;
+    const SpanPlan p = allow_split >= 2 ? plan_batched(rows, cols, ld, allow_split == 2 ? 32 : 64)
+                                        : plan_spans(rows, cols, ld, n_segments, allow_split != 0);
     const int block_waves = p.block_threads / kWave;
     plan[0] = p.vec ? 1 : 0;
     plan[1] = p.grid;

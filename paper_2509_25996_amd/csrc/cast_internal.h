@@ -23,6 +23,8 @@ struct SpanPlan {
 // allow_split: row segments of more than 16 chunks of 256 entries may be cut into pieces with a
 // workgroup each; the caller then supplies a PieceArea for the pieces' dL/dA sums.
 SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool allow_split = false);
+// the plan of the selection and pack kernels (up to four chunks of a span per wavefront, requested together)
+SpanPlan plan_batched(int64_t rows, int64_t cols, int64_t ld, int align);
 
 // Device memory for the piece sums of split plans: what is left of it, and who collects the
 // second halves (adding the pieces up) of the matrices that took a part.

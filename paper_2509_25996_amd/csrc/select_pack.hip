@@ -22,7 +22,7 @@ __device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
 // `align` columns, and as many wavefronts share a piece as it has kBatch chunks (a power of two).
 constexpr int kBatch = 4;
 
-static SpanPlan plan_batched(int64_t rows, int64_t cols, int64_t ld, int align)
+SpanPlan plan_batched(int64_t rows, int64_t cols, int64_t ld, int align)
 {
     int per_row = 0;
     if (ld != cols)

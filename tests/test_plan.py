@@ -55,10 +55,13 @@ SMALL = [(1, 32), (3, 64), (2, 256), (5, 512), (4, 1024), (3, 1280 + 64), (2, 25
 @pytest.mark.parametrize("rows,cols", SMALL)
 @pytest.mark.parametrize("nseg", [0, 1, 2])
 @pytest.mark.parametrize("interleaved", [False, True])
-@pytest.mark.parametrize("split", [False, True])
+@pytest.mark.parametrize("split", [False, True, 2, 3])
 def test_every_entry_is_covered_exactly_once(lib, rows, cols, nseg, interleaved, split):
+    # split = 2, 3: the plan of the selection and pack kernels (spans on multiples of 32 / 64 columns)
     if nseg and (cols % nseg or (cols // nseg) % 4):
         pytest.skip("segments must be whole groups")
+    if split in (2, 3) and nseg:
+        pytest.skip("the selection and pack kernels have no scaling segments in their plan")
     ld = 3 * cols if interleaved else cols
     plan, _ = _plan(lib, rows, cols, ld, nseg, split)
     vec, grid, block_waves, P, pieces = plan
@@ -66,7 +69,9 @@ def test_every_entry_is_covered_exactly_once(lib, rows, cols, nseg, interleaved,
         assert not vec
     if not vec:
         return
-    assert pieces == 1 or (split and nseg)
+    assert pieces == 1 or (split is True and nseg)
+    if split == 3 and cols % 64 == 0:
+        assert all(_plan(lib, rows, cols, ld, nseg, split, b, 0)[1][1] % 64 == 0 for b in range(grid))
     covered = np.zeros(rows * cols, np.int32)
     seen_spans = {}
     for block in range(grid):
@@ -89,7 +94,8 @@ def test_every_entry_is_covered_exactly_once(lib, rows, cols, nseg, interleaved,
 
 @pytest.mark.parametrize("rows,cols", [(4096, 4096), (11008, 4096), (4096, 11008), (5120, 5120), (13824, 5120), (5120, 13824),
                                        (768, 768), (3072, 768), (768, 3072), (4096, 14336), (28672, 8192), (8192, 28672)])
-@pytest.mark.parametrize("nseg,interleaved,split", [(2, True, True), (2, False, False), (0, True, False), (0, False, False)])
+@pytest.mark.parametrize("nseg,interleaved,split", [(2, True, True), (2, False, False), (0, True, False), (0, False, False),
+                                                    (0, True, 2), (0, False, 2), (0, True, 3)])
 def test_benchmark_shapes_stay_in_bounds(lib, rows, cols, nseg, interleaved, split):
     ld = 3 * cols if interleaved else cols
     plan, _ = _plan(lib, rows, cols, ld, nseg, split)
