@@ -195,6 +195,18 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
         hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), block, 0, st, a, q);
         return;
     }
+    if constexpr (REFRESH) {      // refresh statistics without a compute copy: a flavour of the refresh kernels only
+        if (l.extra == kStatsOnly) {
+            if constexpr (SCALED) {
+                if (l.split) {
+                    hipLaunchKernelGGL((adams_step_vec<M, BF16, true, true, true, kStatsOnly>), grid, block, 0, st, a);
+                    return;
+                }
+            }
+            hipLaunchKernelGGL((adams_step_vec<M, BF16, true, SCALED, false, kStatsOnly>), grid, block, 0, st, a);
+            return;
+        }
+    }
     if constexpr (SCALED) {
         if (l.split) {
             if (l.extra == kMuBf16) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, kMuBf16>), grid, block, 0, st, a);
@@ -310,7 +322,7 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     // (a first moment kept in bf16 comes with none of the above: the API has seen to that)
     const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
-    const int extra = mu16 ? kMuBf16 : (own_rule ? 2 : ((x.compute_copy != nullptr || stats) ? 1 : 0));
+    const int extra = mu16 ? kMuBf16 : (own_rule ? 2 : (x.compute_copy != nullptr ? 1 : (stats ? kStatsOnly : 0)));
     p.geom.m_row_gap = mu_bf16_ld(cols, ld) - cols;
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
@@ -354,10 +366,10 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 
 // Up to kMaxFused matrices of one shape in one launch (no split plan, no comparison rule with code of
 // its own): the ramp-up and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a
-// 4096 x 4096 matrix takes.  `extra`: the matrices have compute copies to write or refresh
-// statistics to gather (the flavour that can do both), each its own or none.
+// 4096 x 4096 matrix takes.  `flavour`: 0 plain; 1: the matrices have compute copies to write (and
+// may gather refresh statistics); 4: refresh statistics only; each matrix its own buffers.
 static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
-                                           bool extra, StatsArea *stats_area, hipStream_t st)
+                                           int flavour, StatsArea *stats_area, hipStream_t st)
 {
     SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
     const bool refresh = cfg->refresh_mask != 0;
@@ -366,16 +378,16 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
     for (int k = 0; k < n; ++k) {
         const cast_tensor &t = *ts[k];
         StatsPartial *partials = nullptr;
-        if (extra && refresh && t.refresh_stats) {
+        if (flavour != 0 && refresh && t.refresh_stats) {
             if (stats_area == nullptr || p.grid > stats_area->slots) return CAST_ERR_SHAPE;      // (not reachable through the API)
             partials = take_stats_slots(stats_area, p.grid, t.refresh_stats, t.initial_mask_bits);
         }
         a.set[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, nullptr, partials,
                               partials ? t.initial_mask_bits : nullptr,
-                              extra ? static_cast<uint16_t *>(t.compute_copy) : nullptr, extra ? t.copy_scale : nullptr};
+                              flavour == 1 ? static_cast<uint16_t *>(t.compute_copy) : nullptr, flavour == 1 ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? kMuBf16 : (extra ? 1 : 0)}, a, st);
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? kMuBf16 : flavour}, a, st);
     return launch_status();
 }
 
@@ -570,7 +582,9 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         }
         return stats_jobs.count + n > kMaxStatsJobs ? stats_jobs.flush(st) : CAST_OK;
     };
-    auto needs_extra = [&](const cast_tensor &t) { return t.compute_copy != nullptr || (want_stats && t.refresh_stats != nullptr); };
+    auto flavour_of = [&](const cast_tensor &t) {      // of the kernels a matrix needs (comparison rules aside)
+        return t.compute_copy != nullptr ? 1 : ((want_stats && t.refresh_stats != nullptr) ? kStatsOnly : 0);
+    };
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
@@ -579,12 +593,12 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
             int most = (int)(fuse_launch_params / (t.rows * t.cols));
             if (most > fuse_limit) most = fuse_limit;
             if (most > kMaxFused) most = kMaxFused;
-            const bool extra = needs_extra(t);
+            const int flavour = flavour_of(t);
             const cast_tensor *same[kMaxFused] = {&t};
             int where[kMaxFused] = {i};
             int n = 1, n_stats = with_stats ? 1 : 0;
             for (int j = i + 1; j < count && n < most; ++j)
-                if (!taken[j] && needs_extra(ts[j]) == extra && ts[j].rows == t.rows && ts[j].cols == t.cols && ts[j].ld == t.ld &&
+                if (!taken[j] && flavour_of(ts[j]) == flavour && ts[j].rows == t.rows && ts[j].cols == t.cols && ts[j].ld == t.ld &&
                     (ts[j].scale_grad == nullptr) == (t.scale_grad == nullptr)) {
                     same[n] = &ts[j];
                     where[n] = j;
@@ -599,7 +613,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
                         ++tally->step_launches;
                         dry_stats += n_stats;
                     } else {
-                        const cast_status rc = launch_adams_step_fused(same, n, p, cfg, extra, layout.stats_slots ? &stats_area : nullptr, st);
+                        const cast_status rc = launch_adams_step_fused(same, n, p, cfg, flavour, layout.stats_slots ? &stats_area : nullptr, st);
                         if (rc != CAST_OK) return rc;
                     }
                     for (int k = 0; k < n; ++k) taken[where[k]] = 1;

@@ -63,9 +63,12 @@ static ConstTable as_const_table(const void *device_ptr)
 
 // Kernel flavours (template argument EXTRA): 0 plain; 1 can also write the bf16 compute copy and
 // gather refresh statistics; 2 knows, on top, the comparison update rules with code of their own;
-// 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16).
-constexpr bool has_extras(int extra) { return extra == 1 || extra == 2; }
+// 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16); 4 plain that can gather refresh
+// statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0).
+constexpr bool can_emit(int extra) { return extra == 1 || extra == 2; }
+constexpr bool can_count(int extra) { return extra == 1 || extra == 2 || extra == 4; }
 constexpr int kMuBf16 = 3;
+constexpr int kStatsOnly = 4;
 
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
 template <bool BF16>
@@ -199,11 +202,13 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     }
     c.emit = false;
     c.copy_A = 1.0f;
-    if constexpr (has_extras(EXTRA)) {
+    if constexpr (can_emit(EXTRA)) {
         c.emit = t.compute_copy != nullptr;
         // without a copy the resource is empty: every store through it would be void anyway
         c.copy = span_resource(t.compute_copy + (c.emit ? o.dense_begin : 0), c.emit ? c.len * 2 : 0);
         if (c.emit && t.copy_scale && c.len > 0) c.copy_A = t.copy_scale[c.segment];
+    }
+    if constexpr (can_count(EXTRA)) {
         c.stats_slot = t.stats_partials ? t.stats_partials + block : nullptr;
         const bool initial = t.stats_partials && t.initial_mask;
         c.b.initial_mask = span_resource(t.initial_mask + (initial ? (o.dense_begin >> 5) : 0), initial ? c.len / 8 : 0);
@@ -231,7 +236,7 @@ template <int M, bool BF16, bool REFRESH, bool SCALED, int EXTRA = 0>
 __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Chunk<BF16> cur, int lane, int wave,
                                          float *partial, StatsShared *stats_shared = nullptr)
 {
-    constexpr bool kStats = REFRESH && has_extras(EXTRA);      // refresh statistics are gathered if c.stats_slot says so
+    constexpr bool kStats = REFRESH && can_count(EXTRA);      // refresh statistics are gathered if c.stats_slot says so
     constexpr bool kMu16 = EXTRA == kMuBf16;
     uint32_t flips_prev = 0, flips_init = 0;
     float l1_kept = 0.0f, l1_all = 0.0f;
@@ -245,7 +250,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
     int off = first_offset(c, lane);      // this lane's first entry, relative to the span
     for (int base = c.sub * kChunk; base < len; base += stride) {
         Chunk<BF16> nxt;
-        chunk_load<BF16, (!REFRESH || has_extras(EXTRA)), kStats, kMu16>(nxt, b, off + stride);     // past the end: all zeros, never used
+        chunk_load<BF16, (!REFRESH || can_count(EXTRA)), kStats, kMu16>(nxt, b, off + stride);     // past the end: all zeros, never used
 
         float w[4], g[4], mu[4], v[4];
         unpack4(cur.w, w);
@@ -264,12 +269,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         if constexpr (REFRESH) {
             nib = keep_nibble<M>(w, a.s.n_keep, lane);                   // from the incoming weights
             if constexpr (kStats) {
-                if (c.stats_slot) {      // appendix "Mask Learning": flips against the stored and the initial mask, L1 norms
-                    const uint32_t shift = off & 31;
-                    if (off < len) {     // (lanes past the end hold zeros, of which the first N of a group count as kept)
-                        flips_prev += __popc((nib ^ (cur.word >> shift)) & 0xFu);
-                        flips_init += __popc((nib ^ (cur.initial >> shift)) & 0xFu);
-                    }
+                if (c.stats_slot) {      // appendix "Mask Learning": L1 norms here, flips below where the new word is whole
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
                         const float mag = __builtin_fabsf(w[j]);
@@ -280,6 +280,14 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
             }
             const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
             if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, b.mask, (off >> 5) * 4, 0, kAuxStore);
+            if constexpr (kStats) {
+                // spans are whole mask words, so the first lane of a word inside the span sees all 32 of its entries
+                // (lanes past the end hold zeros, of which the first N of a group would count as kept)
+                if (c.stats_slot && (lane & 7) == 0 && off < len) {
+                    flips_prev += __popc(word ^ cur.word);
+                    flips_init += __popc(word ^ cur.initial);
+                }
+            }
         } else {
             nib = (cur.word >> (off & 31)) & 0xFu;
         }
@@ -299,7 +307,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
             __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
         }
         __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
-        if constexpr (has_extras(EXTRA)) {
+        if constexpr (can_emit(EXTRA)) {
             if (c.emit) {      // the weights the next forward pass multiplies with: bf16(A * w_new), Eq. 12
                 vu2_t h;
                 h.x = f32x2_to_bf16_rne(c.copy_A * w[0], c.copy_A * w[1]);
@@ -377,8 +385,8 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     SpanCtx c;
     span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
     Chunk<BF16> first;
-    chunk_load<BF16, (!REFRESH || has_extras(EXTRA)), (REFRESH && has_extras(EXTRA)), EXTRA == kMuBf16>(first, c.b, first_offset(c, lane));
-    if constexpr (REFRESH && has_extras(EXTRA)) {
+    chunk_load<BF16, (!REFRESH || can_count(EXTRA)), (REFRESH && can_count(EXTRA)), EXTRA == kMuBf16>(first, c.b, first_offset(c, lane));
+    if constexpr (REFRESH && can_count(EXTRA)) {
         __shared__ StatsShared stats_shared;
         span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial, &stats_shared);
     } else {
