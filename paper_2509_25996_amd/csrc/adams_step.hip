@@ -364,10 +364,10 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     return launch_status();
 }
 
-// Up to kMaxFused matrices of one shape in one launch (no split plan, no comparison rule with code of
-// its own): the ramp-up and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a
+// Up to kMaxFused matrices of one shape in one launch (no split plan): the ramp-up and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a
 // 4096 x 4096 matrix takes.  `flavour`: 0 plain; 1: the matrices have compute copies to write (and
-// may gather refresh statistics); 4: refresh statistics only; each matrix its own buffers.
+// may gather refresh statistics); 2: a comparison rule, with or without either; 4: refresh statistics
+// only; each matrix its own buffers.
 static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
                                            int flavour, StatsArea *stats_area, hipStream_t st)
 {
@@ -384,7 +384,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
         }
         a.set[k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, nullptr, partials,
                               partials ? t.initial_mask_bits : nullptr,
-                              flavour == 1 ? static_cast<uint16_t *>(t.compute_copy) : nullptr, flavour == 1 ? t.copy_scale : nullptr};
+                              can_emit(flavour) ? static_cast<uint16_t *>(t.compute_copy) : nullptr, can_emit(flavour) ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
                    VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? kMuBf16 : flavour}, a, st);
@@ -582,14 +582,15 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         }
         return stats_jobs.count + n > kMaxStatsJobs ? stats_jobs.flush(st) : CAST_OK;
     };
-    auto flavour_of = [&](const cast_tensor &t) {      // of the kernels a matrix needs (comparison rules aside)
+    auto flavour_of = [&](const cast_tensor &t) {      // of the kernels a matrix needs
+        if (own_rule) return 2;
         return t.compute_copy != nullptr ? 1 : ((want_stats && t.refresh_stats != nullptr) ? kStatsOnly : 0);
     };
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
         const cast_tensor &t = ts[i];
         const bool with_stats = want_stats && t.refresh_stats != nullptr;
-        if (!own_rule && fuse_limit > 1 && t.rows > 0 && t.cols > 0 && t.rows * t.cols <= fuse_max_params) {
+        if (fuse_limit > 1 && t.rows > 0 && t.cols > 0 && t.rows * t.cols <= fuse_max_params) {
             int most = (int)(fuse_launch_params / (t.rows * t.cols));
             if (most > fuse_limit) most = fuse_limit;
             if (most > kMaxFused) most = kMaxFused;

@@ -181,7 +181,7 @@ def test_list_call_launch_tally(lib):
     assert (step.value, other.value) == (4, 2)          # the sum of down's pieces, the sums of the statistics
     cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, rule=B.RULE_ADAM_L1).c_struct()
     assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), None) == 0
-    assert step.value == 7                              # comparison rules: one launch per matrix
+    assert step.value == 4                              # comparison rules share launches like the others
     bad = (T * 1)(T(a, a, a, a, a, a, a, 4, 66, 66))
     assert lib.cast_adams_multi_launches(bad, 1, C.byref(cfg), C.byref(step), C.byref(other)) == -2
 
