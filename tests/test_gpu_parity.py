@@ -842,3 +842,44 @@ def test_dense_adam_of_the_example_is_library_adam():
     torch.cuda.synchronize()
     assert_same_bits(host(p), o.w, "A")
     assert np.abs(host(p) - ref.detach().numpy()).max() <= 1e-6
+
+
+def test_two_streams_with_their_own_lists_and_workspaces():
+    """The library keeps no state between calls: two lists with their own workspaces stepped on two streams at the
+    same time come out as when they are stepped one after the other (split plans, statistics and compute copies
+    included, i.e. everything that goes through a workspace)."""
+    shapes = [(64, 512)] * 3 + [(16, 11008)] * 2 + [(7, 72), (48, 4096)]
+    nseg, steps = 2, 4
+
+    def make(seed):
+        rng = np.random.default_rng(seed)
+        items = []
+        for i, (r, c) in enumerate(shapes):
+            st = GpuState(synth.weights(seed, i, r, c), nseg, interleaved=c % 8 == 0)
+            items.append(dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=synth.grads_bf16(seed, i, 0, r, c).to(DEV),
+                              scale=dev((1 + 0.1 * rng.standard_normal((r, nseg))).astype(np.float32)), scale_grad=st.scale_grad,
+                              refresh_stats=B.alloc_refresh_stats(DEV) if i % 2 == 0 else None,
+                              compute_copy=torch.zeros((r, c), dtype=torch.bfloat16, device=DEV) if i % 3 == 0 else None))
+        return items
+
+    def run(concurrent):
+        lists = [make(16), make(17)]
+        tls = [B.TensorList(x, DEV) for x in lists]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()] if concurrent else [torch.cuda.current_stream()] * 2
+        torch.cuda.synchronize()
+        for t in range(steps):
+            cfg = B.iteration_config(t, steps, mask_period=2, lr=1e-3, lambda_=1e-3, scale_segments=nseg)
+            for tl, s in zip(tls, streams):
+                B.cast_adams_step_multi(tl, cfg, stream=s)
+        torch.cuda.synchronize()
+        out = []
+        for items in lists:
+            for x in items:
+                out.append(b"".join(host(x[k]).tobytes() for k in ("w", "m", "v", "mask", "scale_grad")))
+                if x["refresh_stats"] is not None:
+                    out.append(host(x["refresh_stats"]).tobytes())
+                if x["compute_copy"] is not None:
+                    out.append(host(x["compute_copy"].view(torch.int16)).tobytes())
+        return out
+
+    assert run(True) == run(False)
