@@ -439,46 +439,26 @@ static int device_compute_units()
     return cus;
 }
 
-// A list of matrices that share one configuration.  Default: one launch per matrix, small matrices
-// of one shape and one kernel flavour several to a launch, long row segments as split plans whose
-// pieces' sums (and the refresh statistics' partial sums) go through the workspace and are added up
-// by follow-up launches.  With CAST_FLAG_WORK_QUEUE, matrices of equal (rows, cols, ld) that the
-// queue can take form one launch of resident workgroups (see adams_step_vec_queue), their buffer
-// addresses in a table that is copied, together with zeroed ticket counters, to the workspace first.
-// With `tally` the call only counts the launches it would make (nothing is enqueued).
-cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast_adams_config *cfg,
-                                    void *workspace, hipStream_t st, MultiTally *tally)
+// The work-queue form of the list call: matrices of equal (rows, cols, ld) whose plan gives every
+// wavefront one chunk per share form one launch of resident workgroups; their buffer sets go to the
+// workspace as a table, with the zeroed ticket counters behind it.  Marks what it steps in `taken`.
+static cast_status launch_queue_groups(const cast_tensor *ts, int count, const cast_adams_config *cfg, void *workspace,
+                                       const MultiLayout &layout, PieceArea &area, PieceJobQueue &jobs,
+                                       std::vector<char> &taken, hipStream_t st, MultiTally *tally)
 {
     const bool dry = tally != nullptr;
-    if (dry) *tally = MultiTally{0, 0};
     const bool bf16 = cfg->grad_dtype == CAST_BF16;
     const bool refresh = cfg->refresh_mask != 0;
     const bool scaled = cfg->scale_segments > 0;
-    // The work queue is opt-in: one launch per matrix has measured faster at every size tried.
-    bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
-    // the work queue knows neither the comparison rules with code of their own nor the compute copy
-    if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN) use_queue = false;
-    if (cfg->flags & CAST_FLAG_MU_BF16) use_queue = false;      // nor a first moment kept in bf16
-    const bool want_stats = cfg->refresh_mask != 0;
-    for (int i = 0; i < count; ++i)
-        if (ts[i].compute_copy || (want_stats && ts[i].refresh_stats)) use_queue = false;      // nor refresh statistics
     // tuning knobs (read once): resident wavefronts per compute unit of the work queue
     static const int waves_per_cu = env_int("CAST_QUEUE_WAVES_PER_CU", 16);
     static const int log2_run = env_int("CAST_QUEUE_LOG2_RUN", 1) & 7;      // shares per ticket = 1 << log2_run
     static const int queue_block_waves = env_int("CAST_QUEUE_BLOCK_WAVES", 8);
-    const MultiLayout layout = multi_layout(ts, count, cfg);
-    PieceJobQueue jobs;
-    // the workspace: table of buffer sets, ticket counters, piece sums, statistics slots (a dry run has none)
-    float *const piece_base = workspace ? reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes)
-                                        : nullptr;
-    StatsPartial *const stats_base = workspace ? reinterpret_cast<StatsPartial *>(piece_base + layout.piece_floats) : nullptr;
-    PieceArea area{piece_base, layout.piece_floats, &jobs};
+    if (waves_per_cu <= 0) return CAST_OK;
     std::vector<int> order;           // indices of vector-path matrices, grouped by shape
-    std::vector<char> taken(count, 0);
     struct Group { int first, n; SpanPlan plan; int block_waves; unsigned blocks_per_matrix; };
     std::vector<Group> groups;
-    if (waves_per_cu <= 0) use_queue = false;
-    for (int i = 0; use_queue && i < count; ++i) {
+    for (int i = 0; i < count; ++i) {
         if (taken[i] || ts[i].rows == 0 || ts[i].cols == 0) continue;
         const bool wants_gA = scaled && ts[i].scale_grad != nullptr;
         SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments, wants_gA && layout.piece_floats > 0);
@@ -560,6 +540,41 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
                 jobs.add(piece_jobs[next_job]);
             }
         }
+    }
+    return CAST_OK;
+}
+
+// A list of matrices that share one configuration.  Default: one launch per matrix, small matrices
+// of one shape and one kernel flavour several to a launch, long row segments as split plans whose
+// pieces' sums (and the refresh statistics' partial sums) go through the workspace and are added up
+// by follow-up launches.  With CAST_FLAG_WORK_QUEUE, matrices of equal (rows, cols, ld) that the
+// queue can take form one launch of resident workgroups (see adams_step_vec_queue), their buffer
+// addresses in a table that is copied, together with zeroed ticket counters, to the workspace first.
+// With `tally` the call only counts the launches it would make (nothing is enqueued).
+cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast_adams_config *cfg,
+                                    void *workspace, hipStream_t st, MultiTally *tally)
+{
+    const bool dry = tally != nullptr;
+    if (dry) *tally = MultiTally{0, 0};
+    // The work queue is opt-in: one launch per matrix has measured faster at every size tried.
+    bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
+    // the work queue knows neither the comparison rules with code of their own nor the compute copy
+    if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN) use_queue = false;
+    if (cfg->flags & CAST_FLAG_MU_BF16) use_queue = false;      // nor a first moment kept in bf16
+    const bool want_stats = cfg->refresh_mask != 0;
+    for (int i = 0; i < count; ++i)
+        if (ts[i].compute_copy || (want_stats && ts[i].refresh_stats)) use_queue = false;      // nor refresh statistics
+    const MultiLayout layout = multi_layout(ts, count, cfg);
+    PieceJobQueue jobs;
+    // the workspace: table of buffer sets, ticket counters, piece sums, statistics slots (a dry run has none)
+    float *const piece_base = workspace ? reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes)
+                                        : nullptr;
+    StatsPartial *const stats_base = workspace ? reinterpret_cast<StatsPartial *>(piece_base + layout.piece_floats) : nullptr;
+    PieceArea area{piece_base, layout.piece_floats, &jobs};
+    std::vector<char> taken(count, 0);
+    if (use_queue) {
+        const cast_status rc = launch_queue_groups(ts, count, cfg, workspace, layout, area, jobs, taken, st, tally);
+        if (rc != CAST_OK) return rc;
     }
     StatsJobQueue stats_jobs;
     StatsArea stats_area{stats_base, layout.stats_slots, &stats_jobs};
