@@ -3,8 +3,8 @@
 // what they pass around.  Host-side planning and launching is in adams_step.hip.
 //
 // The work is a single streaming read-modify-write over w, mu, v (fp32), the gradient (bf16
-// or fp32) and one mask bit per entry: 26.125 bytes per parameter with bf16 gradients and
-// nothing is read twice.  There is no contraction, so no MFMA; the kernel is bound by HBM.
+// or fp32) and one mask bit per entry: 26.125 bytes per parameter with bf16 gradients (22.125
+// with the first moment kept in bf16 as well) and nothing is read twice.  There is no contraction, so no MFMA; the kernel is bound by HBM.
 #pragma once
 #include "cast_device.h"
 #include "cast_internal.h"
@@ -19,7 +19,7 @@ namespace cast {
 struct TensorPtrs {
     float *w;
     const void *grad;
-    float *m;
+    float *m;             // bf16 values instead when the first moment is kept in bf16 (flavour 3)
     float *v;
     uint32_t *mask;
     const float *scale;
