@@ -80,6 +80,44 @@ __global__ __launch_bounds__(kMaxBlockThreads) void nm_select_vec(const float *w
     }
 }
 
+// M = 8 with a whole group per lane (8 consecutive entries, two 16-byte loads): the ranking needs no
+// exchange between lanes, and the bytes of four adjacent lanes form a mask word.  Units of 512 entries
+// per wavefront, two of them requested before the first is worked on.
+__global__ __launch_bounds__(kMaxBlockThreads) void nm_select_8_vec(const float *w, uint32_t *mask, const SpanGeom geom, int n_keep)
+{
+    constexpr int kUnit = 2 * kChunk;
+    constexpr int kUnitsInFlight = 2;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int stride = geom.waves_per_span * kUnit;
+    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
+    const int sub = slot.sub;
+    const SpanOrigin o = span_origin(geom, slot.span);
+    const int len = o.len;
+    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
+    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask + (o.dense_begin >> 5), len / 8);
+    for (int base = sub * kUnit; base < len; base += kUnitsInFlight * stride) {
+        vu4_t lo[kUnitsInFlight], hi[kUnitsInFlight];
+#pragma unroll
+        for (int k = 0; k < kUnitsInFlight; ++k) {      // past the end of the span: zeros
+            const int off = base + k * stride + lane * 8;
+            lo[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad);
+            hi[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4 + 16, 0, kAuxLoad);
+        }
+#pragma unroll
+        for (int k = 0; k < kUnitsInFlight; ++k) {
+            if (base + k * stride >= len) break;      // wave-uniform
+            const int off = base + k * stride + lane * 8;
+            const float x[8] = {__uint_as_float(lo[k].x), __uint_as_float(lo[k].y), __uint_as_float(lo[k].z), __uint_as_float(lo[k].w),
+                                __uint_as_float(hi[k].x), __uint_as_float(hi[k].y), __uint_as_float(hi[k].z), __uint_as_float(hi[k].w)};
+            uint32_t word = keep_bits_group<8>(x, n_keep) << ((lane & 3) * 8);
+            word |= dpp_u32<kDppQuadXor1>(word);
+            word |= dpp_u32<kDppQuadXor2>(word);
+            if ((lane & 3) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmask, (off >> 5) * 4, 0, kAuxStore);
+        }
+    }
+}
+
 // Any shape with cols % M == 0: one thread per mask word (32 consecutive columns of a row).
 template <int M>
 __global__ __launch_bounds__(kBlockThreads) void nm_select_unit(const float *w, uint32_t *mask,
@@ -110,7 +148,7 @@ cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int64_t
         switch (m_group) {
         case 2: hipLaunchKernelGGL(nm_select_vec<2>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
         case 4: hipLaunchKernelGGL(nm_select_vec<4>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
-        default: hipLaunchKernelGGL(nm_select_vec<8>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
+        default: hipLaunchKernelGGL(nm_select_8_vec, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
         }
     } else {
         const int64_t words = rows * ((cols + 31) / 32);
@@ -178,25 +216,18 @@ cast_status launch_weight_scale(const float *w, const float *scale, int64_t rows
 }
 
 // ---- hard prune + fold + pack ---------------------------------------------------------------
-// The half-density patterns 2:4 (the paper's), 4:8 and 1:2.  A lane holds 4 consecutive entries and
-// always ends up with exactly two kept values, which leave as one 8-byte (fp32) or 4-byte (bf16)
-// store at values[off / 2]:
+// The half-density patterns 2:4 (the paper's) and 1:2 (4:8 has a kernel of its own below).  A lane holds 4
+// consecutive entries and always ends up with exactly two kept values, which leave as one 8-byte (fp32) or
+// 4-byte (bf16) store at values[off / 2]:
 //   2:4  the lane is one group; the 4-bit index fields of 8 adjacent lanes form one metadata word;
-//   1:2  the lane is two groups with one kept entry each; 16 lanes' bit pairs form one word;
-//   4:8  two adjacent lanes are one group: they exchange their kept values (DPP), the even lane
-//        stores the group's first two and the odd lane its last two; the group's four 3-bit indices
-//        fill a 16-bit field and 4 lanes form one word.
-__device__ __forceinline__ float pick4(const float (&x)[4], uint32_t i)
-{
-    return i == 0 ? x[0] : (i == 1 ? x[1] : (i == 2 ? x[2] : x[3]));
-}
-
+//   1:2  the lane is two groups with one kept entry each; 16 lanes' bit pairs form one word.
 template <int M, bool BF16OUT>
 __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
     const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
     const SpanGeom geom, uint32_t seg_len, FastDivU32 div_seg_len)
 {
-    constexpr int kEntriesPerWord = M == 4 ? 32 : (M == 8 ? 16 : 64);      // columns one metadata word describes
+    static_assert(M == 4 || M == 2, "2:4 and 1:2 only");
+    constexpr int kEntriesPerWord = M == 4 ? 32 : 64;      // columns one metadata word describes
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int stride = geom.waves_per_span * kChunk;
@@ -254,35 +285,6 @@ __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
                 a = ia ? x[1] : x[0];
                 b = ib ? x[3] : x[2];
                 word = or_reduce_16lanes((ia | (ib << 1)) << ((lane & 15) * 2));
-            } else {
-                // own kept entries in ascending order (p = 4: no such entry) and how many there are
-                const uint32_t r1 = nib & (nib - 1u), r2 = r1 & (r1 - 1u), r3 = r2 & (r2 - 1u);
-                const uint32_t p0 = (uint32_t)__builtin_ctz(nib | 0x10u), p1 = (uint32_t)__builtin_ctz(r1 | 0x10u);
-                const uint32_t p2 = (uint32_t)__builtin_ctz(r2 | 0x10u), p3 = (uint32_t)__builtin_ctz(r3 | 0x10u);
-                const uint32_t cnt = (uint32_t)__popc(nib);
-                float own[4] = {pick4(x, p0 & 3u), pick4(x, p1 & 3u), pick4(x, p2 & 3u), pick4(x, p3 & 3u)};
-                float other[4];
-    #pragma unroll
-                for (int k = 0; k < 4; ++k) other[k] = __uint_as_float(dpp_u32<kDppQuadXor1>(__float_as_uint(own[k])));
-                const uint32_t other_cnt = dpp_u32<kDppQuadXor1>(cnt);
-                const bool odd = (lane & 1) != 0;
-                const uint32_t c0 = odd ? other_cnt : cnt;       // kept entries in the even lane: they come first
-                // the group's kept values in order are L[i] = i < c0 ? E[i] : O[i - c0]; this lane stores L[2*odd], L[2*odd + 1]
-                const uint32_t i0 = odd ? 2u : 0u, i1 = i0 + 1u;
-                const float e0 = pick4(odd ? other : own, i0), o0 = pick4(odd ? own : other, (i0 - c0) & 3u);
-                const float e1 = pick4(odd ? other : own, i1), o1 = pick4(odd ? own : other, (i1 - c0) & 3u);
-                a = i0 < c0 ? e0 : o0;
-                b = i1 < c0 ? e1 : o1;
-                // indices: own s-th kept entry has in-group index 4*odd + p_s and position (odd ? c0 : 0) + s in the field
-                const uint32_t at = odd ? c0 : 0u, hi = odd ? 4u : 0u;
-                uint32_t field = 0;
-                field |= cnt > 0 ? (hi + p0) << (3u * at) : 0u;
-                field |= cnt > 1 ? (hi + p1) << (3u * (at + 1u)) : 0u;
-                field |= cnt > 2 ? (hi + p2) << (3u * (at + 2u)) : 0u;
-                field |= cnt > 3 ? (hi + p3) << (3u * (at + 3u)) : 0u;
-                field |= dpp_u32<kDppQuadXor1>(field);          // both lanes of the group now hold its 12 bits
-                field <<= (lane & 2) * 8;                       // second group of the word: upper 16 bits
-                word = field | dpp_u32<kDppQuadXor2>(field);
             }
             if (scale) { a = A * a; b = A * b; }
             if constexpr (BF16OUT) {
@@ -294,6 +296,80 @@ __global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
             constexpr int kLanesPerWord = kEntriesPerWord / kLaneElems;
             if ((lane & (kLanesPerWord - 1)) == 0)
                 __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off / kEntriesPerWord) * 4, 0, kAuxStore);
+        }
+    }
+}
+
+// 4:8 with a whole group per lane: 8 consecutive entries (two 16-byte loads), so the four kept values
+// are picked inside the lane (the k-th kept entry can only be one of entries k .. k + 4) and leave as
+// one 16-byte (fp32) or 8-byte (bf16) store; two adjacent lanes' 12-bit index fields form a metadata
+// word.  A wavefront takes units of 512 entries, two of them requested before the first is worked on.
+// The exchange between lane pairs that the 4-entries-per-lane form needs made it ALU-bound.
+template <bool BF16OUT>
+__global__ __launch_bounds__(kMaxBlockThreads) void project_compress_4of8_vec(
+    const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
+    const SpanGeom geom, uint32_t seg_len, FastDivU32 div_seg_len)
+{
+    constexpr int kUnit = 2 * kChunk;          // entries a wavefront handles at a time: 8 per lane
+    constexpr int kUnitsInFlight = 2;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int stride = geom.waves_per_span * kUnit;
+    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
+    const int sub = slot.sub;
+    const SpanOrigin o = span_origin(geom, slot.span);
+    const int len = o.len;
+    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
+    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask ? mask + (o.dense_begin >> 5) : nullptr, mask ? len / 8 : 0);
+    const __amdgpu_buffer_rsrc_t rmeta = span_resource(meta + o.dense_begin / 16, len / 16 * 4);
+    const int vbytes = BF16OUT ? 2 : 4;
+    const __amdgpu_buffer_rsrc_t rval = span_resource(static_cast<char *>(values) + (o.dense_begin >> 1) * vbytes, (len >> 1) * vbytes);
+    int64_t first_seg = 0;
+    uint32_t first_seg_off = 0;
+    if (scale) {
+        first_seg = o.dense_begin / (int64_t)seg_len;
+        first_seg_off = (uint32_t)(o.dense_begin - first_seg * (int64_t)seg_len);
+    }
+    for (int base = sub * kUnit; base < len; base += kUnitsInFlight * stride) {
+        vu4_t lo[kUnitsInFlight], hi[kUnitsInFlight];
+        uint32_t bits[kUnitsInFlight];
+#pragma unroll
+        for (int k = 0; k < kUnitsInFlight; ++k) {      // past the end of the span: zeros
+            const int off = base + k * stride + lane * 8;
+            lo[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad);
+            hi[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4 + 16, 0, kAuxLoad);
+            bits[k] = mask ? __builtin_amdgcn_raw_buffer_load_b32(rmask, (off >> 5) * 4, 0, kAuxLoad) : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kUnitsInFlight; ++k) {
+            if (base + k * stride >= len) break;      // wave-uniform
+            const int off = base + k * stride + lane * 8;
+            const float x[8] = {__uint_as_float(lo[k].x), __uint_as_float(lo[k].y), __uint_as_float(lo[k].z), __uint_as_float(lo[k].w),
+                                __uint_as_float(hi[k].x), __uint_as_float(hi[k].y), __uint_as_float(hi[k].z), __uint_as_float(hi[k].w)};
+            const uint32_t kept = mask ? (bits[k] >> (off & 31)) & 0xFFu : keep_bits_group<8>(x, 4);
+            // positions of the four kept entries, ascending (a given mask with fewer bits: the guard bit keeps them in range)
+            const uint32_t r1 = kept & (kept - 1u), r2 = r1 & (r1 - 1u), r3 = r2 & (r2 - 1u);
+            const uint32_t p0 = (uint32_t)__builtin_ctz(kept | 0x100u) & 7u, p1 = (uint32_t)__builtin_ctz(r1 | 0x100u) & 7u;
+            const uint32_t p2 = (uint32_t)__builtin_ctz(r2 | 0x100u) & 7u, p3 = (uint32_t)__builtin_ctz(r3 | 0x100u) & 7u;
+            float v0 = p0 == 0 ? x[0] : (p0 == 1 ? x[1] : (p0 == 2 ? x[2] : (p0 == 3 ? x[3] : x[4])));
+            float v1 = p1 == 1 ? x[1] : (p1 == 2 ? x[2] : (p1 == 3 ? x[3] : (p1 == 4 ? x[4] : x[5])));
+            float v2 = p2 == 2 ? x[2] : (p2 == 3 ? x[3] : (p2 == 4 ? x[4] : (p2 == 5 ? x[5] : x[6])));
+            float v3 = p3 == 3 ? x[3] : (p3 == 4 ? x[4] : (p3 == 5 ? x[5] : (p3 == 6 ? x[6] : x[7])));
+            if (scale) {
+                float A = 1.0f;
+                if (off < len) A = scale[first_seg + fast_div(first_seg_off + (uint32_t)off, div_seg_len)];
+                v0 = A * v0; v1 = A * v1; v2 = A * v2; v3 = A * v3;
+            }
+            if constexpr (BF16OUT) {
+                const vu2_t h = {f32x2_to_bf16_rne(v0, v1), f32x2_to_bf16_rne(v2, v3)};
+                __builtin_amdgcn_raw_buffer_store_b64(h, rval, off, 0, kAuxStore);            // (off / 2) values of 2 bytes
+            } else {
+                const vu4_t q = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
+                __builtin_amdgcn_raw_buffer_store_b128(q, rval, off * 2, 0, kAuxStore);       // (off / 2) values of 4 bytes
+            }
+            const uint32_t field = p0 | (p1 << 3) | (p2 << 6) | (p3 << 9);
+            const uint32_t word = field | (dpp_u32<kDppQuadXor1>(field) << 16);           // even lane: its group, then the odd lane's
+            if ((lane & 1) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off >> 4) * 4, 0, kAuxStore);
         }
     }
 }
@@ -383,8 +459,8 @@ cast_status launch_project_compress(const float *w, const float *scale, int n_se
             else hipLaunchKernelGGL((project_compress_half_vec<4, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
             break;
         case 8:
-            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<8, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
-            else hipLaunchKernelGGL((project_compress_half_vec<8, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
+            if (bf16) hipLaunchKernelGGL(project_compress_4of8_vec<true>, grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
+            else hipLaunchKernelGGL(project_compress_4of8_vec<false>, grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
             break;
         default:
             if (bf16) hipLaunchKernelGGL((project_compress_half_vec<2, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
