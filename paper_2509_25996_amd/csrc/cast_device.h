@@ -259,15 +259,23 @@ __device__ __forceinline__ uint32_t keep_bits_group(const float (&w)[M], int n_k
     uint32_t key[M];
 #pragma unroll
     for (int j = 0; j < M; ++j) key[j] = magnitude_key(w[j]);
-    uint32_t bits = 0;
+    // rank[j] = entries that come before entry j in the order "larger magnitude first, then lower index":
+    // one comparison per pair decides for both of its entries
+    int rank[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) rank[j] = j;           // as if every lower index came first ...
 #pragma unroll
     for (int j = 0; j < M; ++j) {
-        int rank = 0;
 #pragma unroll
-        for (int k = 0; k < M; ++k)
-            rank += (k < j) ? (key[k] >= key[j]) : ((k > j) ? (key[k] > key[j]) : 0);
-        bits |= (uint32_t)(rank < n_keep) << j;
+        for (int k = j + 1; k < M; ++k) {
+            const int later_wins = key[k] > key[j];     // ... unless the higher index has the strictly larger magnitude
+            rank[j] += later_wins;
+            rank[k] -= later_wins;
+        }
     }
+    uint32_t bits = 0;
+#pragma unroll
+    for (int j = 0; j < M; ++j) bits |= (uint32_t)(rank[j] < n_keep) << j;
     return bits;
 }
 
