@@ -172,9 +172,9 @@ cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v,
  * of a model in one call): validated as a whole before anything is launched, then stepped one
  * launch per matrix, or, with CAST_FLAG_WORK_QUEUE, one work-queue launch per group of matrices
  * of equal shape.  w, m, v and mask_bits come out as from cast_adams_step on each matrix, bit for
- * bit; so does scale_grad, except for row segments of more than 4096 entries, which the list call
- * steps in pieces of 2048 entries: their sums are added in another, equally fixed order (per
- * 2048 entries, then left to right).
+ * bit; so does scale_grad, except for row segments of more than 2048 entries other than 4096, which
+ * the list call steps in pieces of 512, 1024 or 2048 entries: their sums are added in another,
+ * equally fixed order (per piece, then the pieces left to right).
  *   tensors    HOST in   `count` descriptors; the device buffers they name follow the rules of
  *                        cast_adams_step (scale / scale_grad NULL or not for all alike, per cfg).
  *                        No two descriptors may name overlapping buffers: the matrices are stepped

@@ -80,7 +80,8 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool
     g.div_spans_per_row = make_fast_div(1);
     g.pieces_per_segment = 1;
     g.div_pieces = make_fast_div(1);
-    static const int split_min_chunks = env_int("CAST_SPLIT_MIN_CHUNKS", 2 * kPieceChunks + 1);
+    static const int split_min_chunks = env_int("CAST_SPLIT_MIN_CHUNKS", kPieceChunks + 1);
+    static const int piece_chunks_knob = env_int("CAST_PIECE_CHUNKS", 0);      // 0: chosen per segment length
     int block_waves = kBlockWaves;
     int per_row = n_segments;
     if (per_row == 0 && ld != cols) {
@@ -97,21 +98,32 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool
         p.vec = cols % per_row == 0 && g.span_len % 32 == 0 && g.span_len < ((int64_t)1 << 28) && ld % 4 == 0 &&
                 g.num_spans < ((int64_t)1 << 31);
         const int64_t chunks = (g.span_len + kChunk - 1) / kChunk;
-        const int64_t pieces = (chunks + kPieceChunks - 1) / kPieceChunks;
+        // Pieces of 8, 4 or 2 chunks: the largest size that leaves at most 11 % of the wavefronts of a
+        // segment's workgroups without a chunk (21.5 chunks: 8, 8, 5.5; 28 chunks: seven fours; 10 chunks:
+        // five twos).  Measured on the benchmark shapes: smaller pieces than needed are no faster.
+        int piece_chunks = 2;
+        for (int c = kPieceChunks; c > 2; c /= 2) {
+            const int64_t slots = (chunks + c - 1) / c * c * kChunk;      // entries the wavefronts could take
+            if ((slots - g.span_len) * 100 <= slots * 11) { piece_chunks = c; break; }
+        }
+        if (piece_chunks_knob == 1 || piece_chunks_knob == 2 || piece_chunks_knob == 4 || piece_chunks_knob == 8) piece_chunks = piece_chunks_knob;
+        const int64_t pieces = (chunks + piece_chunks - 1) / piece_chunks;
         g.segment_len = g.span_len;
-        if (allow_split && p.vec && n_segments > 0 && chunks >= split_min_chunks && pieces > 1 &&
+        // 8 and 16 chunks fill one workgroup of 8 or 16 wavefronts exactly and stay whole
+        if (allow_split && p.vec && n_segments > 0 && chunks >= split_min_chunks && chunks != kMaxBlockWaves && pieces > 1 &&
             g.num_spans * pieces < ((int64_t)1 << 31) && pieces * per_row < ((int64_t)1 << 24)) {
-            // More chunks than the wavefronts of a workgroup: with several chunks per wavefront the
-            // workgroups are few, large and long-lived, and the compute units run half empty.  Cut the
-            // segment into pieces of kPieceChunks chunks, one workgroup and one chunk per wavefront each.
+            // More chunks than a workgroup has wavefronts, or a number of them that leaves wavefront slots
+            // of the compute units empty (10-wavefront workgroups fill 30 of 32): with several chunks per
+            // wavefront the workgroups are few, large and long-lived, and the compute units run half empty.
+            // Cut the segment into pieces, one chunk per wavefront, workgroups of 8 wavefronts.
             g.pieces_per_segment = (int)pieces;
             g.div_pieces = make_fast_div((uint32_t)pieces);
-            g.span_len = (int64_t)kPieceChunks * kChunk;
+            g.span_len = (int64_t)piece_chunks * kChunk;
             g.spans_per_row = per_row * (int)pieces;
             g.div_spans_per_row = make_fast_div((uint32_t)g.spans_per_row);
             p.segments = g.num_spans;
             g.num_spans *= pieces;
-            g.waves_per_span = kPieceChunks;
+            g.waves_per_span = piece_chunks;
             block_waves = kPieceChunks;
         } else {
             if (chunks <= kBlockWaves) {

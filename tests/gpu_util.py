@@ -95,3 +95,10 @@ class OracleState:
         for i, x in enumerate((self.w, self.m, self.v)):
             np.maximum(self.scale[i], np.abs(x), out=self.scale[i])
         return gA
+
+
+def stepped_in_pieces(segment_entries: int) -> bool:
+    """Whether the list call steps row segments of this length in pieces (more than 8 chunks of 256 entries, 16
+    chunks excepted), so that dL/dA is summed per piece first."""
+    chunks = -(-segment_entries // 256)
+    return chunks > 8 and chunks != 16

@@ -9,7 +9,7 @@ import oracle
 from paper_2509_25996_amd import binding as B
 from paper_2509_25996_amd import synth
 
-from gpu_util import DEV, GpuState, OracleState, assert_same_bits, dev, host, oracle_cfg, words
+from gpu_util import DEV, GpuState, stepped_in_pieces, OracleState, assert_same_bits, dev, host, oracle_cfg, words
 
 pytestmark = pytest.mark.gpu
 
@@ -106,7 +106,7 @@ def test_mu_bf16_list_call_equals_single_calls(nseg):
         assert host(x["m"].view(torch.int16)).tobytes() == host(y["m"].view(torch.int16)).tobytes()
         if nseg and x["w"].numel():
             ga, gb = host(x["scale_grad"]), host(y["scale_grad"])
-            if x["w"].shape[1] // nseg > 4096:      # pieces: another, equally fixed summation order
+            if stepped_in_pieces(x["w"].shape[1] // nseg):      # another, equally fixed summation order
                 assert np.abs(ga.astype(np.float64) - gb).max() <= 1e-6
             else:
                 assert ga.tobytes() == gb.tobytes()

@@ -13,6 +13,7 @@ from paper_2509_25996_amd import binding as B
 from paper_2509_25996_amd import synth
 
 from gpu_util import (DEV, GpuState, OracleState, assert_same_bits, dev, host, max_rel_err, oracle_cfg, words)
+from gpu_util import stepped_in_pieces as _stepped_in_pieces
 
 pytestmark = pytest.mark.gpu
 
@@ -406,7 +407,7 @@ def test_strided_weights_in_every_entry_point(rows, cols):
 @pytest.mark.parametrize("nseg", [0, 2])
 def test_multi_tensor_step_equals_single_steps(nseg, queue):
     # (16, 11008) and (7, 8768) have row segments of more than 16 chunks of 256 entries: the list call steps
-    # them in pieces of 2048 entries (with or without the work queue) and adds the pieces' dL/dA sums afterwards
+    # them in pieces of at most 2048 entries (with or without the work queue) and adds the pieces' dL/dA sums afterwards
     # runs of equal shapes: the list call steps up to 16 small matrices of one shape with one launch
     shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (5, 72), (64, 512), (32, 1024), (32, 1024), (3, 40), (0, 64),
               (16, 11008), (16, 11008), (7, 8768), (64, 512), (64, 512), (64, 512), (64, 512), (64, 512), (0, 64), (64, 512)]
@@ -440,7 +441,7 @@ def test_multi_tensor_step_equals_single_steps(nseg, queue):
             for k in ("w", "m", "v", "mask"):
                 assert host(x[k]).tobytes() == host(y[k]).tobytes(), k
             if nseg and x["w"].numel():
-                in_pieces = x["w"].shape[1] // nseg > 4096
+                in_pieces = _stepped_in_pieces(x["w"].shape[1] // nseg)
                 ga, gb = host(x["scale_grad"]), host(y["scale_grad"])
                 if in_pieces:      # another summation order: equal up to fp32 rounding of sums of ~5000 terms of ~2e-5
                     assert np.abs(ga.astype(np.float64) - gb).max() <= 1e-6
@@ -883,3 +884,32 @@ def test_two_streams_with_their_own_lists_and_workspaces():
         return out
 
     assert run(True) == run(False)
+
+
+@pytest.mark.parametrize("rows,cols", [(12, 5120), (9, 6144), (7, 4608), (5, 13824), (3, 6656), (6, 14336)])
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_list_call_pieces_of_two_and_four_chunks(rows, cols, interleaved):
+    """Row segments of 9 to 15 chunks and the long ones whose length suits smaller pieces (10, 12, 9, 27, 13 and 28
+    chunks here) are stepped by the list call as pieces of 2 or 4 chunks, several pieces to a workgroup: state
+    and masks bit for bit against the oracle, dL/dA against the double sum, over refresh and plain steps."""
+    nseg, steps = 2, 3
+    assert _stepped_in_pieces(cols // nseg)
+    w0 = synth.tie_outlier_weights(19, 1, rows, cols)
+    A = (1 + 0.1 * np.random.default_rng(rows).standard_normal((rows, nseg))).astype(np.float32)
+    st = GpuState(w0, nseg, interleaved=interleaved)
+    g = torch.zeros((rows, cols), dtype=torch.bfloat16, device=DEV)
+    tl = B.TensorList([dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=g, scale=dev(A), scale_grad=st.scale_grad)], DEV)
+    o = OracleState(w0, "f32")
+    for t in range(steps):
+        gb = synth.grads_bf16(19, 1, t, rows, cols)
+        g.copy_(gb.to(DEV))
+        cfg = B.iteration_config(t, steps, mask_period=2, lr=1e-3, lambda_=1e-3, scale_segments=nseg)
+        B.cast_adams_step_multi(tl, cfg)
+        ref_gA = o.step(synth.widen_bf16(gb), oracle_cfg(cfg), A=A)
+        terms = np.abs(synth.widen_bf16(gb).astype(np.float64) * 0.05).reshape(rows, nseg, -1).sum(-1)
+        assert (np.abs(host(st.scale_grad) - ref_gA) <= 2e-5 * terms + 1e-9).all()
+    torch.cuda.synchronize()
+    assert (words(st.mask) == oracle.pack_mask_bits(o.keep)).all()
+    assert_same_bits(host(st.w), o.w, "w")
+    assert_same_bits(host(st.m), o.m, "mu")
+    assert_same_bits(host(st.v), o.v, "v")
