@@ -21,7 +21,7 @@ def _mu(t: torch.Tensor) -> np.ndarray:
 
 @pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
 @pytest.mark.parametrize("rows,cols,nseg", [(6, 512, 0), (6, 512, 2), (5, 1280 + 64, 2), (7, 72, 3), (3, 40, 0), (9, 24, 1),
-                                            (12, 4096, 2), (5, 11008, 2), (33, 4096 + 32, 0)])
+                                            (12, 4096, 2), (5, 11008, 2), (33, 4096 + 32, 0), (6, 5120, 2), (4, 13824, 2)])
 @pytest.mark.parametrize("bf16_grad", [False, True])
 @pytest.mark.parametrize("interleaved", [False, True])
 def test_mu_bf16_step_bit_exact(n, m, rows, cols, nseg, bf16_grad, interleaved):
@@ -77,7 +77,8 @@ def test_mu_bf16_special_values():
 @pytest.mark.parametrize("nseg", [0, 2])
 def test_mu_bf16_list_call_equals_single_calls(nseg):
     # equal shapes share launches, the long rows are stepped in pieces, odd shapes one by one
-    shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (64, 512), (16, 11008), (16, 11008), (7, 8768), (0, 64), (64, 512)]
+    shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (64, 512), (16, 11008), (16, 11008), (7, 8768), (0, 64), (64, 512), (12, 5120),
+              (6, 13824)]
     rng = np.random.default_rng(5)
 
     def make():
