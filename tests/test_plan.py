@@ -49,7 +49,8 @@ def _check_span(rows, cols, ld, nseg, plan, span):
 
 
 SMALL = [(1, 32), (3, 64), (2, 256), (5, 512), (4, 1024), (3, 1280 + 64), (2, 2560), (2, 4096), (1, 4096 + 32), (2, 5504),
-         (1, 8768), (1, 11008), (2, 6912), (1, 16384), (1, 262144 + 32), (7, 96)]
+         (1, 8768), (1, 11008), (2, 6912), (1, 16384), (1, 262144 + 32), (7, 96),
+         (2, 5120), (2, 13824), (1, 4608), (1, 6656), (1, 14336), (3, 6144), (1, 7424), (1, 28672)]
 
 
 @pytest.mark.parametrize("rows,cols", SMALL)
