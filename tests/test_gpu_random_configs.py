@@ -89,3 +89,72 @@ def test_random_configurations_match_the_oracle(seed):
                 assert (host(item["compute_copy"].view(torch.int16)).view(np.uint16) == want).all(), note + " copy"
         done += 1
     assert done > count // 2
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_random_selection_scaling_and_packing_match_the_oracle(seed):
+    """The other entry points on random shapes, patterns and layouts: mask selection, A (.) W (fp32, bf16, in place),
+    dL/dA alone, mask statistics, hard projection + fold + pack with the mask recomputed or given."""
+    rnd = random.Random(seed)
+    for case in range(150):
+        m = rnd.choice([2, 4, 4, 8, 8])
+        n = rnd.randint(1, m - 1) if rnd.random() < 0.35 else m // 2
+        nseg = rnd.choice([1, 2, 2, 3, 4])
+        kind = rnd.random()
+        if kind < 0.4:
+            cols = m * nseg * rnd.randint(1, 40)
+        elif kind < 0.85:
+            cols = 64 * nseg * rnd.randint(1, 40)
+        else:
+            cols = rnd.choice([4096, 5120, 11008, 13824, 8192])
+        if cols % (m * nseg) or (cols // nseg) % m:
+            continue
+        rows = rnd.randint(1, 16 if cols > 4000 else 60)
+        interleaved = rnd.random() < 0.5
+        note = f"case {case}: {n}:{m} {rows}x{cols} nseg={nseg} interleaved={interleaved}"
+        w = synth.tie_outlier_weights(seed, case, rows, cols) if cols % 8 == 0 else synth.weights(seed, case, rows, cols)
+        A = (1 + 0.3 * np.random.default_rng(case).standard_normal((rows, nseg))).astype(np.float32)
+        wd = B.interleaved_state(dev(w))[0] if interleaved else dev(w)
+        # selection
+        mask = B.alloc_mask(rows, cols, DEV)
+        B.cast_nm_select(wd, n, m, mask)
+        keep = oracle.nm_select(w, n, m)
+        assert (words(mask) == oracle.pack_mask_bits(keep)).all(), note + " select"
+        # forward scale, fp32 and bf16
+        out32 = torch.empty((rows, cols), device=DEV)
+        out16 = torch.empty((rows, cols), dtype=torch.bfloat16, device=DEV)
+        B.cast_weight_scale(wd, dev(A), out32)
+        B.cast_weight_scale(wd, dev(A), out16)
+        ref = oracle.weight_scale(w, A)
+        assert_same_bits(host(out32), ref, note + " scale")
+        assert (host(out16.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref)).all(), note + " scale bf16"
+        # dL/dA alone
+        g = synth.grads_bf16(seed, case, 0, rows, cols)
+        gA = torch.zeros((rows, nseg), device=DEV)
+        B.cast_weight_scale_grad(wd, g.to(DEV), nseg, gA)
+        ref_gA = oracle.weight_scale_grad(w, synth.widen_bf16(g), nseg)
+        terms = np.abs(synth.widen_bf16(g).astype(np.float64) * w).reshape(rows, nseg, -1).sum(-1)
+        assert (np.abs(host(gA) - ref_gA) <= 2e-5 * terms + 1e-12).all(), note + " dL/dA"
+        # statistics against another mask
+        other = B.alloc_mask(rows, cols, DEV)
+        B.cast_nm_select(dev(synth.weights(seed, case + 1000, rows, cols)), n, m, other)
+        flips = torch.zeros(1, dtype=torch.int64, device=DEV)
+        l1 = torch.zeros(2, dtype=torch.float64, device=DEV)
+        B.cast_mask_stats(wd, mask, other, flips, l1)
+        f_ref, kept, total = oracle.mask_stats(w, keep, oracle.nm_select(synth.weights(seed, case + 1000, rows, cols), n, m))
+        assert int(flips.item()) == f_ref, note + " flips"
+        assert np.allclose(host(l1), [kept, total], rtol=1e-10), note + " norms"
+        # hard projection + fold + pack: mask recomputed, and the other mask given
+        for given, keep_used in ((None, None), (other, oracle.unpack_mask_bits(words(other), cols))):
+            for vdtype, code in ((torch.float32, B.CAST_F32), (torch.bfloat16, B.CAST_BF16)):
+                _, vbytes, mbytes = B.cast_sizes(rows, cols, n, m, code)
+                values = torch.full((rows, cols // m * n), 7.0, dtype=vdtype, device=DEV)
+                meta = torch.full((rows, mbytes // 4 // rows), -1, dtype=torch.int32, device=DEV)
+                B.cast_nm_project_compress(wd, n, m, values, meta, scale=dev(A), mask_bits=given)
+                ref_v, ref_m = oracle.project_compress(w, n, m, A=A, keep=keep_used)
+                assert (words(meta) == ref_m).all(), note + " meta"
+                if vdtype == torch.float32:
+                    assert_same_bits(host(values), ref_v, note + " values")
+                else:
+                    assert (host(values.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref_v)).all(), note + " bf16 values"
+    torch.cuda.synchronize()
