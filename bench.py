@@ -344,6 +344,14 @@ def main():
                 extra["mu_bf16_ms_step"] = round(ms, 3)
                 extra["mu_bf16_Gparams_s"] = round(model.params / (ms * 1e-3) / 1e9, 1)
                 extra["mu_bf16_GBs"] = round((BYTES_PER_PARAM - 4) * model.params / (ms * 1e-3) / 1e9, 1)
+                free_bytes, _ = torch.cuda.mem_get_info()
+                if free_bytes > 2.5 * model.params:      # the same with the bf16 compute copy written along (24.125 B/param)
+                    copies = [torch.empty(x["w"].shape, dtype=torch.bfloat16, device=dev) for x in model.t]
+                    model.tensor_list(B, scaled, dev, queue=False, copies=copies)
+                    ms = timed(0)
+                    extra["mu_bf16_emit_ms_step"] = round(ms, 3)
+                    extra["mu_bf16_emit_GBs"] = round((BYTES_PER_PARAM - 2) * model.params / (ms * 1e-3) / 1e9, 1)
+                    del copies
                 for x, (w, m, v) in zip(model.t, kept):
                     x["w"], x["m"], x["v"] = w, m, v
                 del kept

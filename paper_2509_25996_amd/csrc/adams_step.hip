@@ -222,6 +222,7 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
     if constexpr (SCALED) {
         if (l.split) {
             if (l.extra == kMuBf16) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, kMuBf16>), grid, block, 0, st, a);
+            else if (l.extra == kMuBf16Emit) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, kMuBf16Emit>), grid, block, 0, st, a);
             else if (l.extra == 2) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 2>), grid, block, 0, st, a);
             else if (l.extra == 1) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 1>), grid, block, 0, st, a);
             else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true>), grid, block, 0, st, a);
@@ -230,6 +231,10 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
     }
     if (l.extra == kMuBf16) {
         hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, kMuBf16>), grid, block, 0, st, a);
+        return;
+    }
+    if (l.extra == kMuBf16Emit) {
+        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, kMuBf16Emit>), grid, block, 0, st, a);
         return;
     }
     if (l.extra == 2) {
@@ -332,9 +337,9 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     // a compute copy to write or refresh statistics to gather (1), or a comparison rule with code of
     // its own (2): the EXTRA instantiations
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
-    // (a first moment kept in bf16 comes with none of the above: the API has seen to that)
+    // (a first moment kept in bf16 comes with the compute copy at most: the API has seen to that)
     const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
-    const int extra = mu16 ? kMuBf16 : (own_rule ? 2 : (x.compute_copy != nullptr ? 1 : (stats ? kStatsOnly : 0)));
+    const int extra = mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? 2 : (x.compute_copy != nullptr ? 1 : (stats ? kStatsOnly : 0)));
     p.geom.m_row_gap = mu_bf16_ld(cols, ld) - cols;
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
@@ -399,7 +404,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
                               can_emit(flavour) ? static_cast<uint16_t *>(t.compute_copy) : nullptr, can_emit(flavour) ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? kMuBf16 : flavour}, a, st);
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? (flavour == 1 ? kMuBf16Emit : kMuBf16) : flavour}, a, st);
     return launch_status();
 }
 

@@ -64,10 +64,13 @@ static ConstTable as_const_table(const void *device_ptr)
 // Kernel flavours (template argument EXTRA): 0 plain; 1 can also write the bf16 compute copy and
 // gather refresh statistics; 2 knows, on top, the comparison update rules with code of their own;
 // 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16); 4 plain that can gather refresh
-// statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0).
-constexpr bool can_emit(int extra) { return extra == 1 || extra == 2; }
+// statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0);
+// 5 the first moment in bf16 and the compute copy.
+constexpr bool can_emit(int extra) { return extra == 1 || extra == 2 || extra == 5; }
 constexpr bool can_count(int extra) { return extra == 1 || extra == 2 || extra == 4; }
+constexpr bool mu_is_bf16(int extra) { return extra == 3 || extra == 5; }
 constexpr int kMuBf16 = 3;
+constexpr int kMuBf16Emit = 5;
 constexpr int kStatsOnly = 4;
 
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
@@ -188,7 +191,7 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     o.len = __builtin_amdgcn_readfirstlane(o.len);
     c.len = o.len;
     c.b.w = span_resource(t.w + o.state_begin, c.len * 4);
-    if constexpr (EXTRA == kMuBf16) c.b.m = span_resource(reinterpret_cast<uint16_t *>(t.m) + (int64_t)uniform_u64((unsigned long long)o.m_begin), c.len * 2);
+    if constexpr (mu_is_bf16(EXTRA)) c.b.m = span_resource(reinterpret_cast<uint16_t *>(t.m) + (int64_t)uniform_u64((unsigned long long)o.m_begin), c.len * 2);
     else c.b.m = span_resource(t.m + o.state_begin, c.len * 4);
     c.b.v = span_resource(t.v + o.state_begin, c.len * 4);
     if constexpr (BF16) c.b.g = span_resource(static_cast<const uint16_t *>(t.grad) + o.dense_begin, c.len * 2);
@@ -237,7 +240,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
                                          float *partial, StatsShared *stats_shared = nullptr)
 {
     constexpr bool kStats = REFRESH && can_count(EXTRA);      // refresh statistics are gathered if c.stats_slot says so
-    constexpr bool kMu16 = EXTRA == kMuBf16;
+    constexpr bool kMu16 = mu_is_bf16(EXTRA);
     uint32_t flips_prev = 0, flips_init = 0;
     float l1_kept = 0.0f, l1_all = 0.0f;
     const int P = a.geom.waves_per_span;
@@ -298,7 +301,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
                 g[j] = A * g[j];                                         // chain rule of Eq. 12
             }
         }
-        adams_entries4<(EXTRA == 2), (EXTRA == 1)>(w, g, mu, v, nib, off < len, a.s);
+        adams_entries4<(EXTRA == 2), (EXTRA == 1 || EXTRA == kMuBf16Emit)>(w, g, mu, v, nib, off < len, a.s);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
         if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
             const vu2_t h = {f32x2_to_bf16_rne(mu[0], mu[1]), f32x2_to_bf16_rne(mu[2], mu[3])};
@@ -385,7 +388,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     SpanCtx c;
     span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
     Chunk<BF16> first;
-    chunk_load<BF16, (!REFRESH || can_count(EXTRA)), (REFRESH && can_count(EXTRA)), EXTRA == kMuBf16>(first, c.b, first_offset(c, lane));
+    chunk_load<BF16, (!REFRESH || can_count(EXTRA)), (REFRESH && can_count(EXTRA)), mu_is_bf16(EXTRA)>(first, c.b, first_offset(c, lane));
     if constexpr (REFRESH && can_count(EXTRA)) {
         __shared__ StatsShared stats_shared;
         span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial, &stats_shared);

@@ -107,8 +107,7 @@ static cast_status validate_step(const float *w, const void *grad, const float *
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
     if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE | CAST_FLAG_MU_BF16)) return CAST_ERR_CONFIG;
     if (cfg->rule < CAST_RULE_ADAMS || cfg->rule > CAST_RULE_MASKED_FROZEN) return CAST_ERR_CONFIG;
-    if ((cfg->flags & CAST_FLAG_MU_BF16) && ((cfg->rule != CAST_RULE_ADAMS && cfg->rule != CAST_RULE_ADDITIVE) || compute_copy))
-        return CAST_ERR_CONFIG;
+    if ((cfg->flags & CAST_FLAG_MU_BF16) && cfg->rule != CAST_RULE_ADAMS && cfg->rule != CAST_RULE_ADDITIVE) return CAST_ERR_CONFIG;
     // the bias corrections divide: they must be positive finite numbers (1 - beta^s with s >= 1)
     if (!(cfg->bias_corr1 > 0.0f) || !(cfg->bias_corr2 > 0.0f) || isinf(cfg->bias_corr1) || isinf(cfg->bias_corr2))
         return CAST_ERR_CONFIG;

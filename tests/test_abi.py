@@ -124,7 +124,7 @@ def test_validation_happens_before_any_launch(lib):
     assert step(p, p, p, p, p, nul, nul, 4, 66, 66, C.byref(mu16()), st) == -2
     assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(mu16(rule=1)), st) == -5
     assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(mu16(rule=4)), st) == -5
-    assert emit(p, p, p, p, p, nul, nul, nul, p, 4, 64, 64, C.byref(mu16()), st) == -5
+    assert emit(p, p, p, p, p, nul, nul, nul, p, 4, 64, 64, C.byref(mu16(rule=2)), st) == -5
     # list call: rejected as a whole if any matrix is bad, before anything is enqueued
     T = B._Tensor
     good = T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64)

@@ -152,3 +152,44 @@ def test_mu_bf16_sampled_rows_of_full_size_matrices(rows, cols):
     assert_same_bits(host(w[idx]), ow, "w")
     assert_same_bits(_mu(m[idx]), om, "mu")
     assert_same_bits(host(v[idx]), ov, "v")
+
+
+@pytest.mark.parametrize("rows,cols,nseg", [(16, 1024, 2), (16, 1024, 0), (7, 72, 3), (5, 11008, 2), (6, 5120, 2), (33, 4096 + 32, 1)])
+@pytest.mark.parametrize("refresh", [0, 1])
+def test_mu_bf16_step_also_writes_the_compute_copy(rows, cols, nseg, refresh):
+    """The bf16 first moment together with the bf16 compute copy of the next forward pass (24.125 B/param): single
+    call and list call (three equal matrices, which share a launch), dense and row-interleaved state."""
+    rng = np.random.default_rng(rows + cols)
+    w0 = synth.weights(24, 1, rows, cols)
+    w0[0, :8] = [np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-40, 3e38, -3e38]
+    gb = synth.grads_bf16(24, 1, 0, rows, cols)
+    A = (1 + 0.2 * rng.standard_normal((rows, nseg))).astype(np.float32) if nseg else None
+    cfg = B.iteration_config(3, 10, mask_period=1, lr=1e-3, lambda_=1e-3, scale_segments=nseg)
+    cfg.refresh_mask = refresh
+    cfg.flags |= B.FLAG_MU_BF16
+    o = OracleState(w0, "f32")
+    o.keep[:] = oracle.nm_select(w0, 2, 4)
+    o.step(synth.widen_bf16(gb), oracle_cfg(cfg), A=A)
+    want = oracle.bf16_rne(o.w if A is None else oracle.weight_scale(o.w, A))
+    for interleaved, as_list in ((False, False), (True, False), (True, True), (False, True)):
+        if interleaved and cols % 8:
+            continue
+        states = [GpuState(w0, nseg, interleaved=interleaved, mu_bf16=True) for _ in range(3 if as_list else 1)]
+        copies = [torch.full((rows, cols), 7.0, dtype=torch.bfloat16, device=DEV) for _ in states]
+        for st in states:
+            B.cast_nm_select(st.w, 2, 4, st.mask)
+        scale = None if A is None else dev(A)
+        if as_list:
+            tl = B.TensorList([dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=gb.to(DEV), compute_copy=c, copy_scale=scale,
+                                    scale=scale, scale_grad=st.scale_grad if nseg else None) for st, c in zip(states, copies)], DEV)
+            B.cast_adams_step_multi(tl, cfg)
+        else:
+            B.cast_adams_step_emit(states[0].w, gb.to(DEV), states[0].m, states[0].v, states[0].mask, cfg, copies[0], copy_scale=scale,
+                                   scale=scale, scale_grad=states[0].scale_grad if nseg else None)
+        torch.cuda.synchronize()
+        for st, c in zip(states, copies):
+            assert_same_bits(host(st.w), o.w, "w")
+            assert_same_bits(_mu(st.m), o.m, "mu")
+            assert_same_bits(host(st.v), o.v, "v")
+            got = host(c.view(torch.int16)).view(np.uint16)
+            assert (got == want).all(), (interleaved, as_list, int((got != want).sum()))

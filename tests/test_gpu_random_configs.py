@@ -43,7 +43,7 @@ def test_random_configurations_match_the_oracle(seed):
         if mu16 and rnd.random() < 0.3:
             rule = 3
         bf16 = rnd.random() < 0.6
-        emit = (not mu16) and rnd.random() < 0.3
+        emit = rnd.random() < 0.3
         stats = (not mu16) and rnd.random() < 0.3
         queue = rnd.random() < 0.2
         steps = rnd.randint(2, 4)
