@@ -69,8 +69,9 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  * as when the rows of the three arrays are interleaved in one allocation).  The new mu is rounded
  * to nearest even when stored; mu~, v and the update of the same iteration use the unrounded
  * value.  22.125 instead of 26.125 bytes per parameter.  Only with CAST_RULE_ADAMS and
- * CAST_RULE_ADDITIVE, and without refresh statistics (else CAST_ERR_CONFIG); the compute copy
- * can be written along (24.125 bytes per parameter); the work queue flag is ignored with it. */
+ * CAST_RULE_ADDITIVE, and without refresh statistics (else CAST_ERR_CONFIG; cast_mask_stats
+ * gives the same numbers in a pass of its own); the compute copy can be written along (24.125
+ * bytes per parameter); the work queue flag is ignored with it. */
 #define CAST_FLAG_MU_BF16 4u
 
 /* Update rules.  CAST_RULE_ADAMS is the paper's method (Algorithm 1, Eq. 8); the others are the
