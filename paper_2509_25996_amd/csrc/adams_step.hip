@@ -245,17 +245,7 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
         hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, 1>), grid, block, 0, st, a);
         return;
     }
-    {
-        // experiment knob: cap the resident wavefronts per compute unit by reserving LDS per workgroup
-        static const int cap = env_int("CAST_STATIC_WAVES_PER_CU", 0);
-        unsigned lds = 0;
-        if (cap > 0) {
-            int blocks = cap / (l.block_threads / kWave);
-            if (blocks < 1) blocks = 1;
-            lds = (unsigned)(160 * 1024 / blocks) - 1024;
-        }
-        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), grid, block, lds, st, a);
-    }
+    hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), grid, block, 0, st, a);
 }
 
 template <int M, bool BF16>
