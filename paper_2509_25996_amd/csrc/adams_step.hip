@@ -53,6 +53,14 @@ struct StatsJobQueue {
 };
 
 
+// The kernel flavour of a comparison rule with code of its own: lean, or the one that can also write
+// the compute copy and gather statistics.
+static int rule_flavour(int rule, bool copy_or_stats)
+{
+    if (copy_or_stats) return kAnyRule;
+    return rule == CAST_RULE_ADAMW_L1 ? kOnlyAdamwL1 : rule == CAST_RULE_ADAM_L1 ? kOnlyAdamL1 : kOnlyFrozen;
+}
+
 static int env_int(const char *name, int fallback)
 {
     const char *e = getenv(name);
@@ -189,8 +197,20 @@ struct VecLaunch {
     uint32_t blocks_per_matrix;
     int log2_run;
     bool split;
-    int extra;       // 0, 1 (compute copy) or 2 (comparison rule, with or without compute copy): the EXTRA instantiations
+    int extra;       // the kernel flavour (EXTRA of adams_step_vec)
 };
+
+template <int M, bool BF16, bool REFRESH, bool SCALED, int EXTRA>
+static void launch_vec_flavour(const VecLaunch &l, const SpanArgs &a, dim3 grid, dim3 block, hipStream_t st)
+{
+    if constexpr (SCALED) {
+        if (l.split) {
+            hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, EXTRA>), grid, block, 0, st, a);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, EXTRA>), grid, block, 0, st, a);
+}
 
 template <int M, bool BF16, bool REFRESH, bool SCALED>
 static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
@@ -207,45 +227,22 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
         hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), block, 0, st, a, q);
         return;
     }
-    if constexpr (REFRESH) {      // refresh statistics without a compute copy: a flavour of the refresh kernels only
-        if (l.extra == kStatsOnly) {
-            if constexpr (SCALED) {
-                if (l.split) {
-                    hipLaunchKernelGGL((adams_step_vec<M, BF16, true, true, true, kStatsOnly>), grid, block, 0, st, a);
-                    return;
-                }
-            }
-            hipLaunchKernelGGL((adams_step_vec<M, BF16, true, SCALED, false, kStatsOnly>), grid, block, 0, st, a);
-            return;
+    switch (l.extra) {
+    case 1: launch_vec_flavour<M, BF16, REFRESH, SCALED, 1>(l, a, grid, block, st); break;
+    case kAnyRule: launch_vec_flavour<M, BF16, REFRESH, SCALED, kAnyRule>(l, a, grid, block, st); break;
+    case kMuBf16: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16>(l, a, grid, block, st); break;
+    case kMuBf16Emit: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16Emit>(l, a, grid, block, st); break;
+    case kOnlyAdamwL1: launch_vec_flavour<M, BF16, REFRESH, SCALED, kOnlyAdamwL1>(l, a, grid, block, st); break;
+    case kOnlyAdamL1: launch_vec_flavour<M, BF16, REFRESH, SCALED, kOnlyAdamL1>(l, a, grid, block, st); break;
+    case kOnlyFrozen: launch_vec_flavour<M, BF16, REFRESH, SCALED, kOnlyFrozen>(l, a, grid, block, st); break;
+    case kStatsOnly:      // refresh statistics without a compute copy: a flavour of the refresh kernels only
+        if constexpr (REFRESH) {
+            launch_vec_flavour<M, BF16, true, SCALED, kStatsOnly>(l, a, grid, block, st);
+            break;
         }
+        [[fallthrough]];
+    default: launch_vec_flavour<M, BF16, REFRESH, SCALED, 0>(l, a, grid, block, st); break;
     }
-    if constexpr (SCALED) {
-        if (l.split) {
-            if (l.extra == kMuBf16) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, kMuBf16>), grid, block, 0, st, a);
-            else if (l.extra == kMuBf16Emit) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, kMuBf16Emit>), grid, block, 0, st, a);
-            else if (l.extra == 2) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 2>), grid, block, 0, st, a);
-            else if (l.extra == 1) hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true, 1>), grid, block, 0, st, a);
-            else hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, true, true>), grid, block, 0, st, a);
-            return;
-        }
-    }
-    if (l.extra == kMuBf16) {
-        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, kMuBf16>), grid, block, 0, st, a);
-        return;
-    }
-    if (l.extra == kMuBf16Emit) {
-        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, kMuBf16Emit>), grid, block, 0, st, a);
-        return;
-    }
-    if (l.extra == 2) {
-        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, 2>), grid, block, 0, st, a);
-        return;
-    }
-    if (l.extra == 1) {
-        hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, 1>), grid, block, 0, st, a);
-        return;
-    }
-    hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED>), grid, block, 0, st, a);
 }
 
 template <int M, bool BF16>
@@ -324,12 +321,12 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     if (refresh && x.refresh_stats != nullptr && !stats) return CAST_ERR_SHAPE;      // workspace too small (not reachable through the API)
     StatsPartial *stats_partials = stats ? take_stats_slots(x.stats_area, stats_slots, x.refresh_stats, x.initial_mask) : nullptr;
     const uint32_t *stats_initial = stats ? x.initial_mask : nullptr;
-    // a compute copy to write or refresh statistics to gather (1), or a comparison rule with code of
-    // its own (2): the EXTRA instantiations
+    // the kernel flavour: a compute copy to write or refresh statistics to gather (1), a comparison rule
+    // with code of its own (its lean flavour, or 2 when it comes with either of those)
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     // (a first moment kept in bf16 comes with the compute copy at most: the API has seen to that)
     const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
-    const int extra = mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? 2 : (x.compute_copy != nullptr ? 1 : (stats ? kStatsOnly : 0)));
+    const int extra = mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? rule_flavour(cfg->rule, x.compute_copy != nullptr || stats) : (x.compute_copy != nullptr ? 1 : (stats ? kStatsOnly : 0)));
     p.geom.m_row_gap = mu_bf16_ld(cols, ld) - cols;
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
@@ -373,8 +370,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 
 // Up to kMaxFused matrices of one shape in one launch (no split plan): the ramp-up and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a
 // 4096 x 4096 matrix takes.  `flavour`: 0 plain; 1: the matrices have compute copies to write (and
-// may gather refresh statistics); 2: a comparison rule, with or without either; 4: refresh statistics
-// only; each matrix its own buffers.
+// may gather refresh statistics); 2: a comparison rule with either; 4: refresh statistics only; 6, 7, 8: a
+// comparison rule alone; each matrix its own buffers.
 static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
                                            int flavour, StatsArea *stats_area, hipStream_t st)
 {
@@ -385,7 +382,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
     for (int k = 0; k < n; ++k) {
         const cast_tensor &t = *ts[k];
         StatsPartial *partials = nullptr;
-        if (flavour != 0 && refresh && t.refresh_stats) {
+        if (can_count(flavour) && refresh && t.refresh_stats) {
             if (stats_area == nullptr || p.grid > stats_area->slots) return CAST_ERR_SHAPE;      // (not reachable through the API)
             partials = take_stats_slots(stats_area, p.grid, t.refresh_stats, t.initial_mask_bits);
         }
@@ -605,7 +602,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         return stats_jobs.count + n > kMaxStatsJobs ? stats_jobs.flush(st) : CAST_OK;
     };
     auto flavour_of = [&](const cast_tensor &t) {      // of the kernels a matrix needs
-        if (own_rule) return 2;
+        if (own_rule) return rule_flavour(cfg->rule, t.compute_copy != nullptr || (want_stats && t.refresh_stats != nullptr));
         return t.compute_copy != nullptr ? 1 : ((want_stats && t.refresh_stats != nullptr) ? kStatsOnly : 0);
     };
     for (int i = 0; i < count; ++i) {

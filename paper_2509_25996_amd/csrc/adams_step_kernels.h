@@ -65,13 +65,22 @@ static ConstTable as_const_table(const void *device_ptr)
 // gather refresh statistics; 2 knows, on top, the comparison update rules with code of their own;
 // 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16); 4 plain that can gather refresh
 // statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0);
-// 5 the first moment in bf16 and the compute copy.
+// 5 the first moment in bf16 and the compute copy; 6, 7, 8 one comparison rule each (Eq. 9, Eq. 10, frozen
+// masked entries) fixed at compile time and nothing else: unlike flavour 2, which reads the rule from
+// a.s.rule and pays for all of them in registers, these keep 8 wavefronts per SIMD.
 constexpr bool can_emit(int extra) { return extra == 1 || extra == 2 || extra == 5; }
 constexpr bool can_count(int extra) { return extra == 1 || extra == 2 || extra == 4; }
 constexpr bool mu_is_bf16(int extra) { return extra == 3 || extra == 5; }
 constexpr int kMuBf16 = 3;
 constexpr int kMuBf16Emit = 5;
 constexpr int kStatsOnly = 4;
+constexpr int kAnyRule = 2;
+constexpr int kOnlyAdamwL1 = 6, kOnlyAdamL1 = 7, kOnlyFrozen = 8;
+// the rule argument of adams_entries4: 0 none, -1 read from the scalars, else the rule itself
+constexpr int rule_of(int extra)
+{
+    return extra == kAnyRule ? -1 : extra == kOnlyAdamwL1 ? kRuleAdamwL1 : extra == kOnlyAdamL1 ? kRuleAdamL1 : extra == kOnlyFrozen ? kRuleMaskedFrozen : 0;
+}
 
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
 template <bool BF16>
@@ -301,7 +310,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
                 g[j] = A * g[j];                                         // chain rule of Eq. 12
             }
         }
-        adams_entries4<(EXTRA == 2), (EXTRA == 1 || EXTRA == kMuBf16Emit)>(w, g, mu, v, nib, off < len, a.s);
+        adams_entries4<rule_of(EXTRA), (EXTRA == 1 || EXTRA == kMuBf16Emit)>(w, g, mu, v, nib, off < len, a.s);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
         if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
             const vu2_t h = {f32x2_to_bf16_rne(mu[0], mu[1]), f32x2_to_bf16_rne(mu[2], mu[3])};
@@ -378,7 +387,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
 // EXTRA = 3: the first moment is kept in bf16.
 // EXTRA = 1: instantiations that can also write the bf16 compute copy; EXTRA = 2: those that, on
 // top, know the comparison update rules (a.s.rule), at the price of 12 more registers and one
-// wavefront per SIMD less.  The plain ones (0) carry none of that code.
+// wavefront per SIMD less; EXTRA = 6, 7, 8: one rule alone.  The plain ones (0) carry none of that code.
 template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false, int EXTRA = 0>
 __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
 {
@@ -445,7 +454,7 @@ __device__ __forceinline__ void chunk_step(const SpanArgs &a, const SpanCtx &c, 
             g[j] = c.A * g[j];
         }
     }
-    adams_entries4<false, false>(w, g, mu, v, nib, off < c.len, a.s);
+    adams_entries4<0, false>(w, g, mu, v, nib, off < c.len, a.s);
     __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
     __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
     __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);

@@ -505,39 +505,42 @@ __device__ __forceinline__ float div_short_any(float x, float d)
 // among the 8 dividends of the live lanes: 2^-63 <= |mu~|, v < 2^66 (so zeros, denormals, inf
 // take the long forms; a NaN goes through either form as a NaN).  `live` is false for lanes
 // past the end of the span, whose zeros must not force the long forms.
-// EXTRA: the comparison rules of s.rule are honoured (Eq. 9, Eq. 10, frozen masked entries);
-// without it the code is Algorithm 1 alone.  Nothing of the incoming state is set aside for the
+// RULE: 0 is Algorithm 1 alone; a comparison rule (Eq. 9, Eq. 10, frozen masked entries) given here is
+// honoured, -1 stands for the one in s.rule.  Nothing of the incoming state is set aside for the
 // rules (registers decide how many wavefronts a compute unit holds): what a rule needs of the
 // old values is used before they are overwritten.
 // ONE_LOOP only chooses between two spellings of the same arithmetic (the short/long decision
 // inside or outside the loop over the four entries); which one the compiler schedules better was
 // measured per kernel flavour: outside for the plain step, inside when the compute copy is written
 // (6 % on that step).
-template <bool EXTRA = false, bool ONE_LOOP = false>
+template <int RULE = 0, bool ONE_LOOP = false>
 __device__ __forceinline__ void adams_entries4(float (&w)[4], float (&g)[4], float (&mu)[4],
                                                float (&v)[4], uint32_t nib, bool live,
                                                const StepScalars &s)
 {
     float mt[4], vt[4];
-    uint32_t nib_moments = nib;      // which entries count as kept inside the moments
-    uint32_t held = 0;               // which entries are not updated at all
-    uint32_t decayed_step = 0;       // which entries get the decay beside the adaptive step
-    if constexpr (EXTRA) {
-        if (s.rule == kRuleAdamL1) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if (!((nib >> j) & 1u)) g[j] = g[j] + decay_term(w[j], s);            // Eq. 10
-        }
-        if (s.rule == kRuleAdamwL1 || s.rule == kRuleAdamL1) nib_moments = 0xFu;     // no decay on the momentum
-        if (s.rule == kRuleAdamwL1) decayed_step = ~nib & 0xFu;                      // Eq. 9
-        if (s.rule == kRuleMaskedFrozen) held = ~nib & 0xFu;                         // Sec. 5.7
+    // what the rule changes, as wave-uniform switches; which entries they touch is read off nib where needed
+    bool l1_in_grad = false, keep_all_in_moments = false, l1_beside_step = false, frozen = false;
+    if constexpr (RULE != 0) {
+        const int rule_ = RULE < 0 ? s.rule : RULE;
+        l1_in_grad = rule_ == kRuleAdamL1;                                           // Eq. 10
+        keep_all_in_moments = rule_ == kRuleAdamwL1 || rule_ == kRuleAdamL1;        // no decay on the momentum
+        l1_beside_step = rule_ == kRuleAdamwL1;                                      // Eq. 9
+        frozen = rule_ == kRuleMaskedFrozen;                                         // Sec. 5.7
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
+        const bool kept = (nib >> j) & 1u;
+        if constexpr (RULE != 0) {
+            if (l1_in_grad && !kept) g[j] = g[j] + decay_term(w[j], s);
+        }
         float mu_new = mu[j];
-        adams_moments(w[j], g[j], mu_new, v[j], (nib_moments >> j) & 1u, s, mt[j], vt[j]);
-        if constexpr (EXTRA) mu[j] = ((held >> j) & 1u) ? mu[j] : mu_new;
-        else mu[j] = mu_new;
+        adams_moments(w[j], g[j], mu_new, v[j], kept || keep_all_in_moments, s, mt[j], vt[j]);
+        if constexpr (RULE != 0) {
+            mu[j] = (frozen && !kept) ? mu[j] : mu_new;           // a frozen entry keeps its moments
+        } else {
+            mu[j] = mu_new;
+        }
     }
     float lo = __builtin_fminf(__builtin_fabsf(mt[0]), __builtin_fabsf(mt[1]));
     float hi = __builtin_fmaxf(__builtin_fabsf(mt[0]), __builtin_fabsf(mt[1]));
@@ -546,19 +549,25 @@ __device__ __forceinline__ void adams_entries4(float (&w)[4], float (&g)[4], flo
 #pragma unroll
     for (int j = 0; j < 4; ++j) { lo = __builtin_fminf(lo, vt[j]); hi = __builtin_fmaxf(hi, vt[j]); }
     const bool out_of_range = !(lo >= 0x1p-63f) || !(hi < 0x1p66f);
+    if constexpr (RULE != 0) {
+        // a frozen entry: its old v takes the place of the new one from here on (the quotient computed from
+        // it is not used; the choice of forms above has seen the new one), so that the old state need not
+        // stay in registers through the divisions
+#pragma unroll
+        for (int j = 0; j < 4; ++j) vt[j] = (frozen && !((nib >> j) & 1u)) ? v[j] : vt[j];
+    }
     // what the rules change after the adaptive step q = mu^ / (sqrt(v^) + eps) is known
     auto finish = [&](int j, float q) {
-        if constexpr (EXTRA) {
-            if ((decayed_step >> j) & 1u) q = q + decay_term(w[j], s);
-        }
-        const float step = s.lr * q;
-        if constexpr (EXTRA) {
-            w[j] = ((held >> j) & 1u) ? w[j] : w[j] - step;
-            v[j] = ((held >> j) & 1u) ? v[j] : vt[j];
+        if constexpr (RULE != 0) {
+            const bool kept = (nib >> j) & 1u;
+            if (l1_beside_step && !kept) q = q + decay_term(w[j], s);
+            const float step = s.lr * q;
+            w[j] = (frozen && !kept) ? w[j] : w[j] - step;
         } else {
+            const float step = s.lr * q;
             w[j] = w[j] - step;
-            v[j] = vt[j];
         }
+        v[j] = vt[j];
     };
     const bool short_forms = s.short_forms && !__any(out_of_range && live);      // wave-uniform
     if constexpr (ONE_LOOP) {
