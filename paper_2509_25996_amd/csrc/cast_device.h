@@ -411,7 +411,10 @@ constexpr int kRuleAdamwL1 = 1, kRuleAdamL1 = 2, kRuleMaskedFrozen = 4;
 // alpha*lambda*Sign(w) with Sign(+-0) = Sign(NaN) = 0: the three possible products come from the host
 __device__ __forceinline__ float decay_term(float w, const StepScalars &s)
 {
-    return w > 0.0f ? s.decay_pos : (w < 0.0f ? s.decay_neg : s.decay_zero);
+    // the three values are read before the choice: read inside its arms, the compiler merges the reads into
+    // one per-lane load from the kernel arguments at a chosen address, a vector memory access per entry
+    const float pos = s.decay_pos, neg = s.decay_neg, zero = s.decay_zero;
+    return w > 0.0f ? pos : (w < 0.0f ? neg : zero);
 }
 
 // Every line below is one correctly rounded fp32 operation: the library is compiled with
@@ -532,7 +535,10 @@ __device__ __forceinline__ void adams_entries4(float (&w)[4], float (&g)[4], flo
     for (int j = 0; j < 4; ++j) {
         const bool kept = (nib >> j) & 1u;
         if constexpr (RULE != 0) {
-            if (l1_in_grad && !kept) g[j] = g[j] + decay_term(w[j], s);
+            if (l1_in_grad) {
+                const float decayed = g[j] + decay_term(w[j], s);
+                g[j] = kept ? g[j] : decayed;
+            }
         }
         float mu_new = mu[j];
         adams_moments(w[j], g[j], mu_new, v[j], kept || keep_all_in_moments, s, mt[j], vt[j]);
@@ -560,9 +566,13 @@ __device__ __forceinline__ void adams_entries4(float (&w)[4], float (&g)[4], flo
     auto finish = [&](int j, float q) {
         if constexpr (RULE != 0) {
             const bool kept = (nib >> j) & 1u;
-            if (l1_beside_step && !kept) q = q + decay_term(w[j], s);
+            if (l1_beside_step) {
+                const float decayed = q + decay_term(w[j], s);
+                q = kept ? q : decayed;
+            }
             const float step = s.lr * q;
-            w[j] = (frozen && !kept) ? w[j] : w[j] - step;
+            const float stepped = w[j] - step;
+            w[j] = (frozen && !kept) ? w[j] : stepped;
         } else {
             const float step = s.lr * q;
             w[j] = w[j] - step;
