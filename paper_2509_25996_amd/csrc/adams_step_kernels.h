@@ -386,8 +386,8 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
 // workgroup leaves the dL/dA sum of its piece in a[.].piece_sums and sum_piece_sums adds them up.
 // EXTRA = 3: the first moment is kept in bf16.
 // EXTRA = 1: instantiations that can also write the bf16 compute copy; EXTRA = 2: those that, on
-// top, know the comparison update rules (a.s.rule), at the price of 12 more registers and one
-// wavefront per SIMD less; EXTRA = 6, 7, 8: one rule alone.  The plain ones (0) carry none of that code.
+// top, know the comparison update rules (a.s.rule), at the price of 15 to 25 more registers and one to
+// three wavefronts per SIMD less; EXTRA = 6, 7, 8: one rule alone.  The plain ones (0) carry none of that code.
 template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false, int EXTRA = 0>
 __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
 {
