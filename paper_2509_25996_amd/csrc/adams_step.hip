@@ -53,12 +53,10 @@ struct StatsJobQueue {
 };
 
 
-// The kernel flavour of a comparison rule with code of its own: lean, or the one that can also write
-// the compute copy and gather statistics.
-static int rule_flavour(int rule, bool copy_or_stats)
+// The comparison rule as the kernel flavour carries it: those with code of their own, else none.
+static int flavour_rule(int rule)
 {
-    if (copy_or_stats) return kAnyRule;
-    return rule == CAST_RULE_ADAMW_L1 ? kOnlyAdamwL1 : rule == CAST_RULE_ADAM_L1 ? kOnlyAdamL1 : kOnlyFrozen;
+    return rule == CAST_RULE_ADAMW_L1 ? kRuleAdamwL1 : rule == CAST_RULE_ADAM_L1 ? kRuleAdamL1 : rule == CAST_RULE_MASKED_FROZEN ? kRuleMaskedFrozen : 0;
 }
 
 static int env_int(const char *name, int fallback)
@@ -212,6 +210,30 @@ static void launch_vec_flavour(const VecLaunch &l, const SpanArgs &a, dim3 grid,
     hipLaunchKernelGGL((adams_step_vec<M, BF16, REFRESH, SCALED, false, EXTRA>), grid, block, 0, st, a);
 }
 
+// The rules combine with the plain kernel and with the one that can write the compute copy and gather
+// statistics; the other abilities exist for AdamS (and additive decay, which is AdamS to the kernels) only.
+template <int M, bool BF16, bool REFRESH, bool SCALED, int RULE>
+static void launch_vec_abilities(const VecLaunch &l, const SpanArgs &a, dim3 grid, dim3 block, hipStream_t st)
+{
+    if constexpr (RULE != 0) {
+        if (abilities(l.extra) != 0) launch_vec_flavour<M, BF16, REFRESH, SCALED, with_rule(kEmitAndCount, RULE)>(l, a, grid, block, st);
+        else launch_vec_flavour<M, BF16, REFRESH, SCALED, with_rule(0, RULE)>(l, a, grid, block, st);
+    } else {
+        switch (abilities(l.extra)) {
+        case kEmitAndCount: launch_vec_flavour<M, BF16, REFRESH, SCALED, kEmitAndCount>(l, a, grid, block, st); break;
+        case kMuBf16: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16>(l, a, grid, block, st); break;
+        case kMuBf16Emit: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16Emit>(l, a, grid, block, st); break;
+        case kStatsOnly:      // refresh statistics without a compute copy: a flavour of the refresh kernels only
+            if constexpr (REFRESH) {
+                launch_vec_flavour<M, BF16, true, SCALED, kStatsOnly>(l, a, grid, block, st);
+                break;
+            }
+            [[fallthrough]];
+        default: launch_vec_flavour<M, BF16, REFRESH, SCALED, 0>(l, a, grid, block, st); break;
+        }
+    }
+}
+
 template <int M, bool BF16, bool REFRESH, bool SCALED>
 static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
@@ -227,21 +249,11 @@ static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t
         hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), block, 0, st, a, q);
         return;
     }
-    switch (l.extra) {
-    case 1: launch_vec_flavour<M, BF16, REFRESH, SCALED, 1>(l, a, grid, block, st); break;
-    case kAnyRule: launch_vec_flavour<M, BF16, REFRESH, SCALED, kAnyRule>(l, a, grid, block, st); break;
-    case kMuBf16: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16>(l, a, grid, block, st); break;
-    case kMuBf16Emit: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16Emit>(l, a, grid, block, st); break;
-    case kOnlyAdamwL1: launch_vec_flavour<M, BF16, REFRESH, SCALED, kOnlyAdamwL1>(l, a, grid, block, st); break;
-    case kOnlyAdamL1: launch_vec_flavour<M, BF16, REFRESH, SCALED, kOnlyAdamL1>(l, a, grid, block, st); break;
-    case kOnlyFrozen: launch_vec_flavour<M, BF16, REFRESH, SCALED, kOnlyFrozen>(l, a, grid, block, st); break;
-    case kStatsOnly:      // refresh statistics without a compute copy: a flavour of the refresh kernels only
-        if constexpr (REFRESH) {
-            launch_vec_flavour<M, BF16, true, SCALED, kStatsOnly>(l, a, grid, block, st);
-            break;
-        }
-        [[fallthrough]];
-    default: launch_vec_flavour<M, BF16, REFRESH, SCALED, 0>(l, a, grid, block, st); break;
+    switch (rule_of(l.extra)) {
+    case kRuleAdamwL1: launch_vec_abilities<M, BF16, REFRESH, SCALED, kRuleAdamwL1>(l, a, grid, block, st); break;
+    case kRuleAdamL1: launch_vec_abilities<M, BF16, REFRESH, SCALED, kRuleAdamL1>(l, a, grid, block, st); break;
+    case kRuleMaskedFrozen: launch_vec_abilities<M, BF16, REFRESH, SCALED, kRuleMaskedFrozen>(l, a, grid, block, st); break;
+    default: launch_vec_abilities<M, BF16, REFRESH, SCALED, 0>(l, a, grid, block, st); break;
     }
 }
 
@@ -321,12 +333,11 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     if (refresh && x.refresh_stats != nullptr && !stats) return CAST_ERR_SHAPE;      // workspace too small (not reachable through the API)
     StatsPartial *stats_partials = stats ? take_stats_slots(x.stats_area, stats_slots, x.refresh_stats, x.initial_mask) : nullptr;
     const uint32_t *stats_initial = stats ? x.initial_mask : nullptr;
-    // the kernel flavour: a compute copy to write or refresh statistics to gather (1), a comparison rule
-    // with code of its own (its lean flavour, or 2 when it comes with either of those)
+    // the kernel flavour: what the kernel has to do besides the step, and the comparison rule if it has code of its own
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     // (a first moment kept in bf16 comes with the compute copy at most: the API has seen to that)
     const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
-    const int extra = mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? rule_flavour(cfg->rule, x.compute_copy != nullptr || stats) : (x.compute_copy != nullptr ? 1 : (stats ? kStatsOnly : 0)));
+    const int extra = mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? with_rule((x.compute_copy != nullptr || stats) ? kEmitAndCount : 0, flavour_rule(cfg->rule)) : (x.compute_copy != nullptr ? kEmitAndCount : (stats ? kStatsOnly : 0)));
     p.geom.m_row_gap = mu_bf16_ld(cols, ld) - cols;
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
@@ -369,9 +380,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 }
 
 // Up to kMaxFused matrices of one shape in one launch (no split plan): the ramp-up and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a
-// 4096 x 4096 matrix takes.  `flavour`: 0 plain; 1: the matrices have compute copies to write (and
-// may gather refresh statistics); 2: a comparison rule with either; 4: refresh statistics only; 6, 7, 8: a
-// comparison rule alone; each matrix its own buffers.
+// 4096 x 4096 matrix takes.  `flavour`: the kernel flavour all of them need (before the bf16 first moment is
+// taken into account); each matrix its own buffers.
 static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
                                            int flavour, StatsArea *stats_area, hipStream_t st)
 {
@@ -391,7 +401,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
                               can_emit(flavour) ? static_cast<uint16_t *>(t.compute_copy) : nullptr, can_emit(flavour) ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? (flavour == 1 ? kMuBf16Emit : kMuBf16) : flavour}, a, st);
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? (flavour == kEmitAndCount ? kMuBf16Emit : kMuBf16) : flavour}, a, st);
     return launch_status();
 }
 
@@ -602,8 +612,8 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         return stats_jobs.count + n > kMaxStatsJobs ? stats_jobs.flush(st) : CAST_OK;
     };
     auto flavour_of = [&](const cast_tensor &t) {      // of the kernels a matrix needs
-        if (own_rule) return rule_flavour(cfg->rule, t.compute_copy != nullptr || (want_stats && t.refresh_stats != nullptr));
-        return t.compute_copy != nullptr ? 1 : ((want_stats && t.refresh_stats != nullptr) ? kStatsOnly : 0);
+        if (own_rule) return with_rule((t.compute_copy != nullptr || (want_stats && t.refresh_stats != nullptr)) ? kEmitAndCount : 0, flavour_rule(cfg->rule));
+        return t.compute_copy != nullptr ? kEmitAndCount : ((want_stats && t.refresh_stats != nullptr) ? kStatsOnly : 0);
     };
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;

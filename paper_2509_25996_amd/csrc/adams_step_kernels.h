@@ -61,26 +61,22 @@ static ConstTable as_const_table(const void *device_ptr)
     return (ConstTable)(uintptr_t)device_ptr;
 }
 
-// Kernel flavours (template argument EXTRA): 0 plain; 1 can also write the bf16 compute copy and
-// gather refresh statistics; 2 knows, on top, the comparison update rules with code of their own;
-// 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16); 4 plain that can gather refresh
-// statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0);
-// 5 the first moment in bf16 and the compute copy; 6, 7, 8 one comparison rule each (Eq. 9, Eq. 10, frozen
-// masked entries) fixed at compile time and nothing else: unlike flavour 2, which reads the rule from
-// a.s.rule and pays for all of them in registers, these keep 8 wavefronts per SIMD.
-constexpr bool can_emit(int extra) { return extra == 1 || extra == 2 || extra == 5; }
-constexpr bool can_count(int extra) { return extra == 1 || extra == 2 || extra == 4; }
-constexpr bool mu_is_bf16(int extra) { return extra == 3 || extra == 5; }
+// Kernel flavours (template argument EXTRA) = what the kernel can do besides Algorithm 1, in the low four bits,
+// plus the comparison rule it applies (Eq. 9, Eq. 10, frozen masked entries; 0: none), fixed at compile time,
+// shifted left by four.  The low bits: 0 plain; 1 can also write the bf16 compute copy and gather refresh
+// statistics; 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16); 4 plain that can gather refresh
+// statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0); 5 the
+// first moment in bf16 and the compute copy.  The rules combine with 0 and 1.
+constexpr int kEmitAndCount = 1;
 constexpr int kMuBf16 = 3;
-constexpr int kMuBf16Emit = 5;
 constexpr int kStatsOnly = 4;
-constexpr int kAnyRule = 2;
-constexpr int kOnlyAdamwL1 = 6, kOnlyAdamL1 = 7, kOnlyFrozen = 8;
-// the rule argument of adams_entries4: 0 none, -1 read from the scalars, else the rule itself
-constexpr int rule_of(int extra)
-{
-    return extra == kAnyRule ? -1 : extra == kOnlyAdamwL1 ? kRuleAdamwL1 : extra == kOnlyAdamL1 ? kRuleAdamL1 : extra == kOnlyFrozen ? kRuleMaskedFrozen : 0;
-}
+constexpr int kMuBf16Emit = 5;
+constexpr int abilities(int extra) { return extra & 15; }
+constexpr int rule_of(int extra) { return extra >> 4; }      // kRuleAdamwL1, kRuleAdamL1, kRuleMaskedFrozen or 0
+constexpr int with_rule(int extra, int rule) { return extra | (rule << 4); }
+constexpr bool can_emit(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kMuBf16Emit; }
+constexpr bool can_count(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kStatsOnly; }
+constexpr bool mu_is_bf16(int extra) { return abilities(extra) == kMuBf16 || abilities(extra) == kMuBf16Emit; }
 
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
 template <bool BF16>
@@ -310,7 +306,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
                 g[j] = A * g[j];                                         // chain rule of Eq. 12
             }
         }
-        adams_entries4<rule_of(EXTRA), (EXTRA == 1 || EXTRA == kMuBf16Emit)>(w, g, mu, v, nib, off < len, a.s);
+        adams_entries4<rule_of(EXTRA), can_emit(EXTRA)>(w, g, mu, v, nib, off < len, a.s);
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
         if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
             const vu2_t h = {f32x2_to_bf16_rne(mu[0], mu[1]), f32x2_to_bf16_rne(mu[2], mu[3])};
@@ -384,10 +380,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
 // One matrix, one workgroup per share, dealt by the hardware dispatcher.  SPLIT: the spans are
 // pieces of row segments (Eq. 12) too long for one workgroup of short-lived wavefronts; each
 // workgroup leaves the dL/dA sum of its piece in a[.].piece_sums and sum_piece_sums adds them up.
-// EXTRA = 3: the first moment is kept in bf16.
-// EXTRA = 1: instantiations that can also write the bf16 compute copy; EXTRA = 2: those that, on
-// top, know the comparison update rules (a.s.rule), at the price of 15 to 25 more registers and one to
-// three wavefronts per SIMD less; EXTRA = 6, 7, 8: one rule alone.  The plain ones (0) carry none of that code.
+// EXTRA: the kernel flavour (above); the plain ones (0) carry no code but Algorithm 1's.
 template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false, int EXTRA = 0>
 __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArgs a)
 {

@@ -400,7 +400,7 @@ struct StepScalars {
     int n_keep;
     int v_from_grad;
     int short_forms;       // 1 if the uniform scalars allow the short division / square-root forms
-    int rule;              // CAST_RULE_*; the kernels look at it only in their EXTRA instantiations
+    int rule;              // CAST_RULE_*; read by the one-entry code (adams_entry); the vector kernels have it as a template argument
 };
 
 // The comparison rules (Eq. 9, Eq. 10, Sec. 5.7) as the kernels see them.  Additive decay needs no
@@ -508,8 +508,7 @@ __device__ __forceinline__ float div_short_any(float x, float d)
 // among the 8 dividends of the live lanes: 2^-63 <= |mu~|, v < 2^66 (so zeros, denormals, inf
 // take the long forms; a NaN goes through either form as a NaN).  `live` is false for lanes
 // past the end of the span, whose zeros must not force the long forms.
-// RULE: 0 is Algorithm 1 alone; a comparison rule (Eq. 9, Eq. 10, frozen masked entries) given here is
-// honoured, -1 stands for the one in s.rule.  Nothing of the incoming state is set aside for the
+// RULE: 0 is Algorithm 1 alone, else the comparison rule to apply (Eq. 9, Eq. 10, frozen masked entries).  Nothing of the incoming state is set aside for the
 // rules (registers decide how many wavefronts a compute unit holds): what a rule needs of the
 // old values is used before they are overwritten.
 // ONE_LOOP only chooses between two spellings of the same arithmetic (the short/long decision
@@ -522,14 +521,13 @@ __device__ __forceinline__ void adams_entries4(float (&w)[4], float (&g)[4], flo
                                                const StepScalars &s)
 {
     float mt[4], vt[4];
-    // what the rule changes, as wave-uniform switches; which entries they touch is read off nib where needed
+    // what the rule changes; which entries it touches is read off nib where needed
     bool l1_in_grad = false, keep_all_in_moments = false, l1_beside_step = false, frozen = false;
     if constexpr (RULE != 0) {
-        const int rule_ = RULE < 0 ? s.rule : RULE;
-        l1_in_grad = rule_ == kRuleAdamL1;                                           // Eq. 10
-        keep_all_in_moments = rule_ == kRuleAdamwL1 || rule_ == kRuleAdamL1;        // no decay on the momentum
-        l1_beside_step = rule_ == kRuleAdamwL1;                                      // Eq. 9
-        frozen = rule_ == kRuleMaskedFrozen;                                         // Sec. 5.7
+        l1_in_grad = RULE == kRuleAdamL1;                                            // Eq. 10
+        keep_all_in_moments = RULE == kRuleAdamwL1 || RULE == kRuleAdamL1;           // no decay on the momentum
+        l1_beside_step = RULE == kRuleAdamwL1;                                       // Eq. 9
+        frozen = RULE == kRuleMaskedFrozen;                                          // Sec. 5.7
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
