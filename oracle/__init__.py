@@ -48,7 +48,7 @@ class _Cfg(C.Structure):
                 ("lambda_", C.c_float), ("alpha", C.c_float), ("bias_corr1", C.c_float),
                 ("bias_corr2", C.c_float), ("refresh_mask", C.c_int32),
                 ("scale_segments", C.c_int32), ("v_from_grad", C.c_int32), ("rule", C.c_int32),
-                ("mu_bf16", C.c_int32)]
+                ("mu_bf16", C.c_int32), ("v_bf16", C.c_int32), ("sr_seed", C.c_uint32)]
 
 
 # update rules (the enum of cast_oracle.c)
@@ -73,11 +73,14 @@ class AdamsCfg:
     v_from_grad: int = 0
     rule: int = 0
     mu_bf16: int = 0        # first moment kept in bf16 between iterations (storage variant, not in the paper)
+    v_bf16: int = 0         # second moment kept in bf16 too, stochastically rounded with bits drawn from sr_seed
+    sr_seed: int = 0
 
     def c_struct(self) -> _Cfg:
         return _Cfg(self.n_keep, self.m_group, self.lr, self.beta1, self.beta2, self.eps,
                     self.lambda_, self.alpha, self.bias_corr1, self.bias_corr2,
-                    self.refresh_mask, self.scale_segments, self.v_from_grad, self.rule, self.mu_bf16)
+                    self.refresh_mask, self.scale_segments, self.v_from_grad, self.rule, self.mu_bf16,
+                    self.v_bf16, self.sr_seed & 0xFFFFFFFF)
 
 
 def iteration_scalars(t: int, total_steps: int, beta1: float, beta2: float):
@@ -114,6 +117,10 @@ def lib():
         L.oracle_bf16_rne_array.argtypes = [vp, i64, vp]
         L.oracle_bf16_rne_array.restype = None
         L.oracle_mask_stats.argtypes = [vp, vp, vp, i64, vp, vp, vp]
+        L.oracle_bf16_stochastic.argtypes = [C.c_float, C.c_uint32]
+        L.oracle_bf16_stochastic.restype = C.c_uint16
+        L.oracle_sr_bits.argtypes = [C.c_uint32, C.c_uint64]
+        L.oracle_sr_bits.restype = C.c_uint32
         _lib = L
     return _lib
 
@@ -240,6 +247,16 @@ def project_compress(w, n_keep, m_group, A=None, keep=None):
     if rc:
         raise ValueError(f"oracle_project_compress failed ({rc})")
     return values, meta
+
+
+def bf16_stochastic(x: float, r16: int) -> int:
+    """bf16 bit pattern of the fp32 value x rounded stochastically with the 16 random bits r16."""
+    return int(lib().oracle_bf16_stochastic(float(np.float32(x)), r16 & 0xFFFF))
+
+
+def sr_bits(seed: int, index: int) -> int:
+    """The 16 rounding bits of matrix entry `index` (row * cols + col) under `seed`."""
+    return int(lib().oracle_sr_bits(seed & 0xFFFFFFFF, index))
 
 
 def bf16_rne(x: np.ndarray) -> np.ndarray:

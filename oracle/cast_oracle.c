@@ -29,7 +29,11 @@
  *
  * Parity status: every function here is pinned by tests/test_oracle_*.py except the
  * packed metadata LAYOUT itself, which is this project's own definition ("parity unpinned"
- * by the paper; pinned only by an independent decoder and its invariants).
+ * by the paper; pinned only by an independent decoder and its invariants), and the choice of
+ * generator behind the stochastically rounded bf16 second moment (oracle_sr_bits: which mixer,
+ * which constants, which 16 of its 32 bits are this project's definition, "parity unpinned";
+ * what a rounding needs of it, uniform bits without structure along index and seed, is pinned,
+ * and the rounding itself is pinned exactly).
  */
 #include <math.h>
 #include <stddef.h>
@@ -54,9 +58,28 @@ typedef struct {
                              * storage variant outside the paper): what is stored is the new
                              * mu rounded to nearest-even bf16; everything computed in the
                              * same iteration (mu~, v, the update) uses the unrounded value  */
+    int32_t v_bf16;         /* 1: the second moment is kept in bf16 too, rounded STOCHASTICALLY
+                             * when stored (with beta_2 = 0.999 a step changes v by a thousandth,
+                             * less than half a bf16 unit in the last place: rounded to nearest it
+                             * would never move).  Outside the paper like mu_bf16; the update of
+                             * the same iteration uses the unrounded value.  See
+                             * oracle_bf16_stochastic and oracle_sr_bits.                     */
+    uint32_t sr_seed;       /* seed of the rounding bits; the caller changes it every iteration */
 } oracle_adams_cfg;
 
 uint16_t oracle_bf16_rne(float x);
+
+uint16_t oracle_bf16_stochastic(float x, uint32_t r16);
+uint32_t oracle_sr_bits(uint32_t seed, uint64_t index);
+
+/* the value a stochastically rounded bf16 store of x reads back as; index = row * cols + col */
+static float through_bf16_sr(float x, uint32_t seed, int64_t index)
+{
+    uint32_t bits = (uint32_t)oracle_bf16_stochastic(x, oracle_sr_bits(seed, (uint64_t)index)) << 16;
+    float y;
+    memcpy(&y, &bits, sizeof y);
+    return y;
+}
 
 /* the value a bf16 store of x reads back as */
 static float through_bf16(float x)
@@ -348,7 +371,7 @@ int oracle_adams_step_f64(float *w, const float *grad, float *mu, float *v, uint
                 adams_element_f64(w[idx], g, mu[idx], v[idx], keep[idx], &p, &th, &m1, &v1);
                 w[idx] = (float)th;
                 mu[idx] = cfg->mu_bf16 ? through_bf16((float)m1) : (float)m1;
-                v[idx] = (float)v1;
+                v[idx] = cfg->v_bf16 ? through_bf16_sr((float)v1, cfg->sr_seed, idx) : (float)v1;
             }
         }
     }
@@ -395,7 +418,7 @@ int oracle_adams_step_f32(float *w, const float *grad, float *mu, float *v, uint
                 adams_element_f32(w[idx], g, mu[idx], v[idx], keep[idx], &p, &th, &m1, &v1);
                 w[idx] = th;
                 mu[idx] = cfg->mu_bf16 ? through_bf16(m1) : m1;
-                v[idx] = v1;
+                v[idx] = cfg->v_bf16 ? through_bf16_sr(v1, cfg->sr_seed, idx) : v1;
             }
         }
     }
@@ -508,6 +531,46 @@ uint16_t oracle_bf16_rne(float x)
     uint32_t lsb = (bits >> 16) & 1u;
     bits += 0x7fffu + lsb;
     return (uint16_t)(bits >> 16);
+}
+
+/* Stochastic rounding of a fp32 value to bf16 with 16 given random bits r16 (0 .. 65535): the
+ * value is rounded away from zero with probability (discarded low bits) / 65536, towards zero
+ * otherwise, so the expectation over uniform r16 is the value itself; a value that is a bf16
+ * number already is never changed.  Done on the bit pattern: adding r16 to the 32 bits carries
+ * into bit 16 exactly when low16 + r16 >= 65536 (a carry out of the mantissa moves to the next
+ * binade, the largest finite values can reach infinity).  Infinities and NaN go through the
+ * round-to-nearest conversion. */
+uint16_t oracle_bf16_stochastic(float x, uint32_t r16)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, sizeof bits);
+    if ((bits & 0x7f800000u) == 0x7f800000u) return oracle_bf16_rne(x);
+    return (uint16_t)((bits + (r16 & 0xffffu)) >> 16);
+}
+
+/* The integer finalizer published as "lowbias32" (C. Wellons, "Prospecting for hash functions",
+ * 2018): xor-shift 16, multiply 0x7feb352d, xor-shift 15, multiply 0x846ca68b, xor-shift 16. */
+static uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+/* The 16 rounding bits of one matrix entry: a counter-based generator (nothing is carried from
+ * entry to entry or step to step), this project's own definition.  The seed is mixed into a key
+ * first (so that seeds that differ in a few low bits, a step counter say, do not hand an entry
+ * the bits its neighbour had a step earlier), the key is folded with the 64-bit entry index into
+ * 32 bits, those are mixed, and the upper 16 bits are used. */
+uint32_t oracle_sr_bits(uint32_t seed, uint64_t index)
+{
+    uint32_t key = mix32(seed + 0x9e3779b9u);
+    uint32_t x = (uint32_t)index ^ key;
+    x += (uint32_t)(index >> 32) * 0x9e3779b9u;
+    return mix32(x) >> 16;
 }
 
 void oracle_bf16_rne_array(const float *x, int64_t count, uint16_t *out)

@@ -13,9 +13,9 @@ import oracle as O
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "cast_oracle.c")
 
-STEP, SELECT, SCALE_PACK, RULES, MU16 = ("tests/test_oracle_step.py", "tests/test_oracle_select.py",
-                                         "tests/test_oracle_scale_pack.py", "tests/test_oracle_rules.py",
-                                         "tests/test_oracle_mu_bf16.py")
+STEP, SELECT, SCALE_PACK, RULES, MU16, V16 = ("tests/test_oracle_step.py", "tests/test_oracle_select.py",
+                                              "tests/test_oracle_scale_pack.py", "tests/test_oracle_rules.py",
+                                              "tests/test_oracle_mu_bf16.py", "tests/test_oracle_v_bf16.py")
 
 # (name, pin files expected to notice, [(text in the source, what it becomes, occurrences)])
 MUTANTS = [
@@ -124,6 +124,22 @@ MUTANTS = [
      [("mu[idx] = cfg->mu_bf16 ? through_bf16(m1) : m1;", "mu[idx] = m1;", 1)]),
     ("bf16 moment rounded before it is used (fp32)", [MU16],
      [("    float mu_t = t0 + t1;\n    float mu_tilde;", "    float mu_t = through_bf16(t0 + t1);\n    float mu_tilde;", 1)]),
+    ("stochastic rounding always towards zero", [V16],
+     [("return (uint16_t)((bits + (r16 & 0xffffu)) >> 16);", "return (uint16_t)(bits >> 16);", 1)]),
+    ("stochastic rounding with 15 random bits", [V16],
+     [("return (uint16_t)((bits + (r16 & 0xffffu)) >> 16);", "return (uint16_t)((bits + (r16 & 0x7fffu)) >> 16);", 1)]),
+    ("second moment rounded to nearest instead of stochastically (fp32)", [V16],
+     [("v[idx] = cfg->v_bf16 ? through_bf16_sr(v1, cfg->sr_seed, idx) : v1;", "v[idx] = cfg->v_bf16 ? through_bf16(v1) : v1;", 1)]),
+    ("rounding bits from the column alone", [V16],
+     [("v[idx] = cfg->v_bf16 ? through_bf16_sr(v1, cfg->sr_seed, idx) : v1;", "v[idx] = cfg->v_bf16 ? through_bf16_sr(v1, cfg->sr_seed, c) : v1;", 1)]),
+    ("rounding bits ignore the seed", [V16],
+     [("uint32_t key = mix32(seed + 0x9e3779b9u);", "uint32_t key = mix32(0x9e3779b9u);", 1)]),
+    ("seed used unmixed (neighbours share their bits a step apart)", [V16],
+     [("uint32_t key = mix32(seed + 0x9e3779b9u);", "uint32_t key = seed;", 1)]),
+    ("upper half of the entry index ignored", [V16],
+     [("x += (uint32_t)(index >> 32) * 0x9e3779b9u;", "", 1)]),
+    ("rounded second moment used inside the iteration (fp32)", [V16],
+     [("    float v_t = s0 + s1;\n    float mu_hat = mu_tilde / p->bias_corr1;", "    float v_t = through_bf16(s0 + s1);\n    float mu_hat = mu_tilde / p->bias_corr1;", 1)]),
 ]
 
 
