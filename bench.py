@@ -352,6 +352,23 @@ def main():
                     extra["mu_bf16_emit_ms_step"] = round(ms, 3)
                     extra["mu_bf16_emit_GBs"] = round((BYTES_PER_PARAM - 2) * model.params / (ms * 1e-3) / 1e9, 1)
                     del copies
+                # both moments in bf16, the second one rounded stochastically (18.125 B/param; 20.125 with the copy)
+                for x in model.t:
+                    x["m"] = x["v"] = None
+                    x["w"], x["m"], x["v"] = B.interleaved_state(x["w"], mu_bf16=True, v_bf16=True)
+                model.tensor_list(B, scaled, dev, queue=False)
+                ms = timed(0)
+                extra["both_bf16_ms_step"] = round(ms, 3)
+                extra["both_bf16_Gparams_s"] = round(model.params / (ms * 1e-3) / 1e9, 1)
+                extra["both_bf16_GBs"] = round((BYTES_PER_PARAM - 8) * model.params / (ms * 1e-3) / 1e9, 1)
+                free_bytes, _ = torch.cuda.mem_get_info()
+                if free_bytes > 2.5 * model.params:
+                    copies = [torch.empty(x["w"].shape, dtype=torch.bfloat16, device=dev) for x in model.t]
+                    model.tensor_list(B, scaled, dev, queue=False, copies=copies)
+                    ms = timed(0)
+                    extra["both_bf16_emit_ms_step"] = round(ms, 3)
+                    extra["both_bf16_emit_GBs"] = round((BYTES_PER_PARAM - 6) * model.params / (ms * 1e-3) / 1e9, 1)
+                    del copies
                 for x, (w, m, v) in zip(model.t, kept):
                     x["w"], x["m"], x["v"] = w, m, v
                 del kept

@@ -73,6 +73,19 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  * gives the same numbers in a pass of its own); the compute copy can be written along (24.125
  * bytes per parameter); the work queue flag is ignored with it. */
 #define CAST_FLAG_MU_BF16 4u
+/* Both moments in bf16 (only together with CAST_FLAG_MU_BF16; same rules and exclusions): `v`
+ * points to bf16 values laid out like `m`.  With beta_2 = 0.999 one iteration changes v by a
+ * thousandth, less than half a bf16 unit in the last place, so rounded to nearest a stored v would
+ * never move: the new v is rounded STOCHASTICALLY when stored (away from zero with probability
+ * (discarded 16 bits) / 65536, so the expectation is the fp32 value; infinities and NaN go through
+ * round-to-nearest); the update of the same iteration uses the unrounded value.  The 16 random
+ * bits of the entry with index i = row * cols + col are the upper half of
+ *   mix(((uint32)i ^ mix(sr_seed + 0x9e3779b9)) + (uint32)(i >> 32) * 0x9e3779b9),
+ *   mix(x): x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15; x *= 0x846ca68b; x ^= x >> 16   (uint32)
+ * a counter-based generator: the result depends on (sr_seed, i) only, whatever the launch shape.
+ * The caller passes another cfg->sr_seed every iteration (a step counter will do).
+ * 18.125 bytes per parameter, 20.125 with the compute copy. */
+#define CAST_FLAG_V_BF16 8u
 
 /* Update rules.  CAST_RULE_ADAMS is the paper's method (Algorithm 1, Eq. 8); the others are the
  * rules it is set against, for ablations.  In all of them the decay acts only on entries whose
@@ -109,6 +122,7 @@ typedef struct {
     int32_t  grad_dtype;     /* CAST_F32 or CAST_BF16                                        */
     uint32_t flags;          /* 0, or an OR of CAST_FLAG_*                                   */
     int32_t  rule;           /* CAST_RULE_*; 0 = AdamS                                       */
+    uint32_t sr_seed;        /* seed of the rounding bits under CAST_FLAG_V_BF16, else unused */
 } cast_adams_config;
 
 const char *cast_status_str(cast_status s);

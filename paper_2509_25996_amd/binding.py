@@ -17,6 +17,7 @@ CAST_F32, CAST_BF16 = 0, 1
 FLAG_V_FROM_GRAD = 1
 FLAG_WORK_QUEUE = 2
 FLAG_MU_BF16 = 4
+FLAG_V_BF16 = 8
 RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = range(5)
 
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
@@ -43,7 +44,8 @@ class _Config(C.Structure):
     _fields_ = [("n_keep", C.c_int32), ("m_group", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float),
                 ("beta2", C.c_float), ("eps", C.c_float), ("lambda_", C.c_float), ("alpha", C.c_float),
                 ("bias_corr1", C.c_float), ("bias_corr2", C.c_float), ("refresh_mask", C.c_int32),
-                ("scale_segments", C.c_int32), ("grad_dtype", C.c_int32), ("flags", C.c_uint32), ("rule", C.c_int32)]
+                ("scale_segments", C.c_int32), ("grad_dtype", C.c_int32), ("flags", C.c_uint32), ("rule", C.c_int32),
+                ("sr_seed", C.c_uint32)]
 
 
 @dataclass
@@ -64,11 +66,12 @@ class AdamsConfig:
     grad_dtype: int = CAST_F32
     flags: int = 0
     rule: int = 0
+    sr_seed: int = 0        # seed of the stochastic rounding of a bf16 second moment; another one every iteration
 
     def c_struct(self) -> _Config:
         return _Config(self.n_keep, self.m_group, self.lr, self.beta1, self.beta2, self.eps, self.lambda_,
                        self.alpha, self.bias_corr1, self.bias_corr2, self.refresh_mask, self.scale_segments,
-                       self.grad_dtype, self.flags, self.rule)
+                       self.grad_dtype, self.flags, self.rule, self.sr_seed & 0xFFFFFFFF)
 
 
 _lib = None
@@ -159,25 +162,30 @@ def _ld(w, *same):
     return ld
 
 
-def _mu_flag(cfg, m) -> None:
-    """Sets or clears CAST_FLAG_MU_BF16 according to the dtype of the first moment."""
-    if m.dtype not in (torch.float32, torch.bfloat16):
-        raise TypeError("m must be float32 or bfloat16")
-    cfg.flags = (cfg.flags & ~FLAG_MU_BF16) | (FLAG_MU_BF16 if m.dtype == torch.bfloat16 else 0)
+def _mu_flag(cfg, m, v=None) -> None:
+    """Sets or clears CAST_FLAG_MU_BF16 and CAST_FLAG_V_BF16 according to the dtypes of the moments."""
+    for t in (m, v):
+        if t is not None and t.dtype not in (torch.float32, torch.bfloat16):
+            raise TypeError("m and v must be float32 or bfloat16")
+    cfg.flags = (cfg.flags & ~(FLAG_MU_BF16 | FLAG_V_BF16)) | (FLAG_MU_BF16 if m.dtype == torch.bfloat16 else 0) \
+        | (FLAG_V_BF16 if v is not None and v.dtype == torch.bfloat16 else 0)
 
 
-def interleaved_state(w0: torch.Tensor, mu_bf16: bool = False):
+def interleaved_state(w0: torch.Tensor, mu_bf16: bool = False, v_bf16: bool = False):
     """Allocate w, m, v of one matrix interleaved row by row in one buffer [rows, 3, cols] (row
     stride 3*cols for each of the three views).  w is initialised from w0, m and v are zero.
-    mu_bf16: m is bfloat16 and a row of the buffer is cols fp32, cols bf16, cols fp32 (10 * cols bytes)."""
+    mu_bf16: m is bfloat16 and a row of the buffer is cols fp32, cols bf16, cols fp32 (10 * cols bytes);
+    with v_bf16 on top v is bfloat16 as well (8 * cols bytes a row)."""
     rows, cols = w0.shape
+    if v_bf16 and not mu_bf16:
+        raise ValueError("v_bf16 comes with mu_bf16")
     if mu_bf16:
         if cols % 8:
             raise ValueError("cols must be a multiple of 8")
-        raw = torch.zeros((rows, 10 * cols), dtype=torch.uint8, device=w0.device)
+        raw = torch.zeros((rows, (8 if v_bf16 else 10) * cols), dtype=torch.uint8, device=w0.device)
         w = raw[:, :4 * cols].view(torch.float32)
         m = raw[:, 4 * cols:6 * cols].view(torch.bfloat16)
-        v = raw[:, 6 * cols:].view(torch.float32)
+        v = raw[:, 6 * cols:].view(torch.bfloat16 if v_bf16 else torch.float32)
         w.copy_(w0)
         return w, m, v
     state = torch.zeros((rows, 3, cols), dtype=torch.float32, device=w0.device)
@@ -207,7 +215,7 @@ def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scal
     _dev(grad, mask_bits, scale, scale_grad)
     rows, cols = w.shape
     cfg.grad_dtype = _dtype_code(grad)
-    _mu_flag(cfg, m)
+    _mu_flag(cfg, m, v)
     cs = cfg.c_struct()
     _check(load().cast_adams_step(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
                                   rows, cols, _ld(w, m, v), C.byref(cs), _stream(stream)), "cast_adams_step")
@@ -221,7 +229,7 @@ def cast_adams_step_emit(w, grad, m, v, mask_bits, cfg: AdamsConfig, compute_cop
         raise TypeError("compute_copy must be bfloat16")
     rows, cols = w.shape
     cfg.grad_dtype = _dtype_code(grad)
-    _mu_flag(cfg, m)
+    _mu_flag(cfg, m, v)
     cs = cfg.c_struct()
     _check(load().cast_adams_step_emit(_ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(mask_bits), _ptr(scale), _ptr(scale_grad),
                                        _ptr(copy_scale), _ptr(compute_copy), rows, cols, _ld(w, m, v), C.byref(cs),
@@ -258,9 +266,9 @@ class TensorList:
         self.mu_dtype = None
         for k, x in enumerate(self.items):
             w, m, v = x["w"], x["m"], x["v"]
-            if self.mu_dtype not in (None, m.dtype):
-                raise ValueError("all first moments of a list must have one dtype")
-            self.mu_dtype = m.dtype
+            if self.mu_dtype not in (None, (m.dtype, v.dtype)):
+                raise ValueError("the moments of a list must have the same dtypes in every matrix")
+            self.mu_dtype = (m.dtype, v.dtype)
             _dev(x["grad"], x["mask"], x.get("scale"), x.get("scale_grad"))
             dt = _dtype_code(x["grad"])
             if self.grad_dtype not in (None, dt):
@@ -295,7 +303,7 @@ class TensorList:
 def cast_adams_step_multi(tensors: TensorList, cfg: AdamsConfig, stream=None):
     if tensors.count:
         cfg.grad_dtype = tensors.grad_dtype
-        _mu_flag(cfg, tensors.items[0]["m"])
+        _mu_flag(cfg, tensors.items[0]["m"], tensors.items[0]["v"])
     cs = cfg.c_struct()
     _check(load().cast_adams_step_multi(tensors.array, tensors.count, C.byref(cs), _ptr(tensors.workspace),
                                         tensors.workspace.numel(), _stream(stream)), "cast_adams_step_multi")
@@ -305,7 +313,7 @@ def cast_adams_multi_launches(tensors: TensorList, cfg: AdamsConfig):
     """(launches of the step kernel, other launches) one cast_adams_step_multi call makes for this list."""
     if tensors.count:
         cfg.grad_dtype = tensors.grad_dtype
-        _mu_flag(cfg, tensors.items[0]["m"])
+        _mu_flag(cfg, tensors.items[0]["m"], tensors.items[0]["v"])
     cs = cfg.c_struct()
     a, b = C.c_int32(0), C.c_int32(0)
     _check(load().cast_adams_multi_launches(tensors.array, tensors.count, C.byref(cs), C.byref(a), C.byref(b)),
@@ -371,4 +379,5 @@ def iteration_config(t: int, total_steps: int, mask_period: int = 10, **kw) -> A
     cfg.bias_corr1 = 1.0 - b1 ** (t + 1)
     cfg.bias_corr2 = 1.0 - b2 ** (t + 1)
     cfg.refresh_mask = int(t % mask_period == 0)
+    cfg.sr_seed = t
     return cfg

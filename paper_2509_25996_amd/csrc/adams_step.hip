@@ -179,6 +179,7 @@ static StepScalars make_scalars(const cast_adams_config *cfg)
     s.n_keep = cfg->n_keep;
     s.v_from_grad = (cfg->flags & CAST_FLAG_V_FROM_GRAD) ? 1 : 0;
     s.rule = cfg->rule;
+    s.sr_key = sr_key_of(cfg->sr_seed);
     if (cfg->rule == CAST_RULE_ADDITIVE) s.one_minus_alpha = 1.0f;                              // mu~ = mu + alpha*lambda*Sign
     if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1) s.v_from_grad = 1;   // Eq. 9, Eq. 10
     // the short forms need both bias corrections in [2^-12, 2] and a small non-negative epsilon
@@ -223,6 +224,8 @@ static void launch_vec_abilities(const VecLaunch &l, const SpanArgs &a, dim3 gri
         case kEmitAndCount: launch_vec_flavour<M, BF16, REFRESH, SCALED, kEmitAndCount>(l, a, grid, block, st); break;
         case kMuBf16: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16>(l, a, grid, block, st); break;
         case kMuBf16Emit: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16Emit>(l, a, grid, block, st); break;
+        case kBothBf16: launch_vec_flavour<M, BF16, REFRESH, SCALED, kBothBf16>(l, a, grid, block, st); break;
+        case kBothBf16Emit: launch_vec_flavour<M, BF16, REFRESH, SCALED, kBothBf16Emit>(l, a, grid, block, st); break;
         case kStatsOnly:      // refresh statistics without a compute copy: a flavour of the refresh kernels only
             if constexpr (REFRESH) {
                 launch_vec_flavour<M, BF16, true, SCALED, kStatsOnly>(l, a, grid, block, st);
@@ -336,8 +339,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     // the kernel flavour: what the kernel has to do besides the step, and the comparison rule if it has code of its own
     const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     // (a first moment kept in bf16 comes with the compute copy at most: the API has seen to that)
-    const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
-    const int extra = mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? with_rule((x.compute_copy != nullptr || stats) ? kEmitAndCount : 0, flavour_rule(cfg->rule)) : (x.compute_copy != nullptr ? kEmitAndCount : (stats ? kStatsOnly : 0)));
+    const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0, v16 = (cfg->flags & CAST_FLAG_V_BF16) != 0;
+    const int extra = v16 ? (x.compute_copy != nullptr ? kBothBf16Emit : kBothBf16) : mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? with_rule((x.compute_copy != nullptr || stats) ? kEmitAndCount : 0, flavour_rule(cfg->rule)) : (x.compute_copy != nullptr ? kEmitAndCount : (stats ? kStatsOnly : 0)));
     p.geom.m_row_gap = mu_bf16_ld(cols, ld) - cols;
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
@@ -369,7 +372,7 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
         if (rc != CAST_OK) return rc;
     }
     UnitArgs a{w, grad, m, v, mask_bits, scale, rows, cols, ld, cfg->scale_segments, refresh ? 1 : 0, make_scalars(cfg),
-               static_cast<uint16_t *>(x.compute_copy), x.copy_scale, mu16 ? mu_bf16_ld(cols, ld) : 0};
+               static_cast<uint16_t *>(x.compute_copy), x.copy_scale, mu16 ? mu_bf16_ld(cols, ld) : 0, v16 ? 1 : 0};
     const unsigned grid = (unsigned)unit_grid;
     switch (cfg->m_group) {
     case 2: launch_unit_dtype<2>(bf16, grid, a, st); break;
@@ -387,7 +390,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
 {
     SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
     const bool refresh = cfg->refresh_mask != 0;
-    const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0;
+    const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0, v16 = (cfg->flags & CAST_FLAG_V_BF16) != 0;
     a.geom.m_row_gap = mu_bf16_ld(ts[0]->cols, ts[0]->ld) - ts[0]->cols;
     for (int k = 0; k < n; ++k) {
         const cast_tensor &t = *ts[k];
@@ -401,7 +404,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
                               can_emit(flavour) ? static_cast<uint16_t *>(t.compute_copy) : nullptr, can_emit(flavour) ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, mu16 ? (flavour == kEmitAndCount ? kMuBf16Emit : kMuBf16) : flavour}, a, st);
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, v16 ? (flavour == kEmitAndCount ? kBothBf16Emit : kBothBf16) : mu16 ? (flavour == kEmitAndCount ? kMuBf16Emit : kMuBf16) : flavour}, a, st);
     return launch_status();
 }
 
@@ -574,7 +577,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
     // the work queue knows neither the comparison rules with code of their own nor the compute copy
     if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN) use_queue = false;
-    if (cfg->flags & CAST_FLAG_MU_BF16) use_queue = false;      // nor a first moment kept in bf16
+    if (cfg->flags & (CAST_FLAG_MU_BF16 | CAST_FLAG_V_BF16)) use_queue = false;      // nor moments kept in bf16
     const bool want_stats = cfg->refresh_mask != 0;
     for (int i = 0; i < count; ++i)
         if (ts[i].compute_copy || (want_stats && ts[i].refresh_stats)) use_queue = false;      // nor refresh statistics

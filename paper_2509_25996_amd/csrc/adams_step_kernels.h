@@ -66,22 +66,26 @@ static ConstTable as_const_table(const void *device_ptr)
 // shifted left by four.  The low bits: 0 plain; 1 can also write the bf16 compute copy and gather refresh
 // statistics; 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16); 4 plain that can gather refresh
 // statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0); 5 the
-// first moment in bf16 and the compute copy.  The rules combine with 0 and 1.
+// first moment in bf16 and the compute copy; 6 both moments in bf16, the second one rounded stochastically
+// (CAST_FLAG_V_BF16); 7 the same with the compute copy.  The rules combine with 0 and 1.
 constexpr int kEmitAndCount = 1;
 constexpr int kMuBf16 = 3;
 constexpr int kStatsOnly = 4;
 constexpr int kMuBf16Emit = 5;
+constexpr int kBothBf16 = 6;
+constexpr int kBothBf16Emit = 7;
 constexpr int abilities(int extra) { return extra & 15; }
 constexpr int rule_of(int extra) { return extra >> 4; }      // kRuleAdamwL1, kRuleAdamL1, kRuleMaskedFrozen or 0
 constexpr int with_rule(int extra, int rule) { return extra | (rule << 4); }
-constexpr bool can_emit(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kMuBf16Emit; }
+constexpr bool can_emit(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kMuBf16Emit || abilities(extra) == kBothBf16Emit; }
 constexpr bool can_count(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kStatsOnly; }
-constexpr bool mu_is_bf16(int extra) { return abilities(extra) == kMuBf16 || abilities(extra) == kMuBf16Emit; }
+constexpr bool v_is_bf16(int extra) { return abilities(extra) == kBothBf16 || abilities(extra) == kBothBf16Emit; }
+constexpr bool mu_is_bf16(int extra) { return abilities(extra) == kMuBf16 || abilities(extra) == kMuBf16Emit || v_is_bf16(extra); }
 
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
 template <bool BF16>
 struct Chunk {
-    vu4_t w, m, v;    // a bf16 first moment: the first 2 dwords of m hold 4 values
+    vu4_t w, m, v;    // a bf16 moment: the first 2 dwords of m (of v) hold 4 values
     vu4_t g;          // fp32 gradient: 4 dwords; bf16: the first 2 dwords hold 4 values
     uint32_t word;    // the mask word that holds this lane's 4 bits (non-refresh steps)
     uint32_t initial; // the same word of the initial mask (refresh steps that gather statistics)
@@ -96,7 +100,7 @@ struct SpanBuffers {
 
 // WORD: whether the stored mask word is wanted (non-refresh steps; refresh steps that count flips);
 // INITIAL: whether the initial mask's word is (the latter only)
-template <bool BF16, bool WORD, bool INITIAL = false, bool MU16 = false>
+template <bool BF16, bool WORD, bool INITIAL = false, bool MU16 = false, bool V16 = false>
 __device__ __forceinline__ void chunk_load(Chunk<BF16> &c, const SpanBuffers &b, int off)
 {
     c.w = __builtin_amdgcn_raw_buffer_load_b128(b.w, off * 4, 0, kAuxLoad);
@@ -112,7 +116,12 @@ __device__ __forceinline__ void chunk_load(Chunk<BF16> &c, const SpanBuffers &b,
     } else {
         c.m = __builtin_amdgcn_raw_buffer_load_b128(b.m, off * 4, 0, kAuxLoad);
     }
-    c.v = __builtin_amdgcn_raw_buffer_load_b128(b.v, off * 4, 0, kAuxLoad);
+    if constexpr (V16) {
+        const vu2_t t = __builtin_amdgcn_raw_buffer_load_b64(b.v, off * 2, 0, kAuxLoad);
+        c.v.x = t.x; c.v.y = t.y; c.v.z = 0; c.v.w = 0;
+    } else {
+        c.v = __builtin_amdgcn_raw_buffer_load_b128(b.v, off * 4, 0, kAuxLoad);
+    }
     if constexpr (WORD) c.word = __builtin_amdgcn_raw_buffer_load_b32(b.mask, (off >> 5) * 4, 0, kAuxLoad);
     else c.word = 0;
     if constexpr (INITIAL) c.initial = __builtin_amdgcn_raw_buffer_load_b32(b.initial_mask, (off >> 5) * 4, 0, kAuxLoad);
@@ -144,6 +153,7 @@ struct SpanCtx {
     float copy_A;                  // EXTRA: the factor folded into it
     bool emit;                     // EXTRA: whether there is a compute copy to write
     StatsPartial *stats_slot;      // EXTRA: where this workgroup leaves its refresh statistics, or NULL
+    int64_t dense_begin;           // EXTRA (a bf16 second moment): index row * cols + col of the span's first entry
 };
 
 // `matrix` selects the buffer set (entry of the table of a list call), `block` the workgroup's
@@ -198,7 +208,9 @@ __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, in
     c.b.w = span_resource(t.w + o.state_begin, c.len * 4);
     if constexpr (mu_is_bf16(EXTRA)) c.b.m = span_resource(reinterpret_cast<uint16_t *>(t.m) + (int64_t)uniform_u64((unsigned long long)o.m_begin), c.len * 2);
     else c.b.m = span_resource(t.m + o.state_begin, c.len * 4);
-    c.b.v = span_resource(t.v + o.state_begin, c.len * 4);
+    if constexpr (v_is_bf16(EXTRA)) c.b.v = span_resource(reinterpret_cast<uint16_t *>(t.v) + (int64_t)uniform_u64((unsigned long long)o.m_begin), c.len * 2);
+    else c.b.v = span_resource(t.v + o.state_begin, c.len * 4);
+    c.dense_begin = v_is_bf16(EXTRA) ? (int64_t)uniform_u64((unsigned long long)o.dense_begin) : 0;
     if constexpr (BF16) c.b.g = span_resource(static_cast<const uint16_t *>(t.grad) + o.dense_begin, c.len * 2);
     else c.b.g = span_resource(static_cast<const float *>(t.grad) + o.dense_begin, c.len * 4);
     c.b.mask = span_resource(t.mask + (o.dense_begin >> 5), c.len / 8);    // spans start and end on mask words
@@ -246,6 +258,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
 {
     constexpr bool kStats = REFRESH && can_count(EXTRA);      // refresh statistics are gathered if c.stats_slot says so
     constexpr bool kMu16 = mu_is_bf16(EXTRA);
+    constexpr bool kV16 = v_is_bf16(EXTRA);
     uint32_t flips_prev = 0, flips_init = 0;
     float l1_kept = 0.0f, l1_all = 0.0f;
     const int P = a.geom.waves_per_span;
@@ -258,7 +271,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
     int off = first_offset(c, lane);      // this lane's first entry, relative to the span
     for (int base = c.sub * kChunk; base < len; base += stride) {
         Chunk<BF16> nxt;
-        chunk_load<BF16, (!REFRESH || can_count(EXTRA)), kStats, kMu16>(nxt, b, off + stride);     // past the end: all zeros, never used
+        chunk_load<BF16, (!REFRESH || can_count(EXTRA)), kStats, kMu16, kV16>(nxt, b, off + stride);     // past the end: all zeros, never used
 
         float w[4], g[4], mu[4], v[4];
         unpack4(cur.w, w);
@@ -267,7 +280,11 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         } else {
             unpack4(cur.m, mu);
         }
-        unpack4(cur.v, v);
+        if constexpr (kV16) {
+            v[0] = bf16_lo(cur.v.x); v[1] = bf16_hi(cur.v.x); v[2] = bf16_lo(cur.v.y); v[3] = bf16_hi(cur.v.y);
+        } else {
+            unpack4(cur.v, v);
+        }
         if constexpr (BF16) {
             g[0] = bf16_lo(cur.g.x); g[1] = bf16_hi(cur.g.x); g[2] = bf16_lo(cur.g.y); g[3] = bf16_hi(cur.g.y);
         } else {
@@ -314,7 +331,19 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         } else {
             __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
         }
-        __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
+        if constexpr (kV16) {
+            // rounded stochastically for the store only, with the bits of index row * cols + col: spans begin on
+            // multiples of 32 entries and off is a multiple of 4, so adding the entry number to the low half carries nothing
+            const uint64_t first = (uint64_t)c.dense_begin + (uint32_t)off;
+            const uint32_t lo = (uint32_t)first, hi_term = (uint32_t)(first >> 32) * 0x9e3779b9u;
+            uint32_t h[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) h[j] = f32_to_bf16_sr(v[j], sr_bits(a.s.sr_key, lo + (uint32_t)j, hi_term));
+            const vu2_t packed = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+            __builtin_amdgcn_raw_buffer_store_b64(packed, b.v, off * 2, 0, kAuxStore);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
+        }
         if constexpr (can_emit(EXTRA)) {
             if (c.emit) {      // the weights the next forward pass multiplies with: bf16(A * w_new), Eq. 12
                 vu2_t h;
@@ -390,7 +419,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     SpanCtx c;
     span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
     Chunk<BF16> first;
-    chunk_load<BF16, (!REFRESH || can_count(EXTRA)), (REFRESH && can_count(EXTRA)), mu_is_bf16(EXTRA)>(first, c.b, first_offset(c, lane));
+    chunk_load<BF16, (!REFRESH || can_count(EXTRA)), (REFRESH && can_count(EXTRA)), mu_is_bf16(EXTRA), v_is_bf16(EXTRA)>(first, c.b, first_offset(c, lane));
     if constexpr (REFRESH && can_count(EXTRA)) {
         __shared__ StatsShared stats_shared;
         span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial, &stats_shared);
@@ -630,6 +659,7 @@ struct UnitArgs {
     uint16_t *compute_copy;     // bf16 [rows, cols] or NULL
     const float *copy_scale;    // [rows, n_segments] or NULL
     int64_t m_ld;               // > 0: m is bf16 with this row stride (in its own entries); 0: fp32 like w and v
+    int v_bf16;                 // 1: v is bf16 too, laid out like m, stored with stochastic rounding
 };
 
 template <bool BF16>
@@ -675,12 +705,19 @@ __global__ __launch_bounds__(kBlockThreads) void adams_step_unit(const UnitArgs 
                 float g = load_grad1<BF16>(a.grad, gidx + j);
                 if (a.scale) g = A * g;
                 uint16_t *m16 = reinterpret_cast<uint16_t *>(a.m) + r * a.m_ld + c + j;
-                float mu = a.m_ld > 0 ? bf16_to_f32(*m16) : a.m[idx + j], vv = a.v[idx + j];
+                uint16_t *v16 = reinterpret_cast<uint16_t *>(a.v) + r * a.m_ld + c + j;
+                float mu = a.m_ld > 0 ? bf16_to_f32(*m16) : a.m[idx + j];
+                float vv = a.v_bf16 ? bf16_to_f32(*v16) : a.v[idx + j];
                 adams_entry(wv[j], g, mu, vv, (bits >> j) & 1u, a.s);
                 a.w[idx + j] = wv[j];
                 if (a.m_ld > 0) *m16 = (uint16_t)f32_to_bf16_rne(mu);
                 else a.m[idx + j] = mu;
-                a.v[idx + j] = vv;
+                if (a.v_bf16) {
+                    const uint64_t entry = (uint64_t)(gidx + j);
+                    *v16 = (uint16_t)f32_to_bf16_sr(vv, sr_bits(a.s.sr_key, (uint32_t)entry, (uint32_t)(entry >> 32) * 0x9e3779b9u));
+                } else {
+                    a.v[idx + j] = vv;
+                }
                 if (a.compute_copy) a.compute_copy[gidx + j] = (uint16_t)f32_to_bf16_rne(copy_A * wv[j]);
             }
         }

@@ -105,7 +105,8 @@ static cast_status validate_step(const float *w, const void *grad, const float *
     if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (!dtype_ok(cfg->grad_dtype)) return CAST_ERR_DTYPE;
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
-    if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE | CAST_FLAG_MU_BF16)) return CAST_ERR_CONFIG;
+    if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE | CAST_FLAG_MU_BF16 | CAST_FLAG_V_BF16)) return CAST_ERR_CONFIG;
+    if ((cfg->flags & CAST_FLAG_V_BF16) && !(cfg->flags & CAST_FLAG_MU_BF16)) return CAST_ERR_CONFIG;      // both moments or the first alone
     if (cfg->rule < CAST_RULE_ADAMS || cfg->rule > CAST_RULE_MASKED_FROZEN) return CAST_ERR_CONFIG;
     if ((cfg->flags & CAST_FLAG_MU_BF16) && cfg->rule != CAST_RULE_ADAMS && cfg->rule != CAST_RULE_ADDITIVE) return CAST_ERR_CONFIG;
     // the bias corrections divide: they must be positive finite numbers (1 - beta^s with s >= 1)

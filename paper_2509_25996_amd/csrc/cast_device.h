@@ -390,6 +390,36 @@ __host__ __device__ __forceinline__ float div_by_uniform(float x, const UniformD
     return x / d.y;
 }
 
+// ---- stochastic rounding to bf16 (CAST_FLAG_V_BF16) -----------------------------------------
+// The integer mixer of the rounding bits as include/cast.h defines them.
+__host__ __device__ __forceinline__ uint32_t sr_mix(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+
+__host__ __device__ __forceinline__ uint32_t sr_key_of(uint32_t seed) { return sr_mix(seed + 0x9e3779b9u); }
+
+// 16 rounding bits of the entry whose 64-bit index has the low half index_lo and the high half
+// folded into hi_term = high * 0x9e3779b9.
+__host__ __device__ __forceinline__ uint32_t sr_bits(uint32_t key, uint32_t index_lo, uint32_t hi_term)
+{
+    return sr_mix((index_lo ^ key) + hi_term) >> 16;
+}
+
+// x to bf16, away from zero with probability (discarded bits) / 65536 given 16 uniform bits r16;
+// infinities and NaN as round-to-nearest converts them.
+__device__ __forceinline__ uint32_t f32_to_bf16_sr(float x, uint32_t r16)
+{
+    const uint32_t bits = __float_as_uint(x);
+    const uint32_t rounded = (bits + r16) >> 16;
+    return (bits & 0x7f800000u) == 0x7f800000u ? f32_to_bf16_rne(x) : rounded;
+}
+
 // ---- Algorithm 1 --------------------------------------------------------------------------
 // Scalars of one iteration, prepared on the host in fp32 (one rounding each).
 struct StepScalars {
@@ -400,6 +430,7 @@ struct StepScalars {
     int n_keep;
     int v_from_grad;
     int short_forms;       // 1 if the uniform scalars allow the short division / square-root forms
+    uint32_t sr_key;       // CAST_FLAG_V_BF16: the mixed seed of the rounding bits
     int rule;              // CAST_RULE_*; read by the one-entry code (adams_entry); the vector kernels have it as a template argument
 };
 

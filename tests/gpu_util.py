@@ -57,20 +57,22 @@ def oracle_cfg(cfg: B.AdamsConfig) -> oracle.AdamsCfg:
                            eps=cfg.eps, lambda_=cfg.lambda_, alpha=cfg.alpha, bias_corr1=cfg.bias_corr1,
                            bias_corr2=cfg.bias_corr2, refresh_mask=cfg.refresh_mask,
                            scale_segments=cfg.scale_segments, v_from_grad=int(bool(cfg.flags & B.FLAG_V_FROM_GRAD)),
-                           rule=cfg.rule, mu_bf16=int(bool(cfg.flags & B.FLAG_MU_BF16)))
+                           rule=cfg.rule, mu_bf16=int(bool(cfg.flags & B.FLAG_MU_BF16)),
+                           v_bf16=int(bool(cfg.flags & B.FLAG_V_BF16)), sr_seed=cfg.sr_seed)
 
 
 class GpuState:
     """w, mu, v, mask (and optionally A, dL/dA) of one matrix on the GPU."""
 
-    def __init__(self, w: np.ndarray, n_segments: int = 0, interleaved: bool = False, mu_bf16: bool = False):
+    def __init__(self, w: np.ndarray, n_segments: int = 0, interleaved: bool = False, mu_bf16: bool = False,
+                 v_bf16: bool = False):
         rows, cols = w.shape
-        if interleaved:      # w, mu, v row-interleaved in one buffer: row stride 3 * cols (2.5 * cols with a bf16 mu)
-            self.w, self.m, self.v = B.interleaved_state(dev(w), mu_bf16=mu_bf16)
+        if interleaved:      # w, mu, v row-interleaved in one buffer: row stride 3 * cols (2.5 * cols with a bf16 mu, 2 * cols with both)
+            self.w, self.m, self.v = B.interleaved_state(dev(w), mu_bf16=mu_bf16, v_bf16=v_bf16)
         else:
             self.w = dev(w)
             self.m = torch.zeros_like(self.w, dtype=torch.bfloat16 if mu_bf16 else torch.float32)
-            self.v = torch.zeros_like(self.w)
+            self.v = torch.zeros_like(self.w, dtype=torch.bfloat16 if v_bf16 else torch.float32)
         self.mask = B.alloc_mask(rows, cols, DEV)
         self.scale_grad = torch.zeros((rows, n_segments), dtype=torch.float32, device=DEV) if n_segments else None
 

@@ -125,6 +125,10 @@ def test_validation_happens_before_any_launch(lib):
     assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(mu16(rule=1)), st) == -5
     assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(mu16(rule=4)), st) == -5
     assert emit(p, p, p, p, p, nul, nul, nul, p, 4, 64, 64, C.byref(mu16(rule=2)), st) == -5
+    # the second moment in bf16 only together with the first, and under the same rules
+    assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(_cfg(flags=8)), st) == -5
+    assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(_cfg(flags=12, rule=4)), st) == -5
+    assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(_cfg(flags=16)), st) == -5
     # list call: rejected as a whole if any matrix is bad, before anything is enqueued
     T = B._Tensor
     good = T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64)
