@@ -144,7 +144,8 @@ cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t l
  * One AdamS iteration over one weight matrix: the body of Algorithm 1's loop (Eq. 8), with
  * the proportional decay of Eq. 7 on the entries whose mask bit is 0.
  *
- *   w, m, v     DEVICE in/out  fp32 [rows, cols], row stride ld: theta, first moment mu, second moment v.
+ *   w, m, v     DEVICE in/out  fp32 [rows, cols], row stride ld: theta, first moment mu, second moment v
+ *                              (m, or m and v, bf16 under CAST_FLAG_MU_BF16 / CAST_FLAG_V_BF16, see there).
  *   grad        DEVICE in      [rows, cols] of cfg->grad_dtype.  With scale == NULL it is dL/dW;
  *                              with scale != NULL it is dL/dW_scale and the chain rule of Eq. 12
  *                              (dL/dW = A[r, s] * grad) is applied inside.
