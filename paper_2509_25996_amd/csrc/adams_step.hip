@@ -59,6 +59,17 @@ static int flavour_rule(int rule)
     return rule == CAST_RULE_ADAMW_L1 ? kRuleAdamwL1 : rule == CAST_RULE_ADAM_L1 ? kRuleAdamL1 : rule == CAST_RULE_MASKED_FROZEN ? kRuleMaskedFrozen : 0;
 }
 
+// The kernel flavour for one matrix: how the moments are stored comes first (the API has seen to it that bf16
+// moments come with the compute copy at most), then the rule and what else the kernel has to do.
+static int step_flavour(const cast_adams_config *cfg, bool copy, bool stats)
+{
+    if (cfg->flags & CAST_FLAG_V_BF16) return copy ? kBothBf16Emit : kBothBf16;
+    if (cfg->flags & CAST_FLAG_MU_BF16) return copy ? kMuBf16Emit : kMuBf16;
+    const int rule = flavour_rule(cfg->rule);
+    if (rule != 0) return with_rule((copy || stats) ? kEmitAndCount : 0, rule);
+    return copy ? kEmitAndCount : (stats ? kStatsOnly : 0);
+}
+
 static int env_int(const char *name, int fallback)
 {
     const char *e = getenv(name);
@@ -336,11 +347,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     if (refresh && x.refresh_stats != nullptr && !stats) return CAST_ERR_SHAPE;      // workspace too small (not reachable through the API)
     StatsPartial *stats_partials = stats ? take_stats_slots(x.stats_area, stats_slots, x.refresh_stats, x.initial_mask) : nullptr;
     const uint32_t *stats_initial = stats ? x.initial_mask : nullptr;
-    // the kernel flavour: what the kernel has to do besides the step, and the comparison rule if it has code of its own
-    const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
-    // (a first moment kept in bf16 comes with the compute copy at most: the API has seen to that)
     const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0, v16 = (cfg->flags & CAST_FLAG_V_BF16) != 0;
-    const int extra = v16 ? (x.compute_copy != nullptr ? kBothBf16Emit : kBothBf16) : mu16 ? (x.compute_copy != nullptr ? kMuBf16Emit : kMuBf16) : (own_rule ? with_rule((x.compute_copy != nullptr || stats) ? kEmitAndCount : 0, flavour_rule(cfg->rule)) : (x.compute_copy != nullptr ? kEmitAndCount : (stats ? kStatsOnly : 0)));
+    const int extra = step_flavour(cfg, x.compute_copy != nullptr, stats);
     p.geom.m_row_gap = mu_bf16_ld(cols, ld) - cols;
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
@@ -383,14 +391,12 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 }
 
 // Up to kMaxFused matrices of one shape in one launch (no split plan): the ramp-up and ramp-down of a launch cost about 2.6 us, which is 4 % of the 70 us a
-// 4096 x 4096 matrix takes.  `flavour`: the kernel flavour all of them need (before the bf16 first moment is
-// taken into account); each matrix its own buffers.
+// 4096 x 4096 matrix takes.  `flavour`: the kernel flavour all of them need; each matrix its own buffers.
 static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
                                            int flavour, StatsArea *stats_area, hipStream_t st)
 {
     SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
     const bool refresh = cfg->refresh_mask != 0;
-    const bool mu16 = (cfg->flags & CAST_FLAG_MU_BF16) != 0, v16 = (cfg->flags & CAST_FLAG_V_BF16) != 0;
     a.geom.m_row_gap = mu_bf16_ld(ts[0]->cols, ts[0]->ld) - ts[0]->cols;
     for (int k = 0; k < n; ++k) {
         const cast_tensor &t = *ts[k];
@@ -404,7 +410,7 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
                               can_emit(flavour) ? static_cast<uint16_t *>(t.compute_copy) : nullptr, can_emit(flavour) ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, v16 ? (flavour == kEmitAndCount ? kBothBf16Emit : kBothBf16) : mu16 ? (flavour == kEmitAndCount ? kMuBf16Emit : kMuBf16) : flavour}, a, st);
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, flavour}, a, st);
     return launch_status();
 }
 
@@ -602,7 +608,6 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     static const int fuse_limit = env_int("CAST_FUSE", kMaxFused);            // matrices per launch (1 = never fuse)
     static const int64_t fuse_max_params = (int64_t)env_int("CAST_FUSE_MAX_MPARAMS", 24) << 20;
     static const int64_t fuse_launch_params = (int64_t)env_int("CAST_FUSE_LAUNCH_MPARAMS", 72) << 20;
-    const bool own_rule = cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN;
     int dry_stats = 0;      // dry run: statistics jobs waiting for their launch
     auto stats_room = [&](int n) -> cast_status {      // room for n more statistics jobs before their launch is enqueued
         if (dry) {
@@ -615,8 +620,7 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
         return stats_jobs.count + n > kMaxStatsJobs ? stats_jobs.flush(st) : CAST_OK;
     };
     auto flavour_of = [&](const cast_tensor &t) {      // of the kernels a matrix needs
-        if (own_rule) return with_rule((t.compute_copy != nullptr || (want_stats && t.refresh_stats != nullptr)) ? kEmitAndCount : 0, flavour_rule(cfg->rule));
-        return t.compute_copy != nullptr ? kEmitAndCount : ((want_stats && t.refresh_stats != nullptr) ? kStatsOnly : 0);
+        return step_flavour(cfg, t.compute_copy != nullptr, want_stats && t.refresh_stats != nullptr);
     };
     for (int i = 0; i < count; ++i) {
         if (taken[i]) continue;
