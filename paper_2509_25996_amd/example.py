@@ -5,6 +5,10 @@ mask, the fold of the scale factors and packing (Algorithm 1's last lines, Eq. 1
 
     python -m paper_2509_25996_amd.example
 
+With bf16_moments=True both moments are kept in bf16 (the second one rounded stochastically, a fresh seed per
+step); the refresh steps cannot gather statistics then, so the same numbers come from cast_mask_stats, a pass of
+its own after each refresh step, against a copy of the previous mask.
+
 Gradients are random draws, not a loss: the point is the calling sequence, and that under the ramp the
 masked weights are driven to zero (Sec. 4.1, appendix "Mask Learning"), which the numbers it prints show.
 The scale factors are stepped from scale_grad by a plain Adam, itself a call into the library (DenseAdam below):
@@ -37,20 +41,34 @@ class DenseAdam:
         B.cast_adams_step(self.p, grad, self.m, self.v, self.mask, cfg)
 
 
+def _stats_in_a_pass(x, previous_mask, device):
+    """What a refresh step with refresh_stats reports, from cast_mask_stats after the step (the L1 norms are those of
+    the stepped weights then, one step later than the fused statistics see them)."""
+    out = {}
+    for name, other in (("flips_prev", previous_mask), ("flips_init", x["initial_mask"])):
+        flips = torch.zeros(1, dtype=torch.int64, device=device)
+        l1 = torch.zeros(2, dtype=torch.float64, device=device)
+        B.cast_mask_stats(x["w"], x["mask"], other, flips, l1)
+        out[name] = int(flips.item())
+    out["l1_kept"], out["l1_all"] = (float(t) for t in l1.tolist())
+    return out
+
+
 def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10, lr=1e-3, lam=1e-3, n_keep=2, m_group=4,
-        segments=2, device="cuda:0", verbose=True):
+        segments=2, device="cuda:0", verbose=True, bf16_moments=False):
     """Returns a dict of what a training script would monitor; see the module docstring."""
     B.load()
     items, stats = [], []
     for i, (r, c) in enumerate(shapes):
-        w, m, v = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, 100 + i, device))
+        w, m, v = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, 100 + i, device),
+                                      mu_bf16=bf16_moments, v_bf16=bf16_moments)
         mask, initial = B.alloc_mask(r, c, device), B.alloc_mask(r, c, device)
         B.cast_nm_select(w, n_keep, m_group, initial)                 # the mask of the dense model, for the initial flip rate
         mask.copy_(initial)
         stats.append(B.alloc_refresh_stats(device))
         items.append(dict(w=w, m=m, v=v, mask=mask, grad=torch.empty((r, c), dtype=torch.bfloat16, device=device),
                           scale=torch.ones((r, segments), device=device), scale_grad=torch.zeros((r, segments), device=device),
-                          initial_mask=initial, refresh_stats=stats[-1]))
+                          initial_mask=initial, refresh_stats=None if bf16_moments else stats[-1]))
     tensors = B.TensorList(items, device)
     scale_optimizers = [DenseAdam(x["scale"], lr=1e-4) for x in items]
     total = sum(r * c for r, c in shapes)
@@ -61,11 +79,16 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
             x["grad"].copy_(torch.randn(x["grad"].shape, device=device, generator=gen) * 1e-3)
         cfg = B.iteration_config(t, steps, mask_period=mask_period, lr=lr, lambda_=lam, n_keep=n_keep, m_group=m_group,
                                  scale_segments=segments)
-        B.cast_adams_step_multi(tensors, cfg)
+        if bf16_moments and cfg.refresh_mask:
+            previous = [x["mask"].clone() for x in items]
+        B.cast_adams_step_multi(tensors, cfg)                         # (iteration_config has set cfg.sr_seed = t)
         for opt, x in zip(scale_optimizers, items):                   # A <- Adam(A, dL/dA); the step above used the old A
             opt.step(x["scale_grad"])
         if cfg.refresh_mask:
-            s = [B.read_refresh_stats(x) for x in stats]
+            if bf16_moments:
+                s = [_stats_in_a_pass(x, old, device) for x, old in zip(items, previous)]
+            else:
+                s = [B.read_refresh_stats(x) for x in stats]
             flip_rate = sum(x["flips_prev"] for x in s) / total       # r_t
             initial_flip_rate = sum(x["flips_init"] for x in s) / total       # i_t
             kept_ratio = sum(x["l1_kept"] for x in s) / sum(x["l1_all"] for x in s)       # S_t

@@ -757,12 +757,15 @@ def test_project_compress_vector_kernels_layouts_and_stored_masks(n, m, rows, co
                         assert (host(values.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref_v)).all()
 
 
-def test_example_loop_drives_masked_weights_to_zero():
+@pytest.mark.parametrize("bf16_moments", [False, True])
+def test_example_loop_drives_masked_weights_to_zero(bf16_moments):
     """The calling sequence of the package's example (list call with refresh statistics over a ramp, then the
     projection with the last refreshed mask): the end state the paper describes (Sec. 4.1, appendix "Mask
-    Learning") must come out: masked weights within a few lr of zero, S_t -> 1, masks settling."""
+    Learning") must come out: masked weights within a few lr of zero, S_t -> 1, masks settling.  Also with both
+    moments kept in bf16, where the statistics come from a pass of their own."""
     from paper_2509_25996_amd import example
-    out = example.run(shapes=((64, 1024), (96, 512)), steps=300, mask_period=10, lr=1e-3, lam=1e-3, verbose=False)
+    out = example.run(shapes=((64, 1024), (96, 512)), steps=300, mask_period=10, lr=1e-3, lam=1e-3, verbose=False,
+                      bf16_moments=bf16_moments)
     assert out["largest_masked_weight"] <= 20e-3 * 1.0 and out["pruned_l1_share"] <= 2e-2
     ts, flips, flips_init, kept = zip(*out["history"])
     assert kept[-1] >= 0.98 and kept[-1] > kept[1]
