@@ -69,9 +69,8 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  * as when the rows of the three arrays are interleaved in one allocation).  The new mu is rounded
  * to nearest even when stored; mu~, v and the update of the same iteration use the unrounded
  * value.  22.125 instead of 26.125 bytes per parameter.  Only with CAST_RULE_ADAMS and
- * CAST_RULE_ADDITIVE, and without refresh statistics (else CAST_ERR_CONFIG; cast_mask_stats
- * gives the same numbers in a pass of its own); the compute copy can be written along (24.125
- * bytes per parameter); the work queue flag is ignored with it. */
+ * CAST_RULE_ADDITIVE (else CAST_ERR_CONFIG); the compute copy can be written along (24.125 bytes
+ * per parameter) and refresh statistics gathered; the work queue flag is ignored with it. */
 #define CAST_FLAG_MU_BF16 4u
 /* Both moments in bf16 (only together with CAST_FLAG_MU_BF16; same rules and exclusions): `v`
  * points to bf16 values laid out like `m`.  With beta_2 = 0.999 one iteration changes v by a

@@ -60,11 +60,11 @@ static int flavour_rule(int rule)
 }
 
 // The kernel flavour for one matrix: how the moments are stored comes first (the API has seen to it that bf16
-// moments come with the compute copy at most), then the rule and what else the kernel has to do.
+// moments do not come with the rules that have code of their own), then the rule and what else the kernel has to do.
 static int step_flavour(const cast_adams_config *cfg, bool copy, bool stats)
 {
-    if (cfg->flags & CAST_FLAG_V_BF16) return copy ? kBothBf16Emit : kBothBf16;
-    if (cfg->flags & CAST_FLAG_MU_BF16) return copy ? kMuBf16Emit : kMuBf16;
+    if (cfg->flags & CAST_FLAG_V_BF16) return (copy || stats) ? kBothBf16Emit : kBothBf16;
+    if (cfg->flags & CAST_FLAG_MU_BF16) return (copy || stats) ? kMuBf16Emit : kMuBf16;
     const int rule = flavour_rule(cfg->rule);
     if (rule != 0) return with_rule((copy || stats) ? kEmitAndCount : 0, rule);
     return copy ? kEmitAndCount : (stats ? kStatsOnly : 0);

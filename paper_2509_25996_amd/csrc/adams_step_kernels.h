@@ -66,8 +66,8 @@ static ConstTable as_const_table(const void *device_ptr)
 // shifted left by four.  The low bits: 0 plain; 1 can also write the bf16 compute copy and gather refresh
 // statistics; 3 plain with the first moment kept in bf16 (CAST_FLAG_MU_BF16); 4 plain that can gather refresh
 // statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0); 5 the
-// first moment in bf16 and the compute copy; 6 both moments in bf16, the second one rounded stochastically
-// (CAST_FLAG_V_BF16); 7 the same with the compute copy.  The rules combine with 0 and 1.
+// first moment in bf16, with the abilities of 1; 6 both moments in bf16, the second one rounded stochastically
+// (CAST_FLAG_V_BF16); 7 the same with the abilities of 1.  The rules combine with 0 and 1.
 constexpr int kEmitAndCount = 1;
 constexpr int kMuBf16 = 3;
 constexpr int kStatsOnly = 4;
@@ -78,7 +78,7 @@ constexpr int abilities(int extra) { return extra & 15; }
 constexpr int rule_of(int extra) { return extra >> 4; }      // kRuleAdamwL1, kRuleAdamL1, kRuleMaskedFrozen or 0
 constexpr int with_rule(int extra, int rule) { return extra | (rule << 4); }
 constexpr bool can_emit(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kMuBf16Emit || abilities(extra) == kBothBf16Emit; }
-constexpr bool can_count(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kStatsOnly; }
+constexpr bool can_count(int extra) { return can_emit(extra) || abilities(extra) == kStatsOnly; }
 constexpr bool v_is_bf16(int extra) { return abilities(extra) == kBothBf16 || abilities(extra) == kBothBf16Emit; }
 constexpr bool mu_is_bf16(int extra) { return abilities(extra) == kMuBf16 || abilities(extra) == kMuBf16Emit || v_is_bf16(extra); }
 

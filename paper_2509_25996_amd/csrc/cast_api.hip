@@ -171,7 +171,6 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
         const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
                                              t.compute_copy, t.copy_scale);
         if (rc != CAST_OK) return rc;
-        if ((cfg->flags & CAST_FLAG_MU_BF16) && t.refresh_stats) return CAST_ERR_CONFIG;
     }
     for (int i = 0; i < count; ++i)
         if (!aligned(tensors[i].initial_mask_bits, 4) || !aligned(tensors[i].refresh_stats, 8)) return CAST_ERR_ALIGN;
@@ -189,7 +188,6 @@ cast_status cast_adams_multi_launches(const cast_tensor *tensors, int count, con
         const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
                                              t.compute_copy, t.copy_scale);
         if (rc != CAST_OK) return rc;
-        if ((cfg->flags & CAST_FLAG_MU_BF16) && t.refresh_stats) return CAST_ERR_CONFIG;
     }
     MultiTally tally{0, 0};
     const cast_status rc = launch_adams_step_multi(tensors, count, cfg, nullptr, nullptr, &tally);

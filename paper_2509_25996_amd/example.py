@@ -6,8 +6,7 @@ mask, the fold of the scale factors and packing (Algorithm 1's last lines, Eq. 1
     python -m paper_2509_25996_amd.example
 
 With bf16_moments=True both moments are kept in bf16 (the second one rounded stochastically, a fresh seed per
-step); the refresh steps cannot gather statistics then, so the same numbers come from cast_mask_stats, a pass of
-its own after each refresh step, against a copy of the previous mask.
+step: iteration_config sets cfg.sr_seed = t).
 
 Gradients are random draws, not a loss: the point is the calling sequence, and that under the ramp the
 masked weights are driven to zero (Sec. 4.1, appendix "Mask Learning"), which the numbers it prints show.
@@ -41,19 +40,6 @@ class DenseAdam:
         B.cast_adams_step(self.p, grad, self.m, self.v, self.mask, cfg)
 
 
-def _stats_in_a_pass(x, previous_mask, device):
-    """What a refresh step with refresh_stats reports, from cast_mask_stats after the step (the L1 norms are those of
-    the stepped weights then, one step later than the fused statistics see them)."""
-    out = {}
-    for name, other in (("flips_prev", previous_mask), ("flips_init", x["initial_mask"])):
-        flips = torch.zeros(1, dtype=torch.int64, device=device)
-        l1 = torch.zeros(2, dtype=torch.float64, device=device)
-        B.cast_mask_stats(x["w"], x["mask"], other, flips, l1)
-        out[name] = int(flips.item())
-    out["l1_kept"], out["l1_all"] = (float(t) for t in l1.tolist())
-    return out
-
-
 def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10, lr=1e-3, lam=1e-3, n_keep=2, m_group=4,
         segments=2, device="cuda:0", verbose=True, bf16_moments=False):
     """Returns a dict of what a training script would monitor; see the module docstring."""
@@ -68,7 +54,7 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
         stats.append(B.alloc_refresh_stats(device))
         items.append(dict(w=w, m=m, v=v, mask=mask, grad=torch.empty((r, c), dtype=torch.bfloat16, device=device),
                           scale=torch.ones((r, segments), device=device), scale_grad=torch.zeros((r, segments), device=device),
-                          initial_mask=initial, refresh_stats=None if bf16_moments else stats[-1]))
+                          initial_mask=initial, refresh_stats=stats[-1]))
     tensors = B.TensorList(items, device)
     scale_optimizers = [DenseAdam(x["scale"], lr=1e-4) for x in items]
     total = sum(r * c for r, c in shapes)
@@ -79,16 +65,11 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
             x["grad"].copy_(torch.randn(x["grad"].shape, device=device, generator=gen) * 1e-3)
         cfg = B.iteration_config(t, steps, mask_period=mask_period, lr=lr, lambda_=lam, n_keep=n_keep, m_group=m_group,
                                  scale_segments=segments)
-        if bf16_moments and cfg.refresh_mask:
-            previous = [x["mask"].clone() for x in items]
-        B.cast_adams_step_multi(tensors, cfg)                         # (iteration_config has set cfg.sr_seed = t)
+        B.cast_adams_step_multi(tensors, cfg)
         for opt, x in zip(scale_optimizers, items):                   # A <- Adam(A, dL/dA); the step above used the old A
             opt.step(x["scale_grad"])
         if cfg.refresh_mask:
-            if bf16_moments:
-                s = [_stats_in_a_pass(x, old, device) for x, old in zip(items, previous)]
-            else:
-                s = [B.read_refresh_stats(x) for x in stats]
+            s = [B.read_refresh_stats(x) for x in stats]
             flip_rate = sum(x["flips_prev"] for x in s) / total       # r_t
             initial_flip_rate = sum(x["flips_init"] for x in s) / total       # i_t
             kept_ratio = sum(x["l1_kept"] for x in s) / sum(x["l1_all"] for x in s)       # S_t

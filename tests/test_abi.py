@@ -119,7 +119,7 @@ def test_validation_happens_before_any_launch(lib):
     assert emit(p, p, p, p, p, nul, nul, p, p, 4, 64, 64, C.byref(_cfg()), st) == -2            # copy_scale without segments
     assert emit(p, p, p, p, p, p, nul, nul, C.c_void_p(0x10008), 4, 64, 64, C.byref(c2), st) == -3
     assert emit(nul, nul, nul, nul, nul, nul, nul, nul, nul, 0, 64, 64, C.byref(_cfg()), st) == 0
-    # a first moment kept in bf16 goes with AdamS and additive decay only, without compute copy and statistics
+    # a first moment kept in bf16 goes with AdamS and additive decay only
     mu16 = lambda **kw: _cfg(flags=4, **kw)
     assert step(p, p, p, p, p, nul, nul, 4, 66, 66, C.byref(mu16()), st) == -2
     assert step(p, p, p, p, p, nul, nul, 4, 64, 64, C.byref(mu16(rule=1)), st) == -5
@@ -148,7 +148,7 @@ def test_validation_happens_before_any_launch(lib):
     # refresh statistics: one 16-byte slot per workgroup of the matrix's launch (4 x 64 entries: one workgroup)
     with_stats = (T * 1)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64, None, None, None, 0x10000))
     assert ws_bytes(with_stats, 1, cfg) == 96 + 16 + 16
-    assert lib.cast_adams_step_multi(with_stats, 1, C.byref(_cfg(flags=4, refresh_mask=1)), p, 4096, st) == -5
+    assert lib.cast_adams_step_multi(with_stats, 1, C.byref(_cfg(flags=8, refresh_mask=1)), p, 4096, st) == -5      # bf16 v without bf16 mu
     assert lib.cast_adams_step_multi(arr, 2, C.byref(cfg), p, 176, st) == -2
     assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), p, 32, st) == -2       # workspace too small
     assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), nul, 112, st) == -1

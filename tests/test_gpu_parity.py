@@ -618,10 +618,12 @@ def test_short_sqrt_and_division_every_mantissa(case):
 
 
 # --------------------------------------------------------------------------- refresh statistics gathered by the step itself
+@pytest.mark.parametrize("moments", ["fp32", "mu bf16", "both bf16"])
 @pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
-def test_refresh_steps_gather_mask_learning_statistics(n, m):
+def test_refresh_steps_gather_mask_learning_statistics(n, m, moments):
     """Flip counts against the stored and the initial mask and both L1 norms (appendix "Mask Learning") come
-    out of the refresh step itself; vector shapes, a split plan, odd shapes; exact counts, reproducible norms."""
+    out of the refresh step itself; vector shapes, a split plan, odd shapes; exact counts, reproducible norms;
+    whatever type the moments are kept in."""
     shapes = [(64, 512), (16, 11008), (7, 72), (9, 24), (33, 4096 + 32), (64, 512)]
     shapes = [(r, c) for r, c in shapes if c % m == 0 and (c // 2) % m == 0]
     nseg, steps = 2, 5
@@ -631,7 +633,8 @@ def test_refresh_steps_gather_mask_learning_statistics(n, m):
         items, states = [], []
         for i, (r, c) in enumerate(shapes):
             w0 = synth.weights(12, i, r, c)
-            st = GpuState(w0, nseg, interleaved=(i % 2 == 0))
+            st = GpuState(w0, nseg, interleaved=(i % 2 == 0) and (moments == "fp32" or c % 8 == 0), mu_bf16=moments != "fp32",
+                          v_bf16=moments == "both bf16")
             initial = B.alloc_mask(r, c, DEV)
             B.cast_nm_select(st.w, n, m, initial)
             stats = B.alloc_refresh_stats(DEV)

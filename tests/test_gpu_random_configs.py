@@ -44,7 +44,7 @@ def test_random_configurations_match_the_oracle(seed):
             rule = 3
         bf16 = rnd.random() < 0.6
         emit = rnd.random() < 0.3
-        stats = (not mu16) and rnd.random() < 0.3
+        stats = rnd.random() < 0.3
         queue = rnd.random() < 0.2
         steps = rnd.randint(2, 4)
         period = rnd.choice([1, 2, 3])
