@@ -67,6 +67,46 @@ def test_step_on_sampled_rows_of_full_size_matrices(rows, cols, as_benchmarked):
     assert bool(torch.isfinite(w).all()) and bool(torch.isfinite(v).all()) and bool((v >= 0).all())
 
 
+@pytest.mark.parametrize("with_copy", [False, True])
+@pytest.mark.parametrize("rule", [B.RULE_ADAMW_L1, B.RULE_ADAM_L1, B.RULE_ADDITIVE, B.RULE_MASKED_FROZEN])
+@pytest.mark.parametrize("rows,cols", SHAPES_7B)
+def test_comparison_rules_on_sampled_rows_of_full_size_matrices(rows, cols, rule, with_copy):
+    """The comparison rules (Eq. 9, Eq. 10, additive decay, frozen masked entries) on the LLaMA2-7B shapes in the
+    configuration bench.py times them in (row-interleaved state, bf16 gradients, n = 2, the list call), alone and
+    with the bf16 compute copy written along: sampled whole rows, every bit."""
+    n, steps, n_sample = 2, 3, 16
+    w = synth.device_gaussian((rows, cols), 0.02, torch.float32, 21, DEV)
+    g = synth.device_gaussian((rows, cols), 1e-3, torch.bfloat16, 22, DEV)
+    w, m, v = B.interleaved_state(w)
+    mask = B.alloc_mask(rows, cols, DEV)
+    A = (1 + 0.05 * torch.randn((rows, n), device=DEV, generator=torch.Generator(DEV).manual_seed(4))).contiguous()
+    gA = torch.zeros((rows, n), device=DEV)
+    copy = torch.zeros((rows, cols), dtype=torch.bfloat16, device=DEV) if with_copy else None
+    rng = np.random.default_rng(rows + cols + rule)
+    pick = np.unique(np.concatenate([[0, rows - 1], rng.integers(0, rows, n_sample)]))
+    idx = torch.from_numpy(pick).to(DEV)
+    ow, og, oA = host(w[idx]).copy(), host(g[idx].float()).copy(), host(A[idx]).copy()
+    om, ov = np.zeros_like(ow), np.zeros_like(ow)
+    keep = np.zeros(ow.shape, np.uint8)
+    item = dict(w=w, grad=g, m=m, v=v, mask=mask, scale=A, scale_grad=gA)
+    if with_copy:
+        item.update(compute_copy=copy, copy_scale=A)
+    tl = B.TensorList([item], DEV)
+    for t in range(steps):
+        cfg = B.iteration_config(t, 7500, mask_period=2, lr=2e-5, lambda_=4e-4, scale_segments=n, rule=rule)
+        cfg.alpha = 0.25 + 0.25 * t
+        B.cast_adams_step_multi(tl, cfg)
+        oracle.adams_step(ow, og, om, ov, keep, oracle_cfg(cfg), A=oA, arithmetic="f32", nthreads=8)
+    torch.cuda.synchronize()
+    assert (words(mask[idx]) == oracle.pack_mask_bits(keep)).all()
+    assert_same_bits(host(w[idx]), ow, "w")
+    assert_same_bits(host(m[idx]), om, "mu")
+    assert_same_bits(host(v[idx]), ov, "v")
+    if with_copy:
+        want = oracle.bf16_rne(oracle.weight_scale(ow, oA))
+        assert (host(copy[idx].view(torch.int16)).view(np.uint16) == want).all()
+
+
 @pytest.mark.parametrize("rows,cols", SHAPES_7B)
 @pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
 def test_tie_outlier_select_project_pack_full_size(rows, cols, n, m):
