@@ -29,7 +29,7 @@ BYTES_PER_PARAM = 26.125         # read w, mu, v (fp32) + g (bf16) + 1 mask bit;
 # summarised in profiles/; None until measured.
 MEASURED_TRAFFIC_BYTES_PER_PARAM = 26.20
 
-LR, LAMBDA, TOTAL_STEPS, MASK_PERIOD, SEGMENTS = 2e-5, 4e-7, 7500, 10, 2   # Table 11 (LLaMA), Sec. 4.1, Sec. 5
+LR, LAMBDA, TOTAL_STEPS, MASK_PERIOD, SEGMENTS = 2e-5, 4e-7, 7500, 10, 2   # Table 11 (LLaMA), Sec. 4.1, Sec. 6.1
 
 
 def log(*a):
@@ -69,7 +69,7 @@ class Model:
                                A=torch.ones((r, self.segments), device=dev),
                                gA=torch.zeros((r, self.segments), device=dev)))
 
-    def tensor_list(self, B, scaled: bool, dev, queue: bool, copies=None, stats=None):
+    def tensor_list(self, B, scaled: bool, dev, copies=None, stats=None):
         """Descriptors for the one-call-per-step entry point, marshalled once."""
         self.list = B.TensorList([dict(w=x["w"], grad=x["g"], m=x["m"], v=x["v"], mask=x["mask"],
                                        scale=x["A"] if scaled else None, scale_grad=x["gA"] if scaled else None,
@@ -78,7 +78,7 @@ class Model:
                                        initial_mask=None if stats is None else x["mask"],
                                        refresh_stats=None if stats is None else stats[i])
                                   for i, x in enumerate(self.t)], dev)
-        self.flags = B.FLAG_WORK_QUEUE if queue else 0
+        self.flags = 0
         # launches of the step kernel per call (the list call steps several small matrices with one launch)
         probe = B.AdamsConfig(scale_segments=self.segments if scaled else 0, flags=self.flags)
         self.launches, _ = B.cast_adams_multi_launches(self.list, probe)
@@ -164,9 +164,8 @@ def main():
     ap.add_argument("--no-scale", action="store_true", help="time the step without weight scaling")
     ap.add_argument("--layout", default="interleaved", choices=["interleaved", "interleaved-segments", "separate"],
                     help="w, mu, v of each matrix row-interleaved in one buffer (default) or three dense arrays")
-    ap.add_argument("--launch", default="list", choices=["list", "queue", "per-matrix"],
-                    help="one cast_adams_step_multi call per step (default; 'queue' adds CAST_FLAG_WORK_QUEUE) "
-                         "or one cast_adams_step call per matrix")
+    ap.add_argument("--launch", default="list", choices=["list", "per-matrix"],
+                    help="one cast_adams_step_multi call per step (default) or one cast_adams_step call per matrix")
     ap.add_argument("--row-splits", type=int, default=1, help="per-matrix launch only: launches per matrix (experiment)")
     ap.add_argument("--nm", default="2:4", choices=["1:2", "2:4", "4:8"],
                     help="sparsity pattern of the timed steps (the metric is quoted on 2:4; the extras stay 2:4)")
@@ -194,7 +193,7 @@ def main():
     if model.nm != (2, 4) and not args.no_extra:
         sys.exit("--nm other than 2:4 needs --no-extra")
     if args.launch != "per-matrix":
-        model.tensor_list(B, scaled, dev, queue=args.launch == "queue")
+        model.tensor_list(B, scaled, dev)
     torch.cuda.synchronize()
     log(f"[bench] {args.workload}: {len(model.shapes)} matrices, {model.params} params resident "
         f"({torch.cuda.memory_allocated() / 2**30:.1f} GiB) after {time.time() - t0:.1f} s")
@@ -232,8 +231,7 @@ def main():
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": None if MEASURED_TRAFFIC_BYTES_PER_PARAM is None
                 else MEASURED_TRAFFIC_BYTES_PER_PARAM * model.params / launches,
-                "kernel": ("adams_step_vec_queue" if args.launch == "queue" else "adams_step_vec")
-                + ("<M=4, bf16 grad, stored mask, scaled>" if scaled else "<M=4, bf16 grad, stored mask>"),
+                "kernel": "adams_step_vec" + ("<M=4, bf16 grad, stored mask, scaled>" if scaled else "<M=4, bf16 grad, stored mask>"),
                 "bytes_per_launch": bytes_per_launch, "avg_launch_us": round(dom_ms * 1e3 / launches, 2)}
 
     extra = {"ms_step_non_refresh": round(dom_ms, 3),
@@ -315,7 +313,7 @@ def main():
                 model.rule = 0
                 return e0.elapsed_time(e1) / reps
             copies = [torch.empty(x["w"].shape, dtype=torch.bfloat16, device=dev) for x in model.t]
-            model.tensor_list(B, scaled, dev, queue=False, copies=copies)
+            model.tensor_list(B, scaled, dev, copies=copies)
             ms = timed(0)
             extra["emit_compute_copy_ms_step"] = round(ms, 3)
             extra["emit_compute_copy_GBs"] = round((BYTES_PER_PARAM + 2) * model.params / (ms * 1e-3) / 1e9, 1)
@@ -323,9 +321,9 @@ def main():
             # refresh steps that also gather the mask-learning statistics (one more mask word read per 32 entries,
             # per-workgroup sums through the workspace), against plain refresh steps
             stats = [B.alloc_refresh_stats(dev) for _ in model.t]
-            model.tensor_list(B, scaled, dev, queue=False, stats=stats)
+            model.tensor_list(B, scaled, dev, stats=stats)
             extra["refresh_with_stats_ms_step"] = round(timed(0, t_=10), 3)
-            model.tensor_list(B, scaled, dev, queue=False)
+            model.tensor_list(B, scaled, dev)
             extra["refresh_ms_step"] = round(timed(0, t_=10), 3)
             for name, rule in (("adamw_l1", B.RULE_ADAMW_L1), ("adam_l1", B.RULE_ADAM_L1), ("additive", B.RULE_ADDITIVE),
                                ("masked_frozen", B.RULE_MASKED_FROZEN)):
@@ -339,7 +337,7 @@ def main():
                 kept = [(x["w"], x["m"], x["v"]) for x in model.t]
                 for x in model.t:
                     x["w"], x["m"], x["v"] = B.interleaved_state(x["w"], mu_bf16=True)
-                model.tensor_list(B, scaled, dev, queue=False)
+                model.tensor_list(B, scaled, dev)
                 ms = timed(0)
                 extra["mu_bf16_ms_step"] = round(ms, 3)
                 extra["mu_bf16_Gparams_s"] = round(model.params / (ms * 1e-3) / 1e9, 1)
@@ -347,7 +345,7 @@ def main():
                 free_bytes, _ = torch.cuda.mem_get_info()
                 if free_bytes > 2.5 * model.params:      # the same with the bf16 compute copy written along (24.125 B/param)
                     copies = [torch.empty(x["w"].shape, dtype=torch.bfloat16, device=dev) for x in model.t]
-                    model.tensor_list(B, scaled, dev, queue=False, copies=copies)
+                    model.tensor_list(B, scaled, dev, copies=copies)
                     ms = timed(0)
                     extra["mu_bf16_emit_ms_step"] = round(ms, 3)
                     extra["mu_bf16_emit_GBs"] = round((BYTES_PER_PARAM - 2) * model.params / (ms * 1e-3) / 1e9, 1)
@@ -356,7 +354,7 @@ def main():
                 for x in model.t:
                     x["m"] = x["v"] = None
                     x["w"], x["m"], x["v"] = B.interleaved_state(x["w"], mu_bf16=True, v_bf16=True)
-                model.tensor_list(B, scaled, dev, queue=False)
+                model.tensor_list(B, scaled, dev)
                 ms = timed(0)
                 extra["both_bf16_ms_step"] = round(ms, 3)
                 extra["both_bf16_Gparams_s"] = round(model.params / (ms * 1e-3) / 1e9, 1)
@@ -364,7 +362,7 @@ def main():
                 free_bytes, _ = torch.cuda.mem_get_info()
                 if free_bytes > 2.5 * model.params:
                     copies = [torch.empty(x["w"].shape, dtype=torch.bfloat16, device=dev) for x in model.t]
-                    model.tensor_list(B, scaled, dev, queue=False, copies=copies)
+                    model.tensor_list(B, scaled, dev, copies=copies)
                     ms = timed(0)
                     extra["both_bf16_emit_ms_step"] = round(ms, 3)
                     extra["both_bf16_emit_GBs"] = round((BYTES_PER_PARAM - 6) * model.params / (ms * 1e-3) / 1e9, 1)
@@ -380,7 +378,7 @@ def main():
            "config": {"workload": f"{args.workload} linear weight set ({len(model.shapes)} matrices, {model.params} params), "
                                   f"{args.nm}, fp32 w/mu/v ({args.layout}) + bf16 grads + mask bits resident, "
                                   f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step, "
-                                  f"{ {'list': 'one list call', 'queue': 'one list call (work queue)', 'per-matrix': 'one call per matrix'}[args.launch]} per step",
+                                  f"{ {'list': 'one list call', 'per-matrix': 'one call per matrix'}[args.launch]} per step",
                       "n_keep": model.nm[0], "m_group": model.nm[1], "scale_segments": SEGMENTS if scaled else 0,
                       "pct_of_peak_hbm": round(100 * BYTES_PER_PARAM * value / HBM_PEAK_GBS, 2)},
            "roofline": roofline, "extra": extra}

@@ -59,10 +59,7 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  * this makes the step textbook Adam: what the tests pin against a library optimizer, and a way to
  * step dense parameters such as the scale factors A of Eq. 12 with this library. */
 #define CAST_FLAG_V_FROM_GRAD 1u
-/* cast_adams_step_multi only (ignored elsewhere): step matrices of equal shape with one launch of
- * resident workgroups that draw their work in order from a ticket counter, instead of one launch
- * per matrix.  Same results bit for bit. */
-#define CAST_FLAG_WORK_QUEUE 2u
+/* (flag value 2 is not in use: CAST_ERR_CONFIG) */
 /* Storage variant outside the paper (Algorithm 1 does not say how the moments are kept): the first
  * moment is kept in bf16.  `m` then points to bf16 values (uint16_t), 16-byte aligned, whose row
  * stride in bf16 entries is cols when ld == cols and 2 * ld otherwise (the byte pitch of w and v,
@@ -70,7 +67,7 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  * to nearest even when stored; mu~, v and the update of the same iteration use the unrounded
  * value.  22.125 instead of 26.125 bytes per parameter.  Only with CAST_RULE_ADAMS and
  * CAST_RULE_ADDITIVE (else CAST_ERR_CONFIG); the compute copy can be written along (24.125 bytes
- * per parameter) and refresh statistics gathered; the work queue flag is ignored with it. */
+ * per parameter) and refresh statistics gathered. */
 #define CAST_FLAG_MU_BF16 4u
 /* Both moments in bf16 (only together with CAST_FLAG_MU_BF16; same rules and exclusions): `v`
  * points to bf16 values laid out like `m`.  With beta_2 = 0.999 one iteration changes v by a
@@ -94,7 +91,7 @@ enum { CAST_F32 = 0, CAST_BF16 = 1 };
  *   ADAM_L1        Eq. 10: g~ = g + alpha*lambda*Sign(w);  mu, v from g~ and g~^2
  *   ADDITIVE       Eq. 8 with mu~ = mu + alpha*lambda*Sign(w): the decay is added to the momentum
  *                  instead of being traded against it (the additive decay of Sec. 4.1.2)
- *   MASKED_FROZEN  sparsity-aware fine-tuning (Sec. 5.7): entries with mask bit 0 keep w, mu, v;
+ *   MASKED_FROZEN  sparsity-aware fine-tuning (Sec. 6.7): entries with mask bit 0 keep w, mu, v;
  *                  the others follow Eq. 8 with mu~ = mu */
 enum {
     CAST_RULE_ADAMS = 0,
@@ -185,23 +182,25 @@ cast_status cast_adams_step_emit(float *w, const void *grad, float *m, float *v,
 /*
  * The same iteration over a list of matrices that share one configuration (all linear weights
  * of a model in one call): validated as a whole before anything is launched, then stepped one
- * launch per matrix, or, with CAST_FLAG_WORK_QUEUE, one work-queue launch per group of matrices
- * of equal shape.  w, m, v and mask_bits come out as from cast_adams_step on each matrix, bit for
- * bit; so does scale_grad, except for row segments of more than 2048 entries other than 4096, which
- * the list call steps in pieces of 512, 1024 or 2048 entries: their sums are added in another,
- * equally fixed order (per piece, then the pieces left to right).
+ * launch per matrix, small matrices of one shape several to a launch.  w, m, v and mask_bits come
+ * out as from cast_adams_step on each matrix, bit for bit; so does scale_grad, except for row
+ * segments of more than 2048 entries other than 4096, which the list call steps in pieces of 512,
+ * 1024 or 2048 entries: their sums are added in another, equally fixed order (per piece, then the
+ * pieces left to right).
  *   tensors    HOST in   `count` descriptors; the device buffers they name follow the rules of
  *                        cast_adams_step (scale / scale_grad NULL or not for all alike, per cfg).
  *                        No two descriptors may name overlapping buffers: the matrices are stepped
  *                        in an order of the library's choosing, several of them by one launch.
  *   workspace  DEVICE    at least cast_adams_multi_workspace_bytes(tensors, count, cfg) bytes (it
- *                        depends on shapes, row strides, scale_grad being NULL or not,
- *                        cfg->scale_segments and cfg->flags only), 16-byte aligned, owned by the
- *                        caller; it is overwritten by every call and used by the kernels of that
- *                        call, so it must not be shared between streams (too small: CAST_ERR_SHAPE)
- * Without CAST_FLAG_WORK_QUEUE the call enqueues kernel launches only (no copies, no memsets), so it
- * can be recorded while the stream is being captured into a HIP graph; with the flag it first copies
- * a table from pageable host memory to the workspace, which capture does not allow.
+ *                        depends on shapes, row strides, scale_grad and refresh_stats being NULL or
+ *                        not and cfg->scale_segments only; it holds the dL/dA sums of the pieces and
+ *                        the per-workgroup refresh statistics until follow-up launches of the same
+ *                        call have added them up), 16-byte aligned, owned by the caller; it is
+ *                        overwritten by every call and used by the kernels of that call, so it must
+ *                        not be shared between streams (too small: CAST_ERR_SHAPE; may be NULL when
+ *                        0 bytes are needed)
+ * The call enqueues kernel launches only (no copies, no memsets, nothing allocated on the device), so
+ * it can be recorded while the stream is being captured into a HIP graph.
  */
 /* Mask-learning statistics of one matrix gathered by a refresh step itself (appendix "Mask
  * Learning"; the numerators of the flip rate r_t and the initial flip rate i_t, and both terms of

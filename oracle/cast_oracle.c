@@ -100,7 +100,7 @@ enum {
     RULE_ADAM_L1 = 2,        /* Eq. 10: decay added to the gradient, inside both moments       */
     RULE_ADDITIVE = 3,       /* Eq. 8 with mu~ = mu + alpha*lambda*Sign: decay added to, not   */
                              /* traded against, the momentum (the "additive decay" of Fig. 3) */
-    RULE_MASKED_FROZEN = 4   /* sparsity-aware fine-tuning (Sec. 5.7): entries with mask bit 0 */
+    RULE_MASKED_FROZEN = 4   /* sparsity-aware fine-tuning (Sec. 6.7): entries with mask bit 0 */
                              /* are not updated at all; the others follow Eq. 8 (mu~ = mu)     */
 };
 

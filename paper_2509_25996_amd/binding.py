@@ -15,7 +15,6 @@ LIB_PATH = os.environ.get("CAST_LIBRARY") or os.path.join(_HERE, "libcast.so")  
 
 CAST_F32, CAST_BF16 = 0, 1
 FLAG_V_FROM_GRAD = 1
-FLAG_WORK_QUEUE = 2
 FLAG_MU_BF16 = 4
 FLAG_V_BF16 = 8
 RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = range(5)
@@ -288,15 +287,12 @@ class TensorList:
                                     None if cp is None else cp.data_ptr(), None if cps is None else cps.data_ptr(),
                                     None if im is None else im.data_ptr(), None if rs is None else rs.data_ptr())
         self.count = n
-        # the workspace depends on the shapes, on the number of scaling segments and on the launch form
+        # the workspace depends on the shapes and on the number of scaling segments
         segments = {0 if x.get("scale") is None else x["scale"].shape[1] for x in self.items if x["w"].numel()}
         if len(segments) > 1:
             raise ValueError("all matrices of a list must have the same number of scaling segments")
         probe = AdamsConfig(scale_segments=segments.pop() if segments else 0)
-        need = 16
-        for flags in (0, FLAG_WORK_QUEUE):
-            probe.flags = flags
-            need = max(need, cast_adams_multi_workspace_bytes(self.array, n, probe))
+        need = max(16, cast_adams_multi_workspace_bytes(self.array, n, probe))
         self.workspace = torch.empty(need, dtype=torch.uint8, device=device)
 
 

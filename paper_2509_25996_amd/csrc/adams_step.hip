@@ -3,8 +3,6 @@
 // adams_step_kernels.h.
 #include <stdlib.h>
 
-#include <vector>
-
 #include "adams_step_kernels.h"
 
 #pragma clang fp contract(off)
@@ -70,23 +68,34 @@ static int step_flavour(const cast_adams_config *cfg, bool copy, bool stats)
     return copy ? kEmitAndCount : (stats ? kStatsOnly : 0);
 }
 
-static int env_int(const char *name, int fallback)
+// Launch-plan parameters.  The shipped library uses the measured-best constants; a build with
+// -DCAST_TUNING (never the one build.py makes) reads them from the environment once per process,
+// for sweeps.  They decide the span and piece plan, hence the summation order of dL/dA and the
+// launch counts, which is why the product build does not let the environment near them.
+#ifdef CAST_TUNING
+static int knob(const char *name, int fallback, int lo, int hi)
 {
     const char *e = getenv(name);
-    return e && *e ? atoi(e) : fallback;
+    if (!e || !*e) return fallback;
+    const int x = atoi(e);
+    return x < lo || x > hi ? fallback : x;
 }
+#else
+static constexpr int knob(const char *, int fallback, int, int) { return fallback; }
+#endif
 
 SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool allow_split)
 {
     // HBM rewards a narrow window of addresses in flight: wavefronts are kept short-lived (about
     // one chunk of 256 entries each) and the spans of one workgroup are contiguous, so that the
     // workgroups the dispatcher has resident at any time cover a compact range of every array.
-    // Tuning knobs (read once): CAST_SPAN_LEN forces the flat span length, CAST_WAVES_PER_SPAN
-    // the number of cooperating wavefronts, CAST_BLOCK_WAVES the workgroup size in wavefronts.
-    static const int forced_len = env_int("CAST_SPAN_LEN", 0);
-    static const int forced_p = env_int("CAST_WAVES_PER_SPAN", 0);
-    static const int forced_bw = env_int("CAST_BLOCK_WAVES", 0);
-    static const int piece_len = env_int("CAST_PIECE_LEN", 1024);
+    // CAST_SPAN_LEN forces the flat span length (a multiple of 256, at most 64 chunks: a wavefront's flip
+    // counts and offsets stay far below 32 bits), CAST_WAVES_PER_SPAN the number of cooperating
+    // wavefronts, CAST_BLOCK_WAVES the workgroup size in wavefronts; 0 = chosen by the plan.
+    static const int forced_len = knob("CAST_SPAN_LEN", 0, 0, 64 * kChunk);
+    static const int forced_p = knob("CAST_WAVES_PER_SPAN", 0, 0, kMaxBlockWaves);
+    static const int forced_bw = knob("CAST_BLOCK_WAVES", 0, 0, kMaxBlockWaves);
+    static const int piece_len = knob("CAST_PIECE_LEN", 1024, 32, 1 << 20);
     SpanPlan p{};
     SpanGeom &g = p.geom;
     g.total = rows * cols;
@@ -97,8 +106,8 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool
     g.div_spans_per_row = make_fast_div(1);
     g.pieces_per_segment = 1;
     g.div_pieces = make_fast_div(1);
-    static const int split_min_chunks = env_int("CAST_SPLIT_MIN_CHUNKS", kPieceChunks + 1);
-    static const int piece_chunks_knob = env_int("CAST_PIECE_CHUNKS", 0);      // 0: chosen per segment length
+    static const int split_min_chunks = knob("CAST_SPLIT_MIN_CHUNKS", kPieceChunks + 1, 2, 1 << 20);
+    static const int piece_chunks_knob = knob("CAST_PIECE_CHUNKS", 0, 0, kPieceChunks);      // 0: chosen per segment length
     int block_waves = kBlockWaves;
     int per_row = n_segments;
     if (per_row == 0 && ld != cols) {
@@ -198,14 +207,10 @@ static StepScalars make_scalars(const cast_adams_config *cfg)
     return s;
 }
 
-// how a vector launch is issued: by the dispatcher (tickets == nullptr) or as a work queue
+// the shape of a vector launch
 struct VecLaunch {
     unsigned grid_x, grid_y;
     int block_threads;
-    unsigned long long *tickets;
-    unsigned long long tasks;
-    uint32_t blocks_per_matrix;
-    int log2_run;
     bool split;
     int extra;       // the kernel flavour (EXTRA of adams_step_vec)
 };
@@ -252,17 +257,6 @@ template <int M, bool BF16, bool REFRESH, bool SCALED>
 static void launch_vec_kernel(const VecLaunch &l, const SpanArgs &a, hipStream_t st)
 {
     const dim3 grid(l.grid_x, l.grid_y), block(l.block_threads);
-    if (l.tickets) {
-        const QueueArgs q{l.tickets, (uint32_t)l.tasks, l.blocks_per_matrix, make_fast_div(l.blocks_per_matrix), l.log2_run};
-        if constexpr (SCALED) {
-            if (l.split) {
-                hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, true, true>), dim3(l.grid_x), block, 0, st, a, q);
-                return;
-            }
-        }
-        hipLaunchKernelGGL((adams_step_vec_queue<M, BF16, REFRESH, SCALED>), dim3(l.grid_x), block, 0, st, a, q);
-        return;
-    }
     switch (rule_of(l.extra)) {
     case kRuleAdamwL1: launch_vec_abilities<M, BF16, REFRESH, SCALED, kRuleAdamwL1>(l, a, grid, block, st); break;
     case kRuleAdamL1: launch_vec_abilities<M, BF16, REFRESH, SCALED, kRuleAdamL1>(l, a, grid, block, st); break;
@@ -353,8 +347,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
     if (p.vec) {
         SpanArgs a{{{w, grad, m, v, mask_bits, scale, scale_grad, split ? area->base : nullptr, stats_partials, stats_initial,
                      static_cast<uint16_t *>(x.compute_copy), x.copy_scale}},
-                   as_const_table(nullptr), p.geom, make_scalars(cfg)};
-        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, nullptr, 0, 0, 0, split, extra}, a, st);
+                   p.geom, make_scalars(cfg)};
+        launch_vec_any(cfg->m_group, bf16, refresh, scaled, VecLaunch{p.grid, 1, p.block_threads, split, extra}, a, st);
         if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         if (split) {      // this matrix's part of the area is now in use until the pieces have been added up
             const PieceJob job{area->base, scale_grad, p.segments, p.geom.pieces_per_segment};
@@ -395,7 +389,7 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, const SpanPlan &p, const cast_adams_config *cfg,
                                            int flavour, StatsArea *stats_area, hipStream_t st)
 {
-    SpanArgs a{{}, as_const_table(nullptr), p.geom, make_scalars(cfg)};
+    SpanArgs a{{}, p.geom, make_scalars(cfg)};
     const bool refresh = cfg->refresh_mask != 0;
     a.geom.m_row_gap = mu_bf16_ld(ts[0]->cols, ts[0]->ld) - ts[0]->cols;
     for (int k = 0; k < n; ++k) {
@@ -410,26 +404,22 @@ static cast_status launch_adams_step_fused(const cast_tensor *const *ts, int n, 
                               can_emit(flavour) ? static_cast<uint16_t *>(t.compute_copy) : nullptr, can_emit(flavour) ? t.copy_scale : nullptr};
     }
     launch_vec_any(cfg->m_group, cfg->grad_dtype == CAST_BF16, refresh, cfg->scale_segments > 0,
-                   VecLaunch{p.grid, (unsigned)n, p.block_threads, nullptr, 0, 0, 0, false, flavour}, a, st);
+                   VecLaunch{p.grid, (unsigned)n, p.block_threads, false, flavour}, a, st);
     return launch_status();
 }
 
-// Workspace of a list call: the table of buffer sets, one ticket counter per launch of the work
-// queue, then room for the piece sums of every matrix with a split plan.
+// Workspace of a list call: room for the piece sums of every matrix with a split plan, then one
+// slot per workgroup for every matrix that wants refresh statistics.
 struct MultiLayout {
-    size_t table_bytes, counter_bytes;
     uint64_t piece_floats;
     uint64_t stats_slots;
-    size_t total() const
-    {
-        return table_bytes + counter_bytes + (size_t)piece_floats * sizeof(float) + (size_t)stats_slots * sizeof(StatsPartial);
-    }
+    size_t total() const { return (size_t)piece_floats * sizeof(float) + (size_t)stats_slots * sizeof(StatsPartial); }
 };
 
 static MultiLayout multi_layout(const cast_tensor *ts, int count, const cast_adams_config *cfg)
 {
     const size_t n = (size_t)(count > 0 ? count : 0);
-    MultiLayout l{n * sizeof(TensorPtrs), (n * sizeof(unsigned long long) + 15) & ~(size_t)15, 0, 0};
+    MultiLayout l{0, 0};
     for (size_t i = 0; ts && cfg && i < n; ++i) {      // a slot per workgroup for every matrix that wants refresh statistics
         if (ts[i].rows <= 0 || ts[i].cols <= 0 || !ts[i].refresh_stats) continue;
         const bool may_split = cfg->scale_segments > 0 && ts[i].scale_grad;
@@ -451,163 +441,34 @@ size_t multi_workspace_bytes(const cast_tensor *ts, int count, const cast_adams_
     return multi_layout(ts, count, cfg).total();
 }
 
-static int device_compute_units()
-{
-    static int cus = 0;      // of the device current at the first call
-    if (cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
-        else cus = 256;
-    }
-    return cus;
-}
-
-// The work-queue form of the list call: matrices of equal (rows, cols, ld) whose plan gives every
-// wavefront one chunk per share form one launch of resident workgroups; their buffer sets go to the
-// workspace as a table, with the zeroed ticket counters behind it.  Marks what it steps in `taken`.
-static cast_status launch_queue_groups(const cast_tensor *ts, int count, const cast_adams_config *cfg, void *workspace,
-                                       const MultiLayout &layout, PieceArea &area, PieceJobQueue &jobs,
-                                       std::vector<char> &taken, hipStream_t st, MultiTally *tally)
-{
-    const bool dry = tally != nullptr;
-    const bool bf16 = cfg->grad_dtype == CAST_BF16;
-    const bool refresh = cfg->refresh_mask != 0;
-    const bool scaled = cfg->scale_segments > 0;
-    // tuning knobs (read once): resident wavefronts per compute unit of the work queue
-    static const int waves_per_cu = env_int("CAST_QUEUE_WAVES_PER_CU", 16);
-    static const int log2_run = env_int("CAST_QUEUE_LOG2_RUN", 1) & 7;      // shares per ticket = 1 << log2_run
-    static const int queue_block_waves = env_int("CAST_QUEUE_BLOCK_WAVES", 8);
-    if (waves_per_cu <= 0) return CAST_OK;
-    std::vector<int> order;           // indices of vector-path matrices, grouped by shape
-    struct Group { int first, n; SpanPlan plan; int block_waves; unsigned blocks_per_matrix; };
-    std::vector<Group> groups;
-    for (int i = 0; i < count; ++i) {
-        if (taken[i] || ts[i].rows == 0 || ts[i].cols == 0) continue;
-        const bool wants_gA = scaled && ts[i].scale_grad != nullptr;
-        SpanPlan p = plan_spans(ts[i].rows, ts[i].cols, ts[i].ld, cfg->scale_segments, wants_gA && layout.piece_floats > 0);
-        if (!p.vec) continue;
-        if (p.geom.spans_per_row == 0) {      // flat: one chunk per span
-            p.geom.span_len = kChunk;
-            p.geom.num_spans = (p.geom.total + kChunk - 1) / kChunk;
-        }
-        // the work queue gives every wavefront one chunk of a share; other plans go the ordinary way
-        if (p.geom.span_len > (int64_t)p.geom.waves_per_span * kChunk) continue;
-        // workgroups of the work queue: as many spans side by side as fit the wanted size
-        const int P = p.geom.waves_per_span;
-        int block_waves = p.block_threads / kWave;
-        if ((P & (P - 1)) == 0 && P < queue_block_waves && queue_block_waves <= kMaxBlockWaves && queue_block_waves % P == 0)
-            block_waves = queue_block_waves;
-        const int64_t spans_per_block = block_waves / P;
-        Group g{(int)order.size(), 0, p, block_waves, (unsigned)((p.geom.num_spans + spans_per_block - 1) / spans_per_block)};
-        // tickets are 32-bit task numbers inside the kernel
-        const int fit = (int)(((int64_t)1 << 31) / g.blocks_per_matrix);
-        for (int j = i; j < count && g.n < fit && g.n < 65535; ++j)
-            if (!taken[j] && ts[j].rows == ts[i].rows && ts[j].cols == ts[i].cols && ts[j].ld == ts[i].ld &&
-                (ts[j].scale_grad == nullptr) == (ts[i].scale_grad == nullptr)) {
-                taken[j] = 1;
-                order.push_back(j);
-                ++g.n;
-            }
-        groups.push_back(g);
-    }
-    if (dry) {
-        tally->step_launches += (int)groups.size();
-        for (const Group &g : groups)
-            if (g.plan.geom.pieces_per_segment > 1)
-                for (int k = 0; k < g.n; ++k)
-                    if (++tally->split_matrices % kMaxPieceJobs == 1) ++tally->other_launches;
-    }
-    if (!order.empty() && !dry) {
-        const size_t table_bytes = layout.table_bytes;
-        std::vector<unsigned char> image(table_bytes + groups.size() * sizeof(unsigned long long), 0);
-        TensorPtrs *table = reinterpret_cast<TensorPtrs *>(image.data());
-        std::vector<PieceJob> piece_jobs;      // of the matrices with split plans, launched after their group
-        std::vector<size_t> piece_job_group;
-        for (size_t gi = 0; gi < groups.size(); ++gi) {
-            const Group &g = groups[gi];
-            const bool split = g.plan.geom.pieces_per_segment > 1;
-            for (int k = 0; k < g.n; ++k) {
-                const cast_tensor &t = ts[order[g.first + k]];
-                float *piece_sums = nullptr;
-                if (split) {      // (the layout has counted every such matrix, so the area has the room)
-                    piece_sums = area.base;
-                    const uint64_t used = ((uint64_t)g.plan.geom.num_spans + 3) & ~(uint64_t)3;
-                    area.base += used;
-                    area.floats -= used < area.floats ? used : area.floats;
-                    piece_jobs.push_back(PieceJob{piece_sums, t.scale_grad, g.plan.segments, g.plan.geom.pieces_per_segment});
-                    piece_job_group.push_back(gi);
-                }
-                table[g.first + k] = TensorPtrs{t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, piece_sums, nullptr, nullptr, nullptr, nullptr};
-            }
-        }
-        // pageable source: the runtime stages it before returning, the copy itself is ordered on the stream
-        if (hipMemcpyAsync(workspace, image.data(), image.size(), hipMemcpyHostToDevice, st) != hipSuccess)
-            return CAST_ERR_LAUNCH;
-        unsigned long long *counters = reinterpret_cast<unsigned long long *>(static_cast<char *>(workspace) + table_bytes);
-        const StepScalars sc = make_scalars(cfg);
-        size_t next_job = 0;
-        for (size_t gi = 0; gi < groups.size(); ++gi) {
-            const Group &g = groups[gi];
-            SpanArgs a{{}, as_const_table(static_cast<const TensorPtrs *>(workspace) + g.first), g.plan.geom, sc};
-            const unsigned long long tasks = (unsigned long long)g.blocks_per_matrix * (unsigned)g.n;
-            int blocks_per_cu = waves_per_cu / g.block_waves;
-            if (blocks_per_cu < 1) blocks_per_cu = 1;
-            unsigned long long resident = (unsigned long long)device_compute_units() * blocks_per_cu;
-            if (resident > tasks) resident = tasks;
-            const VecLaunch l{(unsigned)resident, 1, g.block_waves * kWave, counters + gi, tasks, g.blocks_per_matrix, log2_run,
-                              g.plan.geom.pieces_per_segment > 1, 0};
-            launch_vec_any(cfg->m_group, bf16, refresh, scaled, l, a, st);
-            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
-            for (; next_job < piece_jobs.size() && piece_job_group[next_job] == gi; ++next_job) {
-                if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
-                jobs.add(piece_jobs[next_job]);
-            }
-        }
-    }
-    return CAST_OK;
-}
-
-// A list of matrices that share one configuration.  Default: one launch per matrix, small matrices
-// of one shape and one kernel flavour several to a launch, long row segments as split plans whose
-// pieces' sums (and the refresh statistics' partial sums) go through the workspace and are added up
-// by follow-up launches.  With CAST_FLAG_WORK_QUEUE, matrices of equal (rows, cols, ld) that the
-// queue can take form one launch of resident workgroups (see adams_step_vec_queue), their buffer
-// addresses in a table that is copied, together with zeroed ticket counters, to the workspace first.
+// A list of matrices that share one configuration: one launch per matrix, small matrices of one
+// shape and one kernel flavour several to a launch, long row segments as split plans whose pieces'
+// sums (and the refresh statistics' partial sums) go through the workspace and are added up by
+// follow-up launches.  Kernel launches only: nothing is copied, cleared or allocated on the device.
+// `taken`: `count` bytes of host scratch from the caller (which matrices have been stepped).
 // With `tally` the call only counts the launches it would make (nothing is enqueued).
 cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast_adams_config *cfg,
-                                    void *workspace, hipStream_t st, MultiTally *tally)
+                                    void *workspace, char *taken, hipStream_t st, MultiTally *tally)
 {
     const bool dry = tally != nullptr;
     if (dry) *tally = MultiTally{0, 0};
-    // The work queue is opt-in: one launch per matrix has measured faster at every size tried.
-    bool use_queue = (cfg->flags & CAST_FLAG_WORK_QUEUE) != 0;
-    // the work queue knows neither the comparison rules with code of their own nor the compute copy
-    if (cfg->rule == CAST_RULE_ADAMW_L1 || cfg->rule == CAST_RULE_ADAM_L1 || cfg->rule == CAST_RULE_MASKED_FROZEN) use_queue = false;
-    if (cfg->flags & (CAST_FLAG_MU_BF16 | CAST_FLAG_V_BF16)) use_queue = false;      // nor moments kept in bf16
     const bool want_stats = cfg->refresh_mask != 0;
-    for (int i = 0; i < count; ++i)
-        if (ts[i].compute_copy || (want_stats && ts[i].refresh_stats)) use_queue = false;      // nor refresh statistics
     const MultiLayout layout = multi_layout(ts, count, cfg);
     PieceJobQueue jobs;
-    // the workspace: table of buffer sets, ticket counters, piece sums, statistics slots (a dry run has none)
-    float *const piece_base = workspace ? reinterpret_cast<float *>(static_cast<char *>(workspace) + layout.table_bytes + layout.counter_bytes)
-                                        : nullptr;
+    // the workspace: piece sums, then statistics slots (a dry run has none)
+    float *const piece_base = static_cast<float *>(workspace);
     StatsPartial *const stats_base = workspace ? reinterpret_cast<StatsPartial *>(piece_base + layout.piece_floats) : nullptr;
     PieceArea area{piece_base, layout.piece_floats, &jobs};
-    std::vector<char> taken(count, 0);
-    if (use_queue) {
-        const cast_status rc = launch_queue_groups(ts, count, cfg, workspace, layout, area, jobs, taken, st, tally);
-        if (rc != CAST_OK) return rc;
-    }
+    for (int i = 0; i < count; ++i) taken[i] = 0;
     StatsJobQueue stats_jobs;
     StatsArea stats_area{stats_base, layout.stats_slots, &stats_jobs};
     // Small matrices of one shape and one kernel flavour share a launch (they need not follow each
     // other in the list: the matrices are independent).  A launch is kept below about 72 M entries: q, k, v, o of a
     // LLaMA2-7B layer go together, 16 of the 768 x 768 matrices of a 125M model; longer launches
     // lose to the drift between compute units what they gain on ramps.
-    static const int fuse_limit = env_int("CAST_FUSE", kMaxFused);            // matrices per launch (1 = never fuse)
-    static const int64_t fuse_max_params = (int64_t)env_int("CAST_FUSE_MAX_MPARAMS", 24) << 20;
-    static const int64_t fuse_launch_params = (int64_t)env_int("CAST_FUSE_LAUNCH_MPARAMS", 72) << 20;
+    static const int fuse_limit = knob("CAST_FUSE", kMaxFused, 1, kMaxFused);            // matrices per launch (1 = never fuse)
+    static const int64_t fuse_max_params = (int64_t)knob("CAST_FUSE_MAX_MPARAMS", 24, 1, 1024) << 20;
+    static const int64_t fuse_launch_params = (int64_t)knob("CAST_FUSE_LAUNCH_MPARAMS", 72, 1, 1024) << 20;
     int dry_stats = 0;      // dry run: statistics jobs waiting for their launch
     auto stats_room = [&](int n) -> cast_status {      // room for n more statistics jobs before their launch is enqueued
         if (dry) {

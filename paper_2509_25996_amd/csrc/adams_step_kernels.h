@@ -13,9 +13,8 @@
 
 namespace cast {
 
-// The buffers of one matrix.  A dispatcher-dealt launch carries up to kMaxFused sets in its
-// arguments (workgroups with blockIdx.y = k step matrix k); the work queue reads the set of a
-// matrix from a table in device memory.
+// The buffers of one matrix.  A launch carries up to kMaxFused sets in its arguments
+// (workgroups with blockIdx.y = k step matrix k).
 struct TensorPtrs {
     float *w;
     const void *grad;
@@ -25,14 +24,14 @@ struct TensorPtrs {
     const float *scale;
     float *scale_grad;
     float *piece_sums;    // split plans: one partial dL/dA sum per piece, else unused
-    // Flavours that gather refresh statistics only (never read by the work queue):
+    // Flavours that gather refresh statistics only:
     struct StatsPartial *stats_partials;   // one slot per workgroup of the launch, or NULL
     const uint32_t *initial_mask;          // the mask flips_init counts against, or NULL
     // Flavours that can write the bf16 copy of the updated weights for the next forward pass
     // (Eq. 12 applied: copy_scale[r, s] * w_new, or w_new itself when copy_scale is NULL), or NULL:
     uint16_t *compute_copy;
     const float *copy_scale;
-};                        // 96 bytes per entry; the work queue reads the first 64
+};
 
 // What one workgroup contributes to the mask-learning statistics of a refresh step
 // (appendix "Mask Learning"): changed mask bits against the stored and the initial mask, and
@@ -42,24 +41,13 @@ struct StatsPartial {
     float l1_kept, l1_all;
 };
 
-// The table is addressed through the constant address space: its entries do not change while a
-// kernel runs, and only then are they read with scalar loads, straight into the scalar registers
-// where buffer resources have to live.
-typedef const TensorPtrs __attribute__((address_space(4))) *ConstTable;
-
-constexpr int kMaxFused = 16;     // matrices of equal shape that one dispatcher-dealt launch can step (gridDim.y)
+constexpr int kMaxFused = 16;     // matrices of equal shape that one launch can step (gridDim.y)
 
 struct SpanArgs {
-    TensorPtrs set[kMaxFused];   // the buffer sets of a dispatcher-dealt launch: matrix blockIdx.y
-    ConstTable table;     // the buffer sets of a list launch (work queue)
+    TensorPtrs set[kMaxFused];   // the buffer sets of the launch: matrix blockIdx.y
     SpanGeom geom;
     StepScalars s;
 };
-
-static ConstTable as_const_table(const void *device_ptr)
-{
-    return (ConstTable)(uintptr_t)device_ptr;
-}
 
 // Kernel flavours (template argument EXTRA) = what the kernel can do besides Algorithm 1, in the low four bits,
 // plus the comparison rule it applies (Eq. 9, Eq. 10, frozen masked entries; 0: none), fixed at compile time,
@@ -156,38 +144,12 @@ struct SpanCtx {
     int64_t dense_begin;           // EXTRA (a bf16 second moment): index row * cols + col of the span's first entry
 };
 
-// `matrix` selects the buffer set (entry of the table of a list call), `block` the workgroup's
-// share of that matrix: block_waves / waves_per_span consecutive spans.
-template <bool BF16, bool SCALED, bool FROM_TABLE, bool SPLIT = false, int EXTRA = 0>
+// `matrix` selects the buffer set, `block` the workgroup's share of that matrix:
+// block_waves / waves_per_span consecutive spans.
+template <bool BF16, bool SCALED, bool SPLIT = false, int EXTRA = 0>
 __device__ __forceinline__ void span_open(const SpanArgs &a, uint32_t matrix, int64_t block, int wave, SpanCtx &c)
 {
-    // The buffer set of this launch, or of one matrix of a list.  The table is read through the
-    // constant address space so that the (wave-uniform) loads are scalar loads and the pointers
-    // arrive in scalar registers, where buffer resources have to live.
-    TensorPtrs t;
-    if constexpr (FROM_TABLE) {
-        // explicit scalar loads of the first 64 bytes of the entry (two 8-dword reads)
-        typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-        const uint64_t entry = uniform_u64((uint64_t)(uintptr_t)a.table + (uint64_t)matrix * sizeof(TensorPtrs));
-        u32x8 lo, hi;
-        asm volatile("s_load_dwordx8 %0, %2, 0x0\n\ts_load_dwordx8 %1, %2, 0x20\n\ts_waitcnt lgkmcnt(0)"
-                     : "=&s"(lo), "=&s"(hi) : "s"(entry) : "memory");
-        auto ptr = [](uint32_t l, uint32_t h) { return (uintptr_t)(((uint64_t)h << 32) | l); };
-        t.w = (float *)ptr(lo[0], lo[1]);
-        t.grad = (const void *)ptr(lo[2], lo[3]);
-        t.m = (float *)ptr(lo[4], lo[5]);
-        t.v = (float *)ptr(lo[6], lo[7]);
-        t.mask = (uint32_t *)ptr(hi[0], hi[1]);
-        t.scale = (const float *)ptr(hi[2], hi[3]);
-        t.scale_grad = (float *)ptr(hi[4], hi[5]);
-        t.piece_sums = (float *)ptr(hi[6], hi[7]);
-        t.stats_partials = nullptr;
-        t.initial_mask = nullptr;
-        t.compute_copy = nullptr;
-        t.copy_scale = nullptr;
-    } else {
-        t = a.set[matrix];     // a scalar load from the kernel arguments at a wave-uniform offset
-    }
+    const TensorPtrs t = a.set[matrix];     // a scalar load from the kernel arguments at a wave-uniform offset
     const SpanSlot slot = span_slot(a.geom, block, wave, blockDim.x / kWave);
     c.span = (int64_t)uniform_u64((unsigned long long)slot.span);
     c.sub = slot.sub;
@@ -248,7 +210,7 @@ __device__ __forceinline__ int first_offset(const SpanCtx &c, int lane) { return
 // all 64 lanes.
 // LDS through which the wavefronts of a workgroup combine their refresh statistics.
 struct StatsShared {
-    uint32_t flips[kMaxBlockWaves];       // flips against the stored mask | flips against the initial mask << 16
+    uint32_t flips_prev[kMaxBlockWaves], flips_init[kMaxBlockWaves];
     float l1_kept[kMaxBlockWaves], l1_all[kMaxBlockWaves];
 };
 
@@ -360,11 +322,14 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
     bool synced = false;      // whether a workgroup barrier has been passed since the statistics went to LDS
     if constexpr (kStats) {
         if (c.stats_slot) {      // uniform over the workgroup: every wavefront leaves its sums in LDS
-            const uint32_t flips = wave_sum_u32(flips_prev | (flips_init << 16));     // at most 64 * 4 * 64 each
+            // 32-bit counts cannot overflow: all the spans of a workgroup together hold fewer than 2^28 entries
+            flips_prev = wave_sum_u32(flips_prev);
+            flips_init = wave_sum_u32(flips_init);
             l1_kept = wave_sum_fixed_order(l1_kept);
             l1_all = wave_sum_fixed_order(l1_all);
             if (lane == 0) {
-                stats_shared->flips[wave] = flips;
+                stats_shared->flips_prev[wave] = flips_prev;
+                stats_shared->flips_init[wave] = flips_init;
                 stats_shared->l1_kept[wave] = l1_kept;
                 stats_shared->l1_all[wave] = l1_all;
             }
@@ -391,12 +356,10 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
         if (c.stats_slot) {      // one slot per workgroup, the wavefronts' sums added in wavefront order
             if (!synced) __syncthreads();
             if (threadIdx.x == 0) {
-                uint32_t flips = 0;
                 StatsPartial out{0, 0, 0.0f, 0.0f};
                 for (int k = 0; k < (int)(blockDim.x / kWave); ++k) {
-                    flips = stats_shared->flips[k];
-                    out.flips_prev += flips & 0xFFFFu;
-                    out.flips_init += flips >> 16;
+                    out.flips_prev += stats_shared->flips_prev[k];
+                    out.flips_init += stats_shared->flips_init[k];
                     out.l1_kept = k == 0 ? stats_shared->l1_kept[0] : out.l1_kept + stats_shared->l1_kept[k];
                     out.l1_all = k == 0 ? stats_shared->l1_all[0] : out.l1_all + stats_shared->l1_all[k];
                 }
@@ -406,7 +369,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
     }
 }
 
-// One matrix, one workgroup per share, dealt by the hardware dispatcher.  SPLIT: the spans are
+// One workgroup per share of a matrix.  SPLIT: the spans are
 // pieces of row segments (Eq. 12) too long for one workgroup of short-lived wavefronts; each
 // workgroup leaves the dL/dA sum of its piece in a[.].piece_sums and sum_piece_sums adds them up.
 // EXTRA: the kernel flavour (above); the plain ones (0) carry no code but Algorithm 1's.
@@ -417,7 +380,7 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform, in a scalar register
     SpanCtx c;
-    span_open<BF16, SCALED, false, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
+    span_open<BF16, SCALED, SPLIT, EXTRA>(a, blockIdx.y, blockIdx.x, wave, c);
     Chunk<BF16> first;
     chunk_load<BF16, (!REFRESH || can_count(EXTRA)), (REFRESH && can_count(EXTRA)), mu_is_bf16(EXTRA), v_is_bf16(EXTRA)>(first, c.b, first_offset(c, lane));
     if constexpr (REFRESH && can_count(EXTRA)) {
@@ -425,151 +388,6 @@ __global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec(const SpanArg
         span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial, &stats_shared);
     } else {
         span_run<M, BF16, REFRESH, SCALED, EXTRA>(a, c, first, lane, wave, partial);
-    }
-}
-
-// Work queue: a fixed set of resident workgroups draws runs of consecutive shares, in order, from
-// a ticket counter in device memory (zero at launch).  Whatever the relative speed of the compute
-// units and of the 8 XCDs, the shares in flight are always the most recently drawn ones, so every
-// array is walked front to back through one narrow, steadily advancing window, which is what HBM
-// serves fastest, and no wavefront is launched after the first.  One counter serves about 60
-// million tickets a second, so a ticket stands for 2^log2_run shares.  The loop is
-// software-pipelined: while a workgroup works on one share, the first chunk of its next share is
-// already on its way and the ticket after the current one has been asked for.  Every workgroup
-// leaves when its next share lies past the end; nobody waits for anybody.
-struct QueueArgs {
-    unsigned long long *ticket_counter;
-    uint32_t tasks;                  // shares in this launch (all matrices)
-    uint32_t blocks_per_matrix;
-    FastDivU32 div_blocks_per_matrix;
-    int log2_run;                    // shares per ticket = 1 << log2_run
-};
-
-// One chunk of 256 entries of the plain flavour (no compute copy, no statistics, AdamS rule family):
-// what span_run does per iteration, for the work queue, which runs its own pipeline.
-template <int M, bool BF16, bool REFRESH, bool SCALED>
-__device__ __forceinline__ void chunk_step(const SpanArgs &a, const SpanCtx &c, const Chunk<BF16> &cur, int lane, int off,
-                                           bool want_gA, float &acc)
-{
-    const SpanBuffers &b = c.b;
-    float w[4], g[4], mu[4], v[4];
-    unpack4(cur.w, w);
-    unpack4(cur.m, mu);
-    unpack4(cur.v, v);
-    if constexpr (BF16) {
-        g[0] = bf16_lo(cur.g.x); g[1] = bf16_hi(cur.g.x); g[2] = bf16_lo(cur.g.y); g[3] = bf16_hi(cur.g.y);
-    } else {
-        unpack4(cur.g, g);
-    }
-    uint32_t nib;
-    if constexpr (REFRESH) {
-        nib = keep_nibble<M>(w, a.s.n_keep, lane);
-        const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
-        if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, b.mask, (off >> 5) * 4, 0, kAuxStore);
-    } else {
-        nib = (cur.word >> (off & 31)) & 0xFu;
-    }
-    if constexpr (SCALED) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (want_gA) acc = __builtin_fmaf(g[j], w[j], acc);
-            g[j] = c.A * g[j];
-        }
-    }
-    adams_entries4<0, false>(w, g, mu, v, nib, off < c.len, a.s);
-    __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
-    __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
-    __builtin_amdgcn_raw_buffer_store_b128(pack4(v), b.v, off * 4, 0, kAuxStore);
-}
-
-// Every wavefront has one chunk of a share (the host sends only such plans here): while it works on
-// it, its chunk of the next share is on its way.  One barrier per share publishes the ticket and
-// hands the wavefronts' dL/dA sums of the share before to the wavefront that adds them up (two sets
-// of LDS slots, used in turn).  SPLIT: as in adams_step_vec.
-template <int M, bool BF16, bool REFRESH, bool SCALED, bool SPLIT = false>
-__global__ __launch_bounds__(kMaxBlockThreads) void adams_step_vec_queue(const SpanArgs a, const QueueArgs q)
-{
-    __shared__ float partial[2][kMaxBlockWaves];
-    __shared__ unsigned long long drawn[2];
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const uint32_t run_mask = (1u << q.log2_run) - 1u;
-    const int P = a.geom.waves_per_span;
-    unsigned long long pending = 0;
-
-    if (threadIdx.x == 0) drawn[0] = atomicAdd(q.ticket_counter, 1ull);
-    __syncthreads();
-    const unsigned long long first_ticket = uniform_u64(drawn[0]);
-    if ((first_ticket << q.log2_run) >= q.tasks) return;
-    uint32_t share = (uint32_t)first_ticket << q.log2_run;      // wave-uniform
-    Chunk<BF16> cur;
-    {
-        const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
-        SpanCtx c;
-        span_open<BF16, SCALED, true, SPLIT>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
-        chunk_load<BF16, !REFRESH>(cur, c.b, first_offset(c, lane));
-    }
-    if (threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
-    float *sum_to = nullptr;      // where this wavefront puts the dL/dA of the share before, if it is the one to add it up
-
-    uint32_t seq = 0;             // shares this workgroup has finished
-    for (;; ++seq) {
-        const bool last_of_run = (seq & run_mask) == run_mask;          // wave-uniform
-        const int slot = ((seq >> q.log2_run) + 1) & 1;
-        if (last_of_run && threadIdx.x == 0) drawn[slot] = pending;
-        __syncthreads();
-        if constexpr (SCALED) {
-            if (sum_to != nullptr && lane == 0) {
-                const float *from = partial[(seq + 1) & 1] + wave;
-                float sum = from[0];
-                for (int p = 1; p < P; ++p) sum = sum + from[p];
-                *sum_to = sum;
-            }
-        }
-        unsigned long long next = (unsigned long long)share + 1;
-        if (last_of_run) next = uniform_u64(drawn[slot]) << q.log2_run;
-        const bool has_next = next < q.tasks;
-        const uint32_t next_share = __builtin_amdgcn_readfirstlane((uint32_t)next);
-        if (has_next && last_of_run && threadIdx.x == 0) pending = atomicAdd(q.ticket_counter, 1ull);
-        // Scalar registers hold one span context at a time: the next share's is built only to request
-        // its first chunk, and the current share's after that.
-        Chunk<BF16> nxt;
-        if (has_next) {
-            const uint32_t matrix = fast_div(next_share, q.div_blocks_per_matrix);
-            SpanCtx ahead;
-            span_open<BF16, SCALED, true, SPLIT>(a, matrix, (int64_t)(next_share - matrix * q.blocks_per_matrix), wave, ahead);
-            chunk_load<BF16, !REFRESH>(nxt, ahead.b, first_offset(ahead, lane));
-        }
-        const uint32_t matrix = fast_div(share, q.div_blocks_per_matrix);
-        SpanCtx c;
-        span_open<BF16, SCALED, true, SPLIT>(a, matrix, (int64_t)(share - matrix * q.blocks_per_matrix), wave, c);
-        const bool want_gA = SCALED && c.scale_grad != nullptr;
-        float acc = 0.0f;
-        chunk_step<M, BF16, REFRESH, SCALED>(a, c, cur, lane, first_offset(c, lane), want_gA, acc);
-        if constexpr (SCALED) {
-            sum_to = nullptr;
-            if (want_gA) {
-                const float wave_total = wave_sum_fixed_order(acc);
-                if (P == 1) {
-                    if (lane == 0 && c.len > 0) c.scale_grad[c.span] = wave_total;
-                } else {
-                    if (lane == 0) partial[seq & 1][wave] = wave_total;
-                    if (c.sub == 0 && c.len > 0) sum_to = c.scale_grad + c.span;
-                }
-            }
-        }
-        if (!has_next) break;
-        share = next_share;
-        cur = nxt;
-    }
-    if constexpr (SCALED) {
-        __syncthreads();
-        if (sum_to != nullptr && lane == 0) {      // the last share's sums
-            const float *from = partial[seq & 1] + wave;
-            float sum = from[0];
-            for (int p = 1; p < P; ++p) sum = sum + from[p];
-            *sum_to = sum;
-        }
     }
 }
 
@@ -789,14 +607,13 @@ __global__ __launch_bounds__(kBlockThreads) void refresh_stats_unit(const float 
     flips_init = wave_sum_u32(flips_init);
     l1_kept = wave_sum_fixed_order(l1_kept);
     l1_all = wave_sum_fixed_order(l1_all);
-    __shared__ uint32_t sh_init[kBlockWaves];
-    if (lane == 0) { sh.flips[wave] = flips_prev; sh_init[wave] = flips_init; sh.l1_kept[wave] = l1_kept; sh.l1_all[wave] = l1_all; }
+    if (lane == 0) { sh.flips_prev[wave] = flips_prev; sh.flips_init[wave] = flips_init; sh.l1_kept[wave] = l1_kept; sh.l1_all[wave] = l1_all; }
     __syncthreads();
     if (threadIdx.x == 0) {
         StatsPartial out{flips_prev, flips_init, l1_kept, l1_all};
         for (int k = 1; k < kBlockWaves; ++k) {
-            out.flips_prev += sh.flips[k];
-            out.flips_init += sh_init[k];
+            out.flips_prev += sh.flips_prev[k];
+            out.flips_init += sh.flips_init[k];
             out.l1_kept = out.l1_kept + sh.l1_kept[k];
             out.l1_all = out.l1_all + sh.l1_all[k];
         }

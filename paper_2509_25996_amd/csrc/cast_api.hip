@@ -2,6 +2,8 @@
 // Nothing here touches the device except the kernel launches themselves.
 #include <math.h>
 
+#include <vector>
+
 #include "cast_internal.h"
 
 using namespace cast;
@@ -105,7 +107,7 @@ static cast_status validate_step(const float *w, const void *grad, const float *
     if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
     if (!dtype_ok(cfg->grad_dtype)) return CAST_ERR_DTYPE;
     if (cfg->scale_segments < 0) return CAST_ERR_SHAPE;
-    if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_WORK_QUEUE | CAST_FLAG_MU_BF16 | CAST_FLAG_V_BF16)) return CAST_ERR_CONFIG;
+    if (cfg->flags & ~(CAST_FLAG_V_FROM_GRAD | CAST_FLAG_MU_BF16 | CAST_FLAG_V_BF16)) return CAST_ERR_CONFIG;
     if ((cfg->flags & CAST_FLAG_V_BF16) && !(cfg->flags & CAST_FLAG_MU_BF16)) return CAST_ERR_CONFIG;      // both moments or the first alone
     if (cfg->rule < CAST_RULE_ADAMS || cfg->rule > CAST_RULE_MASKED_FROZEN) return CAST_ERR_CONFIG;
     if ((cfg->flags & CAST_FLAG_MU_BF16) && cfg->rule != CAST_RULE_ADAMS && cfg->rule != CAST_RULE_ADDITIVE) return CAST_ERR_CONFIG;
@@ -164,7 +166,7 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
     if (count < 0) return CAST_ERR_SHAPE;
     if (!cfg) return CAST_ERR_NULL;
     if (count == 0) return CAST_OK;
-    if (!tensors || !workspace) return CAST_ERR_NULL;
+    if (!tensors) return CAST_ERR_NULL;
     if (!aligned(workspace, 16)) return CAST_ERR_ALIGN;
     for (int i = 0; i < count; ++i) {    // all or nothing: nothing is launched if any matrix is rejected
         const cast_tensor &t = tensors[i];
@@ -174,8 +176,11 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
     }
     for (int i = 0; i < count; ++i)
         if (!aligned(tensors[i].initial_mask_bits, 4) || !aligned(tensors[i].refresh_stats, 8)) return CAST_ERR_ALIGN;
-    if (workspace_bytes < multi_workspace_bytes(tensors, count, cfg)) return CAST_ERR_SHAPE;
-    return launch_adams_step_multi(tensors, count, cfg, workspace, static_cast<hipStream_t>(stream));
+    const size_t need = multi_workspace_bytes(tensors, count, cfg);
+    if (need > 0 && !workspace) return CAST_ERR_NULL;
+    if (workspace_bytes < need) return CAST_ERR_SHAPE;
+    std::vector<char> taken((size_t)count);
+    return launch_adams_step_multi(tensors, count, cfg, workspace, taken.data(), static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_adams_multi_launches(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
@@ -190,7 +195,8 @@ cast_status cast_adams_multi_launches(const cast_tensor *tensors, int count, con
         if (rc != CAST_OK) return rc;
     }
     MultiTally tally{0, 0};
-    const cast_status rc = launch_adams_step_multi(tensors, count, cfg, nullptr, nullptr, &tally);
+    std::vector<char> taken((size_t)count);
+    const cast_status rc = launch_adams_step_multi(tensors, count, cfg, nullptr, taken.data(), nullptr, &tally);
     if (step_launches) *step_launches = tally.step_launches;
     if (other_launches) *other_launches = tally.other_launches;
     return rc;

@@ -434,7 +434,7 @@ struct StepScalars {
     int rule;              // CAST_RULE_*; read by the one-entry code (adams_entry); the vector kernels have it as a template argument
 };
 
-// The comparison rules (Eq. 9, Eq. 10, Sec. 5.7) as the kernels see them.  Additive decay needs no
+// The comparison rules (Eq. 9, Eq. 10, Sec. 6.7) as the kernels see them.  Additive decay needs no
 // code of its own: the host passes one_minus_alpha = 1 (1 * mu is mu, exactly).  For Eq. 9 and 10
 // the host also sets v_from_grad, and the kernels treat every entry as kept inside the moments.
 constexpr int kRuleAdamwL1 = 1, kRuleAdamL1 = 2, kRuleMaskedFrozen = 4;
@@ -489,7 +489,7 @@ __device__ __forceinline__ float adams_update(float w, float mu_hat, float v_hat
 __device__ __forceinline__ void adams_entry(float &w, float g, float &mu, float &v, bool keep,
                                             const StepScalars &s)
 {
-    if (s.rule == kRuleMaskedFrozen && !keep) return;             // Sec. 5.7: not updated at all
+    if (s.rule == kRuleMaskedFrozen && !keep) return;             // Sec. 6.7: not updated at all
     const bool no_momentum_decay = s.rule == kRuleAdamwL1 || s.rule == kRuleAdamL1;
     const float d = decay_term(w, s);
     if (s.rule == kRuleAdamL1 && !keep) g = g + d;                // Eq. 10: decay inside the gradient
@@ -558,7 +558,7 @@ __device__ __forceinline__ void adams_entries4(float (&w)[4], float (&g)[4], flo
         l1_in_grad = RULE == kRuleAdamL1;                                            // Eq. 10
         keep_all_in_moments = RULE == kRuleAdamwL1 || RULE == kRuleAdamL1;           // no decay on the momentum
         l1_beside_step = RULE == kRuleAdamwL1;                                       // Eq. 9
-        frozen = RULE == kRuleMaskedFrozen;                                          // Sec. 5.7
+        frozen = RULE == kRuleMaskedFrozen;                                          // Sec. 6.7
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -80,8 +80,9 @@ struct MultiTally {
     int other_launches;    // dL/dA reductions of odd shapes, sums of split plans and of refresh statistics
     int split_matrices = 0;
 };
+// taken: `count` bytes of host scratch
 cast_status launch_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
-                                    void *workspace, hipStream_t stream, MultiTally *tally = nullptr);
+                                    void *workspace, char *taken, hipStream_t stream, MultiTally *tally = nullptr);
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
 
 inline cast_status launch_status()

@@ -3,7 +3,7 @@
 This module holds no arithmetic of the method: only tensor shapes and random draws.  It is
 the one module both the GPU tests/benchmark and the CPU oracle's tests may share.
 
-The paper trains OPT / GPT-2 / LLaMA checkpoints on text corpora (Sec. 5, Table 11); neither
+The paper trains OPT / GPT-2 / LLaMA checkpoints on text corpora (Sec. 6.1, Table 11); neither
 the checkpoints nor the corpora are used here.  What is kept is the shape of every linear
 weight of those models ([out_features, in_features], groups of M along in_features, Eq. 3)
 with Gaussian values: weights ~ N(0, std 0.02), gradients ~ N(0, std 1e-3).

@@ -136,22 +136,23 @@ def test_validation_happens_before_any_launch(lib):
     arr = (T * 2)(good, bad)
     cfg = _cfg()
     ws_bytes = lambda a, n, c: lib.cast_adams_multi_workspace_bytes(a, n, C.byref(c))
-    assert ws_bytes(arr, 2, cfg) == 208 and ws_bytes(arr, 0, cfg) == 0 and ws_bytes(None, 2, cfg) == 208    # 2 x 96 + 16
+    assert ws_bytes(arr, 2, cfg) == 0 and ws_bytes(arr, 0, cfg) == 0 and ws_bytes(None, 2, cfg) == 0    # no pieces, no statistics
     # row segments of more than 16 chunks of 256 entries are stepped in pieces of 8 chunks whose dL/dA sums
     # pass through the workspace (one float per piece)
     wide = (T * 2)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, 3, 11008, 11008), good)
     seg = _cfg(scale_segments=2)
-    assert ws_bytes(wide, 2, seg) == 208 + 4 * 20          # 3 rows x 2 segments x 3 pieces, rounded up to 4 floats
-    assert ws_bytes(wide, 2, _cfg(scale_segments=2, flags=2)) == 208 + 4 * 20     # the work queue steps them in pieces too
-    assert ws_bytes(wide, 2, _cfg(scale_segments=8)) == 208
-    assert lib.cast_adams_step_multi(wide, 1, C.byref(seg), p, 176, st) == -2      # no room for the sums
+    assert ws_bytes(wide, 2, seg) == 4 * 20          # 3 rows x 2 segments x 3 pieces, rounded up to 4 floats
+    assert ws_bytes(wide, 2, _cfg(scale_segments=8)) == 0
+    assert lib.cast_adams_step_multi(wide, 1, C.byref(seg), p, 76, st) == -2      # no room for the sums
+    assert lib.cast_adams_step_multi(wide, 1, C.byref(seg), nul, 80, st) == -1     # a workspace is needed and missing
+    assert lib.cast_adams_step_multi(wide, 1, C.byref(_cfg(scale_segments=2, flags=2)), p, 80, st) == -5      # flag value 2 is not in use
     # refresh statistics: one 16-byte slot per workgroup of the matrix's launch (4 x 64 entries: one workgroup)
     with_stats = (T * 1)(T(0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None, None, 4, 64, 64, None, None, None, 0x10000))
-    assert ws_bytes(with_stats, 1, cfg) == 96 + 16 + 16
+    assert ws_bytes(with_stats, 1, cfg) == 16
     assert lib.cast_adams_step_multi(with_stats, 1, C.byref(_cfg(flags=8, refresh_mask=1)), p, 4096, st) == -5      # bf16 v without bf16 mu
     assert lib.cast_adams_step_multi(arr, 2, C.byref(cfg), p, 176, st) == -2
-    assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), p, 32, st) == -2       # workspace too small
-    assert lib.cast_adams_step_multi(arr, 1, C.byref(cfg), nul, 112, st) == -1
+    assert lib.cast_adams_step_multi(with_stats, 1, C.byref(_cfg(refresh_mask=1)), p, 8, st) == -2       # workspace too small
+    assert lib.cast_adams_step_multi(with_stats, 1, C.byref(_cfg(refresh_mask=1)), nul, 112, st) == -1
     assert lib.cast_adams_step_multi(arr, 1, None, p, 112, st) == -1
     assert lib.cast_adams_step_multi(arr, 0, C.byref(cfg), nul, 0, st) == 0
     assert lib.cast_adams_step_multi(arr, -1, C.byref(cfg), p, 64, st) == -2
@@ -171,9 +172,6 @@ def test_list_call_launch_tally(lib):
     step, other = C.c_int32(-1), C.c_int32(-1)
     assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
     assert (step.value, other.value) == (4, 1)
-    cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16, flags=B.FLAG_WORK_QUEUE).c_struct()
-    assert lib.cast_adams_multi_launches(arr, 7, C.byref(cfg), C.byref(step), C.byref(other)) == 0
-    assert (step.value, other.value) == (3, 1)          # one queue launch per shape, and the sum of down's pieces
     # compute copies, and refresh statistics on a refresh step: q, k, v, o still share a launch
     emit = (T * 7)(*[T(a, a, a, a, a, a, a, r, c, 3 * c, a, a) for r, c in layer])
     cfg = B.AdamsConfig(scale_segments=2, grad_dtype=B.CAST_BF16).c_struct()

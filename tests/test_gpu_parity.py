@@ -403,11 +403,10 @@ def test_strided_weights_in_every_entry_point(rows, cols):
 
 
 # --------------------------------------------------------------------------- list of matrices in one call
-@pytest.mark.parametrize("queue", [False, True])
 @pytest.mark.parametrize("nseg", [0, 2])
-def test_multi_tensor_step_equals_single_steps(nseg, queue):
+def test_multi_tensor_step_equals_single_steps(nseg):
     # (16, 11008) and (7, 8768) have row segments of more than 16 chunks of 256 entries: the list call steps
-    # them in pieces of at most 2048 entries (with or without the work queue) and adds the pieces' dL/dA sums afterwards
+    # them in pieces of at most 2048 entries and adds the pieces' dL/dA sums afterwards
     # runs of equal shapes: the list call steps up to 16 small matrices of one shape with one launch
     shapes = [(64, 512), (32, 1024), (64, 512), (5, 72), (5, 72), (64, 512), (32, 1024), (32, 1024), (3, 40), (0, 64),
               (16, 11008), (16, 11008), (7, 8768), (64, 512), (64, 512), (64, 512), (64, 512), (64, 512), (0, 64), (64, 512)]
@@ -434,7 +433,6 @@ def test_multi_tensor_step_equals_single_steps(nseg, queue):
             cfg = B.iteration_config(t, 4, mask_period=2, lr=1e-3, lambda_=1e-3, scale_segments=nseg)
             for x in a:
                 B.cast_adams_step(x["w"], x["grad"], x["m"], x["v"], x["mask"], cfg, scale=x["scale"], scale_grad=x["scale_grad"])
-            cfg.flags |= B.FLAG_WORK_QUEUE if queue else 0
             B.cast_adams_step_multi(tl, cfg)
         torch.cuda.synchronize()
         for x, y in zip(a, b):
@@ -464,7 +462,7 @@ def test_list_call_long_segments_scale_grad_against_oracle():
     for _ in range(2):
         st = GpuState(w0, nseg, interleaved=True)
         tl = B.TensorList([dict(w=st.w, m=st.m, v=st.v, mask=st.mask, grad=g.to(DEV), scale=dev(A), scale_grad=st.scale_grad)], DEV)
-        assert tl.workspace.numel() >= 96 + 16 + 4 * r * nseg * 3
+        assert tl.workspace.numel() >= 4 * r * nseg * 3
         B.cast_adams_step_multi(tl, cfg)
         torch.cuda.synchronize()
         assert_same_bits(host(st.w), ref.w, "w")
@@ -527,8 +525,6 @@ def test_comparison_rules_special_values_and_list_call():
             grad = draw(0.2)
             grad_dev.copy_(dev(grad))
             cfg = B.iteration_config(t, 3, mask_period=1, lr=1e-2, lambda_=1e-3, rule=rule)
-            if t == 1:
-                cfg.flags |= B.FLAG_WORK_QUEUE      # the queue does not know the rules: the call must not use it
             B.cast_adams_step_multi(tl, cfg)
             o.step(grad, oracle_cfg(cfg))
         torch.cuda.synchronize()

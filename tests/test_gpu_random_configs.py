@@ -1,6 +1,6 @@
 """Random valid configurations through the list call against the oracle: pattern, shape (odd ones, vector ones,
 benchmark widths), number of scaling segments, layout, gradient dtype, update rule, bf16 first moment, compute copy,
-refresh statistics, work queue, runs of equal shapes (shared launches), refresh period.  State, masks and compute
+refresh statistics, runs of equal shapes (shared launches), refresh period.  State, masks and compute
 copies bit for bit.  The draws are seeded: a failure names its case."""
 import random
 
@@ -45,12 +45,12 @@ def test_random_configurations_match_the_oracle(seed):
         bf16 = rnd.random() < 0.6
         emit = rnd.random() < 0.3
         stats = rnd.random() < 0.3
-        queue = rnd.random() < 0.2
+        rnd.random()      # (a draw that once chose a launch form; kept so that the seeds give the same cases)
         steps = rnd.randint(2, 4)
         period = rnd.choice([1, 2, 3])
         copies = rnd.randint(1, 3)          # equal shapes in the list: shared launches
         v16 = mu16 and rnd.random() < 0.5   # both moments in bf16, the second one rounded stochastically
-        note = (f"case {case}: {n}:{m} {rows}x{cols} nseg={nseg} mu16={mu16} inter={interleaved} v16={v16} rule={rule} bf16={bf16} emit={emit} stats={stats} queue={queue} steps={steps} x{copies}")
+        note = (f"case {case}: {n}:{m} {rows}x{cols} nseg={nseg} mu16={mu16} inter={interleaved} v16={v16} rule={rule} bf16={bf16} emit={emit} stats={stats} steps={steps} x{copies}")
         items, refs = [], []
         for k in range(copies):
             w0 = synth.tie_outlier_weights(seed, case * 8 + k, rows, cols) if cols % 8 == 0 else synth.weights(seed, case * 8 + k, rows, cols)
@@ -66,8 +66,7 @@ def test_random_configurations_match_the_oracle(seed):
             items.append(item)
             refs.append((OracleState(w0, "f32"), A))
         for t in range(steps):
-            cfg = B.iteration_config(t, steps + 1, mask_period=period, lr=1e-3, lambda_=1e-3, n_keep=n, m_group=m, scale_segments=nseg, rule=rule,
-                                     flags=B.FLAG_WORK_QUEUE if queue else 0)
+            cfg = B.iteration_config(t, steps + 1, mask_period=period, lr=1e-3, lambda_=1e-3, n_keep=n, m_group=m, scale_segments=nseg, rule=rule)
             grads = []
             for k, item in enumerate(items):
                 gr = synth.grads_f32(seed, case * 8 + k, t, rows, cols)

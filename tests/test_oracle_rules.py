@@ -1,6 +1,6 @@
 """Pins for the oracle's comparison update rules: Eq. 9 (decay after the adaptive step), Eq. 10
 (decay inside the gradient), additive decay on the momentum (Sec. 4.1.2) and sparsity-aware
-fine-tuning (Sec. 5.7).  Each is checked against a library Adam, a closed form, or an invariant."""
+fine-tuning (Sec. 6.7).  Each is checked against a library Adam, a closed form, or an invariant."""
 import numpy as np
 import pytest
 import torch
