@@ -50,7 +50,8 @@ enum {
     CAST_ERR_ALIGN = -3,  /* a buffer is not aligned as required                          */
     CAST_ERR_DTYPE = -4,  /* unknown dtype code                                           */
     CAST_ERR_CONFIG = -5, /* a scalar of cast_adams_config is out of range (e.g. bias_corr <= 0) */
-    CAST_ERR_LAUNCH = -6  /* the HIP runtime refused the launch (hipGetLastError != success) */
+    CAST_ERR_LAUNCH = -6, /* the HIP runtime refused the launch (hipGetLastError != success) */
+    CAST_ERR_SCRATCH = -7 /* cast_adams_step_multi_noalloc only: the list exceeds its fixed limits  */
 };
 
 enum { CAST_F32 = 0, CAST_BF16 = 1 };
@@ -238,6 +239,29 @@ size_t cast_adams_multi_workspace_bytes(const cast_tensor *tensors /* HOST */, i
 
 cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                   void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * cast_adams_step_multi for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, serving loops and harnesses that forbid allocation.  Same arguments, same
+ * validation, same kernels and therefore the same results bit for bit (dL/dA included); the workspace
+ * is a buffer of CAST_NOALLOC_SCRATCH_BYTES bytes built into the library, one per GPU, held from the
+ * moment the library's code is loaded on that GPU until the process ends.  The call allocates nothing
+ * on the host or the device and frees nothing; it enqueues kernel launches only.
+ *   - A list that needs more (cast_adams_multi_workspace_bytes(tensors, count, cfg) >
+ *     CAST_NOALLOC_SCRATCH_BYTES) or has more than CAST_NOALLOC_MAX_TENSORS matrices is rejected with
+ *     CAST_ERR_SCRATCH and nothing is launched.  (The LLaMA2-7B-shaped set with n = 2 needs 3 MiB,
+ *     the 13B-shaped one 44 MiB; refresh statistics add 16 bytes per workgroup.)
+ *   - All calls on one GPU share that GPU's buffer.  Every byte a call reads from it was written by
+ *     the same call before, so nothing needs clearing between calls; but two calls whose kernels can
+ *     overlap (different streams, or graphs replayed concurrently) race on it: keep all calls of this
+ *     entry point on one GPU in one stream order.
+ *   - The first call on a GPU looks the buffer's address up (hipGetSymbolAddress); make that call
+ *     outside of stream capture.
+ */
+#define CAST_NOALLOC_SCRATCH_BYTES (64u << 20)
+#define CAST_NOALLOC_MAX_TENSORS 4096
+cast_status cast_adams_step_multi_noalloc(const cast_tensor *tensors /* HOST */, int count,
+                                          const cast_adams_config *cfg /* HOST */, void *stream);
 
 /* How many kernel launches cast_adams_step_multi makes for this list (HOST only, nothing is
  * enqueued; assumes a workspace of the size cast_adams_multi_workspace_bytes returns):

@@ -22,7 +22,7 @@ RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = ran
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
            "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi",
-           "cast_adams_step_emit", "cast_adams_multi_launches", "cast_debug_plan"]
+           "cast_adams_step_emit", "cast_adams_multi_launches", "cast_debug_plan", "cast_adams_step_multi_noalloc"]
 
 
 class CastError(RuntimeError):
@@ -101,6 +101,7 @@ def load():
     L.cast_adams_multi_workspace_bytes.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config)]
     L.cast_adams_multi_workspace_bytes.restype = C.c_size_t
     L.cast_adams_step_multi.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp, C.c_size_t, vp]
+    L.cast_adams_step_multi_noalloc.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp]
     L.cast_debug_plan.argtypes = [i64, i64, i64, ci, ci, i64, ci, C.POINTER(i64), C.POINTER(i64)]
     L.cast_adams_multi_launches.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     for name in EXPORTS:
@@ -303,6 +304,16 @@ def cast_adams_step_multi(tensors: TensorList, cfg: AdamsConfig, stream=None):
     cs = cfg.c_struct()
     _check(load().cast_adams_step_multi(tensors.array, tensors.count, C.byref(cs), _ptr(tensors.workspace),
                                         tensors.workspace.numel(), _stream(stream)), "cast_adams_step_multi")
+
+
+def cast_adams_step_multi_noalloc(tensors: TensorList, cfg: AdamsConfig, stream=None):
+    """cast_adams_step_multi on the library's built-in workspace (the list's own workspace is not used)."""
+    if tensors.count:
+        cfg.grad_dtype = tensors.grad_dtype
+        _mu_flag(cfg, tensors.items[0]["m"], tensors.items[0]["v"])
+    cs = cfg.c_struct()
+    _check(load().cast_adams_step_multi_noalloc(tensors.array, tensors.count, C.byref(cs), _stream(stream)),
+           "cast_adams_step_multi_noalloc")
 
 
 def cast_adams_multi_launches(tensors: TensorList, cfg: AdamsConfig):

@@ -3,6 +3,8 @@
 // adams_step_kernels.h.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "adams_step_kernels.h"
 
 #pragma clang fp contract(off)
@@ -549,6 +551,37 @@ cast_status launch_adams_step_multi(const cast_tensor *ts, int count, const cast
     }
     if (jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
     return stats_jobs.flush(st);
+}
+
+}  // namespace cast
+
+// Built-in workspace of cast_adams_step_multi_noalloc: device memory the library itself holds, one
+// copy per GPU from the moment the code object is loaded there until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; the device address it yields (a different
+// one on every GPU) is what launches receive.  (No `used` attribute here: with it the compiler keeps
+// the device symbol local and at default alignment, and the runtime cannot find it by name.)
+static __device__ __align__(256) unsigned char scratch[CAST_NOALLOC_SCRATCH_BYTES];
+
+namespace cast {
+
+cast_status builtin_workspace(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void *address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CAST_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(guard);
+    if (address[dev] == nullptr) {      // first call with this device current
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+            (void)hipGetLastError();
+            return CAST_ERR_LAUNCH;
+        }
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return CAST_OK;
 }
 
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n)

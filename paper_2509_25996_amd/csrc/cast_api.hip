@@ -59,6 +59,7 @@ const char *cast_status_str(cast_status s)
     case CAST_ERR_DTYPE: return "unknown dtype code";
     case CAST_ERR_CONFIG: return "a configuration scalar is out of range";
     case CAST_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+    case CAST_ERR_SCRATCH: return "the list needs more workspace, or has more matrices, than the entry point that allocates nothing holds";
     default: return "unknown status";
     }
 }
@@ -181,6 +182,29 @@ cast_status cast_adams_step_multi(const cast_tensor *tensors, int count, const c
     if (workspace_bytes < need) return CAST_ERR_SHAPE;
     std::vector<char> taken((size_t)count);
     return launch_adams_step_multi(tensors, count, cfg, workspace, taken.data(), static_cast<hipStream_t>(stream));
+}
+
+cast_status cast_adams_step_multi_noalloc(const cast_tensor *tensors, int count, const cast_adams_config *cfg, void *stream)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (!cfg) return CAST_ERR_NULL;
+    if (count == 0) return CAST_OK;
+    if (!tensors) return CAST_ERR_NULL;
+    if (count > CAST_NOALLOC_MAX_TENSORS) return CAST_ERR_SCRATCH;
+    for (int i = 0; i < count; ++i) {
+        const cast_tensor &t = tensors[i];
+        const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, cfg,
+                                             t.compute_copy, t.copy_scale);
+        if (rc != CAST_OK) return rc;
+    }
+    for (int i = 0; i < count; ++i)
+        if (!aligned(tensors[i].initial_mask_bits, 4) || !aligned(tensors[i].refresh_stats, 8)) return CAST_ERR_ALIGN;
+    if (multi_workspace_bytes(tensors, count, cfg) > (size_t)CAST_NOALLOC_SCRATCH_BYTES) return CAST_ERR_SCRATCH;
+    void *workspace = nullptr;
+    const cast_status rc = builtin_workspace(&workspace);
+    if (rc != CAST_OK) return rc;
+    char taken[CAST_NOALLOC_MAX_TENSORS];      // host scratch on the stack: nothing is allocated anywhere
+    return launch_adams_step_multi(tensors, count, cfg, workspace, taken, static_cast<hipStream_t>(stream));
 }
 
 cast_status cast_adams_multi_launches(const cast_tensor *tensors, int count, const cast_adams_config *cfg,

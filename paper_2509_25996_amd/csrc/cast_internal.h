@@ -83,6 +83,8 @@ struct MultiTally {
 // taken: `count` bytes of host scratch
 cast_status launch_adams_step_multi(const cast_tensor *tensors, int count, const cast_adams_config *cfg,
                                     void *workspace, char *taken, hipStream_t stream, MultiTally *tally = nullptr);
+// Device address, on the current GPU, of the library's built-in workspace of CAST_NOALLOC_SCRATCH_BYTES bytes.
+cast_status builtin_workspace(void **out);
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n);
 
 inline cast_status launch_status()

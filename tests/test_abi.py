@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     assert B.status_str(0) == "ok"
-    for s in range(-6, 0):
+    for s in range(-7, 0):
         assert B.status_str(s) not in ("ok", "unknown status")
     assert B.status_str(-99) == "unknown status"
 
@@ -159,6 +159,38 @@ def test_validation_happens_before_any_launch(lib):
     assert lib.cast_hbm_copy_probe(p, p, 24, st) == -2
     assert lib.cast_hbm_copy_probe(p, odd, 32, st) == -3
     assert lib.cast_hbm_copy_probe(nul, nul, 0, st) == 0
+
+
+def test_noalloc_list_call_rejects_what_does_not_fit(lib):
+    # the entry point that allocates nothing has a fixed workspace (64 MiB) and a fixed list length; anything
+    # beyond is refused on the host before a device is touched
+    T = B._Tensor
+    a = 0x100000
+    st = C.c_void_p(0)
+    call = lib.cast_adams_step_multi_noalloc
+    ws_bytes = lambda arr, n, c: lib.cast_adams_multi_workspace_bytes(arr, n, C.byref(c))
+    refresh = _cfg(refresh_mask=1)
+    # refresh statistics of a 2^22 x 4096 matrix: one 16-byte slot per workgroup of 2048 entries = 128 MiB
+    huge = (T * 1)(T(a, a, a, a, a, None, None, 1 << 22, 4096, 4096, None, None, None, a))
+    assert ws_bytes(huge, 1, refresh) == (1 << 22) * 4096 // 2048 * 16 > (64 << 20)
+    assert call(huge, 1, C.byref(refresh), st) == -7
+    # 16 M row segments in pieces: five floats each
+    many = (T * 1)(T(a, a, a, a, a, a, a, 1 << 23, 5120, 5120))
+    seg = _cfg(scale_segments=2)
+    assert ws_bytes(many, 1, seg) == (1 << 24) * 5 * 4 > (64 << 20)
+    assert call(many, 1, C.byref(seg), st) == -7
+    # more matrices than the fixed list length
+    long_list = (T * 4097)(*[T(a, a, a, a, a, None, None, 4, 64, 64)] * 4097)
+    assert call(long_list, 4097, C.byref(_cfg()), st) == -7
+    # the ordinary rejections come first and are those of the list call
+    bad = (T * 2)(T(a, a, a, a, a, None, None, 4, 64, 64), T(a, a, a, a, a, None, None, 4, 66, 66))
+    assert call(bad, 2, C.byref(_cfg()), st) == -2
+    assert call(bad, 1, None, st) == -1
+    assert call(None, 1, C.byref(_cfg()), st) == -1
+    assert call(bad, 0, C.byref(_cfg()), st) == 0
+    assert call(bad, -1, C.byref(_cfg()), st) == -2
+    assert call(bad, 1, C.byref(_cfg(flags=2)), st) == -5
+    assert B.status_str(-7) not in ("ok", "unknown status")
 
 
 def test_list_call_launch_tally(lib):
