@@ -100,6 +100,70 @@ class Model:
         return cfg.refresh_mask
 
 
+def time_set(torch, B, model, scaled, steps, warmup, t0=1):
+    """ms per step of `steps` consecutive iterations starting at t0 (after `warmup` untimed ones), as the list call
+    makes them, with the kinds of step they were."""
+    t = t0
+    for _ in range(warmup):
+        model.step(B, t, scaled)
+        t += 1
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    kinds = []
+    torch.cuda.synchronize()
+    marks[0].record()
+    for k in range(steps):
+        kinds.append(model.step(B, t, scaled))
+        t += 1
+        marks[k + 1].record()
+    torch.cuda.synchronize()
+    per = [marks[k].elapsed_time(marks[k + 1]) for k in range(steps)]
+    return marks[0].elapsed_time(marks[-1]) / steps, per, kinds
+
+
+def set_figures(ms, params, bpp=BYTES_PER_PARAM):
+    gbs = bpp * params / (ms * 1e-3) / 1e9
+    return {"ms_step": round(ms, 4), "Gparams_s": round(params / (ms * 1e-3) / 1e9, 1), "GBs": round(gbs, 1),
+            "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def stream_probe(torch, B, model, reps=10):
+    """ms per call of cast_hbm_stream_probe over the model's list (it overwrites the state): the same launches and
+    the same memory accesses as a non-refresh step with next to no arithmetic."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        B.cast_hbm_stream_probe(model.list, model.segments)
+    e0.record()
+    for _ in range(reps):
+        B.cast_hbm_stream_probe(model.list, model.segments)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def other_set(torch, B, synth, dev, workload, interleaved, steps, warmup):
+    """Another resident set through the same list call: `steps` iterations with the 1-in-10 refresh mix, and the
+    stream probe over the same list."""
+    shapes = synth.weight_set(workload, None)
+    torch.cuda.empty_cache()
+    free_bytes, _ = torch.cuda.mem_get_info()
+    if free_bytes < 14.5 * synth.set_params(shapes) + (1 << 30):
+        return {"skipped": f"{free_bytes >> 30} GiB of device memory free"}
+    model = Model(workload, None, torch, B, synth, dev, interleaved)
+    model.tensor_list(B, True, dev)
+    torch.cuda.synchronize()
+    ms, per, kinds = time_set(torch, B, model, True, steps, warmup, t0=10)      # the first warm-up step refreshes the masks
+    out = set_figures(ms, model.params)
+    plain = [m for m, k in zip(per, kinds) if not k]
+    out["ms_step_non_refresh"] = round(sum(plain) / len(plain), 4)
+    out["matrices"], out["params"], out["steps"] = len(model.shapes), model.params, steps
+    probe_ms = stream_probe(torch, B, model)
+    out["stream_probe_GBs"] = round(BYTES_PER_PARAM * model.params / (probe_ms * 1e-3) / 1e9, 1)
+    out["frac_of_stream_probe"] = round(probe_ms / out["ms_step_non_refresh"], 4)
+    del model
+    torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(synth):
     """The oracle as it stands (plain C, fp32-per-operation variant, OpenMP over rows), host cores only: the
     headline figure is non-refresh AdamS 2:4 steps with scaling n = 2 over the 7 matrices of one
@@ -222,6 +286,7 @@ def main():
     log(f"[bench] {ms_per_step:.3f} ms/step, {value:.1f} Gparams/s; non-refresh {sum(plain) / max(len(plain), 1):.3f} ms, "
         f"refresh {sum(fresh) / max(len(fresh), 1):.3f} ms")
 
+    n_matrices, n_params, nm = len(model.shapes), model.params, model.nm
     # dominant kernel: the non-refresh step kernel (9 of 10 steps), all its launches of a step taken together
     launches = model.launches
     dom_ms = (sum(plain) / len(plain)) if plain else ms_per_step
@@ -371,19 +436,51 @@ def main():
                     x["w"], x["m"], x["v"] = w, m, v
                 del kept
 
+    if not args.no_extra and model.list is not None and scaled:
+        # The step's timing depends on the data in one way: a wavefront whose 256 entries hold a zero, a denormal or a
+        # huge mu~ or v takes the IEEE division and square root instead of the short forms.  Worst case: one entry
+        # of every 256 with w = g = mu = v = 0 (it stays that way), so that every wavefront takes the long forms.
+        model.tensor_list(B, scaled, dev)
+        for x in model.t:
+            for k in ("w", "g", "m", "v"):
+                x[k][:, ::256] = 0
+        ms, _, _ = time_set(torch, B, model, scaled, 9, 2, t0=1)
+        extra["long_forms"] = set_figures(ms, model.params)
+        extra["long_forms"]["what"] = "non-refresh steps with one all-zero entry per 256: every wavefront takes the IEEE forms"
+        # what the memory system gives the step's access pattern (overwrites the state: last use of this model)
+        probe_ms = stream_probe(torch, B, model)
+        extra["stream_probe"] = {"ms_call": round(probe_ms, 4), "GBs": round(BYTES_PER_PARAM * model.params / (probe_ms * 1e-3) / 1e9, 1),
+                                 "what": "the list call's launches, loads, prefetches and stores with three multiply-adds per entry"}
+        extra["stream_probe"]["frac_of_peak"] = round(extra["stream_probe"]["GBs"] / HBM_PEAK_GBS, 4)
+        roofline["frac_of_stream_probe"] = round(probe_ms / dom_ms, 4)
+    if not args.no_extra and args.workload == "llama2_7b" and args.layers is None and scaled and args.launch == "list":
+        del model, big, x
+        model = None
+        torch.cuda.empty_cache()
+        # the same step on the other resident sets of the workload family, and on three dense state arrays
+        for key, workload, interleaved, steps, warm in (("separate_layout", "llama2_7b", False, 10, 3),
+                                                        ("llama2_13b", "llama2_13b", True, 10, 3),
+                                                        ("opt125m", "opt125m", True, 200, 20)):
+            try:
+                extra[key] = other_set(torch, B, synth, dev, workload, interleaved, steps, warm)
+            except Exception as e:      # an extra must not take the headline down with it
+                extra[key] = {"failed": repr(e)[:200]}
+                torch.cuda.empty_cache()
+            log(f"[bench] {key}: {extra[key]}")
+
     out = {"metric": "AdamS N:M step Gparams/s at LLaMA2-7B shape; % of MI355X peak HBM BW",
            "value": round(value, 2), "unit": "Gparams/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32", "data": "synthetic",
-           "config": {"workload": f"{args.workload} linear weight set ({len(model.shapes)} matrices, {model.params} params), "
+           "config": {"workload": f"{args.workload} linear weight set ({n_matrices} matrices, {n_params} params), "
                                   f"{args.nm}, fp32 w/mu/v ({args.layout}) + bf16 grads + mask bits resident, "
                                   f"{'weight scaling n=2, ' if scaled else ''}mask refresh every 10th step, "
                                   f"{ {'list': 'one list call', 'per-matrix': 'one call per matrix'}[args.launch]} per step",
-                      "n_keep": model.nm[0], "m_group": model.nm[1], "scale_segments": SEGMENTS if scaled else 0,
+                      "n_keep": nm[0], "m_group": nm[1], "scale_segments": SEGMENTS if scaled else 0,
                       "pct_of_peak_hbm": round(100 * BYTES_PER_PARAM * value / HBM_PEAK_GBS, 2)},
            "roofline": roofline, "extra": extra}
     if not args.no_cpu_baseline:
-        del model
+        model = None
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(synth)
     print(json.dumps(out), flush=True)

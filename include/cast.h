@@ -336,6 +336,19 @@ cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uin
 cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *stream);
 
 /*
+ * Measurement aid, not part of the method: the launches cast_adams_step_multi would make for this list
+ * of 2:4 matrices with bf16 gradients on a non-refresh iteration (same plans, same shared launches,
+ * same loads, prefetches and stores of w, m, v, grad and mask_bits, same dL/dA sums), with the
+ * arithmetic of the iteration replaced by three multiply-adds per entry.  Its duration is what the
+ * memory system gives this access pattern: the ceiling the real step can be held against.
+ * w, m, v and scale_grad are OVERWRITTEN with meaningless values.  Descriptors as for
+ * cast_adams_step_multi (no compute_copy, no refresh_stats; shapes the fast kernels take only, else
+ * CAST_ERR_SHAPE); workspace as for that call with the same scale_segments.
+ */
+cast_status cast_hbm_stream_probe(const cast_tensor *tensors /* HOST */, int count, int scale_segments,
+                                  void *workspace /* DEVICE */, size_t workspace_bytes, void *stream);
+
+/*
  * Diagnostic, runs on the HOST (both pointers HOST): out[i] = x[i] / y computed by the very
  * routine the kernels use for the two bias-correction divisions of Eq. 8 (a short FMA sequence
  * with a precomputed reciprocal inside a checked range, the IEEE division outside it).  It

@@ -22,7 +22,8 @@ RULE_ADAMS, RULE_ADAMW_L1, RULE_ADAM_L1, RULE_ADDITIVE, RULE_MASKED_FROZEN = ran
 EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step", "cast_weight_scale",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
            "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi",
-           "cast_adams_step_emit", "cast_adams_multi_launches", "cast_debug_plan", "cast_adams_step_multi_noalloc"]
+           "cast_adams_step_emit", "cast_adams_multi_launches", "cast_debug_plan", "cast_adams_step_multi_noalloc",
+           "cast_hbm_stream_probe"]
 
 
 class CastError(RuntimeError):
@@ -102,6 +103,7 @@ def load():
     L.cast_adams_multi_workspace_bytes.restype = C.c_size_t
     L.cast_adams_step_multi.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp, C.c_size_t, vp]
     L.cast_adams_step_multi_noalloc.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp]
+    L.cast_hbm_stream_probe.argtypes = [C.POINTER(_Tensor), ci, ci, vp, C.c_size_t, vp]
     L.cast_debug_plan.argtypes = [i64, i64, i64, ci, ci, i64, ci, C.POINTER(i64), C.POINTER(i64)]
     L.cast_adams_multi_launches.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     for name in EXPORTS:
@@ -363,6 +365,13 @@ def cast_hbm_copy_probe(dst, src, stream=None):
     _dev(dst, src)
     _check(load().cast_hbm_copy_probe(_ptr(dst), _ptr(src), src.numel() * src.element_size(), _stream(stream)),
            "cast_hbm_copy_probe")
+
+
+def cast_hbm_stream_probe(tensors: TensorList, scale_segments: int, stream=None):
+    """The list call's launches with next to no arithmetic (bandwidth ceiling of its access pattern).
+    Overwrites w, m, v and scale_grad of every matrix of the list."""
+    _check(load().cast_hbm_stream_probe(tensors.array, tensors.count, scale_segments, _ptr(tensors.workspace),
+                                        tensors.workspace.numel(), _stream(stream)), "cast_hbm_stream_probe")
 
 
 def cast_debug_div_by_uniform(x, y: float):

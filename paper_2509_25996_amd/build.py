@@ -7,6 +7,7 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
@@ -15,14 +16,13 @@ SOURCES = ["cast_api.hip", "adams_step.hip", "select_pack.hip"]
 
 # -ffp-contract=off and the correctly rounded divide/sqrt keep every fp32 operation of the
 # update a single IEEE-754 rounding; packed fp32 instructions are switched off.
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
          "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-gpu-flush-denormals-to-zero",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wextra", "-Wno-unused-parameter"]
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
-    cmd = ["hipcc", *FLAGS, *extra, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)
@@ -33,6 +33,18 @@ def build_library(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build_library(verbose: bool = False, extra=()) -> str:
+    """Compiles the three translation units side by side (objects under _build/, which is not tracked),
+    then links libcast.so."""
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
+    with ThreadPoolExecutor(len(SOURCES)) as pool:
+        list(pool.map(lambda so: _run(["hipcc", *FLAGS, *extra, "-c", "-o", so[1], os.path.join(CSRC, so[0])], verbose),
+                      zip(SOURCES, objs)))
+    _run(["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB, *objs], verbose)
     return LIB
 
 

@@ -56,12 +56,15 @@ struct SpanArgs {
 // statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0); 5 the
 // first moment in bf16, with the abilities of 1; 6 both moments in bf16, the second one rounded stochastically
 // (CAST_FLAG_V_BF16); 7 the same with the abilities of 1.  The rules combine with 0 and 1.
+// 8 is not the method: the walk, the loads, the prefetch and the stores of flavour 0 around a few multiply-adds
+// instead of Algorithm 1's arithmetic (cast_hbm_stream_probe: what the memory system gives this access pattern).
 constexpr int kEmitAndCount = 1;
 constexpr int kMuBf16 = 3;
 constexpr int kStatsOnly = 4;
 constexpr int kMuBf16Emit = 5;
 constexpr int kBothBf16 = 6;
 constexpr int kBothBf16Emit = 7;
+constexpr int kStreamProbe = 8;
 constexpr int abilities(int extra) { return extra & 15; }
 constexpr int rule_of(int extra) { return extra >> 4; }      // kRuleAdamwL1, kRuleAdamL1, kRuleMaskedFrozen or 0
 constexpr int with_rule(int extra, int rule) { return extra | (rule << 4); }
@@ -285,7 +288,17 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
                 g[j] = A * g[j];                                         // chain rule of Eq. 12
             }
         }
-        adams_entries4<rule_of(EXTRA), can_emit(EXTRA)>(w, g, mu, v, nib, off < len, a.s);
+        if constexpr (abilities(EXTRA) == kStreamProbe) {
+            // bandwidth probe: every loaded value is used and every stream rewritten, with next to no arithmetic
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                mu[j] = 0.5f * mu[j] + g[j];
+                v[j] = 0.5f * v[j] + (((nib >> j) & 1u) ? g[j] : mu[j]);
+                w[j] = 0.5f * w[j] + v[j];
+            }
+        } else {
+            adams_entries4<rule_of(EXTRA), can_emit(EXTRA)>(w, g, mu, v, nib, off < len, a.s);
+        }
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
         if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
             const vu2_t h = {f32x2_to_bf16_rne(mu[0], mu[1]), f32x2_to_bf16_rne(mu[2], mu[3])};

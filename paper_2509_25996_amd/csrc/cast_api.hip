@@ -297,6 +297,39 @@ cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *
     return launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
+cast_status cast_hbm_stream_probe(const cast_tensor *tensors, int count, int scale_segments, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    cast_adams_config cfg{};
+    cfg.n_keep = 2;
+    cfg.m_group = 4;
+    cfg.beta1 = 0.5f;
+    cfg.beta2 = 0.5f;
+    cfg.bias_corr1 = 1.0f;
+    cfg.bias_corr2 = 1.0f;
+    cfg.refresh_mask = 0;
+    cfg.scale_segments = scale_segments;
+    cfg.grad_dtype = CAST_BF16;
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (count == 0) return CAST_OK;
+    if (!tensors) return CAST_ERR_NULL;
+    if (!aligned(workspace, 16)) return CAST_ERR_ALIGN;
+    for (int i = 0; i < count; ++i) {
+        const cast_tensor &t = tensors[i];
+        const cast_status rc = validate_step(t.w, t.grad, t.m, t.v, t.mask_bits, t.scale, t.scale_grad, t.rows, t.cols, t.ld, &cfg);
+        if (rc != CAST_OK) return rc;
+        if (t.compute_copy || t.refresh_stats) return CAST_ERR_CONFIG;
+        // only shapes the vector kernels take: the others would run the real step
+        if (t.rows > 0 && t.cols > 0 && !plan_spans(t.rows, t.cols, t.ld, scale_segments, false).vec) return CAST_ERR_SHAPE;
+    }
+    const size_t need = multi_workspace_bytes(tensors, count, &cfg);
+    if (need > 0 && !workspace) return CAST_ERR_NULL;
+    if (workspace_bytes < need) return CAST_ERR_SHAPE;
+    cfg.flags = kInternalFlagStreamProbe;
+    std::vector<char> taken((size_t)count);
+    return launch_adams_step_multi(tensors, count, &cfg, workspace, taken.data(), static_cast<hipStream_t>(stream));
+}
+
 cast_status cast_debug_plan(int64_t rows, int64_t cols, int64_t ld, int n_segments, int allow_split,
                             int64_t block, int wave, int64_t plan[5], int64_t span[5])
 {

@@ -20,6 +20,10 @@ struct SpanPlan {
     int64_t segments;    // split plans: row segments of the matrix (rows * n), else 0
 };
 
+// Not part of the ABI (cast_adams_config::flags with this bit is refused): set by cast_hbm_stream_probe on its own
+// copy of the configuration to make the list call run the probe flavour of the step kernel.
+constexpr uint32_t kInternalFlagStreamProbe = 0x80000000u;
+
 // allow_split: row segments of more than 16 chunks of 256 entries may be cut into pieces with a
 // workgroup each; the caller then supplies a PieceArea for the pieces' dL/dA sums.
 SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool allow_split = false);

@@ -1,0 +1,130 @@
+"""The configuration bench.py times, checked as a whole: several full LLaMA2-7B-shaped layers in ONE list call
+(row-interleaved fp32 state, bf16 gradients, 2:4, weight scaling with n = 2), so that q/k/v/o share launches
+(gridDim.y = 4) and the split plans of several down projections feed one launch that adds their pieces up;
+every entry of w, mu, v, of the mask and of dL/dA of every matrix against the oracle.  And the 13B-shaped set
+with all 280 matrices resident, sampled whole rows of every matrix."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_25996_amd import binding as B
+from paper_2509_25996_amd import synth
+
+from gpu_util import DEV, assert_same_bits, host, oracle_cfg, words
+
+pytestmark = pytest.mark.gpu
+
+LR, LAMBDA, TOTAL = 2e-5, 4e-7, 7500      # Table 11 (LLaMA)
+
+
+def _items(shapes, seed, n, with_copy, stats=False):
+    items = []
+    for i, (_, r, c) in enumerate(shapes):
+        w, m, v = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, seed + i, DEV))
+        A = (1 + 0.05 * torch.randn((r, n), device=DEV, generator=torch.Generator(DEV).manual_seed(seed + 1000 + i))).contiguous()
+        x = dict(w=w, m=m, v=v, mask=B.alloc_mask(r, c, DEV), grad=torch.zeros((r, c), dtype=torch.bfloat16, device=DEV),
+                 scale=A, scale_grad=torch.zeros((r, n), device=DEV))
+        if with_copy:
+            x.update(compute_copy=torch.zeros((r, c), dtype=torch.bfloat16, device=DEV), copy_scale=A)
+        items.append(x)
+    return items
+
+
+@pytest.mark.parametrize("with_copy", [False, True])
+def test_two_whole_7b_layers_in_one_list_call_every_entry(with_copy):
+    n, layers = 2, 2
+    shapes = synth.weight_set("llama2_7b", layers)
+    items = _items(shapes, 7000, n, with_copy)
+    tl = B.TensorList(items, DEV)
+    with_stats = [dict(x, initial_mask=torch.zeros_like(x["mask"]), refresh_stats=B.alloc_refresh_stats(DEV)) for x in items]
+    tl_stats = B.TensorList(with_stats, DEV)
+    # the launch form that is timed: q, k, v, o of a layer in one launch (8 matrices -> 2 launches), gate and up
+    # one each, the two down projections as split plans whose pieces one further launch adds up
+    probe = B.AdamsConfig(scale_segments=n, refresh_mask=0)
+    assert B.cast_adams_multi_launches(tl, probe) == (2 + 4 + 2, 1)
+    probe.refresh_mask = 1
+    assert B.cast_adams_multi_launches(tl_stats, probe) == (2 + 4 + 2, 2)      # and one that adds the statistics up
+    refs = []
+    for x in items:
+        w0 = host(x["w"]).copy()
+        refs.append(dict(w=w0, m=np.zeros_like(w0), v=np.zeros_like(w0), keep=np.zeros(w0.shape, np.uint8), A=host(x["scale"]).copy()))
+    gen = torch.Generator(device=DEV).manual_seed(99)
+    for t in range(3):      # refresh, non-refresh, refresh that gathers the mask-learning statistics
+        cfg = B.iteration_config(t, TOTAL, mask_period=2, lr=LR, lambda_=LAMBDA, scale_segments=n)
+        cfg.alpha = 0.2 + 0.3 * t      # the decay as it is late in training
+        for x in items:
+            x["grad"].copy_(torch.randn(x["grad"].shape, device=DEV, generator=gen) * 1e-3)
+        prev_keep = [ref["keep"].copy() for ref in refs] if t == 2 else None
+        w_in = [ref["w"].copy() for ref in refs] if t == 2 else None
+        B.cast_adams_step_multi(tl_stats if t == 2 else tl, cfg)
+        for x, ref in zip(items, refs):
+            g = host(x["grad"].float())
+            ref["g"] = g
+            ref["w_in"] = ref["w"].copy()
+            ref["gA"] = oracle.adams_step(ref["w"], g, ref["m"], ref["v"], ref["keep"], oracle_cfg(cfg), A=ref["A"],
+                                          arithmetic="f32", nthreads=16)
+    torch.cuda.synchronize()
+    for (name, r, c), x, xs, ref, pk, wi in zip(shapes, items, with_stats, refs, prev_keep, w_in):
+        assert (words(x["mask"]) == oracle.pack_mask_bits(ref["keep"])).all(), name
+        assert_same_bits(host(x["w"]), ref["w"], name + " w")
+        assert_same_bits(host(x["m"]), ref["m"], name + " mu")
+        assert_same_bits(host(x["v"]), ref["v"], name + " v")
+        terms = np.abs(ref["g"].astype(np.float64) * ref["w_in"]).reshape(r, n, -1).sum(-1)
+        assert (np.abs(host(x["scale_grad"]) - ref["gA"]) <= 1e-5 * terms + 1e-30).all(), name + " dL/dA"
+        if with_copy:
+            want = oracle.bf16_rne(oracle.weight_scale(ref["w"], ref["A"]))
+            assert (host(x["compute_copy"].view(torch.int16)).view(np.uint16) == want).all(), name + " copy"
+        # statistics of the last refresh: flips against the mask of t = 0 and against an all-zero initial mask, norms of
+        # the weights that entered the step
+        got = B.read_refresh_stats(xs["refresh_stats"])
+        flips, kept, total = oracle.mask_stats(wi, ref["keep"], pk)
+        assert got["flips_prev"] == flips and got["flips_init"] == int(ref["keep"].sum()), name
+        assert abs(got["l1_kept"] - kept) <= 1e-6 * kept and abs(got["l1_all"] - total) <= 1e-6 * total, name
+
+
+def test_whole_13b_set_resident_sampled_rows_of_every_matrix():
+    """All 280 matrices of the LLaMA2-13B-shaped set resident (w, mu, v fp32 row-interleaved, bf16 gradients, masks:
+    about 180 GB), three steps of the one list call bench.py makes, and whole sampled rows of EVERY matrix against
+    the oracle (a row is self-contained: groups and scale segments never cross rows)."""
+    torch.cuda.empty_cache()
+    free_bytes, _ = torch.cuda.mem_get_info()
+    shapes = synth.weight_set("llama2_13b")
+    params = synth.set_params(shapes)
+    if free_bytes < 14.6 * params:
+        pytest.skip("not enough free device memory for the resident 13B-shaped set")
+    n, per_matrix = 2, 5
+    items, refs = [], []
+    rng = np.random.default_rng(13)
+    for i, (_, r, c) in enumerate(shapes):
+        w, m, v = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, 13000 + i, DEV))
+        g = synth.device_gaussian((r, c), 1e-3, torch.bfloat16, 513000 + i, DEV)
+        A = (1 + 0.05 * torch.randn((r, n), device=DEV, generator=torch.Generator(DEV).manual_seed(i))).contiguous()
+        items.append(dict(w=w, m=m, v=v, mask=B.alloc_mask(r, c, DEV), grad=g, scale=A, scale_grad=torch.zeros((r, n), device=DEV)))
+        pick = np.unique(np.concatenate([[0, r - 1], rng.integers(0, r, per_matrix)]))
+        idx = torch.from_numpy(pick).to(DEV)
+        ow = host(w[idx]).copy()
+        refs.append(dict(idx=idx, w=ow, g=host(g[idx].float()).copy(), A=host(A[idx]).copy(), m=np.zeros_like(ow), v=np.zeros_like(ow),
+                         keep=np.zeros(ow.shape, np.uint8)))
+    tl = B.TensorList(items, DEV)
+    step_launches, other = B.cast_adams_multi_launches(tl, B.AdamsConfig(scale_segments=n, refresh_mask=0))
+    assert step_launches < len(shapes) and other >= 1      # 5120 x 5120 matrices share launches; pieces are added up
+    for t in range(3):
+        cfg = B.iteration_config(t, TOTAL, mask_period=2, lr=LR, lambda_=LAMBDA, scale_segments=n)
+        cfg.alpha = 0.25 + 0.25 * t
+        B.cast_adams_step_multi(tl, cfg)
+        for ref in refs:
+            ref["w_in"] = ref["w"].copy()
+            ref["gA"] = oracle.adams_step(ref["w"], ref["g"], ref["m"], ref["v"], ref["keep"], oracle_cfg(cfg), A=ref["A"],
+                                          arithmetic="f32", nthreads=4)
+    torch.cuda.synchronize()
+    for (name, r, c), x, ref in zip(shapes, items, refs):
+        idx = ref["idx"]
+        assert (words(x["mask"][idx]) == oracle.pack_mask_bits(ref["keep"])).all(), name
+        assert_same_bits(host(x["w"][idx]), ref["w"], name + " w")
+        assert_same_bits(host(x["m"][idx]), ref["m"], name + " mu")
+        assert_same_bits(host(x["v"][idx]), ref["v"], name + " v")
+        terms = np.abs(ref["g"].astype(np.float64) * ref["w_in"]).reshape(len(idx), n, -1).sum(-1)
+        assert (np.abs(host(x["scale_grad"][idx]) - ref["gA"]) <= 1e-5 * terms + 1e-30).all(), name + " dL/dA"
+    del items, tl
+    torch.cuda.empty_cache()

@@ -3,8 +3,9 @@ benchmark times (2:4, bf16 gradients, weight scaling with n = 2, w/mu/v row-inte
 buffer, the list call, which steps long row segments in pieces) and in the plain one (three dense
 arrays, one cast_adams_step call).
 
-The AdamS step is checked on sampled whole rows (a row is self-contained: groups and scale
-segments never cross rows), gathered before and after the GPU step and recomputed by the oracle.
+The AdamS step is checked on whole matrices for the LLaMA2-7B shapes and on sampled whole rows for the
+others (a row is self-contained: groups and scale segments never cross rows), gathered before and after
+the GPU step and recomputed by the oracle.
 Selection and hard projection + pack of the tie/outlier stress input are compared in full."""
 import numpy as np
 import pytest
@@ -25,7 +26,7 @@ SHAPES_LLAMA3_8B = [(1024, 4096), (4096, 14336)]      # the shapes LLaMA3-8B add
 
 @pytest.mark.parametrize("as_benchmarked", [True, False])
 @pytest.mark.parametrize("rows,cols", SHAPES_7B + SHAPES_13B + SHAPES_LLAMA3_8B)
-def test_step_on_sampled_rows_of_full_size_matrices(rows, cols, as_benchmarked):
+def test_step_on_full_size_matrices(rows, cols, as_benchmarked):
     n, steps, n_sample = 2, 3, 24
     w = synth.device_gaussian((rows, cols), 0.02, torch.float32, 11, DEV)
     g = synth.device_gaussian((rows, cols), 1e-3, torch.bfloat16, 12, DEV)
@@ -38,6 +39,8 @@ def test_step_on_sampled_rows_of_full_size_matrices(rows, cols, as_benchmarked):
     gA = torch.zeros((rows, n), device=DEV)
     rng = np.random.default_rng(rows + cols)
     pick = np.unique(np.concatenate([[0, rows - 1], rng.integers(0, rows, n_sample)]))
+    if (rows, cols) in SHAPES_7B:
+        pick = np.arange(rows)      # the shapes of the headline: every entry
     idx = torch.from_numpy(pick).to(DEV)
     ow, og, oA = host(w[idx]).copy(), host(g[idx].float()).copy(), host(A[idx]).copy()
     om, ov = np.zeros_like(ow), np.zeros_like(ow)
@@ -50,14 +53,15 @@ def test_step_on_sampled_rows_of_full_size_matrices(rows, cols, as_benchmarked):
             B.cast_adams_step_multi(tl, cfg)
         else:
             B.cast_adams_step(w, g, m, v, mask, cfg, scale=A, scale_grad=gA)
-        ref_gA = oracle.adams_step(ow, og, om, ov, keep, oracle_cfg(cfg), A=oA, arithmetic="f32", nthreads=8)
+        w_in = ow.copy()
+        ref_gA = oracle.adams_step(ow, og, om, ov, keep, oracle_cfg(cfg), A=oA, arithmetic="f32", nthreads=16)
     torch.cuda.synchronize()
     assert (words(mask[idx]) == oracle.pack_mask_bits(keep)).all()
     assert_same_bits(host(w[idx]), ow, "w")
     assert_same_bits(host(m[idx]), om, "mu")
     assert_same_bits(host(v[idx]), ov, "v")
-    terms = np.abs(og.astype(np.float64) * host(w[idx])).reshape(len(pick), n, -1).sum(-1)
-    assert (np.abs(host(gA[idx]) - ref_gA) <= 2e-5 * terms + 1e-12).all()
+    terms = np.abs(og.astype(np.float64) * w_in).reshape(len(pick), n, -1).sum(-1)
+    assert (np.abs(host(gA[idx]) - ref_gA) <= 1e-5 * terms + 1e-30).all()
     # properties that hold for the whole matrix: exactly 2 bits per group in every mask word, state finite
     bits = mask.view(torch.uint8)
     lut = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.uint8, device=DEV)
