@@ -108,7 +108,9 @@ def test_whole_13b_set_resident_sampled_rows_of_every_matrix():
                          keep=np.zeros(ow.shape, np.uint8)))
     tl = B.TensorList(items, DEV)
     step_launches, other = B.cast_adams_multi_launches(tl, B.AdamsConfig(scale_segments=n, refresh_mask=0))
-    assert step_launches < len(shapes) and other >= 1      # 5120 x 5120 matrices share launches; pieces are added up
+    # every 13B shape has row segments that are stepped in pieces (2560 and 6912 entries): one launch per matrix,
+    # and the pieces of up to 32 matrices are added up by one launch
+    assert step_launches == len(shapes) and other == -(-len(shapes) // 32)
     for t in range(3):
         cfg = B.iteration_config(t, TOTAL, mask_period=2, lr=LR, lambda_=LAMBDA, scale_segments=n)
         cfg.alpha = 0.25 + 0.25 * t
