@@ -315,20 +315,49 @@ def main():
         torch.cuda.synchronize()
         extra["copy_probe_GBs"] = round(2 * n * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         del a, b
-        # the epilogue of training: hard 2:4 projection + fold + pack of every matrix (once per run)
-        outs = [(torch.empty((r, c // 2), device=dev), torch.empty((r, c // 32), dtype=torch.int32, device=dev))
-                for (_, r, c) in model.shapes[:7]]
-        for rep in range(2):
+        def timed_calls(call, reps=3):
+            call()
             e0.record()
-            for i, x in enumerate(model.t):
-                vals, meta = outs[i % 7]
-                B.cast_nm_project_compress(x["w"], 2, 4, vals, meta, scale=x["A"] if scaled else None)
+            for _ in range(reps):
+                call()
             e1.record()
             torch.cuda.synchronize()
-        pc_ms = e0.elapsed_time(e1)
-        extra["project_compress_ms"] = round(pc_ms, 3)
-        extra["project_compress_GBs"] = round(6.125 * model.params / (pc_ms * 1e-3) / 1e9, 1)
-        del outs
+            return e0.elapsed_time(e1) / reps
+
+        def figures(ms, bpp):
+            gbs = bpp * model.params / (ms * 1e-3) / 1e9
+            return round(ms, 3), round(gbs, 1), round(gbs / HBM_PEAK_GBS, 4)
+
+        # The once-per-run entry points over the whole set, each as ONE list call (matrices of one shape share
+        # launches), every matrix writing into buffers of its own as a user's would:
+        # the epilogue of training, hard 2:4 projection + fold + pack (6.125 B/param) ...
+        free_bytes, _ = torch.cuda.mem_get_info()
+        if free_bytes > 2.2 * model.params + (4 << 30):
+            outs = [(torch.empty((r, c // 2), device=dev), torch.empty((r, c // 32), dtype=torch.int32, device=dev))
+                    for (_, r, c) in model.shapes]
+            ml = B.MatrixList([dict(w=x["w"], scale=x["A"] if scaled else None, out=o[0], meta=o[1]) for x, o in zip(model.t, outs)])
+            extra["project_compress_ms"], extra["project_compress_GBs"], extra["project_compress_frac"] = \
+                figures(timed_calls(lambda: B.cast_nm_project_compress_multi(ml, 2, 4)), 6.125)
+            # ... with the stored masks instead of Eq. 6 on the final weights (Algorithm 1 literally: 6.25 B/param)
+            ml = B.MatrixList([dict(w=x["w"], scale=x["A"] if scaled else None, out=o[0], meta=o[1], mask=x["mask"])
+                               for x, o in zip(model.t, outs)])
+            B.cast_nm_select_multi(B.MatrixList([dict(w=x["w"], mask=x["mask"]) for x in model.t]), 2, 4)
+            extra["project_compress_stored_mask_ms"], extra["project_compress_stored_mask_GBs"], _ = \
+                figures(timed_calls(lambda: B.cast_nm_project_compress_multi(ml, 2, 4)), 6.25)
+            del outs, ml
+        # ... mask selection alone (Eq. 6: 4.125 B/param) ...
+        ml = B.MatrixList([dict(w=x["w"], mask=x["mask"]) for x in model.t])
+        extra["nm_select_ms"], extra["nm_select_GBs"], extra["nm_select_frac"] = \
+            figures(timed_calls(lambda: B.cast_nm_select_multi(ml, 2, 4)), 4.125)
+        # ... Eq. 12 applied into a bf16 copy of every matrix (6 B/param)
+        free_bytes, _ = torch.cuda.mem_get_info()
+        if scaled and free_bytes > 2 * model.params + (4 << 30):
+            copies16 = [torch.empty(x["w"].shape, dtype=torch.bfloat16, device=dev) for x in model.t]
+            ml = B.MatrixList([dict(w=x["w"], scale=x["A"], out=o) for x, o in zip(model.t, copies16)])
+            extra["weight_scale_bf16_ms"], extra["weight_scale_bf16_GBs"], extra["weight_scale_bf16_frac"] = \
+                figures(timed_calls(lambda: B.cast_weight_scale_multi(ml)), 6.0)
+            del copies16
+        del ml
         # mask-learning statistics of a refresh (flip count against the previous mask, ||W.M||_1, ||W||_1): a pass
         # of its own over w and two masks, 4.25 B/param
         flips = torch.zeros(1, dtype=torch.int64, device=dev)
@@ -342,26 +371,12 @@ def main():
         ms = e0.elapsed_time(e1)
         extra["mask_stats_ms"] = round(ms, 3)
         extra["mask_stats_GBs"] = round(4.25 * model.params / (ms * 1e-3) / 1e9, 1)
-        # the other entry points over the same set: mask selection alone (4.125 B/param), Eq. 12 applied into a bf16
-        # copy (6 B/param), dL/dA alone (6 B/param)
-        big = max(model.t, key=lambda x: x["w"].numel())
-        out16 = torch.empty(big["w"].shape, dtype=torch.bfloat16, device=dev)
-        for name, bpp, call in (
-                ("nm_select", 4.125, lambda x: B.cast_nm_select(x["w"], 2, 4, x["mask"])),
-                ("weight_scale_bf16", 6.0, lambda x: B.cast_weight_scale(x["w"], x["A"], out16.view(-1)[:x["w"].numel()].view(x["w"].shape))),
-                ("weight_scale_grad", 6.0, lambda x: B.cast_weight_scale_grad(x["w"], x["g"], SEGMENTS, x["gA"]))):
-            if not scaled and name != "nm_select":
-                continue
-            for rep in range(2):
-                e0.record()
+        # dL/dA alone (6 B/param), one call per matrix
+        if scaled:
+            def all_scale_grads():
                 for x in model.t:
-                    call(x)
-                e1.record()
-                torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1)
-            extra[f"{name}_ms"] = round(ms, 3)
-            extra[f"{name}_GBs"] = round(bpp * model.params / (ms * 1e-3) / 1e9, 1)
-        del out16
+                    B.cast_weight_scale_grad(x["w"], x["g"], SEGMENTS, x["gA"])
+            extra["weight_scale_grad_ms"], extra["weight_scale_grad_GBs"], _ = figures(timed_calls(all_scale_grads), 6.0)
         if model.list is not None:
             # the widened forms of the step, over the same set and through the same list call: a comparison
             # rule (Eq. 10), and the step that also writes the bf16 weights of the next forward pass
@@ -454,7 +469,7 @@ def main():
         extra["stream_probe"]["frac_of_peak"] = round(extra["stream_probe"]["GBs"] / HBM_PEAK_GBS, 4)
         roofline["frac_of_stream_probe"] = round(probe_ms / dom_ms, 4)
     if not args.no_extra and args.workload == "llama2_7b" and args.layers is None and scaled and args.launch == "list":
-        del model, big, x
+        del model, x
         model = None
         torch.cuda.empty_cache()
         # the same step on the other resident sets of the workload family, and on three dense state arrays

@@ -138,6 +138,26 @@ cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t l
                            int m_group, uint32_t *mask_bits, void *stream);
 
 /*
+ * One matrix of a list for the once-per-run entry points below (cast_nm_select_multi,
+ * cast_weight_scale_multi, cast_nm_project_compress_multi): the arguments of the single-matrix call
+ * of the same name.  Matrices of one shape share kernel launches.
+ */
+typedef struct {
+    const float *w;        /* DEVICE in   fp32 [rows, cols], row stride ld                                      */
+    int64_t rows, cols, ld;
+    const float *scale;    /* DEVICE in   A, fp32 [rows, n_segments]; weight_scale: required; project_compress:  */
+                           /*             or NULL; select: unused                                               */
+    uint32_t *mask_bits;   /* DEVICE      select: out; project_compress: in, or NULL (Eq. 6 on w);               */
+                           /*             weight_scale: unused                                                  */
+    void *out;             /* DEVICE out  weight_scale: out; project_compress: values; select: unused           */
+    uint32_t *meta;        /* DEVICE out  project_compress only                                                 */
+} cast_matrix;
+
+/* cast_nm_select over a list (validated as a whole before anything is launched). */
+cast_status cast_nm_select_multi(const cast_matrix *matrices /* HOST */, int count, int n_keep, int m_group,
+                                 void *stream);
+
+/*
  * One AdamS iteration over one weight matrix: the body of Algorithm 1's loop (Eq. 8), with
  * the proportional decay of Eq. 7 on the entries whose mask bit is 0.
  *
@@ -283,6 +303,11 @@ cast_status cast_adams_multi_launches(const cast_tensor *tensors /* HOST */, int
 cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
                               int64_t ld, int n_segments, void *out, int out_dtype, void *stream);
 
+/* cast_weight_scale over a list: the scaled weights of the whole model before a forward pass
+ * (Algorithm 2 applies Eq. 12 before every forward pass). */
+cast_status cast_weight_scale_multi(const cast_matrix *matrices /* HOST */, int count, int n_segments,
+                                    int out_dtype, void *stream);
+
 /*
  * Gradient of the scale alone, for callers that do not take it from cast_adams_step:
  *   scale_grad[r, s] = sum over c in segment s of grad_scaled[r, c] * w[r, c]
@@ -313,6 +338,11 @@ cast_status cast_nm_project_compress(const float *w, const float *scale, int n_s
                                      const uint32_t *mask_bits, int64_t rows, int64_t cols,
                                      int64_t ld, int n_keep, int m_group, void *values,
                                      int value_dtype, uint32_t *meta, void *stream);
+
+/* cast_nm_project_compress over a list: the last loop of Algorithm 1 over the whole model.
+ * n_segments applies to the matrices whose scale is not NULL. */
+cast_status cast_nm_project_compress_multi(const cast_matrix *matrices /* HOST */, int count, int n_segments,
+                                           int n_keep, int m_group, int value_dtype, void *stream);
 
 /*
  * Mask-learning statistics of one matrix (appendix "Mask Learning"): the numerators of the
@@ -360,8 +390,10 @@ cast_status cast_debug_div_by_uniform(const float *x, float y, float *out, int64
 /*
  * Diagnostic, runs on the HOST: how the step kernels would cover a [rows, cols] matrix with row
  * stride ld and n_segments scaling segments (allow_split = 1: as in a list call with a workspace;
- * allow_split = 2 or 3 with n_segments = 0: the plan of the selection and pack kernels instead, with
- * spans starting on multiples of 32 or 64 columns; other values: CAST_ERR_SHAPE), and
+ * allow_split = 2 or 3 with n_segments = 0: how the selection, scaling and pack kernels cover it instead,
+ * with 4 or 8 entries per thread and load: `wave` then counts the wavefronts of a workgroup's first piece,
+ * then those of its second, ..., each with a span of its own of 256 or 512 entries, plan[2] says how
+ * many, plan[3] = plan[4] = 1; other values: CAST_ERR_SHAPE), and
  * where wavefront `wave` of workgroup `block` would work, computed by the very functions the
  * kernels use.  It exists so that "every entry is covered exactly once and nothing outside the
  * matrix is touched" can be tested for any shape without a GPU.

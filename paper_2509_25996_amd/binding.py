@@ -23,7 +23,7 @@ EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
            "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi",
            "cast_adams_step_emit", "cast_adams_multi_launches", "cast_debug_plan", "cast_adams_step_multi_noalloc",
-           "cast_hbm_stream_probe"]
+           "cast_hbm_stream_probe", "cast_nm_select_multi", "cast_weight_scale_multi", "cast_nm_project_compress_multi"]
 
 
 class CastError(RuntimeError):
@@ -38,6 +38,11 @@ class _Tensor(C.Structure):
                 ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
                 ("compute_copy", C.c_void_p), ("copy_scale", C.c_void_p),
                 ("initial_mask_bits", C.c_void_p), ("refresh_stats", C.c_void_p)]
+
+
+class _Matrix(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64), ("scale", C.c_void_p),
+                ("mask_bits", C.c_void_p), ("out", C.c_void_p), ("meta", C.c_void_p)]
 
 
 class _Config(C.Structure):
@@ -103,6 +108,9 @@ def load():
     L.cast_adams_multi_workspace_bytes.restype = C.c_size_t
     L.cast_adams_step_multi.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp, C.c_size_t, vp]
     L.cast_adams_step_multi_noalloc.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), vp]
+    L.cast_nm_select_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, vp]
+    L.cast_weight_scale_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, vp]
+    L.cast_nm_project_compress_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, ci, ci, vp]
     L.cast_hbm_stream_probe.argtypes = [C.POINTER(_Tensor), ci, ci, vp, C.c_size_t, vp]
     L.cast_debug_plan.argtypes = [i64, i64, i64, ci, ci, i64, ci, C.POINTER(i64), C.POINTER(i64)]
     L.cast_adams_multi_launches.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -211,6 +219,52 @@ def cast_nm_select(w: torch.Tensor, n_keep: int, m_group: int, mask_bits: torch.
     rows, cols = w.shape
     _check(load().cast_nm_select(_ptr(w), rows, cols, _ld(w), n_keep, m_group, _ptr(mask_bits), _stream(stream)),
            "cast_nm_select")
+
+
+class MatrixList:
+    """Descriptors of a list of matrices for the once-per-run list calls (cast_nm_select_multi,
+    cast_weight_scale_multi, cast_nm_project_compress_multi), marshalled once.  Each item is a dict with w and,
+    as the call needs them, scale, mask, out (the scaled weights or the packed values), meta (tensors)."""
+
+    def __init__(self, items):
+        self.items = list(items)     # keeps the tensors alive
+        n = len(self.items)
+        self.array = (_Matrix * max(n, 1))()
+        self.count = n
+        self.out_dtype = None
+        segments = set()
+        for k, x in enumerate(self.items):
+            w = x["w"]
+            sc, mk, out, meta = x.get("scale"), x.get("mask"), x.get("out"), x.get("meta")
+            _dev(sc, mk, out, meta)
+            if out is not None:
+                dt = _dtype_code(out)
+                if self.out_dtype not in (None, dt):
+                    raise ValueError("all outputs of a list must have one dtype")
+                self.out_dtype = dt
+            if sc is not None and w.numel():
+                segments.add(sc.shape[1])
+            self.array[k] = _Matrix(w.data_ptr(), w.shape[0], w.shape[1], _ld(w), None if sc is None else sc.data_ptr(),
+                                    None if mk is None else mk.data_ptr(), None if out is None else out.data_ptr(),
+                                    None if meta is None else meta.data_ptr())
+        if len(segments) > 1:
+            raise ValueError("all matrices of a list must have the same number of scaling segments")
+        self.segments = segments.pop() if segments else 0
+
+
+def cast_nm_select_multi(matrices: MatrixList, n_keep: int, m_group: int, stream=None):
+    _check(load().cast_nm_select_multi(matrices.array, matrices.count, n_keep, m_group, _stream(stream)), "cast_nm_select_multi")
+
+
+def cast_weight_scale_multi(matrices: MatrixList, stream=None):
+    _check(load().cast_weight_scale_multi(matrices.array, matrices.count, matrices.segments, matrices.out_dtype or CAST_F32,
+                                          _stream(stream)), "cast_weight_scale_multi")
+
+
+def cast_nm_project_compress_multi(matrices: MatrixList, n_keep: int, m_group: int, stream=None):
+    _check(load().cast_nm_project_compress_multi(matrices.array, matrices.count, matrices.segments, n_keep, m_group,
+                                                 matrices.out_dtype or CAST_F32, _stream(stream)),
+           "cast_nm_project_compress_multi")
 
 
 def cast_adams_step(w, grad, m, v, mask_bits, cfg: AdamsConfig, scale=None, scale_grad=None, stream=None):

@@ -80,18 +80,36 @@ cast_status cast_sizes(int64_t rows, int64_t cols, int n_keep, int m_group, int 
     return CAST_OK;
 }
 
-cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
-                           int m_group, uint32_t *mask_bits, void *stream)
+static cast_status validate_select(const cast_matrix &t, int n_keep, int m_group)
 {
     cast_status rc = check_nm(n_keep, m_group);
     if (rc != CAST_OK) return rc;
-    rc = check_matrix(rows, cols, m_group);
+    rc = check_matrix(t.rows, t.cols, m_group);
     if (rc != CAST_OK) return rc;
-    if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
-    if (rows == 0 || cols == 0) return CAST_OK;
-    if (!w || !mask_bits) return CAST_ERR_NULL;
-    if (!aligned(w, 16) || !aligned(mask_bits, 4)) return CAST_ERR_ALIGN;
-    return launch_nm_select(w, rows, cols, ld, n_keep, m_group, mask_bits, static_cast<hipStream_t>(stream));
+    if (check_ld(t.cols, t.ld) != CAST_OK) return CAST_ERR_SHAPE;
+    if (t.rows == 0 || t.cols == 0) return CAST_OK;
+    if (!t.w || !t.mask_bits) return CAST_ERR_NULL;
+    if (!aligned(t.w, 16) || !aligned(t.mask_bits, 4)) return CAST_ERR_ALIGN;
+    return CAST_OK;
+}
+
+cast_status cast_nm_select_multi(const cast_matrix *matrices, int count, int n_keep, int m_group, void *stream)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (count == 0) return CAST_OK;
+    if (!matrices) return CAST_ERR_NULL;
+    for (int i = 0; i < count; ++i) {      // all or nothing
+        const cast_status rc = validate_select(matrices[i], n_keep, m_group);
+        if (rc != CAST_OK) return rc;
+    }
+    return launch_nm_select_list(matrices, count, n_keep, m_group, static_cast<hipStream_t>(stream));
+}
+
+cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
+                           int m_group, uint32_t *mask_bits, void *stream)
+{
+    const cast_matrix t{w, rows, cols, ld, nullptr, mask_bits, nullptr, nullptr};
+    return cast_nm_select_multi(&t, 1, n_keep, m_group, stream);
 }
 
 // everything cast_adams_step checks before launching
@@ -226,16 +244,34 @@ cast_status cast_adams_multi_launches(const cast_tensor *tensors, int count, con
     return rc;
 }
 
+static cast_status validate_scale(const cast_matrix &t, int n_segments, int out_dtype)
+{
+    if (t.rows < 0 || t.cols < 0 || n_segments < 1 || (t.cols % n_segments) || t.ld < t.cols) return CAST_ERR_SHAPE;
+    if (t.rows > 0 && t.cols > 0 && t.rows > (((int64_t)1 << 40) / t.cols)) return CAST_ERR_SHAPE;
+    if (!dtype_ok(out_dtype)) return CAST_ERR_DTYPE;
+    if (t.rows == 0 || t.cols == 0) return CAST_OK;
+    if (!t.w || !t.scale || !t.out) return CAST_ERR_NULL;
+    if (!aligned(t.w, 16) || !aligned(t.out, dtype_align(out_dtype)) || !aligned(t.scale, 4)) return CAST_ERR_ALIGN;
+    return CAST_OK;
+}
+
+cast_status cast_weight_scale_multi(const cast_matrix *matrices, int count, int n_segments, int out_dtype, void *stream)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (count == 0) return CAST_OK;
+    if (!matrices) return CAST_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const cast_status rc = validate_scale(matrices[i], n_segments, out_dtype);
+        if (rc != CAST_OK) return rc;
+    }
+    return launch_weight_scale_list(matrices, count, n_segments, out_dtype, static_cast<hipStream_t>(stream));
+}
+
 cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
                               int64_t ld, int n_segments, void *out, int out_dtype, void *stream)
 {
-    if (rows < 0 || cols < 0 || n_segments < 1 || (cols % n_segments) || ld < cols) return CAST_ERR_SHAPE;
-    if (rows > 0 && cols > 0 && rows > (((int64_t)1 << 40) / cols)) return CAST_ERR_SHAPE;
-    if (!dtype_ok(out_dtype)) return CAST_ERR_DTYPE;
-    if (rows == 0 || cols == 0) return CAST_OK;
-    if (!w || !scale || !out) return CAST_ERR_NULL;
-    if (!aligned(w, 16) || !aligned(out, dtype_align(out_dtype)) || !aligned(scale, 4)) return CAST_ERR_ALIGN;
-    return launch_weight_scale(w, scale, rows, cols, ld, n_segments, out, out_dtype, static_cast<hipStream_t>(stream));
+    const cast_matrix t{w, rows, cols, ld, scale, nullptr, out, nullptr};
+    return cast_weight_scale_multi(&t, 1, n_segments, out_dtype, stream);
 }
 
 cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int grad_dtype,
@@ -252,27 +288,45 @@ cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int 
     return launch_scale_grad(w, grad_scaled, grad_dtype, rows, cols, ld, n_segments, scale_grad, static_cast<hipStream_t>(stream));
 }
 
+static cast_status validate_pack(const cast_matrix &t, int n_segments, int n_keep, int m_group, int value_dtype)
+{
+    cast_status rc = check_nm(n_keep, m_group);
+    if (rc != CAST_OK) return rc;
+    rc = check_matrix(t.rows, t.cols, m_group);
+    if (rc != CAST_OK) return rc;
+    if (check_ld(t.cols, t.ld) != CAST_OK) return CAST_ERR_SHAPE;
+    if (!dtype_ok(value_dtype)) return CAST_ERR_DTYPE;
+    if (t.scale && t.cols > 0) {
+        rc = check_segments(t.cols, n_segments, m_group);
+        if (rc != CAST_OK) return rc;
+    }
+    if (t.rows == 0 || t.cols == 0) return CAST_OK;
+    if (!t.w || !t.out || !t.meta) return CAST_ERR_NULL;
+    if (!aligned(t.w, 16) || !aligned(t.out, 8) || !aligned(t.meta, 4) || !aligned(t.mask_bits, 4) || !aligned(t.scale, 4))
+        return CAST_ERR_ALIGN;
+    return CAST_OK;
+}
+
+cast_status cast_nm_project_compress_multi(const cast_matrix *matrices, int count, int n_segments, int n_keep, int m_group,
+                                           int value_dtype, void *stream)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (count == 0) return CAST_OK;
+    if (!matrices) return CAST_ERR_NULL;
+    for (int i = 0; i < count; ++i) {
+        const cast_status rc = validate_pack(matrices[i], n_segments, n_keep, m_group, value_dtype);
+        if (rc != CAST_OK) return rc;
+    }
+    return launch_project_compress_list(matrices, count, n_segments, n_keep, m_group, value_dtype, static_cast<hipStream_t>(stream));
+}
+
 cast_status cast_nm_project_compress(const float *w, const float *scale, int n_segments,
                                      const uint32_t *mask_bits, int64_t rows, int64_t cols,
                                      int64_t ld, int n_keep, int m_group, void *values,
                                      int value_dtype, uint32_t *meta, void *stream)
 {
-    cast_status rc = check_nm(n_keep, m_group);
-    if (rc != CAST_OK) return rc;
-    rc = check_matrix(rows, cols, m_group);
-    if (rc != CAST_OK) return rc;
-    if (check_ld(cols, ld) != CAST_OK) return CAST_ERR_SHAPE;
-    if (!dtype_ok(value_dtype)) return CAST_ERR_DTYPE;
-    if (scale && cols > 0) {
-        rc = check_segments(cols, n_segments, m_group);
-        if (rc != CAST_OK) return rc;
-    }
-    if (rows == 0 || cols == 0) return CAST_OK;
-    if (!w || !values || !meta) return CAST_ERR_NULL;
-    if (!aligned(w, 16) || !aligned(values, 8) || !aligned(meta, 4) || !aligned(mask_bits, 4) || !aligned(scale, 4))
-        return CAST_ERR_ALIGN;
-    return launch_project_compress(w, scale, scale ? n_segments : 0, mask_bits, rows, cols, ld, n_keep, m_group,
-                                   values, value_dtype, meta, static_cast<hipStream_t>(stream));
+    const cast_matrix t{w, rows, cols, ld, scale, const_cast<uint32_t *>(mask_bits), values, meta};
+    return cast_nm_project_compress_multi(&t, 1, n_segments, n_keep, m_group, value_dtype, stream);
 }
 
 cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
@@ -339,8 +393,28 @@ cast_status cast_debug_plan(int64_t rows, int64_t cols, int64_t ld, int n_segmen
     // allow_split: 0, 1 = the step kernels' plan without / with split plans; 2, 3 = the plan of the selection and
     // pack kernels with spans starting on 32 / 64 columns
     if (allow_split < 0 || allow_split > 3 || (allow_split >= 2 && n_segments != 0)) return CAST_ERR_SHAPE;
-    const SpanPlan p = allow_split >= 2 ? plan_batched(rows, cols, ld, allow_split == 2 ? 32 : 64)
-                                        : plan_spans(rows, cols, ld, n_segments, allow_split != 0);
+    if (allow_split >= 2) {      // the selection, scaling and pack kernels: 4 or 8 entries per thread and load
+        const RowsPlan r = plan_rows(rows, cols, ld, allow_split == 2 ? 4 : 8);
+        const int slots = kBlockWaves * r.geom.loads;
+        plan[0] = r.vec ? 1 : 0;
+        plan[1] = r.grid;
+        plan[2] = slots;
+        plan[3] = 1;
+        plan[4] = 1;
+        for (int k = 0; k < 5; ++k) span[k] = 0;
+        if (!r.vec || block >= (int64_t)r.grid || wave >= slots) return CAST_OK;
+        const RowsPiece piece = rows_piece(r.geom, (uint32_t)block, wave / kBlockWaves);
+        const int64_t col = piece.col + (int64_t)(wave % kBlockWaves) * kWave * r.geom.lane_entries;
+        if (col >= cols) return CAST_OK;
+        const int64_t len = kWave * r.geom.lane_entries;
+        span[0] = (int64_t)piece.row * ld + col;
+        span[1] = (int64_t)piece.row * cols + col;
+        span[2] = col + len <= cols ? len : cols - col;
+        span[3] = block * slots + wave;      // a span of its own for every wavefront and piece
+        span[4] = 0;
+        return CAST_OK;
+    }
+    const SpanPlan p = plan_spans(rows, cols, ld, n_segments, allow_split != 0);
     const int block_waves = p.block_threads / kWave;
     plan[0] = p.vec ? 1 : 0;
     plan[1] = p.grid;

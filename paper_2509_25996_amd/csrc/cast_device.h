@@ -146,6 +146,32 @@ __host__ __device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, i
     return o;
 }
 
+// ---- how the selection, scaling and pack kernels cut a matrix ---------------------------------
+// A workgroup of 256 threads covers `loads` pieces of 256 * lane_entries consecutive entries of one
+// row; piece k of workgroup b of a row starts at column (b * loads + k) * 256 * lane_entries.
+struct RowsGeom {
+    int cols;                 // entries per row (at most 2^30)
+    int64_t ld;               // row stride of w
+    int lane_entries;         // 4, or 8 for the 4:8 pack
+    int loads;                // pieces per workgroup
+    uint32_t blocks_per_row;
+    FastDivU32 div_blocks_per_row;
+};
+
+struct RowsPiece {
+    uint32_t row;
+    int col;                  // first column of the piece (may lie past the end of the row: nothing to do then)
+};
+
+__host__ __device__ __forceinline__ RowsPiece rows_piece(const RowsGeom &g, uint32_t block, int k)
+{
+    RowsPiece p;
+    p.row = fast_div(block, g.div_blocks_per_row);
+    const uint32_t in_row = block - p.row * g.blocks_per_row;
+    p.col = (int)((in_row * (uint32_t)g.loads + (uint32_t)k) * (uint32_t)(kBlockThreads * g.lane_entries));
+    return p;
+}
+
 // ---- cross-lane moves inside a row of 16 lanes (DPP: no LDS traffic) -------------------
 // quad_perm selectors: lane i of each quad reads lane perm[i] of the same quad.
 constexpr int kDppQuadXor1 = 0xB1;       // [1,0,3,2]

@@ -27,8 +27,15 @@ constexpr uint32_t kInternalFlagStreamProbe = 0x80000000u;
 // allow_split: row segments of more than 16 chunks of 256 entries may be cut into pieces with a
 // workgroup each; the caller then supplies a PieceArea for the pieces' dL/dA sums.
 SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool allow_split = false);
-// the plan of the selection and pack kernels (up to four chunks of a span per wavefront, requested together)
-SpanPlan plan_batched(int64_t rows, int64_t cols, int64_t ld, int align);
+// How the selection, scaling and pack kernels cover a matrix (see RowsGeom): `lane_entries` consecutive entries
+// per thread and load.  vec = false: the shape goes to the scalar kernels.
+struct RowsPlan {
+    bool vec;
+    RowsGeom geom;
+    unsigned grid;       // workgroups per matrix
+};
+RowsPlan plan_rows(int64_t rows, int64_t cols, int64_t ld, int lane_entries);
+constexpr int kMaxListed = 16;      // matrices of equal shape that one launch of these kernels can take (gridDim.y)
 
 // Device memory for the piece sums of split plans: what is left of it, and who collects the
 // second halves (adding the pieces up) of the matrices that took a part.
@@ -65,15 +72,11 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad,
                               hipStream_t stream);
-cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
-                             int m_group, uint32_t *mask_bits, hipStream_t stream);
-cast_status launch_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
-                                int64_t ld, int n_segments, void *out, int out_dtype,
-                                hipStream_t stream);
-cast_status launch_project_compress(const float *w, const float *scale, int n_segments,
-                                    const uint32_t *mask_bits, int64_t rows, int64_t cols,
-                                    int64_t ld, int n_keep, int m_group, void *values,
-                                    int value_dtype, uint32_t *meta, hipStream_t stream);
+// Lists of matrices (already validated): matrices of one shape share launches.
+cast_status launch_nm_select_list(const cast_matrix *m, int count, int n_keep, int m_group, hipStream_t stream);
+cast_status launch_weight_scale_list(const cast_matrix *m, int count, int n_segments, int out_dtype, hipStream_t stream);
+cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_segments, int n_keep, int m_group,
+                                         int value_dtype, hipStream_t stream);
 cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
                               int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
                               double *l1, hipStream_t stream);

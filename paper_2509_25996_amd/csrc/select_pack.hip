@@ -3,6 +3,8 @@
 // "Mask Learning", and a plain copy kernel used to calibrate bandwidth measurements.
 //
 // w may have a row stride ld >= cols; masks, packed values, metadata and scaled outputs are dense.
+#include <vector>
+
 #include "cast_device.h"
 #include "cast_internal.h"
 
@@ -10,111 +12,112 @@
 
 namespace cast {
 
+// Cache policies of this file's kernels (0 = default, 2 = non-temporal), as measured over the
+// LLaMA2-7B-shaped set with every matrix writing to buffers of its own: weights and masks, read once,
+// and the outputs that every lane writes (packed values, scaled weights: whole cache lines per
+// wavefront) with the non-temporal hint (default policy: pack and Eq. 12 into bf16 10 % slower; it only
+// looks faster when all matrices write into one small buffer that stays in the last-level cache).
+#ifndef CAST_AUX_ONCE_LOAD
+#define CAST_AUX_ONCE_LOAD 2
+#endif
+#ifndef CAST_AUX_FULL_STORE
+#define CAST_AUX_FULL_STORE 2
+#endif
+constexpr int kAuxOnceLoad = CAST_AUX_ONCE_LOAD;      // weights (and masks) read once
+constexpr int kAuxFullStore = CAST_AUX_FULL_STORE;    // packed values, scaled weights: every lane stores, whole lines
+
+template <typename T>
+__device__ __forceinline__ T load_once(const T *p)
+{
+    if constexpr ((kAuxOnceLoad & 2) != 0) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+template <typename T>
+__device__ __forceinline__ void store_full(T *p, const T &x)
+{
+    if constexpr ((kAuxFullStore & 2) != 0) __builtin_nontemporal_store(x, p);
+    else *p = x;
+}
+
 __device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
 {
     f[0] = __uint_as_float(x.x); f[1] = __uint_as_float(x.y); f[2] = __uint_as_float(x.z); f[3] = __uint_as_float(x.w);
 }
 
-// These kernels do little arithmetic per byte, so what counts is memory requests in flight: a
-// wavefront takes up to kBatch chunks of its span and asks for all of them before it works on the
-// first.  The plan: dense matrices are cut into spans of kBatch chunks, one wavefront each; rows
-// with a stride are cut into the fewest equal pieces of at most 16 * kBatch chunks that start on
-// `align` columns, and as many wavefronts share a piece as it has kBatch chunks (a power of two).
-constexpr int kBatch = 4;
+// ---- how these kernels cover a matrix ----------------------------------------------------------
+// They do little arithmetic per byte and read every weight once, so what counts is plain, wide,
+// independent loads: a thread owns kLoads pieces of E consecutive entries (E = 4: one 16-byte load;
+// E = 8 for the 4:8 pack: two), a workgroup of 256 threads covers kLoads * 256 * E consecutive
+// entries of ONE row, its k-th piece being the k-th run of 256 * E entries, and all loads of a thread
+// are requested before the first is used.  Rows are whole mask words (cols % 32 == 0), so every run
+// of 8 lanes (E = 4) holds one mask word.  blockIdx.y picks one of up to kMaxListed matrices of equal
+// shape whose buffers travel in the kernel arguments (list calls).
+// Measured over the LLaMA2-7B-shaped set (weights row-interleaved with the moments): two loads per
+// thread beat one (-15 %), three (-9 %) and four (-2 %); mask and metadata words, which fill a cache
+// line only together with their neighbours', are stored with the default policy so that the L2 merges
+// them (non-temporal: 7 % slower).  A form in which wavefronts walked spans through buffer resources
+// with four chunks in flight, like the step kernels, ran at 5.2 TB/s where this one runs at 6.3.
+#ifndef CAST_ROWS_LOADS
+#define CAST_ROWS_LOADS 2
+#endif
+constexpr int kLoads = CAST_ROWS_LOADS;
 
-SpanPlan plan_batched(int64_t rows, int64_t cols, int64_t ld, int align)
+RowsPlan plan_rows(int64_t rows, int64_t cols, int64_t ld, int lane_entries)
 {
-    int per_row = 0;
-    if (ld != cols)
-        for (int k = 1; k <= 64 && per_row == 0; ++k)
-            if (cols % k == 0 && (cols / k) % align == 0 && cols / k <= (int64_t)kMaxBlockWaves * kBatch * kChunk) per_row = k;
-    SpanPlan p = plan_spans(rows, cols, ld, per_row);
+    RowsPlan p{};
+    const int64_t per_block = (int64_t)kLoads * kBlockThreads * lane_entries;
+    p.vec = rows > 0 && cols > 0 && cols % 32 == 0 && ld % 4 == 0 && cols <= ((int64_t)1 << 30);
     if (!p.vec) return p;
-    SpanGeom &g = p.geom;
-    if (g.spans_per_row == 0) {
-        g.span_len = (int64_t)kBatch * kChunk;
-        g.num_spans = (g.total + g.span_len - 1) / g.span_len;
-    }
-    const int64_t chunks = (g.span_len + kChunk - 1) / kChunk;
-    int P = 1;
-    while ((int64_t)P * kBatch < chunks && P < kMaxBlockWaves) P *= 2;
-    g.waves_per_span = P;
-    const int block_waves = P > kBlockWaves ? P : kBlockWaves;
-    p.block_threads = block_waves * kWave;
-    const int64_t spans_per_block = block_waves / P;
-    p.grid = (unsigned)((g.num_spans + spans_per_block - 1) / spans_per_block);
+    const int64_t blocks_per_row = (cols + per_block - 1) / per_block;
+    if (rows * blocks_per_row >= ((int64_t)1 << 31)) { p.vec = false; return p; }
+    p.geom.cols = (int)cols;
+    p.geom.ld = ld;
+    p.geom.lane_entries = lane_entries;
+    p.geom.loads = kLoads;
+    p.geom.blocks_per_row = (uint32_t)blocks_per_row;
+    p.geom.div_blocks_per_row = make_fast_div((uint32_t)blocks_per_row);
+    p.grid = (unsigned)(rows * blocks_per_row);
     return p;
 }
 
 // ---- Eq. 6 ----------------------------------------------------------------------------------
-// Spans start on mask words; a wavefront's chunks of a span are sub, sub + P, sub + 2P, ...
-template <int M>
-__global__ __launch_bounds__(kMaxBlockThreads) void nm_select_vec(const float *w, uint32_t *mask,
-                                                                  const SpanGeom geom, int n_keep)
-{
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int stride = geom.waves_per_span * kChunk;
-    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
-    const int64_t span = slot.span;
-    const int sub = slot.sub;
-    const SpanOrigin o = span_origin(geom, span);
-    const int len = o.len;
-    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
-    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask + (o.dense_begin >> 5), len / 8);
-    for (int base = sub * kChunk; base < len; base += kBatch * stride) {
-        vu4_t raw[kBatch];
-#pragma unroll
-        for (int k = 0; k < kBatch; ++k)      // past the end of the span: zeros
-            raw[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, (base + k * stride + lane * kLaneElems) * 4, 0, kAuxLoad);
-#pragma unroll
-        for (int k = 0; k < kBatch; ++k) {
-            if (base + k * stride >= len) break;      // wave-uniform
-            const int off = base + k * stride + lane * kLaneElems;
-            float x[4];
-            unpack4u(raw[k], x);
-            const uint32_t nib = keep_nibble<M>(x, n_keep, lane);
-            const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
-            if ((lane & 7) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmask, (off >> 5) * 4, 0, kAuxStore);
-        }
-    }
-}
+struct SelectSet {
+    const float *w;
+    uint32_t *mask;
+};
 
-// M = 8 with a whole group per lane (8 consecutive entries, two 16-byte loads): the ranking needs no
-// exchange between lanes, and the bytes of four adjacent lanes form a mask word.  Units of 512 entries
-// per wavefront, two of them requested before the first is worked on.
-__global__ __launch_bounds__(kMaxBlockThreads) void nm_select_8_vec(const float *w, uint32_t *mask, const SpanGeom geom, int n_keep)
+struct SelectArgs {
+    SelectSet set[kMaxListed];
+    RowsGeom geom;
+    int n_keep;
+};
+
+template <int M>
+__global__ __launch_bounds__(kBlockThreads) void nm_select_rows(const SelectArgs a)
 {
-    constexpr int kUnit = 2 * kChunk;
-    constexpr int kUnitsInFlight = 2;
+    const SelectSet t = a.set[blockIdx.y];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int stride = geom.waves_per_span * kUnit;
-    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
-    const int sub = slot.sub;
-    const SpanOrigin o = span_origin(geom, slot.span);
-    const int len = o.len;
-    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
-    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask + (o.dense_begin >> 5), len / 8);
-    for (int base = sub * kUnit; base < len; base += kUnitsInFlight * stride) {
-        vu4_t lo[kUnitsInFlight], hi[kUnitsInFlight];
+    const int cols = a.geom.cols;
+    vf4_t raw[kLoads];
+    int col[kLoads];
+    const float *src = nullptr;
+    uint32_t *dst = nullptr;
 #pragma unroll
-        for (int k = 0; k < kUnitsInFlight; ++k) {      // past the end of the span: zeros
-            const int off = base + k * stride + lane * 8;
-            lo[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad);
-            hi[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4 + 16, 0, kAuxLoad);
-        }
+    for (int k = 0; k < kLoads; ++k) {
+        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
+        col[k] = piece.col + (int)threadIdx.x * 4;
+        src = t.w + (int64_t)piece.row * a.geom.ld;
+        dst = t.mask + (int64_t)piece.row * (cols >> 5);
+        raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};      // past the end of the row: zeros, nothing stored
+        if (col[k] < cols) raw[k] = load_once(reinterpret_cast<const vf4_t *>(src + col[k]));
+    }
 #pragma unroll
-        for (int k = 0; k < kUnitsInFlight; ++k) {
-            if (base + k * stride >= len) break;      // wave-uniform
-            const int off = base + k * stride + lane * 8;
-            const float x[8] = {__uint_as_float(lo[k].x), __uint_as_float(lo[k].y), __uint_as_float(lo[k].z), __uint_as_float(lo[k].w),
-                                __uint_as_float(hi[k].x), __uint_as_float(hi[k].y), __uint_as_float(hi[k].z), __uint_as_float(hi[k].w)};
-            uint32_t word = keep_bits_group<8>(x, n_keep) << ((lane & 3) * 8);
-            word |= dpp_u32<kDppQuadXor1>(word);
-            word |= dpp_u32<kDppQuadXor2>(word);
-            if ((lane & 3) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmask, (off >> 5) * 4, 0, kAuxStore);
-        }
+    for (int k = 0; k < kLoads; ++k) {
+        const float x[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
+        const uint32_t nib = keep_nibble<M>(x, a.n_keep, lane);      // all 64 lanes take part
+        const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
+        if ((lane & 7) == 0 && col[k] < cols) dst[col[k] >> 5] = word;
     }
 }
 
@@ -139,27 +142,63 @@ __global__ __launch_bounds__(kBlockThreads) void nm_select_unit(const float *w, 
     mask[tid] = word;
 }
 
-cast_status launch_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
-                             int m_group, uint32_t *mask_bits, hipStream_t st)
+// Matrices of one shape (and, for `alike`, the same optional buffers) go several to a launch: up to
+// kMaxListed of them and about 72 M entries, the rule of the step kernels (a short launch pays some 2.6 us
+// of ramp, a very long one lets the compute units drift apart).  Collects into `group` the indices, from
+// `first` on, of matrices not yet taken that are like matrix `first`, and marks them taken.
+template <typename Alike>
+static int take_group(const cast_matrix *m, int count, std::vector<char> &taken, int first, Alike alike, int (&group)[kMaxListed])
 {
-    if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_batched(rows, cols, ld, 32);
-    if (p.vec) {
-        switch (m_group) {
-        case 2: hipLaunchKernelGGL(nm_select_vec<2>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
-        case 4: hipLaunchKernelGGL(nm_select_vec<4>, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
-        default: hipLaunchKernelGGL(nm_select_8_vec, dim3(p.grid), dim3(p.block_threads), 0, st, w, mask_bits, p.geom, n_keep); break;
+    const cast_matrix &t = m[first];
+    int most = kMaxListed;
+    const int64_t entries = t.rows * t.cols;
+    const int64_t launch_entries = (int64_t)72 << 20;
+    if (entries > 0 && launch_entries / entries < most) most = (int)(launch_entries / entries);
+    if (most < 1) most = 1;
+    int n = 0;
+    group[n++] = first;
+    taken[first] = 1;
+    for (int j = first + 1; j < count && n < most; ++j)
+        if (!taken[j] && m[j].rows == t.rows && m[j].cols == t.cols && m[j].ld == t.ld && alike(m[j], t)) {
+            group[n++] = j;
+            taken[j] = 1;
         }
-    } else {
-        const int64_t words = rows * ((cols + 31) / 32);
-        const unsigned grid = (unsigned)((words + kBlockThreads - 1) / kBlockThreads);
-        switch (m_group) {
-        case 2: hipLaunchKernelGGL(nm_select_unit<2>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, ld, n_keep); break;
-        case 4: hipLaunchKernelGGL(nm_select_unit<4>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, ld, n_keep); break;
-        default: hipLaunchKernelGGL(nm_select_unit<8>, dim3(grid), dim3(kBlockThreads), 0, st, w, mask_bits, rows, cols, ld, n_keep); break;
+    return n;
+}
+
+cast_status launch_nm_select_list(const cast_matrix *m, int count, int n_keep, int m_group, hipStream_t st)
+{
+    std::vector<char> taken((size_t)count, 0);
+    for (int i = 0; i < count; ++i) {
+        if (taken[i] || m[i].rows == 0 || m[i].cols == 0) continue;
+        int group[kMaxListed];
+        const int n = take_group(m, count, taken, i, [](const cast_matrix &, const cast_matrix &) { return true; }, group);
+        const RowsPlan p = plan_rows(m[i].rows, m[i].cols, m[i].ld, 4);
+        if (p.vec) {
+            SelectArgs a{{}, p.geom, n_keep};
+            for (int k = 0; k < n; ++k) a.set[k] = SelectSet{m[group[k]].w, m[group[k]].mask_bits};
+            const dim3 grid(p.grid, (unsigned)n), block(kBlockThreads);
+            switch (m_group) {
+            case 2: hipLaunchKernelGGL(nm_select_rows<2>, grid, block, 0, st, a); break;
+            case 4: hipLaunchKernelGGL(nm_select_rows<4>, grid, block, 0, st, a); break;
+            default: hipLaunchKernelGGL(nm_select_rows<8>, grid, block, 0, st, a); break;
+            }
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+            continue;
+        }
+        for (int k = 0; k < n; ++k) {      // other shapes: one thread per mask word, one launch per matrix
+            const cast_matrix &t = m[group[k]];
+            const int64_t words = t.rows * ((t.cols + 31) / 32);
+            const unsigned grid = (unsigned)((words + kBlockThreads - 1) / kBlockThreads);
+            switch (m_group) {
+            case 2: hipLaunchKernelGGL(nm_select_unit<2>, dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.mask_bits, t.rows, t.cols, t.ld, n_keep); break;
+            case 4: hipLaunchKernelGGL(nm_select_unit<4>, dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.mask_bits, t.rows, t.cols, t.ld, n_keep); break;
+            default: hipLaunchKernelGGL(nm_select_unit<8>, dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.mask_bits, t.rows, t.cols, t.ld, n_keep); break;
+            }
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         }
     }
-    return launch_status();
+    return CAST_OK;
 }
 
 // ---- Eq. 12 forward / fold --------------------------------------------------------------------
@@ -175,7 +214,7 @@ __global__ __launch_bounds__(kBlockThreads) void weight_scale_kernel(const float
     const float A = scale[idx / seg_len];      // dense segment index = r * n + s
     float x[W];
     if constexpr (W == 4) {
-        const float4 t = *reinterpret_cast<const float4 *>(w + r * ld + c);
+        const vf4_t t = load_once(reinterpret_cast<const vf4_t *>(w + r * ld + c));
         x[0] = A * t.x; x[1] = A * t.y; x[2] = A * t.z; x[3] = A * t.w;
     } else {
         x[0] = A * w[r * ld + c];
@@ -183,194 +222,244 @@ __global__ __launch_bounds__(kBlockThreads) void weight_scale_kernel(const float
     if constexpr (BF16OUT) {
         uint16_t *o = static_cast<uint16_t *>(out) + idx;
         if constexpr (W == 4) {
-            uint2 q;
-            q.x = f32x2_to_bf16_rne(x[0], x[1]);
-            q.y = f32x2_to_bf16_rne(x[2], x[3]);
-            *reinterpret_cast<uint2 *>(o) = q;
+            const vu2_t q = {f32x2_to_bf16_rne(x[0], x[1]), f32x2_to_bf16_rne(x[2], x[3])};
+            store_full(reinterpret_cast<vu2_t *>(o), q);
         } else {
             o[0] = (uint16_t)f32_to_bf16_rne(x[0]);
         }
     } else {
         float *o = static_cast<float *>(out) + idx;
-        if constexpr (W == 4) *reinterpret_cast<float4 *>(o) = make_float4(x[0], x[1], x[2], x[3]);
+        if constexpr (W == 4) store_full(reinterpret_cast<vf4_t *>(o), vf4_t{x[0], x[1], x[2], x[3]});
         else o[0] = x[0];
     }
 }
 
-cast_status launch_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
-                                int64_t ld, int n_segments, void *out, int out_dtype, hipStream_t st)
+// The same for rows that are whole mask words (the benchmark shapes): the row-block form of this file.
+struct ScaleSet {
+    const float *w;
+    const float *scale;
+    void *out;
+};
+
+struct ScaleArgs {
+    ScaleSet set[kMaxListed];
+    RowsGeom geom;
+    FastDivU32 div_seg_len;
+    int n_segments;
+};
+
+template <bool BF16OUT>
+__global__ __launch_bounds__(kBlockThreads) void weight_scale_rows(const ScaleArgs a)
 {
-    if (rows == 0 || cols == 0) return CAST_OK;
-    const int64_t total = rows * cols, seg_len = cols / n_segments;
-    const bool bf16 = out_dtype == CAST_BF16;
-    if (seg_len % 4 == 0 && ld % 4 == 0) {
-        const unsigned grid = (unsigned)((total / 4 + kBlockThreads - 1) / kBlockThreads);
-        if (bf16) hipLaunchKernelGGL((weight_scale_kernel<true, 4>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
-        else hipLaunchKernelGGL((weight_scale_kernel<false, 4>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
-    } else {
-        const unsigned grid = (unsigned)((total + kBlockThreads - 1) / kBlockThreads);
-        if (bf16) hipLaunchKernelGGL((weight_scale_kernel<true, 1>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
-        else hipLaunchKernelGGL((weight_scale_kernel<false, 1>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, out, rows, cols, ld, seg_len);
+    const ScaleSet t = a.set[blockIdx.y];
+    const int cols = a.geom.cols;
+    vf4_t raw[kLoads];
+    float A[kLoads];
+    int64_t at[kLoads];      // dense index of the thread's first entry, -1: nothing to do
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
+        const int c = piece.col + (int)threadIdx.x * 4;
+        at[k] = -1;
+        raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        A[k] = 0.0f;
+        if (c < cols) {
+            at[k] = (int64_t)piece.row * cols + c;
+            raw[k] = load_once(reinterpret_cast<const vf4_t *>(t.w + (int64_t)piece.row * a.geom.ld + c));
+            A[k] = t.scale[(int64_t)piece.row * a.n_segments + fast_div((uint32_t)c, a.div_seg_len)];
+        }
     }
-    return launch_status();
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+        if (at[k] < 0) continue;
+        const float x0 = A[k] * raw[k].x, x1 = A[k] * raw[k].y, x2 = A[k] * raw[k].z, x3 = A[k] * raw[k].w;      // Eq. 12
+        if constexpr (BF16OUT) {
+            const vu2_t q = {f32x2_to_bf16_rne(x0, x1), f32x2_to_bf16_rne(x2, x3)};
+            store_full(reinterpret_cast<vu2_t *>(static_cast<uint16_t *>(t.out) + at[k]), q);
+        } else {
+            store_full(reinterpret_cast<vf4_t *>(static_cast<float *>(t.out) + at[k]), vf4_t{x0, x1, x2, x3});
+        }
+    }
+}
+
+cast_status launch_weight_scale_list(const cast_matrix *m, int count, int n_segments, int out_dtype, hipStream_t st)
+{
+    const bool bf16 = out_dtype == CAST_BF16;
+    std::vector<char> taken((size_t)count, 0);
+    for (int i = 0; i < count; ++i) {
+        if (taken[i] || m[i].rows == 0 || m[i].cols == 0) continue;
+        int group[kMaxListed];
+        const int n = take_group(m, count, taken, i, [](const cast_matrix &, const cast_matrix &) { return true; }, group);
+        const cast_matrix &t0 = m[i];
+        const int64_t seg_len = t0.cols / n_segments;
+        const RowsPlan p = plan_rows(t0.rows, t0.cols, t0.ld, 4);
+        if (p.vec && seg_len % 4 == 0) {
+            ScaleArgs a{{}, p.geom, make_fast_div((uint32_t)seg_len), n_segments};
+            for (int k = 0; k < n; ++k) a.set[k] = ScaleSet{m[group[k]].w, m[group[k]].scale, m[group[k]].out};
+            const dim3 grid(p.grid, (unsigned)n), block(kBlockThreads);
+            if (bf16) hipLaunchKernelGGL(weight_scale_rows<true>, grid, block, 0, st, a);
+            else hipLaunchKernelGGL(weight_scale_rows<false>, grid, block, 0, st, a);
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+            continue;
+        }
+        for (int k = 0; k < n; ++k) {
+            const cast_matrix &t = m[group[k]];
+            const int64_t total = t.rows * t.cols;
+            if (seg_len % 4 == 0 && t.ld % 4 == 0) {
+                const unsigned grid = (unsigned)((total / 4 + kBlockThreads - 1) / kBlockThreads);
+                if (bf16) hipLaunchKernelGGL((weight_scale_kernel<true, 4>), dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.scale, t.out, t.rows, t.cols, t.ld, seg_len);
+                else hipLaunchKernelGGL((weight_scale_kernel<false, 4>), dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.scale, t.out, t.rows, t.cols, t.ld, seg_len);
+            } else {
+                const unsigned grid = (unsigned)((total + kBlockThreads - 1) / kBlockThreads);
+                if (bf16) hipLaunchKernelGGL((weight_scale_kernel<true, 1>), dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.scale, t.out, t.rows, t.cols, t.ld, seg_len);
+                else hipLaunchKernelGGL((weight_scale_kernel<false, 1>), dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.scale, t.out, t.rows, t.cols, t.ld, seg_len);
+            }
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+        }
+    }
+    return CAST_OK;
 }
 
 // ---- hard prune + fold + pack ---------------------------------------------------------------
+struct PackSet {
+    const float *w;
+    const float *scale;       // or NULL
+    const uint32_t *mask;     // or NULL: Eq. 6 on w
+    void *values;
+    uint32_t *meta;
+};
+
+struct PackArgs {
+    PackSet set[kMaxListed];
+    RowsGeom geom;
+    FastDivU32 div_seg_len;
+    int n_segments;
+};
+
 // The half-density patterns 2:4 (the paper's) and 1:2 (4:8 has a kernel of its own below).  A lane holds 4
 // consecutive entries and always ends up with exactly two kept values, which leave as one 8-byte (fp32) or
-// 4-byte (bf16) store at values[off / 2]:
+// 4-byte (bf16) store at values[dense index / 2]:
 //   2:4  the lane is one group; the 4-bit index fields of 8 adjacent lanes form one metadata word;
 //   1:2  the lane is two groups with one kept entry each; 16 lanes' bit pairs form one word.
 template <int M, bool BF16OUT>
-__global__ __launch_bounds__(kMaxBlockThreads) void project_compress_half_vec(
-    const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
-    const SpanGeom geom, uint32_t seg_len, FastDivU32 div_seg_len)
+__global__ __launch_bounds__(kBlockThreads) void project_compress_half_rows(const PackArgs a)
 {
     static_assert(M == 4 || M == 2, "2:4 and 1:2 only");
     constexpr int kEntriesPerWord = M == 4 ? 32 : 64;      // columns one metadata word describes
+    const PackSet t = a.set[blockIdx.y];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int stride = geom.waves_per_span * kChunk;
-    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
-    const int64_t span = slot.span;
-    const int sub = slot.sub;
-    const SpanOrigin o = span_origin(geom, span);
-    const int len = o.len;
-    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
-    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask ? mask + (o.dense_begin >> 5) : nullptr, mask ? len / 8 : 0);
-    const __amdgpu_buffer_rsrc_t rmeta = span_resource(meta + o.dense_begin / kEntriesPerWord, len / kEntriesPerWord * 4);
-    // half of the entries are kept: the values of a span start at dense_begin / 2
-    const int vbytes = BF16OUT ? 2 : 4;
-    const __amdgpu_buffer_rsrc_t rval = span_resource(static_cast<char *>(values) + (o.dense_begin >> 1) * vbytes, (len >> 1) * vbytes);
-    // Eq. 12: the scale factor of an entry is that of its segment, dense index / seg_len.  One
-    // 64-bit division per span, then 32-bit ones relative to the span's first segment.
-    int64_t first_seg = 0;
-    uint32_t first_seg_off = 0;
-    if (scale) {
-        first_seg = o.dense_begin / (int64_t)seg_len;
-        first_seg_off = (uint32_t)(o.dense_begin - first_seg * (int64_t)seg_len);
+    const int cols = a.geom.cols;
+    vf4_t raw[kLoads];
+    uint32_t bits[kLoads];
+    float A[kLoads];
+    int col[kLoads];
+    uint32_t row = 0;
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
+        row = piece.row;
+        col[k] = piece.col + (int)threadIdx.x * 4;
+        raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        bits[k] = 0;
+        A[k] = 1.0f;
+        if (col[k] < cols) {
+            raw[k] = load_once(reinterpret_cast<const vf4_t *>(t.w + (int64_t)row * a.geom.ld + col[k]));
+            if (t.mask) bits[k] = load_once(t.mask + (int64_t)row * (cols >> 5) + (col[k] >> 5));
+            if (t.scale) A[k] = t.scale[(int64_t)row * a.n_segments + fast_div((uint32_t)col[k], a.div_seg_len)];      // Eq. 12
+        }
     }
-    for (int base = sub * kChunk; base < len; base += kBatch * stride) {
-        vu4_t raw[kBatch];
-        uint32_t bits[kBatch];
+    const int64_t dense_row = (int64_t)row * cols;
 #pragma unroll
-        for (int k = 0; k < kBatch; ++k) {      // past the end of the span: zeros
-            const int off = base + k * stride + lane * kLaneElems;
-            raw[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad);
-            bits[k] = mask ? __builtin_amdgcn_raw_buffer_load_b32(rmask, (off >> 5) * 4, 0, kAuxLoad) : 0u;
+    for (int k = 0; k < kLoads; ++k) {
+        const float x[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
+        uint32_t nib;
+        if (t.mask) nib = (bits[k] >> (col[k] & 31)) & 0xFu;
+        else nib = keep_nibble<M>(x, M / 2, lane);
+        float va, vb;        // the two values this lane stores
+        uint32_t word;       // the metadata word its run of lanes forms
+        if constexpr (M == 4) {
+            const uint32_t first = (uint32_t)__builtin_ctz(nib | 0x10u);      // positions of the two kept entries, ascending
+            const uint32_t rest = nib & (nib - 1u);
+            const uint32_t second = (uint32_t)__builtin_ctz(rest | 0x10u) & 3u;
+            va = first == 0 ? x[0] : (first == 1 ? x[1] : x[2]);
+            vb = second == 1 ? x[1] : (second == 2 ? x[2] : x[3]);
+            const uint32_t field = (first & 3u) | (second << 2);
+            word = or_reduce_8lanes(field << ((lane & 7) * 4));
+        } else {
+            const uint32_t ia = (nib & 1u) ? 0u : 1u, ib = (nib & 4u) ? 0u : 1u;   // which entry of each pair is kept
+            va = ia ? x[1] : x[0];
+            vb = ib ? x[3] : x[2];
+            word = or_reduce_16lanes((ia | (ib << 1)) << ((lane & 15) * 2));
         }
-#pragma unroll
-        for (int k = 0; k < kBatch; ++k) {
-            if (base + k * stride >= len) break;      // wave-uniform
-            const int off = base + k * stride + lane * kLaneElems;
-            float x[4];
-            unpack4u(raw[k], x);
-            uint32_t nib;
-            if (mask) nib = (bits[k] >> (off & 31)) & 0xFu;
-            else nib = keep_nibble<M>(x, M / 2, lane);
-            float A = 1.0f;
-            if (scale && off < len) A = scale[first_seg + fast_div(first_seg_off + (uint32_t)off, div_seg_len)];
-            float a, b;          // the two values this lane stores
-            uint32_t word;       // the metadata word its run of lanes forms
-            if constexpr (M == 4) {
-                const uint32_t first = (uint32_t)__builtin_ctz(nib | 0x10u);      // positions of the two kept entries, ascending
-                const uint32_t rest = nib & (nib - 1u);
-                const uint32_t second = (uint32_t)__builtin_ctz(rest | 0x10u) & 3u;
-                a = first == 0 ? x[0] : (first == 1 ? x[1] : x[2]);
-                b = second == 1 ? x[1] : (second == 2 ? x[2] : x[3]);
-                const uint32_t field = (first & 3u) | (second << 2);
-                word = or_reduce_8lanes(field << ((lane & 7) * 4));
-            } else if constexpr (M == 2) {
-                const uint32_t ia = (nib & 1u) ? 0u : 1u, ib = (nib & 4u) ? 0u : 1u;   // which entry of each pair is kept
-                a = ia ? x[1] : x[0];
-                b = ib ? x[3] : x[2];
-                word = or_reduce_16lanes((ia | (ib << 1)) << ((lane & 15) * 2));
-            }
-            if (scale) { a = A * a; b = A * b; }
-            if constexpr (BF16OUT) {
-                __builtin_amdgcn_raw_buffer_store_b32(f32x2_to_bf16_rne(a, b), rval, (off >> 1) * 2, 0, kAuxStore);
-            } else {
-                const vu2_t pair = {__float_as_uint(a), __float_as_uint(b)};
-                __builtin_amdgcn_raw_buffer_store_b64(pair, rval, (off >> 1) * 4, 0, kAuxStore);
-            }
-            constexpr int kLanesPerWord = kEntriesPerWord / kLaneElems;
-            if ((lane & (kLanesPerWord - 1)) == 0)
-                __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off / kEntriesPerWord) * 4, 0, kAuxStore);
+        if (col[k] >= cols) continue;      // (after the cross-lane steps, which all 64 lanes take)
+        if (t.scale) { va = A[k] * va; vb = A[k] * vb; }
+        const int64_t at = (dense_row + col[k]) >> 1;      // half of the entries are kept
+        if constexpr (BF16OUT) {
+            store_full(static_cast<uint32_t *>(t.values) + (at >> 1), f32x2_to_bf16_rne(va, vb));
+        } else {
+            store_full(reinterpret_cast<vu2_t *>(static_cast<float *>(t.values) + at), vu2_t{__float_as_uint(va), __float_as_uint(vb)});
         }
+        constexpr int kLanesPerWord = kEntriesPerWord / kLaneElems;
+        if ((lane & (kLanesPerWord - 1)) == 0) t.meta[(dense_row + col[k]) / kEntriesPerWord] = word;
     }
 }
 
 // 4:8 with a whole group per lane: 8 consecutive entries (two 16-byte loads), so the four kept values
 // are picked inside the lane (the k-th kept entry can only be one of entries k .. k + 4) and leave as
 // one 16-byte (fp32) or 8-byte (bf16) store; two adjacent lanes' 12-bit index fields form a metadata
-// word.  A wavefront takes units of 512 entries, two of them requested before the first is worked on.
-// The exchange between lane pairs that the 4-entries-per-lane form needs made it ALU-bound.
+// word.  The exchange between lane pairs that a 4-entries-per-lane form needs made it ALU-bound.
 template <bool BF16OUT>
-__global__ __launch_bounds__(kMaxBlockThreads) void project_compress_4of8_vec(
-    const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
-    const SpanGeom geom, uint32_t seg_len, FastDivU32 div_seg_len)
+__global__ __launch_bounds__(kBlockThreads) void project_compress_4of8_rows(const PackArgs a)
 {
-    constexpr int kUnit = 2 * kChunk;          // entries a wavefront handles at a time: 8 per lane
-    constexpr int kUnitsInFlight = 2;
+    const PackSet t = a.set[blockIdx.y];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int stride = geom.waves_per_span * kUnit;
-    const SpanSlot slot = span_slot(geom, blockIdx.x, wave, blockDim.x / kWave);
-    const int sub = slot.sub;
-    const SpanOrigin o = span_origin(geom, slot.span);
-    const int len = o.len;
-    const __amdgpu_buffer_rsrc_t rw = span_resource(w + o.state_begin, len * 4);
-    const __amdgpu_buffer_rsrc_t rmask = span_resource(mask ? mask + (o.dense_begin >> 5) : nullptr, mask ? len / 8 : 0);
-    const __amdgpu_buffer_rsrc_t rmeta = span_resource(meta + o.dense_begin / 16, len / 16 * 4);
-    const int vbytes = BF16OUT ? 2 : 4;
-    const __amdgpu_buffer_rsrc_t rval = span_resource(static_cast<char *>(values) + (o.dense_begin >> 1) * vbytes, (len >> 1) * vbytes);
-    int64_t first_seg = 0;
-    uint32_t first_seg_off = 0;
-    if (scale) {
-        first_seg = o.dense_begin / (int64_t)seg_len;
-        first_seg_off = (uint32_t)(o.dense_begin - first_seg * (int64_t)seg_len);
+    const int cols = a.geom.cols;
+    vf4_t lo[kLoads], hi[kLoads];
+    uint32_t bits[kLoads];
+    float A[kLoads];
+    int col[kLoads];
+    uint32_t row = 0;
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
+        row = piece.row;
+        col[k] = piece.col + (int)threadIdx.x * 8;
+        lo[k] = hi[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        bits[k] = 0;
+        A[k] = 1.0f;
+        if (col[k] < cols) {
+            const vf4_t *src = reinterpret_cast<const vf4_t *>(t.w + (int64_t)row * a.geom.ld + col[k]);
+            lo[k] = load_once(src);
+            hi[k] = load_once(src + 1);
+            if (t.mask) bits[k] = load_once(t.mask + (int64_t)row * (cols >> 5) + (col[k] >> 5));
+            if (t.scale) A[k] = t.scale[(int64_t)row * a.n_segments + fast_div((uint32_t)col[k], a.div_seg_len)];
+        }
     }
-    for (int base = sub * kUnit; base < len; base += kUnitsInFlight * stride) {
-        vu4_t lo[kUnitsInFlight], hi[kUnitsInFlight];
-        uint32_t bits[kUnitsInFlight];
+    const int64_t dense_row = (int64_t)row * cols;
 #pragma unroll
-        for (int k = 0; k < kUnitsInFlight; ++k) {      // past the end of the span: zeros
-            const int off = base + k * stride + lane * 8;
-            lo[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4, 0, kAuxLoad);
-            hi[k] = __builtin_amdgcn_raw_buffer_load_b128(rw, off * 4 + 16, 0, kAuxLoad);
-            bits[k] = mask ? __builtin_amdgcn_raw_buffer_load_b32(rmask, (off >> 5) * 4, 0, kAuxLoad) : 0u;
+    for (int k = 0; k < kLoads; ++k) {
+        const float x[8] = {lo[k].x, lo[k].y, lo[k].z, lo[k].w, hi[k].x, hi[k].y, hi[k].z, hi[k].w};
+        const uint32_t kept = t.mask ? (bits[k] >> (col[k] & 31)) & 0xFFu : keep_bits_group<8>(x, 4);
+        // positions of the four kept entries, ascending (a given mask with fewer bits: the guard bit keeps them in range)
+        const uint32_t r1 = kept & (kept - 1u), r2 = r1 & (r1 - 1u), r3 = r2 & (r2 - 1u);
+        const uint32_t p0 = (uint32_t)__builtin_ctz(kept | 0x100u) & 7u, p1 = (uint32_t)__builtin_ctz(r1 | 0x100u) & 7u;
+        const uint32_t p2 = (uint32_t)__builtin_ctz(r2 | 0x100u) & 7u, p3 = (uint32_t)__builtin_ctz(r3 | 0x100u) & 7u;
+        float v0 = p0 == 0 ? x[0] : (p0 == 1 ? x[1] : (p0 == 2 ? x[2] : (p0 == 3 ? x[3] : x[4])));
+        float v1 = p1 == 1 ? x[1] : (p1 == 2 ? x[2] : (p1 == 3 ? x[3] : (p1 == 4 ? x[4] : x[5])));
+        float v2 = p2 == 2 ? x[2] : (p2 == 3 ? x[3] : (p2 == 4 ? x[4] : (p2 == 5 ? x[5] : x[6])));
+        float v3 = p3 == 3 ? x[3] : (p3 == 4 ? x[4] : (p3 == 5 ? x[5] : (p3 == 6 ? x[6] : x[7])));
+        const uint32_t field = p0 | (p1 << 3) | (p2 << 6) | (p3 << 9);
+        const uint32_t word = field | (dpp_u32<kDppQuadXor1>(field) << 16);           // even lane: its group, then the odd lane's
+        if (col[k] >= cols) continue;
+        if (t.scale) { v0 = A[k] * v0; v1 = A[k] * v1; v2 = A[k] * v2; v3 = A[k] * v3; }
+        const int64_t at = (dense_row + col[k]) >> 1;
+        if constexpr (BF16OUT) {
+            const vu2_t h = {f32x2_to_bf16_rne(v0, v1), f32x2_to_bf16_rne(v2, v3)};
+            store_full(reinterpret_cast<vu2_t *>(static_cast<uint16_t *>(t.values) + at), h);
+        } else {
+            store_full(reinterpret_cast<vf4_t *>(static_cast<float *>(t.values) + at), vf4_t{v0, v1, v2, v3});
         }
-#pragma unroll
-        for (int k = 0; k < kUnitsInFlight; ++k) {
-            if (base + k * stride >= len) break;      // wave-uniform
-            const int off = base + k * stride + lane * 8;
-            const float x[8] = {__uint_as_float(lo[k].x), __uint_as_float(lo[k].y), __uint_as_float(lo[k].z), __uint_as_float(lo[k].w),
-                                __uint_as_float(hi[k].x), __uint_as_float(hi[k].y), __uint_as_float(hi[k].z), __uint_as_float(hi[k].w)};
-            const uint32_t kept = mask ? (bits[k] >> (off & 31)) & 0xFFu : keep_bits_group<8>(x, 4);
-            // positions of the four kept entries, ascending (a given mask with fewer bits: the guard bit keeps them in range)
-            const uint32_t r1 = kept & (kept - 1u), r2 = r1 & (r1 - 1u), r3 = r2 & (r2 - 1u);
-            const uint32_t p0 = (uint32_t)__builtin_ctz(kept | 0x100u) & 7u, p1 = (uint32_t)__builtin_ctz(r1 | 0x100u) & 7u;
-            const uint32_t p2 = (uint32_t)__builtin_ctz(r2 | 0x100u) & 7u, p3 = (uint32_t)__builtin_ctz(r3 | 0x100u) & 7u;
-            float v0 = p0 == 0 ? x[0] : (p0 == 1 ? x[1] : (p0 == 2 ? x[2] : (p0 == 3 ? x[3] : x[4])));
-            float v1 = p1 == 1 ? x[1] : (p1 == 2 ? x[2] : (p1 == 3 ? x[3] : (p1 == 4 ? x[4] : x[5])));
-            float v2 = p2 == 2 ? x[2] : (p2 == 3 ? x[3] : (p2 == 4 ? x[4] : (p2 == 5 ? x[5] : x[6])));
-            float v3 = p3 == 3 ? x[3] : (p3 == 4 ? x[4] : (p3 == 5 ? x[5] : (p3 == 6 ? x[6] : x[7])));
-            if (scale) {
-                float A = 1.0f;
-                if (off < len) A = scale[first_seg + fast_div(first_seg_off + (uint32_t)off, div_seg_len)];
-                v0 = A * v0; v1 = A * v1; v2 = A * v2; v3 = A * v3;
-            }
-            if constexpr (BF16OUT) {
-                const vu2_t h = {f32x2_to_bf16_rne(v0, v1), f32x2_to_bf16_rne(v2, v3)};
-                __builtin_amdgcn_raw_buffer_store_b64(h, rval, off, 0, kAuxStore);            // (off / 2) values of 2 bytes
-            } else {
-                const vu4_t q = {__float_as_uint(v0), __float_as_uint(v1), __float_as_uint(v2), __float_as_uint(v3)};
-                __builtin_amdgcn_raw_buffer_store_b128(q, rval, off * 2, 0, kAuxStore);       // (off / 2) values of 4 bytes
-            }
-            const uint32_t field = p0 | (p1 << 3) | (p2 << 6) | (p3 << 9);
-            const uint32_t word = field | (dpp_u32<kDppQuadXor1>(field) << 16);           // even lane: its group, then the odd lane's
-            if ((lane & 1) == 0) __builtin_amdgcn_raw_buffer_store_b32(word, rmeta, (off >> 4) * 4, 0, kAuxStore);
-        }
+        if ((lane & 1) == 0) t.meta[(dense_row + col[k]) >> 4] = word;
     }
 }
 
@@ -436,47 +525,61 @@ static void launch_pack_unit(bool bf16, unsigned grid, hipStream_t st, const flo
     else hipLaunchKernelGGL((project_compress_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments);
 }
 
-cast_status launch_project_compress(const float *w, const float *scale, int n_segments,
-                                    const uint32_t *mask_bits, int64_t rows, int64_t cols,
-                                    int64_t ld, int n_keep, int m_group, void *values,
-                                    int value_dtype, uint32_t *meta, hipStream_t st)
+cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_segments, int n_keep, int m_group,
+                                         int value_dtype, hipStream_t st)
 {
-    if (rows == 0 || cols == 0) return CAST_OK;
     const bool bf16 = value_dtype == CAST_BF16;
-    const int64_t seg_len64 = scale ? cols / n_segments : cols;
-    // the vector kernel: half-density patterns, spans and rows that are whole metadata words
-    // (32 columns for 2:4, 16 for 4:8, 64 for 1:2), scale segments that are whole groups
-    const int word_cols = m_group == 4 ? 32 : (m_group == 8 ? 16 : 64);
-    const SpanPlan p = plan_batched(rows, cols, ld, word_cols < 32 ? 32 : word_cols);
-    if (2 * n_keep == m_group && p.vec && seg_len64 % m_group == 0 && cols % word_cols == 0 && p.geom.span_len % word_cols == 0 &&
-        seg_len64 < ((int64_t)1 << 31)) {
-        const uint32_t seg_len = (uint32_t)seg_len64;
-        const FastDivU32 div_seg_len = make_fast_div(seg_len);
-        const dim3 grid(p.grid), block(p.block_threads);
-        switch (m_group) {
-        case 4:
-            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<4, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
-            else hipLaunchKernelGGL((project_compress_half_vec<4, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
-            break;
-        case 8:
-            if (bf16) hipLaunchKernelGGL(project_compress_4of8_vec<true>, grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
-            else hipLaunchKernelGGL(project_compress_4of8_vec<false>, grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
-            break;
-        default:
-            if (bf16) hipLaunchKernelGGL((project_compress_half_vec<2, true>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
-            else hipLaunchKernelGGL((project_compress_half_vec<2, false>), grid, block, 0, st, w, scale, mask_bits, values, meta, p.geom, seg_len, div_seg_len);
-            break;
+    std::vector<char> taken((size_t)count, 0);
+    auto alike = [](const cast_matrix &x, const cast_matrix &y) { return (x.scale == nullptr) == (y.scale == nullptr) && (x.mask_bits == nullptr) == (y.mask_bits == nullptr); };
+    for (int i = 0; i < count; ++i) {
+        if (taken[i] || m[i].rows == 0 || m[i].cols == 0) continue;
+        int group[kMaxListed];
+        const int n = take_group(m, count, taken, i, alike, group);
+        const cast_matrix &t0 = m[i];
+        const int segs = t0.scale ? n_segments : 0;
+        const int64_t seg_len = segs ? t0.cols / segs : t0.cols;
+        // the vector kernels: half-density patterns, rows that are whole mask words and whole metadata words
+        // (32 columns for 2:4, 16 for 4:8, 64 for 1:2), scale segments that are whole groups (so a lane's
+        // entries share one factor)
+        const int word_cols = m_group == 4 ? 32 : (m_group == 8 ? 16 : 64);
+        const RowsPlan p = plan_rows(t0.rows, t0.cols, t0.ld, m_group == 8 ? 8 : 4);
+        if (2 * n_keep == m_group && p.vec && t0.cols % word_cols == 0 && seg_len % m_group == 0) {
+            PackArgs a{{}, p.geom, make_fast_div((uint32_t)seg_len), segs};
+            for (int k = 0; k < n; ++k) {
+                const cast_matrix &t = m[group[k]];
+                a.set[k] = PackSet{t.w, t.scale, t.mask_bits, t.out, t.meta};
+            }
+            const dim3 grid(p.grid, (unsigned)n), block(kBlockThreads);
+            switch (m_group) {
+            case 4:
+                if (bf16) hipLaunchKernelGGL((project_compress_half_rows<4, true>), grid, block, 0, st, a);
+                else hipLaunchKernelGGL((project_compress_half_rows<4, false>), grid, block, 0, st, a);
+                break;
+            case 8:
+                if (bf16) hipLaunchKernelGGL(project_compress_4of8_rows<true>, grid, block, 0, st, a);
+                else hipLaunchKernelGGL(project_compress_4of8_rows<false>, grid, block, 0, st, a);
+                break;
+            default:
+                if (bf16) hipLaunchKernelGGL((project_compress_half_rows<2, true>), grid, block, 0, st, a);
+                else hipLaunchKernelGGL((project_compress_half_rows<2, false>), grid, block, 0, st, a);
+                break;
+            }
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+            continue;
         }
-        return launch_status();
+        for (int k = 0; k < n; ++k) {
+            const cast_matrix &t = m[group[k]];
+            const int64_t units = t.rows * ((t.cols + 63) / 64);
+            const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
+            switch (m_group) {
+            case 2: launch_pack_unit<2>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs); break;
+            case 4: launch_pack_unit<4>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs); break;
+            default: launch_pack_unit<8>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs); break;
+            }
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+        }
     }
-    const int64_t units = rows * ((cols + 63) / 64);
-    const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
-    switch (m_group) {
-    case 2: launch_pack_unit<2>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, ld, n_keep, n_segments); break;
-    case 4: launch_pack_unit<4>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, ld, n_keep, n_segments); break;
-    default: launch_pack_unit<8>(bf16, grid, st, w, scale, mask_bits, values, meta, rows, cols, ld, n_keep, n_segments); break;
-    }
-    return launch_status();
+    return CAST_OK;
 }
 
 // ---- appendix "Mask Learning" ---------------------------------------------------------------
@@ -550,10 +653,9 @@ __global__ __launch_bounds__(kMaxBlockThreads) void mask_stats_vec(
             if (t < n_words) {
                 const uint32_t r = fast_div((uint32_t)t, div_words_per_row);
                 const uint32_t word_in_row = (uint32_t)t - r * words_per_row;
-                word[k] = __builtin_nontemporal_load(mask + t);
-                if (other) diff[k] = __builtin_nontemporal_load(other + t);
-                x[k] = __builtin_nontemporal_load(
-                    reinterpret_cast<const vf4_t *>(w + (int64_t)r * ld + (int64_t)word_in_row * 32 + part * 4));
+                word[k] = load_once(mask + t);
+                if (other) diff[k] = load_once(other + t);
+                x[k] = load_once(reinterpret_cast<const vf4_t *>(w + (int64_t)r * ld + (int64_t)word_in_row * 32 + part * 4));
             }
         }
 #pragma unroll

@@ -1,0 +1,123 @@
+"""The list forms of the once-per-run entry points (cast_nm_select_multi, cast_weight_scale_multi,
+cast_nm_project_compress_multi): matrices of one shape share launches (blockIdx.y picks the matrix), other shapes
+and the scalar kernels run in between; every output against the oracle, bit for bit (Eq. 6, Eq. 12, the last loop
+of Algorithm 1 and the packed layout)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2509_25996_amd import binding as B
+from paper_2509_25996_amd import synth
+
+from gpu_util import DEV, assert_same_bits, dev, host, words
+
+pytestmark = pytest.mark.gpu
+
+# runs of equal shapes (shared launches, more than 16 of one shape: two launches), rows that end inside a workgroup's
+# reach (2048 entries), rows shorter than one wavefront's, shapes for the scalar kernels (72, 40 columns), empty ones
+SHAPES = [(64, 512)] * 3 + [(5, 72), (33, 4096 + 32), (64, 512), (0, 64), (7, 2048), (9, 11008), (3, 40), (7, 2048)] + [(16, 256)] * 19 + \
+         [(2, 8192 + 64), (4, 64), (5, 72)]
+
+
+def _state(shapes, seed, interleave_some=True):
+    out = []
+    for i, (r, c) in enumerate(shapes):
+        w0 = synth.tie_outlier_weights(seed, i, r, c) if c % 8 == 0 and r else synth.weights(seed, i, r, c)
+        if interleave_some and i % 3 == 1 and r and c % 8 == 0:
+            w, _, _ = B.interleaved_state(dev(w0))
+        else:
+            w = dev(w0)
+        out.append((w0, w))
+    return out
+
+
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2), (1, 4), (3, 4), (5, 8)])
+def test_select_list_matches_the_oracle(n, m):
+    state = _state(SHAPES, 61)
+    masks = [B.alloc_mask(r, c, DEV) for r, c in SHAPES]
+    for mk in masks:
+        mk.fill_(-1)
+    B.cast_nm_select_multi(B.MatrixList([dict(w=w, mask=mk) for (_, w), mk in zip(state, masks)]), n, m)
+    torch.cuda.synchronize()
+    for (w0, _), mk, shape in zip(state, masks, SHAPES):
+        if w0.size:
+            assert (words(mk) == oracle.pack_mask_bits(oracle.nm_select(w0, n, m))).all(), shape
+
+
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nseg", [1, 2, 4])
+def test_weight_scale_list_matches_the_oracle(nseg, out_dtype):
+    shapes = [s for s in SHAPES if s[1] % nseg == 0]
+    state = _state(shapes, 62)
+    rng = np.random.default_rng(5)
+    A = [(1 + 0.3 * rng.standard_normal((r, nseg))).astype(np.float32) for r, _ in shapes]
+    outs = [torch.full((r, c), 3.0, dtype=out_dtype, device=DEV) for r, c in shapes]
+    B.cast_weight_scale_multi(B.MatrixList([dict(w=w, scale=dev(a), out=o) for (_, w), a, o in zip(state, A, outs)]))
+    torch.cuda.synchronize()
+    for (w0, _), a, o, shape in zip(state, A, outs, shapes):
+        if not w0.size:
+            continue
+        ref = oracle.weight_scale(w0, a)
+        if out_dtype == torch.float32:
+            assert_same_bits(host(o), ref, str(shape))
+        else:
+            assert (host(o.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref)).all(), shape
+
+
+@pytest.mark.parametrize("value_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2), (3, 8)])
+@pytest.mark.parametrize("given_mask", [False, True])
+def test_project_compress_list_matches_the_oracle(n, m, given_mask, value_dtype):
+    nseg = 2
+    shapes = [s for s in SHAPES if (s[1] // nseg) % m == 0]
+    state = _state(shapes, 63)
+    rng = np.random.default_rng(6)
+    items, refs = [], []
+    for i, ((w0, w), (r, c)) in enumerate(zip(state, shapes)):
+        scaled = i % 4 != 2      # some matrices without a scale: they cannot share a launch with the scaled ones
+        a = (1 + 0.3 * rng.standard_normal((r, nseg))).astype(np.float32) if scaled else None
+        keep = None
+        if given_mask and r:      # a stored mask that is NOT the projection of w: the weights of another draw decide
+            keep = oracle.nm_select(synth.weights(64, i, r, c), n, m)
+        _, vbytes, mbytes = B.cast_sizes(r, c, n, m, B.CAST_F32)
+        values = torch.full((r, c // m * n), 5.0, dtype=value_dtype, device=DEV)
+        meta = torch.full((r, (mbytes // 4 // r) if r else 0), -1, dtype=torch.int32, device=DEV)
+        items.append(dict(w=w, scale=None if a is None else dev(a), out=values, meta=meta,
+                          mask=None if keep is None else dev(oracle.pack_mask_bits(keep).view(np.int32))))
+        refs.append((w0, a, keep))
+    B.cast_nm_project_compress_multi(B.MatrixList(items), n, m)
+    torch.cuda.synchronize()
+    for x, (w0, a, keep), shape in zip(items, refs, shapes):
+        if not w0.size:
+            continue
+        ref_v, ref_m = oracle.project_compress(w0, n, m, A=a, keep=keep)
+        assert (words(x["meta"]) == ref_m).all(), shape
+        if value_dtype == torch.float32:
+            assert_same_bits(host(x["out"]), ref_v, str(shape))
+        else:
+            assert (host(x["out"].view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref_v)).all(), shape
+
+
+def test_whole_7b_layer_through_the_list_calls():
+    """One LLaMA2-7B-shaped layer (row-interleaved weights, n = 2): q, k, v, o share launches; selection, Eq. 12 into
+    bf16 and the 2:4 pack with the fold, every entry against the oracle."""
+    shapes = synth.weight_set("llama2_7b", 1)
+    n = 2
+    items, refs = [], []
+    for i, (_, r, c) in enumerate(shapes):
+        w, _, _ = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, 900 + i, DEV))
+        A = (1 + 0.05 * torch.randn((r, n), device=DEV, generator=torch.Generator(DEV).manual_seed(i))).contiguous()
+        items.append(dict(w=w, scale=A, mask=B.alloc_mask(r, c, DEV), out16=torch.empty((r, c), dtype=torch.bfloat16, device=DEV),
+                          values=torch.empty((r, c // 2), device=DEV), meta=torch.empty((r, c // 32), dtype=torch.int32, device=DEV)))
+        refs.append((host(w).copy(), host(A).copy()))
+    B.cast_nm_select_multi(B.MatrixList([dict(w=x["w"], mask=x["mask"]) for x in items]), 2, 4)
+    B.cast_weight_scale_multi(B.MatrixList([dict(w=x["w"], scale=x["scale"], out=x["out16"]) for x in items]))
+    B.cast_nm_project_compress_multi(B.MatrixList([dict(w=x["w"], scale=x["scale"], out=x["values"], meta=x["meta"]) for x in items]), 2, 4)
+    torch.cuda.synchronize()
+    for (name, r, c), x, (w0, a) in zip(shapes, items, refs):
+        assert (words(x["mask"]) == oracle.pack_mask_bits(oracle.nm_select(w0, 2, 4))).all(), name
+        assert (host(x["out16"].view(torch.int16)).view(np.uint16) == oracle.bf16_rne(oracle.weight_scale(w0, a))).all(), name
+        ref_v, ref_m = oracle.project_compress(w0, 2, 4, A=a)
+        assert (words(x["meta"]) == ref_m).all(), name
+        assert_same_bits(host(x["values"]), ref_v, name)
