@@ -151,6 +151,10 @@ typedef struct {
                            /*             weight_scale: unused                                                  */
     void *out;             /* DEVICE out  weight_scale: out; project_compress: values; select: unused           */
     uint32_t *meta;        /* DEVICE out  project_compress only                                                 */
+    uint32_t *mask_status; /* DEVICE i/o  project_compress with a stored mask only, or NULL: the number of groups     */
+                           /*             whose stored bits are not exactly N ones is ADDED to this word (clear it   */
+                           /*             before the call; 0 afterwards = the mask is a valid N:M mask).  Such        */
+                           /*             groups are still packed, with meaningless values and positions.            */
 } cast_matrix;
 
 /* cast_nm_select over a list (validated as a whole before anything is launched). */
@@ -324,7 +328,8 @@ cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int 
  *
  *   mask_bits == NULL: the mask is Eq. 6 on w (projection onto the N:M set);
  *   mask_bits != NULL: the stored mask is applied as is (Algorithm 1 literally); it must hold
- *                      exactly N ones per group, which is NOT checked on the device.
+ *                      exactly N ones per group.  This call does not check that; the list call
+ *                      cast_nm_project_compress_multi does when given a mask_status word.
  *   values  DEVICE out [rows, cols*N/M] of value_dtype: for each group its kept entries in
  *           ascending column order, each multiplied by scale[r, s] if scale != NULL (one fp32
  *           multiply; bf16 = round to nearest even of that; any NaN becomes 0x7FC0).

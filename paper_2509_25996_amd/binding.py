@@ -42,7 +42,7 @@ class _Tensor(C.Structure):
 
 class _Matrix(C.Structure):
     _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64), ("scale", C.c_void_p),
-                ("mask_bits", C.c_void_p), ("out", C.c_void_p), ("meta", C.c_void_p)]
+                ("mask_bits", C.c_void_p), ("out", C.c_void_p), ("meta", C.c_void_p), ("mask_status", C.c_void_p)]
 
 
 class _Config(C.Structure):
@@ -224,7 +224,8 @@ def cast_nm_select(w: torch.Tensor, n_keep: int, m_group: int, mask_bits: torch.
 class MatrixList:
     """Descriptors of a list of matrices for the once-per-run list calls (cast_nm_select_multi,
     cast_weight_scale_multi, cast_nm_project_compress_multi), marshalled once.  Each item is a dict with w and,
-    as the call needs them, scale, mask, out (the scaled weights or the packed values), meta (tensors)."""
+    as the call needs them, scale, mask, out (the scaled weights or the packed values), meta, mask_status (an int32
+    tensor of one word that counts the invalid groups of a stored mask) (tensors)."""
 
     def __init__(self, items):
         self.items = list(items)     # keeps the tensors alive
@@ -235,8 +236,8 @@ class MatrixList:
         segments = set()
         for k, x in enumerate(self.items):
             w = x["w"]
-            sc, mk, out, meta = x.get("scale"), x.get("mask"), x.get("out"), x.get("meta")
-            _dev(sc, mk, out, meta)
+            sc, mk, out, meta, status = x.get("scale"), x.get("mask"), x.get("out"), x.get("meta"), x.get("mask_status")
+            _dev(sc, mk, out, meta, status)
             if out is not None:
                 dt = _dtype_code(out)
                 if self.out_dtype not in (None, dt):
@@ -246,7 +247,7 @@ class MatrixList:
                 segments.add(sc.shape[1])
             self.array[k] = _Matrix(w.data_ptr(), w.shape[0], w.shape[1], _ld(w), None if sc is None else sc.data_ptr(),
                                     None if mk is None else mk.data_ptr(), None if out is None else out.data_ptr(),
-                                    None if meta is None else meta.data_ptr())
+                                    None if meta is None else meta.data_ptr(), None if status is None else status.data_ptr())
         if len(segments) > 1:
             raise ValueError("all matrices of a list must have the same number of scaling segments")
         self.segments = segments.pop() if segments else 0

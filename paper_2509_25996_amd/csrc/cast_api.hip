@@ -108,7 +108,7 @@ cast_status cast_nm_select_multi(const cast_matrix *matrices, int count, int n_k
 cast_status cast_nm_select(const float *w, int64_t rows, int64_t cols, int64_t ld, int n_keep,
                            int m_group, uint32_t *mask_bits, void *stream)
 {
-    const cast_matrix t{w, rows, cols, ld, nullptr, mask_bits, nullptr, nullptr};
+    const cast_matrix t{w, rows, cols, ld, nullptr, mask_bits, nullptr, nullptr, nullptr};
     return cast_nm_select_multi(&t, 1, n_keep, m_group, stream);
 }
 
@@ -270,7 +270,7 @@ cast_status cast_weight_scale_multi(const cast_matrix *matrices, int count, int 
 cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, int64_t cols,
                               int64_t ld, int n_segments, void *out, int out_dtype, void *stream)
 {
-    const cast_matrix t{w, rows, cols, ld, scale, nullptr, out, nullptr};
+    const cast_matrix t{w, rows, cols, ld, scale, nullptr, out, nullptr, nullptr};
     return cast_weight_scale_multi(&t, 1, n_segments, out_dtype, stream);
 }
 
@@ -302,7 +302,8 @@ static cast_status validate_pack(const cast_matrix &t, int n_segments, int n_kee
     }
     if (t.rows == 0 || t.cols == 0) return CAST_OK;
     if (!t.w || !t.out || !t.meta) return CAST_ERR_NULL;
-    if (!aligned(t.w, 16) || !aligned(t.out, 8) || !aligned(t.meta, 4) || !aligned(t.mask_bits, 4) || !aligned(t.scale, 4))
+    if (!aligned(t.w, 16) || !aligned(t.out, 8) || !aligned(t.meta, 4) || !aligned(t.mask_bits, 4) || !aligned(t.scale, 4) ||
+        !aligned(t.mask_status, 4))
         return CAST_ERR_ALIGN;
     return CAST_OK;
 }
@@ -325,7 +326,7 @@ cast_status cast_nm_project_compress(const float *w, const float *scale, int n_s
                                      int64_t ld, int n_keep, int m_group, void *values,
                                      int value_dtype, uint32_t *meta, void *stream)
 {
-    const cast_matrix t{w, rows, cols, ld, scale, const_cast<uint32_t *>(mask_bits), values, meta};
+    const cast_matrix t{w, rows, cols, ld, scale, const_cast<uint32_t *>(mask_bits), values, meta, nullptr};
     return cast_nm_project_compress_multi(&t, 1, n_segments, n_keep, m_group, value_dtype, stream);
 }
 

@@ -327,7 +327,16 @@ struct PackSet {
     const uint32_t *mask;     // or NULL: Eq. 6 on w
     void *values;
     uint32_t *meta;
+    uint32_t *status;         // or NULL: where the number of stored-mask groups without exactly N ones is added
 };
+
+// Adds the wavefront's count of invalid groups to *status with one atomic, and only if there are any: a valid
+// mask costs no atomics at all.
+__device__ __forceinline__ void report_bad_groups(uint32_t *status, uint32_t bad_in_lane)
+{
+    const uint32_t total = wave_sum_u32(bad_in_lane);
+    if (total != 0 && (threadIdx.x & (kWave - 1)) == 0) atomicAdd(status, total);
+}
 
 struct PackArgs {
     PackSet set[kMaxListed];
@@ -391,6 +400,11 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_half_rows(cons
             vb = ib ? x[3] : x[2];
             word = or_reduce_16lanes((ia | (ib << 1)) << ((lane & 15) * 2));
         }
+        if (t.mask && t.status) {      // uniform over the workgroup
+            uint32_t bad = 0;
+            if (col[k] < cols) bad = M == 4 ? (uint32_t)(__popc(nib) != 2) : (uint32_t)(__popc(nib & 3u) != 1) + (uint32_t)(__popc(nib >> 2) != 1);
+            report_bad_groups(t.status, bad);
+        }
         if (col[k] >= cols) continue;      // (after the cross-lane steps, which all 64 lanes take)
         if (t.scale) { va = A[k] * va; vb = A[k] * vb; }
         const int64_t at = (dense_row + col[k]) >> 1;      // half of the entries are kept
@@ -450,6 +464,7 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_4of8_rows(cons
         float v3 = p3 == 3 ? x[3] : (p3 == 4 ? x[4] : (p3 == 5 ? x[5] : (p3 == 6 ? x[6] : x[7])));
         const uint32_t field = p0 | (p1 << 3) | (p2 << 6) | (p3 << 9);
         const uint32_t word = field | (dpp_u32<kDppQuadXor1>(field) << 16);           // even lane: its group, then the odd lane's
+        if (t.mask && t.status) report_bad_groups(t.status, (uint32_t)(col[k] < cols && __popc(kept) != 4));
         if (col[k] >= cols) continue;
         if (t.scale) { v0 = A[k] * v0; v1 = A[k] * v1; v2 = A[k] * v2; v3 = A[k] * v3; }
         const int64_t at = (dense_row + col[k]) >> 1;
@@ -468,7 +483,7 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_4of8_rows(cons
 template <int M, bool BF16OUT>
 __global__ __launch_bounds__(kBlockThreads) void project_compress_unit(
     const float *w, const float *scale, const uint32_t *mask, void *values, uint32_t *meta,
-    int64_t rows, int64_t cols, int64_t ld, int n_keep, int n_segments)
+    int64_t rows, int64_t cols, int64_t ld, int n_keep, int n_segments, uint32_t *status)
 {
     constexpr int B = M == 2 ? 1 : (M == 4 ? 2 : 3);
     int f = 1;
@@ -483,7 +498,7 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_unit(
     const int64_t mask_wpr = (cols + 31) / 32;
     const int64_t meta_wpr = (groups + groups_per_word - 1) / groups_per_word;
     const int64_t seg_len = n_segments > 0 ? cols / n_segments : cols;
-    uint32_t word = 0;
+    uint32_t word = 0, bad = 0;
     for (int64_t c = c0; c < ce; c += M) {
         const int64_t gi = c / M;
         float x[M];
@@ -492,6 +507,7 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_unit(
         uint32_t bits;
         if (mask) bits = (mask[r * mask_wpr + c / 32] >> (unsigned)(c % 32)) & ((1u << M) - 1u);
         else bits = keep_bits_group<M>(x, n_keep);
+        if (mask && status && (int)__popc(bits) != n_keep) ++bad;
         const float A = scale ? scale[r * n_segments + c / seg_len] : 1.0f;
         uint32_t field = 0;
         int q = 0;
@@ -514,15 +530,16 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_unit(
             word = 0;
         }
     }
+    if (bad != 0) atomicAdd(status, bad);      // invalid stored masks only
 }
 
 template <int M>
 static void launch_pack_unit(bool bf16, unsigned grid, hipStream_t st, const float *w, const float *scale,
                              const uint32_t *mask, void *values, uint32_t *meta, int64_t rows,
-                             int64_t cols, int64_t ld, int n_keep, int n_segments)
+                             int64_t cols, int64_t ld, int n_keep, int n_segments, uint32_t *status)
 {
-    if (bf16) hipLaunchKernelGGL((project_compress_unit<M, true>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments);
-    else hipLaunchKernelGGL((project_compress_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments);
+    if (bf16) hipLaunchKernelGGL((project_compress_unit<M, true>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments, status);
+    else hipLaunchKernelGGL((project_compress_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments, status);
 }
 
 cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_segments, int n_keep, int m_group,
@@ -547,7 +564,7 @@ cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_
             PackArgs a{{}, p.geom, make_fast_div((uint32_t)seg_len), segs};
             for (int k = 0; k < n; ++k) {
                 const cast_matrix &t = m[group[k]];
-                a.set[k] = PackSet{t.w, t.scale, t.mask_bits, t.out, t.meta};
+                a.set[k] = PackSet{t.w, t.scale, t.mask_bits, t.out, t.meta, t.mask_bits ? t.mask_status : nullptr};
             }
             const dim3 grid(p.grid, (unsigned)n), block(kBlockThreads);
             switch (m_group) {
@@ -572,9 +589,9 @@ cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_
             const int64_t units = t.rows * ((t.cols + 63) / 64);
             const unsigned grid = (unsigned)((units + kBlockThreads - 1) / kBlockThreads);
             switch (m_group) {
-            case 2: launch_pack_unit<2>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs); break;
-            case 4: launch_pack_unit<4>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs); break;
-            default: launch_pack_unit<8>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs); break;
+            case 2: launch_pack_unit<2>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs, t.mask_bits ? t.mask_status : nullptr); break;
+            case 4: launch_pack_unit<4>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs, t.mask_bits ? t.mask_status : nullptr); break;
+            default: launch_pack_unit<8>(bf16, grid, st, t.w, t.scale, t.mask_bits, t.out, t.meta, t.rows, t.cols, t.ld, n_keep, segs, t.mask_bits ? t.mask_status : nullptr); break;
             }
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
         }

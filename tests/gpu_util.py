@@ -5,6 +5,7 @@ import numpy as np
 import torch
 
 import oracle
+from fp32_bound import Fp32Drift
 from paper_2509_25996_amd import binding as B
 
 DEV = "cuda:0"
@@ -90,10 +91,15 @@ class OracleState:
         self.arith = arithmetic
         # running maximum magnitude of every entry: the scale rounding errors are measured against
         self.scale = [np.abs(w).astype(np.float64), np.zeros(w.shape), np.zeros(w.shape)]
+        # the double run also carries the derived bound on how far an fp32 run may have drifted from it (unscaled steps)
+        self.drift = Fp32Drift(w.shape) if arithmetic == "f64" else None
 
     def step(self, grad_f32: np.ndarray, cfg: oracle.AdamsCfg, A=None, nthreads=8):
+        entering = [x.copy() for x in (self.w, self.m, self.v)] if self.drift is not None and A is None else None
         gA = oracle.adams_step(self.w, grad_f32, self.m, self.v, self.keep, cfg, A=A, arithmetic=self.arith,
                                nthreads=nthreads)
+        if entering is not None:
+            self.drift.advance(*entering, grad_f32, self.keep, **self.drift.scalars(cfg))
         for i, x in enumerate((self.w, self.m, self.v)):
             np.maximum(self.scale[i], np.abs(x), out=self.scale[i])
         return gA

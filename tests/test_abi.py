@@ -230,6 +230,23 @@ def test_iteration_config_reading():
     assert B.iteration_config(30, 100).refresh_mask == 1
 
 
+def test_iteration_config_is_the_oracles_schedule_bit_for_bit():
+    # the binding's helper and the oracle's pinned iteration_scalars are written independently; the GPU tests hand
+    # the binding's numbers to both sides, so a wrong exponent or ramp in the helper would pass them all: here the
+    # two are compared as the fp32 values the library receives, for every iteration of short and long schedules
+    import numpy as np
+
+    import oracle
+    for total, b1, b2, period in ((10, 0.9, 0.999, 10), (100, 0.9, 0.999, 10), (7500, 0.9, 0.95, 7), (1, 0.5, 0.75, 1)):
+        for t in range(total):
+            cfg = B.iteration_config(t, total, mask_period=period, beta1=b1, beta2=b2).c_struct()
+            alpha, bc1, bc2 = oracle.iteration_scalars(t, total, b1, b2)
+            got = np.array([cfg.alpha, cfg.bias_corr1, cfg.bias_corr2], np.float32)
+            want = np.array([alpha, bc1, bc2], np.float32)
+            assert (got.view(np.uint32) == want.view(np.uint32)).all(), (total, t)
+            assert cfg.refresh_mask == int(t % period == 0)
+
+
 def test_division_by_a_common_divisor_is_the_ieee_quotient(lib):
     # the kernels divide by the two bias corrections with a short FMA sequence; on the host the same
     # routine must reproduce the correctly rounded quotient for every mantissa, inside and outside its fast range

@@ -121,3 +121,38 @@ def test_whole_7b_layer_through_the_list_calls():
         ref_v, ref_m = oracle.project_compress(w0, 2, 4, A=a)
         assert (words(x["meta"]) == ref_m).all(), name
         assert_same_bits(host(x["values"]), ref_v, name)
+
+
+@pytest.mark.parametrize("n,m,rows,cols", [(2, 4, 33, 4096 + 32), (4, 8, 9, 11008), (1, 2, 7, 2048), (3, 8, 5, 72), (2, 4, 5, 72)])
+def test_stored_masks_are_checked_when_a_status_word_is_given(n, m, rows, cols):
+    """A stored mask must hold exactly N ones per group (Eq. 4); the oracle refuses one that does not.  The list call
+    counts such groups into the caller's status word: zero for a valid mask, the exact number for a damaged one."""
+    w0 = synth.weights(71, 0, rows, cols)
+    keep = oracle.nm_select(w0, n, m)
+    rng = np.random.default_rng(rows + cols)
+    damaged = keep.copy()
+    groups = damaged.reshape(rows, cols // m, m)
+    hit = rng.random((rows, cols // m)) < 0.03
+    hit[0, 0] = hit[-1, -1] = True
+    for r, g in zip(*np.nonzero(hit)):      # one more or one fewer bit, or none at all
+        kind = rng.integers(0, 3)
+        if kind == 0:
+            groups[r, g, np.flatnonzero(groups[r, g] == 0)[0]] = 1
+        elif kind == 1:
+            groups[r, g, np.flatnonzero(groups[r, g] == 1)[0]] = 0
+        else:
+            groups[r, g, :] = 0
+    with pytest.raises(ValueError):
+        oracle.project_compress(w0, n, m, keep=damaged)
+    _, _, mbytes = B.cast_sizes(rows, cols, n, m, B.CAST_F32)
+    for mask, want in ((keep, 0), (damaged, int(hit.sum()))):
+        status = torch.zeros(1, dtype=torch.int32, device=DEV)
+        item = dict(w=dev(w0), out=torch.empty((rows, cols // m * n), device=DEV), meta=torch.empty((rows, mbytes // 4 // rows), dtype=torch.int32, device=DEV),
+                    mask=dev(oracle.pack_mask_bits(mask).view(np.int32)), mask_status=status)
+        B.cast_nm_project_compress_multi(B.MatrixList([item]), n, m)
+        torch.cuda.synchronize()
+        assert int(status.item()) == want
+        if want == 0:
+            ref_v, ref_m = oracle.project_compress(w0, n, m, keep=keep)
+            assert (words(item["meta"]) == ref_m).all()
+            assert_same_bits(host(item["out"]), ref_v, "values")

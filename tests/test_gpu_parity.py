@@ -80,7 +80,7 @@ def _run_both(w0, grads, cfgs, arith, scales=None, bf16=False, interleaved=False
     return g, o, gAs
 
 
-def _check_state(g, o, exact, w_cancels=False, lr=1e-4):
+def _check_state(g, o, exact, stated_tolerance=True):
     assert (words(g.mask) == oracle.pack_mask_bits(o.keep)).all(), "mask bits"
     for name, got, ref, sc in (("w", host(g.w), o.w, o.scale[0]), ("mu", host(g.m), o.m, o.scale[1]),
                                ("v", host(g.v), o.v, o.scale[2])):
@@ -88,13 +88,12 @@ def _check_state(g, o, exact, w_cancels=False, lr=1e-4):
             assert max_rel_err(got, ref) <= 1e-6, name      # the stated bar ...
             assert_same_bits(got, ref, name)                 # ... and what is actually observed
         else:
+            # against double arithmetic: every entry within the bound derived from the roundings of Eq. 7-8
+            # (tests/fp32_bound.py), and, at the paper's lambda, within the stated 1e-6 of its running maximum
             err = np.abs(got.astype(np.float64) - ref)
-            if name == "w" and w_cancels:
-                # lambda of the gradients' order: the decayed momentum often cancels to rounding noise while
-                # v is still tiny, and mu^/sqrt(v^) turns that noise into a weight change of up to a few lr.
-                # Any fp32 arithmetic differs from double there, so only the bulk is held to 1e-6.
-                assert (err > 1e-6 * sc).mean() <= 1e-3 and err.max() <= 10 * lr
-            else:
+            bound = {"w": o.drift.E_w, "mu": o.drift.E_mu, "v": o.drift.E_v}[name]
+            assert (err <= bound).all(), (name, float((err / np.maximum(bound, 1e-300)).max()))
+            if stated_tolerance:
                 assert (err <= 1e-6 * sc).all(), (name, float((err / np.maximum(sc, 1e-300)).max()))
 
 
@@ -109,7 +108,7 @@ def test_config1_768x768_ten_steps_then_pack(lam, period):
     g, o, _ = _run_both(w0, grads, cfgs, "f32")
     _check_state(g, o, exact=True)
     g64, o64, _ = _run_both(w0, grads, cfgs, "f64")
-    _check_state(g64, o64, exact=False, w_cancels=lam > 1e-4)
+    _check_state(g64, o64, exact=False, stated_tolerance=lam < 1e-4)
     # final hard N:M projection of the trained weights, packed
     for vdtype, code in ((torch.float32, B.CAST_F32), (torch.bfloat16, B.CAST_BF16)):
         _, vbytes, mbytes = B.cast_sizes(rows, cols, 2, 4, code)

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+from fp32_bound import Fp32Drift
 from oracle import AdamsCfg, iteration_scalars
 
 B1, B2, EPS = 0.9, 0.999, 1e-8
@@ -211,39 +212,40 @@ def test_matrix_step_agrees_with_elementwise_double_state(oracle, arith):
     assert (err <= 2e-7 * (np.abs(mu).ravel() + np.abs(g).ravel())).all()
 
 
-@pytest.mark.parametrize("lam,w_cancels", [(2e-6, False), (1e-3, True)])
-def test_fp32_arithmetic_stays_within_1e6_of_double_over_10_steps(oracle, lam, w_cancels):
-    # The tolerance the GPU parity tests use, derived here: fp32-per-operation vs double arithmetic on
-    # the same fp32 storage.  Every fp32 operation errs by at most 2^-24 of its result, and results are
-    # bounded by the operands, so the error of a state entry is a small multiple of 2^-24 times the
-    # largest magnitude that entry has had, NOT of its current value: a masked weight driven through
-    # zero, or a momentum that cancels, keeps the absolute error of its earlier, larger self.  "Relative
-    # error" is therefore measured against each entry's running maximum magnitude.
-    # With lambda at the paper's value (Table 11, 2e-6) that error stays under 1e-6.  With lambda of the
-    # gradients' own order (1e-3, used to force mask flips) the decayed momentum (1-alpha)*mu + alpha*lambda*Sign
-    # often cancels; a cancelled mu~ feeds a tiny v, and mu^/sqrt(v^) then amplifies the rounding of the
-    # cancellation into the weight, in the worst case by a few lr, for any fp32 implementation: there only the
-    # bulk of the weights is held to 1e-6.
+@pytest.mark.parametrize("lr", [1e-4, 1e-2])
+@pytest.mark.parametrize("lam", [2e-6, 1e-3])
+def test_fp32_arithmetic_stays_within_its_derived_bound_of_double_over_10_steps(oracle, lam, lr):
+    # fp32-per-operation against double arithmetic on the same fp32 storage: after every iteration every entry of
+    # w, mu, v lies within the bound that tests/fp32_bound.py derives from the roundings of Eq. 7-8, operation by
+    # operation, entry by entry (including the entries whose decayed momentum cancels while v is still small,
+    # where mu^/sqrt(v^) turns rounding noise into up to 2*sqrt(bc2/(1-beta2))/bc1 steps of size lr).
+    # Besides that the tolerance the workload states (1e-6 after 10 steps) is asserted at the paper's lambda
+    # (Table 11), measured against each entry's running maximum magnitude: a masked weight driven through zero,
+    # or a momentum that cancels, keeps the absolute error of its earlier, larger self, so a relative error
+    # against the current value is unbounded for any fp32 implementation.
     rng = np.random.default_rng(7)
     rows, cols, steps = 32, 256, 10
     w = (rng.standard_normal((rows, cols)) * 0.02).astype(np.float32)
     st = {a: (w.copy(), np.zeros_like(w), np.zeros_like(w), np.zeros(w.shape, np.uint8)) for a in ("f64", "f32")}
     scale = [np.abs(w).astype(np.float64), np.zeros(w.shape), np.zeros(w.shape)]
+    drift = Fp32Drift(w.shape)
     for t in range(steps):
         g = (rng.standard_normal((rows, cols)) * 1e-3).astype(np.float32)
         alpha, bc1, bc2 = iteration_scalars(t, steps, B1, B2)
-        cfg = AdamsCfg(lr=1e-4, lambda_=lam, alpha=alpha, bias_corr1=bc1, bias_corr2=bc2, refresh_mask=int(t == 0))
+        cfg = AdamsCfg(lr=lr, lambda_=lam, alpha=alpha, bias_corr1=bc1, bias_corr2=bc2, refresh_mask=int(t % 5 == 0))
+        entering = [x.copy() for x in st["f64"][:3]]
         for a in st:
             wa, ma, va, ka = st[a]
             oracle.adams_step(wa, g, ma, va, ka, cfg, arithmetic=a)
-        for i in range(3):
+        assert (st["f64"][3] == st["f32"][3]).all()
+        drift.advance(*entering, g, st["f64"][3], **drift.scalars(cfg))
+        for i, bound in enumerate((drift.E_w, drift.E_mu, drift.E_v)):
+            err = np.abs(st["f32"][i].astype(np.float64) - st["f64"][i])
+            assert (err <= bound).all(), (t, i, float((err / np.maximum(bound, 1e-300)).max()))
             scale[i] = np.maximum(scale[i], np.abs(st["f64"][i]))
-    assert (st["f64"][3] == st["f32"][3]).all()
-    for i in range(3):
-        err = np.abs(st["f32"][i].astype(np.float64) - st["f64"][i])
-        if i == 0 and w_cancels:
-            assert (err > 1e-6 * scale[i]).mean() <= 1e-3 and err.max() <= 10 * 1e-4
-        else:
+    if lam == 2e-6 and lr == 1e-4:
+        for i in range(3):
+            err = np.abs(st["f32"][i].astype(np.float64) - st["f64"][i])
             assert (err <= 1e-6 * scale[i]).all(), (i, (err / scale[i]).max())
     # and the naive per-value relative error does blow up on the cancelling entries, which is why it is not used
     rel_w = np.abs(st["f32"][0].astype(np.float64) - st["f64"][0]) / np.abs(st["f64"][0])
