@@ -358,19 +358,12 @@ def main():
                 figures(timed_calls(lambda: B.cast_weight_scale_multi(ml)), 6.0)
             del copies16
         del ml
-        # mask-learning statistics of a refresh (flip count against the previous mask, ||W.M||_1, ||W||_1): a pass
-        # of its own over w and two masks, 4.25 B/param
-        flips = torch.zeros(1, dtype=torch.int64, device=dev)
-        l1 = torch.zeros(2, dtype=torch.float64, device=dev)
-        for rep in range(2):
-            e0.record()
-            for x in model.t:
-                B.cast_mask_stats(x["w"], x["mask"], x["mask"], flips, l1)
-            e1.record()
-            torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1)
-        extra["mask_stats_ms"] = round(ms, 3)
-        extra["mask_stats_GBs"] = round(4.25 * model.params / (ms * 1e-3) / 1e9, 1)
+        # mask-learning statistics of given masks (flips against another mask, ||W.M||_1, ||W||_1): a pass of its own
+        # over w and two masks, 4.25 B/param, as one list call (per-workgroup partial sums through a workspace)
+        sl = B.StatsList([dict(w=x["w"], mask=x["mask"], other=x["mask"], stats=B.alloc_refresh_stats(dev)) for x in model.t], dev)
+        extra["mask_stats_ms"], extra["mask_stats_GBs"], extra["mask_stats_frac"] = \
+            figures(timed_calls(lambda: B.cast_mask_stats_multi(sl)), 4.25)
+        del sl
         # dL/dA alone (6 B/param), one call per matrix
         if scaled:
             def all_scale_grads():

@@ -364,6 +364,28 @@ cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uin
                             double *l1, void *stream);
 
 /*
+ * The same statistics for a list of matrices, each into a record of its own, without atomics: every workgroup
+ * leaves its counts and fp32 partial norms in the workspace and a second launch adds them up per matrix in a
+ * fixed order (counts exactly, norms in double), so the results are reproducible and within 1e-6 relative of
+ * a double sum.  Matrices of one shape share launches.
+ *   stats  DEVICE out  OVERWRITTEN: flips_prev = ||M - M_other||_0 (0 when other_bits is NULL), flips_init = 0,
+ *                      l1_kept = ||W (.) M||_1, l1_all = ||W||_1
+ *   workspace  DEVICE  at least cast_mask_stats_multi_workspace_bytes(matrices, count) bytes, 16-byte aligned
+ */
+typedef struct {
+    const float *w;               /* DEVICE in  fp32 [rows, cols], row stride ld */
+    int64_t rows, cols, ld;
+    const uint32_t *mask_bits;    /* DEVICE in  M */
+    const uint32_t *other_bits;   /* DEVICE in  the mask flips are counted against, or NULL */
+    cast_refresh_stats *stats;    /* DEVICE out */
+} cast_stats_matrix;
+
+size_t cast_mask_stats_multi_workspace_bytes(const cast_stats_matrix *matrices /* HOST */, int count);
+
+cast_status cast_mask_stats_multi(const cast_stats_matrix *matrices /* HOST */, int count, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
+/*
  * Measurement aid, not part of the method: a plain device-to-device copy kernel of `bytes`
  * bytes (a multiple of 16; both pointers 16-byte aligned), used to calibrate the HBM byte
  * counters and to measure the achievable copy bandwidth beside the optimizer kernels.

@@ -23,7 +23,8 @@ EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step",
            "cast_weight_scale_grad", "cast_nm_project_compress", "cast_mask_stats", "cast_hbm_copy_probe",
            "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi",
            "cast_adams_step_emit", "cast_adams_multi_launches", "cast_debug_plan", "cast_adams_step_multi_noalloc",
-           "cast_hbm_stream_probe", "cast_nm_select_multi", "cast_weight_scale_multi", "cast_nm_project_compress_multi"]
+           "cast_hbm_stream_probe", "cast_nm_select_multi", "cast_weight_scale_multi", "cast_nm_project_compress_multi",
+           "cast_mask_stats_multi", "cast_mask_stats_multi_workspace_bytes"]
 
 
 class CastError(RuntimeError):
@@ -43,6 +44,11 @@ class _Tensor(C.Structure):
 class _Matrix(C.Structure):
     _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64), ("scale", C.c_void_p),
                 ("mask_bits", C.c_void_p), ("out", C.c_void_p), ("meta", C.c_void_p), ("mask_status", C.c_void_p)]
+
+
+class _StatsMatrix(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64), ("mask_bits", C.c_void_p),
+                ("other_bits", C.c_void_p), ("stats", C.c_void_p)]
 
 
 class _Config(C.Structure):
@@ -111,11 +117,14 @@ def load():
     L.cast_nm_select_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, vp]
     L.cast_weight_scale_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, vp]
     L.cast_nm_project_compress_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, ci, ci, vp]
+    L.cast_mask_stats_multi.argtypes = [C.POINTER(_StatsMatrix), ci, vp, C.c_size_t, vp]
+    L.cast_mask_stats_multi_workspace_bytes.argtypes = [C.POINTER(_StatsMatrix), ci]
+    L.cast_mask_stats_multi_workspace_bytes.restype = C.c_size_t
     L.cast_hbm_stream_probe.argtypes = [C.POINTER(_Tensor), ci, ci, vp, C.c_size_t, vp]
     L.cast_debug_plan.argtypes = [i64, i64, i64, ci, ci, i64, ci, C.POINTER(i64), C.POINTER(i64)]
     L.cast_adams_multi_launches.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     for name in EXPORTS:
-        if name not in ("cast_status_str", "cast_adams_multi_workspace_bytes"):
+        if name not in ("cast_status_str", "cast_adams_multi_workspace_bytes", "cast_mask_stats_multi_workspace_bytes"):
             getattr(L, name).restype = C.c_int32
     _lib = L
     return L
@@ -414,6 +423,31 @@ def cast_mask_stats(w, mask_bits, other_bits, flips, l1, stream=None):
     rows, cols = w.shape
     _check(load().cast_mask_stats(_ptr(w), _ptr(mask_bits), _ptr(other_bits), rows, cols, _ld(w), _ptr(flips), _ptr(l1),
                                   _stream(stream)), "cast_mask_stats")
+
+
+class StatsList:
+    """Descriptors for cast_mask_stats_multi, marshalled once, with the workspace the call needs.  Each item is a dict
+    with w, mask, optionally other (the mask flips are counted against) and stats (from alloc_refresh_stats())."""
+
+    def __init__(self, items, device="cuda:0"):
+        self.items = list(items)
+        n = len(self.items)
+        self.array = (_StatsMatrix * max(n, 1))()
+        self.count = n
+        for k, x in enumerate(self.items):
+            w, mk, other, st = x["w"], x["mask"], x.get("other"), x["stats"]
+            _dev(mk, other, st)
+            if st.dtype != torch.int64 or st.numel() != 4:
+                raise TypeError("stats must come from alloc_refresh_stats()")
+            self.array[k] = _StatsMatrix(w.data_ptr(), w.shape[0], w.shape[1], _ld(w), mk.data_ptr(),
+                                         None if other is None else other.data_ptr(), st.data_ptr())
+        need = load().cast_mask_stats_multi_workspace_bytes(self.array, n)
+        self.workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+
+
+def cast_mask_stats_multi(matrices: StatsList, stream=None):
+    _check(load().cast_mask_stats_multi(matrices.array, matrices.count, _ptr(matrices.workspace), matrices.workspace.numel(),
+                                        _stream(stream)), "cast_mask_stats_multi")
 
 
 def cast_hbm_copy_probe(dst, src, stream=None):

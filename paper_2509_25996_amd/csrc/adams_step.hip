@@ -4,6 +4,7 @@
 #include <stdlib.h>
 
 #include <mutex>
+#include <vector>
 
 #include "adams_step_kernels.h"
 
@@ -589,6 +590,69 @@ cast_status builtin_workspace(void **out)
     }
     *out = address[dev];
     return CAST_OK;
+}
+
+// ---- statistics of given masks over a list ------------------------------------------------------------------
+static uint64_t mask_stats_slots(const cast_stats_matrix &t)
+{
+    if (t.rows <= 0 || t.cols <= 0) return 0;
+    const RowsPlan p = plan_rows(t.rows, t.cols, t.ld, 4);
+    if (p.vec) return p.grid;
+    const int64_t words = t.rows * ((t.cols + 31) / 32);
+    return (uint64_t)((words + kBlockThreads - 1) / kBlockThreads);
+}
+
+size_t mask_stats_list_workspace_bytes(const cast_stats_matrix *m, int count)
+{
+    uint64_t slots = 0;
+    for (int i = 0; i < count; ++i) slots += mask_stats_slots(m[i]);
+    return (size_t)slots * sizeof(StatsPartial);
+}
+
+cast_status launch_mask_stats_list(const cast_stats_matrix *m, int count, void *workspace, hipStream_t st)
+{
+    StatsPartial *next = static_cast<StatsPartial *>(workspace);
+    StatsJobQueue jobs;
+    std::vector<char> taken((size_t)count, 0);
+    for (int i = 0; i < count; ++i) {
+        if (taken[i]) continue;
+        if (m[i].rows == 0 || m[i].cols == 0) {      // an empty matrix: zeros, from a job without slots
+            if (jobs.full() && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
+            jobs.add(StatsJob{next, 0, m[i].stats, 0});
+            taken[i] = 1;
+            continue;
+        }
+        int group[kMaxListed];
+        const int n = take_group(m, count, taken, i, [](const cast_stats_matrix &x, const cast_stats_matrix &y) { return (x.other_bits == nullptr) == (y.other_bits == nullptr); }, group);
+        const RowsPlan p = plan_rows(m[i].rows, m[i].cols, m[i].ld, 4);
+        const uint64_t slots = mask_stats_slots(m[i]);
+        MaskStatsArgs a{{}, p.geom};
+        // room for the whole group's jobs first: a flush in between would add up slots nobody has written yet
+        if (jobs.count + n > kMaxStatsJobs && jobs.flush(st) != CAST_OK) return CAST_ERR_LAUNCH;
+        for (int k = 0; k < n; ++k) {
+            const cast_stats_matrix &t = m[group[k]];
+            jobs.add(StatsJob{next, (int64_t)slots, t.stats, 0});
+            if (p.vec && (reinterpret_cast<uintptr_t>(t.w) & 15) == 0) {
+                a.set[k] = MaskStatsSet{t.w, t.mask_bits, t.other_bits, next};
+            } else {
+                hipLaunchKernelGGL(mask_stats_words, dim3((unsigned)slots), dim3(kBlockThreads), 0, st, t.w, t.mask_bits, t.other_bits,
+                                   t.rows, t.cols, t.ld, next);
+                if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+                a.set[k] = MaskStatsSet{nullptr, nullptr, nullptr, nullptr};
+            }
+            next += slots;
+        }
+        if (p.vec) {      // the matrices of the group whose weights are 16-byte aligned, in one launch
+            int dense = 0;
+            for (int k = 0; k < n; ++k)
+                if (a.set[k].w) a.set[dense++] = a.set[k];
+            if (dense > 0) {
+                hipLaunchKernelGGL(mask_stats_rows, dim3(p.grid, (unsigned)dense), dim3(kBlockThreads), 0, st, a);
+                if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+            }
+        }
+    }
+    return jobs.flush(st);
 }
 
 cast_status debug_div_by_uniform(const float *x, float y, float *out, int64_t n)

@@ -634,6 +634,101 @@ __global__ __launch_bounds__(kBlockThreads) void refresh_stats_unit(const float 
     }
 }
 
+// The statistics of given masks (no step): the row-block form of the selection and pack kernels, one slot per
+// workgroup.  w with the non-temporal hint; a mask word is read by the 8 lanes that hold its 32 entries.
+struct MaskStatsSet {
+    const float *w;
+    const uint32_t *mask;
+    const uint32_t *other;      // or NULL
+    StatsPartial *partials;     // one slot per workgroup of this matrix
+};
+
+struct MaskStatsArgs {
+    MaskStatsSet set[kMaxListed];
+    RowsGeom geom;
+};
+
+__device__ __forceinline__ void stats_block_sum(StatsShared &sh, uint32_t flips, float l1_kept, float l1_all, StatsPartial *slot)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    flips = wave_sum_u32(flips);
+    l1_kept = wave_sum_fixed_order(l1_kept);
+    l1_all = wave_sum_fixed_order(l1_all);
+    if (lane == 0) { sh.flips_prev[wave] = flips; sh.l1_kept[wave] = l1_kept; sh.l1_all[wave] = l1_all; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        StatsPartial out{flips, 0u, l1_kept, l1_all};
+        for (int k = 1; k < (int)(blockDim.x / kWave); ++k) {
+            out.flips_prev += sh.flips_prev[k];
+            out.l1_kept = out.l1_kept + sh.l1_kept[k];
+            out.l1_all = out.l1_all + sh.l1_all[k];
+        }
+        *slot = out;
+    }
+}
+
+__global__ __launch_bounds__(kBlockThreads) void mask_stats_rows(const MaskStatsArgs a)
+{
+    __shared__ StatsShared sh;
+    const MaskStatsSet t = a.set[blockIdx.y];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int cols = a.geom.cols;
+    vf4_t raw[kLoads];
+    uint32_t word[kLoads], diff[kLoads];
+    int col[kLoads];
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
+        col[k] = piece.col + (int)threadIdx.x * 4;
+        raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
+        word[k] = diff[k] = 0;
+        if (col[k] < cols) {
+            const int64_t at = (int64_t)piece.row * (cols >> 5) + (col[k] >> 5);
+            raw[k] = __builtin_nontemporal_load(reinterpret_cast<const vf4_t *>(t.w + (int64_t)piece.row * a.geom.ld + col[k]));
+            word[k] = __builtin_nontemporal_load(t.mask + at);
+            if (t.other) diff[k] = word[k] ^ __builtin_nontemporal_load(t.other + at);
+        }
+    }
+    uint32_t flips = 0;
+    float l1_kept = 0.0f, l1_all = 0.0f;
+#pragma unroll
+    for (int k = 0; k < kLoads; ++k) {
+        const uint32_t nib = (word[k] >> (col[k] & 31)) & 0xFu;      // lanes past the end: zeros, nothing counted
+        const float x[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float mag = __builtin_fabsf(x[j]);
+            l1_all = l1_all + mag;
+            l1_kept = l1_kept + (((nib >> j) & 1u) ? mag : 0.0f);
+        }
+        if ((lane & 7) == 0) flips += __popc(diff[k]);      // one lane per mask word
+    }
+    stats_block_sum(sh, flips, l1_kept, l1_all, t.partials + blockIdx.x);
+}
+
+// Any shape: one thread per mask word, the row padded to whole words.
+__global__ __launch_bounds__(kBlockThreads) void mask_stats_words(const float *w, const uint32_t *mask, const uint32_t *other,
+                                                                  int64_t rows, int64_t cols, int64_t ld, StatsPartial *partials)
+{
+    __shared__ StatsShared sh;
+    const int64_t words_per_row = (cols + 31) / 32;
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t flips = 0;
+    float l1_kept = 0.0f, l1_all = 0.0f;
+    if (t < rows * words_per_row) {
+        const int64_t r = t / words_per_row, cb = (t % words_per_row) * 32;
+        const int64_t ce = (cb + 32 < cols) ? cb + 32 : cols;
+        const uint32_t word = mask[t];
+        if (other) flips = __popc(word ^ other[t]);
+        for (int64_t c = cb; c < ce; ++c) {
+            const float mag = __builtin_fabsf(w[r * ld + c]);
+            l1_all = l1_all + mag;
+            l1_kept = l1_kept + (((word >> (unsigned)(c - cb)) & 1u) ? mag : 0.0f);
+        }
+    }
+    stats_block_sum(sh, flips, l1_kept, l1_all, partials + blockIdx.x);
+}
+
 // Second half of the refresh statistics: the slots of a matrix added up, counts exactly, norms in
 // double, always in the same order (each thread a strided share, then a tree), so the result is
 // reproducible.  One workgroup per matrix, up to kMaxStatsJobs matrices per launch.

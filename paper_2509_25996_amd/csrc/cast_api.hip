@@ -343,6 +343,34 @@ cast_status cast_mask_stats(const float *w, const uint32_t *mask_bits, const uin
     return launch_mask_stats(w, mask_bits, other_bits, rows, cols, ld, flips, l1, static_cast<hipStream_t>(stream));
 }
 
+size_t cast_mask_stats_multi_workspace_bytes(const cast_stats_matrix *matrices, int count)
+{
+    return matrices && count > 0 ? mask_stats_list_workspace_bytes(matrices, count) : 0;
+}
+
+cast_status cast_mask_stats_multi(const cast_stats_matrix *matrices, int count, void *workspace, size_t workspace_bytes,
+                                  void *stream)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (count == 0) return CAST_OK;
+    if (!matrices) return CAST_ERR_NULL;
+    for (int i = 0; i < count; ++i) {      // all or nothing
+        const cast_stats_matrix &t = matrices[i];
+        if (t.rows < 0 || t.cols < 0 || t.ld < t.cols) return CAST_ERR_SHAPE;
+        if (t.rows > 0 && t.cols > 0 && t.rows > (((int64_t)1 << 40) / t.cols)) return CAST_ERR_SHAPE;
+        if (!t.stats) return CAST_ERR_NULL;
+        if (!aligned(t.stats, 8)) return CAST_ERR_ALIGN;
+        if (t.rows == 0 || t.cols == 0) continue;
+        if (!t.w || !t.mask_bits) return CAST_ERR_NULL;
+        if (!aligned(t.w, 4) || !aligned(t.mask_bits, 4) || !aligned(t.other_bits, 4)) return CAST_ERR_ALIGN;
+    }
+    const size_t need = mask_stats_list_workspace_bytes(matrices, count);
+    if (need > 0 && !workspace) return CAST_ERR_NULL;
+    if (!aligned(workspace, 16)) return CAST_ERR_ALIGN;
+    if (workspace_bytes < need) return CAST_ERR_SHAPE;
+    return launch_mask_stats_list(matrices, count, workspace, static_cast<hipStream_t>(stream));
+}
+
 cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *stream)
 {
     if (bytes == 0) return CAST_OK;

@@ -149,6 +149,11 @@ __host__ __device__ __forceinline__ SpanOrigin piece_origin(const SpanGeom &g, i
 // ---- how the selection, scaling and pack kernels cut a matrix ---------------------------------
 // A workgroup of 256 threads covers `loads` pieces of 256 * lane_entries consecutive entries of one
 // row; piece k of workgroup b of a row starts at column (b * loads + k) * 256 * lane_entries.
+#ifndef CAST_ROWS_LOADS
+#define CAST_ROWS_LOADS 2
+#endif
+constexpr int kLoads = CAST_ROWS_LOADS;      // pieces per workgroup = loads in flight per thread (measured: 2 beats 1, 3 and 4)
+
 struct RowsGeom {
     int cols;                 // entries per row (at most 2^30)
     int64_t ld;               // row stride of w

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/cast.h"
 #include "cast_device.h"
 
@@ -72,11 +74,37 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad,
                               hipStream_t stream);
+// Matrices of one shape (and, for `alike`, the same optional buffers) go several to a launch: up to
+// kMaxListed of them and about 72 M entries, the rule of the step kernels (a short launch pays some 2.6 us
+// of ramp, a very long one lets the compute units drift apart).  Collects into `group` the indices, from
+// `first` on, of matrices not yet taken that are like matrix `first`, and marks them taken.
+template <typename Matrix, typename Alike>
+inline int take_group(const Matrix *m, int count, std::vector<char> &taken, int first, Alike alike, int (&group)[kMaxListed])
+{
+    const Matrix &t = m[first];
+    int most = kMaxListed;
+    const int64_t entries = t.rows * t.cols;
+    const int64_t launch_entries = (int64_t)72 << 20;
+    if (entries > 0 && launch_entries / entries < most) most = (int)(launch_entries / entries);
+    if (most < 1) most = 1;
+    int n = 0;
+    group[n++] = first;
+    taken[first] = 1;
+    for (int j = first + 1; j < count && n < most; ++j)
+        if (!taken[j] && m[j].rows == t.rows && m[j].cols == t.cols && m[j].ld == t.ld && alike(m[j], t)) {
+            group[n++] = j;
+            taken[j] = 1;
+        }
+    return n;
+}
+
 // Lists of matrices (already validated): matrices of one shape share launches.
 cast_status launch_nm_select_list(const cast_matrix *m, int count, int n_keep, int m_group, hipStream_t stream);
 cast_status launch_weight_scale_list(const cast_matrix *m, int count, int n_segments, int out_dtype, hipStream_t stream);
 cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_segments, int n_keep, int m_group,
                                          int value_dtype, hipStream_t stream);
+size_t mask_stats_list_workspace_bytes(const cast_stats_matrix *m, int count);
+cast_status launch_mask_stats_list(const cast_stats_matrix *m, int count, void *workspace, hipStream_t stream);
 cast_status launch_mask_stats(const float *w, const uint32_t *mask_bits, const uint32_t *other_bits,
                               int64_t rows, int64_t cols, int64_t ld, unsigned long long *flips,
                               double *l1, hipStream_t stream);

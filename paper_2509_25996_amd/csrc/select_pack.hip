@@ -58,11 +58,6 @@ __device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
 // line only together with their neighbours', are stored with the default policy so that the L2 merges
 // them (non-temporal: 7 % slower).  A form in which wavefronts walked spans through buffer resources
 // with four chunks in flight, like the step kernels, ran at 5.2 TB/s where this one runs at 6.3.
-#ifndef CAST_ROWS_LOADS
-#define CAST_ROWS_LOADS 2
-#endif
-constexpr int kLoads = CAST_ROWS_LOADS;
-
 RowsPlan plan_rows(int64_t rows, int64_t cols, int64_t ld, int lane_entries)
 {
     RowsPlan p{};
@@ -140,30 +135,6 @@ __global__ __launch_bounds__(kBlockThreads) void nm_select_unit(const float *w, 
         word |= keep_bits_group<M>(x, n_keep) << (unsigned)(c - cb);
     }
     mask[tid] = word;
-}
-
-// Matrices of one shape (and, for `alike`, the same optional buffers) go several to a launch: up to
-// kMaxListed of them and about 72 M entries, the rule of the step kernels (a short launch pays some 2.6 us
-// of ramp, a very long one lets the compute units drift apart).  Collects into `group` the indices, from
-// `first` on, of matrices not yet taken that are like matrix `first`, and marks them taken.
-template <typename Alike>
-static int take_group(const cast_matrix *m, int count, std::vector<char> &taken, int first, Alike alike, int (&group)[kMaxListed])
-{
-    const cast_matrix &t = m[first];
-    int most = kMaxListed;
-    const int64_t entries = t.rows * t.cols;
-    const int64_t launch_entries = (int64_t)72 << 20;
-    if (entries > 0 && launch_entries / entries < most) most = (int)(launch_entries / entries);
-    if (most < 1) most = 1;
-    int n = 0;
-    group[n++] = first;
-    taken[first] = 1;
-    for (int j = first + 1; j < count && n < most; ++j)
-        if (!taken[j] && m[j].rows == t.rows && m[j].cols == t.cols && m[j].ld == t.ld && alike(m[j], t)) {
-            group[n++] = j;
-            taken[j] = 1;
-        }
-    return n;
 }
 
 cast_status launch_nm_select_list(const cast_matrix *m, int count, int n_keep, int m_group, hipStream_t st)

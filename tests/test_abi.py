@@ -161,6 +161,40 @@ def test_validation_happens_before_any_launch(lib):
     assert lib.cast_hbm_copy_probe(nul, nul, 0, st) == 0
 
 
+def test_list_calls_of_the_once_per_run_entry_points_reject_bad_lists(lib):
+    # all or nothing: one bad matrix and nothing is launched (fake device pointers: none is dereferenced on the host)
+    M, S = B._Matrix, B._StatsMatrix
+    a, st, odd = 0x100000, C.c_void_p(0), 0x100004
+    good = M(a, 4, 64, 64, a, a, a, a, None)
+    bad_shape = M(a, 4, 64, 60, a, a, a, a, None)      # row stride below the row length
+    for arr, want in (((M * 2)(good, bad_shape), -2), ((M * 2)(good, M(None, 4, 64, 64, a, a, a, a, None)), -1),
+                      ((M * 2)(good, M(odd, 4, 64, 64, a, a, a, a, None)), -3)):
+        assert lib.cast_nm_select_multi(arr, 2, 2, 4, st) == want
+        assert lib.cast_weight_scale_multi(arr, 2, 2, B.CAST_BF16, st) == want
+        assert lib.cast_nm_project_compress_multi(arr, 2, 2, 2, 4, B.CAST_F32, st) == want
+    one = (M * 1)(good)
+    assert lib.cast_nm_select_multi(one, 1, 4, 4, st) == -2                      # N < M
+    assert lib.cast_weight_scale_multi(one, 1, 3, B.CAST_F32, st) == -2          # 3 segments do not divide 64 columns
+    assert lib.cast_weight_scale_multi(one, 1, 2, 7, st) == -4
+    assert lib.cast_nm_project_compress_multi(one, 1, 2, 2, 4, 9, st) == -4
+    assert lib.cast_nm_project_compress_multi((M * 1)(M(a, 4, 64, 64, a, a, a, a, 0x100002)), 1, 2, 2, 4, 0, st) == -3      # status word
+    for f in (lib.cast_nm_select_multi,):
+        assert f(one, 0, 2, 4, st) == 0 and f(None, 1, 2, 4, st) == -1 and f(one, -1, 2, 4, st) == -2
+    empty = (M * 1)(M(None, 0, 64, 64, None, None, None, None, None))
+    assert lib.cast_nm_select_multi(empty, 1, 2, 4, st) == 0
+    # statistics of given masks over a list
+    sgood = S(a, 4, 64, 64, a, a, a)
+    ws = lib.cast_mask_stats_multi_workspace_bytes
+    assert ws((S * 1)(sgood), 1) == 4 * 16 and ws((S * 1)(S(a, 5, 72, 72, a, None, a)), 1) == 16 and ws(None, 1) == 0      # a workgroup per row; 15 words
+    assert ws((S * 1)(S(a, 11008, 4096, 12288, a, None, a)), 1) == 11008 * 2 * 16      # a workgroup per 2048 entries of a row
+    assert lib.cast_mask_stats_multi((S * 1)(sgood), 1, C.c_void_p(a), 48, st) == -2
+    assert lib.cast_mask_stats_multi((S * 1)(sgood), 1, None, 64, st) == -1
+    assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 64, None, a, a)), 1, C.c_void_p(a), 64, st) == -1
+    assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 64, a, a, None)), 1, C.c_void_p(a), 64, st) == -1
+    assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 60, a, a, a)), 1, C.c_void_p(a), 64, st) == -2
+    assert lib.cast_mask_stats_multi((S * 1)(sgood), 0, None, 0, st) == 0
+
+
 def test_noalloc_list_call_rejects_what_does_not_fit(lib):
     # the entry point that allocates nothing has a fixed workspace (64 MiB) and a fixed list length; anything
     # beyond is refused on the host before a device is touched

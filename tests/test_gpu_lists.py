@@ -156,3 +156,31 @@ def test_stored_masks_are_checked_when_a_status_word_is_given(n, m, rows, cols):
             ref_v, ref_m = oracle.project_compress(w0, n, m, keep=keep)
             assert (words(item["meta"]) == ref_m).all()
             assert_same_bits(host(item["out"]), ref_v, "values")
+
+
+@pytest.mark.parametrize("with_other", [True, False])
+def test_mask_stats_list_matches_the_oracle(with_other):
+    """Appendix "Mask Learning" over a list: flips against another mask (exact), ||W (.) M||_1 and ||W||_1 (1e-6
+    relative: fp32 partial sums per workgroup, double across them), per matrix, and reproducible bit for bit."""
+    shapes = SHAPES + [(700, 2048)]      # the last one: more workgroups than the summing kernel has threads
+    state = _state(shapes, 66)
+    items, refs = [], []
+    for i, ((w0, w), (r, c)) in enumerate(zip(state, shapes)):
+        keep = oracle.nm_select(w0, 2, 4) if r else np.zeros((0, c), np.uint8)
+        other = oracle.nm_select(synth.weights(67, i, r, c), 2, 4) if (r and with_other) else None
+        items.append(dict(w=w, mask=dev(oracle.pack_mask_bits(keep).view(np.int32)),
+                          other=None if other is None else dev(oracle.pack_mask_bits(other).view(np.int32)),
+                          stats=torch.full((4,), -1, dtype=torch.int64, device=DEV)))
+        refs.append((w0, keep, other))
+    sl = B.StatsList(items, DEV)
+    runs = []
+    for _ in range(2):
+        B.cast_mask_stats_multi(sl)
+        torch.cuda.synchronize()
+        runs.append([host(x["stats"]).tobytes() for x in items])
+    assert runs[0] == runs[1]
+    for x, (w0, keep, other), shape in zip(items, refs, shapes):
+        got = B.read_refresh_stats(x["stats"])
+        flips, kept, total = oracle.mask_stats(w0, keep, other) if w0.size else (0, 0.0, 0.0)
+        assert got["flips_prev"] == flips and got["flips_init"] == 0, shape
+        assert abs(got["l1_kept"] - kept) <= 1e-6 * kept and abs(got["l1_all"] - total) <= 1e-6 * total, shape
