@@ -647,7 +647,8 @@ cast_status launch_mask_stats_list(const cast_stats_matrix *m, int count, void *
             for (int k = 0; k < n; ++k)
                 if (a.set[k].w) a.set[dense++] = a.set[k];
             if (dense > 0) {
-                hipLaunchKernelGGL(mask_stats_rows, dim3(p.grid, (unsigned)dense), dim3(kBlockThreads), 0, st, a);
+                if (p.same_row) hipLaunchKernelGGL(mask_stats_rows<true>, dim3(p.grid, (unsigned)dense), dim3(kBlockThreads), 0, st, a);
+                else hipLaunchKernelGGL(mask_stats_rows<false>, dim3(p.grid, (unsigned)dense), dim3(kBlockThreads), 0, st, a);
                 if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
             }
         }

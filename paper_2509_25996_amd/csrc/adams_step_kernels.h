@@ -667,19 +667,21 @@ __device__ __forceinline__ void stats_block_sum(StatsShared &sh, uint32_t flips,
     }
 }
 
+template <bool SAME_ROW>
 __global__ __launch_bounds__(kBlockThreads) void mask_stats_rows(const MaskStatsArgs a)
 {
     __shared__ StatsShared sh;
     const MaskStatsSet t = a.set[blockIdx.y];
     const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int cols = a.geom.cols;
     vf4_t raw[kLoads];
     uint32_t word[kLoads], diff[kLoads];
     int col[kLoads];
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
-        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
-        col[k] = piece.col + (int)threadIdx.x * 4;
+        const RowsPiece piece = rows_piece<SAME_ROW>(a.geom, blockIdx.x, wave, k);
+        col[k] = piece.col + lane * 4;
         raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
         word[k] = diff[k] = 0;
         if (col[k] < cols) {

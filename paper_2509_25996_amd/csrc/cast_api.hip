@@ -432,8 +432,9 @@ cast_status cast_debug_plan(int64_t rows, int64_t cols, int64_t ld, int n_segmen
         plan[4] = 1;
         for (int k = 0; k < 5; ++k) span[k] = 0;
         if (!r.vec || block >= (int64_t)r.grid || wave >= slots) return CAST_OK;
-        const RowsPiece piece = rows_piece(r.geom, (uint32_t)block, wave / kBlockWaves);
-        const int64_t col = piece.col + (int64_t)(wave % kBlockWaves) * kWave * r.geom.lane_entries;
+        const RowsPiece piece = r.same_row ? rows_piece<true>(r.geom, (uint32_t)block, wave % kBlockWaves, wave / kBlockWaves)
+                                           : rows_piece<false>(r.geom, (uint32_t)block, wave % kBlockWaves, wave / kBlockWaves);
+        const int64_t col = piece.col;
         if (col >= cols) return CAST_OK;
         const int64_t len = kWave * r.geom.lane_entries;
         span[0] = (int64_t)piece.row * ld + col;

@@ -33,6 +33,7 @@ SpanPlan plan_spans(int64_t rows, int64_t cols, int64_t ld, int n_segments, bool
 // per thread and load.  vec = false: the shape goes to the scalar kernels.
 struct RowsPlan {
     bool vec;
+    bool same_row;       // rows are whole numbers of workgroups
     RowsGeom geom;
     unsigned grid;       // workgroups per matrix
 };

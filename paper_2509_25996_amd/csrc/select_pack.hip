@@ -48,8 +48,8 @@ __device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
 // ---- how these kernels cover a matrix ----------------------------------------------------------
 // They do little arithmetic per byte and read every weight once, so what counts is plain, wide,
 // independent loads: a thread owns kLoads pieces of E consecutive entries (E = 4: one 16-byte load;
-// E = 8 for the 4:8 pack: two), a workgroup of 256 threads covers kLoads * 256 * E consecutive
-// entries of ONE row, its k-th piece being the k-th run of 256 * E entries, and all loads of a thread
+// E = 8 for the 4:8 pack: two), a wavefront kLoads consecutive chunks of 64 * E entries of a row, a
+// workgroup of 256 threads 4 * kLoads consecutive chunks (see RowsGeom), and all loads of a thread
 // are requested before the first is used.  Rows are whole mask words (cols % 32 == 0), so every run
 // of 8 lanes (E = 4) holds one mask word.  blockIdx.y picks one of up to kMaxListed matrices of equal
 // shape whose buffers travel in the kernel arguments (list calls).
@@ -61,18 +61,21 @@ __device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
 RowsPlan plan_rows(int64_t rows, int64_t cols, int64_t ld, int lane_entries)
 {
     RowsPlan p{};
-    const int64_t per_block = (int64_t)kLoads * kBlockThreads * lane_entries;
+    const int64_t chunk = (int64_t)kWave * lane_entries;
     p.vec = rows > 0 && cols > 0 && cols % 32 == 0 && ld % 4 == 0 && cols <= ((int64_t)1 << 30);
     if (!p.vec) return p;
-    const int64_t blocks_per_row = (cols + per_block - 1) / per_block;
-    if (rows * blocks_per_row >= ((int64_t)1 << 31)) { p.vec = false; return p; }
+    const int64_t chunks_per_row = (cols + chunk - 1) / chunk;
+    if (rows * chunks_per_row >= ((int64_t)1 << 31)) { p.vec = false; return p; }
     p.geom.cols = (int)cols;
     p.geom.ld = ld;
     p.geom.lane_entries = lane_entries;
     p.geom.loads = kLoads;
-    p.geom.blocks_per_row = (uint32_t)blocks_per_row;
-    p.geom.div_blocks_per_row = make_fast_div((uint32_t)blocks_per_row);
-    p.grid = (unsigned)(rows * blocks_per_row);
+    p.geom.chunks_per_row = (uint32_t)chunks_per_row;
+    p.geom.num_chunks = (uint32_t)(rows * chunks_per_row);
+    p.geom.div_chunks_per_row = make_fast_div((uint32_t)chunks_per_row);
+    const int64_t per_block = (int64_t)kBlockWaves * kLoads;
+    p.same_row = chunks_per_row % per_block == 0 && cols % chunk == 0;
+    p.grid = (unsigned)((rows * chunks_per_row + per_block - 1) / per_block);
     return p;
 }
 
@@ -88,31 +91,30 @@ struct SelectArgs {
     int n_keep;
 };
 
-template <int M>
+template <int M, bool SAME_ROW>
 __global__ __launch_bounds__(kBlockThreads) void nm_select_rows(const SelectArgs a)
 {
     const SelectSet t = a.set[blockIdx.y];
     const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int cols = a.geom.cols;
     vf4_t raw[kLoads];
     int col[kLoads];
-    const float *src = nullptr;
-    uint32_t *dst = nullptr;
+    uint32_t *dst[kLoads];
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
-        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
-        col[k] = piece.col + (int)threadIdx.x * 4;
-        src = t.w + (int64_t)piece.row * a.geom.ld;
-        dst = t.mask + (int64_t)piece.row * (cols >> 5);
+        const RowsPiece piece = rows_piece<SAME_ROW>(a.geom, blockIdx.x, wave, k);
+        col[k] = piece.col + lane * 4;
+        dst[k] = t.mask + (int64_t)piece.row * (cols >> 5);
         raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};      // past the end of the row: zeros, nothing stored
-        if (col[k] < cols) raw[k] = load_once(reinterpret_cast<const vf4_t *>(src + col[k]));
+        if (col[k] < cols) raw[k] = load_once(reinterpret_cast<const vf4_t *>(t.w + (int64_t)piece.row * a.geom.ld + col[k]));
     }
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
         const float x[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
         const uint32_t nib = keep_nibble<M>(x, a.n_keep, lane);      // all 64 lanes take part
         const uint32_t word = or_reduce_8lanes(nib << ((lane & 7) * 4));
-        if ((lane & 7) == 0 && col[k] < cols) dst[col[k] >> 5] = word;
+        if ((lane & 7) == 0 && col[k] < cols) dst[k][col[k] >> 5] = word;
     }
 }
 
@@ -149,10 +151,13 @@ cast_status launch_nm_select_list(const cast_matrix *m, int count, int n_keep, i
             SelectArgs a{{}, p.geom, n_keep};
             for (int k = 0; k < n; ++k) a.set[k] = SelectSet{m[group[k]].w, m[group[k]].mask_bits};
             const dim3 grid(p.grid, (unsigned)n), block(kBlockThreads);
-            switch (m_group) {
-            case 2: hipLaunchKernelGGL(nm_select_rows<2>, grid, block, 0, st, a); break;
-            case 4: hipLaunchKernelGGL(nm_select_rows<4>, grid, block, 0, st, a); break;
-            default: hipLaunchKernelGGL(nm_select_rows<8>, grid, block, 0, st, a); break;
+            switch (m_group * 2 + (p.same_row ? 1 : 0)) {
+            case 4: hipLaunchKernelGGL((nm_select_rows<2, false>), grid, block, 0, st, a); break;
+            case 5: hipLaunchKernelGGL((nm_select_rows<2, true>), grid, block, 0, st, a); break;
+            case 8: hipLaunchKernelGGL((nm_select_rows<4, false>), grid, block, 0, st, a); break;
+            case 9: hipLaunchKernelGGL((nm_select_rows<4, true>), grid, block, 0, st, a); break;
+            case 16: hipLaunchKernelGGL((nm_select_rows<8, false>), grid, block, 0, st, a); break;
+            default: hipLaunchKernelGGL((nm_select_rows<8, true>), grid, block, 0, st, a); break;
             }
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
             continue;
@@ -219,18 +224,20 @@ struct ScaleArgs {
     int n_segments;
 };
 
-template <bool BF16OUT>
+template <bool BF16OUT, bool SAME_ROW>
 __global__ __launch_bounds__(kBlockThreads) void weight_scale_rows(const ScaleArgs a)
 {
     const ScaleSet t = a.set[blockIdx.y];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int cols = a.geom.cols;
     vf4_t raw[kLoads];
     float A[kLoads];
     int64_t at[kLoads];      // dense index of the thread's first entry, -1: nothing to do
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
-        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
-        const int c = piece.col + (int)threadIdx.x * 4;
+        const RowsPiece piece = rows_piece<SAME_ROW>(a.geom, blockIdx.x, wave, k);
+        const int c = piece.col + lane * 4;
         at[k] = -1;
         raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
         A[k] = 0.0f;
@@ -268,8 +275,13 @@ cast_status launch_weight_scale_list(const cast_matrix *m, int count, int n_segm
             ScaleArgs a{{}, p.geom, make_fast_div((uint32_t)seg_len), n_segments};
             for (int k = 0; k < n; ++k) a.set[k] = ScaleSet{m[group[k]].w, m[group[k]].scale, m[group[k]].out};
             const dim3 grid(p.grid, (unsigned)n), block(kBlockThreads);
-            if (bf16) hipLaunchKernelGGL(weight_scale_rows<true>, grid, block, 0, st, a);
-            else hipLaunchKernelGGL(weight_scale_rows<false>, grid, block, 0, st, a);
+            if (p.same_row) {
+                if (bf16) hipLaunchKernelGGL((weight_scale_rows<true, true>), grid, block, 0, st, a);
+                else hipLaunchKernelGGL((weight_scale_rows<false, true>), grid, block, 0, st, a);
+            } else {
+                if (bf16) hipLaunchKernelGGL((weight_scale_rows<true, false>), grid, block, 0, st, a);
+                else hipLaunchKernelGGL((weight_scale_rows<false, false>), grid, block, 0, st, a);
+            }
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
             continue;
         }
@@ -321,24 +333,26 @@ struct PackArgs {
 // 4-byte (bf16) store at values[dense index / 2]:
 //   2:4  the lane is one group; the 4-bit index fields of 8 adjacent lanes form one metadata word;
 //   1:2  the lane is two groups with one kept entry each; 16 lanes' bit pairs form one word.
-template <int M, bool BF16OUT>
+template <int M, bool BF16OUT, bool SAME_ROW>
 __global__ __launch_bounds__(kBlockThreads) void project_compress_half_rows(const PackArgs a)
 {
     static_assert(M == 4 || M == 2, "2:4 and 1:2 only");
     constexpr int kEntriesPerWord = M == 4 ? 32 : 64;      // columns one metadata word describes
     const PackSet t = a.set[blockIdx.y];
     const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int cols = a.geom.cols;
     vf4_t raw[kLoads];
     uint32_t bits[kLoads];
     float A[kLoads];
     int col[kLoads];
-    uint32_t row = 0;
+    int64_t dense_row[kLoads];      // dense index of the first entry of the chunk's row
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
-        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
-        row = piece.row;
-        col[k] = piece.col + (int)threadIdx.x * 4;
+        const RowsPiece piece = rows_piece<SAME_ROW>(a.geom, blockIdx.x, wave, k);
+        const uint32_t row = piece.row;
+        dense_row[k] = (int64_t)row * cols;
+        col[k] = piece.col + lane * 4;
         raw[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
         bits[k] = 0;
         A[k] = 1.0f;
@@ -348,7 +362,6 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_half_rows(cons
             if (t.scale) A[k] = t.scale[(int64_t)row * a.n_segments + fast_div((uint32_t)col[k], a.div_seg_len)];      // Eq. 12
         }
     }
-    const int64_t dense_row = (int64_t)row * cols;
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
         const float x[4] = {raw[k].x, raw[k].y, raw[k].z, raw[k].w};
@@ -378,14 +391,14 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_half_rows(cons
         }
         if (col[k] >= cols) continue;      // (after the cross-lane steps, which all 64 lanes take)
         if (t.scale) { va = A[k] * va; vb = A[k] * vb; }
-        const int64_t at = (dense_row + col[k]) >> 1;      // half of the entries are kept
+        const int64_t at = (dense_row[k] + col[k]) >> 1;      // half of the entries are kept
         if constexpr (BF16OUT) {
             store_full(static_cast<uint32_t *>(t.values) + (at >> 1), f32x2_to_bf16_rne(va, vb));
         } else {
             store_full(reinterpret_cast<vu2_t *>(static_cast<float *>(t.values) + at), vu2_t{__float_as_uint(va), __float_as_uint(vb)});
         }
         constexpr int kLanesPerWord = kEntriesPerWord / kLaneElems;
-        if ((lane & (kLanesPerWord - 1)) == 0) t.meta[(dense_row + col[k]) / kEntriesPerWord] = word;
+        if ((lane & (kLanesPerWord - 1)) == 0) t.meta[(dense_row[k] + col[k]) / kEntriesPerWord] = word;
     }
 }
 
@@ -393,22 +406,24 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_half_rows(cons
 // are picked inside the lane (the k-th kept entry can only be one of entries k .. k + 4) and leave as
 // one 16-byte (fp32) or 8-byte (bf16) store; two adjacent lanes' 12-bit index fields form a metadata
 // word.  The exchange between lane pairs that a 4-entries-per-lane form needs made it ALU-bound.
-template <bool BF16OUT>
+template <bool BF16OUT, bool SAME_ROW>
 __global__ __launch_bounds__(kBlockThreads) void project_compress_4of8_rows(const PackArgs a)
 {
     const PackSet t = a.set[blockIdx.y];
     const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int cols = a.geom.cols;
     vf4_t lo[kLoads], hi[kLoads];
     uint32_t bits[kLoads];
     float A[kLoads];
     int col[kLoads];
-    uint32_t row = 0;
+    int64_t dense_row[kLoads];
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
-        const RowsPiece piece = rows_piece(a.geom, blockIdx.x, k);
-        row = piece.row;
-        col[k] = piece.col + (int)threadIdx.x * 8;
+        const RowsPiece piece = rows_piece<SAME_ROW>(a.geom, blockIdx.x, wave, k);
+        const uint32_t row = piece.row;
+        dense_row[k] = (int64_t)row * cols;
+        col[k] = piece.col + lane * 8;
         lo[k] = hi[k] = vf4_t{0.0f, 0.0f, 0.0f, 0.0f};
         bits[k] = 0;
         A[k] = 1.0f;
@@ -420,7 +435,6 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_4of8_rows(cons
             if (t.scale) A[k] = t.scale[(int64_t)row * a.n_segments + fast_div((uint32_t)col[k], a.div_seg_len)];
         }
     }
-    const int64_t dense_row = (int64_t)row * cols;
 #pragma unroll
     for (int k = 0; k < kLoads; ++k) {
         const float x[8] = {lo[k].x, lo[k].y, lo[k].z, lo[k].w, hi[k].x, hi[k].y, hi[k].z, hi[k].w};
@@ -438,14 +452,14 @@ __global__ __launch_bounds__(kBlockThreads) void project_compress_4of8_rows(cons
         if (t.mask && t.status) report_bad_groups(t.status, (uint32_t)(col[k] < cols && __popc(kept) != 4));
         if (col[k] >= cols) continue;
         if (t.scale) { v0 = A[k] * v0; v1 = A[k] * v1; v2 = A[k] * v2; v3 = A[k] * v3; }
-        const int64_t at = (dense_row + col[k]) >> 1;
+        const int64_t at = (dense_row[k] + col[k]) >> 1;
         if constexpr (BF16OUT) {
             const vu2_t h = {f32x2_to_bf16_rne(v0, v1), f32x2_to_bf16_rne(v2, v3)};
             store_full(reinterpret_cast<vu2_t *>(static_cast<uint16_t *>(t.values) + at), h);
         } else {
             store_full(reinterpret_cast<vf4_t *>(static_cast<float *>(t.values) + at), vf4_t{v0, v1, v2, v3});
         }
-        if ((lane & 1) == 0) t.meta[(dense_row + col[k]) >> 4] = word;
+        if ((lane & 1) == 0) t.meta[(dense_row[k] + col[k]) >> 4] = word;
     }
 }
 
@@ -513,6 +527,22 @@ static void launch_pack_unit(bool bf16, unsigned grid, hipStream_t st, const flo
     else hipLaunchKernelGGL((project_compress_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, w, scale, mask, values, meta, rows, cols, ld, n_keep, n_segments, status);
 }
 
+template <bool BF16OUT, bool SAME_ROW>
+static void launch_pack_rows_as(int m_group, dim3 grid, dim3 block, hipStream_t st, const PackArgs &a)
+{
+    switch (m_group) {
+    case 4: hipLaunchKernelGGL((project_compress_half_rows<4, BF16OUT, SAME_ROW>), grid, block, 0, st, a); break;
+    case 8: hipLaunchKernelGGL((project_compress_4of8_rows<BF16OUT, SAME_ROW>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((project_compress_half_rows<2, BF16OUT, SAME_ROW>), grid, block, 0, st, a); break;
+    }
+}
+
+static void launch_pack_rows(int m_group, bool bf16, bool same_row, dim3 grid, dim3 block, hipStream_t st, const PackArgs &a)
+{
+    if (bf16) { if (same_row) launch_pack_rows_as<true, true>(m_group, grid, block, st, a); else launch_pack_rows_as<true, false>(m_group, grid, block, st, a); }
+    else { if (same_row) launch_pack_rows_as<false, true>(m_group, grid, block, st, a); else launch_pack_rows_as<false, false>(m_group, grid, block, st, a); }
+}
+
 cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_segments, int n_keep, int m_group,
                                          int value_dtype, hipStream_t st)
 {
@@ -538,20 +568,7 @@ cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_
                 a.set[k] = PackSet{t.w, t.scale, t.mask_bits, t.out, t.meta, t.mask_bits ? t.mask_status : nullptr};
             }
             const dim3 grid(p.grid, (unsigned)n), block(kBlockThreads);
-            switch (m_group) {
-            case 4:
-                if (bf16) hipLaunchKernelGGL((project_compress_half_rows<4, true>), grid, block, 0, st, a);
-                else hipLaunchKernelGGL((project_compress_half_rows<4, false>), grid, block, 0, st, a);
-                break;
-            case 8:
-                if (bf16) hipLaunchKernelGGL(project_compress_4of8_rows<true>, grid, block, 0, st, a);
-                else hipLaunchKernelGGL(project_compress_4of8_rows<false>, grid, block, 0, st, a);
-                break;
-            default:
-                if (bf16) hipLaunchKernelGGL((project_compress_half_rows<2, true>), grid, block, 0, st, a);
-                else hipLaunchKernelGGL((project_compress_half_rows<2, false>), grid, block, 0, st, a);
-                break;
-            }
+            launch_pack_rows(m_group, bf16, p.same_row, grid, block, st, a);
             if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
             continue;
         }

@@ -185,10 +185,10 @@ def test_list_calls_of_the_once_per_run_entry_points_reject_bad_lists(lib):
     # statistics of given masks over a list
     sgood = S(a, 4, 64, 64, a, a, a)
     ws = lib.cast_mask_stats_multi_workspace_bytes
-    assert ws((S * 1)(sgood), 1) == 4 * 16 and ws((S * 1)(S(a, 5, 72, 72, a, None, a)), 1) == 16 and ws(None, 1) == 0      # a workgroup per row; 15 words
-    assert ws((S * 1)(S(a, 11008, 4096, 12288, a, None, a)), 1) == 11008 * 2 * 16      # a workgroup per 2048 entries of a row
-    assert lib.cast_mask_stats_multi((S * 1)(sgood), 1, C.c_void_p(a), 48, st) == -2
-    assert lib.cast_mask_stats_multi((S * 1)(sgood), 1, None, 64, st) == -1
+    assert ws((S * 1)(sgood), 1) == 16 and ws((S * 1)(S(a, 5, 72, 72, a, None, a)), 1) == 16 and ws(None, 1) == 0      # one workgroup each
+    assert ws((S * 1)(S(a, 11008, 4096, 12288, a, None, a)), 1) == 11008 * 2 * 16      # a workgroup per 2048 entries
+    assert lib.cast_mask_stats_multi((S * 1)(sgood), 1, C.c_void_p(a), 8, st) == -2
+    assert lib.cast_mask_stats_multi((S * 1)(sgood), 1, None, 16, st) == -1
     assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 64, None, a, a)), 1, C.c_void_p(a), 64, st) == -1
     assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 64, a, a, None)), 1, C.c_void_p(a), 64, st) == -1
     assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 60, a, a, a)), 1, C.c_void_p(a), 64, st) == -2
