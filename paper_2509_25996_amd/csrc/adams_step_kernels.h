@@ -311,9 +311,22 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
             // multiples of 32 entries and off is a multiple of 4, so adding the entry number to the low half carries nothing
             const uint64_t first = (uint64_t)c.dense_begin + (uint32_t)off;
             const uint32_t lo = (uint32_t)first, hi_term = (uint32_t)(first >> 32) * 0x9e3779b9u;
-            uint32_t h[4];
+            uint32_t h[4], r16[4];
+            bool finite = true;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) h[j] = f32_to_bf16_sr(v[j], sr_bits(a.s.sr_key, lo + (uint32_t)j, hi_term));
+            for (int j = 0; j < 4; ++j) {
+                r16[j] = sr_bits(a.s.sr_key, lo + (uint32_t)j, hi_term);
+                finite = finite && __builtin_fabsf(v[j]) < __builtin_inff();
+            }
+            // Infinities and NaN go through round-to-nearest; whether a wavefront holds any is decided once (a second
+            // moment is finite unless the step has already overflowed), which keeps that conversion out of the usual path.
+            if (__any(!finite)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[j] = f32_to_bf16_sr(v[j], r16[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[j] = (__float_as_uint(v[j]) + r16[j]) >> 16;
+            }
             const vu2_t packed = {h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
             __builtin_amdgcn_raw_buffer_store_b64(packed, b.v, off * 2, 0, kAuxStore);
         } else {

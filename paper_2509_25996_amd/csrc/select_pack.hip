@@ -557,11 +557,12 @@ cast_status launch_project_compress_list(const cast_matrix *m, int count, int n_
         const int segs = t0.scale ? n_segments : 0;
         const int64_t seg_len = segs ? t0.cols / segs : t0.cols;
         // the vector kernels: half-density patterns, rows that are whole mask words and whole metadata words
-        // (32 columns for 2:4, 16 for 4:8, 64 for 1:2), scale segments that are whole groups (so a lane's
-        // entries share one factor)
+        // (32 columns for 2:4, 16 for 4:8, 64 for 1:2), scale segments that are whole lanes (4 entries, 8 for 4:8:
+        // with 1:2 a lane holds two groups, which must not lie in two segments)
         const int word_cols = m_group == 4 ? 32 : (m_group == 8 ? 16 : 64);
         const RowsPlan p = plan_rows(t0.rows, t0.cols, t0.ld, m_group == 8 ? 8 : 4);
-        if (2 * n_keep == m_group && p.vec && t0.cols % word_cols == 0 && seg_len % m_group == 0) {
+        const int lane_entries = m_group == 8 ? 8 : 4;      // a lane's entries share one scale factor
+        if (2 * n_keep == m_group && p.vec && t0.cols % word_cols == 0 && seg_len % lane_entries == 0) {
             PackArgs a{{}, p.geom, make_fast_div((uint32_t)seg_len), segs};
             for (int k = 0; k < n; ++k) {
                 const cast_matrix &t = m[group[k]];

@@ -184,3 +184,19 @@ def test_mask_stats_list_matches_the_oracle(with_other):
         flips, kept, total = oracle.mask_stats(w0, keep, other) if w0.size else (0, 0.0, 0.0)
         assert got["flips_prev"] == flips and got["flips_init"] == 0, shape
         assert abs(got["l1_kept"] - kept) <= 1e-6 * kept and abs(got["l1_all"] - total) <= 1e-6 * total, shape
+
+
+def test_pack_1of2_with_scale_segments_of_half_a_lane():
+    """1:2 with scale segments of 6 entries: groups of 2 never straddle a segment, but the 4 consecutive entries a lane
+    of the fast kernel holds would; such shapes must take the scalar kernel and still match the oracle."""
+    rows, cols, nseg = 8, 192, 32
+    w0 = synth.weights(72, 0, rows, cols)
+    A = (1 + 0.5 * np.random.default_rng(3).standard_normal((rows, nseg))).astype(np.float32)
+    _, _, mbytes = B.cast_sizes(rows, cols, 1, 2, B.CAST_F32)
+    values = torch.empty((rows, cols // 2), device=DEV)
+    meta = torch.empty((rows, mbytes // 4 // rows), dtype=torch.int32, device=DEV)
+    B.cast_nm_project_compress(dev(w0), 1, 2, values, meta, scale=dev(A))
+    torch.cuda.synchronize()
+    ref_v, ref_m = oracle.project_compress(w0, 1, 2, A=A)
+    assert (words(meta) == ref_m).all()
+    assert_same_bits(host(values), ref_v, "values")
