@@ -49,12 +49,14 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
         w, m, v = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, 100 + i, device),
                                       mu_bf16=bf16_moments, v_bf16=bf16_moments)
         mask, initial = B.alloc_mask(r, c, device), B.alloc_mask(r, c, device)
-        B.cast_nm_select(w, n_keep, m_group, initial)                 # the mask of the dense model, for the initial flip rate
-        mask.copy_(initial)
         stats.append(B.alloc_refresh_stats(device))
         items.append(dict(w=w, m=m, v=v, mask=mask, grad=torch.empty((r, c), dtype=torch.bfloat16, device=device),
                           scale=torch.ones((r, segments), device=device), scale_grad=torch.zeros((r, segments), device=device),
                           initial_mask=initial, refresh_stats=stats[-1]))
+    # the masks of the dense model, for the initial flip rate: Eq. 6 over the whole list in one call
+    B.cast_nm_select_multi(B.MatrixList([dict(w=x["w"], mask=x["initial_mask"]) for x in items]), n_keep, m_group)
+    for x in items:
+        x["mask"].copy_(x["initial_mask"])
     tensors = B.TensorList(items, device)
     scale_optimizers = [DenseAdam(x["scale"], lr=1e-4) for x in items]
     total = sum(r * c for r, c in shapes)
@@ -77,15 +79,19 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
             if verbose and (t // mask_period) % max(1, steps // mask_period // 8) == 0:
                 print(f"step {t:5d}  alpha {cfg.alpha:5.3f}  flip rate {flip_rate:.5f}  against the initial mask "
                       f"{initial_flip_rate:.5f}  ||W.M||_1 / ||W||_1 = {kept_ratio:.5f}")
-    # Algorithm 1's end: prune with the last refreshed mask, fold the scale, pack values + index metadata
-    packed = []
+    # Algorithm 1's end: prune with the last refreshed mask, fold the scale, pack values + index metadata; one list
+    # call, which also checks that every stored mask holds exactly N ones per group
+    packed, outputs = [], []
+    bad_groups = torch.zeros(1, dtype=torch.int32, device=device)
     for x, (r, c) in zip(items, shapes):
         _, _, meta_bytes = B.cast_sizes(r, c, n_keep, m_group, B.CAST_BF16)
         values = torch.empty((r, c // m_group * n_keep), dtype=torch.bfloat16, device=device)
         meta = torch.empty((r, meta_bytes // 4 // r), dtype=torch.int32, device=device)
-        B.cast_nm_project_compress(x["w"], n_keep, m_group, values, meta, scale=x["scale"], mask_bits=x["mask"])
+        outputs.append(dict(w=x["w"], scale=x["scale"], mask=x["mask"], out=values, meta=meta, mask_status=bad_groups))
         packed.append((values, meta))
+    B.cast_nm_project_compress_multi(B.MatrixList(outputs), n_keep, m_group)
     torch.cuda.synchronize()
+    assert int(bad_groups.item()) == 0, "a stored mask is not an N:M mask"
     # what the pruning removes: the largest masked weight and the share of the L1 norm it carried
     worst, masked_l1, all_l1 = 0.0, 0.0, 0.0
     for x, (r, c) in zip(items, shapes):
