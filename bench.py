@@ -445,6 +445,26 @@ def main():
                 del kept
 
     if not args.no_extra and model.list is not None and scaled:
+        # the other patterns over the same state (10 steps from a refresh step on, so that the masks fit the pattern),
+        # and 2:4 with fp32 gradients (28.125 B/param: the single-matrix configuration of the workload family)
+        model.tensor_list(B, scaled, dev)
+        for key, nm in (("pattern_4of8", (4, 8)), ("pattern_1of2", (1, 2))):
+            model.nm = nm
+            ms, _, _ = time_set(torch, B, model, scaled, 10, 1, t0=10)
+            extra[key] = set_figures(ms, model.params)
+        model.nm = (2, 4)
+        free_bytes, _ = torch.cuda.mem_get_info()
+        if free_bytes > 4 * model.params + (4 << 30):
+            g16 = [x["g"] for x in model.t]
+            for x in model.t:
+                x["g"] = x["g"].float()
+            model.tensor_list(B, scaled, dev)
+            ms, _, _ = time_set(torch, B, model, scaled, 10, 1, t0=10)
+            extra["fp32_grads"] = set_figures(ms, model.params, BYTES_PER_PARAM + 2)
+            for x, g in zip(model.t, g16):
+                x["g"] = g
+            del g16
+            model.tensor_list(B, scaled, dev)
         # The step's timing depends on the data in one way: a wavefront whose 256 entries hold a zero, a denormal or a
         # huge mu~ or v takes the IEEE division and square root instead of the short forms.  Worst case: one entry
         # of every 256 with w = g = mu = v = 0 (it stays that way), so that every wavefront takes the long forms.
