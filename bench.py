@@ -8,8 +8,11 @@ Masks are refreshed every 10th step (T_1 = 10), so the timed region holds refres
 non-refresh steps in the paper's 1:9 ratio.  The final hard projection + packing runs once per
 training, not per step; it is timed separately and reported under "extra".
 
-Prints ONE JSON line (see README/DESIGN for the fields).  Inputs are synthetic Gaussians drawn
-in device memory; nothing is read from disk.
+Prints ONE JSON line: the metric (Gparams/s over the whole timed region), `roofline` (algorithmic bytes of the
+non-refresh step kernel per launch / its average launch duration against the 8 TB/s HBM peak, and against the
+library's stream probe), `cpu_baseline` (the CPU oracle timed on a bounded sample) and `extra` (the other entry
+points, step flavours, patterns, layouts and weight sets, each with ms, GB/s and fraction of peak).  Inputs are
+synthetic Gaussians drawn in device memory; nothing is read from disk.
 """
 from __future__ import annotations
 
