@@ -244,9 +244,12 @@ def test_fp32_arithmetic_stays_within_its_derived_bound_of_double_over_10_steps(
             assert (err <= bound).all(), (t, i, float((err / np.maximum(bound, 1e-300)).max()))
             scale[i] = np.maximum(scale[i], np.abs(st["f64"][i]))
     if lam == 2e-6 and lr == 1e-4:
-        for i in range(3):
+        for i, bound in enumerate((drift.E_w, drift.E_mu, drift.E_v)):
             err = np.abs(st["f32"][i].astype(np.float64) - st["f64"][i])
             assert (err <= 1e-6 * scale[i]).all(), (i, (err / scale[i]).max())
+            # the bound is worst-case (every rounding in the same direction for 10 iterations) but not vacuous:
+            # it stays within about ten stated tolerances of every entry's magnitude
+            assert (bound <= 1e-5 * scale[i]).all(), (i, (bound / scale[i]).max())
     # and the naive per-value relative error does blow up on the cancelling entries, which is why it is not used
     rel_w = np.abs(st["f32"][0].astype(np.float64) - st["f64"][0]) / np.abs(st["f64"][0])
     assert rel_w.max() > 1e-6
