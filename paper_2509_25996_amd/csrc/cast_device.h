@@ -386,18 +386,6 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t span_resource(const void *base
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, kRsrcWord3);
 }
 
-__device__ __forceinline__ void load4_stream(const float *p, int64_t idx, float (&x)[4])
-{
-    const vf4_t t = __builtin_nontemporal_load(reinterpret_cast<const vf4_t *>(p + idx));
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-}
-
-__device__ __forceinline__ void load4_bf16_stream(const uint16_t *p, int64_t idx, float (&g)[4])
-{
-    const vu2_t t = __builtin_nontemporal_load(reinterpret_cast<const vu2_t *>(p + idx));
-    g[0] = bf16_lo(t.x); g[1] = bf16_hi(t.x); g[2] = bf16_lo(t.y); g[3] = bf16_hi(t.y);
-}
-
 // ---- correctly rounded division by a divisor that is the same for every entry ---------------
 // The two bias corrections divide every entry by the same number.  With r = RN(1/y) from the
 // host, two Newton corrections carried by exact FMA residuals give RN(x/y) itself (Markstein's

@@ -40,11 +40,6 @@ __device__ __forceinline__ void store_full(T *p, const T &x)
     else *p = x;
 }
 
-__device__ __forceinline__ void unpack4u(const vu4_t &x, float (&f)[4])
-{
-    f[0] = __uint_as_float(x.x); f[1] = __uint_as_float(x.y); f[2] = __uint_as_float(x.z); f[3] = __uint_as_float(x.w);
-}
-
 // ---- how these kernels cover a matrix ----------------------------------------------------------
 // They do little arithmetic per byte and read every weight once, so what counts is plain, wide,
 // independent loads: a thread owns kLoads pieces of E consecutive entries (E = 4: one 16-byte load;
