@@ -11,7 +11,8 @@ step: iteration_config sets cfg.sr_seed = t).
 Gradients are random draws, not a loss: the point is the calling sequence, and that under the ramp the
 masked weights are driven to zero (Sec. 4.1, appendix "Mask Learning"), which the numbers it prints show.
 The scale factors are stepped from scale_grad by a plain Adam, itself a call into the library (DenseAdam below):
-the paper leaves their optimizer open.
+the paper leaves their optimizer open.  All of them live in one flat buffer (and their gradients in another), so
+that this Adam is one launch per step however many matrices there are.
 """
 from __future__ import annotations
 
@@ -45,20 +46,28 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
     """Returns a dict of what a training script would monitor; see the module docstring."""
     B.load()
     items, stats = [], []
+    # every matrix's scale factors and their gradients are slices of two flat buffers, padded to whole rows of 64
+    # for the dense Adam that steps them all at once
+    n_scale = sum(r * segments for r, _ in shapes)
+    scale_all = torch.ones(((n_scale + 63) // 64, 64), device=device)
+    scale_grad_all = torch.zeros_like(scale_all)
+    at = 0
     for i, (r, c) in enumerate(shapes):
         w, m, v = B.interleaved_state(synth.device_gaussian((r, c), 0.02, torch.float32, 100 + i, device),
                                       mu_bf16=bf16_moments, v_bf16=bf16_moments)
         mask, initial = B.alloc_mask(r, c, device), B.alloc_mask(r, c, device)
         stats.append(B.alloc_refresh_stats(device))
         items.append(dict(w=w, m=m, v=v, mask=mask, grad=torch.empty((r, c), dtype=torch.bfloat16, device=device),
-                          scale=torch.ones((r, segments), device=device), scale_grad=torch.zeros((r, segments), device=device),
+                          scale=scale_all.view(-1)[at:at + r * segments].view(r, segments),
+                          scale_grad=scale_grad_all.view(-1)[at:at + r * segments].view(r, segments),
                           initial_mask=initial, refresh_stats=stats[-1]))
+        at += r * segments
     # the masks of the dense model, for the initial flip rate: Eq. 6 over the whole list in one call
     B.cast_nm_select_multi(B.MatrixList([dict(w=x["w"], mask=x["initial_mask"]) for x in items]), n_keep, m_group)
     for x in items:
         x["mask"].copy_(x["initial_mask"])
     tensors = B.TensorList(items, device)
-    scale_optimizers = [DenseAdam(x["scale"], lr=1e-4) for x in items]
+    scale_optimizer = DenseAdam(scale_all, lr=1e-4)
     total = sum(r * c for r, c in shapes)
     history = []
     gen = torch.Generator(device=device).manual_seed(0)
@@ -68,8 +77,7 @@ def run(shapes=((256, 1024), (512, 512), (256, 2048)), steps=200, mask_period=10
         cfg = B.iteration_config(t, steps, mask_period=mask_period, lr=lr, lambda_=lam, n_keep=n_keep, m_group=m_group,
                                  scale_segments=segments)
         B.cast_adams_step_multi(tensors, cfg)
-        for opt, x in zip(scale_optimizers, items):                   # A <- Adam(A, dL/dA); the step above used the old A
-            opt.step(x["scale_grad"])
+        scale_optimizer.step(scale_grad_all)                          # A <- Adam(A, dL/dA); the step above used the old A
         if cfg.refresh_mask:
             s = [B.read_refresh_stats(x) for x in stats]
             flip_rate = sum(x["flips_prev"] for x in s) / total       # r_t
