@@ -451,8 +451,8 @@ def main():
         # the other patterns over the same state (10 steps from a refresh step on, so that the masks fit the pattern),
         # and 2:4 with fp32 gradients (28.125 B/param: the single-matrix configuration of the workload family)
         model.tensor_list(B, scaled, dev)
-        for key, nm in (("pattern_4of8", (4, 8)), ("pattern_1of2", (1, 2))):
-            model.nm = nm
+        for key, pattern in (("pattern_4of8", (4, 8)), ("pattern_1of2", (1, 2))):
+            model.nm = pattern
             ms, _, _ = time_set(torch, B, model, scaled, 10, 1, t0=10)
             extra[key] = set_figures(ms, model.params)
         model.nm = (2, 4)
