@@ -367,12 +367,12 @@ def main():
         extra["mask_stats_ms"], extra["mask_stats_GBs"], extra["mask_stats_frac"] = \
             figures(timed_calls(lambda: B.cast_mask_stats_multi(sl)), 4.25)
         del sl
-        # dL/dA alone (6 B/param), one call per matrix
+        # dL/dA alone (6 B/param), as one list call
         if scaled:
-            def all_scale_grads():
-                for x in model.t:
-                    B.cast_weight_scale_grad(x["w"], x["g"], SEGMENTS, x["gA"])
-            extra["weight_scale_grad_ms"], extra["weight_scale_grad_GBs"], _ = figures(timed_calls(all_scale_grads), 6.0)
+            gl = B.ScaleGradList([dict(w=x["w"], grad=x["g"], scale_grad=x["gA"]) for x in model.t])
+            extra["weight_scale_grad_ms"], extra["weight_scale_grad_GBs"], _ = \
+                figures(timed_calls(lambda: B.cast_weight_scale_grad_multi(gl)), 6.0)
+            del gl
         if model.list is not None:
             # the widened forms of the step, over the same set and through the same list call: a comparison
             # rule (Eq. 10), and the step that also writes the bf16 weights of the next forward pass

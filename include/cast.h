@@ -321,6 +321,20 @@ cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int 
                                    int64_t rows, int64_t cols, int64_t ld, int n_segments,
                                    float *scale_grad, void *stream);
 
+/* One matrix of a list for cast_weight_scale_grad_multi (Eq. 12, derivative with respect to A). */
+typedef struct {
+    const float *w;             /* DEVICE in: fp32 [rows, cols], row stride ld, 16-byte aligned        */
+    const void *grad_scaled;    /* DEVICE in: dL/dW_scale, dense [rows, cols] of the call's grad_dtype */
+    int64_t rows, cols, ld;
+    float *scale_grad;          /* DEVICE out: fp32 [rows, n_segments]                                 */
+} cast_scale_grad_matrix;
+
+/* cast_weight_scale_grad over a list (HOST array): matrices of one shape share launches; same
+ * results, matrix by matrix, as the single call.  All or nothing: an invalid matrix, or an unknown
+ * grad_dtype, returns its error before anything is launched.  count == 0 is CAST_OK. */
+cast_status cast_weight_scale_grad_multi(const cast_scale_grad_matrix *matrices /* HOST */, int count,
+                                         int grad_dtype, int n_segments, void *stream);
+
 /*
  * Final hard prune (last loop of Algorithm 1 / Algorithm 2), fold of the scale (Sec. 4.2)
  * and packing into values + index metadata.  The paper gives no packed layout; this one is

@@ -24,7 +24,7 @@ EXPORTS = ["cast_status_str", "cast_sizes", "cast_nm_select", "cast_adams_step",
            "cast_debug_div_by_uniform", "cast_adams_multi_workspace_bytes", "cast_adams_step_multi",
            "cast_adams_step_emit", "cast_adams_multi_launches", "cast_debug_plan", "cast_adams_step_multi_noalloc",
            "cast_hbm_stream_probe", "cast_nm_select_multi", "cast_weight_scale_multi", "cast_nm_project_compress_multi",
-           "cast_mask_stats_multi", "cast_mask_stats_multi_workspace_bytes"]
+           "cast_mask_stats_multi", "cast_mask_stats_multi_workspace_bytes", "cast_weight_scale_grad_multi"]
 
 
 class CastError(RuntimeError):
@@ -49,6 +49,11 @@ class _Matrix(C.Structure):
 class _StatsMatrix(C.Structure):
     _fields_ = [("w", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64), ("mask_bits", C.c_void_p),
                 ("other_bits", C.c_void_p), ("stats", C.c_void_p)]
+
+
+class _ScaleGradMatrix(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("grad_scaled", C.c_void_p), ("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64),
+                ("scale_grad", C.c_void_p)]
 
 
 class _Config(C.Structure):
@@ -117,6 +122,7 @@ def load():
     L.cast_nm_select_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, vp]
     L.cast_weight_scale_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, vp]
     L.cast_nm_project_compress_multi.argtypes = [C.POINTER(_Matrix), ci, ci, ci, ci, ci, vp]
+    L.cast_weight_scale_grad_multi.argtypes = [C.POINTER(_ScaleGradMatrix), ci, ci, ci, vp]
     L.cast_mask_stats_multi.argtypes = [C.POINTER(_StatsMatrix), ci, vp, C.c_size_t, vp]
     L.cast_mask_stats_multi_workspace_bytes.argtypes = [C.POINTER(_StatsMatrix), ci]
     L.cast_mask_stats_multi_workspace_bytes.restype = C.c_size_t
@@ -406,6 +412,32 @@ def cast_weight_scale_grad(w, grad_scaled, n_segments: int, scale_grad, stream=N
     rows, cols = w.shape
     _check(load().cast_weight_scale_grad(_ptr(w), _ptr(grad_scaled), _dtype_code(grad_scaled), rows, cols, _ld(w),
                                          n_segments, _ptr(scale_grad), _stream(stream)), "cast_weight_scale_grad")
+
+
+class ScaleGradList:
+    """Descriptors for cast_weight_scale_grad_multi, marshalled once.  Each item is a dict with w, grad (dL/dW_scale,
+    dense, one dtype for the whole list) and scale_grad (fp32 [rows, n]: n is the same for the whole list)."""
+
+    def __init__(self, items):
+        self.items = list(items)
+        n = len(self.items)
+        self.array = (_ScaleGradMatrix * max(n, 1))()
+        self.count = n
+        self.grad_dtype, self.segments = None, None
+        for k, x in enumerate(self.items):
+            w, g, sg = x["w"], x["grad"], x["scale_grad"]
+            _dev(g, sg)
+            if self.grad_dtype not in (None, _dtype_code(g)):
+                raise ValueError("all gradients of a list must have one dtype")
+            if self.segments not in (None, sg.shape[1]):
+                raise ValueError("all matrices of a list must have the same number of scaling segments")
+            self.grad_dtype, self.segments = _dtype_code(g), sg.shape[1]
+            self.array[k] = _ScaleGradMatrix(w.data_ptr(), g.data_ptr(), w.shape[0], w.shape[1], _ld(w), sg.data_ptr())
+
+
+def cast_weight_scale_grad_multi(matrices: ScaleGradList, stream=None):
+    _check(load().cast_weight_scale_grad_multi(matrices.array, matrices.count, matrices.grad_dtype or CAST_F32,
+                                               matrices.segments or 1, _stream(stream)), "cast_weight_scale_grad_multi")
 
 
 def cast_nm_project_compress(w, n_keep: int, m_group: int, values, meta, scale=None, mask_bits=None, stream=None):

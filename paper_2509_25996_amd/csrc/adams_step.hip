@@ -299,21 +299,43 @@ static void launch_unit_dtype(bool bf16, unsigned grid, const UnitArgs &a, hipSt
     else hipLaunchKernelGGL((adams_step_unit<M, false>), dim3(grid), dim3(kBlockThreads), 0, st, a);
 }
 
+// dL/dA of a list (already validated): matrices of one shape and row stride share launches of the span kernel.
+cast_status launch_scale_grad_list(const cast_scale_grad_matrix *m, int count, int grad_dtype, int n_segments, hipStream_t st)
+{
+    static_assert(kMaxListed <= kMaxFused, "a group of a list must fit the kernel's argument sets");
+    const bool bf16 = grad_dtype == CAST_BF16;
+    std::vector<char> taken((size_t)count, 0);
+    for (int i = 0; i < count; ++i) {
+        if (taken[i] || m[i].rows == 0 || m[i].cols == 0) continue;
+        int group[kMaxListed];
+        const int n = take_group(m, count, taken, i, [](const cast_scale_grad_matrix &, const cast_scale_grad_matrix &) { return true; }, group);
+        const cast_scale_grad_matrix &t0 = m[i];
+        const SpanPlan p = plan_spans(t0.rows, t0.cols, t0.ld, n_segments, false);
+        if (p.vec) {
+            ScaleGradArgs a{{}, p.geom};
+            for (int k = 0; k < n; ++k) a.set[k] = ScaleGradSet{m[group[k]].w, m[group[k]].grad_scaled, m[group[k]].scale_grad};
+            const dim3 grid(p.grid, (unsigned)n), block(p.block_threads);
+            if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, grid, block, 0, st, a);
+            else hipLaunchKernelGGL(scale_grad_vec<false>, grid, block, 0, st, a);
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+            continue;
+        }
+        for (int k = 0; k < n; ++k) {
+            const cast_scale_grad_matrix &t = m[group[k]];
+            const unsigned grid = (unsigned)((t.rows * n_segments + kBlockWaves - 1) / kBlockWaves);
+            if (bf16) hipLaunchKernelGGL(scale_grad_rows<true>, dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.grad_scaled, t.scale_grad, t.rows, t.cols, t.ld, n_segments);
+            else hipLaunchKernelGGL(scale_grad_rows<false>, dim3(grid), dim3(kBlockThreads), 0, st, t.w, t.grad_scaled, t.scale_grad, t.rows, t.cols, t.ld, n_segments);
+            if (launch_status() != CAST_OK) return CAST_ERR_LAUNCH;
+        }
+    }
+    return CAST_OK;
+}
+
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad, hipStream_t st)
 {
-    if (rows == 0 || cols == 0) return CAST_OK;
-    const SpanPlan p = plan_spans(rows, cols, ld, n_segments, false);
-    const bool bf16 = grad_dtype == CAST_BF16;
-    if (p.vec) {
-        if (bf16) hipLaunchKernelGGL(scale_grad_vec<true>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.geom);
-        else hipLaunchKernelGGL(scale_grad_vec<false>, dim3(p.grid), dim3(p.block_threads), 0, st, w, grad, scale_grad, p.geom);
-    } else {
-        const unsigned grid = (unsigned)((rows * n_segments + kBlockWaves - 1) / kBlockWaves);
-        if (bf16) hipLaunchKernelGGL(scale_grad_rows<true>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, rows, cols, ld, n_segments);
-        else hipLaunchKernelGGL(scale_grad_rows<false>, dim3(grid), dim3(kBlockThreads), 0, st, w, grad, scale_grad, rows, cols, ld, n_segments);
-    }
-    return launch_status();
+    const cast_scale_grad_matrix t{w, grad, rows, cols, ld, scale_grad};
+    return launch_scale_grad_list(&t, 1, grad_dtype, n_segments, st);
 }
 
 // Row stride, in its own entries, of a first moment kept in bf16: dense when w and v are, else the

@@ -443,12 +443,26 @@ __global__ __launch_bounds__(kBlockThreads) void sum_piece_sums(const PieceJobs 
     j.scale_grad[seg] = total;
 }
 
-// dL/dA alone, with exactly the traversal and summation order of adams_step_vec.
+// dL/dA alone, with exactly the traversal and summation order of adams_step_vec; like it, a launch
+// covers up to kMaxFused matrices of one shape (matrix blockIdx.y).
+struct ScaleGradSet {
+    const float *w;
+    const void *grad;
+    float *scale_grad;
+};
+struct ScaleGradArgs {
+    ScaleGradSet set[kMaxFused];
+    SpanGeom geom;
+};
+
 template <bool BF16>
-__global__ __launch_bounds__(kMaxBlockThreads) void scale_grad_vec(const float *w, const void *grad,
-                                                                   float *scale_grad, const SpanGeom geom)
+__global__ __launch_bounds__(kMaxBlockThreads) void scale_grad_vec(const ScaleGradArgs a)
 {
     __shared__ float partial[kMaxBlockWaves];
+    const SpanGeom &geom = a.geom;
+    const float *w = a.set[blockIdx.y].w;
+    const void *grad = a.set[blockIdx.y].grad;
+    float *scale_grad = a.set[blockIdx.y].scale_grad;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int P = geom.waves_per_span;

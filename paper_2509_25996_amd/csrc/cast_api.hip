@@ -274,18 +274,38 @@ cast_status cast_weight_scale(const float *w, const float *scale, int64_t rows, 
     return cast_weight_scale_multi(&t, 1, n_segments, out_dtype, stream);
 }
 
+static cast_status validate_scale_grad(const cast_scale_grad_matrix &t, int grad_dtype, int n_segments)
+{
+    if (t.rows < 0 || t.cols < 0 || n_segments < 1 || (t.cols % n_segments) || t.ld < t.cols) return CAST_ERR_SHAPE;
+    if (t.rows > 0 && t.cols > 0 && t.rows > (((int64_t)1 << 40) / t.cols)) return CAST_ERR_SHAPE;
+    if (!dtype_ok(grad_dtype)) return CAST_ERR_DTYPE;
+    if (too_many_segments(t.rows, n_segments)) return CAST_ERR_SHAPE;
+    if (t.rows == 0 || t.cols == 0) return CAST_OK;
+    if (!t.w || !t.grad_scaled || !t.scale_grad) return CAST_ERR_NULL;
+    if (!aligned(t.w, 16) || !aligned(t.grad_scaled, dtype_align(grad_dtype)) || !aligned(t.scale_grad, 4)) return CAST_ERR_ALIGN;
+    return CAST_OK;
+}
+
+cast_status cast_weight_scale_grad_multi(const cast_scale_grad_matrix *matrices, int count, int grad_dtype,
+                                         int n_segments, void *stream)
+{
+    if (count < 0) return CAST_ERR_SHAPE;
+    if (!dtype_ok(grad_dtype)) return CAST_ERR_DTYPE;
+    if (count == 0) return CAST_OK;
+    if (!matrices) return CAST_ERR_NULL;
+    for (int i = 0; i < count; ++i) {      // all or nothing
+        const cast_status rc = validate_scale_grad(matrices[i], grad_dtype, n_segments);
+        if (rc != CAST_OK) return rc;
+    }
+    return launch_scale_grad_list(matrices, count, grad_dtype, n_segments, static_cast<hipStream_t>(stream));
+}
+
 cast_status cast_weight_scale_grad(const float *w, const void *grad_scaled, int grad_dtype,
                                    int64_t rows, int64_t cols, int64_t ld, int n_segments,
                                    float *scale_grad, void *stream)
 {
-    if (rows < 0 || cols < 0 || n_segments < 1 || (cols % n_segments) || ld < cols) return CAST_ERR_SHAPE;
-    if (rows > 0 && cols > 0 && rows > (((int64_t)1 << 40) / cols)) return CAST_ERR_SHAPE;
-    if (!dtype_ok(grad_dtype)) return CAST_ERR_DTYPE;
-    if (too_many_segments(rows, n_segments)) return CAST_ERR_SHAPE;
-    if (rows == 0 || cols == 0) return CAST_OK;
-    if (!w || !grad_scaled || !scale_grad) return CAST_ERR_NULL;
-    if (!aligned(w, 16) || !aligned(grad_scaled, dtype_align(grad_dtype)) || !aligned(scale_grad, 4)) return CAST_ERR_ALIGN;
-    return launch_scale_grad(w, grad_scaled, grad_dtype, rows, cols, ld, n_segments, scale_grad, static_cast<hipStream_t>(stream));
+    const cast_scale_grad_matrix t{w, grad_scaled, rows, cols, ld, scale_grad};
+    return cast_weight_scale_grad_multi(&t, 1, grad_dtype, n_segments, stream);
 }
 
 static cast_status validate_pack(const cast_matrix &t, int n_segments, int n_keep, int m_group, int value_dtype)

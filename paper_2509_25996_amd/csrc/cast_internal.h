@@ -75,6 +75,8 @@ cast_status launch_adams_step(float *w, const void *grad, float *m, float *v, ui
 cast_status launch_scale_grad(const float *w, const void *grad, int grad_dtype, int64_t rows,
                               int64_t cols, int64_t ld, int n_segments, float *scale_grad,
                               hipStream_t stream);
+cast_status launch_scale_grad_list(const cast_scale_grad_matrix *m, int count, int grad_dtype, int n_segments,
+                                   hipStream_t stream);
 // Matrices of one shape (and, for `alike`, the same optional buffers) go several to a launch: up to
 // kMaxListed of them and about 72 M entries, the rule of the step kernels (a short launch pays some 2.6 us
 // of ramp, a very long one lets the compute units drift apart).  Collects into `group` the indices, from

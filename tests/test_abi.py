@@ -193,6 +193,20 @@ def test_list_calls_of_the_once_per_run_entry_points_reject_bad_lists(lib):
     assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 64, a, a, None)), 1, C.c_void_p(a), 64, st) == -1
     assert lib.cast_mask_stats_multi((S * 1)(S(a, 4, 64, 60, a, a, a)), 1, C.c_void_p(a), 64, st) == -2
     assert lib.cast_mask_stats_multi((S * 1)(sgood), 0, None, 0, st) == 0
+    # dL/dA over a list
+    G = B._ScaleGradMatrix
+    ggood = G(a, a, 4, 64, 64, a)
+    sg = lib.cast_weight_scale_grad_multi
+    for bad, want in ((G(a, a, 4, 64, 60, a), -2), (G(None, a, 4, 64, 64, a), -1), (G(a, None, 4, 64, 64, a), -1),
+                      (G(a, a, 4, 64, 64, None), -1), (G(odd, a, 4, 64, 64, a), -3), (G(a, odd, 4, 64, 64, a), -3),
+                      (G(a, a, -1, 64, 64, a), -2)):
+        assert sg((G * 2)(ggood, bad), 2, B.CAST_BF16, 2, st) == want
+    assert sg((G * 1)(ggood), 1, B.CAST_BF16, 3, st) == -2       # 3 segments do not divide 64 columns
+    assert sg((G * 1)(ggood), 1, B.CAST_BF16, 0, st) == -2
+    assert sg((G * 1)(ggood), 1, 5, 2, st) == -4
+    assert sg((G * 1)(ggood), 0, B.CAST_F32, 2, st) == 0 and sg(None, 1, B.CAST_F32, 2, st) == -1
+    assert sg((G * 1)(ggood), -1, B.CAST_F32, 2, st) == -2
+    assert sg((G * 1)(G(None, None, 0, 64, 64, None)), 1, B.CAST_F32, 2, st) == 0       # an empty matrix needs no buffers
 
 
 def test_noalloc_list_call_rejects_what_does_not_fit(lib):

@@ -1,5 +1,5 @@
 """The list forms of the once-per-run entry points (cast_nm_select_multi, cast_weight_scale_multi,
-cast_nm_project_compress_multi): matrices of one shape share launches (blockIdx.y picks the matrix), other shapes
+cast_weight_scale_grad_multi, cast_nm_project_compress_multi): matrices of one shape share launches (blockIdx.y picks the matrix), other shapes
 and the scalar kernels run in between; every output against the oracle, bit for bit (Eq. 6, Eq. 12, the last loop
 of Algorithm 1 and the packed layout)."""
 import numpy as np
@@ -63,6 +63,30 @@ def test_weight_scale_list_matches_the_oracle(nseg, out_dtype):
             assert_same_bits(host(o), ref, str(shape))
         else:
             assert (host(o.view(torch.int16)).view(np.uint16) == oracle.bf16_rne(ref)).all(), shape
+
+
+@pytest.mark.parametrize("grad_dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("nseg", [1, 2, 4])
+def test_weight_scale_grad_list_matches_the_oracle_and_the_single_call(nseg, grad_dtype):
+    """dL/dA (the derivative of Eq. 12 with respect to A) of a whole list: against the oracle's double sums within
+    the rounding of a fp32 sum, and bit for bit what the call on one matrix gives."""
+    shapes = [s for s in SHAPES if s[1] % nseg == 0 and (grad_dtype == torch.float32 or s[1] % 4 == 0)]
+    state = _state(shapes, 63)
+    grads = [torch.from_numpy(synth.grads_f32(9, i, 0, r, c)).to(grad_dtype) for i, (r, c) in enumerate(shapes)]
+    outs = [torch.full((r, nseg), 7.0, device=DEV) for r, _ in shapes]
+    dgrads = [g.to(DEV) for g in grads]
+    B.cast_weight_scale_grad_multi(B.ScaleGradList([dict(w=w, grad=g, scale_grad=o) for (_, w), g, o in zip(state, dgrads, outs)]))
+    torch.cuda.synchronize()
+    for (w0, w), g, dg, o, (r, c) in zip(state, grads, dgrads, outs, shapes):
+        if not w0.size:
+            continue
+        gs = g.float().numpy()
+        ref = oracle.weight_scale_grad(w0, gs, nseg)
+        terms = np.abs(gs.astype(np.float64) * w0).reshape(r, nseg, -1).sum(-1)
+        assert (np.abs(host(o) - ref) <= 1e-5 * terms + 1e-30).all(), (r, c)
+        single = torch.zeros((r, nseg), device=DEV)
+        B.cast_weight_scale_grad(w, dg, nseg, single)
+        assert host(single).tobytes() == host(o).tobytes(), (r, c)
 
 
 @pytest.mark.parametrize("value_dtype", [torch.float32, torch.bfloat16])
