@@ -53,16 +53,14 @@ SMALL = [(1, 32), (3, 64), (2, 256), (5, 512), (4, 1024), (3, 1280 + 64), (2, 25
          (2, 5120), (2, 13824), (1, 4608), (1, 6656), (1, 14336), (3, 6144), (1, 7424), (1, 28672)]
 
 
+# split = 2, 3: the plan of the selection and pack kernels (spans on multiples of 32 / 64 columns), which has no
+# scaling segments
 @pytest.mark.parametrize("rows,cols", SMALL)
-@pytest.mark.parametrize("nseg", [0, 1, 2])
 @pytest.mark.parametrize("interleaved", [False, True])
-@pytest.mark.parametrize("split", [False, True, 2, 3])
+@pytest.mark.parametrize("nseg,split", [(n, s) for s in (False, True) for n in (0, 1, 2)] + [(0, 2), (0, 3)])
 def test_every_entry_is_covered_exactly_once(lib, rows, cols, nseg, interleaved, split):
-    # split = 2, 3: the plan of the selection and pack kernels (spans on multiples of 32 / 64 columns)
     if nseg and (cols % nseg or (cols // nseg) % 4):
         pytest.skip("segments must be whole groups")
-    if split in (2, 3) and nseg:
-        pytest.skip("the selection and pack kernels have no scaling segments in their plan")
     ld = 3 * cols if interleaved else cols
     plan, _ = _plan(lib, rows, cols, ld, nseg, split)
     vec, grid, block_waves, P, pieces = plan
