@@ -426,6 +426,9 @@ def main():
                     extra["mu_bf16_emit_ms_step"] = round(ms, 3)
                     extra["mu_bf16_emit_GBs"] = round((BYTES_PER_PARAM - 2) * model.params / (ms * 1e-3) / 1e9, 1)
                     del copies
+                    model.tensor_list(B, scaled, dev)
+                # the same launches and streams with next to no arithmetic (overwrites this second state: its last use)
+                extra["mu_bf16_frac_of_stream_probe"] = round(stream_probe(torch, B, model) / extra["mu_bf16_ms_step"], 4)
                 # both moments in bf16, the second one rounded stochastically (18.125 B/param; 20.125 with the copy)
                 for x in model.t:
                     x["m"] = x["v"] = None
@@ -443,6 +446,8 @@ def main():
                     extra["both_bf16_emit_ms_step"] = round(ms, 3)
                     extra["both_bf16_emit_GBs"] = round((BYTES_PER_PARAM - 6) * model.params / (ms * 1e-3) / 1e9, 1)
                     del copies
+                    model.tensor_list(B, scaled, dev)
+                extra["both_bf16_frac_of_stream_probe"] = round(stream_probe(torch, B, model) / extra["both_bf16_ms_step"], 4)
                 for x, (w, m, v) in zip(model.t, kept):
                     x["w"], x["m"], x["v"] = w, m, v
                 del kept
@@ -462,8 +467,13 @@ def main():
             for x in model.t:
                 x["g"] = x["g"].float()
             model.tensor_list(B, scaled, dev)
-            ms, _, _ = time_set(torch, B, model, scaled, 10, 1, t0=10)
+            ms, per, kinds = time_set(torch, B, model, scaled, 10, 1, t0=10)
             extra["fp32_grads"] = set_figures(ms, model.params, BYTES_PER_PARAM + 2)
+            plain32 = [m for m, k in zip(per, kinds) if not k]
+            extra["fp32_grads"]["frac_of_stream_probe"] = round(stream_probe(torch, B, model) / (sum(plain32) / len(plain32)), 4)
+            for x in model.t:      # the probe leaves meaningless values: moments a step can start from again
+                x["m"].zero_()
+                x["v"].zero_()
             for x, g in zip(model.t, g16):
                 x["g"] = g
             del g16

@@ -408,15 +408,19 @@ cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *
 
 /*
  * Measurement aid, not part of the method: the launches cast_adams_step_multi would make for this list
- * of 2:4 matrices with bf16 gradients on a non-refresh iteration (same plans, same shared launches,
- * same loads, prefetches and stores of w, m, v, grad and mask_bits, same dL/dA sums), with the
- * arithmetic of the iteration replaced by three multiply-adds per entry.  Its duration is what the
- * memory system gives this access pattern: the ceiling the real step can be held against.
- * w, m, v and scale_grad are OVERWRITTEN with meaningless values.  Descriptors as for
+ * of 2:4 matrices on a non-refresh iteration (same plans, same shared launches, same loads,
+ * prefetches and stores of w, m, v, grad and mask_bits, same dL/dA sums), with the arithmetic of
+ * the iteration replaced by three multiply-adds per entry (bf16 moments are stored by truncation).
+ * Its duration is what the memory system gives this access pattern: the ceiling the real step can
+ * be held against.  grad_dtype: CAST_BF16 or CAST_F32; moment_flags: 0 (fp32 moments),
+ * CAST_FLAG_MU_BF16 or CAST_FLAG_MU_BF16 | CAST_FLAG_V_BF16, the latter two with bf16 gradients
+ * only (anything else: CAST_ERR_CONFIG), with m and v laid out as those flags lay them out for
+ * the step.  w, m, v and scale_grad are OVERWRITTEN with meaningless values.  Descriptors as for
  * cast_adams_step_multi (no compute_copy, no refresh_stats; shapes the fast kernels take only, else
  * CAST_ERR_SHAPE); workspace as for that call with the same scale_segments.
  */
 cast_status cast_hbm_stream_probe(const cast_tensor *tensors /* HOST */, int count, int scale_segments,
+                                  int grad_dtype, uint32_t moment_flags,
                                   void *workspace /* DEVICE */, size_t workspace_bytes, void *stream);
 
 /*

@@ -126,7 +126,7 @@ def load():
     L.cast_mask_stats_multi.argtypes = [C.POINTER(_StatsMatrix), ci, vp, C.c_size_t, vp]
     L.cast_mask_stats_multi_workspace_bytes.argtypes = [C.POINTER(_StatsMatrix), ci]
     L.cast_mask_stats_multi_workspace_bytes.restype = C.c_size_t
-    L.cast_hbm_stream_probe.argtypes = [C.POINTER(_Tensor), ci, ci, vp, C.c_size_t, vp]
+    L.cast_hbm_stream_probe.argtypes = [C.POINTER(_Tensor), ci, ci, ci, C.c_uint32, vp, C.c_size_t, vp]
     L.cast_debug_plan.argtypes = [i64, i64, i64, ci, ci, i64, ci, C.POINTER(i64), C.POINTER(i64)]
     L.cast_adams_multi_launches.argtypes = [C.POINTER(_Tensor), ci, C.POINTER(_Config), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     for name in EXPORTS:
@@ -489,10 +489,16 @@ def cast_hbm_copy_probe(dst, src, stream=None):
 
 
 def cast_hbm_stream_probe(tensors: TensorList, scale_segments: int, stream=None):
-    """The list call's launches with next to no arithmetic (bandwidth ceiling of its access pattern).
-    Overwrites w, m, v and scale_grad of every matrix of the list."""
-    _check(load().cast_hbm_stream_probe(tensors.array, tensors.count, scale_segments, _ptr(tensors.workspace),
-                                        tensors.workspace.numel(), _stream(stream)), "cast_hbm_stream_probe")
+    """The list call's launches with next to no arithmetic (bandwidth ceiling of its access pattern), for the
+    gradient and moment dtypes of the list.  Overwrites w, m, v and scale_grad of every matrix of the list."""
+    flags = 0
+    if tensors.count:
+        m, v = tensors.items[0]["m"], tensors.items[0]["v"]
+        flags = (FLAG_MU_BF16 if m.dtype == torch.bfloat16 else 0) | (FLAG_V_BF16 if v.dtype == torch.bfloat16 else 0)
+    _check(load().cast_hbm_stream_probe(tensors.array, tensors.count, scale_segments,
+                                        CAST_BF16 if tensors.grad_dtype is None else tensors.grad_dtype, flags,
+                                        _ptr(tensors.workspace), tensors.workspace.numel(), _stream(stream)),
+           "cast_hbm_stream_probe")
 
 
 def cast_debug_div_by_uniform(x, y: float):

@@ -64,7 +64,8 @@ static int flavour_rule(int rule)
 // moments do not come with the rules that have code of their own), then the rule and what else the kernel has to do.
 static int step_flavour(const cast_adams_config *cfg, bool copy, bool stats)
 {
-    if (cfg->flags & kInternalFlagStreamProbe) return kStreamProbe;
+    if (cfg->flags & kInternalFlagStreamProbe)
+        return (cfg->flags & CAST_FLAG_V_BF16) ? kStreamProbeBothBf16 : (cfg->flags & CAST_FLAG_MU_BF16) ? kStreamProbeMuBf16 : kStreamProbe;
     if (cfg->flags & CAST_FLAG_V_BF16) return (copy || stats) ? kBothBf16Emit : kBothBf16;
     if (cfg->flags & CAST_FLAG_MU_BF16) return (copy || stats) ? kMuBf16Emit : kMuBf16;
     const int rule = flavour_rule(cfg->rule);
@@ -246,10 +247,27 @@ static void launch_vec_abilities(const VecLaunch &l, const SpanArgs &a, dim3 gri
         case kMuBf16Emit: launch_vec_flavour<M, BF16, REFRESH, SCALED, kMuBf16Emit>(l, a, grid, block, st); break;
         case kBothBf16: launch_vec_flavour<M, BF16, REFRESH, SCALED, kBothBf16>(l, a, grid, block, st); break;
         case kBothBf16Emit: launch_vec_flavour<M, BF16, REFRESH, SCALED, kBothBf16Emit>(l, a, grid, block, st); break;
-        case kStreamProbe:      // the bandwidth probe exists for the benchmarked form only: 2:4, bf16 gradients, stored mask
-            if constexpr (M == 4 && BF16 && !REFRESH) {
-                launch_vec_flavour<4, true, false, SCALED, kStreamProbe>(l, a, grid, block, st);
+        // the bandwidth probes exist for 2:4 with a stored mask only; with bf16 moments for bf16 gradients only
+        case kStreamProbe:
+            if constexpr (M == 4 && !REFRESH) {
+                launch_vec_flavour<4, BF16, false, SCALED, kStreamProbe>(l, a, grid, block, st);
                 break;
+            }
+            [[fallthrough]];
+        case kStreamProbeMuBf16:
+            if constexpr (M == 4 && BF16 && !REFRESH) {
+                if (abilities(l.extra) == kStreamProbeMuBf16) {
+                    launch_vec_flavour<4, true, false, SCALED, kStreamProbeMuBf16>(l, a, grid, block, st);
+                    break;
+                }
+            }
+            [[fallthrough]];
+        case kStreamProbeBothBf16:
+            if constexpr (M == 4 && BF16 && !REFRESH) {
+                if (abilities(l.extra) == kStreamProbeBothBf16) {
+                    launch_vec_flavour<4, true, false, SCALED, kStreamProbeBothBf16>(l, a, grid, block, st);
+                    break;
+                }
             }
             [[fallthrough]];
         case kStatsOnly:      // refresh statistics without a compute copy: a flavour of the refresh kernels only

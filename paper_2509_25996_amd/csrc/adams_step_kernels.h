@@ -56,8 +56,9 @@ struct SpanArgs {
 // statistics (refresh steps only: without the code for the compute copy it runs close to flavour 0); 5 the
 // first moment in bf16, with the abilities of 1; 6 both moments in bf16, the second one rounded stochastically
 // (CAST_FLAG_V_BF16); 7 the same with the abilities of 1.  The rules combine with 0 and 1.
-// 8 is not the method: the walk, the loads, the prefetch and the stores of flavour 0 around a few multiply-adds
-// instead of Algorithm 1's arithmetic (cast_hbm_stream_probe: what the memory system gives this access pattern).
+// 8, 9, 10 are not the method: the walk, the loads, the prefetch and the stores of flavour 0 (9: of flavour 3,
+// 10: of flavour 6) around a few multiply-adds instead of Algorithm 1's arithmetic, bf16 moments stored by
+// truncation (cast_hbm_stream_probe: what the memory system gives these access patterns).
 constexpr int kEmitAndCount = 1;
 constexpr int kMuBf16 = 3;
 constexpr int kStatsOnly = 4;
@@ -65,13 +66,16 @@ constexpr int kMuBf16Emit = 5;
 constexpr int kBothBf16 = 6;
 constexpr int kBothBf16Emit = 7;
 constexpr int kStreamProbe = 8;
+constexpr int kStreamProbeMuBf16 = 9;
+constexpr int kStreamProbeBothBf16 = 10;
 constexpr int abilities(int extra) { return extra & 15; }
 constexpr int rule_of(int extra) { return extra >> 4; }      // kRuleAdamwL1, kRuleAdamL1, kRuleMaskedFrozen or 0
 constexpr int with_rule(int extra, int rule) { return extra | (rule << 4); }
 constexpr bool can_emit(int extra) { return abilities(extra) == kEmitAndCount || abilities(extra) == kMuBf16Emit || abilities(extra) == kBothBf16Emit; }
 constexpr bool can_count(int extra) { return can_emit(extra) || abilities(extra) == kStatsOnly; }
-constexpr bool v_is_bf16(int extra) { return abilities(extra) == kBothBf16 || abilities(extra) == kBothBf16Emit; }
-constexpr bool mu_is_bf16(int extra) { return abilities(extra) == kMuBf16 || abilities(extra) == kMuBf16Emit || v_is_bf16(extra); }
+constexpr bool is_probe(int extra) { return abilities(extra) >= kStreamProbe && abilities(extra) <= kStreamProbeBothBf16; }
+constexpr bool v_is_bf16(int extra) { return abilities(extra) == kBothBf16 || abilities(extra) == kBothBf16Emit || abilities(extra) == kStreamProbeBothBf16; }
+constexpr bool mu_is_bf16(int extra) { return abilities(extra) == kMuBf16 || abilities(extra) == kMuBf16Emit || abilities(extra) == kStreamProbeMuBf16 || v_is_bf16(extra); }
 
 // Registers of one chunk as loaded: 4 consecutive entries of each array per lane.
 template <bool BF16>
@@ -288,7 +292,7 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
                 g[j] = A * g[j];                                         // chain rule of Eq. 12
             }
         }
-        if constexpr (abilities(EXTRA) == kStreamProbe) {
+        if constexpr (is_probe(EXTRA)) {
             // bandwidth probe: every loaded value is used and every stream rewritten, with next to no arithmetic
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -300,13 +304,21 @@ __device__ __forceinline__ void span_run(const SpanArgs &a, const SpanCtx &c, Ch
             adams_entries4<rule_of(EXTRA), can_emit(EXTRA)>(w, g, mu, v, nib, off < len, a.s);
         }
         __builtin_amdgcn_raw_buffer_store_b128(pack4(w), b.w, off * 4, 0, kAuxStore);
-        if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
+        if constexpr (kMu16 && is_probe(EXTRA)) {
+            const vu2_t h = {(__float_as_uint(mu[0]) >> 16) | (__float_as_uint(mu[1]) & 0xffff0000u),
+                             (__float_as_uint(mu[2]) >> 16) | (__float_as_uint(mu[3]) & 0xffff0000u)};
+            __builtin_amdgcn_raw_buffer_store_b64(h, b.m, off * 2, 0, kAuxStore);
+        } else if constexpr (kMu16) {       // rounded to nearest even for the store only: v and w above used the unrounded value
             const vu2_t h = {f32x2_to_bf16_rne(mu[0], mu[1]), f32x2_to_bf16_rne(mu[2], mu[3])};
             __builtin_amdgcn_raw_buffer_store_b64(h, b.m, off * 2, 0, kAuxStore);
         } else {
             __builtin_amdgcn_raw_buffer_store_b128(pack4(mu), b.m, off * 4, 0, kAuxStore);
         }
-        if constexpr (kV16) {
+        if constexpr (kV16 && is_probe(EXTRA)) {
+            const vu2_t h = {(__float_as_uint(v[0]) >> 16) | (__float_as_uint(v[1]) & 0xffff0000u),
+                             (__float_as_uint(v[2]) >> 16) | (__float_as_uint(v[3]) & 0xffff0000u)};
+            __builtin_amdgcn_raw_buffer_store_b64(h, b.v, off * 2, 0, kAuxStore);
+        } else if constexpr (kV16) {
             // rounded stochastically for the store only, with the bits of index row * cols + col: spans begin on
             // multiples of 32 entries and off is a multiple of 4, so adding the entry number to the low half carries nothing
             const uint64_t first = (uint64_t)c.dense_begin + (uint32_t)off;

@@ -400,9 +400,12 @@ cast_status cast_hbm_copy_probe(void *dst, const void *src, size_t bytes, void *
     return launch_copy_probe(dst, src, bytes, static_cast<hipStream_t>(stream));
 }
 
-cast_status cast_hbm_stream_probe(const cast_tensor *tensors, int count, int scale_segments, void *workspace,
-                                  size_t workspace_bytes, void *stream)
+cast_status cast_hbm_stream_probe(const cast_tensor *tensors, int count, int scale_segments, int grad_dtype,
+                                  uint32_t moment_flags, void *workspace, size_t workspace_bytes, void *stream)
 {
+    if (!dtype_ok(grad_dtype)) return CAST_ERR_DTYPE;
+    if (moment_flags != 0 && moment_flags != CAST_FLAG_MU_BF16 && moment_flags != (CAST_FLAG_MU_BF16 | CAST_FLAG_V_BF16)) return CAST_ERR_CONFIG;
+    if (moment_flags != 0 && grad_dtype != CAST_BF16) return CAST_ERR_CONFIG;
     cast_adams_config cfg{};
     cfg.n_keep = 2;
     cfg.m_group = 4;
@@ -412,7 +415,8 @@ cast_status cast_hbm_stream_probe(const cast_tensor *tensors, int count, int sca
     cfg.bias_corr2 = 1.0f;
     cfg.refresh_mask = 0;
     cfg.scale_segments = scale_segments;
-    cfg.grad_dtype = CAST_BF16;
+    cfg.grad_dtype = grad_dtype;
+    cfg.flags = moment_flags;
     if (count < 0) return CAST_ERR_SHAPE;
     if (count == 0) return CAST_OK;
     if (!tensors) return CAST_ERR_NULL;
@@ -428,7 +432,7 @@ cast_status cast_hbm_stream_probe(const cast_tensor *tensors, int count, int sca
     const size_t need = multi_workspace_bytes(tensors, count, &cfg);
     if (need > 0 && !workspace) return CAST_ERR_NULL;
     if (workspace_bytes < need) return CAST_ERR_SHAPE;
-    cfg.flags = kInternalFlagStreamProbe;
+    cfg.flags |= kInternalFlagStreamProbe;
     std::vector<char> taken((size_t)count);
     return launch_adams_step_multi(tensors, count, &cfg, workspace, taken.data(), static_cast<hipStream_t>(stream));
 }
