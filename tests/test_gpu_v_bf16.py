@@ -23,7 +23,8 @@ def _f(t: torch.Tensor) -> np.ndarray:
 
 @pytest.mark.parametrize("n,m", [(2, 4), (4, 8), (1, 2)])
 @pytest.mark.parametrize("rows,cols,nseg", [(6, 512, 0), (6, 512, 2), (5, 1280 + 64, 2), (7, 72, 3), (3, 40, 0), (9, 24, 1),
-                                            (12, 4096, 2), (5, 11008, 2), (33, 4096 + 32, 0), (6, 5120, 2), (4, 13824, 2)])
+                                            (12, 4096, 2), (5, 11008, 2), (33, 4096 + 32, 0), (6, 5120, 2), (4, 13824, 2),
+                                            (2, 16384 + 256, 1)])      # the last one: 65 chunks for 16 wavefronts
 @pytest.mark.parametrize("bf16_grad", [False, True])
 @pytest.mark.parametrize("interleaved", [False, True])
 def test_v_bf16_step_bit_exact(n, m, rows, cols, nseg, bf16_grad, interleaved):
