@@ -313,3 +313,32 @@ def test_division_by_a_common_divisor_is_the_ieee_quotient(lib):
                 ref = (x / y).astype(np.float32)
             same = (got.view(np.uint32) == ref.view(np.uint32)) | (np.isnan(got) & np.isnan(ref))
             assert same.all(), (float(y), e)
+
+
+def test_without_the_library_the_binding_raises_and_the_package_never_touches_the_oracle():
+    """No fallback path: a missing libcast.so is an error at load(), and neither side imports the other."""
+    import re
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    env = dict(os.environ, CAST_LIBRARY=os.path.join(root, "no_such_dir", "libcast.so"))
+    run = subprocess.run([sys.executable, "-c", "from paper_2509_25996_amd import binding as B\nB.load()"], cwd=root, env=env,
+                         capture_output=True, text=True, timeout=300)
+    assert run.returncode != 0 and "FileNotFoundError" in run.stderr and "no fallback" in run.stderr
+    imports = re.compile(r"^\s*(?:import|from)\s+([\w\.]+)", re.M)
+    pkg = os.path.join(root, "paper_2509_25996_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            mods = imports.findall(open(os.path.join(pkg, name)).read())
+            assert not any(m.split(".")[0] == "oracle" for m in mods), name
+    for name in os.listdir(os.path.join(root, "oracle")):
+        if name.endswith(".py"):
+            mods = imports.findall(open(os.path.join(root, "oracle", name)).read())
+            assert not any(m.split(".")[0] == "paper_2509_25996_amd" for m in mods), name
+    # C sources: nothing under csrc/ or include/ includes a file of the oracle, and the reverse
+    for folder, banned in ((os.path.join(pkg, "csrc"), "oracle"), (os.path.join(root, "include"), "oracle"),
+                           (os.path.join(root, "oracle"), "cast.h")):
+        for name in os.listdir(folder):
+            if name.endswith((".h", ".hip", ".c")):
+                for inc in re.findall(r'#include\s+[<"]([^>"]+)[>"]', open(os.path.join(folder, name)).read()):
+                    assert banned not in inc, (name, inc)
