@@ -61,6 +61,26 @@ SMALL = [(1, 32), (3, 64), (2, 256), (5, 512), (4, 1024), (3, 1280 + 64), (2, 25
 def test_every_entry_is_covered_exactly_once(lib, rows, cols, nseg, interleaved, split):
     if nseg and (cols % nseg or (cols // nseg) % 4):
         pytest.skip("segments must be whole groups")
+    _covered_exactly_once(lib, rows, cols, nseg, interleaved, split)
+
+
+def test_random_shapes_are_covered_exactly_once(lib):
+    """The same over 300 seeded random shapes: any multiple of 32 columns up to 16384, any segment count that
+    divides them into whole groups, every plan kind."""
+    rng = np.random.default_rng(20250928)
+    done = 0
+    while done < 300:
+        cols = 32 * int(rng.integers(1, 513))
+        rows = int(rng.integers(1, 5))
+        split = [False, True, 2, 3][int(rng.integers(0, 4))]
+        nseg = 0 if split in (2, 3) else int(rng.choice([0, 1, 2, 3, 4, 6, 8]))
+        if nseg and (cols % nseg or (cols // nseg) % 4):
+            continue
+        _covered_exactly_once(lib, rows, cols, nseg, bool(rng.integers(0, 2)), split)
+        done += 1
+
+
+def _covered_exactly_once(lib, rows, cols, nseg, interleaved, split):
     ld = 3 * cols if interleaved else cols
     plan, _ = _plan(lib, rows, cols, ld, nseg, split)
     vec, grid, block_waves, P, pieces = plan
