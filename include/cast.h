@@ -3,7 +3,9 @@
  *
  * C ABI.  Every pointer marked DEVICE is an address in the memory of the current HIP device;
  * pointers marked HOST are ordinary process memory.  The caller owns every buffer: the
- * library allocates nothing, keeps no state between calls and frees nothing.
+ * library allocates nothing, keeps no state between calls and frees nothing (one exception,
+ * described where it is declared: cast_adams_step_multi_noalloc works in a device buffer that
+ * is part of the library's image, and remembers that buffer's address per device).
  *
  * Execution: each call validates its arguments on the host, then enqueues its kernels on the
  * HIP stream passed as `stream` (a hipStream_t cast to void*; NULL = the default stream) and
