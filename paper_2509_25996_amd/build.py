@@ -13,6 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcast.so")
 SOURCES = ["cast_api.hip", "adams_step.hip", "select_pack.hip"]
+# a stand-alone measurement aid beside the library: bare kernels with the step's streams (csrc/stream_skeleton.hip)
+SKELETON = os.path.join(HERE, "stream_skeleton")
 
 # -ffp-contract=off and the correctly rounded divide/sqrt keep every fp32 operation of the
 # update a single IEEE-754 rounding; packed fp32 instructions are switched off.
@@ -37,13 +39,15 @@ def _run(cmd, verbose):
 
 def build_library(verbose: bool = False, extra=()) -> str:
     """Compiles the three translation units side by side (objects under _build/, which is not tracked),
-    then links libcast.so."""
+    then links libcast.so; the stand-alone stream_skeleton executable is built along."""
     objdir = os.path.join(HERE, "_build")
     os.makedirs(objdir, exist_ok=True)
     objs = [os.path.join(objdir, s.replace(".hip", ".o")) for s in SOURCES]
-    with ThreadPoolExecutor(len(SOURCES)) as pool:
-        list(pool.map(lambda so: _run(["hipcc", *FLAGS, *extra, "-c", "-o", so[1], os.path.join(CSRC, so[0])], verbose),
-                      zip(SOURCES, objs)))
+    jobs = [["hipcc", *FLAGS, *extra, "-c", "-o", o, os.path.join(CSRC, s)] for s, o in zip(SOURCES, objs)]
+    jobs.append(["hipcc", "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                 "-Wall", "-Wextra", "-o", SKELETON, os.path.join(CSRC, "stream_skeleton.hip")])
+    with ThreadPoolExecutor(len(jobs)) as pool:
+        list(pool.map(lambda cmd: _run(cmd, verbose), jobs))
     _run(["hipcc", "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB, *objs], verbose)
     return LIB
 

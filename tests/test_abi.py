@@ -342,3 +342,13 @@ def test_without_the_library_the_binding_raises_and_the_package_never_touches_th
             if name.endswith((".h", ".hip", ".c")):
                 for inc in re.findall(r'#include\s+[<"]([^>"]+)[>"]', open(os.path.join(folder, name)).read()):
                     assert banned not in inc, (name, inc)
+
+
+def test_stream_skeleton_refuses_shapes_it_cannot_walk():
+    # argument checks come before any HIP call: runs without a GPU
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(B.__file__)), "stream_skeleton")
+    assert os.path.exists(exe), "build it with python -m paper_2509_25996_amd.build"
+    for args in (["5", "100"], ["0", "1024"], ["8", "1024", "65"], ["1048576", "1024"]):
+        run = subprocess.run([exe, *args], capture_output=True, text=True, timeout=60)
+        assert run.returncode == 2 and "usage" in run.stdout, args

@@ -80,3 +80,16 @@ def test_probe_refuses_what_it_has_no_kernel_for():
     assert lib.cast_hbm_stream_probe(tl2.array, 1, 0, B.CAST_BF16, 0, B._ptr(tl2.workspace), tl2.workspace.numel(), None) == -2
     torch.cuda.synchronize()
     assert_same_bits(host(st.w), synth.weights(73, 0, r, c), "nothing ran")
+
+
+def test_stand_alone_skeleton_runs_every_variant():
+    """The bare kernels of paper_2509_25996_amd/stream_skeleton (built by build.py beside the library) on a small
+    ragged shape: every variant launches and reports a figure."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(B.__file__)), "stream_skeleton")
+    assert os.path.exists(exe), "build it with python -m paper_2509_25996_amd.build"
+    run = subprocess.run([exe, "96", "2816", "3"], capture_output=True, text=True, timeout=120)      # 2816 = 11 x 256 columns
+    assert run.returncode == 0, run.stdout[-1500:] + run.stderr[-500:]
+    lines = [x for x in run.stdout.splitlines() if "GB/s" in x]
+    assert len(lines) == 2 * 17 and "HIP error" not in run.stdout      # 18 variants; the 4 KiB tiles do not divide 2816 columns
